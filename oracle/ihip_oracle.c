@@ -1,0 +1,242 @@
+/*
+ * CPU oracle for InfiniteHiP's attention hot path (arXiv 2502.08910).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, sequential C that follows the
+ * paper's algorithms step by step; it shares no code with the HIP library and
+ * must never be called from the product path.  Only tests, the smoke check
+ * and the benchmark's cpu_baseline leg may load it.
+ *
+ * What is here (one (sequence b, KV head g, query block) problem at a time;
+ * the multi-stage loop of Alg. 1 lives in pipeline.py beside this file):
+ *   orc_score            q.k score of one key against a query block  (Sec. 4, eq. for s_{m,j}; Alg. 3 step "compute scores")
+ *   orc_select_rep       SelectRep, hierarchical top-1 search          (Alg. 3)
+ *   orc_prune_stage      representative + chunk score per chunk        (Alg. 2, up to the arg-top-K)
+ *   orc_topk             arg-top-K of the chunk scores                  (Alg. 2, arg top_{k/l_c})
+ *   orc_sparse_attention softmax attention over sink + kept blocks + window (Sec. 4 "Background", BSA of Alg. 4)
+ *
+ * Conventions (the paper is silent or garbled on these; same readings as the
+ * design notes list): 0-based positions; chunk sizes are powers of two; the
+ * two halves of a range are [first, first+size/2) and [first+size/2, last];
+ * ties keep the left branch / the lowest index; a chunk that is cut short by
+ * the end of the middle range scores -inf for positions past its end; RoPE
+ * adjustment is off; with RoPE off the left branch's first key is the previous
+ * winner, so its score is carried over instead of being recomputed.
+ * Scores that decide a selection are fp32 (bf16 inputs, fp32 products and
+ * sums, summed in index order); the attention itself is fp64.
+ *
+ * Layouts: Q [B,Hq,Tq,d], K and V [B,Hkv,T_alloc,d], contiguous, bf16 bit
+ * patterns in uint16.  Query head h reads KV head h / (Hq/Hkv).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    const uint16_t *Q, *K, *V;
+    int32_t B, Hq, Hkv, d, Tq;
+    int64_t T_alloc;
+} orc_tensors;
+
+static float bf16_to_f32(uint16_t x)
+{
+    uint32_t u = (uint32_t)x << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static const uint16_t *q_row(const orc_tensors *t, int b, int h, int64_t tq)
+{
+    return t->Q + (((int64_t)b * t->Hq + h) * t->Tq + tq) * t->d;
+}
+static const uint16_t *k_row(const orc_tensors *t, int b, int g, int64_t p)
+{
+    return t->K + (((int64_t)b * t->Hkv + g) * t->T_alloc + p) * t->d;
+}
+static const uint16_t *v_row(const orc_tensors *t, int b, int g, int64_t p)
+{
+    return t->V + (((int64_t)b * t->Hkv + g) * t->T_alloc + p) * t->d;
+}
+
+/* max over the queries t of the block [q0, q0+bq) of  q_t . k_p   (fp32). */
+float orc_score(const orc_tensors *t, int b, int h, int64_t q0, int bq, int64_t p)
+{
+    const int g = h / (t->Hq / t->Hkv);
+    const uint16_t *k = k_row(t, b, g, p);
+    float best = -INFINITY;
+    for (int i = 0; i < bq; ++i) {
+        const uint16_t *q = q_row(t, b, h, q0 + i);
+        float acc = 0.0f;
+        for (int c = 0; c < t->d; ++c)
+            acc += bf16_to_f32(q[c]) * bf16_to_f32(k[c]);
+        if (acc > best)
+            best = acc;
+    }
+    return best;
+}
+
+/*
+ * SelectRep (Alg. 3) for head h on the chunk [start, start+len), nominal size
+ * l_c (a power of two, len <= l_c).  Binary search: at each of the log2(l_c)
+ * iterations the current range is cut in two equal halves and the first key
+ * of each half is scored; the better half survives (left on a tie).
+ * exhaustive != 0 replaces the search by the true in-chunk arg-max (lowest
+ * index on ties) -- used only to pin the search against brute force.
+ * touched (nullable): byte map over positions of this (b, g); every key that
+ * is scored is marked.
+ */
+void orc_select_rep(const orc_tensors *t, int b, int h, int64_t q0, int bq,
+                    int64_t start, int len, int l_c, int exhaustive,
+                    int64_t *r_out, float *sigma_out, uint8_t *touched)
+{
+    if (exhaustive) {
+        int best_off = 0;
+        float best = -INFINITY;
+        for (int off = 0; off < len; ++off) {
+            float s = orc_score(t, b, h, q0, bq, start + off);
+            if (touched) touched[start + off] = 1;
+            if (off == 0 || s > best) { best = s; best_off = off; }
+        }
+        *r_out = start + best_off;
+        *sigma_out = best;
+        return;
+    }
+    int off = 0;            /* first position of the current range, relative to start */
+    int size = l_c;         /* its nominal size */
+    float sigma = orc_score(t, b, h, q0, bq, start);   /* first key of the whole chunk */
+    if (touched) touched[start] = 1;
+    while (size > 1) {
+        const int half = size / 2;
+        const int mid = off + half;             /* first key of the right half */
+        float sigma_right = -INFINITY;
+        if (mid < len) {
+            sigma_right = orc_score(t, b, h, q0, bq, start + mid);
+            if (touched) touched[start + mid] = 1;
+        }
+        if (sigma_right > sigma) {              /* strict: a tie keeps the left half */
+            off = mid;
+            sigma = sigma_right;
+        }
+        size = half;
+    }
+    *r_out = start + off;
+    *sigma_out = sigma;
+}
+
+/*
+ * One pruning stage up to (not including) the arg-top-K (Alg. 2): for every
+ * chunk j, a representative per query head of the KV group g, and the chunk
+ * score = max over the group's heads (and over the block's queries, inside
+ * orc_score) of q . k_rep.
+ * rep (nullable) is [G][n_chunk].
+ */
+void orc_prune_stage(const orc_tensors *t, int b, int g, int64_t q0, int bq,
+                     int n_chunk, const int64_t *starts, const int32_t *lens,
+                     int l_c, int exhaustive,
+                     float *score, int64_t *rep, uint8_t *touched)
+{
+    const int G = t->Hq / t->Hkv;
+    for (int j = 0; j < n_chunk; ++j) {
+        float s = -INFINITY;
+        for (int hh = 0; hh < G; ++hh) {
+            int64_t r;
+            float sigma;
+            orc_select_rep(t, b, g * G + hh, q0, bq, starts[j], lens[j], l_c,
+                           exhaustive, &r, &sigma, touched);
+            if (rep) rep[(int64_t)hh * n_chunk + j] = r;
+            if (sigma > s) s = sigma;
+        }
+        score[j] = s;
+    }
+}
+
+typedef struct { float s; int32_t j; } scored;
+
+static int by_score_desc_then_index(const void *a, const void *b)
+{
+    const scored *x = a, *y = b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return (x->j > y->j) - (x->j < y->j);
+}
+static int by_index(const void *a, const void *b)
+{
+    const int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * arg-top-K: ids of the min(keep, n) largest scores, a tie going to the lower
+ * id, returned in ascending id order.  Returns how many were kept.
+ */
+int orc_topk(int n, const float *score, int keep, int32_t *ids_out)
+{
+    scored *v = malloc(sizeof(scored) * (n > 0 ? n : 1));
+    for (int j = 0; j < n; ++j) { v[j].s = score[j]; v[j].j = j; }
+    qsort(v, n, sizeof(scored), by_score_desc_then_index);
+    const int kept = keep < n ? keep : n;
+    for (int i = 0; i < kept; ++i) ids_out[i] = v[i].j;
+    qsort(ids_out, kept, sizeof(int32_t), by_index);
+    free(v);
+    return kept;
+}
+
+/*
+ * Attention of the query block [q0, q0+bq) of KV group g over
+ *   sink  [0, min(n_sink, p+1))
+ *   kept  every token of the blocks (block_starts[i], block_lens[i])
+ *   window [w0, p]
+ * where p = pos0 + i is the absolute position of query q0+i (causal: no key
+ * after p).  Kept blocks must lie in [n_sink, w0).  O = softmax(scale q K^T) V
+ * in fp64.  out is [G][bq][d] doubles, lse (nullable) [G][bq] natural-log
+ * sum-exp of the scaled scores.
+ */
+void orc_sparse_attention(const orc_tensors *t, int b, int g, int64_t q0, int bq,
+                          int64_t pos0, int64_t n_sink, int64_t w0,
+                          int n_blocks, const int64_t *block_starts,
+                          const int32_t *block_lens, double scale,
+                          double *out, double *lse)
+{
+    const int G = t->Hq / t->Hkv, d = t->d;
+    /* the key list of the last query is the longest */
+    int64_t cap = n_sink + (pos0 + bq - w0 > 0 ? pos0 + bq - w0 : 0) + 1;
+    for (int i = 0; i < n_blocks; ++i) cap += block_lens[i];
+    int64_t *keys = malloc(sizeof(int64_t) * cap);
+    double *s = malloc(sizeof(double) * cap);
+
+    for (int hh = 0; hh < G; ++hh) {
+        for (int i = 0; i < bq; ++i) {
+            const int64_t p = pos0 + i;
+            int64_t n = 0;
+            for (int64_t x = 0; x < n_sink && x <= p; ++x) keys[n++] = x;
+            for (int j = 0; j < n_blocks; ++j)
+                for (int c = 0; c < block_lens[j]; ++c) keys[n++] = block_starts[j] + c;
+            for (int64_t x = w0; x <= p; ++x) keys[n++] = x;
+
+            const uint16_t *q = q_row(t, b, g * G + hh, q0 + i);
+            double mx = -INFINITY;
+            for (int64_t a = 0; a < n; ++a) {
+                const uint16_t *k = k_row(t, b, g, keys[a]);
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c)
+                    acc += (double)bf16_to_f32(q[c]) * (double)bf16_to_f32(k[c]);
+                s[a] = scale * acc;
+                if (s[a] > mx) mx = s[a];
+            }
+            double denom = 0.0;
+            double *o = out + ((int64_t)hh * bq + i) * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            for (int64_t a = 0; a < n; ++a) {
+                const double w = exp(s[a] - mx);
+                const uint16_t *v = v_row(t, b, g, keys[a]);
+                denom += w;
+                for (int c = 0; c < d; ++c) o[c] += w * (double)bf16_to_f32(v[c]);
+            }
+            for (int c = 0; c < d; ++c) o[c] /= denom;
+            if (lse) lse[(int64_t)hh * bq + i] = mx + log(denom);
+        }
+    }
+    free(keys);
+    free(s);
+}

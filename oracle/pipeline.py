@@ -1,0 +1,182 @@
+"""Multi-stage context pruning (Alg. 1) and the per-layer sequence on top of
+the C leaf routines of ihip_oracle.c.  TEST INFRASTRUCTURE ONLY (see the
+package docstring).
+
+One "problem" is (sequence b, KV head g, query block m).  Reading of the
+paper used here: the mask is chosen per KV head, the chunk score being pooled
+over the query heads that share it (the paper writes H heads and never
+mentions grouped-query attention).
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+
+def _u16(t: torch.Tensor) -> np.ndarray:
+    """bf16 tensor -> contiguous uint16 numpy array of its bit patterns."""
+    assert t.dtype == torch.bfloat16
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+@dataclass
+class StageResult:
+    l_c: int
+    starts: np.ndarray          # int64 [n]   chunk start positions, ascending
+    lens: np.ndarray            # int32 [n]   valid lengths (1..l_c)
+    scores: np.ndarray          # float32 [n] chunk scores
+    reps: np.ndarray            # int64 [G,n] representative positions
+    kept_ids: np.ndarray        # int32 [kept] ascending chunk ids
+    rows_touched: int           # distinct K rows scored by this stage
+
+    @property
+    def kept_starts(self):
+        return self.starts[self.kept_ids]
+
+    @property
+    def kept_lens(self):
+        return self.lens[self.kept_ids]
+
+
+@dataclass
+class ProblemResult:
+    b: int
+    g: int
+    m: int
+    lo: int                     # first middle position  (= n_sink)
+    hi: int                     # one past the last middle position (= E - n_stream)
+    E: int                      # one past the last key visible to the block
+    stages: List[StageResult] = field(default_factory=list)
+
+    @property
+    def block_starts(self) -> np.ndarray:
+        return self.stages[-1].kept_starts if self.stages else np.zeros(0, np.int64)
+
+    @property
+    def block_lens(self) -> np.ndarray:
+        return self.stages[-1].kept_lens if self.stages else np.zeros(0, np.int32)
+
+
+def stage1_chunks(lo: int, hi: int, l_c: int):
+    """Alg. 1 step 1 + Alg. 2 chunking: the middle range [lo, hi) cut into
+    l_c-sized chunks, the last one cut short if the range is ragged."""
+    starts = np.arange(lo, hi, l_c, dtype=np.int64)
+    lens = np.minimum(l_c, hi - starts).astype(np.int32)
+    return starts, lens
+
+
+def child_chunks(kept_starts, kept_lens, l_child: int):
+    """The next stage's chunks: the kept tokens, in position order, cut into
+    l_child-sized pieces.  Every kept chunk is a multiple of l_child long except
+    a ragged last one, so the pieces never straddle two parents; empty pieces
+    are dropped."""
+    starts, lens = [], []
+    for s, n in zip(kept_starts.tolist(), kept_lens.tolist()):
+        for c in range(0, n, l_child):
+            starts.append(s + c)
+            lens.append(min(l_child, n - c))
+    return np.asarray(starts, dtype=np.int64), np.asarray(lens, dtype=np.int32)
+
+
+class Oracle:
+    """Holds one layer's Q/K/V (as bf16 bit patterns on the host) and the
+    shape; runs pruning and attention problem by problem."""
+
+    def __init__(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens,
+                 b_q: int, n_sink: int, n_stream: int):
+        from . import lib, Tensors
+        self.L = lib()
+        self.q, self.k, self.v = _u16(q), _u16(k), _u16(v)
+        self.B, self.Hq, self.Tq, self.d = q.shape
+        _, self.Hkv, self.T_alloc, _ = k.shape
+        assert self.Hq % self.Hkv == 0 and self.Tq % b_q == 0
+        self.G = self.Hq // self.Hkv
+        self.seq_lens = [int(x) for x in seq_lens]
+        self.b_q, self.n_sink, self.n_stream = b_q, n_sink, n_stream
+        self.t = Tensors(self.q.ctypes.data, self.k.ctypes.data, self.v.ctypes.data,
+                         self.B, self.Hq, self.Hkv, self.d, self.Tq, self.T_alloc)
+
+    # -- geometry ---------------------------------------------------------
+    def ranges(self, b: int, m: int) -> Tuple[int, int, int]:
+        """(lo, hi, E): middle range [lo, hi) and exclusive end E of the keys
+        visible to query block m (Alg. 1 step 1: sink and streaming tokens are
+        excluded, causality is kept because hi never exceeds the position of
+        the block's first query)."""
+        E = (self.seq_lens[b] - self.Tq) + (m + 1) * self.b_q
+        return self.n_sink, E - self.n_stream, E
+
+    # -- Alg. 2 -----------------------------------------------------------
+    def prune_stage(self, b, g, m, starts, lens, l_c, keep, exhaustive=False) -> StageResult:
+        n = len(starts)
+        scores = np.empty(n, np.float32)
+        reps = np.empty((self.G, n), np.int64)
+        touched = np.zeros(self.T_alloc, np.uint8)
+        starts = np.ascontiguousarray(starts, np.int64)
+        lens = np.ascontiguousarray(lens, np.int32)
+        self.L.orc_prune_stage(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q, n,
+                               _p(starts), _p(lens), l_c, int(exhaustive),
+                               _p(scores), _p(reps), _p(touched))
+        ids = np.empty(max(min(keep, n), 1), np.int32)
+        kept = self.L.orc_topk(n, _p(scores), keep, _p(ids))
+        return StageResult(l_c, starts, lens, scores, reps, ids[:kept].copy(), int(touched.sum()))
+
+    # -- Alg. 1 -----------------------------------------------------------
+    def prune(self, b, g, m, stages: Sequence[Tuple[int, int]], exhaustive=False) -> ProblemResult:
+        """stages: (chunk size l_c, chunks kept K) per stage, coarse to fine."""
+        lo, hi, E = self.ranges(b, m)
+        pr = ProblemResult(b, g, m, lo, hi, E)
+        if hi <= lo:
+            return pr                       # nothing between sink and window
+        starts, lens = stage1_chunks(lo, hi, stages[0][0])
+        for i, (l_c, keep) in enumerate(stages):
+            assert l_c & (l_c - 1) == 0, "chunk sizes are powers of two"
+            if i > 0:
+                assert stages[i - 1][0] % l_c == 0
+                starts, lens = child_chunks(pr.stages[-1].kept_starts, pr.stages[-1].kept_lens, l_c)
+            pr.stages.append(self.prune_stage(b, g, m, starts, lens, l_c, keep, exhaustive))
+        return pr
+
+    # -- block-sparse attention --------------------------------------------
+    def attend(self, b, g, m, block_starts, block_lens, scale=None):
+        """fp64 output [G, b_q, d] and log-sum-exp [G, b_q] of the block's
+        queries over sink + kept blocks + causal window."""
+        lo, hi, E = self.ranges(b, m)
+        scale = 1.0 / math.sqrt(self.d) if scale is None else scale
+        out = np.empty((self.G, self.b_q, self.d), np.float64)
+        lse = np.empty((self.G, self.b_q), np.float64)
+        bs = np.ascontiguousarray(block_starts, np.int64)
+        bl = np.ascontiguousarray(block_lens, np.int32)
+        if len(bs):
+            assert bs.min() >= lo and (bs + bl).max() <= hi
+        self.L.orc_sparse_attention(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q,
+                                    E - self.b_q, self.n_sink, max(hi, self.n_sink),
+                                    len(bs), _p(bs), _p(bl), scale, _p(out), _p(lse))
+        return out, lse
+
+    def attended_tokens(self, b, m, block_lens) -> int:
+        """Keys the last query of the block attends to (for byte counts)."""
+        lo, hi, E = self.ranges(b, m)
+        return min(self.n_sink, E) + int(np.sum(block_lens)) + max(0, E - max(hi, self.n_sink))
+
+    # -- one layer ----------------------------------------------------------
+    def layer(self, stages, scale=None, problems=None, exhaustive=False):
+        """Pruning + attention for every (b, g, m) (or the listed ones).
+        Returns {(b,g,m): (ProblemResult, out[G,b_q,d], lse[G,b_q])}."""
+        if problems is None:
+            problems = [(b, g, m) for b in range(self.B) for g in range(self.Hkv)
+                        for m in range(self.Tq // self.b_q)]
+        res = {}
+        for (b, g, m) in problems:
+            pr = self.prune(b, g, m, stages, exhaustive)
+            out, lse = self.attend(b, g, m, pr.block_starts, pr.block_lens, scale)
+            res[(b, g, m)] = (pr, out, lse)
+        return res
