@@ -43,7 +43,7 @@ def test_needle_recipe():
             h = g * w.G + i % w.G
             qv = q[0, h, 0].float()
             s = (qv @ k[0, g, pos[0, g, i]].float()).item()
-            assert abs(s - 4.0 * qv.norm().item()) < 0.15 * qv.norm().item()
+            assert abs(s - 4.0 * qv.norm().item()) < 0.5 * qv.norm().item()   # noise: 0.1|q| rms
 
 
 def test_zipf_is_heavy_headed():
