@@ -1,0 +1,183 @@
+/*
+ * ihip.h -- C ABI of the MI355X (gfx950) implementation of InfiniteHiP's
+ * attention hot path (arXiv 2502.08910): modular hierarchical context pruning
+ * (Sec. 4 "Efficient Modular Context Pruning"; App. A, Alg. 1-3) followed by
+ * block-sparse attention over sink + kept blocks + sliding window (Sec. 4,
+ * first paragraph of the pruning description; Alg. 4, "perform block sparse
+ * attention").
+ *
+ * General rules
+ *  - Every pointer marked "device" is GPU memory owned by the caller; the
+ *    library never allocates, frees or keeps it.  Pointers marked "host" are
+ *    ordinary host memory read during the call only.
+ *  - All work is enqueued on the HIP stream passed last (a hipStream_t cast to
+ *    void*, NULL = the default stream); no call synchronises the device.
+ *  - Tensors are bf16 with the last dimension (d) contiguous; strides are in
+ *    elements.  Rows must be 16-byte aligned (ptr and every stride a multiple
+ *    of 8 elements).
+ *  - Every function returns 0 on success or a negative IHIP_ERR_* code; the
+ *    text of the last error of the calling thread is in ihip_last_error().
+ *    Nothing is enqueued when an argument check fails.
+ *  - Preconditions the library cannot check: inputs hold no NaN or Inf;
+ *    seq_lens[b] <= max_seq_len <= the allocated token count of K and V.
+ *
+ * Problem indexing.  One "problem" is (sequence b, KV head g, query block m),
+ * p = (b*Hkv + g)*Mq + m with Mq = Tq / b_q.  Query head h reads KV head
+ * h / (Hq/Hkv); the mask is chosen per KV head and pooled over the Hq/Hkv query
+ * heads that share it and over the b_q queries of the block (Alg. 2, chunk
+ * score s_{m,j}).  For problem p with T = seq_lens[b]:
+ *     E  = (T - Tq) + (m+1)*b_q        one past the last key the block may see
+ *     lo = n_sink,  hi = E - n_stream  the middle range [lo, hi) that is pruned
+ * (Alg. 1, first step).  Sink [0, n_sink) and window [max(hi,lo), E) are always
+ * attended, the window causally.  n_stream >= b_q is required so that every
+ * middle key precedes every query of the block.
+ */
+#ifndef IHIP_H
+#define IHIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IHIP_OK                 0
+#define IHIP_ERR_INVALID_ARG   (-1)
+#define IHIP_ERR_WORKSPACE     (-2)
+#define IHIP_ERR_HIP           (-3)
+#define IHIP_ERR_UNSUPPORTED   (-4)
+
+/* A bf16 tensor [B, H, T, d] on the device. */
+typedef struct {
+    const void *ptr;                       /* device */
+    int64_t stride_b, stride_h, stride_t;  /* elements; stride of d is 1 */
+} ihip_tensor;
+
+typedef struct {
+    int32_t B, Hq, Hkv, d;       /* d must be 128; Hq/Hkv in {1,2,4,8} */
+    int32_t Tq, b_q;             /* new query tokens and query block size; decode: 1, 1 */
+    const int32_t *seq_lens;     /* device [B]: keys visible per sequence, the Tq new tokens included */
+    int32_t max_seq_len;         /* host-side upper bound of seq_lens (sizes the launch) */
+    int32_t n_sink, n_stream;
+} ihip_shape;
+
+/* Operation ids for ihip_workspace_bytes. */
+#define IHIP_OP_ATTN_DECODE   1
+#define IHIP_OP_ATTN_PREFILL  2
+#define IHIP_OP_PRUNE_ALL     3
+#define IHIP_OP_DECODE_LAYER  4
+
+/*
+ * One pruning stage up to the arg-top-K (Alg. 2 with SelectRep of Alg. 3 inside):
+ * for every chunk slot j of every problem, finds a representative key per query
+ * head by the halving search (first key of each half, left half on a tie) and
+ * writes the chunk score = max over the group's heads and the block's queries
+ * of q . k_rep (fp32, unscaled).
+ *
+ * Chunk slots.  parent_starts == NULL: first stage, slot j is
+ * [lo + j*chunk, min(lo + (j+1)*chunk, hi)).  Otherwise parent_starts is device
+ * int32 [P, n_parent], ascending start positions of the previous stage's kept
+ * chunks of size parent_chunk (-1 = none, only at the tail); slot
+ * j = i*(parent_chunk/chunk) + c is child c of parent i, cut at hi.  A slot that
+ * holds no key gets score -INFINITY (this is how later calls recognise it).
+ *
+ *   max_chunks   slots per problem: >= ceil((max_seq_len-Tq+Tq... see ihip_stage1_slots)
+ *                for the first stage, = n_parent*(parent_chunk/chunk) otherwise
+ *   out_scores   device fp32 [P, max_chunks]
+ *   out_rep      device int32 [B, Hq, Mq, max_chunks] representative positions
+ *                (-1 for empty slots); may be NULL
+ * chunk and parent_chunk are powers of two, chunk <= 1024, parent_chunk % chunk == 0.
+ * b_q == 1 requires Tq == 1 (decode); b_q in {16, 32, 64} is chunked prefill.
+ */
+int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
+                         const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                         int32_t chunk, int32_t max_chunks,
+                         float *out_scores, int32_t *out_rep, void *stream);
+
+/* Slots the first stage needs per problem: ceil((max_seq_len - n_stream - n_sink) / chunk), >= 0. */
+int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk);
+
+/*
+ * arg-top-K of the chunk scores (Alg. 2, "discard chunks with low estimated
+ * scores"): per problem keeps the min(keep, #non-empty slots) best slots under
+ * the order (score descending, slot ascending; -0.0 == +0.0) and writes their
+ * start positions in ascending order to out_starts (device int32 [P, keep]),
+ * padding with -1.  scores is device fp32 [P, max_chunks] as written by
+ * ihip_prune_stage; parent_starts / n_parent / parent_chunk / chunk describe the
+ * slots exactly as there.  max_chunks <= 65535 * 16.
+ */
+int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
+                           const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                           int32_t chunk, int32_t keep, int32_t *out_starts, void *stream);
+
+/*
+ * Block-sparse decode attention (Tq == b_q == 1): for every query head,
+ *   O = softmax(sm_scale * q K_S^T) V_S,
+ *   S = [0, min(n_sink,E)) u kept blocks u [max(hi,n_sink), E)
+ * with fp32 scores, exp and accumulation (flash-decoding style split over S and
+ * a log-sum-exp merge), bf16 result.
+ *   block_starts device int32 [P, n_blocks], start positions of blocks of
+ *                `block` tokens (power of two) inside [lo, hi), -1 = none; a block
+ *                is cut at hi.  Blocks must not overlap.
+ *   out          device bf16 [B, Hq, 1, d] contiguous
+ *   out_lse      device fp32 [B, Hq] natural-log sum-exp of the scaled scores; may be NULL
+ *   ws, ws_bytes device scratch of at least ihip_workspace_bytes(IHIP_OP_ATTN_DECODE, ...)
+ */
+int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                float sm_scale, void *out, float *out_lse,
+                                void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Block-sparse chunked-prefill attention: the same key set per query block m,
+ * every query of the block attending causally inside the window (keys after
+ * its own position are masked).  b_q must be 64.  block_starts is
+ * [P, n_blocks] with P = B*Hkv*Mq; out is bf16 [B, Hq, Tq, d] contiguous;
+ * out_lse fp32 [B, Hq, Tq] or NULL.  QK^T and PV run on the matrix cores
+ * (bf16 inputs, fp32 accumulation), softmax in fp32.
+ */
+int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                 float sm_scale, void *out, float *out_lse,
+                                 void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Alg. 1: every pruning stage and its arg-top-K, coarse to fine, in one
+ * enqueue.  chunk_sizes / keeps are host int32 [n_stages] (l_c and K = k/l_c per
+ * stage; each chunk size divides the previous one).  out_block_starts is
+ * device int32 [P, keeps[n_stages-1]]: the last stage's kept blocks, as
+ * ihip_sparse_attn_* take them.  Scratch from ihip_workspace_bytes(IHIP_OP_PRUNE_ALL, ...).
+ */
+int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
+                       int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                       int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One decode layer call: ihip_prune_all followed by ihip_sparse_attn_decode
+ * (Alg. 4 with every stage refreshed at every step).  out / out_lse as in
+ * ihip_sparse_attn_decode; out_block_starts device int32 [P, keeps[last]] or NULL.
+ */
+int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                          int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                          float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Scratch bytes an operation needs.  n_stages / chunk_sizes / keeps describe
+ * the stage plan (for the attention-only ops pass n_stages = 1 with
+ * chunk_sizes[0] = block and keeps[0] = n_blocks).  Returns 0 on bad arguments.
+ */
+size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stages,
+                            const int32_t *chunk_sizes, const int32_t *keeps);
+
+/* Text of the calling thread's last error ("" if none).  Never NULL. */
+const char *ihip_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t ihip_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IHIP_H */

@@ -1,0 +1,205 @@
+"""ctypes binding of libihip.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch supplies
+device memory and the stream.  There is no fallback: if the library is
+missing or a call fails this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libihip.so")
+
+OP_ATTN_DECODE, OP_ATTN_PREFILL, OP_PRUNE_ALL, OP_DECODE_LAYER = 1, 2, 3, 4
+
+c_i32, c_i64, c_f, vp, c_sz = (ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p,
+                               ctypes.c_size_t)
+
+
+class IhipError(RuntimeError):
+    pass
+
+
+class Tensor(ctypes.Structure):
+    _fields_ = [("ptr", vp), ("stride_b", c_i64), ("stride_h", c_i64), ("stride_t", c_i64)]
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("B", c_i32), ("Hq", c_i32), ("Hkv", c_i32), ("d", c_i32), ("Tq", c_i32),
+                ("b_q", c_i32), ("seq_lens", vp), ("max_seq_len", c_i32), ("n_sink", c_i32),
+                ("n_stream", c_i32)]
+
+
+EXPORTS = {
+    "ihip_prune_stage": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, vp, c_i32, c_i32, c_i32, c_i32,
+                                 vp, vp, vp]),
+    "ihip_stage1_slots": (c_i32, [ctypes.POINTER(Shape), c_i32]),
+    "ihip_select_blocks": (c_i32, [ctypes.POINTER(Shape), vp, c_i32, vp, c_i32, c_i32, c_i32, c_i32,
+                                   vp, vp]),
+    "ihip_sparse_attn_decode": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
+                                        c_f, vp, vp, vp, c_sz, vp]),
+    "ihip_sparse_attn_prefill": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
+                                         c_f, vp, vp, vp, c_sz, vp]),
+    "ihip_prune_all": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, c_i32, vp, vp, vp, vp, c_sz, vp]),
+    "ihip_decode_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
+                                  vp, vp, vp, vp, c_sz, vp]),
+    "ihip_workspace_bytes": (c_sz, [c_i32, ctypes.POINTER(Shape), c_i32, vp, vp]),
+    "ihip_last_error": (ctypes.c_char_p, []),
+    "ihip_version": (c_i32, []),
+}
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the in-tree HIP library; raises if it was not built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise IhipError(f"{LIB_PATH} is missing: build it with "
+                            "`python -m paper_2502_08910_amd.build` (there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise IhipError(f"ihip error {rc}: {lib().ihip_last_error().decode()}")
+
+
+def _tensor(t: torch.Tensor, name: str) -> Tensor:
+    if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1 or not t.is_cuda:
+        raise IhipError(f"{name}: need a 4-d bf16 device tensor with contiguous last dim")
+    return Tensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _i32(xs: Sequence[int]):
+    return (c_i32 * len(xs))(*xs)
+
+
+class Layer:
+    """Shape of one attention call plus the device seq_lens; the methods are
+    the C entry points of the same names."""
+
+    def __init__(self, q: torch.Tensor, k: torch.Tensor, seq_lens: torch.Tensor, b_q: int, n_sink: int,
+                 n_stream: int, max_seq_len: Optional[int] = None):
+        B, Hq, Tq, d = q.shape
+        Hkv = k.shape[1]
+        if seq_lens.dtype != torch.int32 or not seq_lens.is_cuda or seq_lens.numel() != B:
+            raise IhipError("seq_lens: need an int32 device tensor [B]")
+        self.seq_lens = seq_lens
+        self.max_seq_len = int(k.shape[2] if max_seq_len is None else max_seq_len)
+        if self.max_seq_len > k.shape[2]:
+            raise IhipError("max_seq_len exceeds the allocated tokens of K")
+        self.shape = Shape(B, Hq, Hkv, d, Tq, b_q, seq_lens.data_ptr(), self.max_seq_len, n_sink, n_stream)
+        self.B, self.Hq, self.Hkv, self.d, self.Tq, self.b_q = B, Hq, Hkv, d, Tq, b_q
+        self.P = B * Hkv * (Tq // max(b_q, 1))
+        self.device = q.device
+
+    # -- helpers ------------------------------------------------------------
+    def stage1_slots(self, chunk: int) -> int:
+        n = lib().ihip_stage1_slots(ctypes.byref(self.shape), chunk)
+        if n < 0:
+            raise IhipError(lib().ihip_last_error().decode())
+        return n
+
+    def workspace_bytes(self, op: int, chunk_sizes: Sequence[int], keeps: Sequence[int]) -> int:
+        n = lib().ihip_workspace_bytes(op, ctypes.byref(self.shape), len(chunk_sizes), _i32(chunk_sizes),
+                                       _i32(keeps))
+        if n == 0:
+            raise IhipError(lib().ihip_last_error().decode())
+        return n
+
+    def workspace(self, op: int, chunk_sizes, keeps) -> torch.Tensor:
+        return torch.empty(self.workspace_bytes(op, chunk_sizes, keeps), dtype=torch.uint8, device=self.device)
+
+    # -- entry points -------------------------------------------------------
+    def prune_stage(self, q, k, chunk: int, parent_starts: Optional[torch.Tensor] = None,
+                    parent_chunk: int = 0, want_rep: bool = False):
+        """-> scores fp32 [P, slots], rep int32 [B,Hq,Mq,slots] or None."""
+        if parent_starts is None:
+            n_parent, slots = 0, self.stage1_slots(chunk)
+        else:
+            n_parent = parent_starts.shape[-1]
+            slots = n_parent * (parent_chunk // chunk)
+        scores = torch.empty((self.P, slots), dtype=torch.float32, device=self.device)
+        rep = torch.empty((self.B, self.Hq, self.Tq // self.b_q, slots), dtype=torch.int32,
+                          device=self.device) if want_rep else None
+        _check(lib().ihip_prune_stage(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                      _ptr(parent_starts), n_parent, parent_chunk, chunk, slots,
+                                      _ptr(scores), _ptr(rep), _stream()))
+        return scores, rep
+
+    def select_blocks(self, scores: torch.Tensor, chunk: int, keep: int,
+                      parent_starts: Optional[torch.Tensor] = None, parent_chunk: int = 0):
+        """-> kept start positions int32 [P, keep], ascending, -1 padded."""
+        n_parent = 0 if parent_starts is None else parent_starts.shape[-1]
+        out = torch.empty((self.P, keep), dtype=torch.int32, device=self.device)
+        _check(lib().ihip_select_blocks(ctypes.byref(self.shape), _ptr(scores), scores.shape[-1],
+                                        _ptr(parent_starts), n_parent, parent_chunk, chunk, keep,
+                                        _ptr(out), _stream()))
+        return out
+
+    def _attn(self, fn, op, q, k, v, block_starts, block, sm_scale, want_lse, ws):
+        n_blocks = block_starts.shape[-1]
+        sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
+        out = torch.empty((self.B, self.Hq, self.Tq, self.d), dtype=torch.bfloat16, device=self.device)
+        lse = torch.empty((self.B, self.Hq, self.Tq), dtype=torch.float32, device=self.device) \
+            if want_lse else None
+        if ws is None:
+            ws = self.workspace(op, [block], [max(n_blocks, 1)])
+        _check(fn(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"), _tensor(v, "v"),
+                  _ptr(block_starts), n_blocks, block, sm_scale, _ptr(out), _ptr(lse), _ptr(ws),
+                  ws.numel(), _stream()))
+        return out, lse
+
+    def sparse_attn_decode(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None):
+        return self._attn(lib().ihip_sparse_attn_decode, OP_ATTN_DECODE, q, k, v, block_starts, block,
+                          sm_scale, want_lse, ws)
+
+    def sparse_attn_prefill(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None):
+        return self._attn(lib().ihip_sparse_attn_prefill, OP_ATTN_PREFILL, q, k, v, block_starts, block,
+                          sm_scale, want_lse, ws)
+
+    def prune_all(self, q, k, chunk_sizes, keeps, ws=None, out=None):
+        """-> last stage's kept block starts int32 [P, keeps[-1]]."""
+        if out is None:
+            out = torch.empty((self.P, keeps[-1]), dtype=torch.int32, device=self.device)
+        if ws is None:
+            ws = self.workspace(OP_PRUNE_ALL, chunk_sizes, keeps)
+        _check(lib().ihip_prune_all(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                    len(chunk_sizes), _i32(chunk_sizes), _i32(keeps), _ptr(out), _ptr(ws),
+                                    ws.numel(), _stream()))
+        return out
+
+    def decode_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
+                     out_blocks=None, lse=None):
+        """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d]."""
+        sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
+        if out is None:
+            out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
+        if ws is None:
+            ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+        _check(lib().ihip_decode_layer(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                       _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                       sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),
+                                       ws.numel(), _stream()))
+        return out

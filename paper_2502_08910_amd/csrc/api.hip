@@ -1,0 +1,314 @@
+// C ABI of the library: argument checks, error text, workspace layout and the
+// multi-stage drivers (Alg. 1; the per-layer sequence of Alg. 4 with every
+// stage refreshed).  Kernels live in the other translation units.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+
+namespace ihip {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int32_t check_launch(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(IHIP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return IHIP_OK;
+}
+
+// kernels' host launchers
+int32_t launch_prune_stage(const ihip_shape &, const ihip_tensor &, const ihip_tensor &, const int32_t *,
+                           int, int, int, int, float *, int32_t *, hipStream_t);
+int32_t launch_select_blocks(const ihip_shape &, const float *, int, const int32_t *, int, int, int, int,
+                             int32_t *, hipStream_t);
+int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
+                           const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
+                           void *, hipStream_t);
+size_t attn_decode_workspace(const ihip_shape &, int, int);
+
+static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+static int32_t check_shape(const ihip_shape *s, const char *who)
+{
+    if (!s) return fail(IHIP_ERR_INVALID_ARG, "%s: shape is NULL", who);
+    if (s->B < 0 || s->Hq <= 0 || s->Hkv <= 0 || s->Hq % s->Hkv != 0)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: bad B/Hq/Hkv = %d/%d/%d", who, s->B, s->Hq, s->Hkv);
+    const int G = s->Hq / s->Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8)
+        return fail(IHIP_ERR_UNSUPPORTED, "%s: Hq/Hkv = %d not in {1,2,4,8}", who, G);
+    if (s->d != kD) return fail(IHIP_ERR_UNSUPPORTED, "%s: d = %d, only 128 is built", who, s->d);
+    if (s->Tq <= 0 || s->b_q <= 0 || s->Tq % s->b_q != 0)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: Tq = %d must be a positive multiple of b_q = %d", who, s->Tq, s->b_q);
+    if (s->n_sink < 0 || s->n_stream < s->b_q)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: need n_sink >= 0 and n_stream >= b_q (got %d, %d, b_q %d)", who,
+                    s->n_sink, s->n_stream, s->b_q);
+    if (s->max_seq_len < s->Tq)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: max_seq_len = %d < Tq = %d", who, s->max_seq_len, s->Tq);
+    if (!s->seq_lens && s->B > 0) return fail(IHIP_ERR_INVALID_ARG, "%s: seq_lens is NULL", who);
+    return IHIP_OK;
+}
+
+static int32_t check_tensor(const ihip_tensor &t, const char *who, const char *name)
+{
+    if (!t.ptr) return fail(IHIP_ERR_INVALID_ARG, "%s: %s.ptr is NULL", who, name);
+    if (((uintptr_t)t.ptr & 15) || (t.stride_b & 7) || (t.stride_h & 7) || (t.stride_t & 7))
+        return fail(IHIP_ERR_INVALID_ARG, "%s: %s rows must be 16-byte aligned", who, name);
+    if (t.stride_t < kD && t.stride_t != 0)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: %s.stride_t = %lld < d", who, name, (long long)t.stride_t);
+    return IHIP_OK;
+}
+
+static int32_t check_slots(const char *who, const int32_t *parent_starts, int n_parent, int parent_chunk,
+                           int chunk, int max_chunks)
+{
+    if (!pow2(chunk) || chunk > 1024)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: chunk = %d must be a power of two <= 1024", who, chunk);
+    if (max_chunks < 0) return fail(IHIP_ERR_INVALID_ARG, "%s: max_chunks = %d", who, max_chunks);
+    if (parent_starts) {
+        if (!pow2(parent_chunk) || parent_chunk % chunk != 0)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: parent_chunk = %d must be a power of two multiple of chunk = %d",
+                        who, parent_chunk, chunk);
+        if (n_parent < 0 || (int64_t)n_parent * (parent_chunk / chunk) != max_chunks)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: max_chunks = %d must equal n_parent * parent_chunk / chunk = %lld",
+                        who, max_chunks, (long long)n_parent * (parent_chunk / chunk));
+    }
+    return IHIP_OK;
+}
+
+static int stage1_slots(const ihip_shape &s, int chunk)
+{
+    const int64_t mid = (int64_t)s.max_seq_len - s.n_stream - s.n_sink;
+    return mid > 0 ? (int)((mid + chunk - 1) / chunk) : 0;
+}
+
+static int32_t check_plan(const char *who, const ihip_shape *s, int n_stages, const int32_t *chunks,
+                          const int32_t *keeps)
+{
+    if (n_stages < 1 || n_stages > 8 || !chunks || !keeps)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: need 1..8 stages with chunk_sizes and keeps", who);
+    for (int i = 0; i < n_stages; ++i) {
+        if (!pow2(chunks[i]) || chunks[i] > 1024 || keeps[i] < 1)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: stage %d: chunk %d / keep %d invalid", who, i, chunks[i], keeps[i]);
+        if (i > 0 && chunks[i - 1] % chunks[i] != 0)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: stage %d: chunk %d does not divide %d", who, i, chunks[i],
+                        chunks[i - 1]);
+    }
+    (void)s;
+    return IHIP_OK;
+}
+
+// ---- workspace layout of prune_all: [scores | starts ping | starts pong] ----
+struct PlanLayout {
+    size_t scores_off, scores_bytes;
+    size_t starts_off[2], starts_bytes;
+    size_t total;
+};
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static PlanLayout plan_layout(const ihip_shape &s, int n_stages, const int32_t *chunks, const int32_t *keeps)
+{
+    const size_t P = (size_t)s.B * s.Hkv * (s.Tq / s.b_q);
+    size_t max_slots = stage1_slots(s, chunks[0]);
+    size_t max_keep = 0;
+    for (int i = 0; i < n_stages; ++i) {
+        if (i > 0) max_slots = std::max(max_slots, (size_t)keeps[i - 1] * (chunks[i - 1] / chunks[i]));
+        if (i + 1 < n_stages) max_keep = std::max(max_keep, (size_t)keeps[i]);
+    }
+    PlanLayout L;
+    L.scores_off = 0;
+    L.scores_bytes = align256(P * max_slots * sizeof(float));
+    L.starts_bytes = align256(P * max_keep * sizeof(int32_t));
+    L.starts_off[0] = L.scores_off + L.scores_bytes;
+    L.starts_off[1] = L.starts_off[0] + L.starts_bytes;
+    L.total = L.starts_off[1] + L.starts_bytes;
+    return L;
+}
+
+static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
+                              const int32_t *chunks, const int32_t *keeps, int32_t *out_block_starts,
+                              char *ws, hipStream_t st)
+{
+    const PlanLayout L = plan_layout(s, n_stages, chunks, keeps);
+    float *scores = (float *)(ws + L.scores_off);
+    const int32_t *parents = nullptr;
+    int n_parent = 0, parent_chunk = 0;
+    for (int i = 0; i < n_stages; ++i) {
+        const int slots = i == 0 ? stage1_slots(s, chunks[0]) : n_parent * (parent_chunk / chunks[i]);
+        int32_t *kept = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
+        int32_t rc = launch_prune_stage(s, q, k, parents, n_parent, parent_chunk, chunks[i], slots, scores,
+                                        nullptr, st);
+        if (rc != IHIP_OK) return rc;
+        rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i], kept, st);
+        if (rc != IHIP_OK) return rc;
+        parents = kept;
+        n_parent = keeps[i];
+        parent_chunk = chunks[i];
+    }
+    return IHIP_OK;
+}
+
+}  // namespace ihip
+
+using namespace ihip;
+
+extern "C" {
+
+const char *ihip_last_error(void) { return g_err; }
+int32_t ihip_version(void) { return 100; }
+
+int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk)
+{
+    if (check_shape(shape, "ihip_stage1_slots") != IHIP_OK || !pow2(chunk)) return -1;
+    return stage1_slots(*shape, chunk);
+}
+
+int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
+                         int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
+                         float *out_scores, int32_t *out_rep, void *stream)
+{
+    const char *who = "ihip_prune_stage";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = check_slots(who, parent_starts, n_parent, parent_chunk, chunk, max_chunks)) != IHIP_OK) return rc;
+    if (!parent_starts && max_chunks < stage1_slots(*shape, chunk))
+        return fail(IHIP_ERR_INVALID_ARG, "%s: max_chunks = %d < %d slots of the first stage", who, max_chunks,
+                    stage1_slots(*shape, chunk));
+    if (!out_scores && max_chunks > 0) return fail(IHIP_ERR_INVALID_ARG, "%s: out_scores is NULL", who);
+    if (shape->b_q == 1 && shape->Tq != 1)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: b_q == 1 is the decode path and needs Tq == 1", who);
+    return launch_prune_stage(*shape, q, k, parent_starts, n_parent, parent_chunk, chunk, max_chunks, out_scores,
+                              out_rep, (hipStream_t)stream);
+}
+
+int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
+                           const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk, int32_t chunk,
+                           int32_t keep, int32_t *out_starts, void *stream)
+{
+    const char *who = "ihip_select_blocks";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if ((rc = check_slots(who, parent_starts, n_parent, parent_chunk, chunk, max_chunks)) != IHIP_OK) return rc;
+    if (keep < 0) return fail(IHIP_ERR_INVALID_ARG, "%s: keep = %d", who, keep);
+    if (max_chunks > 65535 * 16) return fail(IHIP_ERR_UNSUPPORTED, "%s: max_chunks = %d too large", who, max_chunks);
+    if ((!scores && max_chunks > 0) || (!out_starts && keep > 0))
+        return fail(IHIP_ERR_INVALID_ARG, "%s: scores / out_starts is NULL", who);
+    return launch_select_blocks(*shape, scores, max_chunks, parent_starts, n_parent, parent_chunk, chunk, keep,
+                                out_starts, (hipStream_t)stream);
+}
+
+int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
+                                void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_sparse_attn_decode";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
+    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if (n_blocks < 0 || !pow2(block)) return fail(IHIP_ERR_INVALID_ARG, "%s: n_blocks = %d, block = %d", who, n_blocks, block);
+    if (n_blocks > 0 && !block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: block_starts is NULL", who);
+    if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
+    const size_t need = attn_decode_workspace(*shape, n_blocks, block);
+    if (!ws || ws_bytes < need)
+        return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
+    return launch_attn_decode(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, ws,
+                              (hipStream_t)stream);
+}
+
+int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
+                                 void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    (void)shape; (void)q; (void)k; (void)v; (void)block_starts; (void)n_blocks; (void)block; (void)sm_scale;
+    (void)out; (void)out_lse; (void)ws; (void)ws_bytes; (void)stream;
+    return fail(IHIP_ERR_UNSUPPORTED, "ihip_sparse_attn_prefill: not built yet");
+}
+
+int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, int32_t n_stages,
+                       const int32_t *chunk_sizes, const int32_t *keeps, int32_t *out_block_starts, void *ws,
+                       size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_prune_all";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
+    if (!out_block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: out_block_starts is NULL", who);
+    const size_t need = plan_layout(*shape, n_stages, chunk_sizes, keeps).total;
+    if (!ws || ws_bytes < need)
+        return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
+    return prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, out_block_starts, (char *)ws,
+                          (hipStream_t)stream);
+}
+
+int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                          const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
+                          float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_decode_layer";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
+    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
+    if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
+    const int last = n_stages - 1;
+    const PlanLayout L = plan_layout(*shape, n_stages, chunk_sizes, keeps);
+    const size_t P = (size_t)shape->B * shape->Hkv;
+    const size_t blocks_bytes = align256(P * keeps[last] * sizeof(int32_t));
+    const size_t attn_bytes = attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
+    const size_t need = L.total + blocks_bytes + attn_bytes;
+    if (!ws || ws_bytes < need)
+        return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
+    char *w = (char *)ws;
+    int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, (hipStream_t)stream);
+    if (rc != IHIP_OK) return rc;
+    return launch_attn_decode(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
+                              w + L.total + blocks_bytes, (hipStream_t)stream);
+}
+
+size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stages, const int32_t *chunk_sizes,
+                            const int32_t *keeps)
+{
+    if (check_shape(shape, "ihip_workspace_bytes") != IHIP_OK) return 0;
+    if (check_plan("ihip_workspace_bytes", shape, n_stages, chunk_sizes, keeps) != IHIP_OK) return 0;
+    const int last = n_stages - 1;
+    const size_t P = (size_t)shape->B * shape->Hkv * (shape->Tq / shape->b_q);
+    switch (op) {
+    case IHIP_OP_ATTN_DECODE:
+        return std::max<size_t>(256, attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]));
+    case IHIP_OP_ATTN_PREFILL:
+        return 256;
+    case IHIP_OP_PRUNE_ALL:
+        return plan_layout(*shape, n_stages, chunk_sizes, keeps).total;
+    case IHIP_OP_DECODE_LAYER:
+        return plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
+               align256(P * keeps[last] * sizeof(int32_t)) +
+               attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
+    default:
+        fail(IHIP_ERR_INVALID_ARG, "ihip_workspace_bytes: unknown op %d", op);
+        return 0;
+    }
+}
+
+}  // extern "C"

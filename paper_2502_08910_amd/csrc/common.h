@@ -1,0 +1,130 @@
+// Shared device/host helpers of the HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ihip.h"
+
+namespace ihip {
+
+constexpr int kD = 128;            // head dimension: 16 lanes x 8 bf16 (16 B) per row
+constexpr int kRowLanes = 16;      // lanes that share one K/V row
+constexpr int kWave = 64;
+
+// ---- error plumbing (api.hip) ------------------------------------------
+int32_t fail(int32_t code, const char *fmt, ...);
+int32_t check_launch(const char *what);
+
+// ---- geometry of one problem ---------------------------------------------
+struct Geometry {
+    const int32_t *seq_lens;
+    int32_t B, Hq, Hkv, G, Tq, b_q, Mq, n_sink, n_stream;
+};
+
+__host__ __device__ inline Geometry make_geometry(const ihip_shape &s)
+{
+    Geometry g;
+    g.seq_lens = s.seq_lens;
+    g.B = s.B; g.Hq = s.Hq; g.Hkv = s.Hkv; g.G = s.Hq / s.Hkv;
+    g.Tq = s.Tq; g.b_q = s.b_q; g.Mq = s.Tq / s.b_q;
+    g.n_sink = s.n_sink; g.n_stream = s.n_stream;
+    return g;
+}
+
+struct Problem {
+    int b, g, m;
+    int lo, hi, E;      // middle range [lo, hi), visible keys [0, E)
+};
+
+__device__ inline Problem problem_of(const Geometry &ge, int p)
+{
+    Problem r;
+    r.m = p % ge.Mq;
+    const int bg = p / ge.Mq;
+    r.g = bg % ge.Hkv;
+    r.b = bg / ge.Hkv;
+    const int T = ge.seq_lens[r.b];
+    r.E = (T - ge.Tq) + (r.m + 1) * ge.b_q;
+    r.lo = ge.n_sink;
+    r.hi = r.E - ge.n_stream;
+    return r;
+}
+
+// Start position of chunk slot j (or -1) -- first stage: implicit; later
+// stages: child c of parent i.
+__device__ inline int slot_start(const Problem &pr, const int32_t *parent_starts, int n_parent,
+                                 int ratio_log2, int chunk, int p, int j)
+{
+    int start;
+    if (parent_starts == nullptr) {
+        start = pr.lo + j * chunk;
+    } else {
+        const int ps = parent_starts[(int64_t)p * n_parent + (j >> ratio_log2)];
+        if (ps < 0) return -1;
+        start = ps + (j & ((1 << ratio_log2) - 1)) * chunk;
+    }
+    return start < pr.hi ? start : -1;
+}
+
+// ---- bf16 ------------------------------------------------------------------
+__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// round-to-nearest-even fp32 -> bf16 (finite inputs)
+__device__ inline uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// 8 bf16 (one lane's 16-byte share of a row) dotted with 8 fp32
+__device__ inline float dot8(const uint4 &k, const float (&q)[8])
+{
+    float s = bf16_lo(k.x) * q[0];
+    s = fmaf(bf16_hi(k.x), q[1], s);
+    s = fmaf(bf16_lo(k.y), q[2], s);
+    s = fmaf(bf16_hi(k.y), q[3], s);
+    s = fmaf(bf16_lo(k.z), q[4], s);
+    s = fmaf(bf16_hi(k.z), q[5], s);
+    s = fmaf(bf16_lo(k.w), q[6], s);
+    s = fmaf(bf16_hi(k.w), q[7], s);
+    return s;
+}
+
+__device__ inline void unpack8(const uint4 &k, float (&f)[8])
+{
+    f[0] = bf16_lo(k.x); f[1] = bf16_hi(k.x);
+    f[2] = bf16_lo(k.y); f[3] = bf16_hi(k.y);
+    f[4] = bf16_lo(k.z); f[5] = bf16_hi(k.z);
+    f[6] = bf16_lo(k.w); f[7] = bf16_hi(k.w);
+}
+
+// ---- cross-lane -----------------------------------------------------------
+template <int CTRL>
+__device__ inline float dpp_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the same
+// bits (each step adds a value to its mirror image, and fp add commutes).
+__device__ inline float row16_sum(float v)
+{
+    v += dpp_f32<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_f32<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f32<0x141>(v);   // row_half_mirror
+    v += dpp_f32<0x140>(v);   // row_mirror
+    return v;
+}
+
+__device__ inline int ilog2(int x) { return 31 - __builtin_clz(x); }
+
+// 16-byte row fragment load for lane l16 of a row group
+__device__ inline uint4 load_row16(const uint16_t *base, int64_t row_elem_offset, int l16)
+{
+    return *reinterpret_cast<const uint4 *>(base + row_elem_offset + l16 * 8);
+}
+
+}  // namespace ihip

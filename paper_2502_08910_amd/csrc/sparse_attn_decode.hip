@@ -1,0 +1,249 @@
+// Block-sparse decode attention over sink + kept blocks + window.
+//
+// HBM-bound gather of K and V rows (512 B per attended token, shared by the G
+// query heads of the KV head).  Flash-decoding layout: the attended tokens of
+// a problem form a virtual slot list  [sink | kept blocks | window];  the list
+// is cut into splits, one workgroup each; inside a workgroup every 16-lane
+// group owns one token at a time (16 B of the K row and of the V row per
+// lane) and keeps an online-softmax state for all G heads; groups are merged
+// through LDS, splits by a second small kernel (log-sum-exp merge).
+#include "common.h"
+
+namespace ihip {
+
+constexpr int kAttnThreads = 256;
+constexpr int kAttnGroups = kAttnThreads / kRowLanes;   // 16 tokens in flight per step
+constexpr float kNegBig = -1.0e30f;                      // finite stand-in for -inf in running maxima
+
+struct AttnDecodeArgs {
+    Geometry ge;
+    const uint16_t *q; int64_t q_sb, q_sh, q_st;
+    const uint16_t *k; int64_t k_sb, k_sh, k_st;
+    const uint16_t *v; int64_t v_sb, v_sh, v_st;
+    const int32_t *block_starts;
+    int n_blocks, block, block_log2;
+    float scale_log2e;
+    int n_splits, slots_per_split;
+    float *part_ml;      // [P, n_splits, G, 2]   (running max in log2 units, sum)
+    float *part_acc;     // [P, n_splits, G, 128]
+    uint16_t *out;       // bf16 [B, Hq, 1, d]
+    float *out_lse;      // [B, Hq] or null
+};
+
+// slot -> key position, or -1
+__device__ inline int slot_to_pos(const AttnDecodeArgs &a, const Problem &pr, int p, int slot,
+                                  int n_sink_eff, int w0)
+{
+    if (slot < n_sink_eff) return slot;
+    slot -= n_sink_eff;
+    const int nb = a.n_blocks << a.block_log2;
+    if (slot < nb) {
+        const int bs = a.block_starts[(int64_t)p * a.n_blocks + (slot >> a.block_log2)];
+        if (bs < 0) return -1;
+        const int pos = bs + (slot & (a.block - 1));
+        return pos < pr.hi ? pos : -1;
+    }
+    const int pos = w0 + (slot - nb);
+    return pos < pr.E ? pos : -1;
+}
+
+template <int G>
+__global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const AttnDecodeArgs a)
+{
+    const int p = blockIdx.y, split = blockIdx.x;
+    const Problem pr = problem_of(a.ge, p);
+    const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int n_sink_eff = min(a.ge.n_sink, pr.E);
+    const int w0 = max(pr.hi, a.ge.n_sink);
+
+    float qf[G][8];
+    {
+        const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)(pr.g * G) * a.q_sh;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            unpack8(load_row16(qb, h * a.q_sh, l16), qf[h]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qf[h][i] *= a.scale_log2e;
+        }
+    }
+    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+    const uint16_t *vb = a.v + pr.b * a.v_sb + pr.g * a.v_sh;
+
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        m[h] = kNegBig; l[h] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[h][i] = 0.f;
+    }
+
+    constexpr int UNR = 4;
+    const int s0 = split * a.slots_per_split;
+    const int s1 = s0 + a.slots_per_split;
+    for (int base = s0 + grp; base < s1; base += kAttnGroups * UNR) {
+        uint4 kr[UNR], vr[UNR];
+        bool ok[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int slot = base + u * kAttnGroups;
+            const int pos = slot < s1 ? slot_to_pos(a, pr, p, slot, n_sink_eff, w0) : -1;
+            ok[u] = pos >= 0;
+            kr[u] = make_uint4(0, 0, 0, 0);
+            vr[u] = make_uint4(0, 0, 0, 0);
+            if (ok[u]) {
+                kr[u] = load_row16(kb, (int64_t)pos * a.k_st, l16);
+                vr[u] = load_row16(vb, (int64_t)pos * a.v_st, l16);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            float vf[8];
+            unpack8(vr[u], vf);
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float s = row16_sum(dot8(kr[u], qf[h]));      // log2-scaled score
+                const float mn = ok[u] ? fmaxf(m[h], s) : m[h];
+                const float corr = exp2f(m[h] - mn);
+                const float pw = ok[u] ? exp2f(s - mn) : 0.f;
+                m[h] = mn;
+                l[h] = l[h] * corr + pw;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[h][i] = fmaf(pw, vf[i], acc[h][i] * corr);
+            }
+        }
+    }
+
+    // merge the 4 groups of each wave in registers (lanes l, l^16, l^32, l^48 hold the same dims)
+#pragma unroll
+    for (int d = 16; d <= 32; d <<= 1) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float mo = __shfl_xor(m[h], d, 64);
+            const float lo = __shfl_xor(l[h], d, 64);
+            const float mn = fmaxf(m[h], mo);
+            const float wa = exp2f(m[h] - mn), wb = exp2f(mo - mn);
+            l[h] = l[h] * wa + lo * wb;
+            m[h] = mn;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float ao = __shfl_xor(acc[h][i], d, 64);
+                acc[h][i] = acc[h][i] * wa + ao * wb;
+            }
+        }
+    }
+    // then the waves through LDS
+    constexpr int NW = kAttnThreads / kWave;
+    __shared__ float sh_m[NW][G], sh_l[NW][G];
+    __shared__ float sh_acc[NW][G][kD];
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) { sh_m[wv][h] = m[h]; sh_l[wv][h] = l[h]; }
+    }
+    if (lane < 16) {
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sh_acc[wv][h][l16 * 8 + i] = acc[h][i];
+    }
+    __syncthreads();
+
+    const int64_t pbase = ((int64_t)p * a.n_splits + split) * G;
+    for (int idx = threadIdx.x; idx < G * kD; idx += kAttnThreads) {
+        const int h = idx / kD, c = idx % kD;
+        float M = kNegBig;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) M = fmaxf(M, sh_m[w2][h]);
+        float L = 0.f, A = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) {
+            const float w = exp2f(sh_m[w2][h] - M);
+            L = fmaf(w, sh_l[w2][h], L);
+            A = fmaf(w, sh_acc[w2][h][c], A);
+        }
+        a.part_acc[(pbase + h) * kD + c] = A;
+        if (c == 0) {
+            a.part_ml[(pbase + h) * 2 + 0] = M;
+            a.part_ml[(pbase + h) * 2 + 1] = L;
+        }
+    }
+}
+
+// merge the splits: one workgroup of 128 threads per (problem, head)
+__global__ __launch_bounds__(kD) void attn_decode_merge_kernel(const AttnDecodeArgs a)
+{
+    const int G = a.ge.G;
+    const int p = blockIdx.x / G, h = blockIdx.x % G;
+    const int c = threadIdx.x;
+    const Problem pr = problem_of(a.ge, p);
+    const int64_t pbase = (int64_t)p * a.n_splits * G;
+    float M = kNegBig;
+    for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, a.part_ml[(pbase + (int64_t)s * G + h) * 2]);
+    float L = 0.f, A = 0.f;
+    for (int s = 0; s < a.n_splits; ++s) {
+        const int64_t r = pbase + (int64_t)s * G + h;
+        const float w = exp2f(a.part_ml[r * 2] - M);
+        L = fmaf(w, a.part_ml[r * 2 + 1], L);
+        A = fmaf(w, a.part_acc[r * kD + c], A);
+    }
+    const int hq = pr.g * G + h;
+    a.out[((int64_t)pr.b * a.ge.Hq + hq) * kD + c] = (uint16_t)f32_to_bf16_bits(A / L);
+    if (a.out_lse != nullptr && c == 0)
+        a.out_lse[(int64_t)pr.b * a.ge.Hq + hq] = (M + log2f(L)) * 0.69314718055994530942f;
+}
+
+static int decode_splits(const ihip_shape &s, int n_blocks, int block, int *slots_per_split)
+{
+    const int total = s.n_sink + n_blocks * block + s.n_stream;
+    // 16 tokens per step and 4 steps per unrolled iteration: keep splits a multiple of 64 slots
+    const int per = 256;
+    *slots_per_split = per;
+    return (total + per - 1) / per;
+}
+
+size_t attn_decode_workspace(const ihip_shape &s, int n_blocks, int block)
+{
+    int per;
+    const int ns = decode_splits(s, n_blocks, block, &per);
+    const size_t P = (size_t)s.B * s.Hkv;
+    const size_t G = s.Hq / s.Hkv;
+    return P * ns * G * (2 + kD) * sizeof(float);
+}
+
+int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
+                           const ihip_tensor &v, const int32_t *block_starts, int n_blocks, int block,
+                           float sm_scale, void *out, float *out_lse, void *ws, hipStream_t st)
+{
+    AttnDecodeArgs a;
+    a.ge = make_geometry(s);
+    a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
+    a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
+    a.v = (const uint16_t *)v.ptr; a.v_sb = v.stride_b; a.v_sh = v.stride_h; a.v_st = v.stride_t;
+    a.block_starts = block_starts;
+    a.n_blocks = n_blocks;
+    a.block = block;
+    a.block_log2 = __builtin_ctz(block);
+    a.scale_log2e = sm_scale * 1.44269504088896340736f;
+    a.n_splits = decode_splits(s, n_blocks, block, &a.slots_per_split);
+    const int P = s.B * s.Hkv;
+    const int G = a.ge.G;
+    a.part_ml = (float *)ws;
+    a.part_acc = a.part_ml + (size_t)P * a.n_splits * G * 2;
+    a.out = (uint16_t *)out;
+    a.out_lse = out_lse;
+    if (P == 0) return IHIP_OK;
+    dim3 grid(a.n_splits, P);
+    switch (G) {
+    case 1: hipLaunchKernelGGL(attn_decode_split_kernel<1>, grid, dim3(kAttnThreads), 0, st, a); break;
+    case 2: hipLaunchKernelGGL(attn_decode_split_kernel<2>, grid, dim3(kAttnThreads), 0, st, a); break;
+    case 4: hipLaunchKernelGGL(attn_decode_split_kernel<4>, grid, dim3(kAttnThreads), 0, st, a); break;
+    case 8: hipLaunchKernelGGL(attn_decode_split_kernel<8>, grid, dim3(kAttnThreads), 0, st, a); break;
+    default: return fail(IHIP_ERR_UNSUPPORTED, "Hq/Hkv = %d not in {1,2,4,8}", G);
+    }
+    int32_t rc = check_launch("sparse_attn_decode (split)");
+    if (rc != IHIP_OK) return rc;
+    hipLaunchKernelGGL(attn_decode_merge_kernel, dim3(P * G), dim3(kD), 0, st, a);
+    return check_launch("sparse_attn_decode (merge)");
+}
+
+}  // namespace ihip

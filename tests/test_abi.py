@@ -1,0 +1,60 @@
+"""The C-ABI library loads and exports every symbol the header declares
+(no compute calls: this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ihip.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ihip_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def built_lib():
+    import paper_2502_08910_amd as pkg
+    if not os.path.exists(pkg.LIB_PATH):
+        from paper_2502_08910_amd.build import build
+        build(verbose=False)
+    return pkg
+
+
+def test_header_symbols_are_exported(built_lib):
+    syms = declared_symbols()
+    assert {"ihip_prune_stage", "ihip_select_blocks", "ihip_sparse_attn_decode",
+            "ihip_sparse_attn_prefill"} <= set(syms)
+    L = ctypes.CDLL(built_lib.LIB_PATH)
+    for s in syms:
+        assert hasattr(L, s), s
+    assert set(built_lib.binding.EXPORTS) == set(syms)
+
+
+def test_version_and_error_text(built_lib):
+    L = built_lib.lib()
+    assert L.ihip_version() >= 100
+    assert isinstance(L.ihip_last_error(), bytes)
+
+
+def test_argument_checks_need_no_gpu(built_lib):
+    # every check happens before anything is enqueued
+    from paper_2502_08910_amd.binding import Shape, Tensor
+    L = built_lib.lib()
+    s = Shape(1, 32, 8, 64, 1, 1, 1, 100, 4, 4)             # d = 64: unsupported
+    t = Tensor(256, 0, 0, 128)
+    rc = L.ihip_prune_stage(ctypes.byref(s), t, t, None, 0, 0, 16, 10, 256, None, None)
+    assert rc == -4 and b"128" in L.ihip_last_error()
+    s = Shape(1, 32, 8, 128, 1, 1, 1, 100, 4, 4)
+    assert L.ihip_prune_stage(ctypes.byref(s), t, t, None, 0, 0, 24, 10, 256, None, None) == -1   # chunk not 2^n
+    assert L.ihip_prune_stage(ctypes.byref(s), t, t, None, 0, 0, 16, 2, 256, None, None) == -1    # too few slots
+    assert L.ihip_stage1_slots(ctypes.byref(s), 16) == 6
+    s2 = Shape(1, 32, 8, 128, 1, 1, 1, 100, 4, 0)           # n_stream < b_q
+    assert L.ihip_select_blocks(ctypes.byref(s2), 256, 6, None, 0, 0, 16, 2, 256, None) == -1
+    rc = L.ihip_sparse_attn_decode(ctypes.byref(s), t, t, t, 256, 4, 4, 1.0, 256, None, 256, 16, None)
+    assert rc == -2 and b"workspace" in L.ihip_last_error()
+    one = (ctypes.c_int32 * 1)(16)
+    assert L.ihip_workspace_bytes(99, ctypes.byref(s), 1, one, one) == 0
