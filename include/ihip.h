@@ -82,8 +82,8 @@ typedef struct {
  * j = i*(parent_chunk/chunk) + c is child c of parent i, cut at hi.  A slot that
  * holds no key gets score -INFINITY (this is how later calls recognise it).
  *
- *   max_chunks   slots per problem: >= ceil((max_seq_len-Tq+Tq... see ihip_stage1_slots)
- *                for the first stage, = n_parent*(parent_chunk/chunk) otherwise
+ *   max_chunks   slots per problem: >= ihip_stage1_slots(shape, chunk) for the first
+ *                stage, = n_parent*(parent_chunk/chunk) otherwise
  *   out_scores   device fp32 [P, max_chunks]
  *   out_rep      device int32 [B, Hq, Mq, max_chunks] representative positions
  *                (-1 for empty slots); may be NULL
@@ -170,6 +170,18 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
  */
 size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stages,
                             const int32_t *chunk_sizes, const int32_t *keeps);
+
+/*
+ * Optional per-kernel timing (the measurement protocol, not the method): while
+ * enabled, every kernel the library launches is bracketed by two HIP events on
+ * its stream (events are created on first use and recycled).  ihip_profile_read
+ * waits for the recorded events, adds them up per kernel name and forgets
+ * them: it fills up to max_entries of names (static strings owned by the
+ * library), total_ms and launches (host arrays) and returns the number of
+ * distinct kernels, or a negative error.  Not for use under graph capture.
+ */
+int32_t ihip_profile_enable(int32_t on);
+int32_t ihip_profile_read(int32_t max_entries, const char **names, double *total_ms, int64_t *launches);
 
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char *ihip_last_error(void);

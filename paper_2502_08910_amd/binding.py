@@ -50,6 +50,8 @@ EXPORTS = {
     "ihip_decode_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
                                   vp, vp, vp, vp, c_sz, vp]),
     "ihip_workspace_bytes": (c_sz, [c_i32, ctypes.POINTER(Shape), c_i32, vp, vp]),
+    "ihip_profile_enable": (c_i32, [c_i32]),
+    "ihip_profile_read": (c_i32, [c_i32, vp, vp, vp]),
     "ihip_last_error": (ctypes.c_char_p, []),
     "ihip_version": (c_i32, []),
 }
@@ -93,6 +95,21 @@ def _ptr(t: Optional[torch.Tensor]):
 
 def _i32(xs: Sequence[int]):
     return (c_i32 * len(xs))(*xs)
+
+
+def profile_enable(on: bool) -> None:
+    _check(lib().ihip_profile_enable(int(on)))
+
+
+def profile_read(max_entries: int = 64) -> dict:
+    """{kernel name: (total ms, launches)} of the launches recorded since the last read."""
+    names = (ctypes.c_char_p * max_entries)()
+    ms = (ctypes.c_double * max_entries)()
+    cnt = (ctypes.c_int64 * max_entries)()
+    n = lib().ihip_profile_read(max_entries, names, ms, cnt)
+    if n < 0:
+        _check(n)
+    return {names[i].decode(): (ms[i], cnt[i]) for i in range(n)}
 
 
 class Layer:

@@ -4,6 +4,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "common.h"
 
@@ -25,6 +27,49 @@ int32_t check_launch(const char *what)
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(IHIP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
     return IHIP_OK;
+}
+
+// ---- per-kernel event timing -------------------------------------------------
+namespace {
+struct Span { const char *name; hipEvent_t t0, t1; };
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<Span> g_spans;                 // recorded, not yet read
+std::vector<hipEvent_t> g_free_events;     // recycled
+hipEvent_t take_event()
+{
+    hipEvent_t e;
+    if (!g_free_events.empty()) { e = g_free_events.back(); g_free_events.pop_back(); return e; }
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+const char *stage_name(int which, bool first, int chunk)
+{
+    static char names[3][2][11][40];
+    static const char *prefix[3] = {"prune_decode", "prune_prefill", "select_blocks"};
+    const int lg = __builtin_ctz(chunk);
+    char *n = names[which][first][lg];
+    if (n[0] == 0) snprintf(n, 40, first ? "%s.first.l%d" : "%s.l%d", prefix[which], chunk);
+    return n;
+}
+
+void profile_begin(const char *name, hipStream_t st)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof_on) return;
+    Span s{name, take_event(), take_event()};
+    if (!s.t0 || !s.t1) return;
+    hipEventRecord(s.t0, st);
+    g_spans.push_back(s);
+}
+
+void profile_end(hipStream_t st)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof_on || g_spans.empty()) return;
+    hipEventRecord(g_spans.back().t1, st);
 }
 
 // kernels' host launchers
@@ -285,6 +330,36 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
     if (rc != IHIP_OK) return rc;
     return launch_attn_decode(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
                               w + L.total + blocks_bytes, (hipStream_t)stream);
+}
+
+int32_t ihip_profile_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = on != 0;
+    return IHIP_OK;
+}
+
+int32_t ihip_profile_read(int32_t max_entries, const char **names, double *total_ms, int64_t *launches)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    int n = 0;
+    for (const Span &s : g_spans) {
+        float ms = 0.f;
+        if (hipEventSynchronize(s.t1) != hipSuccess || hipEventElapsedTime(&ms, s.t0, s.t1) != hipSuccess)
+            return fail(IHIP_ERR_HIP, "ihip_profile_read: event query failed");
+        int i = 0;
+        while (i < n && names[i] != s.name) ++i;
+        if (i == n) {
+            if (n == max_entries) continue;
+            names[n] = s.name; total_ms[n] = 0.0; launches[n] = 0; ++n;
+        }
+        total_ms[i] += ms;
+        launches[i] += 1;
+        g_free_events.push_back(s.t0);
+        g_free_events.push_back(s.t1);
+    }
+    g_spans.clear();
+    return n;
 }
 
 size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stages, const int32_t *chunk_sizes,

@@ -16,6 +16,20 @@ constexpr int kWave = 64;
 int32_t fail(int32_t code, const char *fmt, ...);
 int32_t check_launch(const char *what);
 
+// ---- optional per-kernel timing (api.hip) ----------------------------------
+// When profiling is on, a KernelTimer brackets one kernel launch with two HIP
+// events on the launch stream; ihip_profile_read() sums them up per name.
+void profile_begin(const char *name, hipStream_t st);
+void profile_end(hipStream_t st);
+// Static name "<prefix>.l<chunk>" (or "<prefix>.first.l<chunk>") for the timing table.
+const char *stage_name(int which, bool first, int chunk);
+enum { kNamePruneDecode = 0, kNamePrunePrefill = 1, kNameSelect = 2 };
+struct KernelTimer {
+    hipStream_t st;
+    KernelTimer(const char *name, hipStream_t s) : st(s) { profile_begin(name, s); }
+    ~KernelTimer() { profile_end(st); }
+};
+
 // ---- geometry of one problem ---------------------------------------------
 struct Geometry {
     const int32_t *seq_lens;

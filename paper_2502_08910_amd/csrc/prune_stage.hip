@@ -130,6 +130,7 @@ static void launch_decode(const PruneArgs &a, int P, hipStream_t st)
 {
     constexpr int U = 2;
     dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
+    KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
     hipLaunchKernelGGL((prune_decode_kernel<G, U>), grid, dim3(256), 0, st, a);
 }
 

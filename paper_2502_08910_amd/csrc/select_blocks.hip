@@ -154,6 +154,7 @@ int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_c
     a.out_starts = out_starts;
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (P == 0 || keep == 0) return IHIP_OK;
+    KernelTimer timer(stage_name(kNameSelect, parent_starts == nullptr, chunk), st);
     hipLaunchKernelGGL(select_blocks_kernel, dim3(P), dim3(kSelThreads), 0, st, a);
     return check_launch("select_blocks");
 }

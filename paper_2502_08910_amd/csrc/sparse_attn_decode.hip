@@ -233,6 +233,8 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     a.out_lse = out_lse;
     if (P == 0) return IHIP_OK;
     dim3 grid(a.n_splits, P);
+    {
+    KernelTimer timer("attn_decode_split", st);
     switch (G) {
     case 1: hipLaunchKernelGGL(attn_decode_split_kernel<1>, grid, dim3(kAttnThreads), 0, st, a); break;
     case 2: hipLaunchKernelGGL(attn_decode_split_kernel<2>, grid, dim3(kAttnThreads), 0, st, a); break;
@@ -240,8 +242,10 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     case 8: hipLaunchKernelGGL(attn_decode_split_kernel<8>, grid, dim3(kAttnThreads), 0, st, a); break;
     default: return fail(IHIP_ERR_UNSUPPORTED, "Hq/Hkv = %d not in {1,2,4,8}", G);
     }
+    }
     int32_t rc = check_launch("sparse_attn_decode (split)");
     if (rc != IHIP_OK) return rc;
+    KernelTimer timer("attn_decode_merge", st);
     hipLaunchKernelGGL(attn_decode_merge_kernel, dim3(P * G), dim3(kD), 0, st, a);
     return check_launch("sparse_attn_decode (merge)");
 }

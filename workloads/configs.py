@@ -6,6 +6,7 @@ by a fixed recipe so that some keys are known to matter.
 """
 from __future__ import annotations
 
+import math
 from dataclasses import dataclass, field, replace
 from typing import List, Tuple
 
@@ -79,30 +80,35 @@ def make_kv(w: Workload, seed: int, device="cpu", kind="normal"):
 
 def needle_rows(w: Workload, q: torch.Tensor, seed: int):
     """Positions [B,Hkv,n] (int64) and bf16 key rows [B,Hkv,n,d] of the planted
-    needles: n distinct stage-1 chunks of the middle range per (sequence, KV
-    head); the key at the chunk's first position is gain*q_h/|q_h| + noise*N(0,1)
-    for query head h = g*G + (i mod G), using the block's first query.  Computed
-    on the CPU in fp32 whatever device q lives on."""
+    needles: n distinct full stage-1 chunks of the middle range per (sequence,
+    KV head), an arithmetic progression (offset + i*stride) mod n_chunks with a
+    seeded offset and a seeded stride coprime to n_chunks; the key at the
+    chunk's first position is gain*q_h/|q_h| + noise*N(0,1) for query head
+    h = g*G + (i mod G), using the first query.  Computed on the CPU in fp32
+    whatever device q lives on."""
     l1 = w.stages[0][0]
-    # middle range of the first query block (decode: the only one)
-    E = (w.T - w.Tq) + w.b_q
-    n_chunks = (E - w.n_sink - w.n_stream) // l1          # full chunks only
-    qc = q.detach().to("cpu", torch.float32)
-    pos = torch.empty((w.B, w.Hkv, w.n_needles), dtype=torch.int64)
-    rows = torch.empty((w.B, w.Hkv, w.n_needles, w.d), dtype=torch.bfloat16)
+    E = (w.T - w.Tq) + w.b_q                      # first query block (decode: the only one)
+    n_chunks = (E - w.n_sink - w.n_stream) // l1  # full chunks only
+    n = w.n_needles
+    assert n <= n_chunks
+    q0 = q.detach()[:, :, 0].to("cpu", torch.float32)                       # [B,Hq,d]
+    qn = q0 / q0.norm(dim=-1, keepdim=True)
+    par = gen.uniform_ints(seed, TID_NEEDLE_POS, 2 * w.B * w.Hkv, 1 << 30).view(w.B, w.Hkv, 2)
+    off = par[..., 0] % n_chunks
+    stride = par[..., 1] % n_chunks
     for b in range(w.B):
         for g in range(w.Hkv):
-            chunks = gen.distinct_ints(seed, TID_NEEDLE_POS + 16 * (b * w.Hkv + g),
-                                       w.n_needles, n_chunks)
-            pos[b, g] = w.n_sink + chunks * l1
-            noise = gen.normal_bf16(seed, TID_NEEDLE_NOISE,
-                                    (w.B, w.Hkv, w.n_needles, w.d), "cpu",
-                                    (b, b + 1, g, g + 1, 0, w.n_needles))[0, 0].float()
-            for i in range(w.n_needles):
-                h = g * w.G + (i % w.G)
-                qv = qc[b, h, 0]
-                kv = w.needle_gain * qv / qv.norm() + w.needle_noise * noise[i]
-                rows[b, g, i] = kv.to(torch.bfloat16)
+            st = max(1, int(stride[b, g]))
+            while math.gcd(st, n_chunks) != 1:
+                st += 1
+            stride[b, g] = st
+    i = torch.arange(n, dtype=torch.int64)
+    chunks = (off[..., None] + i * stride[..., None]) % n_chunks            # [B,Hkv,n]
+    pos = w.n_sink + chunks * l1
+    heads = (torch.arange(w.Hkv).view(1, -1, 1) * w.G + (i % w.G).view(1, 1, -1)).expand(w.B, -1, -1)
+    qsel = torch.gather(qn, 1, heads.reshape(w.B, -1, 1).expand(-1, -1, w.d)).view(w.B, w.Hkv, n, w.d)
+    noise = gen.normal_bf16(seed, TID_NEEDLE_NOISE, (w.B, w.Hkv, n, w.d)).float()
+    rows = (w.needle_gain * qsel + w.needle_noise * noise).to(torch.bfloat16)
     return pos, rows
 
 
@@ -111,9 +117,9 @@ def plant_needles(w: Workload, k: torch.Tensor, q: torch.Tensor, seed: int) -> t
     if w.n_needles == 0:
         return torch.empty((w.B, w.Hkv, 0), dtype=torch.int64)
     pos, rows = needle_rows(w, q, seed)
-    for b in range(w.B):
-        for g in range(w.Hkv):
-            k[b, g, pos[b, g].to(k.device)] = rows[b, g].to(k.device)
+    bi = torch.arange(w.B).view(-1, 1, 1).expand_as(pos).to(k.device)
+    gi = torch.arange(w.Hkv).view(1, -1, 1).expand_as(pos).to(k.device)
+    k[bi, gi, pos.to(k.device)] = rows.to(k.device)
     return pos
 
 
