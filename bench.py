@@ -34,7 +34,10 @@ N_QUERY_SETS = 32
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see
 # profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # FETCH_SIZE 781,266 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 1,220 KiB x 1.0 per launch
+    ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781265.9 * 2.0 + 1220.0) * 1024.0,
+}
 
 
 def parse():
