@@ -81,6 +81,9 @@ int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_t
                            const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
                            void *, hipStream_t);
 size_t attn_decode_workspace(const ihip_shape &, int, int);
+int32_t launch_attn_prefill(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
+                            const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
+                            hipStream_t);
 
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
@@ -280,9 +283,20 @@ int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_te
                                  const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
                                  void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
 {
-    (void)shape; (void)q; (void)k; (void)v; (void)block_starts; (void)n_blocks; (void)block; (void)sm_scale;
-    (void)out; (void)out_lse; (void)ws; (void)ws_bytes; (void)stream;
-    return fail(IHIP_ERR_UNSUPPORTED, "ihip_sparse_attn_prefill: not built yet");
+    const char *who = "ihip_sparse_attn_prefill";
+    int32_t rc;
+    (void)ws; (void)ws_bytes;       // this kernel needs no scratch
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->b_q != 16 && shape->b_q != 32 && shape->b_q != 64)
+        return fail(IHIP_ERR_UNSUPPORTED, "%s: b_q = %d not in {16, 32, 64}", who, shape->b_q);
+    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if (n_blocks < 0 || !pow2(block)) return fail(IHIP_ERR_INVALID_ARG, "%s: n_blocks = %d, block = %d", who, n_blocks, block);
+    if (n_blocks > 0 && !block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: block_starts is NULL", who);
+    if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
+    return launch_attn_prefill(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse,
+                               (hipStream_t)stream);
 }
 
 int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, int32_t n_stages,

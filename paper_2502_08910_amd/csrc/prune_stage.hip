@@ -125,6 +125,137 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Chunked-prefill kernel (b_q = 16*MT queries per block).  The score of a key
+// is max_t q_t . k over the block's queries: a [b_q x 128] x [128 x 16] matrix
+// product per 16 candidate keys, done on the matrix cores
+// (v_mfma_f32_16x16x32_bf16; queries are the rows, candidates the columns, so
+// the max over queries is an in-lane max over the accumulator plus two
+// cross-lane steps).  One wave per query head, G waves per workgroup; a wave
+// walks the searches of NT*16 chunks at a time, one candidate row per chunk
+// and level.  Workgroups are ordered so that all query blocks and KV heads
+// sweep the same chunk range together: the K rows they share stay in L2.
+// Operand layout: lane l holds 8 consecutive dims (kq = l/16) of row/column
+// l%16; accumulator lane l holds column l%16, rows 4*(l/16)..+3.
+// ---------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int MT, int NT>
+__global__ __launch_bounds__(512) void prune_prefill_kernel(const PruneArgs a, const int iters)
+{
+    __shared__ float sh_sigma[8][NT * 16];
+    const int p = blockIdx.x;
+    const Problem pr = problem_of(a.ge, p);
+    const int G = a.ge.G;
+    const int lane = threadIdx.x & 63, hh = threadIdx.x >> 6;      // wave = query head of the group
+    const int n = lane & 15, kq = lane >> 4;
+    const int h = pr.g * G + hh;
+
+    // A operands: the block's queries, [MT tiles of 16 rows] x [4 steps of 32 dims]
+    bf16x8 qa[MT][4];
+    {
+        const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(pr.m * a.ge.b_q) * a.q_st;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                qa[mt][ks] = *reinterpret_cast<const bf16x8 *>(qb + (int64_t)(mt * 16 + n) * a.q_st + ks * 32 + kq * 8);
+    }
+    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh + kq * 8;
+
+    // score of candidate rows pos[t] (column n of tile t): max over the block's queries
+    auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT]) {
+        bf16x8 kr[NT][4];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                uint4 z = make_uint4(0, 0, 0, 0);
+                if (ok[t]) z = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos[t] * a.k_st + ks * 32);
+                kr[t][ks] = __builtin_bit_cast(bf16x8, z);
+            }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            float best = -INFINITY;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[mt][ks], kr[t][ks], c, 0, 0, 0);
+                best = fmaxf(best, fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3])));
+            }
+            best = fmaxf(best, __shfl_xor(best, 16, 64));
+            best = fmaxf(best, __shfl_xor(best, 32, 64));
+            sig[t] = best;
+        }
+    };
+
+    for (int it = 0; it < iters; ++it) {
+        const int jt = (blockIdx.y * iters + it) * NT * 16;
+        int start[NT], len[NT], off[NT], pos[NT];
+        bool valid[NT], ok[NT];
+        float sigma[NT], s[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int j = jt + t * 16 + n;
+            start[t] = j < a.max_chunks
+                           ? slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, j)
+                           : -1;
+            valid[t] = start[t] >= 0;
+            len[t] = valid[t] ? min(a.chunk, pr.hi - start[t]) : 0;
+            off[t] = 0;
+            pos[t] = start[t];
+        }
+        score(pos, valid, sigma);
+        for (int half = a.chunk >> 1; half >= 1; half >>= 1) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                ok[t] = off[t] + half < len[t];
+                pos[t] = start[t] + off[t] + half;
+            }
+            score(pos, ok, s);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                if (ok[t] && s[t] > sigma[t]) { off[t] += half; sigma[t] = s[t]; }   // strict: tie keeps left
+        }
+        // chunk score = max over the group's heads (waves)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int j = jt + t * 16 + n;
+            if (kq == 0) sh_sigma[hh][t * 16 + n] = sigma[t];
+            if (a.out_rep != nullptr && kq == 0 && j < a.max_chunks) {
+                const int64_t row = ((int64_t)(pr.b * a.ge.Hq + h) * a.ge.Mq + pr.m);
+                a.out_rep[row * a.max_chunks + j] = valid[t] ? start[t] + off[t] : -1;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < NT * 16) {
+            const int j = jt + threadIdx.x;
+            if (j < a.max_chunks) {
+                float best = sh_sigma[0][threadIdx.x];
+                for (int g2 = 1; g2 < G; ++g2) best = fmaxf(best, sh_sigma[g2][threadIdx.x]);
+                // validity is the same for every head; recompute it for this slot
+                const bool v = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, j) >= 0;
+                a.out_scores[(int64_t)p * a.max_chunks + j] = v ? best : -INFINITY;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int MT>
+static void launch_prefill(const PruneArgs &a, int P, hipStream_t st)
+{
+    constexpr int NT = 2;
+    const int iters = 2;
+    const int per_wg = NT * 16 * iters;
+    dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
+    KernelTimer timer(stage_name(kNamePrunePrefill, a.parent_starts == nullptr, a.chunk), st);
+    hipLaunchKernelGGL((prune_prefill_kernel<MT, NT>), grid, dim3(64 * a.ge.G), 0, st, a, iters);
+}
+
 template <int G>
 static void launch_decode(const PruneArgs &a, int P, hipStream_t st)
 {
@@ -161,7 +292,13 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
         }
         return check_launch("prune_stage (decode)");
     }
-    return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: b_q = %d not built yet", s.b_q);
+    switch (s.b_q) {
+    case 16: launch_prefill<1>(a, P, st); break;
+    case 32: launch_prefill<2>(a, P, st); break;
+    case 64: launch_prefill<4>(a, P, st); break;
+    default: return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: b_q = %d not in {1, 16, 32, 64}", s.b_q);
+    }
+    return check_launch("prune_stage (prefill)");
 }
 
 }  // namespace ihip

@@ -1,0 +1,298 @@
+// Block-sparse chunked-prefill attention on the matrix cores.
+//
+// One workgroup per problem (sequence, KV head, query block of 64), one wave
+// per query head of the group, so the gathered K/V tiles are staged in LDS
+// once and shared by the G heads.  The attended keys form the virtual slot
+// list [sink | kept blocks | window]; it is consumed 32 slots per step.
+//
+// "Transposed" flash attention, so that every per-query quantity lives in the
+// lanes that own that query and nothing has to be shuffled between the two
+// matrix products:
+//     S^T = K Q^T   (A = K tile from LDS,  B = Q, resident in registers)
+//     O^T = V^T P^T (A = V^T tile from LDS, B = P^T = the lanes' own S^T values)
+// v_mfma_f32_16x16x32_bf16 layouts: A/B lane l holds 8 consecutive k of
+// row/column l%16 (k group l/16); C lane l holds column l%16, rows 4*(l/16)..+3.
+// The k order of the second product (keys) is free as long as V^T and P^T
+// agree: k slot (kq, j) is key kq*4+j of the first 16-key tile for j < 4 and
+// key kq*4+j-4 of the second for j >= 4 -- exactly what a lane's two S^T
+// accumulators hold.  V is transposed on its way into LDS.
+#include "common.h"
+
+namespace ihip {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPfTile = 32;             // key slots per step
+constexpr int kPfKStride = kD + 8;      // K tile row stride in LDS (elements): 272 B, conflict-free 16-B reads
+constexpr int kPfVStride = kPfTile + 8; // V^T row stride (elements): 80 B
+constexpr float kNegBigPf = -1.0e30f;
+
+struct AttnPrefillArgs {
+    Geometry ge;
+    const uint16_t *q; int64_t q_sb, q_sh, q_st;
+    const uint16_t *k; int64_t k_sb, k_sh, k_st;
+    const uint16_t *v; int64_t v_sb, v_sh, v_st;
+    const int32_t *block_starts;
+    int n_blocks, block, block_log2;
+    float scale_log2e;
+    uint16_t *out;       // bf16 [B, Hq, Tq, d]
+    float *out_lse;      // [B, Hq, Tq] or null
+};
+
+__device__ inline int pf_slot_to_pos(const AttnPrefillArgs &a, const Problem &pr, int p, int slot,
+                                     int n_sink_eff, int w0)
+{
+    if (slot < n_sink_eff) return slot;
+    slot -= n_sink_eff;
+    const int nb = a.n_blocks << a.block_log2;
+    if (slot < nb) {
+        const int bs = a.block_starts[(int64_t)p * a.n_blocks + (slot >> a.block_log2)];
+        if (bs < 0) return -1;
+        const int pos = bs + (slot & (a.block - 1));
+        return pos < pr.hi ? pos : -1;
+    }
+    const int pos = w0 + (slot - nb);
+    return pos < pr.E ? pos : -1;
+}
+
+template <int QT, int G>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
+__global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t sK[kPfTile * kPfKStride];
+    __shared__ __attribute__((aligned(16))) uint16_t sVt[kD * kPfVStride];
+    __shared__ int sPos[kPfTile];
+    __shared__ int sFlag[2];             // "this tile needs masking", alternating by tile parity
+
+    const int p = blockIdx.x;
+    const Problem pr = problem_of(a.ge, p);
+    constexpr int nthreads = 64 * G;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, hh = tid >> 6;
+    const int n = lane & 15, kq = lane >> 4;
+    const int h = pr.g * G + hh;
+    const int b_q = 16 * QT;
+    const int q0 = pr.m * b_q;                 // first query row of the block
+    const int qpos0 = pr.E - b_q;              // its absolute position
+
+    const int n_sink_eff = min(a.ge.n_sink, pr.E);
+    const int w0 = max(pr.hi, a.ge.n_sink);
+    const int total = n_sink_eff + (a.n_blocks << a.block_log2) + max(0, pr.E - w0);
+    const int n_tiles = (total + kPfTile - 1) / kPfTile;
+
+    // B operands of the first product: this head's queries
+    bf16x8 qb[QT][4];
+    {
+        const uint16_t *qp = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)q0 * a.q_st;
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                qb[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + (int64_t)(qt * 16 + n) * a.q_st + ks * 32 + kq * 8);
+    }
+    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+    const uint16_t *vb = a.v + pr.b * a.v_sb + pr.g * a.v_sh;
+
+    f32x4 o[8][QT];
+    float m_run[QT], l_run[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        m_run[qt] = kNegBigPf; l_run[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) o[dt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // loader role: item = (key pair a2, dim group c); 16 pairs x 16 groups per tile
+    constexpr int kItems = (kPfTile / 2) * 16;
+    constexpr int kMaxPerThread = (kItems + nthreads - 1) / nthreads;
+    uint4 rk[kMaxPerThread][2], rv[kMaxPerThread][2];
+    int rpos[kMaxPerThread][2];
+
+    auto fetch = [&](int tile) {
+#pragma unroll
+        for (int r = 0; r < kMaxPerThread; ++r) {
+            const int item = tid + r * nthreads;
+            if (item >= kItems) break;
+            const int a2 = item >> 4, c = item & 15;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int slot = tile * kPfTile + a2 * 2 + e;
+                const int pos = slot < total ? pf_slot_to_pos(a, pr, p, slot, n_sink_eff, w0) : -1;
+                rpos[r][e] = pos;
+                rk[r][e] = make_uint4(0, 0, 0, 0);
+                rv[r][e] = make_uint4(0, 0, 0, 0);
+                if (pos >= 0) {
+                    rk[r][e] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos * a.k_st + c * 8);
+                    rv[r][e] = *reinterpret_cast<const uint4 *>(vb + (int64_t)pos * a.v_st + c * 8);
+                }
+            }
+        }
+    };
+    auto stash = [&](int tile) {
+        bool need_mask = false;
+#pragma unroll
+        for (int r = 0; r < kMaxPerThread; ++r) {
+            const int item = tid + r * nthreads;
+            if (item >= kItems) break;
+            const int a2 = item >> 4, c = item & 15;
+            const int key0 = a2 * 2;                                   // keys key0, key0+1 of the 32
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                *reinterpret_cast<uint4 *>(&sK[(key0 + e) * kPfKStride + c * 8]) = rk[r][e];
+            // k slot of key kk: tile t = kk/16, kq = (kk%16)/4, j = kk%4 + 4*t
+            const int t = key0 >> 4, kk = key0 & 15;
+            const int kslot = (kk >> 2) * 8 + (kk & 3) + 4 * t;        // even; key0+1 sits at kslot+1
+            const uint32_t v0[4] = {rv[r][0].x, rv[r][0].y, rv[r][0].z, rv[r][0].w};
+            const uint32_t v1[4] = {rv[r][1].x, rv[r][1].y, rv[r][1].z, rv[r][1].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // dims c*8+2i (low halves) and c*8+2i+1 (high halves)
+                const uint32_t lo = (v0[i] & 0xffffu) | (v1[i] << 16);
+                const uint32_t hi = (v0[i] >> 16) | (v1[i] & 0xffff0000u);
+                *reinterpret_cast<uint32_t *>(&sVt[(c * 8 + 2 * i) * kPfVStride + kslot]) = lo;
+                *reinterpret_cast<uint32_t *>(&sVt[(c * 8 + 2 * i + 1) * kPfVStride + kslot]) = hi;
+            }
+            if (c == 0) { sPos[key0] = rpos[r][0]; sPos[key0 + 1] = rpos[r][1]; }
+            need_mask |= rpos[r][0] < 0 || rpos[r][1] < 0 || rpos[r][0] >= qpos0 || rpos[r][1] >= qpos0;
+        }
+        if (need_mask) sFlag[tile & 1] = 1;
+    };
+
+    if (n_tiles > 0) fetch(0);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        if (tid == 0) sFlag[tile & 1] = 0;     // last read two tiles (and two barriers) ago
+        __syncthreads();                       // previous tile fully consumed, flag cleared
+        stash(tile);
+        __syncthreads();
+        if (tile + 1 < n_tiles) fetch(tile + 1);
+        const bool masked = sFlag[tile & 1] != 0;
+
+        // V^T operands of this tile: dims dt*16+n, k slots kq*8..+8
+        bf16x8 va[8];
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+            va[dt] = *reinterpret_cast<const bf16x8 *>(&sVt[(dt * 16 + n) * kPfVStride + kq * 8]);
+        // K operands: key kt*16+n, dims ks*32+kq*8..+8
+        bf16x8 ka[2][4];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                ka[kt][ks] = *reinterpret_cast<const bf16x8 *>(&sK[(kt * 16 + n) * kPfKStride + ks * 32 + kq * 8]);
+        int kpos[2][4];
+        if (masked) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) kpos[kt][i] = sPos[kt * 16 + kq * 4 + i];
+        }
+
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            // S^T for 32 keys x 16 queries: lane holds keys kt*16 + kq*4 + i of query qt*16 + n
+            f32x4 s[2];
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt][ks], qb[qt][ks], c, 0, 0, 0);
+                s[kt] = c * a.scale_log2e;
+            }
+            if (masked) {
+                const int qpos = qpos0 + qt * 16 + n;
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (kpos[kt][i] < 0 || kpos[kt][i] > qpos) s[kt][i] = -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                             fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mn = fmaxf(m_run[qt], mx);
+            const float corr = exp2f(m_run[qt] - mn);
+            m_run[qt] = mn;
+            float ps = 0.f;
+            bf16x8 pb;
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float pw = exp2f(s[kt][i] - mn);      // exp2(-inf) = 0 for masked keys
+                    ps += pw;
+                    pb[kt * 4 + i] = (__bf16)pw;
+                }
+            l_run[qt] = l_run[qt] * corr + ps;                  // partial over this lane's keys
+            if (__any(corr != 1.0f)) {
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) o[dt][qt] *= corr;
+            }
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+                o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, o[dt][qt], 0, 0, 0);
+        }
+    }
+
+    // epilogue: O[q][dim] = O^T / l
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        float l = l_run[qt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const float inv = 1.0f / l;
+        const int64_t row = ((int64_t)pr.b * a.ge.Hq + h) * a.ge.Tq + q0 + qt * 16 + n;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const f32x4 x = o[dt][qt] * inv;
+            uint2 w;
+            w.x = f32_to_bf16_bits(x[0]) | (f32_to_bf16_bits(x[1]) << 16);
+            w.y = f32_to_bf16_bits(x[2]) | (f32_to_bf16_bits(x[3]) << 16);
+            *reinterpret_cast<uint2 *>(a.out + row * kD + dt * 16 + kq * 4) = w;
+        }
+        if (a.out_lse != nullptr && kq == 0)
+            a.out_lse[row] = (m_run[qt] + log2f(l)) * 0.69314718055994530942f;
+    }
+}
+
+int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
+                            const ihip_tensor &v, const int32_t *block_starts, int n_blocks, int block,
+                            float sm_scale, void *out, float *out_lse, hipStream_t st)
+{
+    AttnPrefillArgs a;
+    a.ge = make_geometry(s);
+    a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
+    a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
+    a.v = (const uint16_t *)v.ptr; a.v_sb = v.stride_b; a.v_sh = v.stride_h; a.v_st = v.stride_t;
+    a.block_starts = block_starts;
+    a.n_blocks = n_blocks;
+    a.block = block;
+    a.block_log2 = __builtin_ctz(block);
+    a.scale_log2e = sm_scale * 1.44269504088896340736f;
+    a.out = (uint16_t *)out;
+    a.out_lse = out_lse;
+    const int P = s.B * s.Hkv * (s.Tq / s.b_q);
+    if (P == 0) return IHIP_OK;
+    KernelTimer timer("attn_prefill", st);
+    const dim3 block_dim(64 * a.ge.G), grid(P);
+#define IHIP_PF_LAUNCH(QT, G) hipLaunchKernelGGL((attn_prefill_kernel<QT, G>), grid, block_dim, 0, st, a)
+#define IHIP_PF_BY_G(QT)                                       \
+    switch (a.ge.G) {                                          \
+    case 1: IHIP_PF_LAUNCH(QT, 1); break;                      \
+    case 2: IHIP_PF_LAUNCH(QT, 2); break;                      \
+    case 4: IHIP_PF_LAUNCH(QT, 4); break;                      \
+    default: IHIP_PF_LAUNCH(QT, 8); break;                     \
+    }
+    switch (s.b_q) {
+    case 16: IHIP_PF_BY_G(1); break;
+    case 32: IHIP_PF_BY_G(2); break;
+    case 64: IHIP_PF_BY_G(4); break;
+    default: return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_prefill: b_q = %d not in {16, 32, 64}", s.b_q);
+    }
+#undef IHIP_PF_BY_G
+#undef IHIP_PF_LAUNCH
+    return check_launch("sparse_attn_prefill");
+}
+
+}  // namespace ihip
