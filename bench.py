@@ -1,25 +1,31 @@
 #!/usr/bin/env python3
-"""Benchmark of the decode hot path: one step = one layer call (all pruning
-stages + arg-top-K selects + block-sparse decode attention, every stage
-refreshed) over one batch of synthetic input resident in HBM.
+"""Benchmark of the hot path on one MI355X.  One step = one layer call: all
+pruning stages + arg-top-K selects + block-sparse attention, every stage
+refreshed, over one batch of synthetic input resident in HBM.
 
-Default workload: cfg3 -- batch 8, 1,048,576 keys per sequence, 32 query / 8
-KV heads, d = 128, bf16, 4 stages (256 -> 64 -> 16 -> 4), 4,096-token budget.
-One layer's K/V (32 GiB) stays in HBM and is reused by 32 different query
-sets, so consecutive steps touch different rows.
+Default workload (the headline metric): cfg3 -- decode, batch 8, 1,048,576
+keys per sequence, 32 query / 8 KV heads, d = 128, bf16, 4 stages
+(256 -> 64 -> 16 -> 4), 4,096-token budget.  One layer's K/V (32 GiB) stays in
+HBM and is reused by 32 different query sets, so consecutive steps touch
+different rows.  `--workload cfg4-prefill-4k-on-256k` times the chunked
+prefill layer instead (4,096 new tokens on a 262,144-token prefix).
 
 Prints one JSON line.  `value` is microseconds per layer call for the whole
 batch.  `roofline` is for the kernel with the largest share of the step:
-algorithmic bytes per launch (distinct K rows the search must score, counted
-by the CPU oracle on a sample of problems, plus the scores it writes) divided
-by that kernel's mean duration, measured with HIP events around the launch on
-its stream in a second pass over the same steps.  `cpu_baseline` is the CPU
-oracle timed on a bounded sample of the same workload in the same run.
+ - decode: algorithmic bytes per launch (distinct K rows the search must
+   score, counted by the CPU oracle on a sample of problems, x 256 B, plus the
+   scores it writes) / mean launch duration, against 8 TB/s of HBM;
+ - prefill: matrix-core flops per launch (2*d per query-key pair actually
+   multiplied) / mean launch duration, against 2.5 PFLOP/s dense bf16.
+The mean launch duration comes from HIP events recorded around every launch
+on its stream in a second pass over the same steps.  `cpu_baseline` is the
+CPU oracle timed on a bounded sample of the same workload in the same run.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -29,11 +35,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 N_QUERY_SETS = 32
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see
-# profiles/.  None until measured for a workload.
+# profiles/.  Absent = not measured for that workload / kernel.
 MEASURED_TRAFFIC_BYTES = {
     # FETCH_SIZE 781,266 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 1,220 KiB x 1.0 per launch
     ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781265.9 * 2.0 + 1220.0) * 1024.0,
@@ -43,8 +50,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg3-decode-1m-b8")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
@@ -55,19 +62,45 @@ def parse():
     return ap.parse_args()
 
 
-def oracle_sample(w, qs, k, v, seq_lens, budget_s):
+def timed_passes(step, steps, warmup, ihip, torch, profile):
+    """W warm-up steps, K timed steps between synchronisations, then (optionally)
+    the same K steps again with HIP events around every kernel launch."""
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / steps * 1e6
+    kernels = {}
+    if profile:
+        ihip.profile_enable(True)
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        ihip.profile_enable(False)
+        for name, (ms, n) in ihip.profile_read().items():
+            kernels[name] = {"us": ms / n * 1e3, "launches_per_step": n / steps}
+    return us, kernels
+
+
+def dominant(kernels):
+    return max(kernels, key=lambda n: kernels[n]["us"] * kernels[n]["launches_per_step"])
+
+
+# ---------------------------------------------------------------------------
+def decode_oracle_sample(w, qs, k, v, seq_lens, budget_s):
     """Times the CPU oracle on sequence 0 (all its KV heads), one query set
     after another until the budget is used; also returns the mean number of
     distinct K rows each stage scores per problem and the attended tokens."""
-    import numpy as np
     import oracle
     oracle.build(force=False)
     k0 = k[0:1].cpu()
     v0 = v[0:1].cpu()
     rows = [0.0] * len(w.stages)
-    tokens, problems, calls = 0.0, 0, 0
-    t_used = 0.0
-    for i, q in enumerate(qs):
+    tokens, problems, calls, t_used = 0.0, 0, 0, 0.0
+    for q in qs:
         o = oracle.Oracle(q[0:1].cpu(), k0, v0, [int(seq_lens[0])], w.b_q, w.n_sink, w.n_stream)
         t0 = time.perf_counter()
         res = o.layer(w.stages)
@@ -80,9 +113,166 @@ def oracle_sample(w, qs, k, v, seq_lens, budget_s):
             problems += 1
         if t_used >= budget_s:
             break
+    return {"seconds": t_used, "layer_calls_one_sequence": calls, "problems": problems,
+            "rows_per_problem": [r / problems for r in rows], "tokens_per_problem": tokens / problems}
+
+
+def bench_decode(args, w, torch, ihip, configs):
+    dev = torch.device("cuda:0")
+    steps = 200 if args.steps is None else args.steps
+    warmup = 20 if args.warmup is None else args.warmup
+    chunks = [s[0] for s in w.stages]
+    keeps = [s[1] for s in w.stages]
+
+    t0 = time.perf_counter()
+    k, v = configs.make_kv(w, 0, dev)
+    qs = []
+    for i in range(N_QUERY_SETS):
+        q = configs.make_q(w, i, dev)
+        configs.plant_needles(w, k, q, i)
+        qs.append(q)
+    seq_lens = torch.full((w.B,), w.T, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t0
+
+    L = ihip.Layer(qs[0], k, seq_lens, w.b_q, w.n_sink, w.n_stream)
+    ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
+    out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
+
+    def step(i):
+        L.decode_layer(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ws=ws, out=out)
+
+    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
+
+    cpu = sample = None
+    if args.cpu_seconds > 0:
+        sample = decode_oracle_sample(w, qs, k, v, seq_lens.cpu().tolist(), args.cpu_seconds)
+        per_seq_call = sample["seconds"] / sample["layer_calls_one_sequence"]
+        cpu = {"value": per_seq_call * w.B * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
+               "sample": f"sequence 0 of {w.B} (its {w.Hkv} KV heads), {sample['layer_calls_one_sequence']} "
+                         f"layer calls with different queries, {sample['seconds']:.1f} s; scaled x{w.B} to the batch"}
+
+    P = w.B * w.Hkv
+    row_bytes = w.d * 2
+    roofline = whole = None
+    if sample is not None:
+        alg = {}
+        slots = [L.stage1_slots(chunks[0])] + [keeps[i - 1] * (chunks[i - 1] // chunks[i])
+                                                 for i in range(1, len(chunks))]
+        for i, c in enumerate(chunks):
+            first = ".first" if i == 0 else ""
+            alg[f"prune_decode{first}.l{c}"] = P * (sample["rows_per_problem"][i] * row_bytes + slots[i] * 4)
+            alg[f"select_blocks{first}.l{c}"] = P * (slots[i] * 4 + keeps[i] * 4)
+        alg["attn_decode_split"] = P * sample["tokens_per_problem"] * 2 * row_bytes
+        total_alg = sum(alg.values())
+        gbs = total_alg / (us_per_layer * 1e-6) / 1e9
+        whole = {"algorithmic_bytes_per_layer": total_alg, "achieved_GBps": gbs,
+                 "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+        for n in kernels:
+            if n in alg:
+                kernels[n]["alg_GBps"] = alg[n] / (kernels[n]["us"] * 1e-6) / 1e9
+        if kernels and dominant(kernels) in alg:
+            dom = dominant(kernels)
+            ach = kernels[dom]["alg_GBps"]
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                        "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
     return {
-        "seconds": t_used, "layer_calls_one_sequence": calls, "problems": problems,
-        "rows_per_problem": [r / problems for r in rows], "tokens_per_problem": tokens / problems,
+        "metric": "sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer",
+        "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
+        "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
+                   "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
+                   "n_stream": w.n_stream, "query_sets": N_QUERY_SETS},
+        "roofline": roofline, "cpu_baseline": cpu, "whole_path": whole, "kernels": kernels, "setup_s": t_setup,
+    }
+
+
+# ---------------------------------------------------------------------------
+def bench_prefill(args, w, torch, ihip, configs):
+    dev = torch.device("cuda:0")
+    steps = 20 if args.steps is None else args.steps
+    warmup = 3 if args.warmup is None else args.warmup
+    chunks = [s[0] for s in w.stages]
+    keeps = [s[1] for s in w.stages]
+
+    t0 = time.perf_counter()
+    q, k, v, seq_lens, _ = configs.make_inputs(w, 0, dev)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t0
+
+    L = ihip.Layer(q, k, seq_lens, w.b_q, w.n_sink, w.n_stream)
+    ws = L.workspace(ihip.OP_PREFILL_LAYER, chunks, keeps)
+    out = torch.empty((w.B, w.Hq, w.Tq, w.d), dtype=torch.bfloat16, device=dev)
+
+    def step(i):
+        L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out)
+
+    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
+
+    # matrix-core flops actually multiplied, from the geometry alone
+    flops = {}
+    n_valid_prev = None
+    for i, (c, keep) in enumerate(w.stages):
+        pairs = 0          # candidate rows scored x queries
+        kept_valid = []
+        for m in range(w.Mq):
+            E = (w.T - w.Tq) + (m + 1) * w.b_q
+            mid = max(0, E - w.n_stream - w.n_sink)
+            if i == 0:
+                n = math.ceil(mid / c)
+            else:
+                n = n_valid_prev[m] * (w.stages[i - 1][0] // c)     # ragged tails ignored (<= 1 chunk)
+            kept_valid.append(min(keep, n))
+            pairs += n * (1 + int(math.log2(c))) * w.b_q
+        n_valid_prev = kept_valid
+        first = ".first" if i == 0 else ""
+        flops[f"prune_prefill{first}.l{c}"] = w.B * w.Hq * pairs * w.d * 2
+    keys = 0
+    for m in range(w.Mq):
+        E = (w.T - w.Tq) + (m + 1) * w.b_q
+        hi = E - w.n_stream
+        keys += min(w.n_sink, E) + n_valid_prev[m] * chunks[-1] + (E - max(hi, w.n_sink))
+    flops["attn_prefill"] = w.B * w.Hq * w.b_q * keys * w.d * 4
+    for n in kernels:
+        if n in flops:
+            kernels[n]["TFLOPs"] = flops[n] / (kernels[n]["us"] * 1e-6) / 1e12
+    roofline = None
+    if kernels and dominant(kernels) in flops:
+        dom = dominant(kernels)
+        ach = kernels[dom]["TFLOPs"]
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "flops_per_launch": flops[dom], "us_per_launch": kernels[dom]["us"]}
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        import oracle
+        oracle.build(force=False)
+        blocks = [0, w.Mq // 3, (2 * w.Mq) // 3, w.Mq - 1]
+        o = oracle.Oracle(q[:, :w.G].cpu(), k[:, :1].cpu(), v[:, :1].cpu(), [w.T] * w.B, w.b_q, w.n_sink, w.n_stream)
+        t0 = time.perf_counter()
+        done = 0
+        for m in blocks:
+            o.layer(w.stages, problems=[(0, 0, m)])
+            done += 1
+            if time.perf_counter() - t0 > args.cpu_seconds:
+                break
+        secs = time.perf_counter() - t0
+        P = w.B * w.Hkv * w.Mq
+        cpu = {"value": secs / done * P * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
+               "sample": f"{done} of {P} (KV head, query block) problems (KV head 0, blocks {blocks[:done]}), "
+                         f"{secs:.1f} s; scaled x{P}/{done}"}
+    return {
+        "metric": "sparse_attn_prefill_us_per_layer",
+        "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
+        "config": {"workload": w.name, "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
+                   "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
+                   "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink, "n_stream": w.n_stream},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "whole_path": {"mfma_flops_per_layer": sum(flops.values()),
+                       "achieved_TFLOPs": sum(flops.values()) / (us_per_layer * 1e-6) / 1e12},
+        "kernels": kernels, "setup_s": t_setup,
     }
 
 
@@ -106,108 +296,14 @@ def main():
 
     ihip.lib()
     w = configs.BY_NAME[args.workload]
-    if w.Tq != 1:
-        print("bench.py: only decode workloads are timed here", file=sys.stderr)
-        sys.exit(2)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    chunks = [s[0] for s in w.stages]
-    keeps = [s[1] for s in w.stages]
-
-    t0 = time.perf_counter()
-    k, v = configs.make_kv(w, 0, dev)
-    qs = []
-    for i in range(N_QUERY_SETS):
-        q = configs.make_q(w, i, dev)
-        configs.plant_needles(w, k, q, i)
-        qs.append(q)
-    seq_lens = torch.full((w.B,), w.T, dtype=torch.int32, device=dev)
-    torch.cuda.synchronize()
-    t_setup = time.perf_counter() - t0
-
-    L = ihip.Layer(qs[0], k, seq_lens, w.b_q, w.n_sink, w.n_stream)
-    ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
-    out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
-
-    def step(i):
-        L.decode_layer(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ws=ws, out=out)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    us_per_layer = elapsed / args.steps * 1e6
-
-    # second pass over the same steps with HIP events around every kernel launch
-    kernels = {}
-    if not args.no_profile_pass:
-        ihip.profile_enable(True)
-        for i in range(args.steps):
-            step(i)
-        torch.cuda.synchronize()
-        ihip.profile_enable(False)
-        for name, (ms, n) in ihip.profile_read().items():
-            kernels[name] = {"us": ms / n * 1e3, "launches_per_step": n / args.steps}
-
-    # CPU oracle on a bounded sample: timing + algorithmic byte counts
-    cpu = None
-    sample = None
-    if args.cpu_seconds > 0:
-        sample = oracle_sample(w, qs, k, v, seq_lens.cpu().tolist(), args.cpu_seconds)
-        per_seq_call = sample["seconds"] / sample["layer_calls_one_sequence"]
-        cpu = {"value": per_seq_call * w.B * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
-               "sample": f"sequence 0 of {w.B} (its {w.Hkv} KV heads), {sample['layer_calls_one_sequence']} "
-                         f"layer calls with different queries, {sample['seconds']:.1f} s; scaled x{w.B} to the batch"}
-
-    P = w.B * w.Hkv
-    row_bytes = w.d * 2
-    roofline = None
-    alg = {}
-    if sample is not None:
-        slots = [L.stage1_slots(chunks[0])] + [keeps[i - 1] * (chunks[i - 1] // chunks[i])
-                                                 for i in range(1, len(chunks))]
-        for i, c in enumerate(chunks):
-            name = f"prune_decode.first.l{c}" if i == 0 else f"prune_decode.l{c}"
-            alg[name] = P * (sample["rows_per_problem"][i] * row_bytes + slots[i] * 4)
-            sname = f"select_blocks.first.l{c}" if i == 0 else f"select_blocks.l{c}"
-            alg[sname] = P * (slots[i] * 4 + keeps[i] * 4)
-        alg["attn_decode_split"] = P * sample["tokens_per_problem"] * 2 * row_bytes
-        total_alg = sum(alg.values())
-        if kernels:
-            dom = max(kernels, key=lambda n: kernels[n]["us"] * kernels[n]["launches_per_step"])
-            if dom in alg:
-                ach = alg[dom] / (kernels[dom]["us"] * 1e-6) / 1e9
-                roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
-                            "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
-            for n in kernels:
-                if n in alg:
-                    kernels[n]["alg_GBps"] = alg[n] / (kernels[n]["us"] * 1e-6) / 1e9
-    else:
-        total_alg = None
-
-    line = {
-        "metric": "sparse_attn_decode_us_per_layer_1m_ctx",
-        "value": us_per_layer, "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": us_per_layer / 1e3, "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
-                   "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
-                   "n_stream": w.n_stream, "query_sets": N_QUERY_SETS},
-        "roofline": roofline,
-        "cpu_baseline": cpu,
-        "whole_path": None if total_alg is None else {
-            "algorithmic_bytes_per_layer": total_alg,
-            "achieved_GBps": total_alg / (us_per_layer * 1e-6) / 1e9,
-            "frac_of_hbm_peak": total_alg / (us_per_layer * 1e-6) / 1e9 / HBM_PEAK_GBS},
-        "kernels": kernels,
-        "setup_s": t_setup,
-    }
+    torch.cuda.set_device(0)
+    body = bench_decode(args, w, torch, ihip, configs) if w.Tq == 1 else bench_prefill(args, w, torch, ihip, configs)
+    line = {"metric": body.pop("metric"), "value": body.pop("value"), "unit": body.pop("unit"), "n_gpus": 1,
+            "steps": body.pop("steps"), "warmup": body.pop("warmup")}
+    line["ms_per_step"] = line["value"] / 1e3
+    line.update({"higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+                 "data": "synthetic"})
+    line.update(body)
     print(json.dumps(line))
 
 

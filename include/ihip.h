@@ -67,6 +67,7 @@ typedef struct {
 #define IHIP_OP_ATTN_PREFILL  2
 #define IHIP_OP_PRUNE_ALL     3
 #define IHIP_OP_DECODE_LAYER  4
+#define IHIP_OP_PREFILL_LAYER 5
 
 /*
  * One pruning stage up to the arg-top-K (Alg. 2 with SelectRep of Alg. 3 inside):
@@ -132,7 +133,7 @@ int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_ten
 /*
  * Block-sparse chunked-prefill attention: the same key set per query block m,
  * every query of the block attending causally inside the window (keys after
- * its own position are masked).  b_q must be 64.  block_starts is
+ * its own position are masked).  b_q in {16, 32, 64}.  block_starts is
  * [P, n_blocks] with P = B*Hkv*Mq; out is bf16 [B, Hq, Tq, d] contiguous;
  * out_lse fp32 [B, Hq, Tq] or NULL.  QK^T and PV run on the matrix cores
  * (bf16 inputs, fp32 accumulation), softmax in fp32.
@@ -162,6 +163,17 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                           int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                           float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
                           void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One chunked-prefill layer call: ihip_prune_all followed by
+ * ihip_sparse_attn_prefill (Alg. 1 per query block, then block-sparse
+ * attention).  out / out_lse as in ihip_sparse_attn_prefill; out_block_starts
+ * device int32 [P, keeps[last]] or NULL.
+ */
+int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                           int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                           float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
+                           void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Scratch bytes an operation needs.  n_stages / chunk_sizes / keeps describe

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libihip.so")
 
-OP_ATTN_DECODE, OP_ATTN_PREFILL, OP_PRUNE_ALL, OP_DECODE_LAYER = 1, 2, 3, 4
+OP_ATTN_DECODE, OP_ATTN_PREFILL, OP_PRUNE_ALL, OP_DECODE_LAYER, OP_PREFILL_LAYER = 1, 2, 3, 4, 5
 
 c_i32, c_i64, c_f, vp, c_sz = (ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p,
                                ctypes.c_size_t)
@@ -49,6 +49,8 @@ EXPORTS = {
     "ihip_prune_all": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, c_i32, vp, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
                                   vp, vp, vp, vp, c_sz, vp]),
+    "ihip_prefill_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
+                                   vp, vp, vp, vp, c_sz, vp]),
     "ihip_workspace_bytes": (c_sz, [c_i32, ctypes.POINTER(Shape), c_i32, vp, vp]),
     "ihip_profile_enable": (c_i32, [c_i32]),
     "ihip_profile_read": (c_i32, [c_i32, vp, vp, vp]),
@@ -219,4 +221,18 @@ class Layer:
                                        _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
                                        sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),
                                        ws.numel(), _stream()))
+        return out
+
+    def prefill_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
+                      out_blocks=None, lse=None):
+        """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d]."""
+        sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
+        if out is None:
+            out = torch.empty((self.B, self.Hq, self.Tq, self.d), dtype=torch.bfloat16, device=self.device)
+        if ws is None:
+            ws = self.workspace(OP_PREFILL_LAYER, chunk_sizes, keeps)
+        _check(lib().ihip_prefill_layer(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                        _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                        sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),
+                                        ws.numel(), _stream()))
         return out

@@ -346,6 +346,35 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                               w + L.total + blocks_bytes, (hipStream_t)stream);
 }
 
+int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                           const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
+                           float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_prefill_layer";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->b_q != 16 && shape->b_q != 32 && shape->b_q != 64)
+        return fail(IHIP_ERR_UNSUPPORTED, "%s: b_q = %d not in {16, 32, 64}", who, shape->b_q);
+    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
+    if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
+    const int last = n_stages - 1;
+    const PlanLayout L = plan_layout(*shape, n_stages, chunk_sizes, keeps);
+    const size_t P = (size_t)shape->B * shape->Hkv * (shape->Tq / shape->b_q);
+    const size_t blocks_bytes = align256(P * keeps[last] * sizeof(int32_t));
+    const size_t need = L.total + blocks_bytes;
+    if (!ws || ws_bytes < need)
+        return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
+    char *w = (char *)ws;
+    int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, (hipStream_t)stream);
+    if (rc != IHIP_OK) return rc;
+    return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
+                               (hipStream_t)stream);
+}
+
 int32_t ihip_profile_enable(int32_t on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -394,6 +423,9 @@ size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stage
         return plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
                align256(P * keeps[last] * sizeof(int32_t)) +
                attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
+    case IHIP_OP_PREFILL_LAYER:
+        return plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
+               align256(P * keeps[last] * sizeof(int32_t));
     default:
         fail(IHIP_ERR_INVALID_ARG, "ihip_workspace_bytes: unknown op %d", op);
         return 0;
