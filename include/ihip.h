@@ -176,6 +176,59 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
                            void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Host-memory KV tier with an on-GPU hot-block cache (Sec. 4 "KV Cache
+ * Offloading"; Alg. 4, the miss lists and the LRU replacement after the layer).
+ *
+ * K and V of the layer, bf16 [B,Hkv,T_alloc,d], live in pinned host memory
+ * that the GPU can address (hipHostMalloc): host_k / host_v carry such
+ * pointers.  The cache keeps copies of block_tokens-token blocks (a power of
+ * two) in two banks carved out of dev_mem (device memory owned by the caller,
+ * 256-byte aligned, at least ihip_cache_device_bytes(...) long): the
+ * mask-selection bank (keys only, mask_slots blocks) read by the pruning
+ * stages, and the sparse-attention bank (keys and values, sa_slots blocks).
+ * The handle itself is a small host object owned by the library; the caller
+ * keeps dev_mem and the host tensors alive until ihip_cache_destroy.
+ *
+ * ihip_decode_layer_cached is ihip_decode_layer reading K/V through the cache:
+ * a resident block is read from its bank, any other row straight from host
+ * memory over the host link; the results are bit-identical to the uncached
+ * call on the same data whatever the cache holds.  It records which blocks
+ * were touched and which were missing.  ihip_cache_update (same stream, after
+ * the layer call) then, per bank, evicts as many least-recently-used slots as
+ * there were missed blocks (oldest last-touch call first, lowest slot on a
+ * tie; never-used slots first) and copies the missed blocks in, in ascending
+ * block order; if more blocks were missed than the bank holds, only the
+ * lowest-numbered ones are inserted.  Layer calls and updates on one cache
+ * must not overlap.
+ *
+ * ihip_cache_stats (synchronises the device) fills stats8 (host):
+ * [0..3] mask bank, [4..7] sparse-attention bank: blocks hit (cumulative over
+ * calls, a block counts once per call), blocks missed (cumulative), blocks
+ * missed in the last call, blocks touched in the last call.
+ * ihip_cache_read_tables (synchronises) copies a bank's page table (int32 per
+ * global block id (b*Hkv+g)*blocks_per_head + block: slot or -1) and slot
+ * table (block id per slot or -1) to host arrays; either may be NULL.
+ */
+typedef struct ihip_cache ihip_cache;
+size_t  ihip_cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens,
+                                int32_t mask_slots, int32_t sa_slots);
+int32_t ihip_cache_create(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k,
+                          ihip_tensor host_v, int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens,
+                          int32_t mask_slots, int32_t sa_slots, void *stream);
+void    ihip_cache_destroy(ihip_cache *cache);
+int32_t ihip_cache_reset(ihip_cache *cache, void *stream);
+int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
+                                 void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_cache_update(ihip_cache *cache, void *stream);
+int32_t ihip_cache_stats(ihip_cache *cache, uint64_t *stats8);
+int32_t ihip_cache_read_tables(ihip_cache *cache, int32_t bank, int32_t *host_page_table,
+                               int32_t *host_slot_block);
+int32_t ihip_cache_geometry(const ihip_cache *cache, int32_t *n_blocks_total, int32_t *mask_slots,
+                            int32_t *sa_slots);
+
+/*
  * Scratch bytes an operation needs.  n_stages / chunk_sizes / keeps describe
  * the stage plan (for the attention-only ops pass n_stages = 1 with
  * chunk_sizes[0] = block and keeps[0] = n_blocks).  Returns 0 on bad arguments.

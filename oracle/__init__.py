@@ -57,3 +57,4 @@ def lib():
 
 
 from .pipeline import Oracle, StageResult, ProblemResult  # noqa: E402,F401
+from .lru import LruBank  # noqa: E402,F401

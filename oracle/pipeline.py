@@ -36,7 +36,11 @@ class StageResult:
     scores: np.ndarray          # float32 [n] chunk scores
     reps: np.ndarray            # int64 [G,n] representative positions
     kept_ids: np.ndarray        # int32 [kept] ascending chunk ids
-    rows_touched: int           # distinct K rows scored by this stage
+    touched_pos: np.ndarray     # int64, ascending: distinct K rows (positions) scored by this stage
+
+    @property
+    def rows_touched(self) -> int:
+        return len(self.touched_pos)
 
     @property
     def kept_starts(self):
@@ -127,7 +131,7 @@ class Oracle:
                                _p(scores), _p(reps), _p(touched))
         ids = np.empty(max(min(keep, n), 1), np.int32)
         kept = self.L.orc_topk(n, _p(scores), keep, _p(ids))
-        return StageResult(l_c, starts, lens, scores, reps, ids[:kept].copy(), int(touched.sum()))
+        return StageResult(l_c, starts, lens, scores, reps, ids[:kept].copy(), np.nonzero(touched)[0].astype(np.int64))
 
     # -- Alg. 1 -----------------------------------------------------------
     def prune(self, b, g, m, stages: Sequence[Tuple[int, int]], exhaustive=False) -> ProblemResult:
@@ -161,6 +165,14 @@ class Oracle:
                                     E - self.b_q, self.n_sink, max(hi, self.n_sink),
                                     len(bs), _p(bs), _p(bl), scale, _p(out), _p(lse))
         return out, lse
+
+    def attended_positions(self, b, m, block_starts, block_lens) -> np.ndarray:
+        """Every key position the block's attention reads (last query's view)."""
+        lo, hi, E = self.ranges(b, m)
+        parts = [np.arange(0, min(self.n_sink, E))]
+        parts += [np.arange(s, s + n) for s, n in zip(block_starts.tolist(), block_lens.tolist())]
+        parts.append(np.arange(max(hi, self.n_sink), E))
+        return np.concatenate(parts).astype(np.int64)
 
     def attended_tokens(self, b, m, block_lens) -> int:
         """Keys the last query of the block attends to (for byte counts)."""

@@ -51,6 +51,17 @@ EXPORTS = {
                                   vp, vp, vp, vp, c_sz, vp]),
     "ihip_prefill_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
                                    vp, vp, vp, vp, c_sz, vp]),
+    "ihip_cache_device_bytes": (c_sz, [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32]),
+    "ihip_cache_create": (c_i32, [ctypes.POINTER(vp), vp, c_sz, Tensor, Tensor, c_i32, c_i32, c_i64, c_i32,
+                                  c_i32, c_i32, vp]),
+    "ihip_cache_destroy": (None, [vp]),
+    "ihip_cache_reset": (c_i32, [vp, vp]),
+    "ihip_decode_layer_cached": (c_i32, [ctypes.POINTER(Shape), Tensor, vp, c_i32, vp, vp, c_f, vp, vp, vp,
+                                         vp, c_sz, vp]),
+    "ihip_cache_update": (c_i32, [vp, vp]),
+    "ihip_cache_stats": (c_i32, [vp, vp]),
+    "ihip_cache_read_tables": (c_i32, [vp, c_i32, vp, vp]),
+    "ihip_cache_geometry": (c_i32, [vp, vp, vp, vp]),
     "ihip_workspace_bytes": (c_sz, [c_i32, ctypes.POINTER(Shape), c_i32, vp, vp]),
     "ihip_profile_enable": (c_i32, [c_i32]),
     "ihip_profile_read": (c_i32, [c_i32, vp, vp, vp]),
@@ -236,3 +247,77 @@ class Layer:
                                         sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),
                                         ws.numel(), _stream()))
         return out
+
+
+class HostKVCache:
+    """Host-resident K/V (pinned memory) with the on-GPU hot-block cache.
+
+    host_k / host_v: pinned bf16 CPU tensors [B,Hkv,T,d] (torch's
+    pin_memory=True); the banks and tables are carved out of one device
+    buffer allocated here through PyTorch and kept alive with the handle."""
+
+    def __init__(self, host_k: torch.Tensor, host_v: torch.Tensor, block_tokens: int, mask_slots: int,
+                 sa_slots: int, device="cuda:0"):
+        for t, name in ((host_k, "host_k"), (host_v, "host_v")):
+            if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1 or t.is_cuda or not t.is_pinned():
+                raise IhipError(f"{name}: need a pinned 4-d bf16 CPU tensor with contiguous last dim")
+        self.host_k, self.host_v = host_k, host_v
+        B, Hkv, T, _ = host_k.shape
+        need = lib().ihip_cache_device_bytes(B, Hkv, T, block_tokens, mask_slots, sa_slots)
+        if need == 0:
+            raise IhipError("ihip_cache_device_bytes: bad sizes")
+        self.dev_mem = torch.empty(need, dtype=torch.uint8, device=device)
+        self.handle = vp()
+        hk = Tensor(host_k.data_ptr(), host_k.stride(0), host_k.stride(1), host_k.stride(2))
+        hv = Tensor(host_v.data_ptr(), host_v.stride(0), host_v.stride(1), host_v.stride(2))
+        with torch.cuda.device(self.dev_mem.device):
+            _check(lib().ihip_cache_create(ctypes.byref(self.handle), self.dev_mem.data_ptr(), need, hk, hv,
+                                           B, Hkv, T, block_tokens, mask_slots, sa_slots, _stream()))
+        self.block_tokens, self.mask_slots, self.sa_slots = block_tokens, mask_slots, sa_slots
+        self.n_blocks_total = B * Hkv * ((T + block_tokens - 1) // block_tokens)
+
+    def close(self):
+        if self.handle:
+            torch.cuda.synchronize()
+            lib().ihip_cache_destroy(self.handle)
+            self.handle = vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self):
+        _check(lib().ihip_cache_reset(self.handle, _stream()))
+
+    def update(self):
+        _check(lib().ihip_cache_update(self.handle, _stream()))
+
+    def stats(self) -> dict:
+        s = (ctypes.c_uint64 * 8)()
+        _check(lib().ihip_cache_stats(self.handle, s))
+        keys = ("hits", "misses", "last_misses", "last_touched")
+        return {"mask": dict(zip(keys, s[0:4])), "sa": dict(zip(keys, s[4:8]))}
+
+    def tables(self, bank: int):
+        """(page_table [n_blocks_total], slot_block [n_slots]) as int32 numpy arrays."""
+        import numpy as np
+        pt = np.empty(self.n_blocks_total, np.int32)
+        sb = np.empty(self.mask_slots if bank == 0 else self.sa_slots, np.int32)
+        _check(lib().ihip_cache_read_tables(self.handle, bank, pt.ctypes.data_as(vp), sb.ctypes.data_as(vp)))
+        return pt, sb
+
+
+def decode_layer_cached(layer: "Layer", q, cache: HostKVCache, chunk_sizes, keeps, sm_scale=None, ws=None,
+                        out=None, out_blocks=None, lse=None):
+    """ihip_decode_layer_cached: the decode layer reading K/V through the host tier."""
+    sm_scale = 1.0 / math.sqrt(layer.d) if sm_scale is None else sm_scale
+    if out is None:
+        out = torch.empty((layer.B, layer.Hq, 1, layer.d), dtype=torch.bfloat16, device=layer.device)
+    if ws is None:
+        ws = layer.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+    _check(lib().ihip_decode_layer_cached(ctypes.byref(layer.shape), _tensor(q, "q"), cache.handle,
+                                          len(chunk_sizes), _i32(chunk_sizes), _i32(keeps), sm_scale, _ptr(out),
+                                          _ptr(lse), _ptr(out_blocks), _ptr(ws), ws.numel(), _stream()))
+    return out

@@ -74,12 +74,14 @@ void profile_end(hipStream_t st)
 
 // kernels' host launchers
 int32_t launch_prune_stage(const ihip_shape &, const ihip_tensor &, const ihip_tensor &, const int32_t *,
-                           int, int, int, int, float *, int32_t *, hipStream_t);
+                           int, int, int, int, float *, int32_t *, const BankView *, hipStream_t);
 int32_t launch_select_blocks(const ihip_shape &, const float *, int, const int32_t *, int, int, int, int,
                              int32_t *, hipStream_t);
 int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                            const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
-                           void *, hipStream_t);
+                           void *, const BankView *, hipStream_t);
+BankView cache_bank_view(const ihip_cache *, int);
+void cache_describe(const ihip_cache *, int32_t *, int32_t *, int64_t *, ihip_tensor *, ihip_tensor *);
 size_t attn_decode_workspace(const ihip_shape &, int, int);
 int32_t launch_attn_prefill(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                             const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
@@ -186,7 +188,7 @@ static PlanLayout plan_layout(const ihip_shape &s, int n_stages, const int32_t *
 
 static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                               const int32_t *chunks, const int32_t *keeps, int32_t *out_block_starts,
-                              char *ws, hipStream_t st)
+                              char *ws, const BankView *bank, hipStream_t st)
 {
     const PlanLayout L = plan_layout(s, n_stages, chunks, keeps);
     float *scores = (float *)(ws + L.scores_off);
@@ -196,7 +198,7 @@ static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const i
         const int slots = i == 0 ? stage1_slots(s, chunks[0]) : n_parent * (parent_chunk / chunks[i]);
         int32_t *kept = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
         int32_t rc = launch_prune_stage(s, q, k, parents, n_parent, parent_chunk, chunks[i], slots, scores,
-                                        nullptr, st);
+                                        nullptr, bank, st);
         if (rc != IHIP_OK) return rc;
         rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i], kept, st);
         if (rc != IHIP_OK) return rc;
@@ -239,7 +241,7 @@ int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, 
     if (shape->b_q == 1 && shape->Tq != 1)
         return fail(IHIP_ERR_INVALID_ARG, "%s: b_q == 1 is the decode path and needs Tq == 1", who);
     return launch_prune_stage(*shape, q, k, parent_starts, n_parent, parent_chunk, chunk, max_chunks, out_scores,
-                              out_rep, (hipStream_t)stream);
+                              out_rep, nullptr, (hipStream_t)stream);
 }
 
 int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
@@ -276,7 +278,7 @@ int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_ten
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     return launch_attn_decode(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, ws,
-                              (hipStream_t)stream);
+                              nullptr, (hipStream_t)stream);
 }
 
 int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
@@ -313,15 +315,15 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, in
     const size_t need = plan_layout(*shape, n_stages, chunk_sizes, keeps).total;
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
-    return prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, out_block_starts, (char *)ws,
+    return prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, out_block_starts, (char *)ws, nullptr,
                           (hipStream_t)stream);
 }
 
-int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
-                          const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
-                          float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
+                                 ihip_tensor v, const ihip_cache *cache, int32_t n_stages,
+                                 const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
+                                 float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
-    const char *who = "ihip_decode_layer";
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
@@ -340,10 +342,39 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
-    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, (hipStream_t)stream);
+    BankView mask_bank, sa_bank;
+    if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, cache ? &mask_bank : nullptr,
+                        (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_decode(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
-                              w + L.total + blocks_bytes, (hipStream_t)stream);
+                              w + L.total + blocks_bytes, cache ? &sa_bank : nullptr, (hipStream_t)stream);
+}
+
+int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                          const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
+                          float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+{
+    return decode_layer_impl("ihip_decode_layer", shape, q, k, v, nullptr, n_stages, chunk_sizes, keeps, sm_scale,
+                             out, out_lse, out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache, int32_t n_stages,
+                                 const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
+                                 float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes,
+                                 void *stream)
+{
+    const char *who = "ihip_decode_layer_cached";
+    if (!cache) return fail(IHIP_ERR_INVALID_ARG, "%s: cache is NULL", who);
+    int32_t B, Hkv;
+    int64_t T_alloc;
+    ihip_tensor hk, hv;
+    cache_describe(cache, &B, &Hkv, &T_alloc, &hk, &hv);
+    if (shape && (shape->B != B || shape->Hkv != Hkv || shape->max_seq_len > T_alloc))
+        return fail(IHIP_ERR_INVALID_ARG, "%s: shape (B %d, Hkv %d, max_seq_len %d) does not fit the cache (%d, %d, %lld)",
+                    who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
+    return decode_layer_impl(who, shape, q, hk, hv, cache, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
+                             out_block_starts, ws, ws_bytes, stream);
 }
 
 int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
@@ -369,7 +400,7 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
-    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, (hipStream_t)stream);
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
                                (hipStream_t)stream);

@@ -1,0 +1,323 @@
+// Host-memory KV tier with two on-GPU hot-block banks (Sec. 4 "KV Cache
+// Offloading"; Alg. 4: "obtain a list of GPU cache misses ... evict cold
+// tokens ... replace them with the cache misses, depending on LRU policy").
+//
+// K/V of the layer live in pinned host memory that kernels can read directly
+// over the host link.  Two banks in HBM hold copies of 2^k-token blocks: the
+// mask-selection bank (keys only, read by the pruning stages) and the
+// sparse-attention bank (keys and values).  A page table maps a global block
+// id (sequence, KV head, block) to a bank slot.  During a layer call kernels
+// only mark blocks (touched / missed) and refresh LRU stamps; after the call
+// ihip_cache_update turns the miss flags into an ascending miss list, picks as
+// many least-recently-used slots (oldest stamp first, lowest slot on a tie)
+// and copies the missed blocks from host memory into them.  Everything is
+// deterministic, so a CPU simulation of the same policy reproduces the tables.
+#include "block_select.h"
+
+namespace ihip {
+
+struct Bank {
+    int n_slots;
+    int32_t *page_table;      // [n_gb]
+    int32_t *slot_block;      // [n_slots] global block id or -1
+    uint32_t *slot_stamp;     // [n_slots]
+    uint8_t *touch_flag;      // [n_gb_pad]
+    uint8_t *miss_flag;       // [n_gb_pad]
+    int32_t *miss_list;       // [n_gb]
+    int32_t *victims;         // [n_slots]
+    unsigned long long *counters;   // [4]: hit blocks, missed blocks (cumulative), last call's misses, last call's touches
+    uint16_t *bank_k, *bank_v;      // [n_slots][block][d]; bank_v null for the keys-only bank
+};
+
+}  // namespace ihip
+
+struct ihip_cache {
+    int B, Hkv;
+    int64_t T_alloc;
+    int block_tokens, block_log2, blocks_per_head, n_gb;
+    ihip_tensor host_k, host_v;
+    ihip::Bank bank[2];
+    uint32_t stamp;           // counter of the current layer call (starts at 1)
+};
+
+namespace ihip {
+
+constexpr int kCacheThreads = 1024;
+
+static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// carve one bank out of dev memory starting at *off (or just measure when base == nullptr)
+static void carve_bank(Bank &b, char *base, size_t &off, int n_gb, int n_slots, int block_tokens, bool has_v)
+{
+    auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += a256(bytes); return p; };
+    b.n_slots = n_slots;
+    b.page_table = (int32_t *)take((size_t)n_gb * 4);
+    b.slot_block = (int32_t *)take((size_t)n_slots * 4);
+    b.slot_stamp = (uint32_t *)take((size_t)n_slots * 4);
+    b.touch_flag = (uint8_t *)take((size_t)n_gb + 16);
+    b.miss_flag = (uint8_t *)take((size_t)n_gb + 16);
+    b.miss_list = (int32_t *)take((size_t)n_gb * 4);
+    b.victims = (int32_t *)take((size_t)n_slots * 4);
+    b.counters = (unsigned long long *)take(4 * 8);
+    b.bank_k = (uint16_t *)take((size_t)n_slots * block_tokens * kD * 2);
+    b.bank_v = has_v ? (uint16_t *)take((size_t)n_slots * block_tokens * kD * 2) : nullptr;
+}
+
+__global__ void cache_init_kernel(const Bank b, const int n_gb)
+{
+    const int stride = gridDim.x * blockDim.x;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_gb; i += stride) {
+        b.page_table[i] = -1;
+        b.touch_flag[i] = 0;
+        b.miss_flag[i] = 0;
+    }
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slots; i += stride) {
+        b.slot_block[i] = -1;
+        b.slot_stamp[i] = 0;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 4) b.counters[threadIdx.x] = 0;
+}
+
+// miss flags -> ascending miss list; counts; clears the flags.  One workgroup.
+__global__ __launch_bounds__(kCacheThreads) void cache_collect_kernel(const Bank b, const int n_gb)
+{
+    __shared__ uint32_t wave_miss[kCacheThreads / 64], wave_touch[kCacheThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int c = (n_gb + kCacheThreads - 1) / kCacheThreads;
+    const int i0 = min(n_gb, tid * c), i1 = min(n_gb, i0 + c);
+    uint32_t miss = 0, touch = 0;
+    for (int i = i0; i < i1; ++i) { miss += b.miss_flag[i]; touch += b.touch_flag[i]; }
+    const uint32_t miss_incl = wave_incl_scan_u32(miss, lane);
+    uint32_t t = touch;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) t += __shfl_xor(t, d, 64);
+    if (lane == 63) wave_miss[wv] = miss_incl;
+    if (lane == 0) wave_touch[wv] = t;
+    __syncthreads();
+    uint32_t base = miss_incl - miss, total_miss = 0, total_touch = 0;
+    for (int w = 0; w < kCacheThreads / 64; ++w) {
+        if (w < wv) base += wave_miss[w];
+        total_miss += wave_miss[w];
+        total_touch += wave_touch[w];
+    }
+    for (int i = i0; i < i1; ++i) {
+        if (b.miss_flag[i]) b.miss_list[base++] = i;
+        b.miss_flag[i] = 0;
+        b.touch_flag[i] = 0;
+    }
+    if (tid == 0) {
+        b.counters[0] += total_touch - total_miss;
+        b.counters[1] += total_miss;
+        b.counters[2] = total_miss;
+        b.counters[3] = total_touch;
+    }
+}
+
+// the min(misses, slots) least recently used slots, ascending slot order.  One workgroup.
+__global__ __launch_bounds__(kCacheThreads) void cache_victims_kernel(const Bank b)
+{
+    __shared__ SelectScratch<kCacheThreads> scratch;
+    const int m_eff = (int)min((unsigned long long)b.n_slots, b.counters[2]);
+    if (m_eff == 0) return;
+    block_select_largest<kCacheThreads>(
+        b.n_slots, m_eff,
+        [&](int i) -> uint32_t { return ~b.slot_stamp[i]; },          // oldest stamp = largest key
+        [&](uint32_t rank, int i) { b.victims[rank] = i; },
+        scratch);
+}
+
+// workgroup i: evict victims[i], install miss_list[i] there and copy its rows from host memory
+__global__ __launch_bounds__(256) void cache_insert_kernel(const Bank b, const ihip_tensor hk, const ihip_tensor hv,
+                                                           const int Hkv, const int64_t T_alloc, const int block_log2,
+                                                           const int blocks_per_head, const uint32_t stamp)
+{
+    const int i = blockIdx.x;
+    const int m_eff = (int)min((unsigned long long)b.n_slots, b.counters[2]);
+    if (i >= m_eff) return;
+    const int gb = b.miss_list[i];
+    const int slot = b.victims[i];
+    if (threadIdx.x == 0) {
+        const int old = b.slot_block[slot];
+        if (old >= 0) b.page_table[old] = -1;
+        b.slot_block[slot] = gb;
+        b.page_table[gb] = slot;
+        b.slot_stamp[slot] = stamp;
+    }
+    const int bg = gb / blocks_per_head, blk = gb % blocks_per_head;
+    const int bb = bg / Hkv, g = bg % Hkv;
+    const int bt = 1 << block_log2;
+    const int l16 = threadIdx.x & 15;
+    const uint16_t *src_k = (const uint16_t *)hk.ptr + bb * hk.stride_b + g * hk.stride_h;
+    const uint16_t *src_v = (const uint16_t *)hv.ptr + bb * hv.stride_b + g * hv.stride_h;
+    for (int r = threadIdx.x >> 4; r < bt; r += 16) {
+        const int64_t pos = ((int64_t)blk << block_log2) + r;
+        if (pos >= T_alloc) break;
+        const int64_t dst = (((int64_t)slot << block_log2) + r) * kD + l16 * 8;
+        *reinterpret_cast<uint4 *>(b.bank_k + dst) =
+            *reinterpret_cast<const uint4 *>(src_k + pos * hk.stride_t + l16 * 8);
+        if (b.bank_v != nullptr)
+            *reinterpret_cast<uint4 *>(b.bank_v + dst) =
+                *reinterpret_cast<const uint4 *>(src_v + pos * hv.stride_t + l16 * 8);
+    }
+}
+
+BankView cache_bank_view(const ihip_cache *c, int which)
+{
+    const Bank &b = c->bank[which];
+    BankView v;
+    v.page_table = b.page_table;
+    v.slot_stamp = b.slot_stamp;
+    v.touch_flag = b.touch_flag;
+    v.miss_flag = b.miss_flag;
+    v.bank_k = b.bank_k;
+    v.bank_v = b.bank_v;
+    v.block_log2 = c->block_log2;
+    v.blocks_per_head = c->blocks_per_head;
+    v.stamp = c->stamp;
+    return v;
+}
+
+void cache_describe(const ihip_cache *c, int32_t *B, int32_t *Hkv, int64_t *T_alloc, ihip_tensor *hk, ihip_tensor *hv)
+{
+    *B = c->B; *Hkv = c->Hkv; *T_alloc = c->T_alloc; *hk = c->host_k; *hv = c->host_v;
+}
+
+static int32_t init_banks(ihip_cache *c, hipStream_t st)
+{
+    for (int w = 0; w < 2; ++w)
+        hipLaunchKernelGGL(cache_init_kernel, dim3(256), dim3(256), 0, st, c->bank[w], c->n_gb);
+    c->stamp = 1;
+    return check_launch("cache init");
+}
+
+}  // namespace ihip
+
+using namespace ihip;
+
+extern "C" {
+
+size_t ihip_cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
+                               int32_t sa_slots)
+{
+    if (B <= 0 || Hkv <= 0 || T_alloc <= 0 || block_tokens <= 0 || (block_tokens & (block_tokens - 1)) ||
+        mask_slots <= 0 || sa_slots <= 0)
+        return 0;
+    const int64_t n_gb = (int64_t)B * Hkv * ((T_alloc + block_tokens - 1) / block_tokens);
+    if (n_gb > 0x7fffffff) return 0;
+    Bank b;
+    size_t off = 0;
+    carve_bank(b, nullptr, off, (int)n_gb, mask_slots, block_tokens, false);
+    carve_bank(b, nullptr, off, (int)n_gb, sa_slots, block_tokens, true);
+    return off;
+}
+
+int32_t ihip_cache_create(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k, ihip_tensor host_v,
+                          int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
+                          int32_t sa_slots, void *stream)
+{
+    const char *who = "ihip_cache_create";
+    if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
+    const size_t need = ihip_cache_device_bytes(B, Hkv, T_alloc, block_tokens, mask_slots, sa_slots);
+    if (need == 0) return fail(IHIP_ERR_INVALID_ARG, "%s: bad sizes (block_tokens must be a power of two)", who);
+    if (mask_slots > 65536 * 16 || sa_slots > 65536 * 16)
+        return fail(IHIP_ERR_UNSUPPORTED, "%s: at most 1,048,576 slots per bank", who);
+    if (!dev_mem || dev_bytes < need || ((uintptr_t)dev_mem & 255))
+        return fail(IHIP_ERR_WORKSPACE, "%s: %zu bytes of 256-byte aligned device memory needed, %zu given", who, need,
+                    dev_bytes);
+    if (!host_k.ptr || !host_v.ptr || ((uintptr_t)host_k.ptr & 15) || ((uintptr_t)host_v.ptr & 15) ||
+        (host_k.stride_t & 7) || (host_v.stride_t & 7) || (host_k.stride_h & 7) || (host_v.stride_h & 7) ||
+        (host_k.stride_b & 7) || (host_v.stride_b & 7))
+        return fail(IHIP_ERR_INVALID_ARG, "%s: host K/V must be non-NULL with 16-byte aligned rows", who);
+    // the kernels dereference these pointers: insist on pinned, GPU-addressable host memory
+    for (ihip_tensor *t : {&host_k, &host_v}) {
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, t->ptr) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(IHIP_ERR_INVALID_ARG, "%s: host K/V is not memory HIP knows (allocate it with hipHostMalloc)", who);
+        }
+        if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: host K/V must be pinned host memory the GPU can address", who);
+        t->ptr = attr.devicePointer;
+    }
+    ihip_cache *c = new ihip_cache();
+    c->B = B; c->Hkv = Hkv; c->T_alloc = T_alloc;
+    c->block_tokens = block_tokens;
+    c->block_log2 = __builtin_ctz(block_tokens);
+    c->blocks_per_head = (int)((T_alloc + block_tokens - 1) / block_tokens);
+    c->n_gb = B * Hkv * c->blocks_per_head;
+    c->host_k = host_k; c->host_v = host_v;
+    size_t off = 0;
+    carve_bank(c->bank[0], (char *)dev_mem, off, c->n_gb, mask_slots, block_tokens, false);
+    carve_bank(c->bank[1], (char *)dev_mem, off, c->n_gb, sa_slots, block_tokens, true);
+    const int32_t rc = init_banks(c, (hipStream_t)stream);
+    if (rc != IHIP_OK) { delete c; return rc; }
+    *out = c;
+    return IHIP_OK;
+}
+
+void ihip_cache_destroy(ihip_cache *c) { delete c; }
+
+int32_t ihip_cache_reset(ihip_cache *c, void *stream)
+{
+    if (!c) return fail(IHIP_ERR_INVALID_ARG, "ihip_cache_reset: cache is NULL");
+    return init_banks(c, (hipStream_t)stream);
+}
+
+int32_t ihip_cache_update(ihip_cache *c, void *stream)
+{
+    if (!c) return fail(IHIP_ERR_INVALID_ARG, "ihip_cache_update: cache is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    for (int w = 0; w < 2; ++w) {
+        const Bank &b = c->bank[w];
+        {
+            KernelTimer t(w == 0 ? "cache_collect.mask" : "cache_collect.sa", st);
+            hipLaunchKernelGGL(cache_collect_kernel, dim3(1), dim3(kCacheThreads), 0, st, b, c->n_gb);
+        }
+        {
+            KernelTimer t(w == 0 ? "cache_victims.mask" : "cache_victims.sa", st);
+            hipLaunchKernelGGL(cache_victims_kernel, dim3(1), dim3(kCacheThreads), 0, st, b);
+        }
+        {
+            KernelTimer t(w == 0 ? "cache_insert.mask" : "cache_insert.sa", st);
+            hipLaunchKernelGGL(cache_insert_kernel, dim3(b.n_slots), dim3(256), 0, st, b, c->host_k, c->host_v, c->Hkv,
+                               c->T_alloc, c->block_log2, c->blocks_per_head, c->stamp);
+        }
+    }
+    c->stamp += 1;
+    return check_launch("cache update");
+}
+
+int32_t ihip_cache_stats(ihip_cache *c, uint64_t *stats8)
+{
+    if (!c || !stats8) return fail(IHIP_ERR_INVALID_ARG, "ihip_cache_stats: NULL argument");
+    if (hipDeviceSynchronize() != hipSuccess) return fail(IHIP_ERR_HIP, "ihip_cache_stats: device synchronise failed");
+    for (int w = 0; w < 2; ++w)
+        if (hipMemcpy(stats8 + 4 * w, c->bank[w].counters, 32, hipMemcpyDeviceToHost) != hipSuccess)
+            return fail(IHIP_ERR_HIP, "ihip_cache_stats: copy failed");
+    return IHIP_OK;
+}
+
+int32_t ihip_cache_read_tables(ihip_cache *c, int32_t bank, int32_t *host_page_table, int32_t *host_slot_block)
+{
+    if (!c || bank < 0 || bank > 1) return fail(IHIP_ERR_INVALID_ARG, "ihip_cache_read_tables: bad argument");
+    if (hipDeviceSynchronize() != hipSuccess) return fail(IHIP_ERR_HIP, "ihip_cache_read_tables: synchronise failed");
+    const Bank &b = c->bank[bank];
+    if (host_page_table &&
+        hipMemcpy(host_page_table, b.page_table, (size_t)c->n_gb * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(IHIP_ERR_HIP, "ihip_cache_read_tables: copy failed");
+    if (host_slot_block &&
+        hipMemcpy(host_slot_block, b.slot_block, (size_t)b.n_slots * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(IHIP_ERR_HIP, "ihip_cache_read_tables: copy failed");
+    return IHIP_OK;
+}
+
+int32_t ihip_cache_geometry(const ihip_cache *c, int32_t *n_blocks_total, int32_t *mask_slots, int32_t *sa_slots)
+{
+    if (!c) return fail(IHIP_ERR_INVALID_ARG, "ihip_cache_geometry: cache is NULL");
+    if (n_blocks_total) *n_blocks_total = c->n_gb;
+    if (mask_slots) *mask_slots = c->bank[0].n_slots;
+    if (sa_slots) *sa_slots = c->bank[1].n_slots;
+    return IHIP_OK;
+}
+
+}  // extern "C"

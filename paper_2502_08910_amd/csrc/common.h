@@ -6,6 +6,8 @@
 
 #include "../../include/ihip.h"
 
+struct ihip_cache;
+
 namespace ihip {
 
 constexpr int kD = 128;            // head dimension: 16 lanes x 8 bf16 (16 B) per row
@@ -80,6 +82,53 @@ __device__ inline int slot_start(const Problem &pr, const int32_t *parent_starts
     }
     return start < pr.hi ? start : -1;
 }
+
+// ---- where a K or V row lives ------------------------------------------------
+// Kernels read rows through a "source".  DirectRows: the tensor is in HBM.
+// CachedRows: the tensor is in pinned host memory and 2^block_log2-token
+// blocks of it may have a copy in an on-GPU bank; a page table maps the global
+// block id to a bank slot (Sec. 4 "KV Cache Offloading").  Every access marks
+// the block as touched; a hit refreshes the slot's LRU stamp, a miss reads the
+// host copy over the host link and flags the block for insertion.
+struct DirectRows {
+    const uint16_t *base;     // row 0 of this (sequence, KV head)
+    int64_t st;               // elements between rows
+    __device__ const uint16_t *row(int pos, bool) const { return base + (int64_t)pos * st; }
+};
+
+struct BankView {
+    const int32_t *page_table;   // [n_blocks_total] slot or -1
+    uint32_t *slot_stamp;        // [n_slots] call counter of the last touch
+    uint8_t *touch_flag;         // [n_blocks_total] touched during this call
+    uint8_t *miss_flag;          // [n_blocks_total] touched and not resident
+    const uint16_t *bank_k;      // [n_slots][block][d]
+    const uint16_t *bank_v;      // same for V, or null (bank holds keys only)
+    int block_log2;
+    int blocks_per_head;         // blocks of one (sequence, KV head)
+    uint32_t stamp;              // this call's counter value
+};
+
+struct CachedRows {
+    BankView c;
+    const uint16_t *host_base;   // row 0 of this (sequence, KV head) in host memory
+    int64_t host_st;
+    const uint16_t *bank;        // bank_k or bank_v
+    int gb0;                     // global id of this (sequence, KV head)'s block 0
+    // leader: one lane per row does the bookkeeping stores
+    __device__ const uint16_t *row(int pos, bool leader) const
+    {
+        const int gb = gb0 + (pos >> c.block_log2);
+        const int slot = c.page_table[gb];
+        if (leader) {
+            c.touch_flag[gb] = 1;
+            if (slot >= 0) c.slot_stamp[slot] = c.stamp;
+            else c.miss_flag[gb] = 1;
+        }
+        if (slot >= 0)
+            return bank + ((((int64_t)slot << c.block_log2) | (pos & ((1 << c.block_log2) - 1))) * kD);
+        return host_base + (int64_t)pos * host_st;
+    }
+};
 
 // ---- bf16 ------------------------------------------------------------------
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

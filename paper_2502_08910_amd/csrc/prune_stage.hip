@@ -19,9 +19,27 @@ struct PruneArgs {
     int n_parent, ratio_log2, chunk, max_chunks;
     float *out_scores;
     int32_t *out_rep;
+    BankView bank;            // used by the cached instantiations only (K then points to host memory)
 };
 
-template <int G, int U>
+template <bool CACHED> struct KeySource;
+template <> struct KeySource<false> {
+    typedef DirectRows type;
+    static __device__ type make(const PruneArgs &a, const Problem &pr)
+    {
+        return DirectRows{a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st};
+    }
+};
+template <> struct KeySource<true> {
+    typedef CachedRows type;
+    static __device__ type make(const PruneArgs &a, const Problem &pr)
+    {
+        return CachedRows{a.bank, a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st, a.bank.bank_k,
+                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+    }
+};
+
+template <int G, int U, bool CACHED>
 __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 {
     const int p = blockIdx.y;
@@ -39,7 +57,9 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 #pragma unroll
         for (int h = 0; h < G; ++h) unpack8(load_row16(qb, h * a.q_sh, l16), qf[h]);
     }
-    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+    const typename KeySource<CACHED>::type src = KeySource<CACHED>::make(a, pr);
+    const bool leader = l16 == 0;
+    auto load_row = [&](int pos) { return *reinterpret_cast<const uint4 *>(src.row(pos, leader) + l16 * 8); };
 
     int start[U], len[U];
     bool valid[U];
@@ -64,8 +84,8 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
         for (int u = 0; u < U; ++u) {
             r0[u] = make_uint4(0, 0, 0, 0);
             r1[u] = make_uint4(0, 0, 0, 0);
-            if (valid[u]) r0[u] = load_row16(kb, (int64_t)start[u] * a.k_st, l16);
-            if (mid >= 1 && mid < len[u]) r1[u] = load_row16(kb, (int64_t)(start[u] + mid) * a.k_st, l16);
+            if (valid[u]) r0[u] = load_row(start[u]);
+            if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -91,7 +111,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
                 const int mid = off[u][h] + half;
                 ok[u][h] = mid < len[u];
                 r[u][h] = make_uint4(0, 0, 0, 0);
-                if (ok[u][h]) r[u][h] = load_row16(kb, (int64_t)(start[u] + mid) * a.k_st, l16);
+                if (ok[u][h]) r[u][h] = load_row(start[u] + mid);
             }
         }
 #pragma unroll
@@ -262,14 +282,19 @@ static void launch_decode(const PruneArgs &a, int P, hipStream_t st)
     constexpr int U = 2;
     dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
     KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
-    hipLaunchKernelGGL((prune_decode_kernel<G, U>), grid, dim3(256), 0, st, a);
+    if (a.bank.page_table != nullptr)
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, true>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, false>), grid, dim3(256), 0, st, a);
 }
 
 int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                            const int32_t *parent_starts, int n_parent, int parent_chunk, int chunk,
-                           int max_chunks, float *out_scores, int32_t *out_rep, hipStream_t st)
+                           int max_chunks, float *out_scores, int32_t *out_rep, const BankView *bank,
+                           hipStream_t st)
 {
     PruneArgs a;
+    a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
@@ -282,6 +307,7 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     a.out_rep = out_rep;
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (max_chunks == 0 || P == 0) return IHIP_OK;
+    if (bank && s.b_q != 1) return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: the host tier serves decode only");
     if (s.b_q == 1) {
         switch (a.ge.G) {
         case 1: launch_decode<1>(a, P, st); break;

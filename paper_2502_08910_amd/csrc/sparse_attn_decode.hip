@@ -28,6 +28,33 @@ struct AttnDecodeArgs {
     float *part_acc;     // [P, n_splits, G, 128]
     uint16_t *out;       // bf16 [B, Hq, 1, d]
     float *out_lse;      // [B, Hq] or null
+    BankView bank;       // used by the cached instantiations only (K/V then point to host memory)
+};
+
+template <bool CACHED> struct KvSource;
+template <> struct KvSource<false> {
+    typedef DirectRows type;
+    static __device__ type k(const AttnDecodeArgs &a, const Problem &pr)
+    {
+        return DirectRows{a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st};
+    }
+    static __device__ type v(const AttnDecodeArgs &a, const Problem &pr)
+    {
+        return DirectRows{a.v + pr.b * a.v_sb + pr.g * a.v_sh, a.v_st};
+    }
+};
+template <> struct KvSource<true> {
+    typedef CachedRows type;
+    static __device__ type k(const AttnDecodeArgs &a, const Problem &pr)
+    {
+        return CachedRows{a.bank, a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st, a.bank.bank_k,
+                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+    }
+    static __device__ type v(const AttnDecodeArgs &a, const Problem &pr)
+    {
+        return CachedRows{a.bank, a.v + pr.b * a.v_sb + pr.g * a.v_sh, a.v_st, a.bank.bank_v,
+                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+    }
 };
 
 // slot -> key position, or -1
@@ -47,7 +74,7 @@ __device__ inline int slot_to_pos(const AttnDecodeArgs &a, const Problem &pr, in
     return pos < pr.E ? pos : -1;
 }
 
-template <int G>
+template <int G, bool CACHED>
 __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const AttnDecodeArgs a)
 {
     const int p = blockIdx.y, split = blockIdx.x;
@@ -66,8 +93,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
             for (int i = 0; i < 8; ++i) qf[h][i] *= a.scale_log2e;
         }
     }
-    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
-    const uint16_t *vb = a.v + pr.b * a.v_sb + pr.g * a.v_sh;
+    const typename KvSource<CACHED>::type ksrc = KvSource<CACHED>::k(a, pr);
+    const typename KvSource<CACHED>::type vsrc = KvSource<CACHED>::v(a, pr);
 
     float m[G], l[G], acc[G][8];
 #pragma unroll
@@ -91,8 +118,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
             kr[u] = make_uint4(0, 0, 0, 0);
             vr[u] = make_uint4(0, 0, 0, 0);
             if (ok[u]) {
-                kr[u] = load_row16(kb, (int64_t)pos * a.k_st, l16);
-                vr[u] = load_row16(vb, (int64_t)pos * a.v_st, l16);
+                kr[u] = *reinterpret_cast<const uint4 *>(ksrc.row(pos, l16 == 0) + l16 * 8);
+                vr[u] = *reinterpret_cast<const uint4 *>(vsrc.row(pos, false) + l16 * 8);   // K did the bookkeeping
             }
         }
 #pragma unroll
@@ -212,9 +239,11 @@ size_t attn_decode_workspace(const ihip_shape &s, int n_blocks, int block)
 
 int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                            const ihip_tensor &v, const int32_t *block_starts, int n_blocks, int block,
-                           float sm_scale, void *out, float *out_lse, void *ws, hipStream_t st)
+                           float sm_scale, void *out, float *out_lse, void *ws, const BankView *bank,
+                           hipStream_t st)
 {
     AttnDecodeArgs a;
+    a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
@@ -236,10 +265,14 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     {
     KernelTimer timer("attn_decode_split", st);
     switch (G) {
-    case 1: hipLaunchKernelGGL(attn_decode_split_kernel<1>, grid, dim3(kAttnThreads), 0, st, a); break;
-    case 2: hipLaunchKernelGGL(attn_decode_split_kernel<2>, grid, dim3(kAttnThreads), 0, st, a); break;
-    case 4: hipLaunchKernelGGL(attn_decode_split_kernel<4>, grid, dim3(kAttnThreads), 0, st, a); break;
-    case 8: hipLaunchKernelGGL(attn_decode_split_kernel<8>, grid, dim3(kAttnThreads), 0, st, a); break;
+#define IHIP_AD_LAUNCH(GG)                                                                                   \
+    if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, true>), grid, dim3(kAttnThreads), 0, st, a);  \
+    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, false>), grid, dim3(kAttnThreads), 0, st, a)
+    case 1: IHIP_AD_LAUNCH(1); break;
+    case 2: IHIP_AD_LAUNCH(2); break;
+    case 4: IHIP_AD_LAUNCH(4); break;
+    case 8: IHIP_AD_LAUNCH(8); break;
+#undef IHIP_AD_LAUNCH
     default: return fail(IHIP_ERR_UNSUPPORTED, "Hq/Hkv = %d not in {1,2,4,8}", G);
     }
     }

@@ -1,0 +1,116 @@
+"""Host-memory KV tier + on-GPU hot-block cache: outputs are bit-identical to
+the HBM-resident path whatever the cache holds, and the page tables, slot
+tables and hit/miss counts follow the CPU simulation of the LRU policy
+exactly (integer-valued inputs, so both sides touch the same rows)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import configs  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def ihip():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_08910_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def orc():
+    import oracle
+    oracle.build(force=False)
+    return oracle
+
+
+def touched_blocks(o, w, stages_res, bt, blocks_per_head, bank):
+    """Global block ids the oracle touches in one layer call: bank 0 = pruning
+    stages (keys), bank 1 = attention (keys and values)."""
+    out = set()
+    for (b, g, m), (pr, _, _) in stages_res.items():
+        base = (b * w.Hkv + g) * blocks_per_head
+        if bank == 0:
+            for st in pr.stages:
+                out.update((base + st.touched_pos // bt).tolist())
+        else:
+            pos = o.attended_positions(b, m, pr.block_starts, pr.block_lens)
+            out.update((base + pos // bt).tolist())
+    return out
+
+
+@pytest.mark.parametrize("mask_slots,sa_slots", [(40, 24), (1000, 1000), (3, 2)])
+def test_cached_layer_equals_resident_and_follows_lru(ihip, orc, mask_slots, sa_slots):
+    w = configs.shrink(configs.CFG1, B=2, Hq=8, Hkv=2, T=4096 + 29, n_stream=256, n_needles=0,
+                       stages=((64, 8), (16, 8), (4, 16)))
+    bt = 64
+    chunks = [s[0] for s in w.stages]
+    keeps = [s[1] for s in w.stages]
+    _, k, v, _, _ = configs.make_inputs(w, 0, kind="int")
+    sl = torch.tensor([w.T, w.T - 700], dtype=torch.int32)
+    hk = torch.empty(k.shape, dtype=torch.bfloat16, pin_memory=True).copy_(k)
+    hv = torch.empty(v.shape, dtype=torch.bfloat16, pin_memory=True).copy_(v)
+    kd, vd, sld = k.cuda(), v.cuda(), sl.cuda()
+    cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots)
+    blocks_per_head = (w.T + bt - 1) // bt
+    sim = [orc.LruBank(cache.n_blocks_total, mask_slots), orc.LruBank(cache.n_blocks_total, sa_slots)]
+    try:
+        for call, seed in enumerate([0, 1, 0, 2, 1, 0, 3]):
+            q = configs.make_q(w, seed, kind="int")
+            qd = q.cuda()
+            L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
+            ref_blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+            ref = L.decode_layer(qd, kd, vd, chunks, keeps, out_blocks=ref_blocks)
+            got_blocks = torch.empty_like(ref_blocks)
+            got = ihip.decode_layer_cached(L, qd, cache, chunks, keeps, out_blocks=got_blocks)
+            cache.update()
+            torch.cuda.synchronize()
+            assert torch.equal(got_blocks, ref_blocks), call
+            assert torch.equal(got, ref), call          # bit-identical whatever the cache holds
+
+            o = orc.Oracle(q, k, v, sl.tolist(), 1, w.n_sink, w.n_stream)
+            res = o.layer(w.stages)
+            stats = cache.stats()
+            for bank, name in ((0, "mask"), (1, "sa")):
+                sim[bank].call(touched_blocks(o, w, res, bt, blocks_per_head, bank))
+                pt, sb = cache.tables(bank)
+                assert stats[name]["last_touched"] == sim[bank].last_touched, (call, name)
+                assert stats[name]["last_misses"] == sim[bank].last_misses, (call, name)
+                assert (stats[name]["hits"], stats[name]["misses"]) == (sim[bank].hits, sim[bank].misses)
+                assert pt.tolist() == sim[bank].page_table, (call, name)
+                assert sb.tolist() == sim[bank].slot_block, (call, name)
+        # a reset empties it again
+        cache.reset()
+        pt, sb = cache.tables(0)
+        assert (pt == -1).all() and (sb == -1).all()
+    finally:
+        cache.close()
+
+
+def test_bank_contents_are_the_host_rows(ihip, orc):
+    # after warming, a layer call served from the banks gives the same bits (checked above);
+    # here: everything resident => second call has no misses at all
+    w = configs.shrink(configs.CFG1, B=1, Hq=4, Hkv=1, T=2048, n_stream=256, n_needles=0,
+                       stages=((64, 8), (16, 8), (4, 16)))
+    chunks = [s[0] for s in w.stages]
+    keeps = [s[1] for s in w.stages]
+    q, k, v, sl, _ = configs.make_inputs(w, 1)
+    hk = torch.empty(k.shape, dtype=torch.bfloat16, pin_memory=True).copy_(k)
+    hv = torch.empty(v.shape, dtype=torch.bfloat16, pin_memory=True).copy_(v)
+    cache = ihip.HostKVCache(hk, hv, 64, 32, 32)          # 32 blocks = the whole sequence
+    try:
+        qd, kd, vd, sld = q.cuda(), k.cuda(), v.cuda(), sl.cuda()
+        L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
+        ref = L.decode_layer(qd, kd, vd, chunks, keeps)
+        for call in range(2):
+            got = ihip.decode_layer_cached(L, qd, cache, chunks, keeps)
+            cache.update()
+            assert torch.equal(got, ref)
+        s = cache.stats()
+        assert s["mask"]["last_misses"] == 0 and s["sa"]["last_misses"] == 0
+        assert s["mask"]["last_touched"] > 0 and s["sa"]["last_touched"] > 0
+    finally:
+        cache.close()
