@@ -276,6 +276,100 @@ def bench_prefill(args, w, torch, ihip, configs):
     }
 
 
+# ---------------------------------------------------------------------------
+def bench_offload(args, w, torch, ihip, configs):
+    """cfg5: K/V of the layer in pinned host memory, 512 MiB of on-GPU banks
+    (256 MiB of keys for the pruning stages, 256 MiB of keys+values for the
+    attention), one decode call after another with Zipf(1.1)-placed needles.
+    The bound here is the host link, not HBM; no roofline object is claimed."""
+    from workloads import gen
+    dev = torch.device("cuda:0")
+    steps = 24 if args.steps is None else args.steps
+    warmup = 4 if args.warmup is None else args.warmup
+    chunks = [s[0] for s in w.stages]
+    keeps = [s[1] for s in w.stages]
+    bt, mask_slots, sa_slots = 64, 16384, 8192
+    shape = (w.B, w.Hkv, w.T, w.d)
+
+    t0 = time.perf_counter()
+    hk = torch.empty(shape, dtype=torch.bfloat16, pin_memory=True)
+    hv = torch.empty(shape, dtype=torch.bfloat16, pin_memory=True)
+    step_t = 1 << 18
+    for tid_, host in ((configs.TID_K, hk), (configs.TID_V, hv)):
+        for t_lo in range(0, w.T, step_t):
+            t_hi = min(w.T, t_lo + step_t)
+            host[:, :, t_lo:t_hi].copy_(gen.normal_bf16(0, tid_, shape, dev, (0, w.B, 0, w.Hkv, t_lo, t_hi)))
+    n_calls = steps + warmup
+    l1 = chunks[0]
+    n_chunks = (w.T - w.n_sink - w.n_stream) // l1
+    qs = []
+    for c in range(n_calls):
+        q = configs.make_q(w, c, "cpu")
+        ranks = gen.zipf_ranks(c, 77, w.Hkv * w.n_needles, n_chunks).view(w.Hkv, w.n_needles)
+        chunk_ids = (ranks * 7919 + 12345) % n_chunks            # fixed scramble of the ranks (7919 is prime)
+        pos = w.n_sink + chunk_ids * l1
+        noise = gen.normal_bf16(c, configs.TID_NEEDLE_NOISE, (1, w.Hkv, w.n_needles, w.d)).float()[0]
+        for g in range(w.Hkv):
+            for i in range(w.n_needles):
+                qv = q[0, g * w.G + i % w.G, 0].float()
+                hk[0, g, pos[g, i]] = (w.needle_gain * qv / qv.norm() + w.needle_noise * noise[g, i]).to(torch.bfloat16)
+        qs.append(q.to(dev))
+    seq_lens = torch.full((w.B,), w.T, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t0
+
+    cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots)
+    kview = torch.empty((w.B, w.Hkv, w.T, 0), dtype=torch.bfloat16, device=dev)     # shape carrier only
+    L = ihip.Layer(qs[0], kview, seq_lens, w.b_q, w.n_sink, w.n_stream)
+    ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
+    out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
+
+    def step(i):
+        ihip.decode_layer_cached(L, qs[i % n_calls], cache, chunks, keeps, ws=ws, out=out)
+        cache.update()
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    s0 = cache.stats()
+    t0 = time.perf_counter()
+    for i in range(warmup, n_calls):
+        step(i)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / steps * 1e6
+    s1 = cache.stats()
+    kernels = {}
+    if not args.no_profile_pass:
+        ihip.profile_enable(True)
+        for i in range(warmup, n_calls):
+            step(i)
+        torch.cuda.synchronize()
+        ihip.profile_enable(False)
+        for name, (ms, n) in ihip.profile_read().items():
+            kernels[name] = {"us": ms / n * 1e3, "launches_per_step": n / steps}
+    hit = {}
+    for bank in ("mask", "sa"):
+        h = s1[bank]["hits"] - s0[bank]["hits"]
+        m = s1[bank]["misses"] - s0[bank]["misses"]
+        hit[bank] = {"block_hits": h, "block_misses": m, "hit_ratio": h / max(1, h + m)}
+    cpu = None
+    if args.cpu_seconds > 0:
+        sample = decode_oracle_sample(w, qs, hk, hv, [w.T], args.cpu_seconds)
+        cpu = {"value": sample["seconds"] / sample["layer_calls_one_sequence"] * 1e6, "unit": "us/layer", "cores": 1,
+               "kind": "oracle", "sample": f"{sample['layer_calls_one_sequence']} whole layer calls (all {w.Hkv} KV heads), "
+                                           f"{sample['seconds']:.1f} s"}
+    cache.close()
+    return {
+        "metric": "sparse_attn_decode_offload_us_per_layer", "value": us, "unit": "us/layer", "steps": steps,
+        "warmup": warmup,
+        "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
+                   "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
+                   "n_stream": w.n_stream, "block_tokens": bt, "mask_bank_MiB": mask_slots * bt * 256 >> 20,
+                   "sa_bank_MiB": sa_slots * bt * 512 >> 20, "needles": "Zipf(1.1) over scrambled chunk ranks"},
+        "roofline": None, "cpu_baseline": cpu, "cache": hit, "kernels": kernels, "setup_s": t_setup,
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -297,7 +391,12 @@ def main():
     ihip.lib()
     w = configs.BY_NAME[args.workload]
     torch.cuda.set_device(0)
-    body = bench_decode(args, w, torch, ihip, configs) if w.Tq == 1 else bench_prefill(args, w, torch, ihip, configs)
+    if w.name.startswith("cfg5"):
+        body = bench_offload(args, w, torch, ihip, configs)
+    elif w.Tq == 1:
+        body = bench_decode(args, w, torch, ihip, configs)
+    else:
+        body = bench_prefill(args, w, torch, ihip, configs)
     line = {"metric": body.pop("metric"), "value": body.pop("value"), "unit": body.pop("unit"), "n_gpus": 1,
             "steps": body.pop("steps"), "warmup": body.pop("warmup")}
     line["ms_per_step"] = line["value"] / 1e3

@@ -196,9 +196,9 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
  * were touched and which were missing.  ihip_cache_update (same stream, after
  * the layer call) then, per bank, evicts as many least-recently-used slots as
  * there were missed blocks (oldest last-touch call first, lowest slot on a
- * tie; never-used slots first) and copies the missed blocks in, in ascending
- * block order; if more blocks were missed than the bank holds, only the
- * lowest-numbered ones are inserted.  Layer calls and updates on one cache
+ * tie; never-used slots first; never a slot touched in this same call) and
+ * copies the missed blocks in, in ascending block order; if more blocks were
+ * missed than there are such slots, only the lowest-numbered ones are inserted.  Layer calls and updates on one cache
  * must not overlap.
  *
  * ihip_cache_stats (synchronises the device) fills stats8 (host):

@@ -7,8 +7,10 @@ a layer call are collected and inserted after it).  Granularity and tie rules
 are this build's reading: blocks of block_tokens tokens; all touches of one
 call share the call's stamp; after the call the missed blocks, in ascending
 block id, replace the slots with the oldest stamps (lowest slot on a tie,
-never-used slots first); if more blocks were missed than the bank holds only
-the lowest-numbered ones are inserted.
+never-used slots first); a slot touched in this same call is never evicted
+(both blocks were just used: a tie, and swapping them buys nothing); if more
+blocks were missed than there are such slots only the lowest-numbered ones are
+inserted.
 """
 from __future__ import annotations
 
@@ -37,8 +39,9 @@ class LruBank:
         self.hits += len(touched) - len(missed)
         self.misses += len(missed)
         self.last_misses, self.last_touched = len(missed), len(touched)
-        n_ins = min(len(missed), len(self.slot_block))
-        order = sorted(range(len(self.slot_block)), key=lambda s: (self.slot_stamp[s], s))
+        eligible = [s for s in range(len(self.slot_block)) if self.slot_stamp[s] != self.stamp]
+        n_ins = min(len(missed), len(eligible))
+        order = sorted(eligible, key=lambda s: (self.slot_stamp[s], s))
         victims = sorted(order[:n_ins])
         for b, s in zip(missed[:n_ins], victims):
             old = self.slot_block[s]

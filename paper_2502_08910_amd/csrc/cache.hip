@@ -9,8 +9,9 @@
 // id (sequence, KV head, block) to a bank slot.  During a layer call kernels
 // only mark blocks (touched / missed) and refresh LRU stamps; after the call
 // ihip_cache_update turns the miss flags into an ascending miss list, picks as
-// many least-recently-used slots (oldest stamp first, lowest slot on a tie)
-// and copies the missed blocks from host memory into them.  Everything is
+// many least-recently-used slots (oldest stamp first, lowest slot on a tie,
+// never a slot touched in this same call) and copies the missed blocks from
+// host memory into them.  Everything is
 // deterministic, so a CPU simulation of the same policy reproduces the tables.
 #include "block_select.h"
 
@@ -25,7 +26,7 @@ struct Bank {
     uint8_t *miss_flag;       // [n_gb_pad]
     int32_t *miss_list;       // [n_gb]
     int32_t *victims;         // [n_slots]
-    unsigned long long *counters;   // [4]: hit blocks, missed blocks (cumulative), last call's misses, last call's touches
+    unsigned long long *counters;   // [8]: hit blocks, missed blocks (cumulative), last call's misses, touches, insertions
     uint16_t *bank_k, *bank_v;      // [n_slots][block][d]; bank_v null for the keys-only bank
 };
 
@@ -58,7 +59,7 @@ static void carve_bank(Bank &b, char *base, size_t &off, int n_gb, int n_slots, 
     b.miss_flag = (uint8_t *)take((size_t)n_gb + 16);
     b.miss_list = (int32_t *)take((size_t)n_gb * 4);
     b.victims = (int32_t *)take((size_t)n_slots * 4);
-    b.counters = (unsigned long long *)take(4 * 8);
+    b.counters = (unsigned long long *)take(8 * 8);
     b.bank_k = (uint16_t *)take((size_t)n_slots * block_tokens * kD * 2);
     b.bank_v = has_v ? (uint16_t *)take((size_t)n_slots * block_tokens * kD * 2) : nullptr;
 }
@@ -66,27 +67,33 @@ static void carve_bank(Bank &b, char *base, size_t &off, int n_gb, int n_slots, 
 __global__ void cache_init_kernel(const Bank b, const int n_gb)
 {
     const int stride = gridDim.x * blockDim.x;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_gb; i += stride) {
-        b.page_table[i] = -1;
-        b.touch_flag[i] = 0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_gb; i += stride) b.page_table[i] = -1;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < ((n_gb + 15) & ~15); i += stride) {
+        b.touch_flag[i] = 0;          // including the padding up to a multiple of 16
         b.miss_flag[i] = 0;
     }
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slots; i += stride) {
         b.slot_block[i] = -1;
         b.slot_stamp[i] = 0;
     }
-    if (blockIdx.x == 0 && threadIdx.x < 4) b.counters[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && threadIdx.x < 8) b.counters[threadIdx.x] = 0;
 }
 
-// miss flags -> ascending miss list; counts; clears the flags.  One workgroup.
+// miss flags -> ascending miss list; counts; clears the flags.  One workgroup;
+// the 0/1 byte flags are read 16 at a time (the arrays are padded and zeroed
+// to a multiple of 16).
 __global__ __launch_bounds__(kCacheThreads) void cache_collect_kernel(const Bank b, const int n_gb)
 {
     __shared__ uint32_t wave_miss[kCacheThreads / 64], wave_touch[kCacheThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int c = (n_gb + kCacheThreads - 1) / kCacheThreads;
-    const int i0 = min(n_gb, tid * c), i1 = min(n_gb, i0 + c);
+    const int n16 = (n_gb + 15) >> 4;
+    const int c = (n16 + kCacheThreads - 1) / kCacheThreads;
+    const int g0 = min(n16, tid * c), g1 = min(n16, g0 + c);
+    uint4 *mf = reinterpret_cast<uint4 *>(b.miss_flag);
+    uint4 *tf = reinterpret_cast<uint4 *>(b.touch_flag);
+    auto ones = [](const uint4 &x) { return __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w); };
     uint32_t miss = 0, touch = 0;
-    for (int i = i0; i < i1; ++i) { miss += b.miss_flag[i]; touch += b.touch_flag[i]; }
+    for (int g = g0; g < g1; ++g) { miss += ones(mf[g]); touch += ones(tf[g]); }
     const uint32_t miss_incl = wave_incl_scan_u32(miss, lane);
     uint32_t t = touch;
 #pragma unroll
@@ -100,10 +107,15 @@ __global__ __launch_bounds__(kCacheThreads) void cache_collect_kernel(const Bank
         total_miss += wave_miss[w];
         total_touch += wave_touch[w];
     }
-    for (int i = i0; i < i1; ++i) {
-        if (b.miss_flag[i]) b.miss_list[base++] = i;
-        b.miss_flag[i] = 0;
-        b.touch_flag[i] = 0;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    for (int g = g0; g < g1; ++g) {
+        const uint4 m = mf[g];
+        const uint32_t w4[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if ((w4[j >> 2] >> ((j & 3) * 8)) & 1u) b.miss_list[base++] = g * 16 + j;
+        mf[g] = zero;
+        tf[g] = zero;
     }
     if (tid == 0) {
         b.counters[0] += total_touch - total_miss;
@@ -113,11 +125,24 @@ __global__ __launch_bounds__(kCacheThreads) void cache_collect_kernel(const Bank
     }
 }
 
-// the min(misses, slots) least recently used slots, ascending slot order.  One workgroup.
-__global__ __launch_bounds__(kCacheThreads) void cache_victims_kernel(const Bank b)
+// The least recently used slots that will be replaced, ascending slot order:
+// as many as there were misses, but only slots not touched in this call
+// (swapping two blocks that were both just used would only burn host-link
+// bandwidth).  One workgroup.
+__global__ __launch_bounds__(kCacheThreads) void cache_victims_kernel(const Bank b, const uint32_t stamp)
 {
     __shared__ SelectScratch<kCacheThreads> scratch;
-    const int m_eff = (int)min((unsigned long long)b.n_slots, b.counters[2]);
+    __shared__ uint32_t sh_eligible;
+    if (threadIdx.x == 0) sh_eligible = 0;
+    __syncthreads();
+    uint32_t mine = 0;
+    for (int i = threadIdx.x; i < b.n_slots; i += kCacheThreads) mine += b.slot_stamp[i] != stamp;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&sh_eligible, mine);
+    __syncthreads();
+    const int m_eff = (int)min((unsigned long long)sh_eligible, b.counters[2]);
+    if (threadIdx.x == 0) b.counters[4] = m_eff;
     if (m_eff == 0) return;
     block_select_largest<kCacheThreads>(
         b.n_slots, m_eff,
@@ -132,8 +157,7 @@ __global__ __launch_bounds__(256) void cache_insert_kernel(const Bank b, const i
                                                            const int blocks_per_head, const uint32_t stamp)
 {
     const int i = blockIdx.x;
-    const int m_eff = (int)min((unsigned long long)b.n_slots, b.counters[2]);
-    if (i >= m_eff) return;
+    if (i >= (int)b.counters[4]) return;
     const int gb = b.miss_list[i];
     const int slot = b.victims[i];
     if (threadIdx.x == 0) {
@@ -275,7 +299,7 @@ int32_t ihip_cache_update(ihip_cache *c, void *stream)
         }
         {
             KernelTimer t(w == 0 ? "cache_victims.mask" : "cache_victims.sa", st);
-            hipLaunchKernelGGL(cache_victims_kernel, dim3(1), dim3(kCacheThreads), 0, st, b);
+            hipLaunchKernelGGL(cache_victims_kernel, dim3(1), dim3(kCacheThreads), 0, st, b, c->stamp);
         }
         {
             KernelTimer t(w == 0 ? "cache_insert.mask" : "cache_insert.sa", st);

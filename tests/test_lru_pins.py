@@ -48,7 +48,7 @@ def test_batch_rules():
     bank.call([60, 61])                      # evicts the two oldest: 7 (slot 1) and 9 (slot 2)
     assert bank.slot_block == [3, 60, 61, 50]
     assert bank.page_table[7] == -1 and bank.page_table[9] == -1 and bank.page_table[60] == 1
-    bank.call([1, 2, 3, 4, 5, 6])            # 3 hits; 5 misses > capacity: only the 4 lowest ids go in
-    assert sorted(bank.slot_block) == [1, 2, 4, 5]
+    bank.call([1, 2, 3, 4, 5, 6])            # 3 hits and stays; 5 misses, 3 older slots: lowest 3 ids go in
+    assert bank.slot_block == [3, 1, 2, 4]
     assert bank.last_misses == 5 and bank.last_touched == 6
-    assert bank.page_table[3] == -1 and bank.page_table[6] == -1
+    assert bank.page_table[3] == 0 and bank.page_table[5] == -1 and bank.page_table[6] == -1
