@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libihip.so")
 SOURCES = ["api.hip", "prune_stage.hip", "select_blocks.hip", "sparse_attn_decode.hip",
-           "sparse_attn_prefill.hip", "cache.hip"]
+           "sparse_attn_prefill.hip", "sparse_attn_prefill32.hip", "cache.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

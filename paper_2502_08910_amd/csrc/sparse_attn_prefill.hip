@@ -16,45 +16,9 @@
 // agree: k slot (kq, j) is key kq*4+j of the first 16-key tile for j < 4 and
 // key kq*4+j-4 of the second for j >= 4 -- exactly what a lane's two S^T
 // accumulators hold.  V is transposed on its way into LDS.
-#include "common.h"
+#include "attn_prefill_args.h"
 
 namespace ihip {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kPfTile = 32;             // key slots per step
-constexpr int kPfKStride = kD + 8;      // K tile row stride in LDS (elements): 272 B, conflict-free 16-B reads
-constexpr int kPfVStride = kPfTile + 8; // V^T row stride (elements): 80 B
-constexpr float kNegBigPf = -1.0e30f;
-
-struct AttnPrefillArgs {
-    Geometry ge;
-    const uint16_t *q; int64_t q_sb, q_sh, q_st;
-    const uint16_t *k; int64_t k_sb, k_sh, k_st;
-    const uint16_t *v; int64_t v_sb, v_sh, v_st;
-    const int32_t *block_starts;
-    int n_blocks, block, block_log2;
-    float scale_log2e;
-    uint16_t *out;       // bf16 [B, Hq, Tq, d]
-    float *out_lse;      // [B, Hq, Tq] or null
-};
-
-__device__ inline int pf_slot_to_pos(const AttnPrefillArgs &a, const Problem &pr, int p, int slot,
-                                     int n_sink_eff, int w0)
-{
-    if (slot < n_sink_eff) return slot;
-    slot -= n_sink_eff;
-    const int nb = a.n_blocks << a.block_log2;
-    if (slot < nb) {
-        const int bs = a.block_starts[(int64_t)p * a.n_blocks + (slot >> a.block_log2)];
-        if (bs < 0) return -1;
-        const int pos = bs + (slot & (a.block - 1));
-        return pos < pr.hi ? pos : -1;
-    }
-    const int pos = w0 + (slot - nb);
-    return pos < pr.E ? pos : -1;
-}
 
 template <int QT, int G>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
 __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillArgs a)
@@ -276,22 +240,26 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     if (P == 0) return IHIP_OK;
     KernelTimer timer("attn_prefill", st);
     const dim3 block_dim(64 * a.ge.G), grid(P);
-#define IHIP_PF_LAUNCH(QT, G) hipLaunchKernelGGL((attn_prefill_kernel<QT, G>), grid, block_dim, 0, st, a)
-#define IHIP_PF_BY_G(QT)                                       \
-    switch (a.ge.G) {                                          \
-    case 1: IHIP_PF_LAUNCH(QT, 1); break;                      \
-    case 2: IHIP_PF_LAUNCH(QT, 2); break;                      \
-    case 4: IHIP_PF_LAUNCH(QT, 4); break;                      \
-    default: IHIP_PF_LAUNCH(QT, 8); break;                     \
+#define IHIP_PF_BY_G(KERNEL, QT)                                                                   \
+    switch (a.ge.G) {                                                                              \
+    case 1: hipLaunchKernelGGL((KERNEL<QT, 1>), grid, block_dim, 0, st, a); break;                 \
+    case 2: hipLaunchKernelGGL((KERNEL<QT, 2>), grid, block_dim, 0, st, a); break;                 \
+    case 4: hipLaunchKernelGGL((KERNEL<QT, 4>), grid, block_dim, 0, st, a); break;                 \
+    default: hipLaunchKernelGGL((KERNEL<QT, 8>), grid, block_dim, 0, st, a); break;                \
+    }
+    // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
+    const bool fits32 = s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= kPf32MaxSlots;
+    if (fits32) {
+        launch_attn_prefill32(a, P, st);
+        return check_launch("sparse_attn_prefill");
     }
     switch (s.b_q) {
-    case 16: IHIP_PF_BY_G(1); break;
-    case 32: IHIP_PF_BY_G(2); break;
-    case 64: IHIP_PF_BY_G(4); break;
+    case 16: IHIP_PF_BY_G(attn_prefill_kernel, 1); break;
+    case 32: IHIP_PF_BY_G(attn_prefill_kernel, 2); break;
+    case 64: IHIP_PF_BY_G(attn_prefill_kernel, 4); break;
     default: return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_prefill: b_q = %d not in {16, 32, 64}", s.b_q);
     }
 #undef IHIP_PF_BY_G
-#undef IHIP_PF_LAUNCH
     return check_launch("sparse_attn_prefill");
 }
 
