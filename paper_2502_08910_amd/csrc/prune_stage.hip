@@ -161,13 +161,18 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int MT, int NT>
-__global__ __launch_bounds__(512) void prune_prefill_kernel(const PruneArgs a, const int iters)
+template <int MT, int NT, int G>
+__global__ __launch_bounds__(64 * G) void prune_prefill_kernel(const PruneArgs a, const int iters)
 {
-    __shared__ float sh_sigma[8][NT * 16];
-    const int p = blockIdx.x;
+    constexpr int kRowStride = kD + 8;               // 272 B: conflict-free 16-byte column reads
+    __shared__ float sh_sigma[G][NT * 16];
+    __shared__ __attribute__((aligned(16))) uint16_t sh_rows[G][NT * 16 * kRowStride];
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id; let the KV head be the fastest
+    // index, so that (with 8 KV heads) one XCD's L2 only ever holds one head's K rows and all
+    // query blocks that share those rows run on that XCD at about the same time.
+    const int p = ((blockIdx.x / a.ge.Hkv / a.ge.Mq) * a.ge.Hkv + blockIdx.x % a.ge.Hkv) * a.ge.Mq +
+                  (blockIdx.x / a.ge.Hkv) % a.ge.Mq;
     const Problem pr = problem_of(a.ge, p);
-    const int G = a.ge.G;
     const int lane = threadIdx.x & 63, hh = threadIdx.x >> 6;      // wave = query head of the group
     const int n = lane & 15, kq = lane >> 4;
     const int h = pr.g * G + hh;
@@ -182,19 +187,35 @@ __global__ __launch_bounds__(512) void prune_prefill_kernel(const PruneArgs a, c
             for (int ks = 0; ks < 4; ++ks)
                 qa[mt][ks] = *reinterpret_cast<const bf16x8 *>(qb + (int64_t)(mt * 16 + n) * a.q_st + ks * 32 + kq * 8);
     }
-    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh + kq * 8;
+    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh + n * 8;
 
-    // score of candidate rows pos[t] (column n of tile t): max over the block's queries
+    // score of candidate rows pos[t] (column n of tile t): max over the block's queries.
+    // The rows are fetched coalesced (16 lanes x 16 B = one whole row, 4 rows per load) into a
+    // wave-private LDS tile and re-read from there in the B-operand layout (lane = (column n,
+    // 8 dims of group kq)): reading them from global memory in that layout costs four times as
+    // many L1 accesses per row and makes the L1 tag rate the bound.
+    uint16_t *tile = &sh_rows[hh][0];
     auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT]) {
+        constexpr int kLoads = NT * 4;               // 4 rows per load
+        uint4 rows[kLoads];
+#pragma unroll
+        for (int r = 0; r < kLoads; ++r) {
+            // row r*4 + kq of the tile set = candidate (t = r/4, column (r%4)*4 + kq)
+            const int col = (r & 3) * 4 + kq;
+            const int pr_ = __shfl(ok[r >> 2] ? pos[r >> 2] : -1, col, 64);     // lanes 0..15 hold column = lane
+            rows[r] = make_uint4(0, 0, 0, 0);
+            if (pr_ >= 0) rows[r] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pr_ * a.k_st);
+        }
+#pragma unroll
+        for (int r = 0; r < kLoads; ++r)
+            *reinterpret_cast<uint4 *>(&tile[((r >> 2) * 16 + (r & 3) * 4 + kq) * kRowStride + n * 8]) = rows[r];
+        // same wave wrote and reads: only the LDS counter has to drain (the compiler inserts the wait)
         bf16x8 kr[NT][4];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                uint4 z = make_uint4(0, 0, 0, 0);
-                if (ok[t]) z = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos[t] * a.k_st + ks * 32);
-                kr[t][ks] = __builtin_bit_cast(bf16x8, z);
-            }
+            for (int ks = 0; ks < 4; ++ks)
+                kr[t][ks] = *reinterpret_cast<const bf16x8 *>(&tile[(t * 16 + n) * kRowStride + ks * 32 + kq * 8]);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             float best = -INFINITY;
@@ -273,7 +294,12 @@ static void launch_prefill(const PruneArgs &a, int P, hipStream_t st)
     const int per_wg = NT * 16 * iters;
     dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
     KernelTimer timer(stage_name(kNamePrunePrefill, a.parent_starts == nullptr, a.chunk), st);
-    hipLaunchKernelGGL((prune_prefill_kernel<MT, NT>), grid, dim3(64 * a.ge.G), 0, st, a, iters);
+    switch (a.ge.G) {
+    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1>), grid, dim3(64), 0, st, a, iters); break;
+    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2>), grid, dim3(128), 0, st, a, iters); break;
+    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4>), grid, dim3(256), 0, st, a, iters); break;
+    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8>), grid, dim3(512), 0, st, a, iters); break;
+    }
 }
 
 template <int G>

@@ -16,9 +16,13 @@
 //
 // Latency hiding.  The position of every key slot is computed once into LDS
 // (so the steady state has no dependent global loads); K/V rows travel
-// global -> registers -> LDS with two register buffers and two LDS stages:
-// the rows of tile t+3 are requested while tile t is being multiplied, and
-// there is one barrier per tile.
+// global -> registers -> LDS with two register buffers and three LDS stages:
+// the rows of tile t+4 are requested while tile t is being multiplied, and
+// there is one barrier per tile.  Inside a wave the first product of tile t+1
+// is issued before the softmax arithmetic of tile t, so the matrix pipe works
+// while the vector pipe does exponentials.  V^T granules (8 keys = 16 B) are
+// XOR-swizzled by the row's dim group so the transposing stores spread over
+// the LDS banks.
 #include "attn_prefill_args.h"
 
 namespace ihip {
@@ -31,9 +35,10 @@ constexpr int kPfStageV = kD * kPfVStride;
 template <int NQ, int G>   // NQ = b_q / 32 query tiles, G query heads: NQ*G waves
 __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnPrefillArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t sK[2 * kPfStageK];
-    __shared__ __attribute__((aligned(16))) uint16_t sVt[2 * kPfStageV];
-    __shared__ int sPos[kPf32MaxSlots];
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t *sK = smem;                                   // 3 stages
+    uint16_t *sVt = smem + 3 * kPfStageK;                  // 3 stages
+    int *sPos = reinterpret_cast<int *>(smem + 3 * (kPfStageK + kPfStageV));   // one int per key slot
 
     const int p = blockIdx.x;
     const Problem pr = problem_of(a.ge, p);
@@ -103,8 +108,8 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
     };
     auto stash = [&](const RowBuf &buf, int tile) {
         if (tile >= n_tiles) return;
-        uint16_t *dK = sK + (tile & 1) * kPfStageK;
-        uint16_t *dV = sVt + (tile & 1) * kPfStageV;
+        uint16_t *dK = sK + (tile % 3) * kPfStageK;
+        uint16_t *dV = sVt + (tile % 3) * kPfStageV;
 #pragma unroll
         for (int r = 0; r < kPerK; ++r) {
             const int item = tid + r * nthreads;
@@ -119,7 +124,8 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
             // position of key kappa in a V^T row: 16*(kappa/16) + 8*half + j,
             // half = (kappa%8)/4, j = 4*((kappa%16)/8) + kappa%4
             const int k16 = key0 & 15;
-            const int vslot = (key0 & 16) + ((k16 & 7) >> 2) * 8 + (k16 >> 3) * 4 + (k16 & 3);   // even
+            int vslot = (key0 & 16) + ((k16 & 7) >> 2) * 8 + (k16 >> 3) * 4 + (k16 & 3);   // even
+            vslot ^= ((c >> 1) & 3) << 3;                     // granule swizzle by dim group
             const uint32_t v0[4] = {buf.v[r][0].x, buf.v[r][0].y, buf.v[r][0].z, buf.v[r][0].w};
             const uint32_t v1[4] = {buf.v[r][1].x, buf.v[r][1].y, buf.v[r][1].z, buf.v[r][1].w};
 #pragma unroll
@@ -132,13 +138,9 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
         }
     };
 
-    auto compute = [&](int tile) {
-        const uint16_t *cK = sK + (tile & 1) * kPfStageK;
-        const uint16_t *cV = sVt + (tile & 1) * kPfStageV;
-        // a tile needs masking if it has an empty slot or a key at or after the block's first query
-        const int myp = sPos[tile * kPfTile + n];
-        const bool masked = __any(myp < 0 || myp >= qpos0);
-
+    // first product of a tile: S^T = K Q^T for this wave's 32 queries
+    auto scores = [&](int tile) -> f32x16 {
+        const uint16_t *cK = sK + (tile % 3) * kPfStageK;
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -147,7 +149,14 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
             const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(&cK[n * kPfKStride + ks * 16 + half * 8]);
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[ks], s, 0, 0, 0);
         }
-        if (masked) {
+        return s;
+    };
+    // softmax update and second product of a tile
+    auto finish = [&](int tile, f32x16 s) {
+        const uint16_t *cV = sVt + (tile % 3) * kPfStageV;
+        // a tile needs masking if it has an empty slot or a key at or after the block's first query
+        const int myp = sPos[tile * kPfTile + n];
+        if (__any(myp < 0 || myp >= qpos0)) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int kp = sPos[tile * kPfTile + 8 * (r >> 2) + 4 * half + (r & 3)];
@@ -175,31 +184,41 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
             for (int dt = 0; dt < 4; ++dt) o[dt] *= corr;
         }
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < 4; ++dt) {
+            const int row = dt * 32 + n;
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(&cV[(dt * 32 + n) * kPfVStride + kk * 16 + half * 8]);
+                const int g = (kk * 2 + half) ^ ((row >> 4) & 3);     // swizzled 16-byte granule
+                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(&cV[row * kPfVStride + g * 8]);
                 o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kk], o[dt], 0, 0, 0);
             }
+        }
     };
 
     __syncthreads();                        // sPos complete
     fetch(bufA, 0);
     fetch(bufB, 1);
     stash(bufA, 0);
+    stash(bufB, 1);
     fetch(bufA, 2);
-    // invariant at the top of iteration t (even): LDS stage t%2 holds tile t (after the barrier),
-    // bufB holds tile t+1, bufA holds tile t+2
+    fetch(bufB, 3);
+    __syncthreads();
+    f32x16 s_cur = scores(0);
+    // At the top of iteration t: stage t%3 holds tile t, stage (t+1)%3 tile t+1 (visible after the
+    // barrier), the buffer of t's parity holds tile t+2 and the other one tile t+3.
     for (int tile = 0; tile < n_tiles; tile += 2) {
         __syncthreads();
-        compute(tile);
-        stash(bufB, tile + 1);              // into the stage tile-1 was read from: everyone is past it
-        fetch(bufB, tile + 3);
+        f32x16 s_next = s_cur;
+        if (tile + 1 < n_tiles) s_next = scores(tile + 1);
+        finish(tile, s_cur);
+        stash(bufA, tile + 2);              // stage (tile+2)%3 was last read for tile-1: everyone is past it
+        fetch(bufA, tile + 4);
         if (tile + 1 >= n_tiles) break;
         __syncthreads();
-        compute(tile + 1);
-        stash(bufA, tile + 2);
-        fetch(bufA, tile + 4);
+        if (tile + 2 < n_tiles) s_cur = scores(tile + 2);
+        finish(tile + 1, s_next);
+        stash(bufB, tile + 3);
+        fetch(bufB, tile + 5);
     }
 
     float l = l_run;
@@ -223,7 +242,18 @@ void launch_attn_prefill32(const AttnPrefillArgs &a, int P, hipStream_t st)
 {
     const int NQ = a.ge.b_q / 32;
     const dim3 block_dim(64 * NQ * a.ge.G), grid(P);
-#define IHIP_PF32(NQV, GV) hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV>), grid, block_dim, 0, st, a)
+    const int slots = (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile;
+    const size_t lds = 3 * (kPfStageK + kPfStageV) * sizeof(uint16_t) + (size_t)slots * sizeof(int);
+#define IHIP_PF32(NQV, GV)                                                                               \
+    {                                                                                                    \
+        static bool attr_set = false;     /* allow more than 64 KiB of dynamic LDS, once per kernel */   \
+        if (!attr_set) {                                                                                 \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_prefill32_kernel<NQV, GV>),  \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kPf32MaxLds);         \
+            attr_set = true;                                                                             \
+        }                                                                                                \
+        hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV>), grid, block_dim, lds, st, a);              \
+    }
 #define IHIP_PF32_BY_G(NQV)             \
     switch (a.ge.G) {                   \
     case 1: IHIP_PF32(NQV, 1); break;   \
