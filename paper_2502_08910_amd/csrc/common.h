@@ -156,6 +156,17 @@ __device__ inline float dot8(const uint4 &k, const float (&q)[8])
     return s;
 }
 
+// the same with both sides packed bf16: four v_dot2_f32_bf16 (products exact, fp32 sums)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ inline float dot8_bf16(const uint4 &k, const uint4 &q)
+{
+    float s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.x), __builtin_bit_cast(bf16x2_t, q.x), 0.f, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.y), __builtin_bit_cast(bf16x2_t, q.y), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.z), __builtin_bit_cast(bf16x2_t, q.z), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.w), __builtin_bit_cast(bf16x2_t, q.w), s, false);
+    return s;
+}
+
 __device__ inline void unpack8(const uint4 &k, float (&f)[8])
 {
     f[0] = bf16_lo(k.x); f[1] = bf16_hi(k.x);

@@ -72,6 +72,145 @@ __global__ __launch_bounds__(kSelThreads) void select_blocks_kernel(const Select
     for (int i = keep_eff + tid; i < a.keep; i += kSelThreads) out[i] = -1;
 }
 
+// ---------------------------------------------------------------------------
+// Fast path for up to 16 slots per thread.  Scores are bucketed into 2048
+// linear bins between the problem's smallest and largest score (monotone in
+// the key order, so the K-th best lies in one identifiable bin); only the few
+// candidates of that bin are ranked exactly, by (key descending, slot
+// ascending).  One pass over the scores, no contended atomics, ~10 barriers.
+// If the threshold bin holds more candidates than threads (heavy ties), the
+// radix select above finishes the job on the keys already in LDS.
+// ---------------------------------------------------------------------------
+constexpr int kFastItems = 16;
+constexpr int kFastBins = 2048;
+
+template <int NT>
+__global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs a)
+{
+    constexpr int NW = NT / 64;
+    __shared__ uint32_t keys[NT * kFastItems];          // all keys (for the tie fallback and the ranking)
+    __shared__ uint32_t hist[kFastBins];
+    __shared__ uint8_t sel[NT * kFastItems];            // candidate of the threshold bin that is kept
+    __shared__ uint32_t cand[NT];                       // slots of the threshold bin's candidates
+    __shared__ float red_min[NW], red_max[NW];
+    __shared__ uint32_t red_cnt[NW], wave_tot[NW];
+    __shared__ uint32_t sh_bin, sh_above, sh_ncand;
+    __shared__ SelectScratch<NT> scratch;
+
+    const int p = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int n = a.max_chunks;
+    const float *sc = a.scores + (int64_t)p * n;
+    const int per = (n + NT - 1) / NT;                  // <= kFastItems, slots [tid*per, tid*per + per)
+    const int i0 = tid * per;
+
+    float v[kFastItems];
+    float mn = INFINITY, mx = -INFINITY;
+    uint32_t valid = 0;
+#pragma unroll
+    for (int i = 0; i < kFastItems; ++i) {
+        const int idx = i0 + i;
+        v[i] = (i < per && idx < n) ? sc[idx] + 0.0f : -INFINITY;      // -0.0 -> +0.0
+        if (i < per && idx < n) keys[idx] = order_key(v[i]);
+        if (v[i] > -INFINITY) { mn = fminf(mn, v[i]); mx = fmaxf(mx, v[i]); ++valid; }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, d, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+        valid += __shfl_xor(valid, d, 64);
+    }
+    if (lane == 0) { red_min[wv] = mn; red_max[wv] = mx; red_cnt[wv] = valid; }
+    for (int i = tid; i < kFastBins; i += NT) hist[i] = 0;
+    for (int i = tid; i < NT * kFastItems / 4; i += NT) reinterpret_cast<uint32_t *>(sel)[i] = 0;
+    if (tid == 0) sh_ncand = 0;
+    __syncthreads();
+    uint32_t n_valid = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { mn = fminf(mn, red_min[w]); mx = fmaxf(mx, red_max[w]); n_valid += red_cnt[w]; }
+    const int keep_eff = min((int)n_valid, a.keep);
+    int32_t *out = a.out_starts + (int64_t)p * a.keep;
+
+    if (keep_eff > 0) {
+        const float scale = mx > mn ? (float)(kFastBins - 1) / (mx - mn) : 0.f;
+        int bin[kFastItems];
+#pragma unroll
+        for (int i = 0; i < kFastItems; ++i) {
+            bin[i] = -1;
+            if (v[i] > -INFINITY) {
+                bin[i] = min(kFastBins - 1, (int)((v[i] - mn) * scale));
+                atomicAdd(&hist[bin[i]], 1u);
+            }
+        }
+        __syncthreads();
+        // suffix sums over the bins: thread t owns bins [t*bp, t*bp + bp), highest bins = lowest threads
+        constexpr int bp = kFastBins / NT > 0 ? kFastBins / NT : 1;
+        const bool owns = tid * bp < kFastBins;
+        uint32_t mine = 0;
+        if (owns)
+#pragma unroll
+            for (int j = 0; j < bp; ++j) mine += hist[kFastBins - 1 - (tid * bp + j)];
+        uint32_t incl = wave_incl_scan_u32(mine, lane);
+        if (lane == 63) wave_tot[wv] = incl;
+        __syncthreads();
+        for (int w = 0; w < wv; ++w) incl += wave_tot[w];
+        // the K-th best lies in the first bin (from the top) where the running count reaches keep_eff
+        if (owns && incl >= (uint32_t)keep_eff && incl - mine < (uint32_t)keep_eff) {
+            uint32_t run = incl - mine;
+            for (int j = 0; j < bp; ++j) {
+                const int b = kFastBins - 1 - (tid * bp + j);
+                if (run + hist[b] >= (uint32_t)keep_eff) { sh_bin = b; sh_above = run; break; }
+                run += hist[b];
+            }
+        }
+        __syncthreads();
+        const int tb = sh_bin;
+        const uint32_t need = keep_eff - sh_above;         // kept from the threshold bin
+        const uint32_t n_cand = hist[tb];
+        if (n_cand <= (uint32_t)NT) {
+            // list the candidates, then rank each exactly among them
+#pragma unroll
+            for (int i = 0; i < kFastItems; ++i)
+                if (bin[i] == tb) cand[atomicAdd(&sh_ncand, 1u)] = i0 + i;
+            __syncthreads();
+            if ((uint32_t)tid < n_cand) {
+                const uint32_t me = cand[tid], mk = keys[me];
+                uint32_t rank = 0;
+                for (uint32_t j = 0; j < n_cand; ++j) {
+                    const uint32_t o = cand[j], ok = keys[o];
+                    rank += (ok > mk) || (ok == mk && o < me);
+                }
+                if (rank < need) sel[me] = 1;
+            }
+            __syncthreads();
+            // ordered compaction
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int i = 0; i < kFastItems; ++i) cnt += bin[i] > tb || (bin[i] == tb && sel[i0 + i]);
+            uint32_t cincl = wave_incl_scan_u32(cnt, lane);
+            if (lane == 63) red_cnt[wv] = cincl;
+            __syncthreads();
+            uint32_t pos = cincl - cnt;
+            for (int w = 0; w < wv; ++w) pos += red_cnt[w];
+            const Problem pr = problem_of(a.ge, p);
+#pragma unroll
+            for (int i = 0; i < kFastItems; ++i)
+                if (bin[i] > tb || (bin[i] == tb && sel[i0 + i]))
+                    out[pos++] = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i0 + i);
+        } else {
+            // heavy ties: exact radix select over the keys in LDS
+            const Problem pr = problem_of(a.ge, p);
+            block_select_largest<NT>(
+                n, keep_eff, [&](int i) -> uint32_t { return keys[i]; },
+                [&](uint32_t rank, int i) {
+                    out[rank] = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i);
+                },
+                scratch);
+        }
+    }
+    for (int i = keep_eff + tid; i < a.keep; i += NT) out[i] = -1;
+}
+
 int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_chunks,
                              const int32_t *parent_starts, int n_parent, int parent_chunk, int chunk,
                              int keep, int32_t *out_starts, hipStream_t st)
@@ -89,7 +228,12 @@ int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_c
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (P == 0 || keep == 0) return IHIP_OK;
     KernelTimer timer(stage_name(kNameSelect, parent_starts == nullptr, chunk), st);
-    hipLaunchKernelGGL(select_blocks_kernel, dim3(P), dim3(kSelThreads), 0, st, a);
+    if (max_chunks <= 256 * kFastItems)
+        hipLaunchKernelGGL(select_blocks_fast_kernel<256>, dim3(P), dim3(256), 0, st, a);
+    else if (max_chunks <= 1024 * kFastItems)
+        hipLaunchKernelGGL(select_blocks_fast_kernel<1024>, dim3(P), dim3(1024), 0, st, a);
+    else
+        hipLaunchKernelGGL(select_blocks_kernel, dim3(P), dim3(kSelThreads), 0, st, a);
     return check_launch("select_blocks");
 }
 

@@ -83,15 +83,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
     const int n_sink_eff = min(a.ge.n_sink, pr.E);
     const int w0 = max(pr.hi, a.ge.n_sink);
 
-    float qf[G][8];
+    // this lane's 8 dims of the G query vectors, kept packed (bf16 pairs) for the dot2 instruction
+    uint4 qp[G];
     {
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)(pr.g * G) * a.q_sh;
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-            unpack8(load_row16(qb, h * a.q_sh, l16), qf[h]);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) qf[h][i] *= a.scale_log2e;
-        }
+        for (int h = 0; h < G; ++h) qp[h] = load_row16(qb, h * a.q_sh, l16);
     }
     const typename KvSource<CACHED>::type ksrc = KvSource<CACHED>::k(a, pr);
     const typename KvSource<CACHED>::type vsrc = KvSource<CACHED>::v(a, pr);
@@ -107,13 +104,19 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
     constexpr int UNR = 4;
     const int s0 = split * a.slots_per_split;
     const int s1 = s0 + a.slots_per_split;
+    // key position of every slot of this split, one per thread, so that the main loop has no
+    // dependent global loads (block start -> row address)
+    __shared__ int sh_pos[kAttnThreads];
+    sh_pos[threadIdx.x] = (int)threadIdx.x < a.slots_per_split
+                              ? slot_to_pos(a, pr, p, s0 + threadIdx.x, n_sink_eff, w0) : -1;
+    __syncthreads();
     for (int base = s0 + grp; base < s1; base += kAttnGroups * UNR) {
         uint4 kr[UNR], vr[UNR];
         bool ok[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int slot = base + u * kAttnGroups;
-            const int pos = slot < s1 ? slot_to_pos(a, pr, p, slot, n_sink_eff, w0) : -1;
+            const int pos = slot < s1 ? sh_pos[slot - s0] : -1;
             ok[u] = pos >= 0;
             kr[u] = make_uint4(0, 0, 0, 0);
             vr[u] = make_uint4(0, 0, 0, 0);
@@ -122,21 +125,39 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
                 vr[u] = *reinterpret_cast<const uint4 *>(vsrc.row(pos, false) + l16 * 8);   // K did the bookkeeping
             }
         }
+        // scores of the UNR tokens for all heads (log2 units), then one running-max update per batch
+        float sc[UNR][G];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int h = 0; h < G; ++h)
+                sc[u][h] = ok[u] ? row16_sum(dot8_bf16(kr[u], qp[h])) * a.scale_log2e : kNegBig;
+        float pw[UNR][G], corr[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float mn = m[h];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) mn = fmaxf(mn, sc[u][h]);
+            corr[h] = __builtin_amdgcn_exp2f(m[h] - mn);
+            m[h] = mn;
+            float ps = 0.f;
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                pw[u][h] = ok[u] ? __builtin_amdgcn_exp2f(sc[u][h] - mn) : 0.f;
+                ps += pw[u][h];
+            }
+            l[h] = l[h] * corr[h] + ps;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[h][i] *= corr[h];
+        }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             float vf[8];
             unpack8(vr[u], vf);
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const float s = row16_sum(dot8(kr[u], qf[h]));      // log2-scaled score
-                const float mn = ok[u] ? fmaxf(m[h], s) : m[h];
-                const float corr = exp2f(m[h] - mn);
-                const float pw = ok[u] ? exp2f(s - mn) : 0.f;
-                m[h] = mn;
-                l[h] = l[h] * corr + pw;
+            for (int h = 0; h < G; ++h)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[h][i] = fmaf(pw, vf[i], acc[h][i] * corr);
-            }
+                for (int i = 0; i < 8; ++i) acc[h][i] = fmaf(pw[u][h], vf[i], acc[h][i]);
         }
     }
 
@@ -148,7 +169,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
             const float mo = __shfl_xor(m[h], d, 64);
             const float lo = __shfl_xor(l[h], d, 64);
             const float mn = fmaxf(m[h], mo);
-            const float wa = exp2f(m[h] - mn), wb = exp2f(mo - mn);
+            const float wa = __builtin_amdgcn_exp2f(m[h] - mn), wb = __builtin_amdgcn_exp2f(mo - mn);
             l[h] = l[h] * wa + lo * wb;
             m[h] = mn;
 #pragma unroll
@@ -184,7 +205,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
         float L = 0.f, A = 0.f;
 #pragma unroll
         for (int w2 = 0; w2 < NW; ++w2) {
-            const float w = exp2f(sh_m[w2][h] - M);
+            const float w = __builtin_amdgcn_exp2f(sh_m[w2][h] - M);
             L = fmaf(w, sh_l[w2][h], L);
             A = fmaf(w, sh_acc[w2][h][c], A);
         }
@@ -204,13 +225,25 @@ __global__ __launch_bounds__(kD) void attn_decode_merge_kernel(const AttnDecodeA
     const int c = threadIdx.x;
     const Problem pr = problem_of(a.ge, p);
     const int64_t pbase = (int64_t)p * a.n_splits * G;
+    const float2 *ml = reinterpret_cast<const float2 *>(a.part_ml);
+    // running maximum over the splits: strided over the threads, then reduced
+    __shared__ float sh_max[kD / 64];
     float M = kNegBig;
-    for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, a.part_ml[(pbase + (int64_t)s * G + h) * 2]);
+    for (int s = c; s < a.n_splits; s += kD) M = fmaxf(M, ml[pbase + (int64_t)s * G + h].x);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d, 64));
+    if ((c & 63) == 0) sh_max[c >> 6] = M;
+    __syncthreads();
+    M = fmaxf(sh_max[0], sh_max[1]);
+    // every thread walks all splits for its own dim; the loads of a step do not depend on the
+    // previous one, so unrolling keeps several in flight
     float L = 0.f, A = 0.f;
+#pragma unroll 8
     for (int s = 0; s < a.n_splits; ++s) {
         const int64_t r = pbase + (int64_t)s * G + h;
-        const float w = exp2f(a.part_ml[r * 2] - M);
-        L = fmaf(w, a.part_ml[r * 2 + 1], L);
+        const float2 x = ml[r];
+        const float w = __builtin_amdgcn_exp2f(x.x - M);
+        L = fmaf(w, x.y, L);
         A = fmaf(w, a.part_acc[r * kD + c], A);
     }
     const int hq = pr.g * G + h;
@@ -223,7 +256,7 @@ static int decode_splits(const ihip_shape &s, int n_blocks, int block, int *slot
 {
     const int total = s.n_sink + n_blocks * block + s.n_stream;
     // 16 tokens per step and 4 steps per unrolled iteration: keep splits a multiple of 64 slots
-    const int per = 256;
+    const int per = kAttnThreads;          // one slot position per thread in the kernel's prologue
     *slots_per_split = per;
     return (total + per - 1) / per;
 }
