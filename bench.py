@@ -42,8 +42,8 @@ N_QUERY_SETS = 32
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see
 # profiles/.  Absent = not measured for that workload / kernel.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 781,266 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 1,220 KiB x 1.0 per launch
-    ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781265.9 * 2.0 + 1220.0) * 1024.0,
+    # FETCH_SIZE 781,289 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 1,220 KiB x 1.0 per launch
+    ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781288.9 * 2.0 + 1219.6) * 1024.0,
 }
 
 
@@ -62,17 +62,25 @@ def parse():
     return ap.parse_args()
 
 
+def progress(msg):
+    """One line per finished phase on stderr (a long profiled run is not silent)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def timed_passes(step, steps, warmup, ihip, torch, profile):
     """W warm-up steps, K timed steps between synchronisations, then (optionally)
     the same K steps again with HIP events around every kernel launch."""
+    progress("inputs ready")
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
+    progress("warm-up done")
     t0 = time.perf_counter()
     for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     us = (time.perf_counter() - t0) / steps * 1e6
+    progress(f"{steps} timed steps done")
     kernels = {}
     if profile:
         ihip.profile_enable(True)

@@ -106,11 +106,13 @@ def small_int_bf16(seed, tensor_id, full_shape, device="cpu", sl=None) -> torch.
     return ((h >> 8) % 5 - 2).to(torch.float32).to(torch.bfloat16)
 
 
-def fill_(out: torch.Tensor, seed, tensor_id, kind="normal", t_step=1 << 16) -> torch.Tensor:
+def fill_(out: torch.Tensor, seed, tensor_id, kind="normal", t_step=None) -> torch.Tensor:
     """Fill a (possibly huge, possibly strided) [B,H,T,d] tensor in place, a
     bounded slab of tokens at a time, so temporaries stay small."""
     B, H, T, d = out.shape
     fn = normal_bf16 if kind == "normal" else small_int_bf16
+    if t_step is None:              # ~0.3 G elements per slab on a GPU (few launches), 8 M on the CPU
+        t_step = max(1, ((1 << 28) if out.is_cuda else (1 << 23)) // (H * d))
     for b in range(B):
         for t0 in range(0, T, t_step):
             t1 = min(T, t0 + t_step)
