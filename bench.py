@@ -56,6 +56,10 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--refresh", default=None,
+                    help="decode only: comma-separated mask refresh intervals per stage (e.g. 16,8,4,2); "
+                         "stage i is recomputed only at steps that are multiples of its interval and the "
+                         "cached masks are reused otherwise (the reported value is then the amortised time)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 device copies of 1 GiB (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -147,8 +151,18 @@ def bench_decode(args, w, torch, ihip, configs):
     ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
     out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
 
-    def step(i):
-        L.decode_layer(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ws=ws, out=out)
+    refresh = None
+    if args.refresh:
+        refresh = [int(x) for x in args.refresh.split(",")]
+        assert len(refresh) == len(chunks), "one refresh interval per stage"
+        state = L.mask_state(keeps)
+
+        def step(i):
+            L.decode_layer_masked(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ihip.first_stage_due(i, refresh),
+                                  state, ws=ws, out=out)
+    else:
+        def step(i):
+            L.decode_layer(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ws=ws, out=out)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 
@@ -163,7 +177,7 @@ def bench_decode(args, w, torch, ihip, configs):
     P = w.B * w.Hkv
     row_bytes = w.d * 2
     roofline = whole = None
-    if sample is not None:
+    if sample is not None and refresh is None:
         alg = {}
         slots = [L.stage1_slots(chunks[0])] + [keeps[i - 1] * (chunks[i - 1] // chunks[i])
                                                  for i in range(1, len(chunks))]
@@ -186,11 +200,12 @@ def bench_decode(args, w, torch, ihip, configs):
                         "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                         "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
     return {
-        "metric": "sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer",
+        "metric": ("sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer")
+        + ("_amortised_mask_cache" if refresh else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
-                   "n_stream": w.n_stream, "query_sets": N_QUERY_SETS},
+                   "n_stream": w.n_stream, "query_sets": N_QUERY_SETS, "mask_refresh": refresh},
         "roofline": roofline, "cpu_baseline": cpu, "whole_path": whole, "kernels": kernels, "setup_s": t_setup,
     }
 

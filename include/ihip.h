@@ -165,6 +165,26 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Decode layer with per-stage mask caching (Sec. 4 "Sparse Attention Mask
+ * Caching"; Alg. 4: a stage is re-run only every n_refresh steps, otherwise
+ * its cached index list is reused).  stage_starts is device int32, owned and
+ * kept by the caller between the decode steps of one layer: every stage's
+ * kept chunk starts, [P, keeps[0]] then [P, keeps[1]] ... back to back
+ * (ihip_mask_state_elems elements).  Stages first_stage .. n_stages-1 are
+ * recomputed with the current q and stored; stages before first_stage are
+ * taken as cached (first_stage = 0 recomputes everything, = n_stages only
+ * runs the attention over the cached final blocks).  The window and the
+ * cut of blocks at the end of the middle range always follow the current
+ * seq_lens.  Which stage is due at which step (c mod n_refresh == 0) is the
+ * caller's policy.  Scratch as for IHIP_OP_DECODE_LAYER.
+ */
+size_t  ihip_mask_state_elems(const ihip_shape *shape, int32_t n_stages, const int32_t *keeps);
+int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 int32_t first_stage, int32_t *stage_starts, float sm_scale, void *out,
+                                 float *out_lse, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * One chunked-prefill layer call: ihip_prune_all followed by
  * ihip_sparse_attn_prefill (Alg. 1 per query block, then block-sparse
  * attention).  out / out_lse as in ihip_sparse_attn_prefill; out_block_starts

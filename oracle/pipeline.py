@@ -149,6 +149,31 @@ class Oracle:
             pr.stages.append(self.prune_stage(b, g, m, starts, lens, l_c, keep, exhaustive))
         return pr
 
+    # -- Alg. 4: cached masks ------------------------------------------------
+    def prune_from(self, b, g, m, stages, first_stage, cached_kept):
+        """Mask caching (Sec. 4 "Sparse Attention Mask Caching", Alg. 4): stages
+        first_stage.. are re-run with the current queries, the earlier ones keep
+        the index lists cached from an earlier step.  cached_kept: per stage, the
+        kept chunk starts (int64 arrays) of that earlier step.  Returns the per
+        stage kept starts after this step and the final blocks (starts, lens).
+        Lengths always follow the current end of the middle range."""
+        lo, hi, E = self.ranges(b, m)
+        kept = [np.asarray(x, np.int64) for x in cached_kept]
+        if hi <= lo:
+            return [np.zeros(0, np.int64) for _ in stages], np.zeros(0, np.int64), np.zeros(0, np.int32)
+        for i, (l_c, keep) in enumerate(stages):
+            if i < first_stage:
+                continue
+            if i == 0:
+                starts, lens = stage1_chunks(lo, hi, l_c)
+            else:
+                ps = kept[i - 1]
+                plens = np.minimum(stages[i - 1][0], hi - ps).astype(np.int32)
+                starts, lens = child_chunks(ps, plens, l_c)
+            kept[i] = self.prune_stage(b, g, m, starts, lens, l_c, keep).kept_starts
+        bs = kept[-1]
+        return kept, bs, np.minimum(stages[-1][0], hi - bs).astype(np.int32)
+
     # -- block-sparse attention --------------------------------------------
     def attend(self, b, g, m, block_starts, block_lens, scale=None):
         """fp64 output [G, b_q, d] and log-sum-exp [G, b_q] of the block's

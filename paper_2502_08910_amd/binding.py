@@ -49,6 +49,9 @@ EXPORTS = {
     "ihip_prune_all": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, c_i32, vp, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
                                   vp, vp, vp, vp, c_sz, vp]),
+    "ihip_mask_state_elems": (c_sz, [ctypes.POINTER(Shape), c_i32, vp]),
+    "ihip_decode_layer_masked": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_i32, vp,
+                                         c_f, vp, vp, vp, c_sz, vp]),
     "ihip_prefill_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
                                    vp, vp, vp, vp, c_sz, vp]),
     "ihip_cache_device_bytes": (c_sz, [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32]),
@@ -234,6 +237,25 @@ class Layer:
                                        ws.numel(), _stream()))
         return out
 
+    def mask_state(self, keeps) -> torch.Tensor:
+        """Device buffer for every stage's cached kept starts (ihip_decode_layer_masked)."""
+        n = lib().ihip_mask_state_elems(ctypes.byref(self.shape), len(keeps), _i32(keeps))
+        return torch.full((n,), -1, dtype=torch.int32, device=self.device)
+
+    def decode_layer_masked(self, q, k, v, chunk_sizes, keeps, first_stage, stage_starts, sm_scale=None,
+                            ws=None, out=None, lse=None):
+        """Decode layer that recomputes stages first_stage.. and reuses the cached earlier ones."""
+        sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
+        if out is None:
+            out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
+        if ws is None:
+            ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+        _check(lib().ihip_decode_layer_masked(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                              _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                              first_stage, _ptr(stage_starts), sm_scale, _ptr(out), _ptr(lse),
+                                              _ptr(ws), ws.numel(), _stream()))
+        return out
+
     def prefill_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
                       out_blocks=None, lse=None):
         """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d]."""
@@ -247,6 +269,16 @@ class Layer:
                                         sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),
                                         ws.numel(), _stream()))
         return out
+
+
+def first_stage_due(step: int, refresh: Sequence[int]) -> int:
+    """Alg. 4's refresh rule: the first stage i whose counter is due (step mod refresh[i] == 0);
+    len(refresh) if none is.  With nested intervals (each a multiple of the next) every later
+    stage is due as well."""
+    for i, r in enumerate(refresh):
+        if step % r == 0:
+            return i
+    return len(refresh)
 
 
 class HostKVCache:

@@ -186,27 +186,37 @@ static PlanLayout plan_layout(const ihip_shape &s, int n_stages, const int32_t *
     return L;
 }
 
+// Stages first_stage..n_stages-1 of Alg. 1.  stage_out[i] receives stage i's kept starts; for
+// first_stage > 0 stage_out[first_stage-1] must already hold the previous stage's kept starts
+// (a cached mask, Alg. 4).
+static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
+                                 const int32_t *chunks, const int32_t *keeps, int first_stage,
+                                 int32_t *const *stage_out, float *scores, const BankView *bank, hipStream_t st)
+{
+    for (int i = first_stage; i < n_stages; ++i) {
+        const int32_t *parents = i == 0 ? nullptr : stage_out[i - 1];
+        const int n_parent = i == 0 ? 0 : keeps[i - 1];
+        const int parent_chunk = i == 0 ? 0 : chunks[i - 1];
+        const int slots = i == 0 ? stage1_slots(s, chunks[0]) : n_parent * (parent_chunk / chunks[i]);
+        int32_t rc = launch_prune_stage(s, q, k, parents, n_parent, parent_chunk, chunks[i], slots, scores,
+                                        nullptr, bank, st);
+        if (rc != IHIP_OK) return rc;
+        rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i],
+                                  stage_out[i], st);
+        if (rc != IHIP_OK) return rc;
+    }
+    return IHIP_OK;
+}
+
 static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                               const int32_t *chunks, const int32_t *keeps, int32_t *out_block_starts,
                               char *ws, const BankView *bank, hipStream_t st)
 {
     const PlanLayout L = plan_layout(s, n_stages, chunks, keeps);
-    float *scores = (float *)(ws + L.scores_off);
-    const int32_t *parents = nullptr;
-    int n_parent = 0, parent_chunk = 0;
-    for (int i = 0; i < n_stages; ++i) {
-        const int slots = i == 0 ? stage1_slots(s, chunks[0]) : n_parent * (parent_chunk / chunks[i]);
-        int32_t *kept = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
-        int32_t rc = launch_prune_stage(s, q, k, parents, n_parent, parent_chunk, chunks[i], slots, scores,
-                                        nullptr, bank, st);
-        if (rc != IHIP_OK) return rc;
-        rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i], kept, st);
-        if (rc != IHIP_OK) return rc;
-        parents = kept;
-        n_parent = keeps[i];
-        parent_chunk = chunks[i];
-    }
-    return IHIP_OK;
+    int32_t *stage_out[8];
+    for (int i = 0; i < n_stages; ++i)
+        stage_out[i] = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
+    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, st);
 }
 
 }  // namespace ihip
@@ -375,6 +385,48 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
                     who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
     return decode_layer_impl(who, shape, q, hk, hv, cache, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
                              out_block_starts, ws, ws_bytes, stream);
+}
+
+size_t ihip_mask_state_elems(const ihip_shape *shape, int32_t n_stages, const int32_t *keeps)
+{
+    if (check_shape(shape, "ihip_mask_state_elems") != IHIP_OK || n_stages < 1 || n_stages > 8 || !keeps) return 0;
+    const size_t P = (size_t)shape->B * shape->Hkv * (shape->Tq / shape->b_q);
+    size_t n = 0;
+    for (int i = 0; i < n_stages; ++i) n += P * (size_t)keeps[i];
+    return n;
+}
+
+int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 int32_t first_stage, int32_t *stage_starts, float sm_scale, void *out,
+                                 float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_decode_layer_masked";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
+    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
+    if (first_stage < 0 || first_stage > n_stages)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d not in 0..%d", who, first_stage, n_stages);
+    if (!out || !stage_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: out / stage_starts is NULL", who);
+    const int last = n_stages - 1;
+    const PlanLayout L = plan_layout(*shape, n_stages, chunk_sizes, keeps);
+    const size_t attn_bytes = attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
+    const size_t need = L.scores_bytes + attn_bytes;
+    if (!ws || ws_bytes < need)
+        return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
+    const size_t P = (size_t)shape->B * shape->Hkv;
+    int32_t *stage_out[8];
+    size_t off = 0;
+    for (int i = 0; i < n_stages; ++i) { stage_out[i] = stage_starts + off; off += P * (size_t)keeps[i]; }
+    rc = prune_stages_impl(*shape, q, k, n_stages, chunk_sizes, keeps, first_stage, stage_out, (float *)ws, nullptr,
+                           (hipStream_t)stream);
+    if (rc != IHIP_OK) return rc;
+    return launch_attn_decode(*shape, q, k, v, stage_out[last], keeps[last], chunk_sizes[last], sm_scale, out,
+                              out_lse, (char *)ws + L.scores_bytes, nullptr, (hipStream_t)stream);
 }
 
 int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,

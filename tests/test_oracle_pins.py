@@ -424,3 +424,32 @@ def test_child_chunks_equal_list_chunking():
         assert s.tolist() == [p[0] for p in pieces]
         assert n.tolist() == [len(p) for p in pieces]
         assert all((np.diff(p) == 1).all() for p in pieces)
+
+
+# --------------------------------------------------------------------------
+# 9. mask caching (Alg. 4): identities that hold whatever the data
+# --------------------------------------------------------------------------
+def test_mask_caching_identities():
+    w = configs.shrink(configs.CFG1, T=2048, n_stream=256, stages=((64, 8), (16, 8), (4, 16)))
+    q, k, v, sl, _ = configs.make_inputs(w, 2)
+    o = Oracle(q, k, v, sl, 1, w.n_sink, w.n_stream)
+    full = o.prune(0, 1, 0, w.stages)
+    want = [st.kept_starts.tolist() for st in full.stages]
+    none = [np.zeros(0, np.int64)] * 3
+    # refreshing every stage == no caching
+    kept, bs, bl = o.prune_from(0, 1, 0, w.stages, 0, none)
+    assert [x.tolist() for x in kept] == want
+    assert bs.tolist() == full.block_starts.tolist() and bl.tolist() == full.block_lens.tolist()
+    # same queries, same length: reusing any prefix of cached stages changes nothing
+    for first in (1, 2, 3):
+        kept2, bs2, bl2 = o.prune_from(0, 1, 0, w.stages, first, kept)
+        assert [x.tolist() for x in kept2] == want and bs2.tolist() == bs.tolist()
+    # different queries: cached stages stay, later stages follow the new queries inside them
+    q2 = gen.normal_bf16(9, 1, tuple(q.shape))
+    o2 = Oracle(q2, k, v, sl, 1, w.n_sink, w.n_stream)
+    kept3, bs3, _ = o2.prune_from(0, 1, 0, w.stages, 1, kept)
+    assert kept3[0].tolist() == want[0]
+    parents = set(kept3[0].tolist())
+    assert all((s - w.n_sink) // 64 * 64 + w.n_sink in parents for s in kept3[1].tolist())
+    assert all(any(p <= s < p + 16 for p in kept3[1].tolist()) for s in bs3.tolist())
+    assert kept3[1].tolist() != want[1]      # (new queries do pick different chunks)
