@@ -102,17 +102,21 @@ def dominant(kernels):
 
 
 # ---------------------------------------------------------------------------
-def decode_oracle_sample(w, qs, k, v, seq_lens, budget_s):
+def decode_oracle_sample(w, qs, kvs, seq_lens, budget_s):
     """Times the CPU oracle on sequence 0 (all its KV heads), one query set
-    after another until the budget is used; also returns the mean number of
-    distinct K rows each stage scores per problem and the attended tokens."""
+    (with its layer's K/V) after another until the budget is used; also returns
+    the mean number of distinct K rows each stage scores per problem and the
+    attended tokens."""
     import oracle
     oracle.build(force=False)
-    k0 = k[0:1].cpu()
-    v0 = v[0:1].cpu()
+    host = {}
     rows = [0.0] * len(w.stages)
     tokens, problems, calls, t_used = 0.0, 0, 0, 0.0
-    for q in qs:
+    for i, q in enumerate(qs):
+        layer = i % len(kvs)
+        if layer not in host:
+            host = {layer: (kvs[layer][0][0:1].cpu(), kvs[layer][1][0:1].cpu())}
+        k0, v0 = host[layer]
         o = oracle.Oracle(q[0:1].cpu(), k0, v0, [int(seq_lens[0])], w.b_q, w.n_sink, w.n_stream)
         t0 = time.perf_counter()
         res = o.layer(w.stages)
@@ -137,12 +141,17 @@ def bench_decode(args, w, torch, ihip, configs):
     keeps = [s[1] for s in w.stages]
 
     t0 = time.perf_counter()
-    k, v = configs.make_kv(w, 0, dev)
+    # one layer's K/V when it is far larger than the 256 MB last-level cache; otherwise as many
+    # distinct layers as query sets (32), rotated, so that steps never find their rows cached
+    layer_bytes = 2 * w.B * w.Hkv * w.T * w.d * 2
+    n_layers = 1 if layer_bytes >= (4 << 30) else N_QUERY_SETS
+    kvs = [configs.make_kv(w, layer, dev) for layer in range(n_layers)]
     qs = []
     for i in range(N_QUERY_SETS):
         q = configs.make_q(w, i, dev)
-        configs.plant_needles(w, k, q, i)
+        configs.plant_needles(w, kvs[i % n_layers][0], q, i)
         qs.append(q)
+    k, v = kvs[0]
     seq_lens = torch.full((w.B,), w.T, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t0
@@ -157,18 +166,21 @@ def bench_decode(args, w, torch, ihip, configs):
         assert len(refresh) == len(chunks), "one refresh interval per stage"
         state = L.mask_state(keeps)
 
+        assert n_layers == 1, "mask caching follows one layer's decode steps"
+
         def step(i):
             L.decode_layer_masked(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ihip.first_stage_due(i, refresh),
                                   state, ws=ws, out=out)
     else:
         def step(i):
-            L.decode_layer(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ws=ws, out=out)
+            kl, vl = kvs[i % n_layers]
+            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 
     cpu = sample = None
     if args.cpu_seconds > 0:
-        sample = decode_oracle_sample(w, qs, k, v, seq_lens.cpu().tolist(), args.cpu_seconds)
+        sample = decode_oracle_sample(w, qs, kvs, seq_lens.cpu().tolist(), args.cpu_seconds)
         per_seq_call = sample["seconds"] / sample["layer_calls_one_sequence"]
         cpu = {"value": per_seq_call * w.B * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
                "sample": f"sequence 0 of {w.B} (its {w.Hkv} KV heads), {sample['layer_calls_one_sequence']} "
@@ -205,7 +217,8 @@ def bench_decode(args, w, torch, ihip, configs):
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
-                   "n_stream": w.n_stream, "query_sets": N_QUERY_SETS, "mask_refresh": refresh},
+                   "n_stream": w.n_stream, "query_sets": N_QUERY_SETS, "distinct_kv_layers": n_layers,
+                   "mask_refresh": refresh},
         "roofline": roofline, "cpu_baseline": cpu, "whole_path": whole, "kernels": kernels, "setup_s": t_setup,
     }
 
@@ -377,7 +390,7 @@ def bench_offload(args, w, torch, ihip, configs):
         hit[bank] = {"block_hits": h, "block_misses": m, "hit_ratio": h / max(1, h + m)}
     cpu = None
     if args.cpu_seconds > 0:
-        sample = decode_oracle_sample(w, qs, hk, hv, [w.T], args.cpu_seconds)
+        sample = decode_oracle_sample(w, qs, [(hk, hv)], [w.T], args.cpu_seconds)
         cpu = {"value": sample["seconds"] / sample["layer_calls_one_sequence"] * 1e6, "unit": "us/layer", "cores": 1,
                "kind": "oracle", "sample": f"{sample['layer_calls_one_sequence']} whole layer calls (all {w.Hkv} KV heads), "
                                            f"{sample['seconds']:.1f} s"}

@@ -232,3 +232,37 @@ def test_select_blocks_alone(ihip, orc, n, keep, ties):
         want = n_sink + ids[:cnt].astype(np.int64) * chunk
         assert np.array_equal(got[p, :cnt], want), p
         assert (got[p, cnt:] == -1).all()
+
+
+def test_decode_layer_under_graph_capture(ihip, orc):
+    """The fused layer call allocates nothing and never synchronises, so it can be captured into a
+    HIP graph; every replay (with eager work in between, new queries written in place) must give
+    the eager result."""
+    w = configs.shrink(configs.CFG1, B=2, T=4096 + 7)
+    chunks = [s[0] for s in w.stages]
+    keeps = [s[1] for s in w.stages]
+    q, k, v, sl, _ = configs.make_inputs(w, 7)
+    qd, kd, vd, sld = dev(q, k, v, sl)
+    L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
+    ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
+    out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device="cuda")
+    blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside capture
+        L.decode_layer(qd, kd, vd, chunks, keeps, ws=ws, out=out, out_blocks=blocks)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        L.decode_layer(qd, kd, vd, chunks, keeps, ws=ws, out=out, out_blocks=blocks)
+    for seed in (11, 12, 13):
+        qn = configs.make_q(w, seed).cuda()
+        ref_blocks = torch.empty_like(blocks)
+        ref = L.decode_layer(qn, kd, vd, chunks, keeps, out_blocks=ref_blocks)     # eager, own buffers
+        qd.copy_(qn)                                    # new input written in place
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(blocks, ref_blocks), seed
+        assert torch.equal(out, ref), seed
