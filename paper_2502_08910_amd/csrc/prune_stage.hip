@@ -8,6 +8,7 @@
 // of a chunk are common to the heads, the rest are G independent loads in
 // flight).  U slots per group are interleaved to put more loads in flight.
 #include "common.h"
+#include <type_traits>
 
 namespace ihip {
 
@@ -161,12 +162,14 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int MT, int NT, int G>
-__global__ __launch_bounds__(64 * G) void prune_prefill_kernel(const PruneArgs a, const int iters)
+template <int MT, int NT, int G, bool WIDE>
+__global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArgs a, const int iters)
 {
-    constexpr int kRowStride = kD + 8;               // 272 B: conflict-free 16-byte column reads
+    static_assert(NT == 2, "the shared first phase assumes two 16-chunk tiles per wave");
+    constexpr int kTile = NT * 16 * kD;              // one tile: 32 rows of 256 bytes, no padding
+    constexpr bool kShare = G >= 2;                  // two tiles are needed for the shared phase
     __shared__ float sh_sigma[G][NT * 16];
-    __shared__ __attribute__((aligned(16))) uint16_t sh_rows[G][NT * 16 * kRowStride];
+    __shared__ __attribute__((aligned(16))) uint16_t sh_rows[G * kTile];
     // Workgroups are dealt to the 8 XCDs round-robin by linear id; let the KV head be the fastest
     // index, so that (with 8 KV heads) one XCD's L2 only ever holds one head's K rows and all
     // query blocks that share those rows run on that XCD at about the same time.
@@ -176,46 +179,60 @@ __global__ __launch_bounds__(64 * G) void prune_prefill_kernel(const PruneArgs a
     const int lane = threadIdx.x & 63, hh = threadIdx.x >> 6;      // wave = query head of the group
     const int n = lane & 15, kq = lane >> 4;
     const int h = pr.g * G + hh;
+    using off_t = typename std::conditional<WIDE, int64_t, uint32_t>::type;   // element offset of a row
+    const off_t k_st = (off_t)a.k_st;
 
-    // A operands: the block's queries, [MT tiles of 16 rows] x [4 steps of 32 dims]
+    // Rows travel from global memory straight into LDS (global_load_lds, 16 bytes per lane: 16
+    // lanes fetch one whole 256-byte row, 4 rows per instruction, landing at base + lane*16) and
+    // are re-read from there in the MFMA operand layout (lane = (row or column n, 8 dims of group
+    // kq)).  Reading them from global memory in that layout costs four times as many L1 accesses
+    // per row and makes the L1 tag rate the bound; staging through registers costs 32 VGPRs and 8
+    // LDS stores per phase.  The LDS destination of a lane is fixed, so the bank swizzle is applied
+    // on the source side: 16-byte slot c of tile row R holds dims 8*(c ^ (R%16)).., which makes the
+    // 16 rows of an operand read hit 16 different bank groups.
+    // load4(base, dst, row): lanes 16*kq..+15 fetch row `row` (their own copy of it, -1 = none;
+    // the lanes are then masked off and the slot keeps stale data) to tile row dst_row0 + kq.
+    auto load4 = [&](const uint16_t *base, off_t stride, uint16_t *dst, int row, int swz) {
+        if (row >= 0)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(base + (off_t)row * stride + ((n ^ swz) << 3)),
+                (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+    auto operand = [&](const uint16_t *tile, int row16, int ks) {
+        return *reinterpret_cast<const bf16x8 *>(&tile[(row16 + n) * kD + (((ks << 2) + kq) ^ n) * 8]);
+    };
+
+    // A operands: the block's queries, [MT tiles of 16 rows] x [4 steps of 32 dims], staged
+    // through this wave's own tile, 32 rows at a time
+    uint16_t *tile = &sh_rows[hh * kTile];
     bf16x8 qa[MT][4];
     {
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(pr.m * a.ge.b_q) * a.q_st;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int m0 = 0; m0 < MT; m0 += 2) {
+            constexpr int kRows = MT >= 2 ? 32 : 16;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                qa[mt][ks] = *reinterpret_cast<const bf16x8 *>(qb + (int64_t)(mt * 16 + n) * a.q_st + ks * 32 + kq * 8);
-    }
-    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh + n * 8;
-
-    // score of candidate rows pos[t] (column n of tile t): max over the block's queries.
-    // The rows are fetched coalesced (16 lanes x 16 B = one whole row, 4 rows per load) into a
-    // wave-private LDS tile and re-read from there in the B-operand layout (lane = (column n,
-    // 8 dims of group kq)): reading them from global memory in that layout costs four times as
-    // many L1 accesses per row and makes the L1 tag rate the bound.
-    uint16_t *tile = &sh_rows[hh][0];
-    auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT]) {
-        constexpr int kLoads = NT * 4;               // 4 rows per load
-        uint4 rows[kLoads];
+            for (int r = 0; r < kRows / 4; ++r)
+                load4(qb, (off_t)a.q_st, tile + r * 4 * kD, m0 * 16 + r * 4 + kq, (r & 3) * 4 + kq);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int r = 0; r < kLoads; ++r) {
-            // row r*4 + kq of the tile set = candidate (t = r/4, column (r%4)*4 + kq)
-            const int col = (r & 3) * 4 + kq;
-            const int pr_ = __shfl(ok[r >> 2] ? pos[r >> 2] : -1, col, 64);     // lanes 0..15 hold column = lane
-            rows[r] = make_uint4(0, 0, 0, 0);
-            if (pr_ >= 0) rows[r] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pr_ * a.k_st);
+            for (int mt = m0; mt < m0 + 2 && mt < MT; ++mt)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) qa[mt][ks] = operand(tile, (mt - m0) * 16, ks);
+            // the reads must have left LDS before the next loads land in the same tile
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
-#pragma unroll
-        for (int r = 0; r < kLoads; ++r)
-            *reinterpret_cast<uint4 *>(&tile[((r >> 2) * 16 + (r & 3) * 4 + kq) * kRowStride + n * 8]) = rows[r];
-        // same wave wrote and reads: only the LDS counter has to drain (the compiler inserts the wait)
+    }
+    if (kShare) __syncthreads();                     // other waves' tiles are written below
+    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+
+    // scores of the 32 rows of a tile (column n of 16-row tile t): max over the block's queries
+    auto mfma_scores = [&](const uint16_t *src, float (&sig)[NT]) {
         bf16x8 kr[NT][4];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                kr[t][ks] = *reinterpret_cast<const bf16x8 *>(&tile[(t * 16 + n) * kRowStride + ks * 32 + kq * 8]);
+            for (int ks = 0; ks < 4; ++ks) kr[t][ks] = operand(src, t * 16, ks);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             float best = -INFINITY;
@@ -231,6 +248,19 @@ __global__ __launch_bounds__(64 * G) void prune_prefill_kernel(const PruneArgs a
             best = fmaxf(best, __shfl_xor(best, 32, 64));
             sig[t] = best;
         }
+    };
+    // score of candidate rows pos[t] of this wave's own searches.  Columns whose search has ended
+    // load nothing and their scores are ignored by the caller.
+    auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT]) {
+#pragma unroll
+        for (int r = 0; r < NT * 4; ++r) {
+            // tile row r*4 + kq = candidate (t = r/4, column (r%4)*4 + kq); lanes 0..15 hold column = lane
+            const int col = (r & 3) * 4 + kq;
+            load4(kb, k_st, tile + r * 4 * kD, __shfl(ok[r >> 2] ? pos[r >> 2] : -1, col, 64), col);
+        }
+        // the loads count on vmcnt; the wave reads its own tile, so no barrier is needed
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        mfma_scores(tile, sig);
     };
 
     for (int it = 0; it < iters; ++it) {
@@ -249,8 +279,35 @@ __global__ __launch_bounds__(64 * G) void prune_prefill_kernel(const PruneArgs a
             off[t] = 0;
             pos[t] = start[t];
         }
-        score(pos, valid, sigma);
-        for (int half = a.chunk >> 1; half >= 1; half >>= 1) {
+        int half = a.chunk >> 1;
+        if (kShare) {
+            // The first key of a chunk and of its right half are the same rows for every head of
+            // the group: the waves fetch them together, once (tile 0: first keys, tile 1: first
+            // keys of the right halves; 16 four-row loads dealt evenly to the G waves), and each
+            // wave scores both tiles against its own queries.
+            constexpr int kPerWave = 16 / G;
+#pragma unroll
+            for (int i = 0; i < kPerWave; ++i) {
+                const int ld = hh * kPerWave + i;                    // wave-uniform
+                const int set = ld >> 3, r = ld & 7;
+                const int col = (r & 3) * 4 + kq;
+                const int st_ = (r >> 2) ? start[1] : start[0], ln_ = (r >> 2) ? len[1] : len[0];
+                const int cand = set == 0 ? st_ : (half >= 1 && half < ln_ ? st_ + half : -1);
+                load4(kb, k_st, &sh_rows[set * kTile + r * 4 * kD], __shfl(cand, col, 64), col);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            mfma_scores(&sh_rows[0], sigma);
+            mfma_scores(&sh_rows[kTile], s);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                if (half >= 1 && half < len[t] && s[t] > sigma[t]) { off[t] = half; sigma[t] = s[t]; }
+            half >>= 1;
+            __syncthreads();                         // tiles 0 and 1 go back to their waves
+        } else {
+            score(pos, valid, sigma);
+        }
+        for (; half >= 1; half >>= 1) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 ok[t] = off[t] + half < len[t];
@@ -286,8 +343,8 @@ __global__ __launch_bounds__(64 * G) void prune_prefill_kernel(const PruneArgs a
     }
 }
 
-template <int MT>
-static void launch_prefill(const PruneArgs &a, int P, hipStream_t st)
+template <int MT, bool WIDE>
+static void launch_prefill_w(const PruneArgs &a, int P, hipStream_t st)
 {
     constexpr int NT = 2;
     const int iters = 2;
@@ -295,11 +352,23 @@ static void launch_prefill(const PruneArgs &a, int P, hipStream_t st)
     dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
     KernelTimer timer(stage_name(kNamePrunePrefill, a.parent_starts == nullptr, a.chunk), st);
     switch (a.ge.G) {
-    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1>), grid, dim3(64), 0, st, a, iters); break;
-    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2>), grid, dim3(128), 0, st, a, iters); break;
-    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4>), grid, dim3(256), 0, st, a, iters); break;
-    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8>), grid, dim3(512), 0, st, a, iters); break;
+    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE>), grid, dim3(64), 0, st, a, iters); break;
+    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE>), grid, dim3(128), 0, st, a, iters); break;
+    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE>), grid, dim3(256), 0, st, a, iters); break;
+    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE>), grid, dim3(512), 0, st, a, iters); break;
     }
+}
+
+// 32-bit element offsets (one VGPR per address, saddr-form loads) when every row of a (batch,
+// head) slab of Q and K lies within 2^31 elements of its base; 64-bit offsets otherwise.
+template <int MT>
+static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, hipStream_t st)
+{
+    const int64_t lim = (int64_t)1 << 31;
+    const bool wide = max_seq_len * a.k_st + kD >= lim || (int64_t)a.ge.b_q * a.q_st + kD >= lim ||
+                      a.k_st < 0 || a.q_st < 0;
+    if (wide) launch_prefill_w<MT, true>(a, P, st);
+    else launch_prefill_w<MT, false>(a, P, st);
 }
 
 template <int G>
@@ -345,9 +414,9 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
         return check_launch("prune_stage (decode)");
     }
     switch (s.b_q) {
-    case 16: launch_prefill<1>(a, P, st); break;
-    case 32: launch_prefill<2>(a, P, st); break;
-    case 64: launch_prefill<4>(a, P, st); break;
+    case 16: launch_prefill<1>(a, P, s.max_seq_len, st); break;
+    case 32: launch_prefill<2>(a, P, s.max_seq_len, st); break;
+    case 64: launch_prefill<4>(a, P, s.max_seq_len, st); break;
     default: return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: b_q = %d not in {1, 16, 32, 64}", s.b_q);
     }
     return check_launch("prune_stage (prefill)");
