@@ -347,7 +347,10 @@ template <int MT, bool WIDE>
 static void launch_prefill_w(const PruneArgs &a, int P, hipStream_t st)
 {
     constexpr int NT = 2;
-    const int iters = 2;
+    // several chunk groups per workgroup amortise the staging of the queries, as long as the
+    // launch still has a few thousand workgroups
+    int iters = 4;
+    while (iters > 1 && (int64_t)P * ((a.max_chunks + NT * 16 * iters - 1) / (NT * 16 * iters)) < 2048) iters >>= 1;
     const int per_wg = NT * 16 * iters;
     dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
     KernelTimer timer(stage_name(kNamePrunePrefill, a.parent_starts == nullptr, a.chunk), st);

@@ -2,47 +2,64 @@
 //
 // One workgroup per problem (sequence, KV head, query block); one wave per
 // (query head of the group, 32 queries of the block), i.e. G * b_q/32 waves
-// (8 for Llama-shaped GQA with b_q = 64), two per SIMD, so that one wave's
-// softmax arithmetic overlaps the other's matrix work.  The gathered K/V tile
-// (32 key slots) is staged in LDS once and shared by all waves.
+// (8 for Llama-shaped GQA with b_q = 64).  The gathered K/V tile (32 key
+// slots) is staged in LDS once and shared by all waves.
 //
-// Same "transposed" scheme as the 16x16 kernel:  S^T = K Q^T,  O^T = V^T P^T.
+// "Transposed" scheme:  S^T = K Q^T,  O^T = V^T P^T.
 // Layouts: A/B lane l holds 8 consecutive k (group half = l/32) of row/column
 // n = l%32; C lane l holds column n, element r = row 8*(r/4) + 4*half + r%4.
 // A lane's 16 S^T values are keys {8*(r/4) + 4*half + r%4}; taken 8 at a time
-// (r < 8: keys 0..15, r >= 8: keys 16..31) they are the B operand of the second
-// product, and V^T is laid out in LDS to match: k slot half*8 + j of step kk is
-// key 16*kk + 8*(j/4) + 4*half + j%4.
+// (r < 8: keys 0..15, r >= 8: keys 16..31) they are, rounded to bf16, the B
+// operand of the second product without any data movement: element i of k-step
+// kk stands for key 16*kk + 8*(i/4) + 4*half + i%4, and the A operand (V^T) is
+// read to match.
 //
-// Latency hiding.  The position of every key slot is computed once into LDS
-// (so the steady state has no dependent global loads); K/V rows travel
-// global -> registers -> LDS with two register buffers and three LDS stages:
-// the rows of tile t+4 are requested while tile t is being multiplied, and
-// there is one barrier per tile.  Inside a wave the first product of tile t+1
-// is issued before the softmax arithmetic of tile t, so the matrix pipe works
-// while the vector pipe does exponentials.  V^T granules (8 keys = 16 B) are
-// XOR-swizzled by the row's dim group so the transposing stores spread over
-// the LDS banks.
+// On this chip vector and matrix instructions of the waves of a SIMD mostly
+// take turns rather than overlap, so the design goal is few vector
+// instructions per tile besides the softmax itself:
+//  * K and V rows go from global memory straight into LDS (global_load_lds,
+//    16 bytes per lane: 16 lanes fetch one 256-byte row, 4 rows per
+//    instruction, landing at base + lane*16): no staging registers, no LDS
+//    stores, and 16 load instructions per tile for the whole workgroup.
+//  * V stays row-major ([key][dim]) in LDS and is transposed by the read
+//    (ds_read_b64_tr_b16): within 16 lanes, lane i supplies the address of 4
+//    elements and lane L receives element L%4 of the addresses of lanes
+//    L/4 + 4j, j = 0..3.  With lane i pointing at key (i/4), dims 4*(i%4)..+3,
+//    lane L gets dim L of four keys.
+//  * The LDS destination of a direct load is fixed, so bank swizzles are
+//    applied on the source side: 16-byte chunk c of a K row sits in slot
+//    c ^ (key%16) (conflict-free 16-byte column reads), of a V row in slot
+//    c ^ 4*(key%4) (the four keys of a transposing read hit different banks).
+//  * The position of every key slot is computed once into LDS, so the steady
+//    state has no dependent global loads.  Empty slots fetch row 0 (finite
+//    data) and are masked in the scores.
+// Four LDS stages: the rows of tile t+3 are requested at the start of period
+// t, tile t+2 must have landed at the barrier that ends it.  K(u) is read in
+// period u-1 (and before the loop for u = 0), V(u) in period u, so the stage of
+// tile u-1 is free when period t = u-3... begins.
 #include "attn_prefill_args.h"
 
 namespace ihip {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kPfStageK = kPfTile * kPfKStride;    // elements per LDS stage
-constexpr int kPfStageV = kD * kPfVStride;
+constexpr int kPfStages = 4;
+constexpr int kPfTileEl = kPfTile * kD;            // elements of one K (or V) tile: 32 rows of 256 bytes
+constexpr int kPfStageEl = 2 * kPfTileEl;          // K tile, then V tile
+constexpr float kPfSlack = 8.0f;                   // log2 units of head-room before the softmax reference moves
 
 template <int NQ, int G>   // NQ = b_q / 32 query tiles, G query heads: NQ*G waves
 __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnPrefillArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t *sK = smem;                                   // 3 stages
-    uint16_t *sVt = smem + 3 * kPfStageK;                  // 3 stages
-    int *sPos = reinterpret_cast<int *>(smem + 3 * (kPfStageK + kPfStageV));   // one int per key slot
+    int *sPos = reinterpret_cast<int *>(smem + kPfStages * kPfStageEl);      // one int per key slot
 
     const int p = blockIdx.x;
     const Problem pr = problem_of(a.ge, p);
-    constexpr int nthreads = 64 * NQ * G;
+    constexpr int NW = NQ * G;
+    constexpr int nthreads = 64 * NW;
     constexpr int b_q = 32 * NQ;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -77,83 +94,41 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
     float m_run = kNegBigPf, l_run = 0.f;
 
-    // loader roles.  K: item = (key, dim group c), 32 x 16 = 512 sixteen-byte pieces.
-    // V: item = (key pair, dim group c), 16 x 16 = 256 pairs of pieces (a pair packs into 32-bit V^T stores).
-    constexpr int kItemsK = kPfTile * 16, kItemsV = (kPfTile / 2) * 16;
-    constexpr int kPerK = (kItemsK + nthreads - 1) / nthreads, kPerV = (kItemsV + nthreads - 1) / nthreads;
-    struct RowBuf { uint4 k[kPerK], v[kPerV][2]; };
-    RowBuf bufA, bufB;
-
-    auto fetch = [&](RowBuf &buf, int tile) {
+    // Loads of a tile: 8 four-row instructions for K and 8 for V, dealt to the NW waves.
+    constexpr int kLoadsPerWave = 16 / NW;
+    static_assert(kLoadsPerWave * NW == 16, "wave count must divide 16");
+    auto request = [&](int tile) {
         if (tile >= n_tiles) return;
+        uint16_t *stage = smem + (tile % kPfStages) * kPfStageEl;
 #pragma unroll
-        for (int r = 0; r < kPerK; ++r) {
-            const int item = tid + r * nthreads;
-            if (item >= kItemsK) break;
-            const int pos = sPos[tile * kPfTile + (item >> 4)];
-            buf.k[r] = make_uint4(0, 0, 0, 0);
-            if (pos >= 0) buf.k[r] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos * a.k_st + (item & 15) * 8);
-        }
-#pragma unroll
-        for (int r = 0; r < kPerV; ++r) {
-            const int item = tid + r * nthreads;
-            if (item >= kItemsV) break;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int pos = sPos[tile * kPfTile + (item >> 4) * 2 + e];
-                buf.v[r][e] = make_uint4(0, 0, 0, 0);
-                if (pos >= 0) buf.v[r][e] = *reinterpret_cast<const uint4 *>(vb + (int64_t)pos * a.v_st + (item & 15) * 8);
-            }
-        }
-    };
-    auto stash = [&](const RowBuf &buf, int tile) {
-        if (tile >= n_tiles) return;
-        uint16_t *dK = sK + (tile % 3) * kPfStageK;
-        uint16_t *dV = sVt + (tile % 3) * kPfStageV;
-#pragma unroll
-        for (int r = 0; r < kPerK; ++r) {
-            const int item = tid + r * nthreads;
-            if (item >= kItemsK) break;
-            *reinterpret_cast<uint4 *>(&dK[(item >> 4) * kPfKStride + (item & 15) * 8]) = buf.k[r];
-        }
-#pragma unroll
-        for (int r = 0; r < kPerV; ++r) {
-            const int item = tid + r * nthreads;
-            if (item >= kItemsV) break;
-            const int key0 = (item >> 4) * 2, c = item & 15;
-            // position of key kappa in a V^T row: 16*(kappa/16) + 8*half + j,
-            // half = (kappa%8)/4, j = 4*((kappa%16)/8) + kappa%4
-            const int k16 = key0 & 15;
-            int vslot = (key0 & 16) + ((k16 & 7) >> 2) * 8 + (k16 >> 3) * 4 + (k16 & 3);   // even
-            vslot ^= ((c >> 1) & 3) << 3;                     // granule swizzle by dim group
-            const uint32_t v0[4] = {buf.v[r][0].x, buf.v[r][0].y, buf.v[r][0].z, buf.v[r][0].w};
-            const uint32_t v1[4] = {buf.v[r][1].x, buf.v[r][1].y, buf.v[r][1].z, buf.v[r][1].w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t lo = (v0[i] & 0xffffu) | (v1[i] << 16);            // dim c*8+2i of both keys
-                const uint32_t hi = (v0[i] >> 16) | (v1[i] & 0xffff0000u);        // dim c*8+2i+1
-                *reinterpret_cast<uint32_t *>(&dV[(c * 8 + 2 * i) * kPfVStride + vslot]) = lo;
-                *reinterpret_cast<uint32_t *>(&dV[(c * 8 + 2 * i + 1) * kPfVStride + vslot]) = hi;
-            }
+        for (int i = 0; i < kLoadsPerWave; ++i) {
+            const int j = wave + i * NW;                       // wave-uniform; j < 8: K rows, else V rows
+            const bool is_v = j >= 8;
+            const int key = 4 * (j & 7) + (lane >> 4);
+            const int pos = max(sPos[tile * kPfTile + key], 0);
+            const int slot = lane & 15;
+            const int chunk = is_v ? slot ^ ((key & 3) << 2) : slot ^ (key & 15);
+            const uint16_t *src = (is_v ? vb + (int64_t)pos * a.v_st : kb + (int64_t)pos * a.k_st) + chunk * 8;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(stage + j * 4 * kD), 16, 0, 0);
         }
     };
 
     // first product of a tile: S^T = K Q^T for this wave's 32 queries
     auto scores = [&](int tile) -> f32x16 {
-        const uint16_t *cK = sK + (tile % 3) * kPfStageK;
+        const uint16_t *cK = smem + (tile % kPfStages) * kPfStageEl + n * kD;
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(&cK[n * kPfKStride + ks * 16 + half * 8]);
+            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(&cK[((ks * 2 + half) ^ (n & 15)) * 8]);
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[ks], s, 0, 0, 0);
         }
         return s;
     };
-    // softmax update and second product of a tile
-    auto finish = [&](int tile, f32x16 s) {
-        const uint16_t *cV = sVt + (tile % 3) * kPfStageV;
+    // softmax update of a tile's scores: P (bf16) for the second product, running sum, rescale
+    auto softmax = [&](int tile, f32x16 s, bf16x8 (&pb)[2]) {
         // a tile needs masking if it has an empty slot or a key at or after the block's first query
         const int myp = sPos[tile * kPfTile + n];
         if (__any(myp < 0 || myp >= qpos0)) {
@@ -167,11 +142,18 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mn = fmaxf(m_run, mx * a.scale_log2e);       // running max in scaled (log2) units
-        const float corr = __builtin_amdgcn_exp2f(m_run - mn);
-        m_run = mn;
+        // Reference point of the exponentials, in scaled (log2) units.  It only has to bound the
+        // scores from above loosely: it moves (and the accumulators are rescaled, 64 multiplies
+        // per lane) only when some query's tile maximum exceeds it by more than 2^kPfSlack, so
+        // p <= 2^kPfSlack, far inside the fp32 and bf16 ranges, and out = o / l is unchanged.
+        const float cand = mx * a.scale_log2e;
+        float mn = m_run, corr = 1.0f;
+        if (__any(cand > m_run + kPfSlack)) {
+            mn = fmaxf(m_run, cand);
+            corr = __builtin_amdgcn_exp2f(m_run - mn);
+            m_run = mn;
+        }
         float ps = 0.f;
-        bf16x8 pb[2];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const float pw = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2e, -mn));   // exp2(-inf) = 0
@@ -183,42 +165,56 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) o[dt] *= corr;
         }
+    };
+    // second product of a tile: O^T += V^T P^T.  Address of this lane in a transposing read:
+    // key 4*half + i/4 (+16*kk, +8 for the upper four keys), dims 32*dt + 16*(n/16) + 4*(i%4)..+3,
+    // i = lane%16; the lane then receives dim 32*dt + n of keys 16*kk (+8) + 4*half + 0..3.
+    int voff[4];
+    {
+        const int i = lane & 15, key = 4 * half + (i >> 2);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-            const int row = dt * 32 + n;
+            const int chunk = dt * 4 + ((n >> 4) << 1) + ((i & 3) >> 1);
+            voff[dt] = kPfTileEl + key * kD + ((chunk ^ ((key & 3) << 2)) << 3) + ((i & 1) << 2);
+        }
+    }
+    auto accumulate = [&](int tile, const bf16x8 (&pb)[2]) {
+        const uint16_t *cV = smem + (tile % kPfStages) * kPfStageEl;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const int g = (kk * 2 + half) ^ ((row >> 4) & 3);     // swizzled 16-byte granule
-                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(&cV[row * kPfVStride + g * 8]);
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kk], o[dt], 0, 0, 0);
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(cV + voff[dt] + (16 * kk) * kD));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4 *)(cV + voff[dt] + (16 * kk + 8) * kD));
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kk], o[dt], 0, 0, 0);
             }
         }
     };
+    // this wave's loads up to the newest tile but `newer` have landed in LDS
+    auto landed = [&](bool all) {
+        if (all) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
+    };
 
     __syncthreads();                        // sPos complete
-    fetch(bufA, 0);
-    fetch(bufB, 1);
-    stash(bufA, 0);
-    stash(bufB, 1);
-    fetch(bufA, 2);
-    fetch(bufB, 3);
+    request(0);
+    request(1);
+    request(2);
+    landed(n_tiles <= 2);                   // tiles 0 and 1
     __syncthreads();
-    f32x16 s_cur = scores(0);
-    // At the top of iteration t: stage t%3 holds tile t, stage (t+1)%3 tile t+1 (visible after the
-    // barrier), the buffer of t's parity holds tile t+2 and the other one tile t+3.
-    for (int tile = 0; tile < n_tiles; tile += 2) {
+    f32x16 s_nxt;
+    bf16x8 pb[2];
+    softmax(0, scores(0), pb);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        request(tile + 3);
+        if (tile + 1 < n_tiles) s_nxt = scores(tile + 1);
+        accumulate(tile, pb);
+        if (tile + 1 < n_tiles) softmax(tile + 1, s_nxt, pb);
+        landed(tile + 3 >= n_tiles);        // tile + 2
         __syncthreads();
-        f32x16 s_next = s_cur;
-        if (tile + 1 < n_tiles) s_next = scores(tile + 1);
-        finish(tile, s_cur);
-        stash(bufA, tile + 2);              // stage (tile+2)%3 was last read for tile-1: everyone is past it
-        fetch(bufA, tile + 4);
-        if (tile + 1 >= n_tiles) break;
-        __syncthreads();
-        if (tile + 2 < n_tiles) s_cur = scores(tile + 2);
-        finish(tile + 1, s_next);
-        stash(bufB, tile + 3);
-        fetch(bufB, tile + 5);
     }
 
     float l = l_run;
@@ -243,7 +239,7 @@ void launch_attn_prefill32(const AttnPrefillArgs &a, int P, hipStream_t st)
     const int NQ = a.ge.b_q / 32;
     const dim3 block_dim(64 * NQ * a.ge.G), grid(P);
     const int slots = (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile;
-    const size_t lds = 3 * (kPfStageK + kPfStageV) * sizeof(uint16_t) + (size_t)slots * sizeof(int);
+    const size_t lds = (size_t)kPfStages * kPfStageEl * sizeof(uint16_t) + (size_t)slots * sizeof(int);
 #define IHIP_PF32(NQV, GV)                                                                               \
     {                                                                                                    \
         static bool attr_set = false;     /* allow more than 64 KiB of dynamic LDS, once per kernel */   \
