@@ -190,13 +190,14 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
     // LDS stores per phase.  The LDS destination of a lane is fixed, so the bank swizzle is applied
     // on the source side: 16-byte slot c of tile row R holds dims 8*(c ^ (R%16)).., which makes the
     // 16 rows of an operand read hit 16 different bank groups.
-    // load4(base, dst, row): lanes 16*kq..+15 fetch row `row` (their own copy of it, -1 = none;
-    // the lanes are then masked off and the slot keeps stale data) to tile row dst_row0 + kq.
+    // load4(base, dst, row): lanes 16*kq..+15 fetch row `row` (their own copy of it) to tile row
+    // dst_row0 + kq.  A row of -1 stands for "no candidate": row 0 is fetched instead (always
+    // readable) and the caller ignores the score, which keeps the loads free of branches: with
+    // exec-masked loads every shuffle result has to be waited for on its own.
     auto load4 = [&](const uint16_t *base, off_t stride, uint16_t *dst, int row, int swz) {
-        if (row >= 0)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(base + (off_t)row * stride + ((n ^ swz) << 3)),
-                (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(base + (off_t)max(row, 0) * stride + ((n ^ swz) << 3)),
+            (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
     auto operand = [&](const uint16_t *tile, int row16, int ks) {
         return *reinterpret_cast<const bf16x8 *>(&tile[(row16 + n) * kD + (((ks << 2) + kq) ^ n) * 8]);
@@ -249,15 +250,16 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             sig[t] = best;
         }
     };
-    // score of candidate rows pos[t] of this wave's own searches.  Columns whose search has ended
-    // load nothing and their scores are ignored by the caller.
+    // score of candidate rows pos[t] of this wave's own searches.  The scores of columns whose
+    // search has ended are ignored by the caller.
     auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT]) {
+        int cand[NT * 4];
 #pragma unroll
-        for (int r = 0; r < NT * 4; ++r) {
-            // tile row r*4 + kq = candidate (t = r/4, column (r%4)*4 + kq); lanes 0..15 hold column = lane
-            const int col = (r & 3) * 4 + kq;
-            load4(kb, k_st, tile + r * 4 * kD, __shfl(ok[r >> 2] ? pos[r >> 2] : -1, col, 64), col);
-        }
+        for (int r = 0; r < NT * 4; ++r)     // lanes 0..15 hold column = lane
+            cand[r] = __shfl(ok[r >> 2] ? pos[r >> 2] : -1, (r & 3) * 4 + kq, 64);
+#pragma unroll
+        for (int r = 0; r < NT * 4; ++r)     // tile row r*4 + kq = candidate (t = r/4, column (r%4)*4 + kq)
+            load4(kb, k_st, tile + r * 4 * kD, cand[r], (r & 3) * 4 + kq);
         // the loads count on vmcnt; the wave reads its own tile, so no barrier is needed
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         mfma_scores(tile, sig);
@@ -286,14 +288,20 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             // keys of the right halves; 16 four-row loads dealt evenly to the G waves), and each
             // wave scores both tiles against its own queries.
             constexpr int kPerWave = 16 / G;
+            int cand[kPerWave];
 #pragma unroll
             for (int i = 0; i < kPerWave; ++i) {
                 const int ld = hh * kPerWave + i;                    // wave-uniform
                 const int set = ld >> 3, r = ld & 7;
-                const int col = (r & 3) * 4 + kq;
                 const int st_ = (r >> 2) ? start[1] : start[0], ln_ = (r >> 2) ? len[1] : len[0];
-                const int cand = set == 0 ? st_ : (half >= 1 && half < ln_ ? st_ + half : -1);
-                load4(kb, k_st, &sh_rows[set * kTile + r * 4 * kD], __shfl(cand, col, 64), col);
+                const int c = set == 0 ? st_ : (half >= 1 && half < ln_ ? st_ + half : -1);
+                cand[i] = __shfl(c, (r & 3) * 4 + kq, 64);
+            }
+#pragma unroll
+            for (int i = 0; i < kPerWave; ++i) {
+                const int ld = hh * kPerWave + i;
+                const int set = ld >> 3, r = ld & 7;
+                load4(kb, k_st, &sh_rows[set * kTile + r * 4 * kD], cand[i], (r & 3) * 4 + kq);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();

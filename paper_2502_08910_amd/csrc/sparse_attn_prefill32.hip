@@ -36,8 +36,10 @@
 // Four LDS stages: the rows of tile t+3 are requested at the start of period
 // t, tile t+2 must have landed at the barrier that ends it.  K(u) is read in
 // period u-1 (and before the loop for u = 0), V(u) in period u, so the stage of
-// tile u-1 is free when period t = u-3... begins.
+// tile t-1 is free when period t begins and takes tile t+3.  The loop is
+// unrolled by the four stages.
 #include "attn_prefill_args.h"
+#include <type_traits>
 
 namespace ihip {
 
@@ -97,26 +99,47 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
     // Loads of a tile: 8 four-row instructions for K and 8 for V, dealt to the NW waves.
     constexpr int kLoadsPerWave = 16 / NW;
     static_assert(kLoadsPerWave * NW == 16, "wave count must divide 16");
-    auto request = [&](int tile) {
-        if (tile >= n_tiles) return;
-        uint16_t *stage = smem + (tile % kPfStages) * kPfStageEl;
+    // The loads are written as assembly: a compiler-visible LDS-bound load makes the compiler
+    // drain the vector-memory counter before the next LDS read it cannot tell apart from the
+    // destination, which would undo the prefetch distance.  landed() below is the only wait.
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    // the stage of a tile (tile % kPfStages) is a compile-time constant in the unrolled loop below,
+    // so LDS addresses are per-lane constants plus immediates
+    auto stage_of = [&](int st) { return smem + (st & (kPfStages - 1)) * kPfStageEl; };
+    // key positions of this lane's rows in the loads of a tile (read a period ahead of the request)
+    struct Rows { int pos[kLoadsPerWave]; };
+    auto rows_of = [&](int tile) {
+        Rows r;
 #pragma unroll
         for (int i = 0; i < kLoadsPerWave; ++i) {
-            const int j = wave + i * NW;                       // wave-uniform; j < 8: K rows, else V rows
-            const bool is_v = j >= 8;
+            const int j = wave_s + i * NW;
+            r.pos[i] = tile < n_tiles ? sPos[tile * kPfTile + 4 * (j & 7) + (lane >> 4)] : 0;
+        }
+        return r;
+    };
+    auto request = [&](int tile, int st, const Rows &rows) {
+        if (tile >= n_tiles) return;
+        uint16_t *stage = stage_of(st);
+#pragma unroll
+        for (int i = 0; i < kLoadsPerWave; ++i) {
+            // instruction j of the tile: j < 8 fetches K rows 4j..4j+3, j >= 8 V rows 4(j-8)..
+            const bool is_v = NW <= 8 ? i * NW >= 8 : wave_s >= 8;
+            const int j = wave_s + i * NW;
             const int key = 4 * (j & 7) + (lane >> 4);
-            const int pos = max(sPos[tile * kPfTile + key], 0);
+            const int pos = max(rows.pos[i], 0);
             const int slot = lane & 15;
             const int chunk = is_v ? slot ^ ((key & 3) << 2) : slot ^ (key & 15);
             const uint16_t *src = (is_v ? vb + (int64_t)pos * a.v_st : kb + (int64_t)pos * a.k_st) + chunk * 8;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(stage + j * 4 * kD), 16, 0, 0);
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(
+                (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)(stage + j * 4 * kD));
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+                         : "memory");
         }
     };
 
     // first product of a tile: S^T = K Q^T for this wave's 32 queries
-    auto scores = [&](int tile) -> f32x16 {
-        const uint16_t *cK = smem + (tile % kPfStages) * kPfStageEl + n * kD;
+    auto scores = [&](int st) -> f32x16 {
+        const uint16_t *cK = stage_of(st) + n * kD;
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -128,7 +151,7 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
         return s;
     };
     // softmax update of a tile's scores: P (bf16) for the second product, running sum, rescale
-    auto softmax = [&](int tile, f32x16 s, bf16x8 (&pb)[2]) {
+    auto softmax = [&](int tile, f32x16 &s, bf16x8 (&pb)[2]) {
         // a tile needs masking if it has an empty slot or a key at or after the block's first query
         const int myp = sPos[tile * kPfTile + n];
         if (__any(myp < 0 || myp >= qpos0)) {
@@ -178,20 +201,20 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
             voff[dt] = kPfTileEl + key * kD + ((chunk ^ ((key & 3) << 2)) << 3) + ((i & 1) << 2);
         }
     }
-    auto accumulate = [&](int tile, const bf16x8 (&pb)[2]) {
-        const uint16_t *cV = smem + (tile % kPfStages) * kPfStageEl;
+    auto v_operand = [&](const uint16_t *cV, int dt, int kk) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4 *)(cV + voff[dt] + (16 * kk) * kD));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4 *)(cV + voff[dt] + (16 * kk + 8) * kD));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto accumulate = [&](int st, const bf16x8 (&pb)[2]) {
+        const uint16_t *cV = stage_of(st);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
+        for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4 *)(cV + voff[dt] + (16 * kk) * kD));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4 *)(cV + voff[dt] + (16 * kk + 8) * kD));
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[kk], o[dt], 0, 0, 0);
-            }
-        }
+            for (int kk = 0; kk < 2; ++kk)
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(cV, dt, kk), pb[kk], o[dt], 0, 0, 0);
     };
     // this wave's loads up to the newest tile but `newer` have landed in LDS
     auto landed = [&](bool all) {
@@ -200,21 +223,34 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
     };
 
     __syncthreads();                        // sPos complete
-    request(0);
-    request(1);
-    request(2);
+    request(0, 0, rows_of(0));
+    request(1, 1, rows_of(1));
+    request(2, 2, rows_of(2));
+    Rows rows = rows_of(3);
     landed(n_tiles <= 2);                   // tiles 0 and 1
     __syncthreads();
-    f32x16 s_nxt;
+    f32x16 s_nxt = scores(0);
     bf16x8 pb[2];
-    softmax(0, scores(0), pb);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        request(tile + 3);
-        if (tile + 1 < n_tiles) s_nxt = scores(tile + 1);
-        accumulate(tile, pb);
+    softmax(0, s_nxt, pb);
+    // one tile period; ST = tile % kPfStages
+    auto period = [&](auto st_c, int tile) {
+        constexpr int ST = decltype(st_c)::value;
+        request(tile + 3, ST + 3, rows);
+        if (tile + 1 < n_tiles) s_nxt = scores(ST + 1);
+        accumulate(ST, pb);
         if (tile + 1 < n_tiles) softmax(tile + 1, s_nxt, pb);
+        rows = rows_of(tile + 4);
         landed(tile + 3 >= n_tiles);        // tile + 2
         __syncthreads();
+    };
+    for (int tile = 0; tile < n_tiles; tile += 4) {
+        period(std::integral_constant<int, 0>{}, tile);
+        if (tile + 1 >= n_tiles) break;
+        period(std::integral_constant<int, 1>{}, tile + 1);
+        if (tile + 2 >= n_tiles) break;
+        period(std::integral_constant<int, 2>{}, tile + 2);
+        if (tile + 3 >= n_tiles) break;
+        period(std::integral_constant<int, 3>{}, tile + 3);
     }
 
     float l = l_run;
