@@ -190,14 +190,21 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
     // LDS stores per phase.  The LDS destination of a lane is fixed, so the bank swizzle is applied
     // on the source side: 16-byte slot c of tile row R holds dims 8*(c ^ (R%16)).., which makes the
     // 16 rows of an operand read hit 16 different bank groups.
-    // load4(base, dst, row): lanes 16*kq..+15 fetch row `row` (their own copy of it) to tile row
-    // dst_row0 + kq.  A row of -1 stands for "no candidate": row 0 is fetched instead (always
-    // readable) and the caller ignores the score, which keeps the loads free of branches: with
-    // exec-masked loads every shuffle result has to be waited for on its own.
-    auto load4 = [&](const uint16_t *base, off_t stride, uint16_t *dst, int row, int swz) {
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(base + (off_t)max(row, 0) * stride + ((n ^ swz) << 3)),
-            (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    // load4(base, stride, dst, row, swz): lanes 16*kq..+15 fetch row `row` (their own copy of it)
+    // to the tile row dst + kq; dst is the LDS byte address of a four-row group, wave-uniform.  A
+    // row of -1 stands for "no candidate": row 0 is fetched instead (always readable) and the
+    // caller ignores the score, which keeps the loads free of branches: with exec-masked loads
+    // every shuffle result has to be waited for on its own.  The instruction is written as
+    // assembly so that the destinations can be computed once, outside the search loops.
+    auto load4 = [&](const uint16_t *base, off_t stride, uint32_t dst, int row, int swz) {
+        const off_t r = (off_t)max(row, 0);
+        const off_t at = WIDE ? r * stride : (off_t)__umul24((uint32_t)r, (uint32_t)stride);
+        const uint16_t *src = base + at + ((n ^ swz) << 3);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+    };
+    auto lds_addr = [&](const uint16_t *ptr) {
+        return (uint32_t)__builtin_amdgcn_readfirstlane(
+            (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)ptr);
     };
     auto operand = [&](const uint16_t *tile, int row16, int ks) {
         return *reinterpret_cast<const bf16x8 *>(&tile[(row16 + n) * kD + (((ks << 2) + kq) ^ n) * 8]);
@@ -206,6 +213,9 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
     // A operands: the block's queries, [MT tiles of 16 rows] x [4 steps of 32 dims], staged
     // through this wave's own tile, 32 rows at a time
     uint16_t *tile = &sh_rows[hh * kTile];
+    uint32_t dst_own[NT * 4];                        // this wave's tile, four rows at a time
+#pragma unroll
+    for (int r = 0; r < NT * 4; ++r) dst_own[r] = lds_addr(tile + r * 4 * kD);
     bf16x8 qa[MT][4];
     {
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(pr.m * a.ge.b_q) * a.q_st;
@@ -214,7 +224,7 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             constexpr int kRows = MT >= 2 ? 32 : 16;
 #pragma unroll
             for (int r = 0; r < kRows / 4; ++r)
-                load4(qb, (off_t)a.q_st, tile + r * 4 * kD, m0 * 16 + r * 4 + kq, (r & 3) * 4 + kq);
+                load4(qb, (off_t)a.q_st, dst_own[r], m0 * 16 + r * 4 + kq, (r & 3) * 4 + kq);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
             for (int mt = m0; mt < m0 + 2 && mt < MT; ++mt)
@@ -259,12 +269,16 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             cand[r] = __shfl(ok[r >> 2] ? pos[r >> 2] : -1, (r & 3) * 4 + kq, 64);
 #pragma unroll
         for (int r = 0; r < NT * 4; ++r)     // tile row r*4 + kq = candidate (t = r/4, column (r%4)*4 + kq)
-            load4(kb, k_st, tile + r * 4 * kD, cand[r], (r & 3) * 4 + kq);
+            load4(kb, k_st, dst_own[r], cand[r], (r & 3) * 4 + kq);
         // the loads count on vmcnt; the wave reads its own tile, so no barrier is needed
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         mfma_scores(tile, sig);
     };
 
+    // destinations of this wave's share of the loads of the shared first phase
+    uint32_t dst_shared[kShare ? 16 / G : 1];
+#pragma unroll
+    for (int i = 0; i < (kShare ? 16 / G : 1); ++i) dst_shared[i] = lds_addr(&sh_rows[(hh * (16 / G) + i) % (G * 8) * 4 * kD]);
     for (int it = 0; it < iters; ++it) {
         const int jt = (blockIdx.y * iters + it) * NT * 16;
         int start[NT], len[NT], off[NT], pos[NT];
@@ -299,9 +313,8 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             }
 #pragma unroll
             for (int i = 0; i < kPerWave; ++i) {
-                const int ld = hh * kPerWave + i;
-                const int set = ld >> 3, r = ld & 7;
-                load4(kb, k_st, &sh_rows[set * kTile + r * 4 * kD], cand[i], (r & 3) * 4 + kq);
+                const int r = (hh * kPerWave + i) & 7;
+                load4(kb, k_st, dst_shared[i], cand[i], (r & 3) * 4 + kq);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
@@ -370,14 +383,16 @@ static void launch_prefill_w(const PruneArgs &a, int P, hipStream_t st)
     }
 }
 
-// 32-bit element offsets (one VGPR per address, saddr-form loads) when every row of a (batch,
-// head) slab of Q and K lies within 2^31 elements of its base; 64-bit offsets otherwise.
+// 32-bit element offsets (one VGPR per address, full-rate 24-bit multiply) when every row of a
+// (batch, head) slab of Q and K lies within 2^31 elements of its base and positions and strides are
+// below 2^24; 64-bit offsets otherwise.
 template <int MT>
 static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, hipStream_t st)
 {
     const int64_t lim = (int64_t)1 << 31;
+    const int64_t lim24 = (int64_t)1 << 24;         // narrow offsets are formed by a 24-bit multiply
     const bool wide = max_seq_len * a.k_st + kD >= lim || (int64_t)a.ge.b_q * a.q_st + kD >= lim ||
-                      a.k_st < 0 || a.q_st < 0;
+                      a.k_st < 0 || a.q_st < 0 || max_seq_len >= lim24 || a.k_st >= lim24 || a.q_st >= lim24;
     if (wide) launch_prefill_w<MT, true>(a, P, st);
     else launch_prefill_w<MT, false>(a, P, st);
 }
