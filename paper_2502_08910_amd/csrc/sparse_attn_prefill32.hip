@@ -50,10 +50,10 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 constexpr int kPfStages = 4;
 constexpr int kPfTileEl = kPfTile * kD;            // elements of one K (or V) tile: 32 rows of 256 bytes
 constexpr int kPfStageEl = 2 * kPfTileEl;          // K tile, then V tile
-constexpr float kPfSlack = 8.0f;                   // log2 units of head-room before the softmax reference moves
+constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above which the softmax reference moves
 
 template <int NQ, int G>   // NQ = b_q / 32 query tiles, G query heads: NQ*G waves
-__global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnPrefillArgs a)
+__global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) void attn_prefill32_kernel(const AttnPrefillArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     int *sPos = reinterpret_cast<int *>(smem + kPfStages * kPfStageEl);      // one int per key slot
@@ -161,33 +161,40 @@ __global__ __launch_bounds__(64 * NQ * G) void attn_prefill32_kernel(const AttnP
                 if (kp < 0 || kp > qpos) s[r] = -INFINITY;
             }
         }
-        float mx = s[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // Reference point of the exponentials, in scaled (log2) units.  It only has to bound the
-        // scores from above loosely: it moves (and the accumulators are rescaled, 64 multiplies
-        // per lane) only when some query's tile maximum exceeds it by more than 2^kPfSlack, so
-        // p <= 2^kPfSlack, far inside the fp32 and bf16 ranges, and out = o / l is unchanged.
-        const float cand = mx * a.scale_log2e;
-        float mn = m_run, corr = 1.0f;
-        if (__any(cand > m_run + kPfSlack)) {
-            mn = fmaxf(m_run, cand);
-            corr = __builtin_amdgcn_exp2f(m_run - mn);
-            m_run = mn;
-        }
+        // Reference point m_run of the exponentials, in scaled (log2) units.  It only has to bound
+        // the scores from above loosely, so the common path takes the exponentials against the
+        // current one without looking for the tile maximum, and checks the row sums: a sum above
+        // kPfMaxSum (or an overflow) in any lane sends the whole wave to the exact path, which
+        // moves the reference to the maximum and rescales the accumulators (64 multiplies per
+        // lane).  p <= kPfMaxSum stays far inside the fp32 and bf16 ranges and out = o / l is
+        // unchanged.  The two lanes of a query (key halves) always share one reference.
         float ps = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float pw = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2e, -mn));   // exp2(-inf) = 0
+            const float pw = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2e, -m_run));   // exp2(-inf) = 0
             ps += pw;
             pb[r >> 3][r & 7] = (__bf16)pw;
         }
-        l_run = l_run * corr + ps;                                // partial over this lane's keys
-        if (__any(corr != 1.0f)) {
+        if (__any(!(ps <= kPfMaxSum))) {
+            float mx = s[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mn = fmaxf(m_run, mx * a.scale_log2e);
+            const float corr = __builtin_amdgcn_exp2f(m_run - mn);
+            m_run = mn;
+            ps = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pw = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2e, -mn));
+                ps += pw;
+                pb[r >> 3][r & 7] = (__bf16)pw;
+            }
+            l_run *= corr;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) o[dt] *= corr;
         }
+        l_run += ps;                                              // partial over this lane's keys
     };
     // second product of a tile: O^T += V^T P^T.  Address of this lane in a transposing read:
     // key 4*half + i/4 (+16*kk, +8 for the upper four keys), dims 32*dt + 16*(n/16) + 4*(i%4)..+3,
