@@ -137,6 +137,28 @@ def test_keep_everything_is_dense_causal(ihip, orc, prefix):
     assert (out.cpu().double() - ref).abs().max().item() <= 2e-2
 
 
+@pytest.mark.parametrize("gain", [6.0, 24.0])
+def test_softmax_reference_moves(ihip, orc, gain):
+    # Keys grow louder along the sequence, so the running softmax reference of the kernel has to
+    # move many times (and far: scores reach a few hundred in log2 units at gain 24); everything
+    # is kept, so the result is dense causal attention.
+    prefix = 3000
+    keep = (prefix + 512) // 64 + 1
+    w = small(Tq=512, prefix=prefix, n_stream=128, stages=((64, keep), (16, 4 * keep)))
+    q, k, v, sl, _ = configs.make_inputs(w, 11)
+    ramp = torch.linspace(0.05, 1.0, w.T).view(1, 1, -1, 1) * gain
+    k = (k.float() * ramp).to(torch.bfloat16)
+    L, stages, out, lse = gpu_prefill(ihip, w, *dev(q, k, v, sl), want_rep=False)
+    G, T, Tq = w.G, w.T, w.Tq
+    mask = torch.arange(T).view(1, -1) <= torch.arange(T - Tq, T).view(-1, 1)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        q.double(), k.double().repeat_interleave(G, 1), v.double().repeat_interleave(G, 1), attn_mask=mask)
+    assert (out.cpu().double() - ref).abs().max().item() <= 2e-2
+    logits = torch.einsum("bhqd,bhkd->bhqk", q.double(), k.double().repeat_interleave(G, 1)) / 128 ** 0.5
+    ref_lse = torch.logsumexp(logits.masked_fill(~mask, float("-inf")), -1)
+    assert torch.allclose(lse.cpu().double(), ref_lse, rtol=1e-4, atol=1e-3)
+
+
 def test_attention_alone_on_oracle_indices(ihip, orc):
     w = small(Tq=128, prefix=3000, Hq=8, Hkv=2, stages=((64, 16), (16, 24)))
     q, k, v, sl, _ = configs.make_inputs(w, 3)
