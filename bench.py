@@ -272,6 +272,13 @@ def bench_prefill(args, w, torch, ihip, configs):
     for n in kernels:
         if n in flops:
             kernels[n]["TFLOPs"] = flops[n] / (kernels[n]["us"] * 1e-6) / 1e12
+    # what the matrix cores of this GPU sustain on independent chains of the two MFMA shapes the
+    # kernels use (no memory traffic), next to the vendor's peak
+    measured = {"attn_prefill": ihip.mfma_rate(0), "prune_prefill": ihip.mfma_rate(1)}
+    for n in kernels:
+        if "TFLOPs" in kernels[n]:
+            kernels[n]["frac_of_peak"] = kernels[n]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+            kernels[n]["frac_of_measured_mfma_rate"] = kernels[n]["TFLOPs"] / measured[n.split(".")[0]]
     roofline = None
     if kernels and dominant(kernels) in flops:
         dom = dominant(kernels)
@@ -279,7 +286,9 @@ def bench_prefill(args, w, torch, ihip, configs):
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
-                    "flops_per_launch": flops[dom], "us_per_launch": kernels[dom]["us"]}
+                    "flops_per_launch": flops[dom], "us_per_launch": kernels[dom]["us"],
+                    "measured_mfma_rate": measured[dom.split(".")[0]],
+                    "frac_of_measured_mfma_rate": ach / measured[dom.split(".")[0]]}
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -307,7 +316,9 @@ def bench_prefill(args, w, torch, ihip, configs):
                    "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink, "n_stream": w.n_stream},
         "roofline": roofline, "cpu_baseline": cpu,
         "whole_path": {"mfma_flops_per_layer": sum(flops.values()),
-                       "achieved_TFLOPs": sum(flops.values()) / (us_per_layer * 1e-6) / 1e12},
+                       "achieved_TFLOPs": sum(flops.values()) / (us_per_layer * 1e-6) / 1e12,
+                       "measured_mfma_rate_TFLOPs": {"32x32x16_bf16": measured["attn_prefill"],
+                                                     "16x16x32_bf16": measured["prune_prefill"]}},
         "kernels": kernels, "setup_s": t_setup,
     }
 

@@ -268,6 +268,18 @@ size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stage
 int32_t ihip_profile_enable(int32_t on);
 int32_t ihip_profile_read(int32_t max_entries, const char **names, double *total_ms, int64_t *launches);
 
+/*
+ * Dense matrix-core rate of the current device (the measurement protocol, not
+ * the method): runs independent accumulation chains of one bf16 MFMA shape
+ * (kind 0: 32x32x16, the prefill attention's; kind 1: 16x16x32, the prefill
+ * pruning's) with no memory traffic, `iters` instructions per chain, on every
+ * compute unit, twice (the second run is timed with HIP events on `stream`),
+ * and writes the rate in TFLOP/s (2 flops per multiply-add) to the host double
+ * *tflops.  scratch: device, >= 512 floats, never written in practice.  Blocks
+ * until the timed run has finished.  Not for use under graph capture.
+ */
+int32_t ihip_mfma_rate(int32_t kind, int32_t iters, float *scratch, double *tflops, void *stream);
+
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char *ihip_last_error(void);
 

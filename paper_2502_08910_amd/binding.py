@@ -68,6 +68,7 @@ EXPORTS = {
     "ihip_workspace_bytes": (c_sz, [c_i32, ctypes.POINTER(Shape), c_i32, vp, vp]),
     "ihip_profile_enable": (c_i32, [c_i32]),
     "ihip_profile_read": (c_i32, [c_i32, vp, vp, vp]),
+    "ihip_mfma_rate": (c_i32, [c_i32, c_i32, vp, vp, vp]),
     "ihip_last_error": (ctypes.c_char_p, []),
     "ihip_version": (c_i32, []),
 }
@@ -126,6 +127,14 @@ def profile_read(max_entries: int = 64) -> dict:
     if n < 0:
         _check(n)
     return {names[i].decode(): (ms[i], cnt[i]) for i in range(n)}
+
+
+def mfma_rate(kind: int, iters: int = 20000) -> float:
+    """Dense bf16 MFMA rate of the current GPU in TFLOP/s (kind 0: 32x32x16, 1: 16x16x32)."""
+    scratch = torch.zeros(512, dtype=torch.float32, device="cuda")
+    out = ctypes.c_double(0.0)
+    _check(lib().ihip_mfma_rate(kind, iters, scratch.data_ptr(), ctypes.byref(out), _stream()))
+    return out.value
 
 
 class Layer:

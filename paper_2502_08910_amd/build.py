@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libihip.so")
 SOURCES = ["api.hip", "prune_stage.hip", "select_blocks.hip", "sparse_attn_decode.hip",
-           "sparse_attn_prefill.hip", "sparse_attn_prefill32.hip", "cache.hip"]
+           "sparse_attn_prefill.hip", "sparse_attn_prefill32.hip", "cache.hip", "mfma_rate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

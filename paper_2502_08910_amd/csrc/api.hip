@@ -228,6 +228,16 @@ extern "C" {
 const char *ihip_last_error(void) { return g_err; }
 int32_t ihip_version(void) { return 100; }
 
+int32_t ihip_mfma_rate(int32_t kind, int32_t iters, float *scratch, double *tflops, void *stream)
+{
+    if ((kind != 0 && kind != 1) || iters <= 0 || iters > (1 << 22) || !scratch || !tflops)
+        return fail(IHIP_ERR_INVALID_ARG, "ihip_mfma_rate: kind in {0,1}, 1 <= iters <= 2^22, scratch and tflops non-NULL");
+    const double r = measure_mfma_rate(kind, iters, scratch, (hipStream_t)stream);
+    if (r < 0.0) return fail(IHIP_ERR_HIP, "ihip_mfma_rate: HIP error while timing");
+    *tflops = r;
+    return IHIP_OK;
+}
+
 int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk)
 {
     if (check_shape(shape, "ihip_stage1_slots") != IHIP_OK || !pow2(chunk)) return -1;

@@ -32,6 +32,9 @@ struct KernelTimer {
     ~KernelTimer() { profile_end(st); }
 };
 
+// ---- matrix-core throughput probe (mfma_rate.hip) ---------------------------
+double measure_mfma_rate(int kind, int iters, float *sink, hipStream_t st);
+
 // ---- geometry of one problem ---------------------------------------------
 struct Geometry {
     const int32_t *seq_lens;
