@@ -105,7 +105,7 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     // the stage of a tile (tile % kPfStages) is a compile-time constant in the unrolled loop below,
     // so LDS addresses are per-lane constants plus immediates
-    auto stage_of = [&](int st) { return smem + (st & (kPfStages - 1)) * kPfStageEl; };
+    auto stage_of = [&](int st) { return smem + (st % kPfStages) * kPfStageEl; };
     // key positions of this lane's rows in the loads of a tile (read a period ahead of the request)
     struct Rows { int pos[kLoadsPerWave]; };
     auto rows_of = [&](int tile) {
@@ -223,18 +223,20 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
             for (int kk = 0; kk < 2; ++kk)
                 o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(cV, dt, kk), pb[kk], o[dt], 0, 0, 0);
     };
-    // this wave's loads up to the newest tile but `newer` have landed in LDS
+    // Tile t+D is requested at the start of period t (D = kPfStages-1); tile t+2 must have landed
+    // at the barrier that ends it, so D-2 newer requests may still be on their way then (near the
+    // end of the key list fewer are: everything is waited for).
+    constexpr int D = kPfStages - 1;
     auto landed = [&](bool all) {
-        if (all) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
+        if (all || D == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * kLoadsPerWave) : "memory");
     };
 
     __syncthreads();                        // sPos complete
-    request(0, 0, rows_of(0));
-    request(1, 1, rows_of(1));
-    request(2, 2, rows_of(2));
-    Rows rows = rows_of(3);
-    landed(n_tiles <= 2);                   // tiles 0 and 1
+#pragma unroll
+    for (int t = 0; t < D; ++t) request(t, t, rows_of(t));
+    Rows rows = rows_of(D);
+    landed(true);                           // tiles 0 and 1 (and the rest of the prologue's requests)
     __syncthreads();
     f32x16 s_nxt = scores(0);
     bf16x8 pb[2];
@@ -242,22 +244,29 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     // one tile period; ST = tile % kPfStages
     auto period = [&](auto st_c, int tile) {
         constexpr int ST = decltype(st_c)::value;
-        request(tile + 3, ST + 3, rows);
+        request(tile + D, ST + D, rows);
         if (tile + 1 < n_tiles) s_nxt = scores(ST + 1);
         accumulate(ST, pb);
         if (tile + 1 < n_tiles) softmax(tile + 1, s_nxt, pb);
-        rows = rows_of(tile + 4);
-        landed(tile + 3 >= n_tiles);        // tile + 2
+        rows = rows_of(tile + D + 1);
+        landed(tile + D >= n_tiles);        // tile + 2
         __syncthreads();
     };
-    for (int tile = 0; tile < n_tiles; tile += 4) {
-        period(std::integral_constant<int, 0>{}, tile);
-        if (tile + 1 >= n_tiles) break;
-        period(std::integral_constant<int, 1>{}, tile + 1);
-        if (tile + 2 >= n_tiles) break;
-        period(std::integral_constant<int, 2>{}, tile + 2);
-        if (tile + 3 >= n_tiles) break;
-        period(std::integral_constant<int, 3>{}, tile + 3);
+    auto periods = [&](int tile, auto... st) {      // up to kPfStages periods, stopping at the last tile
+        bool more = true;
+        ((more = more && tile + decltype(st)::value < n_tiles && (period(st, tile + decltype(st)::value), true)), ...);
+    };
+    for (int tile = 0; tile < n_tiles; tile += kPfStages) {
+        if constexpr (kPfStages == 4)
+            periods(tile, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{},
+                    std::integral_constant<int, 2>{}, std::integral_constant<int, 3>{});
+        else if constexpr (kPfStages == 5)
+            periods(tile, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{},
+                    std::integral_constant<int, 2>{}, std::integral_constant<int, 3>{}, std::integral_constant<int, 4>{});
+        else
+            periods(tile, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{},
+                    std::integral_constant<int, 2>{}, std::integral_constant<int, 3>{}, std::integral_constant<int, 4>{},
+                    std::integral_constant<int, 5>{});
     }
 
     float l = l_run;
