@@ -61,7 +61,7 @@ void profile_begin(const char *name, hipStream_t st)
     if (!g_prof_on) return;
     Span s{name, take_event(), take_event()};
     if (!s.t0 || !s.t1) return;
-    hipEventRecord(s.t0, st);
+    (void)hipEventRecord(s.t0, st);
     g_spans.push_back(s);
 }
 
@@ -69,7 +69,7 @@ void profile_end(hipStream_t st)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);
     if (!g_prof_on || g_spans.empty()) return;
-    hipEventRecord(g_spans.back().t1, st);
+    (void)hipEventRecord(g_spans.back().t1, st);
 }
 
 // kernels' host launchers

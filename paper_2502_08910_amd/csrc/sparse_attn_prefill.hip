@@ -250,7 +250,7 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
     const bool fits32 = s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= kPf32MaxSlots;
     if (fits32) {
-        launch_attn_prefill32(a, P, st);
+        launch_attn_prefill32(a, P, s.max_seq_len, st);
         return check_launch("sparse_attn_prefill");
     }
     switch (s.b_q) {

@@ -52,11 +52,17 @@ constexpr int kPfTileEl = kPfTile * kD;            // elements of one K (or V) t
 constexpr int kPfStageEl = 2 * kPfTileEl;          // K tile, then V tile
 constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above which the softmax reference moves
 
-template <int NQ, int G>   // NQ = b_q / 32 query tiles, G query heads: NQ*G waves
+// NQ = b_q / 32 query tiles, G query heads: NQ*G waves.  WIDE: 64-bit row offsets; otherwise every
+// row of a (sequence, KV head) slab of K and V lies within 2^31 elements of its base and positions
+// and strides are below 2^24, so an offset is one full-rate 24-bit multiply.
+template <int NQ, int G, bool WIDE>
 __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) void attn_prefill32_kernel(const AttnPrefillArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     int *sPos = reinterpret_cast<int *>(smem + kPfStages * kPfStageEl);      // one int per key slot
+    // one flag per tile, behind the positions of the most slots this geometry can have
+    uint8_t *sMasked = reinterpret_cast<uint8_t *>(
+        sPos + (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile);
 
     const int p = blockIdx.x;
     const Problem pr = problem_of(a.ge, p);
@@ -77,8 +83,13 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     const int total = n_sink_eff + (a.n_blocks << a.block_log2) + max(0, pr.E - w0);
     const int n_tiles = (total + kPfTile - 1) / kPfTile;     // host guarantees n_tiles*32 <= kPf32MaxSlots
 
-    for (int slot = tid; slot < n_tiles * kPfTile; slot += nthreads)
-        sPos[slot] = slot < total ? pf_slot_to_pos(a, pr, p, slot, n_sink_eff, w0) : -1;
+    // a tile needs masking if it has an empty slot or a key at or after the block's first query
+    for (int slot = tid; slot < n_tiles * kPfTile; slot += nthreads) {
+        const int pos = slot < total ? pf_slot_to_pos(a, pr, p, slot, n_sink_eff, w0) : -1;
+        sPos[slot] = pos;
+        const unsigned long long m = __ballot(pos < 0 || pos >= qpos0);      // a tile is half a wave
+        if ((lane & 31) == 0) sMasked[slot >> 5] = (uint32_t)(m >> (lane & 32)) != 0u;
+    }
 
     bf16x8 qb[8];
     {
@@ -129,7 +140,9 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
             const int pos = max(rows.pos[i], 0);
             const int slot = lane & 15;
             const int chunk = is_v ? slot ^ ((key & 3) << 2) : slot ^ (key & 15);
-            const uint16_t *src = (is_v ? vb + (int64_t)pos * a.v_st : kb + (int64_t)pos * a.k_st) + chunk * 8;
+            const uint16_t *src;
+            if (WIDE) src = (is_v ? vb + (int64_t)pos * a.v_st : kb + (int64_t)pos * a.k_st) + chunk * 8;
+            else src = (is_v ? vb : kb) + (__umul24((uint32_t)pos, (uint32_t)(is_v ? a.v_st : a.k_st)) + (uint32_t)(chunk * 8));
             const uint32_t dst = __builtin_amdgcn_readfirstlane(
                 (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)(stage + j * 4 * kD));
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
@@ -151,10 +164,8 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
         return s;
     };
     // softmax update of a tile's scores: P (bf16) for the second product, running sum, rescale
-    auto softmax = [&](int tile, f32x16 &s, bf16x8 (&pb)[2]) {
-        // a tile needs masking if it has an empty slot or a key at or after the block's first query
-        const int myp = sPos[tile * kPfTile + n];
-        if (__any(myp < 0 || myp >= qpos0)) {
+    auto softmax = [&](int tile, bool masked, f32x16 &s, bf16x8 (&pb)[2]) {
+        if (masked) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int kp = sPos[tile * kPfTile + 8 * (r >> 2) + 4 * half + (r & 3)];
@@ -240,14 +251,16 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     __syncthreads();
     f32x16 s_nxt = scores(0);
     bf16x8 pb[2];
-    softmax(0, s_nxt, pb);
+    softmax(0, sMasked[0] != 0, s_nxt, pb);
+    int masked_nxt = n_tiles > 1 ? sMasked[1] : 0;      // read a period ahead, like the row positions
     // one tile period; ST = tile % kPfStages
     auto period = [&](auto st_c, int tile) {
         constexpr int ST = decltype(st_c)::value;
         request(tile + D, ST + D, rows);
         if (tile + 1 < n_tiles) s_nxt = scores(ST + 1);
         accumulate(ST, pb);
-        if (tile + 1 < n_tiles) softmax(tile + 1, s_nxt, pb);
+        if (tile + 1 < n_tiles) softmax(tile + 1, masked_nxt != 0, s_nxt, pb);
+        masked_nxt = tile + 2 < n_tiles ? sMasked[tile + 2] : 0;
         rows = rows_of(tile + D + 1);
         landed(tile + D >= n_tiles);        // tile + 2
         __syncthreads();
@@ -286,30 +299,38 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
         a.out_lse[row] = (m_run + log2f(l)) * 0.69314718055994530942f;
 }
 
-void launch_attn_prefill32(const AttnPrefillArgs &a, int P, hipStream_t st)
+void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len, hipStream_t st)
 {
     const int NQ = a.ge.b_q / 32;
     const dim3 block_dim(64 * NQ * a.ge.G), grid(P);
     const int slots = (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile;
-    const size_t lds = (size_t)kPfStages * kPfStageEl * sizeof(uint16_t) + (size_t)slots * sizeof(int);
-#define IHIP_PF32(NQV, GV)                                                                               \
-    {                                                                                                    \
-        static bool attr_set = false;     /* allow more than 64 KiB of dynamic LDS, once per kernel */   \
-        if (!attr_set) {                                                                                 \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_prefill32_kernel<NQV, GV>),  \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, kPf32MaxLds);         \
-            attr_set = true;                                                                             \
-        }                                                                                                \
-        hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV>), grid, block_dim, lds, st, a);              \
+    const size_t lds = (size_t)kPfStages * kPfStageEl * sizeof(uint16_t) + (size_t)slots * sizeof(int) +
+                       slots / kPfTile;             // stages, slot positions, per-tile flags
+    const int64_t lim = (int64_t)1 << 31, lim24 = (int64_t)1 << 24;
+    const bool wide = max_seq_len >= lim24 || a.k_st < 0 || a.v_st < 0 || a.k_st >= lim24 || a.v_st >= lim24 ||
+                      max_seq_len * a.k_st + kD >= lim || max_seq_len * a.v_st + kD >= lim;
+#define IHIP_PF32(NQV, GV, WV)                                                                               \
+    {                                                                                                        \
+        static bool attr_set = false;     /* allow more than 64 KiB of dynamic LDS, once per kernel */       \
+        if (!attr_set) {                                                                                     \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_prefill32_kernel<NQV, GV, WV>),  \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kPf32MaxLds);             \
+            attr_set = true;                                                                                 \
+        }                                                                                                    \
+        hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV, WV>), grid, block_dim, lds, st, a);              \
     }
-#define IHIP_PF32_BY_G(NQV)             \
-    switch (a.ge.G) {                   \
-    case 1: IHIP_PF32(NQV, 1); break;   \
-    case 2: IHIP_PF32(NQV, 2); break;   \
-    case 4: IHIP_PF32(NQV, 4); break;   \
-    default: IHIP_PF32(NQV, 8); break;  \
+#define IHIP_PF32_BY_G(NQV, WV)             \
+    switch (a.ge.G) {                       \
+    case 1: IHIP_PF32(NQV, 1, WV); break;   \
+    case 2: IHIP_PF32(NQV, 2, WV); break;   \
+    case 4: IHIP_PF32(NQV, 4, WV); break;   \
+    default: IHIP_PF32(NQV, 8, WV); break;  \
     }
-    if (NQ == 1) { IHIP_PF32_BY_G(1) } else { IHIP_PF32_BY_G(2) }
+    if (wide) {
+        if (NQ == 1) { IHIP_PF32_BY_G(1, true) } else { IHIP_PF32_BY_G(2, true) }
+    } else {
+        if (NQ == 1) { IHIP_PF32_BY_G(1, false) } else { IHIP_PF32_BY_G(2, false) }
+    }
 #undef IHIP_PF32_BY_G
 #undef IHIP_PF32
 }
