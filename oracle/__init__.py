@@ -25,6 +25,10 @@ def build(force: bool = True) -> str:
     return _SO
 
 
+class Rope(ctypes.Structure):
+    _fields_ = [("cos", ctypes.c_void_p), ("sin", ctypes.c_void_p), ("n_pos", ctypes.c_int32)]
+
+
 class Tensors(ctypes.Structure):
     _fields_ = [("Q", ctypes.c_void_p), ("K", ctypes.c_void_p), ("V", ctypes.c_void_p),
                 ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
@@ -52,9 +56,20 @@ def lib():
         L.orc_sparse_attention.restype = None
         L.orc_sparse_attention.argtypes = [P(Tensors), c_i32, c_i32, c_i64, c_i32, c_i64, c_i64,
                                            c_i64, c_i32, vp, vp, c_d, vp, vp]
+        L.orc_score_rope.restype = c_f
+        L.orc_score_rope.argtypes = [P(Tensors), c_i32, c_i32, c_i64, c_i32, c_i64, P(Rope), vp, c_i64]
+        L.orc_select_rep_rope.restype = None
+        L.orc_select_rep_rope.argtypes = [P(Tensors), c_i32, c_i32, c_i64, c_i32, c_i64, c_i32, c_i32,
+                                          P(Rope), c_i32, vp, c_i64, P(c_i64), vp]
+        L.orc_prune_stage_rope.restype = None
+        L.orc_prune_stage_rope.argtypes = [P(Tensors), c_i32, c_i32, c_i64, c_i32, c_i64, c_i32, vp, vp,
+                                           c_i32, P(Rope), c_i32, c_i64, vp, vp, vp]
+        L.orc_sparse_attention_rope.restype = None
+        L.orc_sparse_attention_rope.argtypes = [P(Tensors), c_i32, c_i32, c_i64, c_i32, c_i64, c_i64,
+                                                c_i64, c_i32, vp, vp, c_d, P(Rope), vp, vp]
         _lib = L
     return _lib
 
 
-from .pipeline import Oracle, StageResult, ProblemResult  # noqa: E402,F401
+from .pipeline import Oracle, RopeSpec, StageResult, ProblemResult  # noqa: E402,F401
 from .lru import LruBank  # noqa: E402,F401

@@ -13,14 +13,16 @@
  *   orc_prune_stage      representative + chunk score per chunk        (Alg. 2, up to the arg-top-K)
  *   orc_topk             arg-top-K of the chunk scores                  (Alg. 2, arg top_{k/l_c})
  *   orc_sparse_attention softmax attention over sink + kept blocks + window (Sec. 4 "Background", BSA of Alg. 4)
+ *   orc_*_rope           the same steps with dynamic RoPE (Sec. 4 "Dynamic RoPE ..."; second half of this file)
  *
  * Conventions (the paper is silent or garbled on these; same readings as the
  * design notes list): 0-based positions; chunk sizes are powers of two; the
  * two halves of a range are [first, first+size/2) and [first+size/2, last];
  * ties keep the left branch / the lowest index; a chunk that is cut short by
- * the end of the middle range scores -inf for positions past its end; RoPE
- * adjustment is off; with RoPE off the left branch's first key is the previous
- * winner, so its score is carried over instead of being recomputed.
+ * the end of the middle range scores -inf for positions past its end.  In the
+ * first half of the file RoPE adjustment is off; with RoPE off the left
+ * branch's first key is the previous winner, so its score is carried over
+ * instead of being recomputed.
  * Scores that decide a selection are fp32 (bf16 inputs, fp32 products and
  * sums, summed in index order); the attention itself is fp64.
  *
@@ -239,4 +241,187 @@ void orc_sparse_attention(const orc_tensors *t, int b, int g, int64_t q0, int bq
     }
     free(keys);
     free(s);
+}
+
+/* ===========================================================================
+ * Dynamic RoPE (Sec. 4 "Dynamic RoPE for OOL generalization"; the ApplyRopeQ /
+ * ApplyRopeK definitions after Alg. 3).  Q and K are stored without positional
+ * rotation; the pruning stages and the attention rotate them on the fly with
+ * position ids of their own choosing.
+ *
+ * Readings (the paper cites RoFormer for ApplyRope and is terse on the ids):
+ *  - ApplyRope(x, p_i): dims (2j, 2j+1) form a pair that is turned by the angle
+ *    of position i at frequency j; the table gives cos and sin of that angle,
+ *    rope->cos[i*(d/2) + j], rope->sin[...].
+ *  - Relative style (layers after the third): the query block is at position
+ *    n_stream + 1; in SelectRep the left branch's key is at position 0 and the
+ *    right branch's at position 1; the chunk score puts the representative at
+ *    position 1 (ApplyRopeK_{l,2}).  The two branches use different positions,
+ *    so both scores are computed at every iteration (no carried score).
+ *  - Chunk-indexed style (first three layers): every key of chunk j of the
+ *    stage's chunk list (0-based, in position order) is at position j; query t
+ *    of the block is at min(original position, (n_chunk - 1) + n_stream), i.e.
+ *    the last chunk is n_stream behind the query.
+ *  - Streaming style (attention): the keys a query attends to, in position
+ *    order, are at positions 0, 1, ..., n-1 and the query at n-1 (the position
+ *    of the most recent key, which is the query's own token).
+ * Rotations for the selection scores are fp32 (products and sums rounded one
+ * by one), the attention is fp64 throughout.
+ * =========================================================================== */
+typedef struct {
+    const float *cos, *sin;     /* [n_pos][d/2] */
+    int32_t n_pos;
+} orc_rope;
+
+static void rope_f32(const uint16_t *x, const orc_rope *r, int64_t pos, int d, float *out)
+{
+    const float *c = r->cos + pos * (d / 2), *s = r->sin + pos * (d / 2);
+    for (int j = 0; j < d / 2; ++j) {
+        const float a = bf16_to_f32(x[2 * j]), b = bf16_to_f32(x[2 * j + 1]);
+        out[2 * j] = a * c[j] - b * s[j];
+        out[2 * j + 1] = a * s[j] + b * c[j];
+    }
+}
+
+/* max over the block's queries t of ApplyRope(q_t, qpos[t]) . ApplyRope(k_p, kpos)   (fp32) */
+float orc_score_rope(const orc_tensors *t, int b, int h, int64_t q0, int bq, int64_t p,
+                     const orc_rope *rope, const int64_t *qpos, int64_t kpos)
+{
+    const int g = h / (t->Hq / t->Hkv), d = t->d;
+    float *kr = malloc(sizeof(float) * d), *qr = malloc(sizeof(float) * d);
+    rope_f32(k_row(t, b, g, p), rope, kpos, d, kr);
+    float best = -INFINITY;
+    for (int i = 0; i < bq; ++i) {
+        rope_f32(q_row(t, b, h, q0 + i), rope, qpos[i], d, qr);
+        float acc = 0.0f;
+        for (int c = 0; c < d; ++c) acc += qr[c] * kr[c];
+        if (acc > best) best = acc;
+    }
+    free(kr);
+    free(qr);
+    return best;
+}
+
+/*
+ * SelectRep (Alg. 3) with ApplyRopeQ / ApplyRopeK: style 1 = relative (branch j's
+ * key at position j-1), style 2 = chunk-indexed (both branches' keys at
+ * position chunk_index).  Same halving, tie and ragged-end rules as
+ * orc_select_rep; both branches are scored at every iteration.
+ */
+void orc_select_rep_rope(const orc_tensors *t, int b, int h, int64_t q0, int bq,
+                         int64_t start, int len, int l_c, const orc_rope *rope, int style,
+                         const int64_t *qpos, int64_t chunk_index, int64_t *r_out, uint8_t *touched)
+{
+    int off = 0, size = l_c;
+    if (touched) touched[start] = 1;
+    while (size > 1) {
+        const int half = size / 2, mid = off + half;
+        const int64_t pos_left = style == 1 ? 0 : chunk_index, pos_right = style == 1 ? 1 : chunk_index;
+        const float sigma_left = orc_score_rope(t, b, h, q0, bq, start + off, rope, qpos, pos_left);
+        float sigma_right = -INFINITY;
+        if (mid < len) {
+            sigma_right = orc_score_rope(t, b, h, q0, bq, start + mid, rope, qpos, pos_right);
+            if (touched) touched[start + mid] = 1;
+        }
+        if (sigma_right > sigma_left) off = mid;    /* strict: a tie keeps the left half */
+        size = half;
+    }
+    *r_out = start + off;
+}
+
+/*
+ * One pruning stage (Alg. 2) with dynamic RoPE.  pos0 = original position of
+ * the block's first query.  The chunk score rotates the representative as
+ * branch 2 (relative: position 1; chunk-indexed: its chunk's index).
+ */
+void orc_prune_stage_rope(const orc_tensors *t, int b, int g, int64_t q0, int bq, int64_t pos0,
+                          int n_chunk, const int64_t *starts, const int32_t *lens, int l_c,
+                          const orc_rope *rope, int style, int64_t n_stream,
+                          float *score, int64_t *rep, uint8_t *touched)
+{
+    const int G = t->Hq / t->Hkv;
+    int64_t *qpos = malloc(sizeof(int64_t) * bq);
+    for (int i = 0; i < bq; ++i) {
+        if (style == 1) qpos[i] = n_stream + 1;
+        else {
+            const int64_t cap = (int64_t)(n_chunk - 1) + n_stream;
+            qpos[i] = pos0 + i < cap ? pos0 + i : cap;
+        }
+    }
+    for (int j = 0; j < n_chunk; ++j) {
+        float s = -INFINITY;
+        for (int hh = 0; hh < G; ++hh) {
+            int64_t r;
+            orc_select_rep_rope(t, b, g * G + hh, q0, bq, starts[j], lens[j], l_c, rope, style,
+                                qpos, j, &r, touched);
+            if (rep) rep[(int64_t)hh * n_chunk + j] = r;
+            const float sigma = orc_score_rope(t, b, g * G + hh, q0, bq, r, rope, qpos, style == 1 ? 1 : j);
+            if (sigma > s) s = sigma;
+        }
+        score[j] = s;
+    }
+    free(qpos);
+}
+
+/*
+ * orc_sparse_attention with streaming-style positions: key a of a query's key
+ * list (position order) is rotated to position a, the query to position n-1.
+ */
+void orc_sparse_attention_rope(const orc_tensors *t, int b, int g, int64_t q0, int bq,
+                               int64_t pos0, int64_t n_sink, int64_t w0,
+                               int n_blocks, const int64_t *block_starts,
+                               const int32_t *block_lens, double scale, const orc_rope *rope,
+                               double *out, double *lse)
+{
+    const int G = t->Hq / t->Hkv, d = t->d;
+    int64_t cap = n_sink + (pos0 + bq - w0 > 0 ? pos0 + bq - w0 : 0) + 1;
+    for (int i = 0; i < n_blocks; ++i) cap += block_lens[i];
+    int64_t *keys = malloc(sizeof(int64_t) * cap);
+    double *s = malloc(sizeof(double) * cap);
+    double *qr = malloc(sizeof(double) * d), *kr = malloc(sizeof(double) * d);
+
+    for (int hh = 0; hh < G; ++hh) {
+        for (int i = 0; i < bq; ++i) {
+            const int64_t p = pos0 + i;
+            int64_t n = 0;
+            for (int64_t x = 0; x < n_sink && x <= p; ++x) keys[n++] = x;
+            for (int j = 0; j < n_blocks; ++j)
+                for (int c = 0; c < block_lens[j]; ++c) keys[n++] = block_starts[j] + c;
+            for (int64_t x = w0; x <= p; ++x) keys[n++] = x;
+
+            const uint16_t *q = q_row(t, b, g * G + hh, q0 + i);
+            const float *cq = rope->cos + (n - 1) * (d / 2), *sq = rope->sin + (n - 1) * (d / 2);
+            for (int j = 0; j < d / 2; ++j) {
+                const double x0 = bf16_to_f32(q[2 * j]), x1 = bf16_to_f32(q[2 * j + 1]);
+                qr[2 * j] = x0 * cq[j] - x1 * sq[j];
+                qr[2 * j + 1] = x0 * sq[j] + x1 * cq[j];
+            }
+            double mx = -INFINITY;
+            for (int64_t a = 0; a < n; ++a) {
+                const uint16_t *k = k_row(t, b, g, keys[a]);
+                const float *ck = rope->cos + a * (d / 2), *sk = rope->sin + a * (d / 2);
+                double acc = 0.0;
+                for (int j = 0; j < d / 2; ++j) {
+                    const double x0 = bf16_to_f32(k[2 * j]), x1 = bf16_to_f32(k[2 * j + 1]);
+                    kr[2 * j] = x0 * ck[j] - x1 * sk[j];
+                    kr[2 * j + 1] = x0 * sk[j] + x1 * ck[j];
+                }
+                for (int c = 0; c < d; ++c) acc += qr[c] * kr[c];
+                s[a] = scale * acc;
+                if (s[a] > mx) mx = s[a];
+            }
+            double denom = 0.0;
+            double *o = out + ((int64_t)hh * bq + i) * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            for (int64_t a = 0; a < n; ++a) {
+                const double w = exp(s[a] - mx);
+                const uint16_t *v = v_row(t, b, g, keys[a]);
+                denom += w;
+                for (int c = 0; c < d; ++c) o[c] += w * (double)bf16_to_f32(v[c]);
+            }
+            for (int c = 0; c < d; ++c) o[c] /= denom;
+            if (lse) lse[(int64_t)hh * bq + i] = mx + log(denom);
+        }
+    }
+    free(keys); free(s); free(qr); free(kr);
 }

@@ -70,6 +70,17 @@ class ProblemResult:
         return self.stages[-1].kept_lens if self.stages else np.zeros(0, np.int32)
 
 
+@dataclass
+class RopeSpec:
+    """Dynamic RoPE (Sec. 4 "Dynamic RoPE for OOL generalization").  cos / sin:
+    float32 [n_pos, d/2], cos and sin of (position x frequency j's angle);
+    prune: None, "relative" or "chunk"; attn: None or "streaming"."""
+    cos: np.ndarray
+    sin: np.ndarray
+    prune: Optional[str] = None
+    attn: Optional[str] = None
+
+
 def stage1_chunks(lo: int, hi: int, l_c: int):
     """Alg. 1 step 1 + Alg. 2 chunking: the middle range [lo, hi) cut into
     l_c-sized chunks, the last one cut short if the range is ragged."""
@@ -96,9 +107,15 @@ class Oracle:
     shape; runs pruning and attention problem by problem."""
 
     def __init__(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens,
-                 b_q: int, n_sink: int, n_stream: int):
-        from . import lib, Tensors
+                 b_q: int, n_sink: int, n_stream: int, rope: Optional[RopeSpec] = None):
+        from . import lib, Tensors, Rope
         self.L = lib()
+        self.rope = rope
+        if rope is not None:
+            self._cos = np.ascontiguousarray(rope.cos, np.float32)
+            self._sin = np.ascontiguousarray(rope.sin, np.float32)
+            assert self._cos.shape == self._sin.shape and self._cos.shape[1] * 2 == q.shape[-1]
+            self._rope = Rope(self._cos.ctypes.data, self._sin.ctypes.data, self._cos.shape[0])
         self.q, self.k, self.v = _u16(q), _u16(k), _u16(v)
         self.B, self.Hq, self.Tq, self.d = q.shape
         _, self.Hkv, self.T_alloc, _ = k.shape
@@ -126,9 +143,19 @@ class Oracle:
         touched = np.zeros(self.T_alloc, np.uint8)
         starts = np.ascontiguousarray(starts, np.int64)
         lens = np.ascontiguousarray(lens, np.int32)
-        self.L.orc_prune_stage(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q, n,
-                               _p(starts), _p(lens), l_c, int(exhaustive),
-                               _p(scores), _p(reps), _p(touched))
+        if self.rope is not None and self.rope.prune is not None:
+            assert not exhaustive
+            style = {"relative": 1, "chunk": 2}[self.rope.prune]
+            E = self.ranges(b, m)[2]
+            need = self.n_stream + 2 if style == 1 else n + self.n_stream
+            assert self._cos.shape[0] >= need, "RoPE table too short"
+            self.L.orc_prune_stage_rope(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q, E - self.b_q, n,
+                                        _p(starts), _p(lens), l_c, ctypes.byref(self._rope), style,
+                                        self.n_stream, _p(scores), _p(reps), _p(touched))
+        else:
+            self.L.orc_prune_stage(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q, n,
+                                   _p(starts), _p(lens), l_c, int(exhaustive),
+                                   _p(scores), _p(reps), _p(touched))
         ids = np.empty(max(min(keep, n), 1), np.int32)
         kept = self.L.orc_topk(n, _p(scores), keep, _p(ids))
         return StageResult(l_c, starts, lens, scores, reps, ids[:kept].copy(), np.nonzero(touched)[0].astype(np.int64))
@@ -186,9 +213,17 @@ class Oracle:
         bl = np.ascontiguousarray(block_lens, np.int32)
         if len(bs):
             assert bs.min() >= lo and (bs + bl).max() <= hi
-        self.L.orc_sparse_attention(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q,
-                                    E - self.b_q, self.n_sink, max(hi, self.n_sink),
-                                    len(bs), _p(bs), _p(bl), scale, _p(out), _p(lse))
+        if self.rope is not None and self.rope.attn is not None:
+            assert self.rope.attn == "streaming"
+            assert self._cos.shape[0] >= self.attended_tokens(b, m, bl), "RoPE table too short"
+            self.L.orc_sparse_attention_rope(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q,
+                                             E - self.b_q, self.n_sink, max(hi, self.n_sink),
+                                             len(bs), _p(bs), _p(bl), scale, ctypes.byref(self._rope),
+                                             _p(out), _p(lse))
+        else:
+            self.L.orc_sparse_attention(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q,
+                                        E - self.b_q, self.n_sink, max(hi, self.n_sink),
+                                        len(bs), _p(bs), _p(bl), scale, _p(out), _p(lse))
         return out, lse
 
     def attended_positions(self, b, m, block_starts, block_lens) -> np.ndarray:

@@ -151,3 +151,21 @@ def zipf_ranks(seed, tensor_id, n, modulus, exponent=1.1) -> torch.Tensor:
     cdf = cdf / cdf[-1]
     u = (uniform_ints(seed, tensor_id, n, 1 << 24).to(torch.float64) + 0.5) / float(1 << 24)
     return torch.searchsorted(cdf, u).clamp_(max=modulus - 1)
+
+
+def rope_table(n_pos: int, d: int, base: float = 10000.0, device="cpu"):
+    """cos / sin (float32 [n_pos, d/2]) of position i times the angle base**(-2j/d) of frequency j:
+    the rotary-embedding table of Su et al. for head dimension d."""
+    j = torch.arange(d // 2, dtype=torch.float64)
+    ang = torch.arange(n_pos, dtype=torch.float64).view(-1, 1) * base ** (-2.0 * j / d).view(1, -1)
+    return ang.cos().to(torch.float32).to(device), ang.sin().to(torch.float32).to(device)
+
+
+def quarter_turn_table(n_pos: int, d: int, device="cpu"):
+    """A rotary table whose angles are whole quarter turns (frequency j turns (j+1) quarters per
+    position), so cos and sin are exactly 0 or +-1 and rotating integer-valued vectors stays exact."""
+    j = torch.arange(d // 2, dtype=torch.int64).view(1, -1)
+    q = (torch.arange(n_pos, dtype=torch.int64).view(-1, 1) * (j + 1)) % 4
+    cos = torch.tensor([1.0, 0.0, -1.0, 0.0])[q]
+    sin = torch.tensor([0.0, 1.0, 0.0, -1.0])[q]
+    return cos.to(torch.float32).to(device), sin.to(torch.float32).to(device)
