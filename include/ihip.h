@@ -62,6 +62,38 @@ typedef struct {
     int32_t n_sink, n_stream;
 } ihip_shape;
 
+/*
+ * Dynamic RoPE (Sec. 4 "Dynamic RoPE for OOL generalization"; ApplyRopeQ /
+ * ApplyRopeK after Alg. 3).  With it, Q and K are stored without positional
+ * rotation and the kernels rotate them on the fly with position ids of the
+ * method's own choosing.  cos / sin: device fp32 [n_pos][d/2], cos and sin of
+ * (position i) x (angle of frequency j), the table of Su et al.; dims (2j, 2j+1)
+ * of a vector form pair j.  The kernels rely on the table being one of true
+ * rotations (they fold R(a)q . R(b)k into R(a-b)q . k).
+ *   prune_style  IHIP_ROPE_RELATIVE: the query at n_stream+1, a left-branch key of
+ *                SelectRep at 0, a right-branch key and the representative in the
+ *                chunk score at 1 (needs n_pos >= n_stream + 2).
+ *                IHIP_ROPE_CHUNK_INDEXED: every key of chunk j (index in the stage's
+ *                list of non-empty chunks) at j, the query at min(its own position,
+ *                n_chunk - 1 + n_stream) (needs n_pos >= max_chunks + n_stream).
+ *   attn_style   IHIP_ROPE_STREAMING: the keys a query attends to, in position
+ *                order, at 0..n-1, the query at n-1 (needs n_pos >= n_sink +
+ *                n_blocks*block + n_stream).
+ * Built for decode (Tq == b_q == 1) from device memory; other uses return
+ * IHIP_ERR_UNSUPPORTED.
+ */
+#define IHIP_ROPE_NONE          0
+#define IHIP_ROPE_RELATIVE      1
+#define IHIP_ROPE_CHUNK_INDEXED 2
+#define IHIP_ROPE_STREAMING     1
+typedef struct ihip_rope {
+    const float *cos;
+    const float *sin;
+    int32_t n_pos;
+    int32_t prune_style;         /* IHIP_ROPE_NONE / _RELATIVE / _CHUNK_INDEXED */
+    int32_t attn_style;          /* IHIP_ROPE_NONE / _STREAMING */
+} ihip_rope;
+
 /* Operation ids for ihip_workspace_bytes. */
 #define IHIP_OP_ATTN_DECODE   1
 #define IHIP_OP_ATTN_PREFILL  2
@@ -95,6 +127,12 @@ int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                          const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
                          int32_t chunk, int32_t max_chunks,
                          float *out_scores, int32_t *out_rep, void *stream);
+
+/* ihip_prune_stage with rope->prune_style applied (decode only); rope must not be NULL. */
+int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
+                              const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                              int32_t chunk, int32_t max_chunks, const ihip_rope *rope,
+                              float *out_scores, int32_t *out_rep, void *stream);
 
 /* Slots the first stage needs per problem: ceil((max_seq_len - n_stream - n_sink) / chunk), >= 0. */
 int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk);
@@ -130,6 +168,12 @@ int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_ten
                                 float sm_scale, void *out, float *out_lse,
                                 void *ws, size_t ws_bytes, void *stream);
 
+/* ihip_sparse_attn_decode with rope->attn_style applied to q and K (V is not rotated). */
+int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                     const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                     float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                     void *ws, size_t ws_bytes, void *stream);
+
 /*
  * Block-sparse chunked-prefill attention: the same key set per query block m,
  * every query of the block attending causally inside the window (keys after
@@ -163,6 +207,12 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                           int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                           float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
                           void *ws, size_t ws_bytes, void *stream);
+
+/* ihip_decode_layer with dynamic RoPE in every pruning stage and in the attention. */
+int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                               int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                               float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                               int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Decode layer with per-stage mask caching (Sec. 4 "Sparse Attention Mask

@@ -39,6 +39,12 @@ class Shape(ctypes.Structure):
 EXPORTS = {
     "ihip_prune_stage": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, vp, c_i32, c_i32, c_i32, c_i32,
                                  vp, vp, vp]),
+    "ihip_prune_stage_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, vp, c_i32, c_i32, c_i32, c_i32,
+                                      vp, vp, vp, vp]),
+    "ihip_sparse_attn_decode_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
+                                             c_f, vp, vp, vp, vp, c_sz, vp]),
+    "ihip_decode_layer_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
+                                       vp, vp, vp, vp, c_sz, vp]),
     "ihip_stage1_slots": (c_i32, [ctypes.POINTER(Shape), c_i32]),
     "ihip_select_blocks": (c_i32, [ctypes.POINTER(Shape), vp, c_i32, vp, c_i32, c_i32, c_i32, c_i32,
                                    vp, vp]),
@@ -137,6 +143,30 @@ def mfma_rate(kind: int, iters: int = 20000) -> float:
     return out.value
 
 
+ROPE_NONE, ROPE_RELATIVE, ROPE_CHUNK_INDEXED, ROPE_STREAMING = 0, 1, 2, 1
+
+
+class RopeStruct(ctypes.Structure):
+    _fields_ = [("cos", vp), ("sin", vp), ("n_pos", c_i32), ("prune_style", c_i32), ("attn_style", c_i32)]
+
+
+class Rope:
+    """ihip_rope: device fp32 cos / sin tables [n_pos, d/2] and the styles to apply."""
+
+    def __init__(self, cos: torch.Tensor, sin: torch.Tensor, prune_style: int = ROPE_NONE,
+                 attn_style: int = ROPE_NONE):
+        for t in (cos, sin):
+            if t.dtype != torch.float32 or t.dim() != 2 or not t.is_cuda or not t.is_contiguous():
+                raise IhipError("rope tables: need contiguous 2-d fp32 device tensors")
+        if cos.shape != sin.shape:
+            raise IhipError("rope tables: cos and sin differ in shape")
+        self.cos, self.sin = cos, sin          # keep the tables alive
+        self.c = RopeStruct(cos.data_ptr(), sin.data_ptr(), cos.shape[0], prune_style, attn_style)
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
 class Layer:
     """Shape of one attention call plus the device seq_lens; the methods are
     the C entry points of the same names."""
@@ -175,7 +205,7 @@ class Layer:
 
     # -- entry points -------------------------------------------------------
     def prune_stage(self, q, k, chunk: int, parent_starts: Optional[torch.Tensor] = None,
-                    parent_chunk: int = 0, want_rep: bool = False):
+                    parent_chunk: int = 0, want_rep: bool = False, rope: Optional["Rope"] = None):
         """-> scores fp32 [P, slots], rep int32 [B,Hq,Mq,slots] or None."""
         if parent_starts is None:
             n_parent, slots = 0, self.stage1_slots(chunk)
@@ -185,6 +215,11 @@ class Layer:
         scores = torch.empty((self.P, slots), dtype=torch.float32, device=self.device)
         rep = torch.empty((self.B, self.Hq, self.Tq // self.b_q, slots), dtype=torch.int32,
                           device=self.device) if want_rep else None
+        if rope is not None:
+            _check(lib().ihip_prune_stage_rope(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                               _ptr(parent_starts), n_parent, parent_chunk, chunk, slots,
+                                               rope.ref(), _ptr(scores), _ptr(rep), _stream()))
+            return scores, rep
         _check(lib().ihip_prune_stage(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                       _ptr(parent_starts), n_parent, parent_chunk, chunk, slots,
                                       _ptr(scores), _ptr(rep), _stream()))
@@ -213,7 +248,13 @@ class Layer:
                   ws.numel(), _stream()))
         return out, lse
 
-    def sparse_attn_decode(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None):
+    def sparse_attn_decode(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None,
+                           rope: Optional["Rope"] = None):
+        if rope is not None:
+            def fn(shape, tq, tk, tv, bs, n_blocks, blk, scale, out, lse, w, w_bytes, stream):
+                return lib().ihip_sparse_attn_decode_rope(shape, tq, tk, tv, bs, n_blocks, blk, scale, rope.ref(),
+                                                          out, lse, w, w_bytes, stream)
+            return self._attn(fn, OP_ATTN_DECODE, q, k, v, block_starts, block, sm_scale, want_lse, ws)
         return self._attn(lib().ihip_sparse_attn_decode, OP_ATTN_DECODE, q, k, v, block_starts, block,
                           sm_scale, want_lse, ws)
 
@@ -233,13 +274,19 @@ class Layer:
         return out
 
     def decode_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
-                     out_blocks=None, lse=None):
+                     out_blocks=None, lse=None, rope: Optional["Rope"] = None):
         """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d]."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+        if rope is not None:
+            _check(lib().ihip_decode_layer_rope(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                                _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                                sm_scale, rope.ref(), _ptr(out), _ptr(lse), _ptr(out_blocks),
+                                                _ptr(ws), ws.numel(), _stream()))
+            return out
         _check(lib().ihip_decode_layer(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                        _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
                                        sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libihip.so")
-SOURCES = ["api.hip", "prune_stage.hip", "select_blocks.hip", "sparse_attn_decode.hip",
+SOURCES = ["api.hip", "prune_stage.hip", "prune_stage_rope.hip", "select_blocks.hip", "sparse_attn_decode.hip",
            "sparse_attn_prefill.hip", "sparse_attn_prefill32.hip", "cache.hip", "mfma_rate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -74,12 +74,12 @@ void profile_end(hipStream_t st)
 
 // kernels' host launchers
 int32_t launch_prune_stage(const ihip_shape &, const ihip_tensor &, const ihip_tensor &, const int32_t *,
-                           int, int, int, int, float *, int32_t *, const BankView *, hipStream_t);
+                           int, int, int, int, float *, int32_t *, const BankView *, const ihip_rope *, hipStream_t);
 int32_t launch_select_blocks(const ihip_shape &, const float *, int, const int32_t *, int, int, int, int,
                              int32_t *, hipStream_t);
 int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                            const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
-                           void *, const BankView *, hipStream_t);
+                           void *, const BankView *, const ihip_rope *, hipStream_t);
 BankView cache_bank_view(const ihip_cache *, int);
 void cache_describe(const ihip_cache *, int32_t *, int32_t *, int64_t *, ihip_tensor *, ihip_tensor *);
 size_t attn_decode_workspace(const ihip_shape &, int, int);
@@ -191,7 +191,8 @@ static PlanLayout plan_layout(const ihip_shape &s, int n_stages, const int32_t *
 // (a cached mask, Alg. 4).
 static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                                  const int32_t *chunks, const int32_t *keeps, int first_stage,
-                                 int32_t *const *stage_out, float *scores, const BankView *bank, hipStream_t st)
+                                 int32_t *const *stage_out, float *scores, const BankView *bank,
+                                 const ihip_rope *rope, hipStream_t st)
 {
     for (int i = first_stage; i < n_stages; ++i) {
         const int32_t *parents = i == 0 ? nullptr : stage_out[i - 1];
@@ -199,7 +200,7 @@ static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, cons
         const int parent_chunk = i == 0 ? 0 : chunks[i - 1];
         const int slots = i == 0 ? stage1_slots(s, chunks[0]) : n_parent * (parent_chunk / chunks[i]);
         int32_t rc = launch_prune_stage(s, q, k, parents, n_parent, parent_chunk, chunks[i], slots, scores,
-                                        nullptr, bank, st);
+                                        nullptr, bank, rope, st);
         if (rc != IHIP_OK) return rc;
         rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i],
                                   stage_out[i], st);
@@ -210,13 +211,13 @@ static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, cons
 
 static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                               const int32_t *chunks, const int32_t *keeps, int32_t *out_block_starts,
-                              char *ws, const BankView *bank, hipStream_t st)
+                              char *ws, const BankView *bank, const ihip_rope *rope, hipStream_t st)
 {
     const PlanLayout L = plan_layout(s, n_stages, chunks, keeps);
     int32_t *stage_out[8];
     for (int i = 0; i < n_stages; ++i)
         stage_out[i] = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
-    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, st);
+    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, rope, st);
 }
 
 }  // namespace ihip
@@ -244,11 +245,10 @@ int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk)
     return stage1_slots(*shape, chunk);
 }
 
-int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
+static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
                          int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
                          float *out_scores, int32_t *out_rep, void *stream)
 {
-    const char *who = "ihip_prune_stage";
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
@@ -261,7 +261,24 @@ int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, 
     if (shape->b_q == 1 && shape->Tq != 1)
         return fail(IHIP_ERR_INVALID_ARG, "%s: b_q == 1 is the decode path and needs Tq == 1", who);
     return launch_prune_stage(*shape, q, k, parent_starts, n_parent, parent_chunk, chunk, max_chunks, out_scores,
-                              out_rep, nullptr, (hipStream_t)stream);
+                              out_rep, nullptr, rope, (hipStream_t)stream);
+}
+
+int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
+                         int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
+                         float *out_scores, int32_t *out_rep, void *stream)
+{
+    return prune_stage_entry("ihip_prune_stage", nullptr, shape, q, k, parent_starts, n_parent, parent_chunk, chunk,
+                             max_chunks, out_scores, out_rep, stream);
+}
+
+int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
+                              int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
+                              const ihip_rope *rope, float *out_scores, int32_t *out_rep, void *stream)
+{
+    if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_prune_stage_rope: rope is NULL");
+    return prune_stage_entry("ihip_prune_stage_rope", rope, shape, q, k, parent_starts, n_parent, parent_chunk, chunk,
+                             max_chunks, out_scores, out_rep, stream);
 }
 
 int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
@@ -280,11 +297,10 @@ int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t
                                 out_starts, (hipStream_t)stream);
 }
 
-int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                 const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
                                 void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
 {
-    const char *who = "ihip_sparse_attn_decode";
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
@@ -298,7 +314,25 @@ int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_ten
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     return launch_attn_decode(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, ws,
-                              nullptr, (hipStream_t)stream);
+                              nullptr, rope, (hipStream_t)stream);
+}
+
+int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
+                                void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    return attn_decode_entry("ihip_sparse_attn_decode", nullptr, shape, q, k, v, block_starts, n_blocks, block,
+                             sm_scale, out, out_lse, ws, ws_bytes, stream);
+}
+
+int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                     const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
+                                     const ihip_rope *rope, void *out, float *out_lse, void *ws, size_t ws_bytes,
+                                     void *stream)
+{
+    if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_sparse_attn_decode_rope: rope is NULL");
+    return attn_decode_entry("ihip_sparse_attn_decode_rope", rope, shape, q, k, v, block_starts, n_blocks, block,
+                             sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
 int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
@@ -335,12 +369,12 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, in
     const size_t need = plan_layout(*shape, n_stages, chunk_sizes, keeps).total;
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
-    return prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, out_block_starts, (char *)ws, nullptr,
+    return prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, out_block_starts, (char *)ws, nullptr, nullptr,
                           (hipStream_t)stream);
 }
 
 static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
-                                 ihip_tensor v, const ihip_cache *cache, int32_t n_stages,
+                                 ihip_tensor v, const ihip_cache *cache, const ihip_rope *rope, int32_t n_stages,
                                  const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                                  float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
@@ -364,19 +398,30 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
     BankView mask_bank, sa_bank;
     if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
-    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, cache ? &mask_bank : nullptr,
+    if (cache && rope) return fail(IHIP_ERR_UNSUPPORTED, "%s: dynamic RoPE is not built for the host tier", who);
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, cache ? &mask_bank : nullptr, rope,
                         (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_decode(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
-                              w + L.total + blocks_bytes, cache ? &sa_bank : nullptr, (hipStream_t)stream);
+                              w + L.total + blocks_bytes, cache ? &sa_bank : nullptr, rope, (hipStream_t)stream);
 }
 
 int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
                           const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                           float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
-    return decode_layer_impl("ihip_decode_layer", shape, q, k, v, nullptr, n_stages, chunk_sizes, keeps, sm_scale,
-                             out, out_lse, out_block_starts, ws, ws_bytes, stream);
+    return decode_layer_impl("ihip_decode_layer", shape, q, k, v, nullptr, nullptr, n_stages, chunk_sizes, keeps,
+                             sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                               const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, const ihip_rope *rope,
+                               void *out, float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes,
+                               void *stream)
+{
+    if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_decode_layer_rope: rope is NULL");
+    return decode_layer_impl("ihip_decode_layer_rope", shape, q, k, v, nullptr, rope, n_stages, chunk_sizes, keeps,
+                             sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
 int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache, int32_t n_stages,
@@ -393,7 +438,7 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
     if (shape && (shape->B != B || shape->Hkv != Hkv || shape->max_seq_len > T_alloc))
         return fail(IHIP_ERR_INVALID_ARG, "%s: shape (B %d, Hkv %d, max_seq_len %d) does not fit the cache (%d, %d, %lld)",
                     who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
-    return decode_layer_impl(who, shape, q, hk, hv, cache, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
+    return decode_layer_impl(who, shape, q, hk, hv, cache, nullptr, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
                              out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -433,10 +478,10 @@ int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_te
     size_t off = 0;
     for (int i = 0; i < n_stages; ++i) { stage_out[i] = stage_starts + off; off += P * (size_t)keeps[i]; }
     rc = prune_stages_impl(*shape, q, k, n_stages, chunk_sizes, keeps, first_stage, stage_out, (float *)ws, nullptr,
-                           (hipStream_t)stream);
+                           nullptr, (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_decode(*shape, q, k, v, stage_out[last], keeps[last], chunk_sizes[last], sm_scale, out,
-                              out_lse, (char *)ws + L.scores_bytes, nullptr, (hipStream_t)stream);
+                              out_lse, (char *)ws + L.scores_bytes, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
@@ -462,7 +507,7 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
-    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, (hipStream_t)stream);
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, nullptr, (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
                                (hipStream_t)stream);

@@ -1,0 +1,44 @@
+// Arguments of the pruning-stage kernels (Alg. 2 / Alg. 3), shared by the plain and the
+// dynamic-RoPE translation units.
+#pragma once
+
+#include "common.h"
+
+namespace ihip {
+
+// Rotary table handed in by the caller: cos and sin of (position x angle of frequency j),
+// fp32 [n_pos][d/2].
+struct RopeView {
+    const float *cos, *sin;
+    int n_pos;
+};
+
+struct PruneArgs {
+    Geometry ge;
+    const uint16_t *q; int64_t q_sb, q_sh, q_st;
+    const uint16_t *k; int64_t k_sb, k_sh, k_st;
+    const int32_t *parent_starts;
+    int n_parent, ratio_log2, chunk, max_chunks;
+    float *out_scores;
+    int32_t *out_rep;
+    BankView bank;            // used by the cached instantiations only (K then points to host memory)
+};
+
+template <bool CACHED> struct KeySource;
+template <> struct KeySource<false> {
+    typedef DirectRows type;
+    static __device__ type make(const PruneArgs &a, const Problem &pr)
+    {
+        return DirectRows{a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st};
+    }
+};
+template <> struct KeySource<true> {
+    typedef CachedRows type;
+    static __device__ type make(const PruneArgs &a, const Problem &pr)
+    {
+        return CachedRows{a.bank, a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st, a.bank.bank_k,
+                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+    }
+};
+
+}  // namespace ihip

@@ -7,38 +7,10 @@
 // searches of all G query heads of its KV head together (the first two rows
 // of a chunk are common to the heads, the rest are G independent loads in
 // flight).  U slots per group are interleaved to put more loads in flight.
-#include "common.h"
+#include "prune_args.h"
 #include <type_traits>
 
 namespace ihip {
-
-struct PruneArgs {
-    Geometry ge;
-    const uint16_t *q; int64_t q_sb, q_sh, q_st;
-    const uint16_t *k; int64_t k_sb, k_sh, k_st;
-    const int32_t *parent_starts;
-    int n_parent, ratio_log2, chunk, max_chunks;
-    float *out_scores;
-    int32_t *out_rep;
-    BankView bank;            // used by the cached instantiations only (K then points to host memory)
-};
-
-template <bool CACHED> struct KeySource;
-template <> struct KeySource<false> {
-    typedef DirectRows type;
-    static __device__ type make(const PruneArgs &a, const Problem &pr)
-    {
-        return DirectRows{a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st};
-    }
-};
-template <> struct KeySource<true> {
-    typedef CachedRows type;
-    static __device__ type make(const PruneArgs &a, const Problem &pr)
-    {
-        return CachedRows{a.bank, a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st, a.bank.bank_k,
-                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
-    }
-};
 
 template <int G, int U, bool CACHED>
 __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
@@ -409,10 +381,12 @@ static void launch_decode(const PruneArgs &a, int P, hipStream_t st)
         hipLaunchKernelGGL((prune_decode_kernel<G, U, false>), grid, dim3(256), 0, st, a);
 }
 
+int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, hipStream_t st);
+
 int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                            const int32_t *parent_starts, int n_parent, int parent_chunk, int chunk,
                            int max_chunks, float *out_scores, int32_t *out_rep, const BankView *bank,
-                           hipStream_t st)
+                           const ihip_rope *rope, hipStream_t st)
 {
     PruneArgs a;
     a.bank = bank ? *bank : BankView{};
@@ -429,6 +403,20 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (max_chunks == 0 || P == 0) return IHIP_OK;
     if (bank && s.b_q != 1) return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: the host tier serves decode only");
+    if (rope && rope->prune_style != IHIP_ROPE_NONE) {
+        if (s.b_q != 1 || bank)
+            return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: dynamic RoPE is built for decode from device memory only");
+        const int style = rope->prune_style;
+        if (style != IHIP_ROPE_RELATIVE && style != IHIP_ROPE_CHUNK_INDEXED)
+            return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope prune_style = %d", style);
+        if (!rope->cos || !rope->sin) return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope tables are NULL");
+        // largest table row the kernel may read: n_stream + 1, or the query's position (chunk-indexed)
+        const int64_t need = style == IHIP_ROPE_RELATIVE ? (int64_t)s.n_stream + 2 : (int64_t)max_chunks + s.n_stream;
+        if (rope->n_pos < need)
+            return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope table has %d positions, %lld needed", rope->n_pos,
+                        (long long)need);
+        return launch_prune_stage_rope(a, RopeView{rope->cos, rope->sin, rope->n_pos}, style, P, st);
+    }
     if (s.b_q == 1) {
         switch (a.ge.G) {
         case 1: launch_decode<1>(a, P, st); break;

@@ -29,6 +29,7 @@ struct AttnDecodeArgs {
     uint16_t *out;       // bf16 [B, Hq, 1, d]
     float *out_lse;      // [B, Hq] or null
     BankView bank;       // used by the cached instantiations only (K/V then point to host memory)
+    const float *rope_cos, *rope_sin;   // streaming-style RoPE instantiations only: fp32 [n_pos][d/2]
 };
 
 template <bool CACHED> struct KvSource;
@@ -74,7 +75,11 @@ __device__ inline int slot_to_pos(const AttnDecodeArgs &a, const Problem &pr, in
     return pos < pr.E ? pos : -1;
 }
 
-template <int G, bool CACHED>
+// ROPE: streaming-style positions (Sec. 4 "Dynamic RoPE ..."): the attended keys, in position
+// order, are rotated to positions 0, 1, ..., n-1 and the query to n-1.  Attended slots are a
+// prefix of the block part of the slot list (blocks are ascending, empty ones last, only the last
+// one can be cut short), so a key's id is its slot, less the empty block slots for window keys.
+template <int G, bool CACHED, bool ROPE>
 __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const AttnDecodeArgs a)
 {
     const int p = blockIdx.y, split = blockIdx.x;
@@ -89,6 +94,40 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)(pr.g * G) * a.q_sh;
 #pragma unroll
         for (int h = 0; h < G; ++h) qp[h] = load_row16(qb, h * a.q_sh, l16);
+    }
+    // ROPE: tokens in the kept blocks (so that window keys and the query know their ids) and the
+    // rotated queries, fp32
+    __shared__ int sh_block_tokens;
+    float qr[ROPE ? G : 1][8];
+    int block_slots = 0, block_tokens = 0;
+    if (ROPE) {
+        if (threadIdx.x == 0) sh_block_tokens = 0;
+        __syncthreads();
+        int mine = 0;
+        for (int i = threadIdx.x; i < a.n_blocks; i += kAttnThreads) {
+            const int bs = a.block_starts[(int64_t)p * a.n_blocks + i];
+            if (bs >= 0 && bs < pr.hi) mine += min(a.block, pr.hi - bs);
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
+        if ((threadIdx.x & 63) == 0 && mine > 0) atomicAdd(&sh_block_tokens, mine);
+        __syncthreads();
+        block_slots = a.n_blocks << a.block_log2;
+        block_tokens = sh_block_tokens;
+        const int n_sel = n_sink_eff + block_tokens + max(0, pr.E - w0);
+        const float4 c = *reinterpret_cast<const float4 *>(a.rope_cos + (int64_t)(n_sel - 1) * (kD / 2) + l16 * 4);
+        const float4 sn = *reinterpret_cast<const float4 *>(a.rope_sin + (int64_t)(n_sel - 1) * (kD / 2) + l16 * 4);
+        const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float x[8];
+            unpack8(qp[h], x);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                qr[h][2 * i] = x[2 * i] * cc[i] - x[2 * i + 1] * ss[i];
+                qr[h][2 * i + 1] = x[2 * i] * ss[i] + x[2 * i + 1] * cc[i];
+            }
+        }
     }
     const typename KvSource<CACHED>::type ksrc = KvSource<CACHED>::k(a, pr);
     const typename KvSource<CACHED>::type vsrc = KvSource<CACHED>::v(a, pr);
@@ -127,11 +166,37 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
         }
         // scores of the UNR tokens for all heads (log2 units), then one running-max update per batch
         float sc[UNR][G];
+        if (ROPE) {
 #pragma unroll
-        for (int u = 0; u < UNR; ++u)
+            for (int u = 0; u < UNR; ++u) {
+                const int slot = base + u * kAttnGroups;
+                // id of the key: its slot, less the empty block slots if it is a window key
+                const int id = ok[u] ? (slot < n_sink_eff + block_slots ? slot : slot - (block_slots - block_tokens)) : 0;
+                const float4 c = *reinterpret_cast<const float4 *>(a.rope_cos + (int64_t)id * (kD / 2) + l16 * 4);
+                const float4 sn = *reinterpret_cast<const float4 *>(a.rope_sin + (int64_t)id * (kD / 2) + l16 * 4);
+                const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+                float x[8], kt[8];
+                unpack8(kr[u], x);
 #pragma unroll
-            for (int h = 0; h < G; ++h)
-                sc[u][h] = ok[u] ? row16_sum(dot8_bf16(kr[u], qp[h])) * a.scale_log2e : kNegBig;
+                for (int i = 0; i < 4; ++i) {
+                    kt[2 * i] = x[2 * i] * cc[i] - x[2 * i + 1] * ss[i];
+                    kt[2 * i + 1] = x[2 * i] * ss[i] + x[2 * i + 1] * cc[i];
+                }
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+                    float d8 = kt[0] * qr[h][0];
+#pragma unroll
+                    for (int i = 1; i < 8; ++i) d8 = fmaf(kt[i], qr[h][i], d8);
+                    sc[u][h] = ok[u] ? row16_sum(d8) * a.scale_log2e : kNegBig;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int h = 0; h < G; ++h)
+                    sc[u][h] = ok[u] ? row16_sum(dot8_bf16(kr[u], qp[h])) * a.scale_log2e : kNegBig;
+        }
         float pw[UNR][G], corr[G];
 #pragma unroll
         for (int h = 0; h < G; ++h) {
@@ -273,9 +338,23 @@ size_t attn_decode_workspace(const ihip_shape &s, int n_blocks, int block)
 int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                            const ihip_tensor &v, const int32_t *block_starts, int n_blocks, int block,
                            float sm_scale, void *out, float *out_lse, void *ws, const BankView *bank,
-                           hipStream_t st)
+                           const ihip_rope *rope, hipStream_t st)
 {
     AttnDecodeArgs a;
+    const bool use_rope = rope && rope->attn_style != IHIP_ROPE_NONE;
+    a.rope_cos = a.rope_sin = nullptr;
+    if (use_rope) {
+        if (rope->attn_style != IHIP_ROPE_STREAMING)
+            return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_decode: rope attn_style = %d", rope->attn_style);
+        if (bank) return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: dynamic RoPE is not built for the host tier");
+        if (!rope->cos || !rope->sin) return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_decode: rope tables are NULL");
+        const int64_t need = (int64_t)s.n_sink + (int64_t)n_blocks * block + s.n_stream;   // most keys a query can attend
+        if (rope->n_pos < need)
+            return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_decode: rope table has %d positions, %lld needed",
+                        rope->n_pos, (long long)need);
+        a.rope_cos = rope->cos;
+        a.rope_sin = rope->sin;
+    }
     a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
@@ -298,9 +377,10 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     {
     KernelTimer timer("attn_decode_split", st);
     switch (G) {
-#define IHIP_AD_LAUNCH(GG)                                                                                   \
-    if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, true>), grid, dim3(kAttnThreads), 0, st, a);  \
-    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, false>), grid, dim3(kAttnThreads), 0, st, a)
+#define IHIP_AD_LAUNCH(GG)                                                                                          \
+    if (use_rope) hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, true>), grid, dim3(kAttnThreads), 0, st, a);   \
+    else if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, true, false>), grid, dim3(kAttnThreads), 0, st, a);  \
+    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, false>), grid, dim3(kAttnThreads), 0, st, a)
     case 1: IHIP_AD_LAUNCH(1); break;
     case 2: IHIP_AD_LAUNCH(2); break;
     case 4: IHIP_AD_LAUNCH(4); break;
