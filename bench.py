@@ -57,6 +57,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg3-decode-1m-b8")
+    ap.add_argument("--rope", default=None, choices=["relative", "chunk"],
+                    help="decode workloads: dynamic RoPE in the pruning stages (this style) and the attention "
+                         "(streaming style); a separate metric, no roofline / cpu_baseline objects")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--no-profile-pass", action="store_true")
@@ -175,6 +178,16 @@ def bench_decode(args, w, torch, ihip, configs):
         def step(i):
             L.decode_layer_masked(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ihip.first_stage_due(i, refresh),
                                   state, ws=ws, out=out)
+    elif args.rope:
+        from workloads import gen
+        n_pos = max(L.stage1_slots(chunks[0]), max(keeps)) + w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8
+        cos, sin = gen.rope_table(n_pos, w.d, device=dev)
+        rope = ihip.Rope(cos, sin, ihip.ROPE_RELATIVE if args.rope == "relative" else ihip.ROPE_CHUNK_INDEXED,
+                         ihip.ROPE_STREAMING)
+
+        def step(i):
+            kl, vl = kvs[i % n_layers]
+            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out, rope=rope)
     else:
         def step(i):
             kl, vl = kvs[i % n_layers]
@@ -183,7 +196,7 @@ def bench_decode(args, w, torch, ihip, configs):
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 
     cpu = sample = None
-    if args.cpu_seconds > 0:
+    if args.cpu_seconds > 0 and not args.rope:
         sample = decode_oracle_sample(w, qs, kvs, seq_lens.cpu().tolist(), args.cpu_seconds)
         per_seq_call = sample["seconds"] / sample["layer_calls_one_sequence"]
         cpu = {"value": per_seq_call * w.B * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
@@ -217,7 +230,7 @@ def bench_decode(args, w, torch, ihip, configs):
                         "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
     return {
         "metric": ("sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer")
-        + ("_amortised_mask_cache" if refresh else ""),
+        + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
