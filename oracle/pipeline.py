@@ -176,6 +176,31 @@ class Oracle:
             pr.stages.append(self.prune_stage(b, g, m, starts, lens, l_c, keep, exhaustive))
         return pr
 
+    # -- Alg. 2 as printed: one mask per layer ---------------------------------
+    def prune_all_heads(self, b, m, stages: Sequence[Tuple[int, int]]) -> List[ProblemResult]:
+        """The paper's own pooling (Sec. 4: the chunk score is max-pooled over all
+        H attention heads, Alg. 2 `max_{h=1..H, t}`): every stage scores the chunks
+        per KV group as usual, the group scores are max-pooled and one arg-top-K
+        decides the chunks kept for all heads.  Returns one ProblemResult per KV
+        head (scores = the pooled ones, representatives its own heads')."""
+        lo, hi, E = self.ranges(b, m)
+        prs = [ProblemResult(b, g, m, lo, hi, E) for g in range(self.Hkv)]
+        if hi <= lo:
+            return prs
+        starts, lens = stage1_chunks(lo, hi, stages[0][0])
+        for i, (l_c, keep) in enumerate(stages):
+            if i > 0:
+                starts, lens = child_chunks(prs[0].stages[-1].kept_starts, prs[0].stages[-1].kept_lens, l_c)
+            per_g = [self.prune_stage(b, g, m, starts, lens, l_c, keep) for g in range(self.Hkv)]
+            pooled = np.max(np.stack([r.scores for r in per_g]), axis=0) if len(starts) else np.zeros(0, np.float32)
+            pooled = np.ascontiguousarray(pooled, np.float32)
+            ids = np.empty(max(min(keep, len(starts)), 1), np.int32)
+            kept = self.L.orc_topk(len(starts), _p(pooled), keep, _p(ids))
+            for g in range(self.Hkv):
+                r = per_g[g]
+                prs[g].stages.append(StageResult(l_c, r.starts, r.lens, pooled, r.reps, ids[:kept].copy(), r.touched_pos))
+        return prs
+
     # -- Alg. 4: cached masks ------------------------------------------------
     def prune_from(self, b, g, m, stages, first_stage, cached_kept):
         """Mask caching (Sec. 4 "Sparse Attention Mask Caching", Alg. 4): stages

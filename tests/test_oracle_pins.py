@@ -453,3 +453,60 @@ def test_mask_caching_identities():
     assert all((s - w.n_sink) // 64 * 64 + w.n_sink in parents for s in kept3[1].tolist())
     assert all(any(p <= s < p + 16 for p in kept3[1].tolist()) for s in bs3.tolist())
     assert kept3[1].tolist() != want[1]      # (new queries do pick different chunks)
+
+
+# ---------------------------------------------------------------------------
+# Paper-literal pooling over all heads (Sec. 4 / Alg. 2: max over h = 1..H)
+# ---------------------------------------------------------------------------
+def _small_layer(seed, Hq=8, Hkv=4, T=900, kind="normal"):
+    torch.manual_seed(seed)
+    if kind == "int":
+        mk = lambda *s: torch.randint(-2, 3, s).to(torch.bfloat16)
+    else:
+        mk = lambda *s: torch.randn(*s).to(torch.bfloat16)
+    return mk(1, Hq, 1, 128), mk(1, Hkv, T, 128), mk(1, Hkv, T, 128)
+
+
+def test_all_heads_pooling_with_one_kv_head_is_the_group_pooling():
+    q, k, v = _small_layer(0, Hq=4, Hkv=1)
+    o = oracle.Oracle(q, k, v, [900], 1, 16, 64)
+    stages = [(32, 8), (8, 12), (2, 20)]
+    a, b = o.prune(0, 0, 0, stages), o.prune_all_heads(0, 0, stages)[0]
+    for sa, sb in zip(a.stages, b.stages):
+        assert np.array_equal(sa.scores, sb.scores) and np.array_equal(sa.kept_ids, sb.kept_ids)
+
+
+def test_all_heads_pooling_is_the_max_over_every_head_and_one_mask():
+    q, k, v = _small_layer(1, kind="int")
+    o = oracle.Oracle(q, k, v, [900], 1, 16, 64)
+    stages = [(32, 8), (8, 12)]
+    prs = o.prune_all_heads(0, 0, stages)
+    G = o.G
+    for i in range(len(stages)):
+        st0 = prs[0].stages[i]
+        # the pooled score of chunk j is the best q_h . k_{rep_h} over all Hq heads, each head
+        # against its own KV head's keys (recomputed here from the raw tensors)
+        for j in range(len(st0.starts)):
+            best = -np.inf
+            for g in range(o.Hkv):
+                for hh in range(G):
+                    r = int(prs[g].stages[i].reps[hh, j])
+                    best = max(best, float((q[0, g * G + hh, 0].double() * k[0, g, r].double()).sum()))
+            assert st0.scores[j] == best
+        # one mask for the layer
+        for g in range(1, o.Hkv):
+            assert np.array_equal(prs[g].stages[i].kept_ids, st0.kept_ids)
+            assert np.array_equal(prs[g].stages[i].starts, st0.starts)
+
+
+def test_all_heads_pooling_ignores_the_order_of_the_kv_heads():
+    q, k, v = _small_layer(2)
+    o = oracle.Oracle(q, k, v, [900], 1, 16, 64)
+    perm = [2, 0, 3, 1]
+    G = 2
+    qp = torch.cat([q[:, g * G:(g + 1) * G] for g in perm], 1)
+    op = oracle.Oracle(qp, k[:, perm], v[:, perm], [900], 1, 16, 64)
+    stages = [(32, 8), (8, 12), (2, 20)]
+    a, b = o.prune_all_heads(0, 0, stages), op.prune_all_heads(0, 0, stages)
+    for sa, sb in zip(a[0].stages, b[0].stages):
+        assert np.array_equal(sa.kept_starts, sb.kept_starts) and np.array_equal(sa.scores, sb.scores)
