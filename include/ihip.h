@@ -151,6 +151,23 @@ int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t
                            int32_t chunk, int32_t keep, int32_t *out_starts, void *stream);
 
 /*
+ * Pooling of the chunk scores before the arg-top-K.  IHIP_POOL_KV_HEAD: one
+ * selection per (sequence, KV head, query block), the scores as ihip_prune_stage
+ * writes them (pooled over the query heads of the KV head) -- what every other
+ * entry point does.  IHIP_POOL_ALL_HEADS: the paper's own rule (Sec. 4 and
+ * Alg. 2: max over all attention heads h = 1..H): the Hkv score rows of a
+ * (sequence, query block) are max-pooled and one selection is written to all
+ * Hkv rows of out_starts, i.e. one mask per layer.  Requires the Hkv problems
+ * to have identical slots (true when every earlier stage was pooled the same way).
+ */
+#define IHIP_POOL_KV_HEAD   0
+#define IHIP_POOL_ALL_HEADS 1
+int32_t ihip_select_blocks_pooled(const ihip_shape *shape, const float *scores, int32_t max_chunks,
+                                  const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                                  int32_t chunk, int32_t keep, int32_t pooling, int32_t *out_starts,
+                                  void *stream);
+
+/*
  * Block-sparse decode attention (Tq == b_q == 1): for every query head,
  *   O = softmax(sm_scale * q K_S^T) V_S,
  *   S = [0, min(n_sink,E)) u kept blocks u [max(hi,n_sink), E)
@@ -207,6 +224,16 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                           int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                           float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
                           void *ws, size_t ws_bytes, void *stream);
+
+/* ihip_decode_layer / ihip_prefill_layer with the given pooling rule in every stage's selection. */
+int32_t ihip_decode_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 int32_t pooling, float sm_scale, void *out, float *out_lse,
+                                 int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_prefill_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                  int32_t pooling, float sm_scale, void *out, float *out_lse,
+                                  int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
 /* ihip_decode_layer with dynamic RoPE in every pruning stage and in the attention. */
 int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,

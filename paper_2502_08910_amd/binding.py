@@ -48,6 +48,12 @@ EXPORTS = {
     "ihip_stage1_slots": (c_i32, [ctypes.POINTER(Shape), c_i32]),
     "ihip_select_blocks": (c_i32, [ctypes.POINTER(Shape), vp, c_i32, vp, c_i32, c_i32, c_i32, c_i32,
                                    vp, vp]),
+    "ihip_select_blocks_pooled": (c_i32, [ctypes.POINTER(Shape), vp, c_i32, vp, c_i32, c_i32, c_i32, c_i32, c_i32,
+                                          vp, vp]),
+    "ihip_decode_layer_pooled": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_i32, c_f,
+                                         vp, vp, vp, vp, c_sz, vp]),
+    "ihip_prefill_layer_pooled": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_i32, c_f,
+                                          vp, vp, vp, vp, c_sz, vp]),
     "ihip_sparse_attn_decode": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
                                         c_f, vp, vp, vp, c_sz, vp]),
     "ihip_sparse_attn_prefill": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
@@ -144,6 +150,7 @@ def mfma_rate(kind: int, iters: int = 20000) -> float:
 
 
 ROPE_NONE, ROPE_RELATIVE, ROPE_CHUNK_INDEXED, ROPE_STREAMING = 0, 1, 2, 1
+POOL_KV_HEAD, POOL_ALL_HEADS = 0, 1
 
 
 class RopeStruct(ctypes.Structure):
@@ -226,10 +233,16 @@ class Layer:
         return scores, rep
 
     def select_blocks(self, scores: torch.Tensor, chunk: int, keep: int,
-                      parent_starts: Optional[torch.Tensor] = None, parent_chunk: int = 0):
+                      parent_starts: Optional[torch.Tensor] = None, parent_chunk: int = 0,
+                      pooling: Optional[int] = None):
         """-> kept start positions int32 [P, keep], ascending, -1 padded."""
         n_parent = 0 if parent_starts is None else parent_starts.shape[-1]
         out = torch.empty((self.P, keep), dtype=torch.int32, device=self.device)
+        if pooling is not None:
+            _check(lib().ihip_select_blocks_pooled(ctypes.byref(self.shape), _ptr(scores), scores.shape[-1],
+                                                   _ptr(parent_starts), n_parent, parent_chunk, chunk, keep,
+                                                   pooling, _ptr(out), _stream()))
+            return out
         _check(lib().ihip_select_blocks(ctypes.byref(self.shape), _ptr(scores), scores.shape[-1],
                                         _ptr(parent_starts), n_parent, parent_chunk, chunk, keep,
                                         _ptr(out), _stream()))
@@ -274,13 +287,19 @@ class Layer:
         return out
 
     def decode_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
-                     out_blocks=None, lse=None, rope: Optional["Rope"] = None):
+                     out_blocks=None, lse=None, rope: Optional["Rope"] = None, pooling: Optional[int] = None):
         """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d]."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+        if pooling is not None:
+            _check(lib().ihip_decode_layer_pooled(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                                  _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                                  pooling, sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks),
+                                                  _ptr(ws), ws.numel(), _stream()))
+            return out
         if rope is not None:
             _check(lib().ihip_decode_layer_rope(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                                 _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
@@ -313,13 +332,19 @@ class Layer:
         return out
 
     def prefill_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
-                      out_blocks=None, lse=None):
+                      out_blocks=None, lse=None, pooling: Optional[int] = None):
         """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d]."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, self.Tq, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_PREFILL_LAYER, chunk_sizes, keeps)
+        if pooling is not None:
+            _check(lib().ihip_prefill_layer_pooled(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                                   _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                                   pooling, sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks),
+                                                   _ptr(ws), ws.numel(), _stream()))
+            return out
         _check(lib().ihip_prefill_layer(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                         _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
                                         sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),

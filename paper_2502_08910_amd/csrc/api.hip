@@ -76,7 +76,7 @@ void profile_end(hipStream_t st)
 int32_t launch_prune_stage(const ihip_shape &, const ihip_tensor &, const ihip_tensor &, const int32_t *,
                            int, int, int, int, float *, int32_t *, const BankView *, const ihip_rope *, hipStream_t);
 int32_t launch_select_blocks(const ihip_shape &, const float *, int, const int32_t *, int, int, int, int,
-                             int32_t *, hipStream_t);
+                             int32_t *, bool, hipStream_t);
 int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                            const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
                            void *, const BankView *, const ihip_rope *, hipStream_t);
@@ -192,7 +192,7 @@ static PlanLayout plan_layout(const ihip_shape &s, int n_stages, const int32_t *
 static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                                  const int32_t *chunks, const int32_t *keeps, int first_stage,
                                  int32_t *const *stage_out, float *scores, const BankView *bank,
-                                 const ihip_rope *rope, hipStream_t st)
+                                 const ihip_rope *rope, bool all_heads, hipStream_t st)
 {
     for (int i = first_stage; i < n_stages; ++i) {
         const int32_t *parents = i == 0 ? nullptr : stage_out[i - 1];
@@ -203,7 +203,7 @@ static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, cons
                                         nullptr, bank, rope, st);
         if (rc != IHIP_OK) return rc;
         rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i],
-                                  stage_out[i], st);
+                                  stage_out[i], all_heads, st);
         if (rc != IHIP_OK) return rc;
     }
     return IHIP_OK;
@@ -211,13 +211,13 @@ static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, cons
 
 static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                               const int32_t *chunks, const int32_t *keeps, int32_t *out_block_starts,
-                              char *ws, const BankView *bank, const ihip_rope *rope, hipStream_t st)
+                              char *ws, const BankView *bank, const ihip_rope *rope, bool all_heads, hipStream_t st)
 {
     const PlanLayout L = plan_layout(s, n_stages, chunks, keeps);
     int32_t *stage_out[8];
     for (int i = 0; i < n_stages; ++i)
         stage_out[i] = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
-    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, rope, st);
+    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, rope, all_heads, st);
 }
 
 }  // namespace ihip
@@ -281,11 +281,10 @@ int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tenso
                              max_chunks, out_scores, out_rep, stream);
 }
 
-int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
+static int32_t select_blocks_entry(const char *who, bool all_heads, const ihip_shape *shape, const float *scores, int32_t max_chunks,
                            const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk, int32_t chunk,
                            int32_t keep, int32_t *out_starts, void *stream)
 {
-    const char *who = "ihip_select_blocks";
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if ((rc = check_slots(who, parent_starts, n_parent, parent_chunk, chunk, max_chunks)) != IHIP_OK) return rc;
@@ -294,7 +293,32 @@ int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t
     if ((!scores && max_chunks > 0) || (!out_starts && keep > 0))
         return fail(IHIP_ERR_INVALID_ARG, "%s: scores / out_starts is NULL", who);
     return launch_select_blocks(*shape, scores, max_chunks, parent_starts, n_parent, parent_chunk, chunk, keep,
-                                out_starts, (hipStream_t)stream);
+                                out_starts, all_heads, (hipStream_t)stream);
+}
+
+int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
+                           const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk, int32_t chunk,
+                           int32_t keep, int32_t *out_starts, void *stream)
+{
+    return select_blocks_entry("ihip_select_blocks", false, shape, scores, max_chunks, parent_starts, n_parent,
+                               parent_chunk, chunk, keep, out_starts, stream);
+}
+
+static int32_t check_pooling(const char *who, int32_t pooling)
+{
+    if (pooling != IHIP_POOL_KV_HEAD && pooling != IHIP_POOL_ALL_HEADS)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: pooling = %d", who, pooling);
+    return IHIP_OK;
+}
+
+int32_t ihip_select_blocks_pooled(const ihip_shape *shape, const float *scores, int32_t max_chunks,
+                                  const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                                  int32_t chunk, int32_t keep, int32_t pooling, int32_t *out_starts, void *stream)
+{
+    const int32_t rc = check_pooling("ihip_select_blocks_pooled", pooling);
+    if (rc != IHIP_OK) return rc;
+    return select_blocks_entry("ihip_select_blocks_pooled", pooling == IHIP_POOL_ALL_HEADS, shape, scores, max_chunks,
+                               parent_starts, n_parent, parent_chunk, chunk, keep, out_starts, stream);
 }
 
 static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
@@ -370,11 +394,12 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, in
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     return prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, out_block_starts, (char *)ws, nullptr, nullptr,
-                          (hipStream_t)stream);
+                          false, (hipStream_t)stream);
 }
 
 static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
-                                 ihip_tensor v, const ihip_cache *cache, const ihip_rope *rope, int32_t n_stages,
+                                 ihip_tensor v, const ihip_cache *cache, const ihip_rope *rope, bool all_heads,
+                                 int32_t n_stages,
                                  const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                                  float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
@@ -400,7 +425,7 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
     if (cache && rope) return fail(IHIP_ERR_UNSUPPORTED, "%s: dynamic RoPE is not built for the host tier", who);
     rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, cache ? &mask_bank : nullptr, rope,
-                        (hipStream_t)stream);
+                        all_heads, (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_decode(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
                               w + L.total + blocks_bytes, cache ? &sa_bank : nullptr, rope, (hipStream_t)stream);
@@ -410,8 +435,20 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                           const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                           float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
-    return decode_layer_impl("ihip_decode_layer", shape, q, k, v, nullptr, nullptr, n_stages, chunk_sizes, keeps,
-                             sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
+    return decode_layer_impl("ihip_decode_layer", shape, q, k, v, nullptr, nullptr, false, n_stages, chunk_sizes,
+                             keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_decode_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps, int32_t pooling,
+                                 float sm_scale, void *out, float *out_lse, int32_t *out_block_starts, void *ws,
+                                 size_t ws_bytes, void *stream)
+{
+    const int32_t rc = check_pooling("ihip_decode_layer_pooled", pooling);
+    if (rc != IHIP_OK) return rc;
+    return decode_layer_impl("ihip_decode_layer_pooled", shape, q, k, v, nullptr, nullptr,
+                             pooling == IHIP_POOL_ALL_HEADS, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
+                             out_block_starts, ws, ws_bytes, stream);
 }
 
 int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
@@ -420,7 +457,7 @@ int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tens
                                void *stream)
 {
     if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_decode_layer_rope: rope is NULL");
-    return decode_layer_impl("ihip_decode_layer_rope", shape, q, k, v, nullptr, rope, n_stages, chunk_sizes, keeps,
+    return decode_layer_impl("ihip_decode_layer_rope", shape, q, k, v, nullptr, rope, false, n_stages, chunk_sizes, keeps,
                              sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -438,7 +475,7 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
     if (shape && (shape->B != B || shape->Hkv != Hkv || shape->max_seq_len > T_alloc))
         return fail(IHIP_ERR_INVALID_ARG, "%s: shape (B %d, Hkv %d, max_seq_len %d) does not fit the cache (%d, %d, %lld)",
                     who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
-    return decode_layer_impl(who, shape, q, hk, hv, cache, nullptr, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
+    return decode_layer_impl(who, shape, q, hk, hv, cache, nullptr, false, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
                              out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -478,17 +515,16 @@ int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_te
     size_t off = 0;
     for (int i = 0; i < n_stages; ++i) { stage_out[i] = stage_starts + off; off += P * (size_t)keeps[i]; }
     rc = prune_stages_impl(*shape, q, k, n_stages, chunk_sizes, keeps, first_stage, stage_out, (float *)ws, nullptr,
-                           nullptr, (hipStream_t)stream);
+                           nullptr, false, (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_decode(*shape, q, k, v, stage_out[last], keeps[last], chunk_sizes[last], sm_scale, out,
                               out_lse, (char *)ws + L.scores_bytes, nullptr, nullptr, (hipStream_t)stream);
 }
 
-int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
                            const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                            float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
-    const char *who = "ihip_prefill_layer";
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if (shape->b_q != 16 && shape->b_q != 32 && shape->b_q != 64)
@@ -507,10 +543,30 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
-    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, nullptr, (hipStream_t)stream);
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, nullptr, all_heads,
+                        (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
     return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
                                (hipStream_t)stream);
+}
+
+int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                           const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
+                           float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+{
+    return prefill_layer_impl("ihip_prefill_layer", false, shape, q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out,
+                              out_lse, out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_prefill_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                  int32_t pooling, float sm_scale, void *out, float *out_lse,
+                                  int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+{
+    const int32_t rc = check_pooling("ihip_prefill_layer_pooled", pooling);
+    if (rc != IHIP_OK) return rc;
+    return prefill_layer_impl("ihip_prefill_layer_pooled", pooling == IHIP_POOL_ALL_HEADS, shape, q, k, v, n_stages,
+                              chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
 int32_t ihip_profile_enable(int32_t on)

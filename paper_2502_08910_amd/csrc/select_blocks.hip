@@ -18,6 +18,38 @@ struct SelectArgs {
     const int32_t *parent_starts;
     int n_parent, ratio_log2, chunk, keep;
     int32_t *out_starts;
+    int pool;                 // 1: one selection per KV head; Hkv: scores max-pooled over the KV heads
+                              // of a (sequence, query block), one selection written to all of them
+};
+
+// Which problem a workgroup selects for, how it reads a (possibly pooled) score and where the
+// selection goes.  With pooling the Hkv problems of a (sequence, query block) have identical
+// slots, so the first one's parent list describes them all.
+struct SelView {
+    int p;                    // first problem of the pooled set (the problem itself without pooling)
+    int pool;
+    int64_t in_stride, out_stride;   // elements between consecutive KV heads' rows
+    const float *sc;
+    int32_t *out;
+    __device__ SelView(const SelectArgs &a, int wg)
+    {
+        pool = a.pool;
+        p = pool > 1 ? (wg / a.ge.Mq) * a.ge.Hkv * a.ge.Mq + wg % a.ge.Mq : wg;
+        in_stride = (int64_t)a.ge.Mq * a.max_chunks;
+        out_stride = (int64_t)a.ge.Mq * a.keep;
+        sc = a.scores + (int64_t)p * a.max_chunks;
+        out = a.out_starts + (int64_t)p * a.keep;
+    }
+    __device__ float score(int i) const
+    {
+        float v = sc[i];
+        for (int g = 1; g < pool; ++g) v = fmaxf(v, sc[g * in_stride + i]);
+        return v;
+    }
+    __device__ void put(int rank, int value) const
+    {
+        for (int g = 0; g < pool; ++g) out[g * out_stride + rank] = value;
+    }
 };
 
 // Monotone map fp32 -> u32 (larger float <=> larger key); -0.0 maps with +0.0.
@@ -34,16 +66,16 @@ __global__ __launch_bounds__(kSelThreads) void select_blocks_kernel(const Select
     __shared__ SelectScratch<kSelThreads> scratch;
     __shared__ uint32_t sh_valid;
 
-    const int p = blockIdx.x;
+    const SelView view(a, blockIdx.x);
+    const int p = view.p;
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = a.max_chunks;
-    const float *sc = a.scores + (int64_t)p * n;
     const bool cached = n <= kSelLdsKeys;
 
     // load keys, count non-empty slots
     uint32_t my_valid = 0;
     for (int i = tid; i < n; i += kSelThreads) {
-        const uint32_t kk = order_key(sc[i]);
+        const uint32_t kk = order_key(view.score(i));
         if (cached) keys[i] = kk;
         my_valid += kk != kKeyNegInf;
     }
@@ -57,19 +89,18 @@ __global__ __launch_bounds__(kSelThreads) void select_blocks_kernel(const Select
     }
     __syncthreads();
     const int keep_eff = min((int)sh_valid, a.keep);
-    int32_t *out = a.out_starts + (int64_t)p * a.keep;
 
     if (keep_eff > 0) {
         const Problem pr = problem_of(a.ge, p);
         block_select_largest<kSelThreads>(
             n, keep_eff,
-            [&](int i) -> uint32_t { return cached ? keys[i] : order_key(sc[i]); },
+            [&](int i) -> uint32_t { return cached ? keys[i] : order_key(view.score(i)); },
             [&](uint32_t rank, int i) {
-                out[rank] = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i);
+                view.put(rank, slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i));
             },
             scratch);
     }
-    for (int i = keep_eff + tid; i < a.keep; i += kSelThreads) out[i] = -1;
+    for (int i = keep_eff + tid; i < a.keep; i += kSelThreads) view.put(i, -1);
 }
 
 // ---------------------------------------------------------------------------
@@ -97,10 +128,10 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
     __shared__ uint32_t sh_bin, sh_above, sh_ncand;
     __shared__ SelectScratch<NT> scratch;
 
-    const int p = blockIdx.x;
+    const SelView view(a, blockIdx.x);
+    const int p = view.p;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int n = a.max_chunks;
-    const float *sc = a.scores + (int64_t)p * n;
     const int per = (n + NT - 1) / NT;                  // <= kFastItems, slots [tid*per, tid*per + per)
     const int i0 = tid * per;
 
@@ -110,7 +141,7 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
 #pragma unroll
     for (int i = 0; i < kFastItems; ++i) {
         const int idx = i0 + i;
-        v[i] = (i < per && idx < n) ? sc[idx] + 0.0f : -INFINITY;      // -0.0 -> +0.0
+        v[i] = (i < per && idx < n) ? view.score(idx) + 0.0f : -INFINITY;      // -0.0 -> +0.0
         if (i < per && idx < n) keys[idx] = order_key(v[i]);
         if (v[i] > -INFINITY) { mn = fminf(mn, v[i]); mx = fmaxf(mx, v[i]); ++valid; }
     }
@@ -129,7 +160,6 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
 #pragma unroll
     for (int w = 0; w < NW; ++w) { mn = fminf(mn, red_min[w]); mx = fmaxf(mx, red_max[w]); n_valid += red_cnt[w]; }
     const int keep_eff = min((int)n_valid, a.keep);
-    int32_t *out = a.out_starts + (int64_t)p * a.keep;
 
     if (keep_eff > 0) {
         const float scale = mx > mn ? (float)(kFastBins - 1) / (mx - mn) : 0.f;
@@ -196,26 +226,27 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
 #pragma unroll
             for (int i = 0; i < kFastItems; ++i)
                 if (bin[i] > tb || (bin[i] == tb && sel[i0 + i]))
-                    out[pos++] = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i0 + i);
+                    view.put(pos++, slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i0 + i));
         } else {
             // heavy ties: exact radix select over the keys in LDS
             const Problem pr = problem_of(a.ge, p);
             block_select_largest<NT>(
                 n, keep_eff, [&](int i) -> uint32_t { return keys[i]; },
                 [&](uint32_t rank, int i) {
-                    out[rank] = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i);
+                    view.put(rank, slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i));
                 },
                 scratch);
         }
     }
-    for (int i = keep_eff + tid; i < a.keep; i += NT) out[i] = -1;
+    for (int i = keep_eff + tid; i < a.keep; i += NT) view.put(i, -1);
 }
 
 int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_chunks,
                              const int32_t *parent_starts, int n_parent, int parent_chunk, int chunk,
-                             int keep, int32_t *out_starts, hipStream_t st)
+                             int keep, int32_t *out_starts, bool all_heads, hipStream_t st)
 {
     SelectArgs a;
+    a.pool = all_heads ? s.Hkv : 1;
     a.ge = make_geometry(s);
     a.scores = scores;
     a.max_chunks = max_chunks;
@@ -225,7 +256,7 @@ int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_c
     a.chunk = chunk;
     a.keep = keep;
     a.out_starts = out_starts;
-    const int P = s.B * s.Hkv * (s.Tq / s.b_q);
+    const int P = s.B * (all_heads ? 1 : s.Hkv) * (s.Tq / s.b_q);      // workgroups
     if (P == 0 || keep == 0) return IHIP_OK;
     KernelTimer timer(stage_name(kNameSelect, parent_starts == nullptr, chunk), st);
     if (max_chunks <= 256 * kFastItems)
