@@ -32,7 +32,8 @@ class Rope(ctypes.Structure):
 class Tensors(ctypes.Structure):
     _fields_ = [("Q", ctypes.c_void_p), ("K", ctypes.c_void_p), ("V", ctypes.c_void_p),
                 ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
-                ("d", ctypes.c_int32), ("Tq", ctypes.c_int32), ("T_alloc", ctypes.c_int64)]
+                ("d", ctypes.c_int32), ("Tq", ctypes.c_int32), ("T_alloc", ctypes.c_int64),
+                ("kv_fp8", ctypes.c_int32), ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float)]
 
 
 def lib():
@@ -56,6 +57,8 @@ def lib():
         L.orc_sparse_attention.restype = None
         L.orc_sparse_attention.argtypes = [P(Tensors), c_i32, c_i32, c_i64, c_i32, c_i64, c_i64,
                                            c_i64, c_i32, vp, vp, c_d, vp, vp]
+        L.orc_e4m3_to_f32.restype = c_f
+        L.orc_e4m3_to_f32.argtypes = [ctypes.c_uint8]
         L.orc_score_rope.restype = c_f
         L.orc_score_rope.argtypes = [P(Tensors), c_i32, c_i32, c_i64, c_i32, c_i64, P(Rope), vp, c_i64]
         L.orc_select_rep_rope.restype = None

@@ -27,7 +27,8 @@
  * sums, summed in index order); the attention itself is fp64.
  *
  * Layouts: Q [B,Hq,Tq,d], K and V [B,Hkv,T_alloc,d], contiguous, bf16 bit
- * patterns in uint16.  Query head h reads KV head h / (Hq/Hkv).
+ * patterns in uint16 (K and V optionally E4M3 bytes with a scale each, see
+ * orc_tensors).  Query head h reads KV head h / (Hq/Hkv).
  */
 #include <math.h>
 #include <stdint.h>
@@ -38,6 +39,11 @@ typedef struct {
     const uint16_t *Q, *K, *V;
     int32_t B, Hq, Hkv, d, Tq;
     int64_t T_alloc;
+    /* FP8 KV cache (the paper's end-to-end runs keep K and V in 8 bits): when kv_fp8 != 0, K and V
+     * point to bytes in the OCP 8-bit float format E4M3 and an element's value is its scale times
+     * the decoded byte (one scale per tensor).  Q stays bf16. */
+    int32_t kv_fp8;
+    float k_scale, v_scale;
 } orc_tensors;
 
 static float bf16_to_f32(uint16_t x)
@@ -48,30 +54,50 @@ static float bf16_to_f32(uint16_t x)
     return f;
 }
 
+/*
+ * OCP FP8 E4M3: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits; no
+ * infinities; exponent 15 with mantissa 7 is NaN; exponent 0 holds the
+ * subnormals m/8 * 2^-6.
+ */
+float orc_e4m3_to_f32(uint8_t x)
+{
+    const int sign = x >> 7, e = (x >> 3) & 15, m = x & 7;
+    float v;
+    if (e == 15 && m == 7) v = NAN;
+    else if (e == 0) v = ldexpf((float)m, -9);
+    else v = ldexpf((float)(8 + m), e - 10);
+    return sign ? -v : v;
+}
+
+/* element c of key / value row p of (sequence b, KV head g), as a float */
+static float k_elem(const orc_tensors *t, int b, int g, int64_t p, int c)
+{
+    const int64_t i = (((int64_t)b * t->Hkv + g) * t->T_alloc + p) * t->d + c;
+    if (t->kv_fp8) return t->k_scale * orc_e4m3_to_f32(((const uint8_t *)t->K)[i]);
+    return bf16_to_f32(t->K[i]);
+}
+static float v_elem(const orc_tensors *t, int b, int g, int64_t p, int c)
+{
+    const int64_t i = (((int64_t)b * t->Hkv + g) * t->T_alloc + p) * t->d + c;
+    if (t->kv_fp8) return t->v_scale * orc_e4m3_to_f32(((const uint8_t *)t->V)[i]);
+    return bf16_to_f32(t->V[i]);
+}
+
 static const uint16_t *q_row(const orc_tensors *t, int b, int h, int64_t tq)
 {
     return t->Q + (((int64_t)b * t->Hq + h) * t->Tq + tq) * t->d;
-}
-static const uint16_t *k_row(const orc_tensors *t, int b, int g, int64_t p)
-{
-    return t->K + (((int64_t)b * t->Hkv + g) * t->T_alloc + p) * t->d;
-}
-static const uint16_t *v_row(const orc_tensors *t, int b, int g, int64_t p)
-{
-    return t->V + (((int64_t)b * t->Hkv + g) * t->T_alloc + p) * t->d;
 }
 
 /* max over the queries t of the block [q0, q0+bq) of  q_t . k_p   (fp32). */
 float orc_score(const orc_tensors *t, int b, int h, int64_t q0, int bq, int64_t p)
 {
     const int g = h / (t->Hq / t->Hkv);
-    const uint16_t *k = k_row(t, b, g, p);
     float best = -INFINITY;
     for (int i = 0; i < bq; ++i) {
         const uint16_t *q = q_row(t, b, h, q0 + i);
         float acc = 0.0f;
         for (int c = 0; c < t->d; ++c)
-            acc += bf16_to_f32(q[c]) * bf16_to_f32(k[c]);
+            acc += bf16_to_f32(q[c]) * k_elem(t, b, g, p, c);
         if (acc > best)
             best = acc;
     }
@@ -219,10 +245,9 @@ void orc_sparse_attention(const orc_tensors *t, int b, int g, int64_t q0, int bq
             const uint16_t *q = q_row(t, b, g * G + hh, q0 + i);
             double mx = -INFINITY;
             for (int64_t a = 0; a < n; ++a) {
-                const uint16_t *k = k_row(t, b, g, keys[a]);
                 double acc = 0.0;
                 for (int c = 0; c < d; ++c)
-                    acc += (double)bf16_to_f32(q[c]) * (double)bf16_to_f32(k[c]);
+                    acc += (double)bf16_to_f32(q[c]) * (double)k_elem(t, b, g, keys[a], c);
                 s[a] = scale * acc;
                 if (s[a] > mx) mx = s[a];
             }
@@ -231,9 +256,8 @@ void orc_sparse_attention(const orc_tensors *t, int b, int g, int64_t q0, int bq
             for (int c = 0; c < d; ++c) o[c] = 0.0;
             for (int64_t a = 0; a < n; ++a) {
                 const double w = exp(s[a] - mx);
-                const uint16_t *v = v_row(t, b, g, keys[a]);
                 denom += w;
-                for (int c = 0; c < d; ++c) o[c] += w * (double)bf16_to_f32(v[c]);
+                for (int c = 0; c < d; ++c) o[c] += w * (double)v_elem(t, b, g, keys[a], c);
             }
             for (int c = 0; c < d; ++c) o[c] /= denom;
             if (lse) lse[(int64_t)hh * bq + i] = mx + log(denom);
@@ -273,11 +297,11 @@ typedef struct {
     int32_t n_pos;
 } orc_rope;
 
-static void rope_f32(const uint16_t *x, const orc_rope *r, int64_t pos, int d, float *out)
+static void rope_f32(const float *x, const orc_rope *r, int64_t pos, int d, float *out)
 {
     const float *c = r->cos + pos * (d / 2), *s = r->sin + pos * (d / 2);
     for (int j = 0; j < d / 2; ++j) {
-        const float a = bf16_to_f32(x[2 * j]), b = bf16_to_f32(x[2 * j + 1]);
+        const float a = x[2 * j], b = x[2 * j + 1];
         out[2 * j] = a * c[j] - b * s[j];
         out[2 * j + 1] = a * s[j] + b * c[j];
     }
@@ -288,17 +312,20 @@ float orc_score_rope(const orc_tensors *t, int b, int h, int64_t q0, int bq, int
                      const orc_rope *rope, const int64_t *qpos, int64_t kpos)
 {
     const int g = h / (t->Hq / t->Hkv), d = t->d;
-    float *kr = malloc(sizeof(float) * d), *qr = malloc(sizeof(float) * d);
-    rope_f32(k_row(t, b, g, p), rope, kpos, d, kr);
+    float *kr = malloc(sizeof(float) * d), *qr = malloc(sizeof(float) * d), *x = malloc(sizeof(float) * d);
+    for (int c = 0; c < d; ++c) x[c] = k_elem(t, b, g, p, c);
+    rope_f32(x, rope, kpos, d, kr);
     float best = -INFINITY;
     for (int i = 0; i < bq; ++i) {
-        rope_f32(q_row(t, b, h, q0 + i), rope, qpos[i], d, qr);
+        for (int c = 0; c < d; ++c) x[c] = bf16_to_f32(q_row(t, b, h, q0 + i)[c]);
+        rope_f32(x, rope, qpos[i], d, qr);
         float acc = 0.0f;
         for (int c = 0; c < d; ++c) acc += qr[c] * kr[c];
         if (acc > best) best = acc;
     }
     free(kr);
     free(qr);
+    free(x);
     return best;
 }
 
@@ -398,11 +425,10 @@ void orc_sparse_attention_rope(const orc_tensors *t, int b, int g, int64_t q0, i
             }
             double mx = -INFINITY;
             for (int64_t a = 0; a < n; ++a) {
-                const uint16_t *k = k_row(t, b, g, keys[a]);
                 const float *ck = rope->cos + a * (d / 2), *sk = rope->sin + a * (d / 2);
                 double acc = 0.0;
                 for (int j = 0; j < d / 2; ++j) {
-                    const double x0 = bf16_to_f32(k[2 * j]), x1 = bf16_to_f32(k[2 * j + 1]);
+                    const double x0 = k_elem(t, b, g, keys[a], 2 * j), x1 = k_elem(t, b, g, keys[a], 2 * j + 1);
                     kr[2 * j] = x0 * ck[j] - x1 * sk[j];
                     kr[2 * j + 1] = x0 * sk[j] + x1 * ck[j];
                 }
@@ -415,9 +441,8 @@ void orc_sparse_attention_rope(const orc_tensors *t, int b, int g, int64_t q0, i
             for (int c = 0; c < d; ++c) o[c] = 0.0;
             for (int64_t a = 0; a < n; ++a) {
                 const double w = exp(s[a] - mx);
-                const uint16_t *v = v_row(t, b, g, keys[a]);
                 denom += w;
-                for (int c = 0; c < d; ++c) o[c] += w * (double)bf16_to_f32(v[c]);
+                for (int c = 0; c < d; ++c) o[c] += w * (double)v_elem(t, b, g, keys[a], c);
             }
             for (int c = 0; c < d; ++c) o[c] /= denom;
             if (lse) lse[(int64_t)hh * bq + i] = mx + log(denom);

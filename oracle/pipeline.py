@@ -107,7 +107,10 @@ class Oracle:
     shape; runs pruning and attention problem by problem."""
 
     def __init__(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens,
-                 b_q: int, n_sink: int, n_stream: int, rope: Optional[RopeSpec] = None):
+                 b_q: int, n_sink: int, n_stream: int, rope: Optional[RopeSpec] = None,
+                 kv_scales: Optional[Tuple[float, float]] = None):
+        """kv_scales = (k_scale, v_scale): K and V are uint8 tensors of E4M3 bytes (FP8 KV cache),
+        an element being its scale times the decoded byte; otherwise they are bf16."""
         from . import lib, Tensors, Rope
         self.L = lib()
         self.rope = rope
@@ -116,7 +119,12 @@ class Oracle:
             self._sin = np.ascontiguousarray(rope.sin, np.float32)
             assert self._cos.shape == self._sin.shape and self._cos.shape[1] * 2 == q.shape[-1]
             self._rope = Rope(self._cos.ctypes.data, self._sin.ctypes.data, self._cos.shape[0])
-        self.q, self.k, self.v = _u16(q), _u16(k), _u16(v)
+        if kv_scales is None:
+            self.q, self.k, self.v = _u16(q), _u16(k), _u16(v)
+        else:
+            assert k.dtype == torch.uint8 and v.dtype == torch.uint8
+            self.q = _u16(q)
+            self.k, self.v = k.detach().cpu().contiguous().numpy(), v.detach().cpu().contiguous().numpy()
         self.B, self.Hq, self.Tq, self.d = q.shape
         _, self.Hkv, self.T_alloc, _ = k.shape
         assert self.Hq % self.Hkv == 0 and self.Tq % b_q == 0
@@ -124,7 +132,9 @@ class Oracle:
         self.seq_lens = [int(x) for x in seq_lens]
         self.b_q, self.n_sink, self.n_stream = b_q, n_sink, n_stream
         self.t = Tensors(self.q.ctypes.data, self.k.ctypes.data, self.v.ctypes.data,
-                         self.B, self.Hq, self.Hkv, self.d, self.Tq, self.T_alloc)
+                         self.B, self.Hq, self.Hkv, self.d, self.Tq, self.T_alloc,
+                         0 if kv_scales is None else 1,
+                         1.0 if kv_scales is None else kv_scales[0], 1.0 if kv_scales is None else kv_scales[1])
 
     # -- geometry ---------------------------------------------------------
     def ranges(self, b: int, m: int) -> Tuple[int, int, int]:

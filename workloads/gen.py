@@ -169,3 +169,10 @@ def quarter_turn_table(n_pos: int, d: int, device="cpu"):
     cos = torch.tensor([1.0, 0.0, -1.0, 0.0])[q]
     sin = torch.tensor([0.0, 1.0, 0.0, -1.0])[q]
     return cos.to(torch.float32).to(device), sin.to(torch.float32).to(device)
+
+
+def to_e4m3(x: torch.Tensor, scale: float) -> torch.Tensor:
+    """Quantise a tensor to FP8 E4M3 bytes (uint8) with one scale: byte = e4m3(x / scale), values
+    beyond the format's largest finite number (448) saturating to it."""
+    y = (x.float() / scale).clamp_(-448.0, 448.0)
+    return y.to(torch.float8_e4m3fn).view(torch.uint8)
