@@ -128,6 +128,30 @@ int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                          int32_t chunk, int32_t max_chunks,
                          float *out_scores, int32_t *out_rep, void *stream);
 
+/*
+ * FP8 KV cache (the paper's end-to-end runs keep K and V in 8 bits): the
+ * *_fp8kv entry points take K and V as bytes in the OCP FP8 format E4M3 (1 sign,
+ * 4 exponent bits with bias 7, 3 mantissa bits, no infinities), one positive
+ * scale per tensor: element = scale * decoded byte.  Their ihip_tensor strides
+ * count bytes; rows are 128 bytes, 16-byte aligned.  Q and the output stay
+ * bf16.  Chunk scores are k_scale * (q . decoded k) in fp32 (the selection does
+ * not depend on the scale); the attention multiplies its scores by k_scale and
+ * its output by v_scale.  Built for decode (Tq == b_q == 1) from device memory
+ * without dynamic RoPE.
+ */
+int32_t ihip_prune_stage_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
+                               const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                               int32_t chunk, int32_t max_chunks, float k_scale,
+                               float *out_scores, int32_t *out_rep, void *stream);
+int32_t ihip_sparse_attn_decode_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                      float sm_scale, float k_scale, float v_scale, void *out,
+                                      float *out_lse, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                float sm_scale, float k_scale, float v_scale, void *out, float *out_lse,
+                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+
 /* ihip_prune_stage with rope->prune_style applied (decode only); rope must not be NULL. */
 int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                               const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,

@@ -45,6 +45,12 @@ EXPORTS = {
                                              c_f, vp, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
                                        vp, vp, vp, vp, c_sz, vp]),
+    "ihip_prune_stage_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, vp, c_i32, c_i32, c_i32, c_i32,
+                                       c_f, vp, vp, vp]),
+    "ihip_sparse_attn_decode_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
+                                              c_f, c_f, c_f, vp, vp, vp, c_sz, vp]),
+    "ihip_decode_layer_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, c_f, c_f,
+                                        vp, vp, vp, vp, c_sz, vp]),
     "ihip_stage1_slots": (c_i32, [ctypes.POINTER(Shape), c_i32]),
     "ihip_select_blocks": (c_i32, [ctypes.POINTER(Shape), vp, c_i32, vp, c_i32, c_i32, c_i32, c_i32,
                                    vp, vp]),
@@ -111,6 +117,13 @@ def _check(rc: int):
 def _tensor(t: torch.Tensor, name: str) -> Tensor:
     if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1 or not t.is_cuda:
         raise IhipError(f"{name}: need a 4-d bf16 device tensor with contiguous last dim")
+    return Tensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
+
+
+def _tensor8(t: torch.Tensor, name: str) -> Tensor:
+    """FP8 (E4M3) K/V as a uint8 tensor; strides in bytes."""
+    if t.dtype != torch.uint8 or t.dim() != 4 or t.stride(3) != 1 or not t.is_cuda:
+        raise IhipError(f"{name}: need a 4-d uint8 device tensor with contiguous last dim")
     return Tensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
 
 
@@ -212,8 +225,9 @@ class Layer:
 
     # -- entry points -------------------------------------------------------
     def prune_stage(self, q, k, chunk: int, parent_starts: Optional[torch.Tensor] = None,
-                    parent_chunk: int = 0, want_rep: bool = False, rope: Optional["Rope"] = None):
-        """-> scores fp32 [P, slots], rep int32 [B,Hq,Mq,slots] or None."""
+                    parent_chunk: int = 0, want_rep: bool = False, rope: Optional["Rope"] = None,
+                    k_scale: Optional[float] = None):
+        """-> scores fp32 [P, slots], rep int32 [B,Hq,Mq,slots] or None.  k_scale: k holds E4M3 bytes."""
         if parent_starts is None:
             n_parent, slots = 0, self.stage1_slots(chunk)
         else:
@@ -222,6 +236,11 @@ class Layer:
         scores = torch.empty((self.P, slots), dtype=torch.float32, device=self.device)
         rep = torch.empty((self.B, self.Hq, self.Tq // self.b_q, slots), dtype=torch.int32,
                           device=self.device) if want_rep else None
+        if k_scale is not None:
+            _check(lib().ihip_prune_stage_fp8kv(ctypes.byref(self.shape), _tensor(q, "q"), _tensor8(k, "k"),
+                                                _ptr(parent_starts), n_parent, parent_chunk, chunk, slots,
+                                                k_scale, _ptr(scores), _ptr(rep), _stream()))
+            return scores, rep
         if rope is not None:
             _check(lib().ihip_prune_stage_rope(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                                _ptr(parent_starts), n_parent, parent_chunk, chunk, slots,
@@ -262,7 +281,19 @@ class Layer:
         return out, lse
 
     def sparse_attn_decode(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None,
-                           rope: Optional["Rope"] = None):
+                           rope: Optional["Rope"] = None, kv_scales: Optional[Sequence[float]] = None):
+        if kv_scales is not None:
+            n_blocks = block_starts.shape[-1]
+            sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
+            out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
+            lse = torch.empty((self.B, self.Hq, 1), dtype=torch.float32, device=self.device) if want_lse else None
+            if ws is None:
+                ws = self.workspace(OP_ATTN_DECODE, [block], [max(n_blocks, 1)])
+            _check(lib().ihip_sparse_attn_decode_fp8kv(ctypes.byref(self.shape), _tensor(q, "q"), _tensor8(k, "k"),
+                                                       _tensor8(v, "v"), _ptr(block_starts), n_blocks, block,
+                                                       sm_scale, kv_scales[0], kv_scales[1], _ptr(out), _ptr(lse),
+                                                       _ptr(ws), ws.numel(), _stream()))
+            return out, lse
         if rope is not None:
             def fn(shape, tq, tk, tv, bs, n_blocks, blk, scale, out, lse, w, w_bytes, stream):
                 return lib().ihip_sparse_attn_decode_rope(shape, tq, tk, tv, bs, n_blocks, blk, scale, rope.ref(),
@@ -287,13 +318,20 @@ class Layer:
         return out
 
     def decode_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
-                     out_blocks=None, lse=None, rope: Optional["Rope"] = None, pooling: Optional[int] = None):
+                     out_blocks=None, lse=None, rope: Optional["Rope"] = None, pooling: Optional[int] = None,
+                     kv_scales: Optional[Sequence[float]] = None):
         """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d]."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+        if kv_scales is not None:
+            _check(lib().ihip_decode_layer_fp8kv(ctypes.byref(self.shape), _tensor(q, "q"), _tensor8(k, "k"),
+                                                 _tensor8(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                                 sm_scale, kv_scales[0], kv_scales[1], _ptr(out), _ptr(lse),
+                                                 _ptr(out_blocks), _ptr(ws), ws.numel(), _stream()))
+            return out
         if pooling is not None:
             _check(lib().ihip_decode_layer_pooled(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                                   _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),

@@ -74,12 +74,13 @@ void profile_end(hipStream_t st)
 
 // kernels' host launchers
 int32_t launch_prune_stage(const ihip_shape &, const ihip_tensor &, const ihip_tensor &, const int32_t *,
-                           int, int, int, int, float *, int32_t *, const BankView *, const ihip_rope *, hipStream_t);
+                           int, int, int, int, float *, int32_t *, const BankView *, const ihip_rope *, hipStream_t,
+                           const KvFormat * = nullptr);
 int32_t launch_select_blocks(const ihip_shape &, const float *, int, const int32_t *, int, int, int, int,
                              int32_t *, bool, hipStream_t);
 int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                            const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
-                           void *, const BankView *, const ihip_rope *, hipStream_t);
+                           void *, const BankView *, const ihip_rope *, hipStream_t, const KvFormat * = nullptr);
 BankView cache_bank_view(const ihip_cache *, int);
 void cache_describe(const ihip_cache *, int32_t *, int32_t *, int64_t *, ihip_tensor *, ihip_tensor *);
 size_t attn_decode_workspace(const ihip_shape &, int, int);
@@ -88,6 +89,22 @@ int32_t launch_attn_prefill(const ihip_shape &, const ihip_tensor &, const ihip_
                             hipStream_t);
 
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// FP8 K/V tensors: strides count bytes; rows 16-byte aligned like the bf16 ones
+static int32_t check_tensor8(const ihip_tensor &t, const char *who, const char *name)
+{
+    if (!t.ptr) return fail(IHIP_ERR_INVALID_ARG, "%s: %s.ptr is NULL", who, name);
+    if (((uintptr_t)t.ptr | (uintptr_t)t.stride_b | (uintptr_t)t.stride_h | (uintptr_t)t.stride_t) & 15)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: %s rows must be 16-byte aligned", who, name);
+    if (t.stride_t < kD) return fail(IHIP_ERR_INVALID_ARG, "%s: %s.stride_t = %lld < d", who, name, (long long)t.stride_t);
+    return IHIP_OK;
+}
+static int32_t check_scales(const char *who, float k_scale, float v_scale)
+{
+    if (!(k_scale > 0.f) || !(v_scale > 0.f) || k_scale > 3.0e38f || v_scale > 3.0e38f)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: scales must be positive and finite", who);
+    return IHIP_OK;
+}
 
 static int32_t check_shape(const ihip_shape *s, const char *who)
 {
@@ -192,7 +209,8 @@ static PlanLayout plan_layout(const ihip_shape &s, int n_stages, const int32_t *
 static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                                  const int32_t *chunks, const int32_t *keeps, int first_stage,
                                  int32_t *const *stage_out, float *scores, const BankView *bank,
-                                 const ihip_rope *rope, bool all_heads, hipStream_t st)
+                                 const ihip_rope *rope, bool all_heads, hipStream_t st,
+                                 const KvFormat *fmt = nullptr)
 {
     for (int i = first_stage; i < n_stages; ++i) {
         const int32_t *parents = i == 0 ? nullptr : stage_out[i - 1];
@@ -200,7 +218,7 @@ static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, cons
         const int parent_chunk = i == 0 ? 0 : chunks[i - 1];
         const int slots = i == 0 ? stage1_slots(s, chunks[0]) : n_parent * (parent_chunk / chunks[i]);
         int32_t rc = launch_prune_stage(s, q, k, parents, n_parent, parent_chunk, chunks[i], slots, scores,
-                                        nullptr, bank, rope, st);
+                                        nullptr, bank, rope, st, fmt);
         if (rc != IHIP_OK) return rc;
         rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i],
                                   stage_out[i], all_heads, st);
@@ -211,13 +229,14 @@ static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, cons
 
 static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
                               const int32_t *chunks, const int32_t *keeps, int32_t *out_block_starts,
-                              char *ws, const BankView *bank, const ihip_rope *rope, bool all_heads, hipStream_t st)
+                              char *ws, const BankView *bank, const ihip_rope *rope, bool all_heads, hipStream_t st,
+                              const KvFormat *fmt = nullptr)
 {
     const PlanLayout L = plan_layout(s, n_stages, chunks, keeps);
     int32_t *stage_out[8];
     for (int i = 0; i < n_stages; ++i)
         stage_out[i] = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
-    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, rope, all_heads, st);
+    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, rope, all_heads, st, fmt);
 }
 
 }  // namespace ihip
@@ -245,14 +264,14 @@ int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk)
     return stage1_slots(*shape, chunk);
 }
 
-static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
+static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
                          int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
                          float *out_scores, int32_t *out_rep, void *stream)
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
+    if ((rc = (fmt ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
     if ((rc = check_slots(who, parent_starts, n_parent, parent_chunk, chunk, max_chunks)) != IHIP_OK) return rc;
     if (!parent_starts && max_chunks < stage1_slots(*shape, chunk))
         return fail(IHIP_ERR_INVALID_ARG, "%s: max_chunks = %d < %d slots of the first stage", who, max_chunks,
@@ -261,14 +280,14 @@ static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const i
     if (shape->b_q == 1 && shape->Tq != 1)
         return fail(IHIP_ERR_INVALID_ARG, "%s: b_q == 1 is the decode path and needs Tq == 1", who);
     return launch_prune_stage(*shape, q, k, parent_starts, n_parent, parent_chunk, chunk, max_chunks, out_scores,
-                              out_rep, nullptr, rope, (hipStream_t)stream);
+                              out_rep, nullptr, rope, (hipStream_t)stream, fmt);
 }
 
 int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
                          int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
                          float *out_scores, int32_t *out_rep, void *stream)
 {
-    return prune_stage_entry("ihip_prune_stage", nullptr, shape, q, k, parent_starts, n_parent, parent_chunk, chunk,
+    return prune_stage_entry("ihip_prune_stage", nullptr, nullptr, shape, q, k, parent_starts, n_parent, parent_chunk, chunk,
                              max_chunks, out_scores, out_rep, stream);
 }
 
@@ -277,7 +296,7 @@ int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tenso
                               const ihip_rope *rope, float *out_scores, int32_t *out_rep, void *stream)
 {
     if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_prune_stage_rope: rope is NULL");
-    return prune_stage_entry("ihip_prune_stage_rope", rope, shape, q, k, parent_starts, n_parent, parent_chunk, chunk,
+    return prune_stage_entry("ihip_prune_stage_rope", rope, nullptr, shape, q, k, parent_starts, n_parent, parent_chunk, chunk,
                              max_chunks, out_scores, out_rep, stream);
 }
 
@@ -294,6 +313,17 @@ static int32_t select_blocks_entry(const char *who, bool all_heads, const ihip_s
         return fail(IHIP_ERR_INVALID_ARG, "%s: scores / out_starts is NULL", who);
     return launch_select_blocks(*shape, scores, max_chunks, parent_starts, n_parent, parent_chunk, chunk, keep,
                                 out_starts, all_heads, (hipStream_t)stream);
+}
+
+int32_t ihip_prune_stage_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
+                               int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
+                               float k_scale, float *out_scores, int32_t *out_rep, void *stream)
+{
+    const int32_t rc = check_scales("ihip_prune_stage_fp8kv", k_scale, 1.0f);
+    if (rc != IHIP_OK) return rc;
+    const KvFormat fmt{true, k_scale, 1.0f};
+    return prune_stage_entry("ihip_prune_stage_fp8kv", nullptr, &fmt, shape, q, k, parent_starts, n_parent,
+                             parent_chunk, chunk, max_chunks, out_scores, out_rep, stream);
 }
 
 int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
@@ -321,7 +351,7 @@ int32_t ihip_select_blocks_pooled(const ihip_shape *shape, const float *scores, 
                                parent_starts, n_parent, parent_chunk, chunk, keep, out_starts, stream);
 }
 
-static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                 const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
                                 void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
 {
@@ -329,8 +359,8 @@ static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const i
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if ((rc = (fmt ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
+    if ((rc = (fmt ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
     if (n_blocks < 0 || !pow2(block)) return fail(IHIP_ERR_INVALID_ARG, "%s: n_blocks = %d, block = %d", who, n_blocks, block);
     if (n_blocks > 0 && !block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: block_starts is NULL", who);
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
@@ -338,15 +368,27 @@ static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const i
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     return launch_attn_decode(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, ws,
-                              nullptr, rope, (hipStream_t)stream);
+                              nullptr, rope, (hipStream_t)stream, fmt);
 }
 
 int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                 const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
                                 void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
 {
-    return attn_decode_entry("ihip_sparse_attn_decode", nullptr, shape, q, k, v, block_starts, n_blocks, block,
+    return attn_decode_entry("ihip_sparse_attn_decode", nullptr, nullptr, shape, q, k, v, block_starts, n_blocks, block,
                              sm_scale, out, out_lse, ws, ws_bytes, stream);
+}
+
+int32_t ihip_sparse_attn_decode_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
+                                      float k_scale, float v_scale, void *out, float *out_lse, void *ws,
+                                      size_t ws_bytes, void *stream)
+{
+    const int32_t rc = check_scales("ihip_sparse_attn_decode_fp8kv", k_scale, v_scale);
+    if (rc != IHIP_OK) return rc;
+    const KvFormat fmt{true, k_scale, v_scale};
+    return attn_decode_entry("ihip_sparse_attn_decode_fp8kv", nullptr, &fmt, shape, q, k, v, block_starts, n_blocks,
+                             block, sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
 int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
@@ -355,7 +397,7 @@ int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihi
                                      void *stream)
 {
     if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_sparse_attn_decode_rope: rope is NULL");
-    return attn_decode_entry("ihip_sparse_attn_decode_rope", rope, shape, q, k, v, block_starts, n_blocks, block,
+    return attn_decode_entry("ihip_sparse_attn_decode_rope", rope, nullptr, shape, q, k, v, block_starts, n_blocks, block,
                              sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
@@ -399,7 +441,7 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, in
 
 static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                                  ihip_tensor v, const ihip_cache *cache, const ihip_rope *rope, bool all_heads,
-                                 int32_t n_stages,
+                                 const KvFormat *fmt, int32_t n_stages,
                                  const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                                  float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
@@ -407,8 +449,8 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if ((rc = (fmt ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
+    if ((rc = (fmt ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
     if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
     const int last = n_stages - 1;
@@ -425,17 +467,17 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
     if (cache && rope) return fail(IHIP_ERR_UNSUPPORTED, "%s: dynamic RoPE is not built for the host tier", who);
     rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, cache ? &mask_bank : nullptr, rope,
-                        all_heads, (hipStream_t)stream);
+                        all_heads, (hipStream_t)stream, fmt);
     if (rc != IHIP_OK) return rc;
     return launch_attn_decode(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
-                              w + L.total + blocks_bytes, cache ? &sa_bank : nullptr, rope, (hipStream_t)stream);
+                              w + L.total + blocks_bytes, cache ? &sa_bank : nullptr, rope, (hipStream_t)stream, fmt);
 }
 
 int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
                           const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                           float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
-    return decode_layer_impl("ihip_decode_layer", shape, q, k, v, nullptr, nullptr, false, n_stages, chunk_sizes,
+    return decode_layer_impl("ihip_decode_layer", shape, q, k, v, nullptr, nullptr, false, nullptr, n_stages, chunk_sizes,
                              keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -447,8 +489,20 @@ int32_t ihip_decode_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_te
     const int32_t rc = check_pooling("ihip_decode_layer_pooled", pooling);
     if (rc != IHIP_OK) return rc;
     return decode_layer_impl("ihip_decode_layer_pooled", shape, q, k, v, nullptr, nullptr,
-                             pooling == IHIP_POOL_ALL_HEADS, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
+                             pooling == IHIP_POOL_ALL_HEADS, nullptr, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
                              out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                                const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, float k_scale,
+                                float v_scale, void *out, float *out_lse, int32_t *out_block_starts, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    const int32_t rc = check_scales("ihip_decode_layer_fp8kv", k_scale, v_scale);
+    if (rc != IHIP_OK) return rc;
+    const KvFormat fmt{true, k_scale, v_scale};
+    return decode_layer_impl("ihip_decode_layer_fp8kv", shape, q, k, v, nullptr, nullptr, false, &fmt, n_stages,
+                             chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
 int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
@@ -457,7 +511,7 @@ int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tens
                                void *stream)
 {
     if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_decode_layer_rope: rope is NULL");
-    return decode_layer_impl("ihip_decode_layer_rope", shape, q, k, v, nullptr, rope, false, n_stages, chunk_sizes, keeps,
+    return decode_layer_impl("ihip_decode_layer_rope", shape, q, k, v, nullptr, rope, false, nullptr, n_stages, chunk_sizes, keeps,
                              sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -475,7 +529,7 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
     if (shape && (shape->B != B || shape->Hkv != Hkv || shape->max_seq_len > T_alloc))
         return fail(IHIP_ERR_INVALID_ARG, "%s: shape (B %d, Hkv %d, max_seq_len %d) does not fit the cache (%d, %d, %lld)",
                     who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
-    return decode_layer_impl(who, shape, q, hk, hv, cache, nullptr, false, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
+    return decode_layer_impl(who, shape, q, hk, hv, cache, nullptr, false, nullptr, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
                              out_block_starts, ws, ws_bytes, stream);
 }
 

@@ -178,6 +178,44 @@ __device__ inline void unpack8(const uint4 &k, float (&f)[8])
     f[6] = bf16_lo(k.w); f[7] = bf16_hi(k.w);
 }
 
+// ---- FP8 (OCP E4M3) K/V ------------------------------------------------------
+// An FP8 row is 128 bytes: 8 bytes per lane of a 16-lane row group.  The hardware
+// converter handles two bytes of one 16-bit half of a word at a time; E4M3 values
+// are a subset of bf16, so repacking them as bf16 is exact.
+struct KvFormat {             // nullptr / fp8 == false: bf16 K and V
+    bool fp8;
+    float k_scale, v_scale;   // value = scale * decoded byte (one scale per tensor)
+};
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ inline void unpack8_fp8(const uint2 &k, float (&f)[8])
+{
+    const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8(k.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(k.x, true);
+    const f32x2_t c = __builtin_amdgcn_cvt_pk_f32_fp8(k.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(k.y, true);
+    f[0] = a[0]; f[1] = a[1]; f[2] = b[0]; f[3] = b[1];
+    f[4] = c[0]; f[5] = c[1]; f[6] = d[0]; f[7] = d[1];
+}
+__device__ inline float dot8(const uint2 &k, const float (&q)[8])
+{
+    float f[8];
+    unpack8_fp8(k, f);
+    float s = f[0] * q[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) s = fmaf(f[i], q[i], s);
+    return s;
+}
+__device__ inline uint4 fp8x8_to_bf16x8(const uint2 &k)
+{
+    float f[8];
+    unpack8_fp8(k, f);
+    uint4 r;
+    r.x = (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xffff0000u);
+    r.y = (__float_as_uint(f[2]) >> 16) | (__float_as_uint(f[3]) & 0xffff0000u);
+    r.z = (__float_as_uint(f[4]) >> 16) | (__float_as_uint(f[5]) & 0xffff0000u);
+    r.w = (__float_as_uint(f[6]) >> 16) | (__float_as_uint(f[7]) & 0xffff0000u);
+    return r;
+}
+__device__ inline void unpack8(const uint2 &k, float (&f)[8]) { unpack8_fp8(k, f); }
+
 // ---- cross-lane -----------------------------------------------------------
 template <int CTRL>
 __device__ inline float dpp_f32(float v)

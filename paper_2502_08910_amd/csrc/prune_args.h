@@ -22,6 +22,8 @@ struct PruneArgs {
     float *out_scores;
     int32_t *out_rep;
     BankView bank;            // used by the cached instantiations only (K then points to host memory)
+    float k_scale;            // FP8 instantiations only: the scores are multiplied by it (K strides then
+                              // count 2-byte units of the byte rows)
 };
 
 template <bool CACHED> struct KeySource;

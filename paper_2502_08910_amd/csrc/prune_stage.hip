@@ -12,9 +12,12 @@
 
 namespace ihip {
 
-template <int G, int U, bool CACHED>
+// KV8: K rows are 128 bytes of E4M3 (8 bytes per lane); the dot products run on the decoded values
+// and the chunk score is multiplied by the tensor's scale.
+template <int G, int U, bool CACHED, bool KV8>
 __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 {
+    using piece_t = typename std::conditional<KV8, uint2, uint4>::type;     // a lane's share of a row
     const int p = blockIdx.y;
     const Problem pr = problem_of(a.ge, p);
     const int l16 = threadIdx.x & 15;
@@ -32,7 +35,10 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
     }
     const typename KeySource<CACHED>::type src = KeySource<CACHED>::make(a, pr);
     const bool leader = l16 == 0;
-    auto load_row = [&](int pos) { return *reinterpret_cast<const uint4 *>(src.row(pos, leader) + l16 * 8); };
+    auto load_row = [&](int pos) {
+        return *reinterpret_cast<const piece_t *>(src.row(pos, leader) + l16 * (KV8 ? 4 : 8));
+    };
+    const piece_t zero = {};
 
     int start[U], len[U];
     bool valid[U];
@@ -51,12 +57,12 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 
     // first key of the chunk, and the first key of its right half: common to all heads
     {
-        uint4 r0[U], r1[U];
+        piece_t r0[U], r1[U];
         const int mid = a.chunk >> 1;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            r0[u] = make_uint4(0, 0, 0, 0);
-            r1[u] = make_uint4(0, 0, 0, 0);
+            r0[u] = zero;
+            r1[u] = zero;
             if (valid[u]) r0[u] = load_row(start[u]);
             if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid);
         }
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 
     // remaining halvings: G*U independent row reads per step
     for (int half = a.chunk >> 2; half >= 1; half >>= 1) {
-        uint4 r[U][G];
+        piece_t r[U][G];
         bool ok[U][G];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -83,7 +89,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
             for (int h = 0; h < G; ++h) {
                 const int mid = off[u][h] + half;
                 ok[u][h] = mid < len[u];
-                r[u][h] = make_uint4(0, 0, 0, 0);
+                r[u][h] = zero;
                 if (ok[u][h]) r[u][h] = load_row(start[u] + mid);
             }
         }
@@ -107,6 +113,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
         float best = sigma[u][0];
 #pragma unroll
         for (int h = 1; h < G; ++h) best = fmaxf(best, sigma[u][h]);
+        if (KV8) best *= a.k_scale;
         if (l16 == 0) a.out_scores[(int64_t)p * a.max_chunks + j] = valid[u] ? best : -INFINITY;
         if (a.out_rep != nullptr && l16 < G) {
             int o = off[u][0];
@@ -370,15 +377,17 @@ static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, hipSt
 }
 
 template <int G>
-static void launch_decode(const PruneArgs &a, int P, hipStream_t st)
+static void launch_decode(const PruneArgs &a, int P, bool fp8, hipStream_t st)
 {
     constexpr int U = 2;
     dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
     KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
-    if (a.bank.page_table != nullptr)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, true>), grid, dim3(256), 0, st, a);
+    if (fp8)
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, false, true>), grid, dim3(256), 0, st, a);
+    else if (a.bank.page_table != nullptr)
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, true, false>), grid, dim3(256), 0, st, a);
     else
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, false>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, false, false>), grid, dim3(256), 0, st, a);
 }
 
 int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, hipStream_t st);
@@ -386,13 +395,16 @@ int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int st
 int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                            const int32_t *parent_starts, int n_parent, int parent_chunk, int chunk,
                            int max_chunks, float *out_scores, int32_t *out_rep, const BankView *bank,
-                           const ihip_rope *rope, hipStream_t st)
+                           const ihip_rope *rope, hipStream_t st, const KvFormat *fmt)
 {
     PruneArgs a;
+    const bool fp8 = fmt && fmt->fp8;
+    a.k_scale = fp8 ? fmt->k_scale : 1.0f;
     a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
+    if (fp8) { a.k_sb /= 2; a.k_sh /= 2; a.k_st /= 2; }      // byte strides (even) in 2-byte units
     a.parent_starts = parent_starts;
     a.n_parent = n_parent;
     a.ratio_log2 = parent_starts ? __builtin_ctz(parent_chunk / chunk) : 0;
@@ -403,6 +415,8 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (max_chunks == 0 || P == 0) return IHIP_OK;
     if (bank && s.b_q != 1) return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: the host tier serves decode only");
+    if (fp8 && (s.b_q != 1 || bank || (rope && rope->prune_style != IHIP_ROPE_NONE)))
+        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: FP8 keys are built for plain decode from device memory only");
     if (rope && rope->prune_style != IHIP_ROPE_NONE) {
         if (s.b_q != 1 || bank)
             return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: dynamic RoPE is built for decode from device memory only");
@@ -419,10 +433,10 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     }
     if (s.b_q == 1) {
         switch (a.ge.G) {
-        case 1: launch_decode<1>(a, P, st); break;
-        case 2: launch_decode<2>(a, P, st); break;
-        case 4: launch_decode<4>(a, P, st); break;
-        case 8: launch_decode<8>(a, P, st); break;
+        case 1: launch_decode<1>(a, P, fp8, st); break;
+        case 2: launch_decode<2>(a, P, fp8, st); break;
+        case 4: launch_decode<4>(a, P, fp8, st); break;
+        case 8: launch_decode<8>(a, P, fp8, st); break;
         default: return fail(IHIP_ERR_UNSUPPORTED, "Hq/Hkv = %d not in {1,2,4,8}", a.ge.G);
         }
         return check_launch("prune_stage (decode)");

@@ -8,6 +8,7 @@
 // lane) and keeps an online-softmax state for all G heads; groups are merged
 // through LDS, splits by a second small kernel (log-sum-exp merge).
 #include "common.h"
+#include <type_traits>
 
 namespace ihip {
 
@@ -30,7 +31,12 @@ struct AttnDecodeArgs {
     float *out_lse;      // [B, Hq] or null
     BankView bank;       // used by the cached instantiations only (K/V then point to host memory)
     const float *rope_cos, *rope_sin;   // streaming-style RoPE instantiations only: fp32 [n_pos][d/2]
+    float v_scale;       // FP8 instantiations: the output is multiplied by it (the K scale is folded into
+                         // scale_log2e; K/V strides then count 2-byte units of the byte rows)
 };
+
+__device__ inline uint4 as_bf16x8(const uint4 &k) { return k; }
+__device__ inline uint4 as_bf16x8(const uint2 &k) { return fp8x8_to_bf16x8(k); }
 
 template <bool CACHED> struct KvSource;
 template <> struct KvSource<false> {
@@ -79,9 +85,12 @@ __device__ inline int slot_to_pos(const AttnDecodeArgs &a, const Problem &pr, in
 // order, are rotated to positions 0, 1, ..., n-1 and the query to n-1.  Attended slots are a
 // prefix of the block part of the slot list (blocks are ascending, empty ones last, only the last
 // one can be cut short), so a key's id is its slot, less the empty block slots for window keys.
-template <int G, bool CACHED, bool ROPE>
+// KV8: K and V rows are 128 bytes of E4M3 (8 bytes per lane), repacked exactly as bf16 for the dot.
+template <int G, bool CACHED, bool ROPE, bool KV8>
 __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const AttnDecodeArgs a)
 {
+    using piece_t = typename std::conditional<KV8, uint2, uint4>::type;     // a lane's share of a row
+    constexpr int kLaneOff = KV8 ? 4 : 8;                                   // in 2-byte units
     const int p = blockIdx.y, split = blockIdx.x;
     const Problem pr = problem_of(a.ge, p);
     const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
@@ -150,18 +159,18 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
                               ? slot_to_pos(a, pr, p, s0 + threadIdx.x, n_sink_eff, w0) : -1;
     __syncthreads();
     for (int base = s0 + grp; base < s1; base += kAttnGroups * UNR) {
-        uint4 kr[UNR], vr[UNR];
+        piece_t kr[UNR], vr[UNR];
         bool ok[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int slot = base + u * kAttnGroups;
             const int pos = slot < s1 ? sh_pos[slot - s0] : -1;
             ok[u] = pos >= 0;
-            kr[u] = make_uint4(0, 0, 0, 0);
-            vr[u] = make_uint4(0, 0, 0, 0);
+            kr[u] = piece_t{};
+            vr[u] = piece_t{};
             if (ok[u]) {
-                kr[u] = *reinterpret_cast<const uint4 *>(ksrc.row(pos, l16 == 0) + l16 * 8);
-                vr[u] = *reinterpret_cast<const uint4 *>(vsrc.row(pos, false) + l16 * 8);   // K did the bookkeeping
+                kr[u] = *reinterpret_cast<const piece_t *>(ksrc.row(pos, l16 == 0) + l16 * kLaneOff);
+                vr[u] = *reinterpret_cast<const piece_t *>(vsrc.row(pos, false) + l16 * kLaneOff);   // K did the bookkeeping
             }
         }
         // scores of the UNR tokens for all heads (log2 units), then one running-max update per batch
@@ -195,7 +204,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
             for (int u = 0; u < UNR; ++u)
 #pragma unroll
                 for (int h = 0; h < G; ++h)
-                    sc[u][h] = ok[u] ? row16_sum(dot8_bf16(kr[u], qp[h])) * a.scale_log2e : kNegBig;
+                    sc[u][h] = ok[u] ? row16_sum(dot8_bf16(as_bf16x8(kr[u]), qp[h])) * a.scale_log2e : kNegBig;
         }
         float pw[UNR][G], corr[G];
 #pragma unroll
@@ -312,7 +321,7 @@ __global__ __launch_bounds__(kD) void attn_decode_merge_kernel(const AttnDecodeA
         A = fmaf(w, a.part_acc[r * kD + c], A);
     }
     const int hq = pr.g * G + h;
-    a.out[((int64_t)pr.b * a.ge.Hq + hq) * kD + c] = (uint16_t)f32_to_bf16_bits(A / L);
+    a.out[((int64_t)pr.b * a.ge.Hq + hq) * kD + c] = (uint16_t)f32_to_bf16_bits(A / L * a.v_scale);
     if (a.out_lse != nullptr && c == 0)
         a.out_lse[(int64_t)pr.b * a.ge.Hq + hq] = (M + log2f(L)) * 0.69314718055994530942f;
 }
@@ -338,9 +347,11 @@ size_t attn_decode_workspace(const ihip_shape &s, int n_blocks, int block)
 int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                            const ihip_tensor &v, const int32_t *block_starts, int n_blocks, int block,
                            float sm_scale, void *out, float *out_lse, void *ws, const BankView *bank,
-                           const ihip_rope *rope, hipStream_t st)
+                           const ihip_rope *rope, hipStream_t st, const KvFormat *fmt)
 {
     AttnDecodeArgs a;
+    const bool fp8 = fmt && fmt->fp8;
+    a.v_scale = fp8 ? fmt->v_scale : 1.0f;
     const bool use_rope = rope && rope->attn_style != IHIP_ROPE_NONE;
     a.rope_cos = a.rope_sin = nullptr;
     if (use_rope) {
@@ -360,11 +371,17 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
     a.v = (const uint16_t *)v.ptr; a.v_sb = v.stride_b; a.v_sh = v.stride_h; a.v_st = v.stride_t;
+    if (fp8) {
+        if (bank || use_rope)
+            return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: FP8 K/V is built for plain decode from device memory only");
+        a.k_sb /= 2; a.k_sh /= 2; a.k_st /= 2;      // byte strides (even) in 2-byte units
+        a.v_sb /= 2; a.v_sh /= 2; a.v_st /= 2;
+    }
     a.block_starts = block_starts;
     a.n_blocks = n_blocks;
     a.block = block;
     a.block_log2 = __builtin_ctz(block);
-    a.scale_log2e = sm_scale * 1.44269504088896340736f;
+    a.scale_log2e = sm_scale * 1.44269504088896340736f * (fp8 ? fmt->k_scale : 1.0f);
     a.n_splits = decode_splits(s, n_blocks, block, &a.slots_per_split);
     const int P = s.B * s.Hkv;
     const int G = a.ge.G;
@@ -378,9 +395,10 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     KernelTimer timer("attn_decode_split", st);
     switch (G) {
 #define IHIP_AD_LAUNCH(GG)                                                                                          \
-    if (use_rope) hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, true>), grid, dim3(kAttnThreads), 0, st, a);   \
-    else if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, true, false>), grid, dim3(kAttnThreads), 0, st, a);  \
-    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, false>), grid, dim3(kAttnThreads), 0, st, a)
+    if (fp8) hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, false, true>), grid, dim3(kAttnThreads), 0, st, a);          \
+    else if (use_rope) hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, true, false>), grid, dim3(kAttnThreads), 0, st, a); \
+    else if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, true, false, false>), grid, dim3(kAttnThreads), 0, st, a);     \
+    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, false, false>), grid, dim3(kAttnThreads), 0, st, a)
     case 1: IHIP_AD_LAUNCH(1); break;
     case 2: IHIP_AD_LAUNCH(2); break;
     case 4: IHIP_AD_LAUNCH(4); break;
