@@ -57,6 +57,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg3-decode-1m-b8")
+    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
+                    help="decode workloads: fp8 = K and V quantised to E4M3 bytes (scale 1/64 each), a separate metric")
     ap.add_argument("--rope", default=None, choices=["relative", "chunk"],
                     help="decode workloads: dynamic RoPE in the pruning stages (this style) and the attention "
                          "(streaming style); a separate metric, no roofline / cpu_baseline objects")
@@ -109,7 +111,7 @@ def dominant(kernels):
 
 
 # ---------------------------------------------------------------------------
-def decode_oracle_sample(w, qs, kvs, seq_lens, budget_s):
+def decode_oracle_sample(w, qs, kvs, seq_lens, budget_s, kv_scales=None):
     """Times the CPU oracle on sequence 0 (all its KV heads), one query set
     (with its layer's K/V) after another until the budget is used; also returns
     the mean number of distinct K rows each stage scores per problem and the
@@ -124,7 +126,8 @@ def decode_oracle_sample(w, qs, kvs, seq_lens, budget_s):
         if layer not in host:
             host = {layer: (kvs[layer][0][0:1].cpu(), kvs[layer][1][0:1].cpu())}
         k0, v0 = host[layer]
-        o = oracle.Oracle(q[0:1].cpu(), k0, v0, [int(seq_lens[0])], w.b_q, w.n_sink, w.n_stream)
+        o = oracle.Oracle(q[0:1].cpu(), k0, v0, [int(seq_lens[0])], w.b_q, w.n_sink, w.n_stream,
+                          kv_scales=kv_scales)
         t0 = time.perf_counter()
         res = o.layer(w.stages)
         t_used += time.perf_counter() - t0
@@ -158,6 +161,22 @@ def bench_decode(args, w, torch, ihip, configs):
         q = configs.make_q(w, i, dev)
         configs.plant_needles(w, kvs[i % n_layers][0], q, i)
         qs.append(q)
+    kv_scales = None
+    if args.kv_dtype == "fp8":
+        # the same Gaussian K/V, quantised one sequence at a time (needles included)
+        from workloads import gen
+        kv_scales = (1.0 / 64, 1.0 / 64)
+        kvs8 = []
+        for (kb, vb) in kvs:
+            k8 = torch.empty(kb.shape, dtype=torch.uint8, device=dev)
+            v8 = torch.empty(vb.shape, dtype=torch.uint8, device=dev)
+            for b in range(w.B):
+                k8[b] = gen.to_e4m3(kb[b], kv_scales[0])
+                v8[b] = gen.to_e4m3(vb[b], kv_scales[1])
+            kvs8.append((k8, v8))
+        kvs = kvs8
+        del kvs8, kb, vb
+        torch.cuda.empty_cache()
     k, v = kvs[0]
     seq_lens = torch.full((w.B,), w.T, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
@@ -166,6 +185,7 @@ def bench_decode(args, w, torch, ihip, configs):
     L = ihip.Layer(qs[0], k, seq_lens, w.b_q, w.n_sink, w.n_stream)
     ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
     out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
+    assert not (kv_scales and (args.refresh or args.rope)), "fp8 K/V: plain decode layer only"
 
     refresh = None
     if args.refresh:
@@ -191,20 +211,20 @@ def bench_decode(args, w, torch, ihip, configs):
     else:
         def step(i):
             kl, vl = kvs[i % n_layers]
-            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out)
+            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out, kv_scales=kv_scales)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 
     cpu = sample = None
     if args.cpu_seconds > 0 and not args.rope:
-        sample = decode_oracle_sample(w, qs, kvs, seq_lens.cpu().tolist(), args.cpu_seconds)
+        sample = decode_oracle_sample(w, qs, kvs, seq_lens.cpu().tolist(), args.cpu_seconds, kv_scales)
         per_seq_call = sample["seconds"] / sample["layer_calls_one_sequence"]
         cpu = {"value": per_seq_call * w.B * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
                "sample": f"sequence 0 of {w.B} (its {w.Hkv} KV heads), {sample['layer_calls_one_sequence']} "
                          f"layer calls with different queries, {sample['seconds']:.1f} s; scaled x{w.B} to the batch"}
 
     P = w.B * w.Hkv
-    row_bytes = w.d * 2
+    row_bytes = w.d * (1 if kv_scales else 2)
     roofline = whole = None
     if sample is not None and refresh is None:
         alg = {}
@@ -226,11 +246,12 @@ def bench_decode(args, w, torch, ihip, configs):
             dom = dominant(kernels)
             ach = kernels[dom]["alg_GBps"]
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                        "frac": ach / HBM_PEAK_GBS,
+                        "traffic": None if kv_scales else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                         "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
     return {
         "metric": ("sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer")
-        + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else ""),
+        + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else "") + ("_fp8_kv" if kv_scales else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
@@ -464,7 +485,8 @@ def main():
     line = {"metric": body.pop("metric"), "value": body.pop("value"), "unit": body.pop("unit"), "n_gpus": 1,
             "steps": body.pop("steps"), "warmup": body.pop("warmup")}
     line["ms_per_step"] = line["value"] / 1e3
-    line.update({"higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+    line.update({"higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+                 "dtype": "bf16 (K/V stored as fp8 e4m3)" if args.kv_dtype == "fp8" else "bf16",
                  "data": "synthetic"})
     line.update(body)
     print(json.dumps(line))
