@@ -152,6 +152,37 @@ int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_ten
                                 float sm_scale, float k_scale, float v_scale, void *out, float *out_lse,
                                 int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Paged KV cache (the serving systems the paper runs in keep K and V in
+ * fixed-size pages): the *_paged entry points take K and V as page pools plus a
+ * block table.  k_pool / v_pool: ptr = page 0, stride_b = elements between
+ * pages, stride_h = between the KV heads of a page, stride_t = between the
+ * tokens of a page.  block_table: device int32 [B][table_stride], the page id
+ * of logical page i (tokens [i*page_tokens, (i+1)*page_tokens)) of sequence b;
+ * entries beyond a sequence's length are never read.  page_tokens is a power
+ * of two and table_stride * page_tokens >= max_seq_len.  Everything else as in
+ * the entry points of the same names without the suffix.  Built for decode
+ * (Tq == b_q == 1), bf16.
+ */
+typedef struct ihip_paged_kv {
+    const int32_t *block_table;
+    int32_t table_stride;
+    int32_t page_tokens;
+} ihip_paged_kv;
+int32_t ihip_prune_stage_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
+                               const ihip_paged_kv *paged, const int32_t *parent_starts, int32_t n_parent,
+                               int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
+                               float *out_scores, int32_t *out_rep, void *stream);
+int32_t ihip_sparse_attn_decode_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
+                                      ihip_tensor v_pool, const ihip_paged_kv *paged,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                      float sm_scale, void *out, float *out_lse, void *ws, size_t ws_bytes,
+                                      void *stream);
+int32_t ihip_decode_layer_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, ihip_tensor v_pool,
+                                const ihip_paged_kv *paged, int32_t n_stages, const int32_t *chunk_sizes,
+                                const int32_t *keeps, float sm_scale, void *out, float *out_lse,
+                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+
 /* ihip_prune_stage with rope->prune_style applied (decode only); rope must not be NULL. */
 int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                               const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,

@@ -51,6 +51,12 @@ EXPORTS = {
                                               c_f, c_f, c_f, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, c_f, c_f,
                                         vp, vp, vp, vp, c_sz, vp]),
+    "ihip_prune_stage_paged": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, vp, vp, c_i32, c_i32, c_i32, c_i32,
+                                       vp, vp, vp]),
+    "ihip_sparse_attn_decode_paged": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, vp, c_i32, c_i32,
+                                              c_f, vp, vp, vp, c_sz, vp]),
+    "ihip_decode_layer_paged": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, vp, vp, c_f,
+                                        vp, vp, vp, vp, c_sz, vp]),
     "ihip_stage1_slots": (c_i32, [ctypes.POINTER(Shape), c_i32]),
     "ihip_select_blocks": (c_i32, [ctypes.POINTER(Shape), vp, c_i32, vp, c_i32, c_i32, c_i32, c_i32,
                                    vp, vp]),
@@ -187,6 +193,25 @@ class Rope:
         return ctypes.byref(self.c)
 
 
+class PagedStruct(ctypes.Structure):
+    _fields_ = [("block_table", vp), ("table_stride", c_i32), ("page_tokens", c_i32)]
+
+
+class PagedKV:
+    """ihip_paged_kv: K / V page pools [n_pages, Hkv, page_tokens, d] (bf16, any strides with a
+    contiguous last dim) and the device block table int32 [B, table_stride]."""
+
+    def __init__(self, k_pool: torch.Tensor, v_pool: torch.Tensor, block_table: torch.Tensor):
+        if block_table.dtype != torch.int32 or not block_table.is_cuda or block_table.dim() != 2 \
+                or not block_table.is_contiguous():
+            raise IhipError("block_table: need a contiguous int32 device tensor [B, pages]")
+        self.k_pool, self.v_pool, self.block_table = k_pool, v_pool, block_table
+        self.c = PagedStruct(block_table.data_ptr(), block_table.shape[1], k_pool.shape[2])
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
 class Layer:
     """Shape of one attention call plus the device seq_lens; the methods are
     the C entry points of the same names."""
@@ -226,8 +251,9 @@ class Layer:
     # -- entry points -------------------------------------------------------
     def prune_stage(self, q, k, chunk: int, parent_starts: Optional[torch.Tensor] = None,
                     parent_chunk: int = 0, want_rep: bool = False, rope: Optional["Rope"] = None,
-                    k_scale: Optional[float] = None):
-        """-> scores fp32 [P, slots], rep int32 [B,Hq,Mq,slots] or None.  k_scale: k holds E4M3 bytes."""
+                    k_scale: Optional[float] = None, paged: Optional["PagedKV"] = None):
+        """-> scores fp32 [P, slots], rep int32 [B,Hq,Mq,slots] or None.  k_scale: k holds E4M3 bytes;
+        paged: k is ignored, the K pool of `paged` is read through its block table."""
         if parent_starts is None:
             n_parent, slots = 0, self.stage1_slots(chunk)
         else:
@@ -236,6 +262,12 @@ class Layer:
         scores = torch.empty((self.P, slots), dtype=torch.float32, device=self.device)
         rep = torch.empty((self.B, self.Hq, self.Tq // self.b_q, slots), dtype=torch.int32,
                           device=self.device) if want_rep else None
+        if paged is not None:
+            _check(lib().ihip_prune_stage_paged(ctypes.byref(self.shape), _tensor(q, "q"),
+                                                _tensor(paged.k_pool, "k_pool"), paged.ref(), _ptr(parent_starts),
+                                                n_parent, parent_chunk, chunk, slots, _ptr(scores), _ptr(rep),
+                                                _stream()))
+            return scores, rep
         if k_scale is not None:
             _check(lib().ihip_prune_stage_fp8kv(ctypes.byref(self.shape), _tensor(q, "q"), _tensor8(k, "k"),
                                                 _ptr(parent_starts), n_parent, parent_chunk, chunk, slots,
@@ -281,7 +313,15 @@ class Layer:
         return out, lse
 
     def sparse_attn_decode(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None,
-                           rope: Optional["Rope"] = None, kv_scales: Optional[Sequence[float]] = None):
+                           rope: Optional["Rope"] = None, kv_scales: Optional[Sequence[float]] = None,
+                           paged: Optional["PagedKV"] = None):
+        if paged is not None:
+            def fn(shape, tq, tk, tv, bs, n_blocks, blk, scale, out, lse, w, w_bytes, stream):
+                return lib().ihip_sparse_attn_decode_paged(shape, tq, _tensor(paged.k_pool, "k_pool"),
+                                                           _tensor(paged.v_pool, "v_pool"), paged.ref(), bs, n_blocks,
+                                                           blk, scale, out, lse, w, w_bytes, stream)
+            return self._attn(fn, OP_ATTN_DECODE, q, paged.k_pool, paged.v_pool, block_starts, block, sm_scale,
+                              want_lse, ws)
         if kv_scales is not None:
             n_blocks = block_starts.shape[-1]
             sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
@@ -319,13 +359,21 @@ class Layer:
 
     def decode_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
                      out_blocks=None, lse=None, rope: Optional["Rope"] = None, pooling: Optional[int] = None,
-                     kv_scales: Optional[Sequence[float]] = None):
-        """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d]."""
+                     kv_scales: Optional[Sequence[float]] = None, paged: Optional["PagedKV"] = None):
+        """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d].
+        paged: k and v are ignored, the pools of `paged` are read through its block table."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+        if paged is not None:
+            _check(lib().ihip_decode_layer_paged(ctypes.byref(self.shape), _tensor(q, "q"),
+                                                 _tensor(paged.k_pool, "k_pool"), _tensor(paged.v_pool, "v_pool"),
+                                                 paged.ref(), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                                 sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),
+                                                 ws.numel(), _stream()))
+            return out
         if kv_scales is not None:
             _check(lib().ihip_decode_layer_fp8kv(ctypes.byref(self.shape), _tensor(q, "q"), _tensor8(k, "k"),
                                                  _tensor8(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),

@@ -99,6 +99,18 @@ static int32_t check_tensor8(const ihip_tensor &t, const char *who, const char *
     if (t.stride_t < kD) return fail(IHIP_ERR_INVALID_ARG, "%s: %s.stride_t = %lld < d", who, name, (long long)t.stride_t);
     return IHIP_OK;
 }
+// paged K/V: pools through strides (stride_b = elements between pages) + a block table
+static int32_t check_paged(const char *who, const ihip_shape *shape, const ihip_paged_kv *pg, KvFormat *fmt)
+{
+    if (!pg || !pg->block_table) return fail(IHIP_ERR_INVALID_ARG, "%s: paged / block_table is NULL", who);
+    if (!pow2(pg->page_tokens)) return fail(IHIP_ERR_INVALID_ARG, "%s: page_tokens = %d is not a power of two", who, pg->page_tokens);
+    if (shape && (int64_t)pg->table_stride * pg->page_tokens < shape->max_seq_len)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: the block table covers %lld tokens, max_seq_len is %d", who,
+                    (long long)pg->table_stride * pg->page_tokens, shape->max_seq_len);
+    *fmt = KvFormat{false, 1.0f, 1.0f, PagedView{pg->block_table, pg->table_stride, __builtin_ctz(pg->page_tokens)}};
+    return IHIP_OK;
+}
+
 static int32_t check_scales(const char *who, float k_scale, float v_scale)
 {
     if (!(k_scale > 0.f) || !(v_scale > 0.f) || k_scale > 3.0e38f || v_scale > 3.0e38f)
@@ -271,7 +283,7 @@ static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const K
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = (fmt ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
     if ((rc = check_slots(who, parent_starts, n_parent, parent_chunk, chunk, max_chunks)) != IHIP_OK) return rc;
     if (!parent_starts && max_chunks < stage1_slots(*shape, chunk))
         return fail(IHIP_ERR_INVALID_ARG, "%s: max_chunks = %d < %d slots of the first stage", who, max_chunks,
@@ -326,6 +338,17 @@ int32_t ihip_prune_stage_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tens
                              parent_chunk, chunk, max_chunks, out_scores, out_rep, stream);
 }
 
+int32_t ihip_prune_stage_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, const ihip_paged_kv *paged,
+                               const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk, int32_t chunk,
+                               int32_t max_chunks, float *out_scores, int32_t *out_rep, void *stream)
+{
+    KvFormat fmt;
+    const int32_t rc = check_paged("ihip_prune_stage_paged", shape, paged, &fmt);
+    if (rc != IHIP_OK) return rc;
+    return prune_stage_entry("ihip_prune_stage_paged", nullptr, &fmt, shape, q, k_pool, parent_starts, n_parent,
+                             parent_chunk, chunk, max_chunks, out_scores, out_rep, stream);
+}
+
 int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
                            const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk, int32_t chunk,
                            int32_t keep, int32_t *out_starts, void *stream)
@@ -359,8 +382,8 @@ static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const K
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = (fmt ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
-    if ((rc = (fmt ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
     if (n_blocks < 0 || !pow2(block)) return fail(IHIP_ERR_INVALID_ARG, "%s: n_blocks = %d, block = %d", who, n_blocks, block);
     if (n_blocks > 0 && !block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: block_starts is NULL", who);
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
@@ -389,6 +412,18 @@ int32_t ihip_sparse_attn_decode_fp8kv(const ihip_shape *shape, ihip_tensor q, ih
     const KvFormat fmt{true, k_scale, v_scale};
     return attn_decode_entry("ihip_sparse_attn_decode_fp8kv", nullptr, &fmt, shape, q, k, v, block_starts, n_blocks,
                              block, sm_scale, out, out_lse, ws, ws_bytes, stream);
+}
+
+int32_t ihip_sparse_attn_decode_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, ihip_tensor v_pool,
+                                      const ihip_paged_kv *paged, const int32_t *block_starts, int32_t n_blocks,
+                                      int32_t block, float sm_scale, void *out, float *out_lse, void *ws,
+                                      size_t ws_bytes, void *stream)
+{
+    KvFormat fmt;
+    const int32_t rc = check_paged("ihip_sparse_attn_decode_paged", shape, paged, &fmt);
+    if (rc != IHIP_OK) return rc;
+    return attn_decode_entry("ihip_sparse_attn_decode_paged", nullptr, &fmt, shape, q, k_pool, v_pool, block_starts,
+                             n_blocks, block, sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
 int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
@@ -449,8 +484,8 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = (fmt ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
-    if ((rc = (fmt ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
     if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
     const int last = n_stages - 1;
@@ -503,6 +538,19 @@ int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_ten
     const KvFormat fmt{true, k_scale, v_scale};
     return decode_layer_impl("ihip_decode_layer_fp8kv", shape, q, k, v, nullptr, nullptr, false, &fmt, n_stages,
                              chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_decode_layer_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, ihip_tensor v_pool,
+                                const ihip_paged_kv *paged, int32_t n_stages, const int32_t *chunk_sizes,
+                                const int32_t *keeps, float sm_scale, void *out, float *out_lse,
+                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+{
+    KvFormat fmt;
+    const int32_t rc = check_paged("ihip_decode_layer_paged", shape, paged, &fmt);
+    if (rc != IHIP_OK) return rc;
+    return decode_layer_impl("ihip_decode_layer_paged", shape, q, k_pool, v_pool, nullptr, nullptr, false, &fmt,
+                             n_stages, chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes,
+                             stream);
 }
 
 int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,

@@ -99,6 +99,25 @@ struct DirectRows {
     __device__ const uint16_t *row(int pos, bool) const { return base + (int64_t)pos * st; }
 };
 
+// PagedRows: the tensor is a pool of fixed-size pages, [page][KV head][token in page][d] through
+// the strides; a per-sequence block table maps logical page -> page id (paged KV cache).
+struct PagedView {
+    const int32_t *block_table;  // [B][table_stride]
+    int table_stride;
+    int page_log2;               // tokens per page = 1 << page_log2
+};
+struct PagedRows {
+    const uint16_t *pool;        // page 0, this KV head, token 0
+    const int32_t *table;        // this sequence's row of the block table
+    int64_t page_st, st;         // elements between pages / between tokens of a page
+    int page_log2;
+    __device__ const uint16_t *row(int pos, bool) const
+    {
+        const int page = table[pos >> page_log2];
+        return pool + (int64_t)page * page_st + (int64_t)(pos & ((1 << page_log2) - 1)) * st;
+    }
+};
+
 struct BankView {
     const int32_t *page_table;   // [n_blocks_total] slot or -1
     uint32_t *slot_stamp;        // [n_slots] call counter of the last touch
@@ -182,9 +201,10 @@ __device__ inline void unpack8(const uint4 &k, float (&f)[8])
 // An FP8 row is 128 bytes: 8 bytes per lane of a 16-lane row group.  The hardware
 // converter handles two bytes of one 16-bit half of a word at a time; E4M3 values
 // are a subset of bf16, so repacking them as bf16 is exact.
-struct KvFormat {             // nullptr / fp8 == false: bf16 K and V
+struct KvFormat {             // nullptr: bf16 K and V in HBM through strides
     bool fp8;
-    float k_scale, v_scale;   // value = scale * decoded byte (one scale per tensor)
+    float k_scale, v_scale;   // fp8: value = scale * decoded byte (one scale per tensor)
+    PagedView paged;          // block_table != nullptr: K and V are page pools
 };
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ inline void unpack8_fp8(const uint2 &k, float (&f)[8])

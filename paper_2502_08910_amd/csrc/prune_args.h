@@ -22,24 +22,35 @@ struct PruneArgs {
     float *out_scores;
     int32_t *out_rep;
     BankView bank;            // used by the cached instantiations only (K then points to host memory)
+    PagedView paged;          // paged instantiations only: K is the page pool, k_sb the page stride
     float k_scale;            // FP8 instantiations only: the scores are multiplied by it (K strides then
                               // count 2-byte units of the byte rows)
 };
 
-template <bool CACHED> struct KeySource;
-template <> struct KeySource<false> {
+// SRC 0: K in HBM through strides; 1: host tier with the on-GPU bank; 2: paged pool
+template <int SRC> struct KeySource;
+template <> struct KeySource<0> {
     typedef DirectRows type;
     static __device__ type make(const PruneArgs &a, const Problem &pr)
     {
         return DirectRows{a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st};
     }
 };
-template <> struct KeySource<true> {
+template <> struct KeySource<1> {
     typedef CachedRows type;
     static __device__ type make(const PruneArgs &a, const Problem &pr)
     {
         return CachedRows{a.bank, a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st, a.bank.bank_k,
                           (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+    }
+};
+
+template <> struct KeySource<2> {
+    typedef PagedRows type;
+    static __device__ type make(const PruneArgs &a, const Problem &pr)
+    {
+        return PagedRows{a.k + pr.g * a.k_sh, a.paged.block_table + (int64_t)pr.b * a.paged.table_stride, a.k_sb,
+                         a.k_st, a.paged.page_log2};
     }
 };
 

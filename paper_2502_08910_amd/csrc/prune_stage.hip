@@ -14,7 +14,7 @@ namespace ihip {
 
 // KV8: K rows are 128 bytes of E4M3 (8 bytes per lane); the dot products run on the decoded values
 // and the chunk score is multiplied by the tensor's scale.
-template <int G, int U, bool CACHED, bool KV8>
+template <int G, int U, int SRC, bool KV8>
 __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 {
     using piece_t = typename std::conditional<KV8, uint2, uint4>::type;     // a lane's share of a row
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 #pragma unroll
         for (int h = 0; h < G; ++h) unpack8(load_row16(qb, h * a.q_sh, l16), qf[h]);
     }
-    const typename KeySource<CACHED>::type src = KeySource<CACHED>::make(a, pr);
+    const typename KeySource<SRC>::type src = KeySource<SRC>::make(a, pr);
     const bool leader = l16 == 0;
     auto load_row = [&](int pos) {
         return *reinterpret_cast<const piece_t *>(src.row(pos, leader) + l16 * (KV8 ? 4 : 8));
@@ -383,11 +383,13 @@ static void launch_decode(const PruneArgs &a, int P, bool fp8, hipStream_t st)
     dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
     KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
     if (fp8)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, false, true>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, true>), grid, dim3(256), 0, st, a);
+    else if (a.paged.block_table != nullptr)
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, false>), grid, dim3(256), 0, st, a);
     else if (a.bank.page_table != nullptr)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, true, false>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, 1, false>), grid, dim3(256), 0, st, a);
     else
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, false, false>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, false>), grid, dim3(256), 0, st, a);
 }
 
 int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, hipStream_t st);
@@ -400,6 +402,9 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     PruneArgs a;
     const bool fp8 = fmt && fmt->fp8;
     a.k_scale = fp8 ? fmt->k_scale : 1.0f;
+    a.paged = (fmt && fmt->paged.block_table) ? fmt->paged : PagedView{nullptr, 0, 0};
+    if (a.paged.block_table && (fp8 || bank || s.b_q != 1 || (rope && rope->prune_style != IHIP_ROPE_NONE)))
+        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: paged K is built for plain bf16 decode only");
     a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;

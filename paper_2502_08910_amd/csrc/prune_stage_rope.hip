@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
 #pragma unroll
         for (int h = 0; h < G; ++h) unpack8(load_row16(qb, h * a.q_sh, l16), qf[h]);
     }
-    const DirectRows src = KeySource<false>::make(a, pr);
+    const DirectRows src = KeySource<0>::make(a, pr);
     auto load_row = [&](int pos) { return *reinterpret_cast<const uint4 *>(src.row(pos, false) + l16 * 8); };
 
     int start[U], len[U];

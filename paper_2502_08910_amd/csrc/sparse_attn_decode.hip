@@ -31,6 +31,7 @@ struct AttnDecodeArgs {
     float *out_lse;      // [B, Hq] or null
     BankView bank;       // used by the cached instantiations only (K/V then point to host memory)
     const float *rope_cos, *rope_sin;   // streaming-style RoPE instantiations only: fp32 [n_pos][d/2]
+    PagedView paged;     // paged instantiations only: K and V are page pools, *_sb the page strides
     float v_scale;       // FP8 instantiations: the output is multiplied by it (the K scale is folded into
                          // scale_log2e; K/V strides then count 2-byte units of the byte rows)
 };
@@ -38,8 +39,9 @@ struct AttnDecodeArgs {
 __device__ inline uint4 as_bf16x8(const uint4 &k) { return k; }
 __device__ inline uint4 as_bf16x8(const uint2 &k) { return fp8x8_to_bf16x8(k); }
 
-template <bool CACHED> struct KvSource;
-template <> struct KvSource<false> {
+// SRC 0: K/V in HBM through strides; 1: host tier with the on-GPU bank; 2: paged pools
+template <int SRC> struct KvSource;
+template <> struct KvSource<0> {
     typedef DirectRows type;
     static __device__ type k(const AttnDecodeArgs &a, const Problem &pr)
     {
@@ -50,7 +52,7 @@ template <> struct KvSource<false> {
         return DirectRows{a.v + pr.b * a.v_sb + pr.g * a.v_sh, a.v_st};
     }
 };
-template <> struct KvSource<true> {
+template <> struct KvSource<1> {
     typedef CachedRows type;
     static __device__ type k(const AttnDecodeArgs &a, const Problem &pr)
     {
@@ -61,6 +63,20 @@ template <> struct KvSource<true> {
     {
         return CachedRows{a.bank, a.v + pr.b * a.v_sb + pr.g * a.v_sh, a.v_st, a.bank.bank_v,
                           (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+    }
+};
+
+template <> struct KvSource<2> {
+    typedef PagedRows type;
+    static __device__ type k(const AttnDecodeArgs &a, const Problem &pr)
+    {
+        return PagedRows{a.k + pr.g * a.k_sh, a.paged.block_table + (int64_t)pr.b * a.paged.table_stride, a.k_sb,
+                         a.k_st, a.paged.page_log2};
+    }
+    static __device__ type v(const AttnDecodeArgs &a, const Problem &pr)
+    {
+        return PagedRows{a.v + pr.g * a.v_sh, a.paged.block_table + (int64_t)pr.b * a.paged.table_stride, a.v_sb,
+                         a.v_st, a.paged.page_log2};
     }
 };
 
@@ -86,7 +102,7 @@ __device__ inline int slot_to_pos(const AttnDecodeArgs &a, const Problem &pr, in
 // prefix of the block part of the slot list (blocks are ascending, empty ones last, only the last
 // one can be cut short), so a key's id is its slot, less the empty block slots for window keys.
 // KV8: K and V rows are 128 bytes of E4M3 (8 bytes per lane), repacked exactly as bf16 for the dot.
-template <int G, bool CACHED, bool ROPE, bool KV8>
+template <int G, int SRC, bool ROPE, bool KV8>
 __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const AttnDecodeArgs a)
 {
     using piece_t = typename std::conditional<KV8, uint2, uint4>::type;     // a lane's share of a row
@@ -138,8 +154,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
             }
         }
     }
-    const typename KvSource<CACHED>::type ksrc = KvSource<CACHED>::k(a, pr);
-    const typename KvSource<CACHED>::type vsrc = KvSource<CACHED>::v(a, pr);
+    const typename KvSource<SRC>::type ksrc = KvSource<SRC>::k(a, pr);
+    const typename KvSource<SRC>::type vsrc = KvSource<SRC>::v(a, pr);
 
     float m[G], l[G], acc[G][8];
 #pragma unroll
@@ -352,6 +368,10 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     AttnDecodeArgs a;
     const bool fp8 = fmt && fmt->fp8;
     a.v_scale = fp8 ? fmt->v_scale : 1.0f;
+    a.paged = (fmt && fmt->paged.block_table) ? fmt->paged : PagedView{nullptr, 0, 0};
+    const bool paged = a.paged.block_table != nullptr;
+    if (paged && (fp8 || bank || (rope && rope->attn_style != IHIP_ROPE_NONE)))
+        return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: paged K/V is built for plain bf16 decode only");
     const bool use_rope = rope && rope->attn_style != IHIP_ROPE_NONE;
     a.rope_cos = a.rope_sin = nullptr;
     if (use_rope) {
@@ -395,10 +415,11 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     KernelTimer timer("attn_decode_split", st);
     switch (G) {
 #define IHIP_AD_LAUNCH(GG)                                                                                          \
-    if (fp8) hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, false, true>), grid, dim3(kAttnThreads), 0, st, a);          \
-    else if (use_rope) hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, true, false>), grid, dim3(kAttnThreads), 0, st, a); \
-    else if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, true, false, false>), grid, dim3(kAttnThreads), 0, st, a);     \
-    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, false, false, false>), grid, dim3(kAttnThreads), 0, st, a)
+    if (fp8) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 0, false, true>), grid, dim3(kAttnThreads), 0, st, a);          \
+    else if (use_rope) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 0, true, false>), grid, dim3(kAttnThreads), 0, st, a); \
+    else if (paged) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 2, false, false>), grid, dim3(kAttnThreads), 0, st, a);   \
+    else if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 1, false, false>), grid, dim3(kAttnThreads), 0, st, a);    \
+    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, 0, false, false>), grid, dim3(kAttnThreads), 0, st, a)
     case 1: IHIP_AD_LAUNCH(1); break;
     case 2: IHIP_AD_LAUNCH(2); break;
     case 4: IHIP_AD_LAUNCH(4); break;
