@@ -59,6 +59,11 @@ def parse():
     ap.add_argument("--workload", default="cfg3-decode-1m-b8")
     ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
                     help="decode workloads: fp8 = K and V quantised to E4M3 bytes (scale 1/64 each), a separate metric")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
+                    help="decode workloads: K and V scattered into pages of this many tokens in a seeded random "
+                         "order, read through a block table (a separate metric)")
+    ap.add_argument("--paged-order", default="random", choices=["random", "sequential"],
+                    help="with --paged: page ids in a seeded random order (default) or in token order")
     ap.add_argument("--rope", default=None, choices=["relative", "chunk"],
                     help="decode workloads: dynamic RoPE in the pruning stages (this style) and the attention "
                          "(streaming style); a separate metric, no roofline / cpu_baseline objects")
@@ -177,6 +182,25 @@ def bench_decode(args, w, torch, ihip, configs):
         kvs = kvs8
         del kvs8, kb, vb
         torch.cuda.empty_cache()
+    paged = None
+    if args.paged:
+        assert n_layers == 1 and kv_scales is None, "paged: one bf16 layer"
+        page = args.paged
+        per_seq = (w.T + page - 1) // page
+        assert per_seq * page == w.T, "context must be a whole number of pages"
+        gen_ = torch.Generator(device=dev)
+        gen_.manual_seed(1234)
+        if args.paged_order == "random":
+            order = torch.randperm(w.B * per_seq, generator=gen_, device=dev).view(w.B, per_seq)
+        else:
+            order = torch.arange(w.B * per_seq, device=dev).view(w.B, per_seq)
+        kb, vb = kvs[0]
+        k_pool = torch.empty((w.B * per_seq, w.Hkv, page, w.d), dtype=torch.bfloat16, device=dev)
+        v_pool = torch.empty_like(k_pool)
+        for b in range(w.B):
+            k_pool[order[b]] = kb[b].view(w.Hkv, per_seq, page, w.d).permute(1, 0, 2, 3)
+            v_pool[order[b]] = vb[b].view(w.Hkv, per_seq, page, w.d).permute(1, 0, 2, 3)
+        paged = ihip.PagedKV(k_pool, v_pool, order.to(torch.int32).contiguous())
     k, v = kvs[0]
     seq_lens = torch.full((w.B,), w.T, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
@@ -185,7 +209,7 @@ def bench_decode(args, w, torch, ihip, configs):
     L = ihip.Layer(qs[0], k, seq_lens, w.b_q, w.n_sink, w.n_stream)
     ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
     out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
-    assert not (kv_scales and (args.refresh or args.rope)), "fp8 K/V: plain decode layer only"
+    assert not ((kv_scales or paged) and (args.refresh or args.rope)), "fp8 / paged K/V: plain decode layer only"
 
     refresh = None
     if args.refresh:
@@ -211,7 +235,8 @@ def bench_decode(args, w, torch, ihip, configs):
     else:
         def step(i):
             kl, vl = kvs[i % n_layers]
-            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out, kv_scales=kv_scales)
+            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out, kv_scales=kv_scales,
+                           paged=paged)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 
@@ -251,7 +276,7 @@ def bench_decode(args, w, torch, ihip, configs):
                         "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
     return {
         "metric": ("sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer")
-        + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else "") + ("_fp8_kv" if kv_scales else ""),
+        + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else "") + ("_fp8_kv" if kv_scales else "") + (f"_paged{args.paged}_{args.paged_order}" if args.paged else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,

@@ -111,11 +111,12 @@ struct PagedRows {
     const int32_t *table;        // this sequence's row of the block table
     int64_t page_st, st;         // elements between pages / between tokens of a page
     int page_log2;
-    __device__ const uint16_t *row(int pos, bool) const
+    __device__ const uint16_t *row_in_page(int page, int pos) const
     {
-        const int page = table[pos >> page_log2];
         return pool + (int64_t)page * page_st + (int64_t)(pos & ((1 << page_log2) - 1)) * st;
     }
+    __device__ int table_entry(int pos) const { return table[pos >> page_log2]; }
+    __device__ const uint16_t *row(int pos, bool) const { return row_in_page(table_entry(pos), pos); }
 };
 
 struct BankView {

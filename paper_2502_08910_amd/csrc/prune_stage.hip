@@ -35,9 +35,6 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
     }
     const typename KeySource<SRC>::type src = KeySource<SRC>::make(a, pr);
     const bool leader = l16 == 0;
-    auto load_row = [&](int pos) {
-        return *reinterpret_cast<const piece_t *>(src.row(pos, leader) + l16 * (KV8 ? 4 : 8));
-    };
     const piece_t zero = {};
 
     int start[U], len[U];
@@ -52,6 +49,38 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
         len[u] = valid[u] ? min(a.chunk, pr.hi - start[u]) : 0;
     }
 
+    // Paged K: the page ids of a chunk's first 16 pages are fetched once, one per lane of the row
+    // group (one coalesced read of the block table), and handed round by a shuffle, so that the
+    // search below has no table lookup in front of every row read.
+    int page_first[U], page_ids[U];
+    if (SRC == 2) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            page_first[u] = max(start[u], 0) >> a.paged.page_log2;
+            const int e = page_first[u] + l16;
+            page_ids[u] = valid[u] && e < a.paged.table_stride
+                              ? a.paged.block_table[(int64_t)pr.b * a.paged.table_stride + e] : 0;
+        }
+    }
+    // page id of row `pos` of chunk u (paged K; every lane of the row group takes part in the shuffle)
+    auto page_of = [&](int pos, int u) {
+        if constexpr (SRC == 2) {
+            const int idx = (pos >> a.paged.page_log2) - page_first[u];
+            int page = __shfl(page_ids[u], idx & 15, 16);
+            if (idx >= 16) page = src.table[pos >> a.paged.page_log2];      // chunk wider than 16 pages
+            return page;
+        } else {
+            return 0;
+        }
+    };
+    // row `pos` (in page `page`, if K is paged): this lane's share of it
+    auto load_row = [&](int pos, int page) {
+        if constexpr (SRC == 2)
+            return *reinterpret_cast<const piece_t *>(src.row_in_page(page, pos) + l16 * 8);
+        else
+            return *reinterpret_cast<const piece_t *>(src.row(pos, leader) + l16 * (KV8 ? 4 : 8));
+    };
+
     int off[U][G];
     float sigma[U][G];
 
@@ -63,8 +92,9 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
         for (int u = 0; u < U; ++u) {
             r0[u] = zero;
             r1[u] = zero;
-            if (valid[u]) r0[u] = load_row(start[u]);
-            if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid);
+            const int pg0 = page_of(max(start[u], 0), u), pg1 = page_of(max(start[u], 0) + mid, u);
+            if (valid[u]) r0[u] = load_row(start[u], pg0);
+            if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid, pg1);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -83,6 +113,11 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
     for (int half = a.chunk >> 2; half >= 1; half >>= 1) {
         piece_t r[U][G];
         bool ok[U][G];
+        int page[U][G];      // all shuffles first, then all loads: one wait instead of one per row
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int h = 0; h < G; ++h) page[u][h] = page_of(max(start[u], 0) + off[u][h] + half, u);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -90,7 +125,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
                 const int mid = off[u][h] + half;
                 ok[u][h] = mid < len[u];
                 r[u][h] = zero;
-                if (ok[u][h]) r[u][h] = load_row(start[u] + mid);
+                if (ok[u][h]) r[u][h] = load_row(start[u] + mid, page[u][h]);
             }
         }
 #pragma unroll

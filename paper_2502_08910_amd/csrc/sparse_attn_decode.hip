@@ -171,8 +171,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
     // key position of every slot of this split, one per thread, so that the main loop has no
     // dependent global loads (block start -> row address)
     __shared__ int sh_pos[kAttnThreads];
-    sh_pos[threadIdx.x] = (int)threadIdx.x < a.slots_per_split
-                              ? slot_to_pos(a, pr, p, s0 + threadIdx.x, n_sink_eff, w0) : -1;
+    __shared__ int sh_page[SRC == 2 ? kAttnThreads : 1];     // paged K/V: the slot's page id, looked up here once
+    {
+        const int pos = (int)threadIdx.x < a.slots_per_split
+                            ? slot_to_pos(a, pr, p, s0 + threadIdx.x, n_sink_eff, w0) : -1;
+        sh_pos[threadIdx.x] = pos;
+        if constexpr (SRC == 2) sh_page[threadIdx.x] = pos >= 0 ? ksrc.table_entry(pos) : 0;
+    }
     __syncthreads();
     for (int base = s0 + grp; base < s1; base += kAttnGroups * UNR) {
         piece_t kr[UNR], vr[UNR];
@@ -185,8 +190,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
             kr[u] = piece_t{};
             vr[u] = piece_t{};
             if (ok[u]) {
-                kr[u] = *reinterpret_cast<const piece_t *>(ksrc.row(pos, l16 == 0) + l16 * kLaneOff);
-                vr[u] = *reinterpret_cast<const piece_t *>(vsrc.row(pos, false) + l16 * kLaneOff);   // K did the bookkeeping
+                if constexpr (SRC == 2) {
+                    const int page = sh_page[slot - s0];
+                    kr[u] = *reinterpret_cast<const piece_t *>(ksrc.row_in_page(page, pos) + l16 * kLaneOff);
+                    vr[u] = *reinterpret_cast<const piece_t *>(vsrc.row_in_page(page, pos) + l16 * kLaneOff);
+                } else {
+                    kr[u] = *reinterpret_cast<const piece_t *>(ksrc.row(pos, l16 == 0) + l16 * kLaneOff);
+                    vr[u] = *reinterpret_cast<const piece_t *>(vsrc.row(pos, false) + l16 * kLaneOff);   // K did the bookkeeping
+                }
             }
         }
         // scores of the UNR tokens for all heads (log2 units), then one running-max update per batch
