@@ -64,6 +64,9 @@ def parse():
                          "order, read through a block table (a separate metric)")
     ap.add_argument("--paged-order", default="random", choices=["random", "sequential"],
                     help="with --paged: page ids in a seeded random order (default) or in token order")
+    ap.add_argument("--kv-layout", default="bhtd", choices=["bhtd", "bthd"],
+                    help="decode workloads: memory order of K and V (the same logical [B,Hkv,T,d] tensors; bthd = "
+                         "token-major, the KV heads of a token adjacent)")
     ap.add_argument("--rope", default=None, choices=["relative", "chunk"],
                     help="decode workloads: dynamic RoPE in the pruning stages (this style) and the attention "
                          "(streaming style); a separate metric, no roofline / cpu_baseline objects")
@@ -201,6 +204,19 @@ def bench_decode(args, w, torch, ihip, configs):
             k_pool[order[b]] = kb[b].view(w.Hkv, per_seq, page, w.d).permute(1, 0, 2, 3)
             v_pool[order[b]] = vb[b].view(w.Hkv, per_seq, page, w.d).permute(1, 0, 2, 3)
         paged = ihip.PagedKV(k_pool, v_pool, order.to(torch.int32).contiguous())
+    if args.kv_layout == "bthd":
+        # same values, token-major in memory: [B,T,Hkv,d] storage viewed as [B,Hkv,T,d]
+        re = []
+        for (kb, vb) in kvs:
+            k2 = torch.empty((w.B, w.T, w.Hkv, w.d), dtype=kb.dtype, device=dev)
+            v2 = torch.empty_like(k2)
+            for b in range(w.B):
+                k2[b] = kb[b].transpose(0, 1)
+                v2[b] = vb[b].transpose(0, 1)
+            re.append((k2.transpose(1, 2), v2.transpose(1, 2)))
+        kvs = re
+        del re, kb, vb
+        torch.cuda.empty_cache()
     k, v = kvs[0]
     seq_lens = torch.full((w.B,), w.T, dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
@@ -281,7 +297,7 @@ def bench_decode(args, w, torch, ihip, configs):
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
                    "n_stream": w.n_stream, "query_sets": N_QUERY_SETS, "distinct_kv_layers": n_layers,
-                   "mask_refresh": refresh},
+                   "mask_refresh": refresh, "kv_layout": args.kv_layout},
         "roofline": roofline, "cpu_baseline": cpu, "whole_path": whole, "kernels": kernels, "setup_s": t_setup,
     }
 

@@ -58,3 +58,40 @@ def test_argument_checks_need_no_gpu(built_lib):
     assert rc == -2 and b"workspace" in L.ihip_last_error()
     one = (ctypes.c_int32 * 1)(16)
     assert L.ihip_workspace_bytes(99, ctypes.byref(s), 1, one, one) == 0
+
+
+def test_argument_checks_of_the_variants_need_no_gpu(built_lib):
+    """Dynamic RoPE, FP8 K/V, paged K/V and pooled selection: what they refuse, before any launch."""
+    from paper_2502_08910_amd.binding import Shape, Tensor, RopeStruct, PagedStruct
+    L = built_lib.lib()
+    s = Shape(1, 32, 8, 128, 1, 1, 1, 4096, 128, 1024)      # decode, 4096 keys
+    t = Tensor(256, 0, 0, 128)
+    slots = L.ihip_stage1_slots(ctypes.byref(s), 64)
+    # rope: NULL struct, NULL tables, unknown style, table too short for the relative style
+    assert L.ihip_prune_stage_rope(ctypes.byref(s), t, t, None, 0, 0, 64, slots, None, 256, None, None) == -1
+    r = RopeStruct(None, None, 4096, 1, 1)
+    assert L.ihip_prune_stage_rope(ctypes.byref(s), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None) == -1
+    r = RopeStruct(256, 256, 4096, 7, 1)
+    assert L.ihip_prune_stage_rope(ctypes.byref(s), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None) == -1
+    r = RopeStruct(256, 256, 1025, 1, 1)                     # needs n_stream + 2 = 1026 rows
+    assert L.ihip_prune_stage_rope(ctypes.byref(s), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None) == -1
+    assert b"1026" in L.ihip_last_error()
+    # rope is a decode feature
+    sp = Shape(1, 32, 8, 128, 64, 64, 1, 4096, 128, 1024)
+    r = RopeStruct(256, 256, 8192, 1, 1)
+    rc = L.ihip_prune_stage_rope(ctypes.byref(sp), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None)
+    assert rc == -4
+    # fp8: scales must be positive and finite; rows 16-byte aligned in bytes
+    f = ctypes.c_float
+    assert L.ihip_prune_stage_fp8kv(ctypes.byref(s), t, t, None, 0, 0, 64, slots, f(0.0), 256, None, None) == -1
+    assert L.ihip_prune_stage_fp8kv(ctypes.byref(s), t, t, None, 0, 0, 64, slots, f(float("inf")), 256, None, None) == -1
+    t8 = Tensor(256, 0, 0, 136)
+    assert L.ihip_prune_stage_fp8kv(ctypes.byref(s), t, t8, None, 0, 0, 64, slots, f(1.0), 256, None, None) == -1
+    # paged: NULL table, page size not a power of two, table too short
+    assert L.ihip_prune_stage_paged(ctypes.byref(s), t, t, None, None, 0, 0, 64, slots, 256, None, None) == -1
+    pg = PagedStruct(256, 256, 24)
+    assert L.ihip_prune_stage_paged(ctypes.byref(s), t, t, ctypes.byref(pg), None, 0, 0, 64, slots, 256, None, None) == -1
+    pg = PagedStruct(256, 100, 16)                           # covers 1600 < 4096 tokens
+    assert L.ihip_prune_stage_paged(ctypes.byref(s), t, t, ctypes.byref(pg), None, 0, 0, 64, slots, 256, None, None) == -1
+    # pooling rule
+    assert L.ihip_select_blocks_pooled(ctypes.byref(s), 256, slots, None, 0, 0, 64, 8, 5, 256, None) == -1
