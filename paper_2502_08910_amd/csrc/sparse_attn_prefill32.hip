@@ -52,7 +52,11 @@ constexpr int kPfTileEl = kPfTile * kD;            // elements of one K (or V) t
 constexpr int kPfStageEl = 2 * kPfTileEl;          // K tile, then V tile
 constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above which the softmax reference moves
 
-// NQ = b_q / 32 query tiles, G query heads: NQ*G waves.  WIDE: 64-bit row offsets; otherwise every
+// NQ = b_q / 32 query tiles, G query heads per workgroup: NQ*G waves.  A group of more heads than
+// that (8 heads with two query tiles would be 16 waves, whose registers spill) is spread over
+// G_total/G workgroups placed 8 apart in launch order, i.e. on the same XCD, so that the second
+// reads the K and V rows from that XCD's L2.
+// WIDE: 64-bit row offsets; otherwise every
 // row of a (sequence, KV head) slab of K and V lies within 2^31 elements of its base and positions
 // and strides are below 2^24, so an offset is one full-rate 24-bit multiply.
 template <int NQ, int G, bool WIDE>
@@ -64,7 +68,14 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     uint8_t *sMasked = reinterpret_cast<uint8_t *>(
         sPos + (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile);
 
-    const int p = blockIdx.x;
+    int p = blockIdx.x, head_part = 0;
+    if (a.ge.G != G) {                               // blocks of 8 problems x (G_total/G) parts
+        const int parts = a.ge.G / G;
+        const int r = blockIdx.x % (8 * parts);
+        p = blockIdx.x / (8 * parts) * 8 + (r & 7);
+        head_part = r >> 3;
+        if (p >= a.ge.B * a.ge.Hkv * a.ge.Mq) return;
+    }
     const Problem pr = problem_of(a.ge, p);
     constexpr int NW = NQ * G;
     constexpr int nthreads = 64 * NW;
@@ -73,7 +84,7 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     const int lane = tid & 63, wave = tid >> 6;
     const int hh = wave % G, qt = wave / G;          // this wave's head and query tile
     const int n = lane & 31, half = lane >> 5;
-    const int h = pr.g * G + hh;
+    const int h = pr.g * a.ge.G + head_part * G + hh;
     const int q0 = pr.m * b_q + qt * 32;             // first query row of this wave
     const int qpos0 = pr.E - b_q;                    // absolute position of the block's first query
     const int qpos = qpos0 + qt * 32 + n;            // ... of this lane's query
@@ -302,7 +313,9 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
 void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len, hipStream_t st)
 {
     const int NQ = a.ge.b_q / 32;
-    const dim3 block_dim(64 * NQ * a.ge.G), grid(P);
+    const int heads_per_wg = NQ * a.ge.G > 8 ? a.ge.G / 2 : a.ge.G;
+    const int parts = a.ge.G / heads_per_wg;
+    const dim3 block_dim(64 * NQ * heads_per_wg), grid(parts == 1 ? P : (P + 7) / 8 * 8 * parts);
     const int slots = (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile;
     const size_t lds = (size_t)kPfStages * kPfStageEl * sizeof(uint16_t) + (size_t)slots * sizeof(int) +
                        slots / kPfTile;             // stages, slot positions, per-tile flags
@@ -320,7 +333,7 @@ void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len,
         hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV, WV>), grid, block_dim, lds, st, a);              \
     }
 #define IHIP_PF32_BY_G(NQV, WV)             \
-    switch (a.ge.G) {                       \
+    switch (heads_per_wg) {                 \
     case 1: IHIP_PF32(NQV, 1, WV); break;   \
     case 2: IHIP_PF32(NQV, 2, WV); break;   \
     case 4: IHIP_PF32(NQV, 4, WV); break;   \
