@@ -79,8 +79,12 @@ typedef struct {
  *   attn_style   IHIP_ROPE_STREAMING: the keys a query attends to, in position
  *                order, at 0..n-1, the query at n-1 (needs n_pos >= n_sink +
  *                n_blocks*block + n_stream).
- * Built for decode (Tq == b_q == 1) from device memory; other uses return
- * IHIP_ERR_UNSUPPORTED.
+ * Built for K and V in device memory: decode (Tq == b_q == 1) with every
+ * style, chunked prefill with the relative style in the pruning stages and the
+ * streaming style in the attention (all queries of a block share the relative
+ * position; query t of a block gets its own streaming id from the number of
+ * keys it attends to).  The prefill kernels round the rotated Q and K operands
+ * to bf16 for the matrix cores.  Other uses return IHIP_ERR_UNSUPPORTED.
  */
 #define IHIP_ROPE_NONE          0
 #define IHIP_ROPE_RELATIVE      1
@@ -183,7 +187,7 @@ int32_t ihip_decode_layer_paged(const ihip_shape *shape, ihip_tensor q, ihip_ten
                                 const int32_t *keeps, float sm_scale, void *out, float *out_lse,
                                 int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
-/* ihip_prune_stage with rope->prune_style applied (decode only); rope must not be NULL. */
+/* ihip_prune_stage with rope->prune_style applied; rope must not be NULL. */
 int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                               const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
                               int32_t chunk, int32_t max_chunks, const ihip_rope *rope,
@@ -270,6 +274,12 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                        int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                        int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
+/* ihip_sparse_attn_prefill with rope->attn_style applied to Q and K (V is not rotated). */
+int32_t ihip_sparse_attn_prefill_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                      float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                      void *ws, size_t ws_bytes, void *stream);
+
 /*
  * One decode layer call: ihip_prune_all followed by ihip_sparse_attn_decode
  * (Alg. 4 with every stage refreshed at every step).  out / out_lse as in
@@ -290,11 +300,15 @@ int32_t ihip_prefill_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_t
                                   int32_t pooling, float sm_scale, void *out, float *out_lse,
                                   int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
-/* ihip_decode_layer with dynamic RoPE in every pruning stage and in the attention. */
+/* ihip_decode_layer / ihip_prefill_layer with dynamic RoPE in every pruning stage and in the attention. */
 int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                                float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Decode layer with per-stage mask caching (Sec. 4 "Sparse Attention Mask

@@ -45,6 +45,10 @@ EXPORTS = {
                                              c_f, vp, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
                                        vp, vp, vp, vp, c_sz, vp]),
+    "ihip_sparse_attn_prefill_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
+                                              c_f, vp, vp, vp, vp, c_sz, vp]),
+    "ihip_prefill_layer_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
+                                        vp, vp, vp, vp, c_sz, vp]),
     "ihip_prune_stage_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, vp, c_i32, c_i32, c_i32, c_i32,
                                        c_f, vp, vp, vp]),
     "ihip_sparse_attn_decode_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
@@ -342,7 +346,13 @@ class Layer:
         return self._attn(lib().ihip_sparse_attn_decode, OP_ATTN_DECODE, q, k, v, block_starts, block,
                           sm_scale, want_lse, ws)
 
-    def sparse_attn_prefill(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None):
+    def sparse_attn_prefill(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None,
+                            rope: Optional["Rope"] = None):
+        if rope is not None:
+            def fn(shape, tq, tk, tv, bs, n_blocks, blk, scale, out, lse, w, w_bytes, stream):
+                return lib().ihip_sparse_attn_prefill_rope(shape, tq, tk, tv, bs, n_blocks, blk, scale, rope.ref(),
+                                                           out, lse, w, w_bytes, stream)
+            return self._attn(fn, OP_ATTN_PREFILL, q, k, v, block_starts, block, sm_scale, want_lse, ws)
         return self._attn(lib().ihip_sparse_attn_prefill, OP_ATTN_PREFILL, q, k, v, block_starts, block,
                           sm_scale, want_lse, ws)
 
@@ -418,7 +428,7 @@ class Layer:
         return out
 
     def prefill_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
-                      out_blocks=None, lse=None, pooling: Optional[int] = None):
+                      out_blocks=None, lse=None, pooling: Optional[int] = None, rope: Optional["Rope"] = None):
         """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d]."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
@@ -430,6 +440,12 @@ class Layer:
                                                    _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
                                                    pooling, sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks),
                                                    _ptr(ws), ws.numel(), _stream()))
+            return out
+        if rope is not None:
+            _check(lib().ihip_prefill_layer_rope(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                                 _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                                 sm_scale, rope.ref(), _ptr(out), _ptr(lse), _ptr(out_blocks),
+                                                 _ptr(ws), ws.numel(), _stream()))
             return out
         _check(lib().ihip_prefill_layer(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                         _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),

@@ -86,7 +86,7 @@ void cache_describe(const ihip_cache *, int32_t *, int32_t *, int64_t *, ihip_te
 size_t attn_decode_workspace(const ihip_shape &, int, int);
 int32_t launch_attn_prefill(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                             const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
-                            hipStream_t);
+                            const ihip_rope *, hipStream_t);
 
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
@@ -436,11 +436,11 @@ int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihi
                              sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
-int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                 const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
-                                 void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+static int32_t attn_prefill_entry(const char *who, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q,
+                                  ihip_tensor k, ihip_tensor v, const int32_t *block_starts, int32_t n_blocks,
+                                  int32_t block, float sm_scale, void *out, float *out_lse, void *ws,
+                                  size_t ws_bytes, void *stream)
 {
-    const char *who = "ihip_sparse_attn_prefill";
     int32_t rc;
     (void)ws; (void)ws_bytes;       // this kernel needs no scratch
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
@@ -452,8 +452,26 @@ int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_te
     if (n_blocks < 0 || !pow2(block)) return fail(IHIP_ERR_INVALID_ARG, "%s: n_blocks = %d, block = %d", who, n_blocks, block);
     if (n_blocks > 0 && !block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: block_starts is NULL", who);
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
-    return launch_attn_prefill(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse,
+    return launch_attn_prefill(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, rope,
                                (hipStream_t)stream);
+}
+
+int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
+                                 void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    return attn_prefill_entry("ihip_sparse_attn_prefill", nullptr, shape, q, k, v, block_starts, n_blocks, block,
+                              sm_scale, out, out_lse, ws, ws_bytes, stream);
+}
+
+int32_t ihip_sparse_attn_prefill_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
+                                      const ihip_rope *rope, void *out, float *out_lse, void *ws, size_t ws_bytes,
+                                      void *stream)
+{
+    if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_sparse_attn_prefill_rope: rope is NULL");
+    return attn_prefill_entry("ihip_sparse_attn_prefill_rope", rope, shape, q, k, v, block_starts, n_blocks, block,
+                              sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
 int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, int32_t n_stages,
@@ -623,7 +641,7 @@ int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_te
                               out_lse, (char *)ws + L.scores_bytes, nullptr, nullptr, (hipStream_t)stream);
 }
 
-static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
                            const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                            float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
@@ -645,10 +663,10 @@ static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_sh
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
-    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, nullptr, all_heads,
+    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, rope, all_heads,
                         (hipStream_t)stream);
     if (rc != IHIP_OK) return rc;
-    return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
+    return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse, rope,
                                (hipStream_t)stream);
 }
 
@@ -656,7 +674,7 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
                            const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                            float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
-    return prefill_layer_impl("ihip_prefill_layer", false, shape, q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out,
+    return prefill_layer_impl("ihip_prefill_layer", false, nullptr, shape, q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out,
                               out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -667,8 +685,18 @@ int32_t ihip_prefill_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_t
 {
     const int32_t rc = check_pooling("ihip_prefill_layer_pooled", pooling);
     if (rc != IHIP_OK) return rc;
-    return prefill_layer_impl("ihip_prefill_layer_pooled", pooling == IHIP_POOL_ALL_HEADS, shape, q, k, v, n_stages,
+    return prefill_layer_impl("ihip_prefill_layer_pooled", pooling == IHIP_POOL_ALL_HEADS, nullptr, shape, q, k, v, n_stages,
                               chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale,
+                                const ihip_rope *rope, void *out, float *out_lse, int32_t *out_block_starts,
+                                void *ws, size_t ws_bytes, void *stream)
+{
+    if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_prefill_layer_rope: rope is NULL");
+    return prefill_layer_impl("ihip_prefill_layer_rope", false, rope, shape, q, k, v, n_stages, chunk_sizes, keeps,
+                              sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
 int32_t ihip_profile_enable(int32_t on)

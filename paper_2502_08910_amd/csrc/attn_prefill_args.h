@@ -23,7 +23,43 @@ struct AttnPrefillArgs {
     float scale_log2e;
     uint16_t *out;       // bf16 [B, Hq, Tq, d]
     float *out_lse;      // [B, Hq, Tq] or null
+    const float *rope_cos, *rope_sin;   // streaming-style RoPE instantiations only: fp32 [n_pos][d/2]
 };
+
+// Streaming-style positions (Sec. 4 "Dynamic RoPE for OOL generalization"): the keys a query
+// attends to, in position order, sit at 0, 1, ..., n-1 and the query at n-1.  Attended slots are a
+// prefix of the block part of the slot list (blocks are ascending, empty ones last, only the last
+// one can be cut short), so a key's id is its slot, less the empty block slots for window keys;
+// n_stream >= b_q keeps every block key before every query of the block, so the id does not depend
+// on the query.
+struct StreamIds {
+    int n_sink_eff, block_slots, block_tokens, w0;
+    __device__ int key(int slot) const
+    {
+        return slot < n_sink_eff + block_slots ? slot : slot - (block_slots - block_tokens);
+    }
+    __device__ int query(int n_sink, int qpos) const      // = (number of keys the query attends to) - 1
+    {
+        return min(n_sink, qpos + 1) + block_tokens + max(0, qpos - w0 + 1) - 1;
+    }
+};
+
+// tokens in the kept blocks of problem p; every thread of the workgroup calls it (uses *sh, barriers)
+__device__ inline int pf_block_tokens(const AttnPrefillArgs &a, const Problem &pr, int p, int nthreads, int *sh)
+{
+    if (threadIdx.x == 0) *sh = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int i = threadIdx.x; i < a.n_blocks; i += nthreads) {
+        const int bs = a.block_starts[(int64_t)p * a.n_blocks + i];
+        if (bs >= 0 && bs < pr.hi) mine += min(a.block, pr.hi - bs);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
+    if ((threadIdx.x & 63) == 0 && mine > 0) atomicAdd(sh, mine);
+    __syncthreads();
+    return *sh;
+}
 
 __device__ inline int pf_slot_to_pos(const AttnPrefillArgs &a, const Problem &pr, int p, int slot,
                                      int n_sink_eff, int w0)
@@ -45,5 +81,6 @@ constexpr int kPf32MaxLds = 160 * 1024;  // LDS per workgroup the 32x32 kernel m
 constexpr int kPf32MaxSlots = 24320;    // key slots whose positions (and per-tile flags) the 32x32 kernel keeps in LDS
 
 void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len, hipStream_t st);
+
 
 }  // namespace ihip

@@ -176,8 +176,22 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int MT, int NT, int G, bool WIDE>
-__global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArgs a, const int iters)
+//
+// ROPE: relative-style dynamic RoPE (Sec. 4 "Dynamic RoPE for OOL generalization"; ApplyRopeQ /
+// ApplyRopeK after Alg. 3).  Every query of the block sits at n_stream+1, a left-branch key at 0,
+// a right-branch key (and the representative in the chunk score) at 1.  With a table of true
+// rotations the key rotations fold into the queries: two rotated copies of the query operands,
+// q_L = R(n_stream+1) q and q_R = R(n_stream) q (rounded to bf16 for the matrix cores), and every
+// candidate row is scored against both, because a key that wins as the right branch is the left
+// branch of the next iteration.  Twice the matrix work and twice the query registers.
+__device__ inline bf16x8 rotate_operand(const bf16x8 x, const float *cos4, const float *sin4)
+{
+    return __builtin_bit_cast(bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, x), cos4, sin4));
+}
+
+template <int MT, int NT, int G, bool WIDE, bool ROPE>
+__global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
+                                                                            const RopeView rope)
 {
     static_assert(NT == 2, "the shared first phase assumes two 16-chunk tiles per wave");
     constexpr int kTile = NT * 16 * kD;              // one tile: 32 rows of 256 bytes, no padding
@@ -230,7 +244,8 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
     uint32_t dst_own[NT * 4];                        // this wave's tile, four rows at a time
 #pragma unroll
     for (int r = 0; r < NT * 4; ++r) dst_own[r] = lds_addr(tile + r * 4 * kD);
-    bf16x8 qa[MT][4];
+    bf16x8 qa[MT][4];                                // ROPE: q_L
+    bf16x8 qaR[ROPE ? MT : 1][4];                    // ROPE: q_R
     {
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(pr.m * a.ge.b_q) * a.q_st;
 #pragma unroll
@@ -243,7 +258,15 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
 #pragma unroll
             for (int mt = m0; mt < m0 + 2 && mt < MT; ++mt)
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) qa[mt][ks] = operand(tile, (mt - m0) * 16, ks);
+                for (int ks = 0; ks < 4; ++ks) {
+                    qa[mt][ks] = operand(tile, (mt - m0) * 16, ks);
+                    if constexpr (ROPE) {
+                        const int pair = ((ks << 2) + kq) * 4;       // first of this operand's 4 dim pairs
+                        const int64_t posR = (int64_t)a.ge.n_stream * (kD / 2) + pair, posL = posR + kD / 2;
+                        qaR[mt][ks] = rotate_operand(qa[mt][ks], rope.cos + posR, rope.sin + posR);
+                        qa[mt][ks] = rotate_operand(qa[mt][ks], rope.cos + posL, rope.sin + posL);
+                    }
+                }
             // the reads must have left LDS before the next loads land in the same tile
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
@@ -252,7 +275,8 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
     const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
 
     // scores of the 32 rows of a tile (column n of 16-row tile t): max over the block's queries
-    auto mfma_scores = [&](const uint16_t *src, float (&sig)[NT]) {
+    // (ROPE: sig against q_L, sigR against q_R)
+    auto mfma_scores = [&](const uint16_t *src, float (&sig)[NT], float (&sigR)[NT]) {
         bf16x8 kr[NT][4];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
@@ -260,7 +284,7 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             for (int ks = 0; ks < 4; ++ks) kr[t][ks] = operand(src, t * 16, ks);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            float best = -INFINITY;
+            float best = -INFINITY, bestR = -INFINITY;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 f32x4 c = {0.f, 0.f, 0.f, 0.f};
@@ -268,15 +292,27 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
                 for (int ks = 0; ks < 4; ++ks)
                     c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[mt][ks], kr[t][ks], c, 0, 0, 0);
                 best = fmaxf(best, fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3])));
+                if constexpr (ROPE) {
+                    f32x4 cr = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        cr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qaR[mt][ks], kr[t][ks], cr, 0, 0, 0);
+                    bestR = fmaxf(bestR, fmaxf(fmaxf(cr[0], cr[1]), fmaxf(cr[2], cr[3])));
+                }
             }
             best = fmaxf(best, __shfl_xor(best, 16, 64));
             best = fmaxf(best, __shfl_xor(best, 32, 64));
             sig[t] = best;
+            if constexpr (ROPE) {
+                bestR = fmaxf(bestR, __shfl_xor(bestR, 16, 64));
+                bestR = fmaxf(bestR, __shfl_xor(bestR, 32, 64));
+                sigR[t] = bestR;
+            }
         }
     };
     // score of candidate rows pos[t] of this wave's own searches.  The scores of columns whose
     // search has ended are ignored by the caller.
-    auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT]) {
+    auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT], float (&sigR)[NT]) {
         int cand[NT * 4];
 #pragma unroll
         for (int r = 0; r < NT * 4; ++r)     // lanes 0..15 hold column = lane
@@ -286,7 +322,7 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             load4(kb, k_st, dst_own[r], cand[r], (r & 3) * 4 + kq);
         // the loads count on vmcnt; the wave reads its own tile, so no barrier is needed
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        mfma_scores(tile, sig);
+        mfma_scores(tile, sig, sigR);
     };
 
     // destinations of this wave's share of the loads of the shared first phase
@@ -297,7 +333,8 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
         const int jt = (blockIdx.y * iters + it) * NT * 16;
         int start[NT], len[NT], off[NT], pos[NT];
         bool valid[NT], ok[NT];
-        float sigma[NT], s[NT];
+        float sigma[NT], s[NT];                      // chunk score so far; scores of the candidates
+        float sL[NT], sR[NT];                        // ROPE: the current left key against q_L; candidates against q_R
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int j = jt + t * 16 + n;
@@ -332,15 +369,27 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            mfma_scores(&sh_rows[0], sigma);
-            mfma_scores(&sh_rows[kTile], s);
+            float l0r[NT];
+            mfma_scores(&sh_rows[0], sigma, l0r);
+            mfma_scores(&sh_rows[kTile], s, sR);
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                if (half >= 1 && half < len[t] && s[t] > sigma[t]) { off[t] = half; sigma[t] = s[t]; }
+            for (int t = 0; t < NT; ++t) {
+                const bool has_right = half >= 1 && half < len[t];
+                if constexpr (ROPE) {
+                    const bool right = has_right && sR[t] > sigma[t];        // strict: tie keeps left
+                    off[t] = right ? half : 0;
+                    sL[t] = right ? s[t] : sigma[t];
+                    sigma[t] = right ? sR[t] : l0r[t];
+                } else if (has_right && s[t] > sigma[t]) { off[t] = half; sigma[t] = s[t]; }
+            }
             half >>= 1;
             __syncthreads();                         // tiles 0 and 1 go back to their waves
         } else {
-            score(pos, valid, sigma);
+            score(pos, valid, sigma, sR);
+            if constexpr (ROPE) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) { sL[t] = sigma[t]; sigma[t] = sR[t]; }
+            }
         }
         for (; half >= 1; half >>= 1) {
 #pragma unroll
@@ -348,10 +397,13 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
                 ok[t] = off[t] + half < len[t];
                 pos[t] = start[t] + off[t] + half;
             }
-            score(pos, ok, s);
+            score(pos, ok, s, sR);
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                if (ok[t] && s[t] > sigma[t]) { off[t] += half; sigma[t] = s[t]; }   // strict: tie keeps left
+            for (int t = 0; t < NT; ++t) {
+                if constexpr (ROPE) {
+                    if (ok[t] && sR[t] > sL[t]) { off[t] += half; sL[t] = s[t]; sigma[t] = sR[t]; }
+                } else if (ok[t] && s[t] > sigma[t]) { off[t] += half; sigma[t] = s[t]; }   // strict: tie keeps left
+            }
         }
         // chunk score = max over the group's heads (waves)
 #pragma unroll
@@ -378,8 +430,8 @@ __global__ __launch_bounds__(64 * G, 3) void prune_prefill_kernel(const PruneArg
     }
 }
 
-template <int MT, bool WIDE>
-static void launch_prefill_w(const PruneArgs &a, int P, hipStream_t st)
+template <int MT, bool WIDE, bool ROPE>
+static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hipStream_t st)
 {
     constexpr int NT = 2;
     // several chunk groups per workgroup amortise the staging of the queries, as long as the
@@ -390,10 +442,10 @@ static void launch_prefill_w(const PruneArgs &a, int P, hipStream_t st)
     dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
     KernelTimer timer(stage_name(kNamePrunePrefill, a.parent_starts == nullptr, a.chunk), st);
     switch (a.ge.G) {
-    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE>), grid, dim3(64), 0, st, a, iters); break;
-    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE>), grid, dim3(128), 0, st, a, iters); break;
-    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE>), grid, dim3(256), 0, st, a, iters); break;
-    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE>), grid, dim3(512), 0, st, a, iters); break;
+    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE, ROPE>), grid, dim3(64), 0, st, a, iters, rope); break;
+    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE, ROPE>), grid, dim3(128), 0, st, a, iters, rope); break;
+    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE>), grid, dim3(256), 0, st, a, iters, rope); break;
+    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE, ROPE>), grid, dim3(512), 0, st, a, iters, rope); break;
     }
 }
 
@@ -401,14 +453,20 @@ static void launch_prefill_w(const PruneArgs &a, int P, hipStream_t st)
 // (batch, head) slab of Q and K lies within 2^31 elements of its base and positions and strides are
 // below 2^24; 64-bit offsets otherwise.
 template <int MT>
-static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, hipStream_t st)
+static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, const RopeView *rope, hipStream_t st)
 {
     const int64_t lim = (int64_t)1 << 31;
     const int64_t lim24 = (int64_t)1 << 24;         // narrow offsets are formed by a 24-bit multiply
     const bool wide = max_seq_len * a.k_st + kD >= lim || (int64_t)a.ge.b_q * a.q_st + kD >= lim ||
                       a.k_st < 0 || a.q_st < 0 || max_seq_len >= lim24 || a.k_st >= lim24 || a.q_st >= lim24;
-    if (wide) launch_prefill_w<MT, true>(a, P, st);
-    else launch_prefill_w<MT, false>(a, P, st);
+    if (rope) {
+        if (wide) launch_prefill_w<MT, true, true>(a, P, *rope, st);
+        else launch_prefill_w<MT, false, true>(a, P, *rope, st);
+    } else {
+        const RopeView none{nullptr, nullptr, 0};
+        if (wide) launch_prefill_w<MT, true, false>(a, P, none, st);
+        else launch_prefill_w<MT, false, false>(a, P, none, st);
+    }
 }
 
 template <int G>
@@ -457,10 +515,13 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     if (bank && s.b_q != 1) return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: the host tier serves decode only");
     if (fp8 && (s.b_q != 1 || bank || (rope && rope->prune_style != IHIP_ROPE_NONE)))
         return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: FP8 keys are built for plain decode from device memory only");
+    RopeView rope_view{nullptr, nullptr, 0};
     if (rope && rope->prune_style != IHIP_ROPE_NONE) {
-        if (s.b_q != 1 || bank)
-            return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: dynamic RoPE is built for decode from device memory only");
+        if (bank)
+            return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: dynamic RoPE is built for K in device memory only");
         const int style = rope->prune_style;
+        if (s.b_q != 1 && style == IHIP_ROPE_CHUNK_INDEXED)
+            return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: chunk-indexed RoPE is built for decode only");
         if (style != IHIP_ROPE_RELATIVE && style != IHIP_ROPE_CHUNK_INDEXED)
             return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope prune_style = %d", style);
         if (!rope->cos || !rope->sin) return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope tables are NULL");
@@ -469,8 +530,10 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
         if (rope->n_pos < need)
             return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope table has %d positions, %lld needed", rope->n_pos,
                         (long long)need);
-        return launch_prune_stage_rope(a, RopeView{rope->cos, rope->sin, rope->n_pos}, style, P, st);
+        rope_view = RopeView{rope->cos, rope->sin, rope->n_pos};
+        if (s.b_q == 1) return launch_prune_stage_rope(a, rope_view, style, P, st);
     }
+    const RopeView *rv = rope_view.cos ? &rope_view : nullptr;
     if (s.b_q == 1) {
         switch (a.ge.G) {
         case 1: launch_decode<1>(a, P, fp8, st); break;
@@ -482,9 +545,9 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
         return check_launch("prune_stage (decode)");
     }
     switch (s.b_q) {
-    case 16: launch_prefill<1>(a, P, s.max_seq_len, st); break;
-    case 32: launch_prefill<2>(a, P, s.max_seq_len, st); break;
-    case 64: launch_prefill<4>(a, P, s.max_seq_len, st); break;
+    case 16: launch_prefill<1>(a, P, s.max_seq_len, rv, st); break;
+    case 32: launch_prefill<2>(a, P, s.max_seq_len, rv, st); break;
+    case 64: launch_prefill<4>(a, P, s.max_seq_len, rv, st); break;
     default: return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: b_q = %d not in {1, 16, 32, 64}", s.b_q);
     }
     return check_launch("prune_stage (prefill)");

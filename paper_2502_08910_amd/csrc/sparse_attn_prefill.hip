@@ -20,7 +20,9 @@
 
 namespace ihip {
 
-template <int QT, int G>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
+// ROPE: streaming-style dynamic RoPE; the queries are rotated once, a K piece on its way from the
+// staging registers into LDS (its table row is fetched along with it), both rounded to bf16.
+template <int QT, int G, bool ROPE>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
 __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sK[kPfTile * kPfKStride];
@@ -43,6 +45,11 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
     const int w0 = max(pr.hi, a.ge.n_sink);
     const int total = n_sink_eff + (a.n_blocks << a.block_log2) + max(0, pr.E - w0);
     const int n_tiles = (total + kPfTile - 1) / kPfTile;
+    StreamIds ids{n_sink_eff, a.n_blocks << a.block_log2, 0, w0};
+    if constexpr (ROPE) {
+        __shared__ int sh_tokens;
+        ids.block_tokens = pf_block_tokens(a, pr, p, nthreads, &sh_tokens);
+    }
 
     // B operands of the first product: this head's queries
     bf16x8 qb[QT][4];
@@ -51,8 +58,14 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
+            for (int ks = 0; ks < 4; ++ks) {
                 qb[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + (int64_t)(qt * 16 + n) * a.q_st + ks * 32 + kq * 8);
+                if constexpr (ROPE) {
+                    const int64_t at = (int64_t)ids.query(a.ge.n_sink, qpos0 + qt * 16 + n) * (kD / 2) + ks * 16 + kq * 4;
+                    qb[qt][ks] = __builtin_bit_cast(
+                        bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, qb[qt][ks]), a.rope_cos + at, a.rope_sin + at));
+                }
+            }
     }
     const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
     const uint16_t *vb = a.v + pr.b * a.v_sb + pr.g * a.v_sh;
@@ -71,6 +84,7 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
     constexpr int kMaxPerThread = (kItems + nthreads - 1) / nthreads;
     uint4 rk[kMaxPerThread][2], rv[kMaxPerThread][2];
     int rpos[kMaxPerThread][2];
+    float4 rc[ROPE ? kMaxPerThread : 1][2], rs[ROPE ? kMaxPerThread : 1][2];     // table row piece of each K piece
 
     auto fetch = [&](int tile) {
 #pragma unroll
@@ -89,6 +103,11 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
                     rk[r][e] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos * a.k_st + c * 8);
                     rv[r][e] = *reinterpret_cast<const uint4 *>(vb + (int64_t)pos * a.v_st + c * 8);
                 }
+                if constexpr (ROPE) {
+                    const int64_t at = (int64_t)(pos >= 0 ? ids.key(slot) : 0) * (kD / 2) + c * 4;
+                    rc[r][e] = *reinterpret_cast<const float4 *>(a.rope_cos + at);
+                    rs[r][e] = *reinterpret_cast<const float4 *>(a.rope_sin + at);
+                }
             }
         }
     };
@@ -101,8 +120,12 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
             const int a2 = item >> 4, c = item & 15;
             const int key0 = a2 * 2;                                   // keys key0, key0+1 of the 32
 #pragma unroll
-            for (int e = 0; e < 2; ++e)
+            for (int e = 0; e < 2; ++e) {
+                if constexpr (ROPE)
+                    rk[r][e] = rotate_bf16x8(rk[r][e], reinterpret_cast<const float *>(&rc[r][e]),
+                                             reinterpret_cast<const float *>(&rs[r][e]));
                 *reinterpret_cast<uint4 *>(&sK[(key0 + e) * kPfKStride + c * 8]) = rk[r][e];
+            }
             // k slot of key kk: tile t = kk/16, kq = (kk%16)/4, j = kk%4 + 4*t
             const int t = key0 >> 4, kk = key0 & 15;
             const int kslot = (kk >> 2) * 8 + (kk & 3) + 4 * t;        // even; key0+1 sits at kslot+1
@@ -222,9 +245,23 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
 
 int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                             const ihip_tensor &v, const int32_t *block_starts, int n_blocks, int block,
-                            float sm_scale, void *out, float *out_lse, hipStream_t st)
+                            float sm_scale, void *out, float *out_lse, const ihip_rope *rope, hipStream_t st)
 {
     AttnPrefillArgs a;
+    const bool use_rope = rope && rope->attn_style != IHIP_ROPE_NONE;
+    a.rope_cos = a.rope_sin = nullptr;
+    if (use_rope) {
+        if (rope->attn_style != IHIP_ROPE_STREAMING)
+            return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_prefill: rope attn_style = %d", rope->attn_style);
+        if (!rope->cos || !rope->sin) return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_prefill: rope tables are NULL");
+        // largest id: a query that attends to every slot
+        const int64_t need = (int64_t)s.n_sink + (int64_t)n_blocks * block + s.n_stream;
+        if (rope->n_pos < need)
+            return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_prefill: rope table has %d positions, %lld needed",
+                        rope->n_pos, (long long)need);
+        a.rope_cos = rope->cos;
+        a.rope_sin = rope->sin;
+    }
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
@@ -240,16 +277,18 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     if (P == 0) return IHIP_OK;
     KernelTimer timer("attn_prefill", st);
     const dim3 block_dim(64 * a.ge.G), grid(P);
-#define IHIP_PF_BY_G(KERNEL, QT)                                                                   \
+#define IHIP_PF_BY_G2(KERNEL, QT, RP)                                                              \
     switch (a.ge.G) {                                                                              \
-    case 1: hipLaunchKernelGGL((KERNEL<QT, 1>), grid, block_dim, 0, st, a); break;                 \
-    case 2: hipLaunchKernelGGL((KERNEL<QT, 2>), grid, block_dim, 0, st, a); break;                 \
-    case 4: hipLaunchKernelGGL((KERNEL<QT, 4>), grid, block_dim, 0, st, a); break;                 \
-    default: hipLaunchKernelGGL((KERNEL<QT, 8>), grid, block_dim, 0, st, a); break;                \
+    case 1: hipLaunchKernelGGL((KERNEL<QT, 1, RP>), grid, block_dim, 0, st, a); break;             \
+    case 2: hipLaunchKernelGGL((KERNEL<QT, 2, RP>), grid, block_dim, 0, st, a); break;             \
+    case 4: hipLaunchKernelGGL((KERNEL<QT, 4, RP>), grid, block_dim, 0, st, a); break;             \
+    default: hipLaunchKernelGGL((KERNEL<QT, 8, RP>), grid, block_dim, 0, st, a); break;            \
     }
+#define IHIP_PF_BY_G(KERNEL, QT)                                                                   \
+    if (use_rope) { IHIP_PF_BY_G2(KERNEL, QT, true) } else { IHIP_PF_BY_G2(KERNEL, QT, false) }
     // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
     const bool fits32 = s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= kPf32MaxSlots;
-    if (fits32) {
+    if (fits32 && !use_rope) {
         launch_attn_prefill32(a, P, s.max_seq_len, st);
         return check_launch("sparse_attn_prefill");
     }
@@ -260,6 +299,7 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     default: return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_prefill: b_q = %d not in {16, 32, 64}", s.b_q);
     }
 #undef IHIP_PF_BY_G
+#undef IHIP_PF_BY_G2
     return check_launch("sparse_attn_prefill");
 }
 

@@ -76,13 +76,21 @@ def test_argument_checks_of_the_variants_need_no_gpu(built_lib):
     r = RopeStruct(256, 256, 1025, 1, 1)                     # needs n_stream + 2 = 1026 rows
     assert L.ihip_prune_stage_rope(ctypes.byref(s), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None) == -1
     assert b"1026" in L.ihip_last_error()
-    # rope is a decode feature
+    # chunked prefill: the chunk-indexed style is a decode feature; the attention checks the table
     sp = Shape(1, 32, 8, 128, 64, 64, 1, 4096, 128, 1024)
-    r = RopeStruct(256, 256, 8192, 1, 1)
+    r = RopeStruct(256, 256, 8192, 2, 1)
     rc = L.ihip_prune_stage_rope(ctypes.byref(sp), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None)
     assert rc == -4
-    # fp8: scales must be positive and finite; rows 16-byte aligned in bytes
     f = ctypes.c_float
+    assert L.ihip_sparse_attn_prefill_rope(ctypes.byref(sp), t, t, t, 256, 16, 16, f(0.1), None, 256, None, None, 0,
+                                           None) == -1
+    r = RopeStruct(256, 256, 128 + 256 + 1024 - 1, 1, 1)     # needs n_sink + n_blocks*block + n_stream rows
+    assert L.ihip_sparse_attn_prefill_rope(ctypes.byref(sp), t, t, t, 256, 16, 16, f(0.1), ctypes.byref(r), 256,
+                                           None, None, 0, None) == -1
+    assert b"1408" in L.ihip_last_error()
+    assert L.ihip_prefill_layer_rope(ctypes.byref(sp), t, t, t, 0, None, None, f(0.1), None, 256, None, None, None,
+                                     0, None) == -1
+    # fp8: scales must be positive and finite; rows 16-byte aligned in bytes
     assert L.ihip_prune_stage_fp8kv(ctypes.byref(s), t, t, None, 0, 0, 64, slots, f(0.0), 256, None, None) == -1
     assert L.ihip_prune_stage_fp8kv(ctypes.byref(s), t, t, None, 0, 0, 64, slots, f(float("inf")), 256, None, None) == -1
     t8 = Tensor(256, 0, 0, 136)
