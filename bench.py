@@ -319,8 +319,15 @@ def bench_prefill(args, w, torch, ihip, configs):
     ws = L.workspace(ihip.OP_PREFILL_LAYER, chunks, keeps)
     out = torch.empty((w.B, w.Hq, w.Tq, w.d), dtype=torch.bfloat16, device=dev)
 
+    rope = None
+    if args.rope:
+        assert args.rope == "relative", "chunked prefill: relative-style pruning + streaming-style attention only"
+        from workloads import gen
+        cos, sin = gen.rope_table(w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8, w.d, device=dev)
+        rope = ihip.Rope(cos, sin, ihip.ROPE_RELATIVE, ihip.ROPE_STREAMING)
+
     def step(i):
-        L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out)
+        L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out, rope=rope)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 
@@ -341,7 +348,8 @@ def bench_prefill(args, w, torch, ihip, configs):
             pairs += n * (1 + int(math.log2(c))) * w.b_q
         n_valid_prev = kept_valid
         first = ".first" if i == 0 else ""
-        flops[f"prune_prefill{first}.l{c}"] = w.B * w.Hq * pairs * w.d * 2
+        # relative-style RoPE: every candidate row against two rotated copies of the queries
+        flops[f"prune_prefill{first}.l{c}"] = w.B * w.Hq * pairs * w.d * 2 * (2 if rope else 1)
     keys = 0
     for m in range(w.Mq):
         E = (w.T - w.Tq) + (m + 1) * w.b_q
@@ -364,13 +372,13 @@ def bench_prefill(args, w, torch, ihip, configs):
         ach = kernels[dom]["TFLOPs"]
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "traffic": None if rope else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                     "flops_per_launch": flops[dom], "us_per_launch": kernels[dom]["us"],
                     "measured_mfma_rate": measured[dom.split(".")[0]],
                     "frac_of_measured_mfma_rate": ach / measured[dom.split(".")[0]]}
 
     cpu = None
-    if args.cpu_seconds > 0:
+    if args.cpu_seconds > 0 and not rope:
         import oracle
         oracle.build(force=False)
         blocks = [0, w.Mq // 3, (2 * w.Mq) // 3, w.Mq - 1]
@@ -390,7 +398,7 @@ def bench_prefill(args, w, torch, ihip, configs):
     return {
         "metric": "sparse_attn_prefill_us_per_layer",
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
-        "config": {"workload": w.name, "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
+        "config": {"workload": w.name + ("_dynamic_rope_relative" if rope else ""), "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
                    "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink, "n_stream": w.n_stream},
         "roofline": roofline, "cpu_baseline": cpu,

@@ -79,6 +79,7 @@ __device__ inline int pf_slot_to_pos(const AttnPrefillArgs &a, const Problem &pr
 
 constexpr int kPf32MaxLds = 160 * 1024;  // LDS per workgroup the 32x32 kernel may ask for
 constexpr int kPf32MaxSlots = 24320;    // key slots whose positions (and per-tile flags) the 32x32 kernel keeps in LDS
+constexpr int kPf32MaxSlotsRope = 20224; // ... with streaming-style RoPE (one more K/V stage)
 
 void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len, hipStream_t st);
 

@@ -167,9 +167,8 @@ __device__ inline uint32_t f32_to_bf16_bits(float f)
 
 // 8 bf16 = 4 (even, odd) dim pairs, each turned by the angle whose cos and sin are given (fp32
 // arithmetic, results rounded to bf16, nearest-even): ApplyRope of Sec. 4 on a 16-byte piece of a row
-__device__ inline uint4 rotate_bf16x8(const uint4 x, const float *cos4, const float *sin4)
+__device__ inline uint4 rotate_bf16x8(const uint4 x, const float4 c, const float4 sn)
 {
-    const float4 c = *reinterpret_cast<const float4 *>(cos4), sn = *reinterpret_cast<const float4 *>(sin4);
     const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
     const uint32_t in[4] = {x.x, x.y, x.z, x.w};
     uint32_t w[4];
@@ -179,6 +178,10 @@ __device__ inline uint4 rotate_bf16x8(const uint4 x, const float *cos4, const fl
         w[i] = f32_to_bf16_bits(e * cc[i] - o * ss[i]) | (f32_to_bf16_bits(e * ss[i] + o * cc[i]) << 16);
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
+}
+__device__ inline uint4 rotate_bf16x8(const uint4 x, const float *cos4, const float *sin4)
+{
+    return rotate_bf16x8(x, *reinterpret_cast<const float4 *>(cos4), *reinterpret_cast<const float4 *>(sin4));
 }
 
 // 8 bf16 (one lane's 16-byte share of a row) dotted with 8 fp32

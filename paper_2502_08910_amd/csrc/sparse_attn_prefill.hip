@@ -122,8 +122,7 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 if constexpr (ROPE)
-                    rk[r][e] = rotate_bf16x8(rk[r][e], reinterpret_cast<const float *>(&rc[r][e]),
-                                             reinterpret_cast<const float *>(&rs[r][e]));
+                    rk[r][e] = rotate_bf16x8(rk[r][e], rc[r][e], rs[r][e]);
                 *reinterpret_cast<uint4 *>(&sK[(key0 + e) * kPfKStride + c * 8]) = rk[r][e];
             }
             // k slot of key kk: tile t = kk/16, kq = (kk%16)/4, j = kk%4 + 4*t
@@ -288,7 +287,8 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     if (use_rope) { IHIP_PF_BY_G2(KERNEL, QT, true) } else { IHIP_PF_BY_G2(KERNEL, QT, false) }
     // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
     const bool fits32 = s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= kPf32MaxSlots;
-    if (fits32 && !use_rope) {
+    const bool fits32_rope = s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= kPf32MaxSlotsRope;
+    if (use_rope ? fits32_rope : fits32) {
         launch_attn_prefill32(a, P, s.max_seq_len, st);
         return check_launch("sparse_attn_prefill");
     }

@@ -38,6 +38,14 @@
 // period u-1 (and before the loop for u = 0), V(u) in period u, so the stage of
 // tile t-1 is free when period t begins and takes tile t+3.  The loop is
 // unrolled by the four stages.
+//
+// ROPE (streaming-style dynamic RoPE, Sec. 4 "Dynamic RoPE for OOL
+// generalization"): the queries are rotated once, to the id of their last key.
+// A K tile is rotated in place in LDS, each thread one 16-byte piece, in the
+// period between its landing and its first read, which takes a fifth stage:
+// tile t+4 is requested at the start of period t, tile t+3 must have landed at
+// its end, K(t+2) is rotated during it (with table pieces fetched a period
+// earlier) and read in period t+1.  Rotated operands are rounded to bf16.
 #include "attn_prefill_args.h"
 #include <type_traits>
 
@@ -47,7 +55,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kPfStages = 4;
+constexpr int kPfStagesPlain = 4, kPfStagesRope = 5;
 constexpr int kPfTileEl = kPfTile * kD;            // elements of one K (or V) tile: 32 rows of 256 bytes
 constexpr int kPfStageEl = 2 * kPfTileEl;          // K tile, then V tile
 constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above which the softmax reference moves
@@ -59,9 +67,10 @@ constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above w
 // WIDE: 64-bit row offsets; otherwise every
 // row of a (sequence, KV head) slab of K and V lies within 2^31 elements of its base and positions
 // and strides are below 2^24, so an offset is one full-rate 24-bit multiply.
-template <int NQ, int G, bool WIDE>
-__global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) void attn_prefill32_kernel(const AttnPrefillArgs a)
+template <int NQ, int G, bool WIDE, bool ROPE>
+__global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || (ROPE && NQ * G == 8) ? 2 : NQ * G == 8 ? 3 : 4) void attn_prefill32_kernel(const AttnPrefillArgs a)
 {
+    constexpr int kPfStages = ROPE ? kPfStagesRope : kPfStagesPlain;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     int *sPos = reinterpret_cast<int *>(smem + kPfStages * kPfStageEl);      // one int per key slot
     // one flag per tile, behind the positions of the most slots this geometry can have
@@ -102,11 +111,24 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
         if ((lane & 31) == 0) sMasked[slot >> 5] = (uint32_t)(m >> (lane & 32)) != 0u;
     }
 
+    StreamIds ids{n_sink_eff, a.n_blocks << a.block_log2, 0, w0};
+    if constexpr (ROPE) {
+        __shared__ int sh_tokens;
+        ids.block_tokens = pf_block_tokens(a, pr, p, nthreads, &sh_tokens);
+    }
+
     bf16x8 qb[8];
     {
         const uint16_t *qp = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(q0 + n) * a.q_st + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qb[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+        for (int ks = 0; ks < 8; ++ks) {
+            qb[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+            if constexpr (ROPE) {       // dims 16*ks + 8*half .. +7 = pairs 8*ks + 4*half .. +3
+                const int64_t at = (int64_t)ids.query(a.ge.n_sink, qpos) * (kD / 2) + ks * 8 + half * 4;
+                qb[ks] = __builtin_bit_cast(
+                    bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, qb[ks]), a.rope_cos + at, a.rope_sin + at));
+            }
+        }
     }
     const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
     const uint16_t *vb = a.v + pr.b * a.v_sb + pr.g * a.v_sh;
@@ -158,6 +180,36 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
                 (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)(stage + j * 4 * kD));
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
                          : "memory");
+        }
+    };
+
+    // ROPE: the K part of a stage is 32 rows x 16 pieces of 16 bytes, dealt to the threads; slot s
+    // of row r holds dims 8*(s ^ r%16)..  table_of fetches the table pieces of a tile's keys,
+    // rotate_k turns the tile in place.
+    constexpr int kPieces = ROPE ? (kPfTile * 16 + nthreads - 1) / nthreads : 1;
+    struct Table { float4 c[kPieces], s[kPieces]; };
+    auto table_of = [&](int tile) {
+        Table tb;
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) {
+            const int item = tid + i * nthreads, r = (item >> 4) & (kPfTile - 1), sl = item & 15;
+            const int slot = tile * kPfTile + r;
+            const int id = tile < n_tiles && slot < total ? ids.key(slot) : 0;
+            const int64_t at = (int64_t)id * (kD / 2) + ((sl ^ (r & 15)) << 2);
+            tb.c[i] = *reinterpret_cast<const float4 *>(a.rope_cos + at);
+            tb.s[i] = *reinterpret_cast<const float4 *>(a.rope_sin + at);
+        }
+        return tb;
+    };
+    auto rotate_k = [&](int tile, int st, const Table &tb) {
+        if (tile >= n_tiles) return;
+        uint16_t *stage = stage_of(st);
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) {
+            const int item = tid + i * nthreads;
+            if (kPfTile * 16 % nthreads != 0 && item >= kPfTile * 16) break;
+            uint4 *piece = reinterpret_cast<uint4 *>(stage + (item >> 4) * kD + (item & 15) * 8);
+            *piece = rotate_bf16x8(*piece, tb.c[i], tb.s[i]);
         }
     };
 
@@ -245,13 +297,14 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
             for (int kk = 0; kk < 2; ++kk)
                 o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(cV, dt, kk), pb[kk], o[dt], 0, 0, 0);
     };
-    // Tile t+D is requested at the start of period t (D = kPfStages-1); tile t+2 must have landed
-    // at the barrier that ends it, so D-2 newer requests may still be on their way then (near the
-    // end of the key list fewer are: everything is waited for).
+    // Tile t+D is requested at the start of period t (D = kPfStages-1); tile t+2 (ROPE: t+3) must
+    // have landed at the barrier that ends it, so one newer request may still be on its way then
+    // (near the end of the key list fewer are: everything is waited for).
     constexpr int D = kPfStages - 1;
+    constexpr int kInFlight = ROPE ? D - 3 : D - 2;
     auto landed = [&](bool all) {
-        if (all || D == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * kLoadsPerWave) : "memory");
+        if (all || kInFlight == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight * kLoadsPerWave) : "memory");
     };
 
     __syncthreads();                        // sPos complete
@@ -260,6 +313,13 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     Rows rows = rows_of(D);
     landed(true);                           // tiles 0 and 1 (and the rest of the prologue's requests)
     __syncthreads();
+    Table table;                            // ROPE: table pieces of the tile that the next period rotates
+    if constexpr (ROPE) {
+        rotate_k(0, 0, table_of(0));
+        rotate_k(1, 1, table_of(1));
+        table = table_of(2);
+        __syncthreads();
+    }
     f32x16 s_nxt = scores(0);
     bf16x8 pb[2];
     softmax(0, sMasked[0] != 0, s_nxt, pb);
@@ -267,13 +327,21 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 ? 2 : NQ * G == 8 ? 3 : 4) 
     // one tile period; ST = tile % kPfStages
     auto period = [&](auto st_c, int tile) {
         constexpr int ST = decltype(st_c)::value;
+        // the table loads come before the request: the wait the compiler puts before their use then
+        // lets exactly the newer request stay in flight
+        Table table_nxt;
+        if constexpr (ROPE) table_nxt = table_of(tile + 3);
         request(tile + D, ST + D, rows);
         if (tile + 1 < n_tiles) s_nxt = scores(ST + 1);
         accumulate(ST, pb);
         if (tile + 1 < n_tiles) softmax(tile + 1, masked_nxt != 0, s_nxt, pb);
         masked_nxt = tile + 2 < n_tiles ? sMasked[tile + 2] : 0;
         rows = rows_of(tile + D + 1);
-        landed(tile + D >= n_tiles);        // tile + 2
+        if constexpr (ROPE) {
+            rotate_k(tile + 2, ST + 2, table);
+            table = table_nxt;
+        }
+        landed(tile + D >= n_tiles);        // tile + 2 (ROPE: tile + 3)
         __syncthreads();
     };
     auto periods = [&](int tile, auto... st) {      // up to kPfStages periods, stopping at the last tile
@@ -317,21 +385,24 @@ void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len,
     const int parts = a.ge.G / heads_per_wg;
     const dim3 block_dim(64 * NQ * heads_per_wg), grid(parts == 1 ? P : (P + 7) / 8 * 8 * parts);
     const int slots = (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile;
-    const size_t lds = (size_t)kPfStages * kPfStageEl * sizeof(uint16_t) + (size_t)slots * sizeof(int) +
-                       slots / kPfTile;             // stages, slot positions, per-tile flags
+    const bool use_rope = a.rope_cos != nullptr;
+    const size_t lds = (size_t)(use_rope ? kPfStagesRope : kPfStagesPlain) * kPfStageEl * sizeof(uint16_t) +
+                       (size_t)slots * sizeof(int) + slots / kPfTile;     // stages, slot positions, per-tile flags
     const int64_t lim = (int64_t)1 << 31, lim24 = (int64_t)1 << 24;
     const bool wide = max_seq_len >= lim24 || a.k_st < 0 || a.v_st < 0 || a.k_st >= lim24 || a.v_st >= lim24 ||
                       max_seq_len * a.k_st + kD >= lim || max_seq_len * a.v_st + kD >= lim;
-#define IHIP_PF32(NQV, GV, WV)                                                                               \
+#define IHIP_PF32_R(NQV, GV, WV, RV)                                                                         \
     {                                                                                                        \
         static bool attr_set = false;     /* allow more than 64 KiB of dynamic LDS, once per kernel */       \
         if (!attr_set) {                                                                                     \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_prefill32_kernel<NQV, GV, WV>),  \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, kPf32MaxLds);             \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_prefill32_kernel<NQV, GV, WV, RV>), \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kPf32MaxLds - (RV ? 64 : 0)); \
             attr_set = true;                                                                                 \
         }                                                                                                    \
-        hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV, WV>), grid, block_dim, lds, st, a);              \
+        hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV, WV, RV>), grid, block_dim, lds, st, a);          \
     }
+#define IHIP_PF32(NQV, GV, WV)                                                                               \
+    if (use_rope) IHIP_PF32_R(NQV, GV, WV, true) else IHIP_PF32_R(NQV, GV, WV, false)
 #define IHIP_PF32_BY_G(NQV, WV)             \
     switch (heads_per_wg) {                 \
     case 1: IHIP_PF32(NQV, 1, WV); break;   \
@@ -346,6 +417,7 @@ void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len,
     }
 #undef IHIP_PF32_BY_G
 #undef IHIP_PF32
+#undef IHIP_PF32_R
 }
 
 }  // namespace ihip
