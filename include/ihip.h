@@ -325,6 +325,7 @@ int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_ten
  * caller's policy.  Scratch as for IHIP_OP_DECODE_LAYER.
  */
 size_t  ihip_mask_state_elems(const ihip_shape *shape, int32_t n_stages, const int32_t *keeps);
+
 int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                                  int32_t first_stage, int32_t *stage_starts, float sm_scale, void *out,
@@ -387,6 +388,39 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                                  float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
                                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The decode layer with any combination of the variants above that the kernels
+ * are built for, chosen by one options struct (zero-initialise it: every zero
+ * field means "off"):
+ *   rope          dynamic RoPE (pruning and attention styles inside), or NULL
+ *   cache         host tier: k and v are ignored, the handle's host tensors and
+ *                 banks are used, or NULL
+ *   paged         k and v are page pools read through this block table, or NULL
+ *   kv_fp8        non-zero: k and v hold E4M3 bytes with the scales k_scale, v_scale
+ *   pooling       IHIP_POOL_KV_HEAD / IHIP_POOL_ALL_HEADS
+ *   stage_starts  mask-caching state as in ihip_decode_layer_masked, or NULL;
+ *   first_stage   first stage to recompute (needs stage_starts unless 0)
+ * Paged, FP8 and RoPE combine freely with each other, with either pooling rule
+ * and with mask caching; the host tier combines with pooling and mask caching
+ * only (IHIP_ERR_UNSUPPORTED otherwise).  With stage_starts the scratch is the
+ * scores buffer plus the attention partials (IHIP_OP_DECODE_LAYER covers it);
+ * out_block_starts, if given, receives a copy of the final list.
+ */
+typedef struct ihip_decode_options {
+    const ihip_rope *rope;
+    const ihip_cache *cache;
+    const ihip_paged_kv *paged;
+    int32_t kv_fp8;
+    float k_scale, v_scale;
+    int32_t pooling;
+    int32_t first_stage;
+    int32_t *stage_starts;
+} ihip_decode_options;
+int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                             int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                             float sm_scale, const ihip_decode_options *opt, void *out, float *out_lse,
+                             int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 int32_t ihip_cache_update(ihip_cache *cache, void *stream);
 int32_t ihip_cache_stats(ihip_cache *cache, uint64_t *stats8);
 int32_t ihip_cache_read_tables(ihip_cache *cache, int32_t bank, int32_t *host_page_table,

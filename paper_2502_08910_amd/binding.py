@@ -45,6 +45,8 @@ EXPORTS = {
                                              c_f, vp, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
                                        vp, vp, vp, vp, c_sz, vp]),
+    "ihip_decode_layer_ex": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
+                                     vp, vp, vp, vp, c_sz, vp]),
     "ihip_sparse_attn_prefill_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
                                               c_f, vp, vp, vp, vp, c_sz, vp]),
     "ihip_prefill_layer_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
@@ -216,6 +218,12 @@ class PagedKV:
         return ctypes.byref(self.c)
 
 
+class DecodeOptions(ctypes.Structure):
+    """ihip_decode_options (all zero = the plain decode layer)."""
+    _fields_ = [("rope", vp), ("cache", vp), ("paged", vp), ("kv_fp8", c_i32), ("k_scale", c_f), ("v_scale", c_f),
+                ("pooling", c_i32), ("first_stage", c_i32), ("stage_starts", vp)]
+
+
 class Layer:
     """Shape of one attention call plus the device seq_lens; the methods are
     the C entry points of the same names."""
@@ -369,14 +377,48 @@ class Layer:
 
     def decode_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
                      out_blocks=None, lse=None, rope: Optional["Rope"] = None, pooling: Optional[int] = None,
-                     kv_scales: Optional[Sequence[float]] = None, paged: Optional["PagedKV"] = None):
+                     kv_scales: Optional[Sequence[float]] = None, paged: Optional["PagedKV"] = None,
+                     cache: Optional["HostKVCache"] = None, stage_starts: Optional[torch.Tensor] = None,
+                     first_stage: Optional[int] = None):
         """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d].
-        paged: k and v are ignored, the pools of `paged` are read through its block table."""
+        paged: k and v are ignored, the pools of `paged` are read through its block table.
+        cache: k and v are ignored, the host tier is read.  stage_starts / first_stage: mask caching
+        (see decode_layer_masked).  One variant alone goes to its own entry point, combinations (and
+        the host tier) to ihip_decode_layer_ex."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
+        n_variants = sum(x is not None for x in (rope, pooling, kv_scales, paged, cache, stage_starts))
+        if stage_starts is not None and first_stage is None:
+            raise IhipError("decode_layer: stage_starts needs first_stage")
+        if n_variants > 1 or cache is not None:
+            # combinations go through the one entry point that takes them all
+            opt = DecodeOptions()
+            opt.rope = ctypes.cast(rope.ref(), vp) if rope is not None else None
+            opt.cache = cache.handle if cache is not None else None
+            opt.paged = ctypes.cast(paged.ref(), vp) if paged is not None else None
+            if kv_scales is not None:
+                opt.kv_fp8, opt.k_scale, opt.v_scale = 1, kv_scales[0], kv_scales[1]
+            opt.pooling = POOL_KV_HEAD if pooling is None else pooling
+            opt.first_stage = 0 if first_stage is None else first_stage
+            opt.stage_starts = stage_starts.data_ptr() if stage_starts is not None else None
+            conv = _tensor8 if kv_scales is not None else _tensor
+            if paged is not None:
+                tk, tv = conv(paged.k_pool, "k_pool"), conv(paged.v_pool, "v_pool")
+            elif cache is not None:
+                tk = tv = Tensor(None, 0, 0, 0)
+            else:
+                tk, tv = conv(k, "k"), conv(v, "v")
+            _check(lib().ihip_decode_layer_ex(ctypes.byref(self.shape), _tensor(q, "q"), tk, tv, len(chunk_sizes),
+                                              _i32(chunk_sizes), _i32(keeps), sm_scale, ctypes.byref(opt),
+                                              _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws), ws.numel(),
+                                              _stream()))
+            return out
+        if stage_starts is not None:
+            return self.decode_layer_masked(q, k, v, chunk_sizes, keeps, first_stage, stage_starts, sm_scale, ws,
+                                            out, lse)
         if paged is not None:
             _check(lib().ihip_decode_layer_paged(ctypes.byref(self.shape), _tensor(q, "q"),
                                                  _tensor(paged.k_pool, "k_pool"), _tensor(paged.v_pool, "v_pool"),

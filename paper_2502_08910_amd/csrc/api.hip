@@ -492,11 +492,13 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, in
                           false, (hipStream_t)stream);
 }
 
+// stage_starts != NULL: mask caching (the caller's per-stage lists; stages first_stage.. are recomputed)
 static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                                  ihip_tensor v, const ihip_cache *cache, const ihip_rope *rope, bool all_heads,
                                  const KvFormat *fmt, int32_t n_stages,
                                  const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
-                                 float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+                                 float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream,
+                                 int32_t first_stage = 0, int32_t *stage_starts = nullptr)
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
@@ -511,14 +513,35 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     const size_t P = (size_t)shape->B * shape->Hkv;
     const size_t blocks_bytes = align256(P * keeps[last] * sizeof(int32_t));
     const size_t attn_bytes = attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
+    BankView mask_bank, sa_bank;
+    if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
+    if (cache && rope) return fail(IHIP_ERR_UNSUPPORTED, "%s: dynamic RoPE is not built for the host tier", who);
+    if (stage_starts) {
+        if (first_stage < 0 || first_stage > n_stages)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d not in 0..%d", who, first_stage, n_stages);
+        const size_t need = L.scores_bytes + attn_bytes;
+        if (!ws || ws_bytes < need)
+            return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
+        int32_t *stage_out[8];
+        size_t off = 0;
+        for (int i = 0; i < n_stages; ++i) { stage_out[i] = stage_starts + off; off += P * (size_t)keeps[i]; }
+        rc = prune_stages_impl(*shape, q, k, n_stages, chunk_sizes, keeps, first_stage, stage_out, (float *)ws,
+                               cache ? &mask_bank : nullptr, rope, all_heads, (hipStream_t)stream, fmt);
+        if (rc != IHIP_OK) return rc;
+        if (out_block_starts &&
+            hipMemcpyAsync(out_block_starts, stage_out[last], P * keeps[last] * sizeof(int32_t),
+                           hipMemcpyDeviceToDevice, (hipStream_t)stream) != hipSuccess)
+            return fail(IHIP_ERR_HIP, "%s: copy of the final block list failed", who);
+        return launch_attn_decode(*shape, q, k, v, stage_out[last], keeps[last], chunk_sizes[last], sm_scale, out,
+                                  out_lse, (char *)ws + L.scores_bytes, cache ? &sa_bank : nullptr, rope,
+                                  (hipStream_t)stream, fmt);
+    }
+    if (first_stage != 0) return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d without stage_starts", who, first_stage);
     const size_t need = L.total + blocks_bytes + attn_bytes;
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
-    BankView mask_bank, sa_bank;
-    if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
-    if (cache && rope) return fail(IHIP_ERR_UNSUPPORTED, "%s: dynamic RoPE is not built for the host tier", who);
     rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, cache ? &mask_bank : nullptr, rope,
                         all_heads, (hipStream_t)stream, fmt);
     if (rc != IHIP_OK) return rc;
@@ -614,31 +637,42 @@ int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_te
                                  float *out_lse, void *ws, size_t ws_bytes, void *stream)
 {
     const char *who = "ihip_decode_layer_masked";
+    if (!stage_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: out / stage_starts is NULL", who);
+    return decode_layer_impl(who, shape, q, k, v, nullptr, nullptr, false, nullptr, n_stages, chunk_sizes, keeps,
+                             sm_scale, out, out_lse, nullptr, ws, ws_bytes, stream, first_stage, stage_starts);
+}
+
+int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                             const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale,
+                             const ihip_decode_options *opt, void *out, float *out_lse, int32_t *out_block_starts,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_decode_layer_ex";
+    if (!opt) return fail(IHIP_ERR_INVALID_ARG, "%s: options are NULL", who);
     int32_t rc;
-    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
-    if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
-    if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
-    if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
-    if (first_stage < 0 || first_stage > n_stages)
-        return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d not in 0..%d", who, first_stage, n_stages);
-    if (!out || !stage_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: out / stage_starts is NULL", who);
-    const int last = n_stages - 1;
-    const PlanLayout L = plan_layout(*shape, n_stages, chunk_sizes, keeps);
-    const size_t attn_bytes = attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
-    const size_t need = L.scores_bytes + attn_bytes;
-    if (!ws || ws_bytes < need)
-        return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
-    const size_t P = (size_t)shape->B * shape->Hkv;
-    int32_t *stage_out[8];
-    size_t off = 0;
-    for (int i = 0; i < n_stages; ++i) { stage_out[i] = stage_starts + off; off += P * (size_t)keeps[i]; }
-    rc = prune_stages_impl(*shape, q, k, n_stages, chunk_sizes, keeps, first_stage, stage_out, (float *)ws, nullptr,
-                           nullptr, false, (hipStream_t)stream);
-    if (rc != IHIP_OK) return rc;
-    return launch_attn_decode(*shape, q, k, v, stage_out[last], keeps[last], chunk_sizes[last], sm_scale, out,
-                              out_lse, (char *)ws + L.scores_bytes, nullptr, nullptr, (hipStream_t)stream);
+    KvFormat fmt{false, 1.0f, 1.0f, PagedView{nullptr, 0, 0}};
+    if (opt->paged && (rc = check_paged(who, shape, opt->paged, &fmt)) != IHIP_OK) return rc;
+    if (opt->kv_fp8) {
+        if ((rc = check_scales(who, opt->k_scale, opt->v_scale)) != IHIP_OK) return rc;
+        fmt.fp8 = true; fmt.k_scale = opt->k_scale; fmt.v_scale = opt->v_scale;
+    }
+    if ((rc = check_pooling(who, opt->pooling)) != IHIP_OK) return rc;
+    if (opt->first_stage != 0 && !opt->stage_starts)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d without stage_starts", who, opt->first_stage);
+    if (opt->cache) {
+        if (opt->paged || opt->kv_fp8)
+            return fail(IHIP_ERR_UNSUPPORTED, "%s: the host tier holds contiguous bf16 K/V", who);
+        int32_t B, Hkv;
+        int64_t T_alloc;
+        cache_describe(opt->cache, &B, &Hkv, &T_alloc, &k, &v);
+        if (shape && (shape->B != B || shape->Hkv != Hkv || shape->max_seq_len > T_alloc))
+            return fail(IHIP_ERR_INVALID_ARG, "%s: shape (B %d, Hkv %d, max_seq_len %d) does not fit the cache (%d, %d, %lld)",
+                        who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
+    }
+    const bool plain = !opt->paged && !opt->kv_fp8;
+    return decode_layer_impl(who, shape, q, k, v, opt->cache, opt->rope, opt->pooling == IHIP_POOL_ALL_HEADS,
+                             plain ? nullptr : &fmt, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
+                             out_block_starts, ws, ws_bytes, stream, opt->first_stage, opt->stage_starts);
 }
 
 static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,

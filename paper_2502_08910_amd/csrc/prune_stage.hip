@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
     // row `pos` (in page `page`, if K is paged): this lane's share of it
     auto load_row = [&](int pos, int page) {
         if constexpr (SRC == 2)
-            return *reinterpret_cast<const piece_t *>(src.row_in_page(page, pos) + l16 * 8);
+            return *reinterpret_cast<const piece_t *>(src.row_in_page(page, pos) + l16 * (KV8 ? 4 : 8));
         else
             return *reinterpret_cast<const piece_t *>(src.row(pos, leader) + l16 * (KV8 ? 4 : 8));
     };
@@ -475,7 +475,9 @@ static void launch_decode(const PruneArgs &a, int P, bool fp8, hipStream_t st)
     constexpr int U = 2;
     dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
     KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
-    if (fp8)
+    if (fp8 && a.paged.block_table != nullptr)
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, true>), grid, dim3(256), 0, st, a);
+    else if (fp8)
         hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, true>), grid, dim3(256), 0, st, a);
     else if (a.paged.block_table != nullptr)
         hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, false>), grid, dim3(256), 0, st, a);
@@ -485,7 +487,7 @@ static void launch_decode(const PruneArgs &a, int P, bool fp8, hipStream_t st)
         hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, false>), grid, dim3(256), 0, st, a);
 }
 
-int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, hipStream_t st);
+int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, bool fp8, hipStream_t st);
 
 int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                            const int32_t *parent_starts, int n_parent, int parent_chunk, int chunk,
@@ -496,8 +498,8 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     const bool fp8 = fmt && fmt->fp8;
     a.k_scale = fp8 ? fmt->k_scale : 1.0f;
     a.paged = (fmt && fmt->paged.block_table) ? fmt->paged : PagedView{nullptr, 0, 0};
-    if (a.paged.block_table && (fp8 || bank || s.b_q != 1 || (rope && rope->prune_style != IHIP_ROPE_NONE)))
-        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: paged K is built for plain bf16 decode only");
+    if (a.paged.block_table && (bank || s.b_q != 1))
+        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: paged K is built for decode from device memory only");
     a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
@@ -513,8 +515,8 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (max_chunks == 0 || P == 0) return IHIP_OK;
     if (bank && s.b_q != 1) return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: the host tier serves decode only");
-    if (fp8 && (s.b_q != 1 || bank || (rope && rope->prune_style != IHIP_ROPE_NONE)))
-        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: FP8 keys are built for plain decode from device memory only");
+    if (fp8 && (s.b_q != 1 || bank))
+        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: FP8 keys are built for decode from device memory only");
     RopeView rope_view{nullptr, nullptr, 0};
     if (rope && rope->prune_style != IHIP_ROPE_NONE) {
         if (bank)
@@ -531,7 +533,7 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
             return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope table has %d positions, %lld needed", rope->n_pos,
                         (long long)need);
         rope_view = RopeView{rope->cos, rope->sin, rope->n_pos};
-        if (s.b_q == 1) return launch_prune_stage_rope(a, rope_view, style, P, st);
+        if (s.b_q == 1) return launch_prune_stage_rope(a, rope_view, style, P, fp8, st);
     }
     const RopeView *rv = rope_view.cos ? &rope_view : nullptr;
     if (s.b_q == 1) {

@@ -18,7 +18,11 @@
 //                        min(its own position, n_chunk - 1 + n_stream): one
 //                        rotated copy of q per chunk, R(qpos - j) q, and the
 //                        carried-score search of the plain kernel.
+// SRC 0: K through strides, 2: paged pool (one block-table lookup per row read); KV8: rows are 128
+// bytes of E4M3, the scores are multiplied by the K scale at the end (a positive factor: the
+// searches do not depend on it).
 #include "prune_args.h"
+#include <type_traits>
 
 namespace ihip {
 
@@ -35,9 +39,11 @@ __device__ inline void rotate8(const float (&x)[8], const RopeView &rope, int po
     }
 }
 
-template <int G, int U, int STYLE>   // STYLE 1: relative, 2: chunk-indexed
+template <int G, int U, int STYLE, int SRC, bool KV8>   // STYLE 1: relative, 2: chunk-indexed
 __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs a, const RopeView rope)
 {
+    using piece_t = typename std::conditional<KV8, uint2, uint4>::type;     // a lane's share of a row
+    constexpr int kLaneOff = KV8 ? 4 : 8;                                   // in 2-byte units
     const int p = blockIdx.y;
     const Problem pr = problem_of(a.ge, p);
     const int l16 = threadIdx.x & 15;
@@ -75,8 +81,8 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
 #pragma unroll
         for (int h = 0; h < G; ++h) unpack8(load_row16(qb, h * a.q_sh, l16), qf[h]);
     }
-    const DirectRows src = KeySource<0>::make(a, pr);
-    auto load_row = [&](int pos) { return *reinterpret_cast<const uint4 *>(src.row(pos, false) + l16 * 8); };
+    const typename KeySource<SRC>::type src = KeySource<SRC>::make(a, pr);
+    auto load_row = [&](int pos) { return *reinterpret_cast<const piece_t *>(src.row(pos, false) + l16 * kLaneOff); };
 
     int start[U], len[U];
     bool valid[U];
@@ -103,12 +109,12 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
         float sL[U][G];      // the current left key against q_L; score[][] holds it against q_R
         {
             // first key of the chunk and of its right half: common to all heads
-            uint4 r0[U], r1[U];
+            piece_t r0[U], r1[U];
             const int mid = a.chunk >> 1;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                r0[u] = make_uint4(0, 0, 0, 0);
-                r1[u] = make_uint4(0, 0, 0, 0);
+                r0[u] = piece_t{};
+                r1[u] = piece_t{};
                 if (valid[u]) r0[u] = load_row(start[u]);
                 if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid);
             }
@@ -126,7 +132,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
             }
         }
         for (int half = a.chunk >> 2; half >= 1; half >>= 1) {
-            uint4 r[U][G];
+            piece_t r[U][G];
             bool ok[U][G];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
                 for (int h = 0; h < G; ++h) {
                     const int mid = off[u][h] + half;
                     ok[u][h] = mid < len[u];
-                    r[u][h] = make_uint4(0, 0, 0, 0);
+                    r[u][h] = piece_t{};
                     if (ok[u][h]) r[u][h] = load_row(start[u] + mid);
                 }
             }
@@ -162,12 +168,12 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
             for (int h = 0; h < G; ++h) rotate8(qf[h], rope, delta, l16, qr[u][h]);
         }
         {
-            uint4 r0[U], r1[U];
+            piece_t r0[U], r1[U];
             const int mid = a.chunk >> 1;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                r0[u] = make_uint4(0, 0, 0, 0);
-                r1[u] = make_uint4(0, 0, 0, 0);
+                r0[u] = piece_t{};
+                r1[u] = piece_t{};
                 if (valid[u]) r0[u] = load_row(start[u]);
                 if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid);
             }
@@ -184,7 +190,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
             }
         }
         for (int half = a.chunk >> 2; half >= 1; half >>= 1) {
-            uint4 r[U][G];
+            piece_t r[U][G];
             bool ok[U][G];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
                 for (int h = 0; h < G; ++h) {
                     const int mid = off[u][h] + half;
                     ok[u][h] = mid < len[u];
-                    r[u][h] = make_uint4(0, 0, 0, 0);
+                    r[u][h] = piece_t{};
                     if (ok[u][h]) r[u][h] = load_row(start[u] + mid);
                 }
             }
@@ -217,6 +223,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
         float best = score[u][0];
 #pragma unroll
         for (int h = 1; h < G; ++h) best = fmaxf(best, score[u][h]);
+        if (KV8) best *= a.k_scale;
         if (l16 == 0) a.out_scores[(int64_t)p * a.max_chunks + j] = valid[u] ? best : -INFINITY;
         if (a.out_rep != nullptr && l16 < G) {
             int o = off[u][0];
@@ -228,23 +235,33 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
     }
 }
 
-template <int G>
+template <int G, int SRC, bool KV8>
 static void launch_rope(const PruneArgs &a, const RopeView &rope, int style, int P, hipStream_t st)
 {
     constexpr int U = 2;
     dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
     KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
-    if (style == 1) hipLaunchKernelGGL((prune_decode_rope_kernel<G, U, 1>), grid, dim3(256), 0, st, a, rope);
-    else hipLaunchKernelGGL((prune_decode_rope_kernel<G, U, 2>), grid, dim3(256), 0, st, a, rope);
+    if (style == 1) hipLaunchKernelGGL((prune_decode_rope_kernel<G, U, 1, SRC, KV8>), grid, dim3(256), 0, st, a, rope);
+    else hipLaunchKernelGGL((prune_decode_rope_kernel<G, U, 2, SRC, KV8>), grid, dim3(256), 0, st, a, rope);
 }
 
-int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, hipStream_t st)
+template <int G>
+static void launch_rope_g(const PruneArgs &a, const RopeView &rope, int style, int P, bool fp8, hipStream_t st)
+{
+    const bool paged = a.paged.block_table != nullptr;
+    if (paged && fp8) launch_rope<G, 2, true>(a, rope, style, P, st);
+    else if (paged) launch_rope<G, 2, false>(a, rope, style, P, st);
+    else if (fp8) launch_rope<G, 0, true>(a, rope, style, P, st);
+    else launch_rope<G, 0, false>(a, rope, style, P, st);
+}
+
+int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, bool fp8, hipStream_t st)
 {
     switch (a.ge.G) {
-    case 1: launch_rope<1>(a, rope, style, P, st); break;
-    case 2: launch_rope<2>(a, rope, style, P, st); break;
-    case 4: launch_rope<4>(a, rope, style, P, st); break;
-    case 8: launch_rope<8>(a, rope, style, P, st); break;
+    case 1: launch_rope_g<1>(a, rope, style, P, fp8, st); break;
+    case 2: launch_rope_g<2>(a, rope, style, P, fp8, st); break;
+    case 4: launch_rope_g<4>(a, rope, style, P, fp8, st); break;
+    case 8: launch_rope_g<8>(a, rope, style, P, fp8, st); break;
     default: return fail(IHIP_ERR_UNSUPPORTED, "Hq/Hkv = %d not in {1,2,4,8}", a.ge.G);
     }
     return check_launch("prune_stage (decode, dynamic RoPE)");

@@ -381,8 +381,8 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     a.v_scale = fp8 ? fmt->v_scale : 1.0f;
     a.paged = (fmt && fmt->paged.block_table) ? fmt->paged : PagedView{nullptr, 0, 0};
     const bool paged = a.paged.block_table != nullptr;
-    if (paged && (fp8 || bank || (rope && rope->attn_style != IHIP_ROPE_NONE)))
-        return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: paged K/V is built for plain bf16 decode only");
+    if (paged && bank)
+        return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: paged K/V and the host tier exclude each other");
     const bool use_rope = rope && rope->attn_style != IHIP_ROPE_NONE;
     a.rope_cos = a.rope_sin = nullptr;
     if (use_rope) {
@@ -403,8 +403,8 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
     a.v = (const uint16_t *)v.ptr; a.v_sb = v.stride_b; a.v_sh = v.stride_h; a.v_st = v.stride_t;
     if (fp8) {
-        if (bank || use_rope)
-            return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: FP8 K/V is built for plain decode from device memory only");
+        if (bank)
+            return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: FP8 K/V is built for decode from device memory only");
         a.k_sb /= 2; a.k_sh /= 2; a.k_st /= 2;      // byte strides (even) in 2-byte units
         a.v_sb /= 2; a.v_sh /= 2; a.v_st /= 2;
     }
@@ -425,17 +425,24 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     {
     KernelTimer timer("attn_decode_split", st);
     switch (G) {
+#define IHIP_AD_KERNEL(GG, SRCV, RV, F8V)                                                                           \
+    hipLaunchKernelGGL((attn_decode_split_kernel<GG, SRCV, RV, F8V>), grid, dim3(kAttnThreads), 0, st, a)
+#define IHIP_AD_BY_FMT(GG, SRCV)                                                                                    \
+    if (use_rope && fp8) IHIP_AD_KERNEL(GG, SRCV, true, true);                                                      \
+    else if (use_rope) IHIP_AD_KERNEL(GG, SRCV, true, false);                                                       \
+    else if (fp8) IHIP_AD_KERNEL(GG, SRCV, false, true);                                                            \
+    else IHIP_AD_KERNEL(GG, SRCV, false, false)
 #define IHIP_AD_LAUNCH(GG)                                                                                          \
-    if (fp8) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 0, false, true>), grid, dim3(kAttnThreads), 0, st, a);          \
-    else if (use_rope) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 0, true, false>), grid, dim3(kAttnThreads), 0, st, a); \
-    else if (paged) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 2, false, false>), grid, dim3(kAttnThreads), 0, st, a);   \
-    else if (bank) hipLaunchKernelGGL((attn_decode_split_kernel<GG, 1, false, false>), grid, dim3(kAttnThreads), 0, st, a);    \
-    else hipLaunchKernelGGL((attn_decode_split_kernel<GG, 0, false, false>), grid, dim3(kAttnThreads), 0, st, a)
+    if (bank) IHIP_AD_KERNEL(GG, 1, false, false);                                                                  \
+    else if (paged) { IHIP_AD_BY_FMT(GG, 2); }                                                                      \
+    else { IHIP_AD_BY_FMT(GG, 0); }
     case 1: IHIP_AD_LAUNCH(1); break;
     case 2: IHIP_AD_LAUNCH(2); break;
     case 4: IHIP_AD_LAUNCH(4); break;
     case 8: IHIP_AD_LAUNCH(8); break;
 #undef IHIP_AD_LAUNCH
+#undef IHIP_AD_BY_FMT
+#undef IHIP_AD_KERNEL
     default: return fail(IHIP_ERR_UNSUPPORTED, "Hq/Hkv = %d not in {1,2,4,8}", G);
     }
     }

@@ -101,5 +101,18 @@ def test_argument_checks_of_the_variants_need_no_gpu(built_lib):
     assert L.ihip_prune_stage_paged(ctypes.byref(s), t, t, ctypes.byref(pg), None, 0, 0, 64, slots, 256, None, None) == -1
     pg = PagedStruct(256, 100, 16)                           # covers 1600 < 4096 tokens
     assert L.ihip_prune_stage_paged(ctypes.byref(s), t, t, ctypes.byref(pg), None, 0, 0, 64, slots, 256, None, None) == -1
+    # the combined entry point: NULL options, bad scales, a stage offset without state, host tier + pages
+    from paper_2502_08910_amd.binding import DecodeOptions
+    i32 = (ctypes.c_int32 * 1)
+    ex = lambda opt: L.ihip_decode_layer_ex(ctypes.byref(s), t, t, t, 1, i32(64), i32(8), f(0.1), opt, 256, None,  # noqa: E731
+                                            None, 256, 1 << 30, None)
+    assert ex(None) == -1
+    o = DecodeOptions(); o.kv_fp8, o.k_scale, o.v_scale = 1, -1.0, 1.0
+    assert ex(ctypes.byref(o)) == -1
+    o = DecodeOptions(); o.first_stage = 1
+    assert ex(ctypes.byref(o)) == -1
+    assert b"first_stage" in L.ihip_last_error()
+    o = DecodeOptions(); o.pooling = 9
+    assert ex(ctypes.byref(o)) == -1
     # pooling rule
     assert L.ihip_select_blocks_pooled(ctypes.byref(s), 256, slots, None, 0, 0, 64, 8, 5, 256, None) == -1
