@@ -187,7 +187,7 @@ def bench_decode(args, w, torch, ihip, configs):
         torch.cuda.empty_cache()
     paged = None
     if args.paged:
-        assert n_layers == 1 and kv_scales is None, "paged: one bf16 layer"
+        assert n_layers == 1, "paged: one layer"
         page = args.paged
         per_seq = (w.T + page - 1) // page
         assert per_seq * page == w.T, "context must be a whole number of pages"
@@ -198,7 +198,7 @@ def bench_decode(args, w, torch, ihip, configs):
         else:
             order = torch.arange(w.B * per_seq, device=dev).view(w.B, per_seq)
         kb, vb = kvs[0]
-        k_pool = torch.empty((w.B * per_seq, w.Hkv, page, w.d), dtype=torch.bfloat16, device=dev)
+        k_pool = torch.empty((w.B * per_seq, w.Hkv, page, w.d), dtype=kb.dtype, device=dev)
         v_pool = torch.empty_like(k_pool)
         for b in range(w.B):
             k_pool[order[b]] = kb[b].view(w.Hkv, per_seq, page, w.d).permute(1, 0, 2, 3)
@@ -225,34 +225,26 @@ def bench_decode(args, w, torch, ihip, configs):
     L = ihip.Layer(qs[0], k, seq_lens, w.b_q, w.n_sink, w.n_stream)
     ws = L.workspace(ihip.OP_DECODE_LAYER, chunks, keeps)
     out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
-    assert not ((kv_scales or paged) and (args.refresh or args.rope)), "fp8 / paged K/V: plain decode layer only"
-
-    refresh = None
-    if args.refresh:
-        refresh = [int(x) for x in args.refresh.split(",")]
-        assert len(refresh) == len(chunks), "one refresh interval per stage"
-        state = L.mask_state(keeps)
-
-        assert n_layers == 1, "mask caching follows one layer's decode steps"
-
-        def step(i):
-            L.decode_layer_masked(qs[i % N_QUERY_SETS], k, v, chunks, keeps, ihip.first_stage_due(i, refresh),
-                                  state, ws=ws, out=out)
-    elif args.rope:
+    # any combination of the variants goes through the one call (ihip_decode_layer_ex underneath)
+    rope = None
+    if args.rope:
         from workloads import gen
         n_pos = max(L.stage1_slots(chunks[0]), max(keeps)) + w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8
         cos, sin = gen.rope_table(n_pos, w.d, device=dev)
         rope = ihip.Rope(cos, sin, ihip.ROPE_RELATIVE if args.rope == "relative" else ihip.ROPE_CHUNK_INDEXED,
                          ihip.ROPE_STREAMING)
+    refresh = state = None
+    if args.refresh:
+        refresh = [int(x) for x in args.refresh.split(",")]
+        assert len(refresh) == len(chunks), "one refresh interval per stage"
+        assert n_layers == 1, "mask caching follows one layer's decode steps"
+        state = L.mask_state(keeps)
 
-        def step(i):
-            kl, vl = kvs[i % n_layers]
-            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out, rope=rope)
-    else:
-        def step(i):
-            kl, vl = kvs[i % n_layers]
-            L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out, kv_scales=kv_scales,
-                           paged=paged)
+    def step(i):
+        kl, vl = kvs[i % n_layers]
+        L.decode_layer(qs[i % N_QUERY_SETS], kl, vl, chunks, keeps, ws=ws, out=out, rope=rope, kv_scales=kv_scales,
+                       paged=paged, stage_starts=state,
+                       first_stage=ihip.first_stage_due(i, refresh) if refresh else None)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 

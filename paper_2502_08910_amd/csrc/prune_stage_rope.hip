@@ -18,7 +18,7 @@
 //                        min(its own position, n_chunk - 1 + n_stream): one
 //                        rotated copy of q per chunk, R(qpos - j) q, and the
 //                        carried-score search of the plain kernel.
-// SRC 0: K through strides, 2: paged pool (one block-table lookup per row read); KV8: rows are 128
+// SRC 0: K through strides, 2: paged pool; KV8: rows are 128
 // bytes of E4M3, the scores are multiplied by the K scale at the end (a positive factor: the
 // searches do not depend on it).
 #include "prune_args.h"
@@ -82,7 +82,6 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
         for (int h = 0; h < G; ++h) unpack8(load_row16(qb, h * a.q_sh, l16), qf[h]);
     }
     const typename KeySource<SRC>::type src = KeySource<SRC>::make(a, pr);
-    auto load_row = [&](int pos) { return *reinterpret_cast<const piece_t *>(src.row(pos, false) + l16 * kLaneOff); };
 
     int start[U], len[U];
     bool valid[U];
@@ -95,6 +94,36 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
         valid[u] = start[u] >= 0;
         len[u] = valid[u] ? min(a.chunk, pr.hi - start[u]) : 0;
     }
+
+    // Paged K: the page ids of a chunk's first 16 pages are fetched once, one per lane of the row
+    // group, and handed round by shuffles (all shuffles of a search level before its row loads), as
+    // in the plain kernel.
+    int page_first[U], page_ids[U];
+    if (SRC == 2) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            page_first[u] = max(start[u], 0) >> a.paged.page_log2;
+            const int e = page_first[u] + l16;
+            page_ids[u] = valid[u] && e < a.paged.table_stride
+                              ? a.paged.block_table[(int64_t)pr.b * a.paged.table_stride + e] : 0;
+        }
+    }
+    auto page_of = [&](int pos, int u) {
+        if constexpr (SRC == 2) {
+            const int idx = (pos >> a.paged.page_log2) - page_first[u];
+            int page = __shfl(page_ids[u], idx & 15, 16);
+            if (idx >= 16) page = src.table[pos >> a.paged.page_log2];      // chunk wider than 16 pages
+            return page;
+        } else {
+            return 0;
+        }
+    };
+    auto load_row = [&](int pos, int page) {
+        if constexpr (SRC == 2)
+            return *reinterpret_cast<const piece_t *>(src.row_in_page(page, pos) + l16 * kLaneOff);
+        else
+            return *reinterpret_cast<const piece_t *>(src.row(pos, false) + l16 * kLaneOff);
+    };
 
     int off[U][G];
     float score[U][G];       // what the chunk score takes from head h
@@ -115,8 +144,9 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
             for (int u = 0; u < U; ++u) {
                 r0[u] = piece_t{};
                 r1[u] = piece_t{};
-                if (valid[u]) r0[u] = load_row(start[u]);
-                if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid);
+                const int pg0 = page_of(max(start[u], 0), u), pg1 = page_of(max(start[u], 0) + mid, u);
+                if (valid[u]) r0[u] = load_row(start[u], pg0);
+                if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid, pg1);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -134,6 +164,11 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
         for (int half = a.chunk >> 2; half >= 1; half >>= 1) {
             piece_t r[U][G];
             bool ok[U][G];
+            int page[U][G];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int h = 0; h < G; ++h) page[u][h] = page_of(max(start[u], 0) + off[u][h] + half, u);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -141,7 +176,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
                     const int mid = off[u][h] + half;
                     ok[u][h] = mid < len[u];
                     r[u][h] = piece_t{};
-                    if (ok[u][h]) r[u][h] = load_row(start[u] + mid);
+                    if (ok[u][h]) r[u][h] = load_row(start[u] + mid, page[u][h]);
                 }
             }
 #pragma unroll
@@ -174,8 +209,9 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
             for (int u = 0; u < U; ++u) {
                 r0[u] = piece_t{};
                 r1[u] = piece_t{};
-                if (valid[u]) r0[u] = load_row(start[u]);
-                if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid);
+                const int pg0 = page_of(max(start[u], 0), u), pg1 = page_of(max(start[u], 0) + mid, u);
+                if (valid[u]) r0[u] = load_row(start[u], pg0);
+                if (mid >= 1 && mid < len[u]) r1[u] = load_row(start[u] + mid, pg1);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -192,6 +228,11 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
         for (int half = a.chunk >> 2; half >= 1; half >>= 1) {
             piece_t r[U][G];
             bool ok[U][G];
+            int page[U][G];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int h = 0; h < G; ++h) page[u][h] = page_of(max(start[u], 0) + off[u][h] + half, u);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -199,7 +240,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
                     const int mid = off[u][h] + half;
                     ok[u][h] = mid < len[u];
                     r[u][h] = piece_t{};
-                    if (ok[u][h]) r[u][h] = load_row(start[u] + mid);
+                    if (ok[u][h]) r[u][h] = load_row(start[u] + mid, page[u][h]);
                 }
             }
 #pragma unroll
