@@ -318,8 +318,26 @@ def bench_prefill(args, w, torch, ihip, configs):
         cos, sin = gen.rope_table(w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8, w.d, device=dev)
         rope = ihip.Rope(cos, sin, ihip.ROPE_RELATIVE, ihip.ROPE_STREAMING)
 
+    paged = None
+    if args.paged:
+        page = args.paged
+        per_seq = (w.T + page - 1) // page
+        assert per_seq * page == w.T, "context must be a whole number of pages"
+        gen_ = torch.Generator(device=dev)
+        gen_.manual_seed(1234)
+        if args.paged_order == "random":
+            order = torch.randperm(w.B * per_seq, generator=gen_, device=dev).view(w.B, per_seq)
+        else:
+            order = torch.arange(w.B * per_seq, device=dev).view(w.B, per_seq)
+        k_pool = torch.empty((w.B * per_seq, w.Hkv, page, w.d), dtype=k.dtype, device=dev)
+        v_pool = torch.empty_like(k_pool)
+        for b in range(w.B):
+            k_pool[order[b]] = k[b].view(w.Hkv, per_seq, page, w.d).permute(1, 0, 2, 3)
+            v_pool[order[b]] = v[b].view(w.Hkv, per_seq, page, w.d).permute(1, 0, 2, 3)
+        paged = ihip.PagedKV(k_pool, v_pool, order.to(torch.int32).contiguous())
+
     def step(i):
-        L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out, rope=rope)
+        L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out, rope=rope, paged=paged)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
 
@@ -364,7 +382,7 @@ def bench_prefill(args, w, torch, ihip, configs):
         ach = kernels[dom]["TFLOPs"]
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": None if rope else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "traffic": None if rope or paged else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                     "flops_per_launch": flops[dom], "us_per_launch": kernels[dom]["us"],
                     "measured_mfma_rate": measured[dom.split(".")[0]],
                     "frac_of_measured_mfma_rate": ach / measured[dom.split(".")[0]]}
@@ -390,7 +408,8 @@ def bench_prefill(args, w, torch, ihip, configs):
     return {
         "metric": "sparse_attn_prefill_us_per_layer",
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
-        "config": {"workload": w.name + ("_dynamic_rope_relative" if rope else ""), "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
+        "config": {"workload": w.name + ("_dynamic_rope_relative" if rope else "")
+                   + (f"_paged{args.paged}_{args.paged_order}" if paged else ""), "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
                    "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink, "n_stream": w.n_stream},
         "roofline": roofline, "cpu_baseline": cpu,

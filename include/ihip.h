@@ -166,7 +166,8 @@ int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_ten
  * entries beyond a sequence's length are never read.  page_tokens is a power
  * of two and table_stride * page_tokens >= max_seq_len.  Everything else as in
  * the entry points of the same names without the suffix.  Built for decode
- * (Tq == b_q == 1), bf16.
+ * and chunked prefill from bf16 pools; FP8 pools (decode only) and the other
+ * variants combine through ihip_decode_layer_ex / ihip_prefill_layer_ex.
  */
 typedef struct ihip_paged_kv {
     const int32_t *block_table;
@@ -280,6 +281,13 @@ int32_t ihip_sparse_attn_prefill_rope(const ihip_shape *shape, ihip_tensor q, ih
                                       float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
                                       void *ws, size_t ws_bytes, void *stream);
 
+/* ihip_sparse_attn_prefill reading K and V from page pools (see ihip_paged_kv); rope may be NULL. */
+int32_t ihip_sparse_attn_prefill_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
+                                       ihip_tensor v_pool, const ihip_paged_kv *paged,
+                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                       float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                       void *ws, size_t ws_bytes, void *stream);
+
 /*
  * One decode layer call: ihip_prune_all followed by ihip_sparse_attn_decode
  * (Alg. 4 with every stage refreshed at every step).  out / out_lse as in
@@ -309,6 +317,22 @@ int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_ten
                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                                 float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
                                 int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The prefill layer with the variants in any combination: dynamic RoPE
+ * (relative style in the pruning stages, streaming style in the attention),
+ * paged K/V (k and v are then the page pools) and the pooling rule.
+ * Zero-initialise the struct: every zero field means "off".
+ */
+typedef struct ihip_prefill_options {
+    const ihip_rope *rope;
+    const ihip_paged_kv *paged;
+    int32_t pooling;
+} ihip_prefill_options;
+int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                              int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                              float sm_scale, const ihip_prefill_options *opt, void *out, float *out_lse,
+                              int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Decode layer with per-stage mask caching (Sec. 4 "Sparse Attention Mask

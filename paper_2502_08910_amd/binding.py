@@ -47,6 +47,10 @@ EXPORTS = {
                                        vp, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer_ex": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
                                      vp, vp, vp, vp, c_sz, vp]),
+    "ihip_sparse_attn_prefill_paged": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, vp, c_i32, c_i32,
+                                               c_f, vp, vp, vp, vp, c_sz, vp]),
+    "ihip_prefill_layer_ex": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
+                                      vp, vp, vp, vp, c_sz, vp]),
     "ihip_sparse_attn_prefill_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
                                               c_f, vp, vp, vp, vp, c_sz, vp]),
     "ihip_prefill_layer_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
@@ -224,6 +228,11 @@ class DecodeOptions(ctypes.Structure):
                 ("pooling", c_i32), ("first_stage", c_i32), ("stage_starts", vp)]
 
 
+class PrefillOptions(ctypes.Structure):
+    """ihip_prefill_options (all zero = the plain prefill layer)."""
+    _fields_ = [("rope", vp), ("paged", vp), ("pooling", c_i32)]
+
+
 class Layer:
     """Shape of one attention call plus the device seq_lens; the methods are
     the C entry points of the same names."""
@@ -355,7 +364,14 @@ class Layer:
                           sm_scale, want_lse, ws)
 
     def sparse_attn_prefill(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None,
-                            rope: Optional["Rope"] = None):
+                            rope: Optional["Rope"] = None, paged: Optional["PagedKV"] = None):
+        if paged is not None:
+            def fn(shape, tq, tk, tv, bs, n_blocks, blk, scale, out, lse, w, w_bytes, stream):
+                return lib().ihip_sparse_attn_prefill_paged(shape, tq, tk, tv, paged.ref(), bs, n_blocks, blk, scale,
+                                                            rope.ref() if rope is not None else None, out, lse, w,
+                                                            w_bytes, stream)
+            return self._attn(fn, OP_ATTN_PREFILL, q, paged.k_pool, paged.v_pool, block_starts, block, sm_scale,
+                              want_lse, ws)
         if rope is not None:
             def fn(shape, tq, tk, tv, bs, n_blocks, blk, scale, out, lse, w, w_bytes, stream):
                 return lib().ihip_sparse_attn_prefill_rope(shape, tq, tk, tv, bs, n_blocks, blk, scale, rope.ref(),
@@ -470,13 +486,28 @@ class Layer:
         return out
 
     def prefill_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
-                      out_blocks=None, lse=None, pooling: Optional[int] = None, rope: Optional["Rope"] = None):
-        """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d]."""
+                      out_blocks=None, lse=None, pooling: Optional[int] = None, rope: Optional["Rope"] = None,
+                      paged: Optional["PagedKV"] = None):
+        """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d].
+        paged: k and v are ignored.  One variant alone goes to its own entry point, paged K/V and
+        combinations to ihip_prefill_layer_ex."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, self.Tq, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_PREFILL_LAYER, chunk_sizes, keeps)
+        if paged is not None or (pooling is not None and rope is not None):
+            opt = PrefillOptions()
+            opt.rope = ctypes.cast(rope.ref(), vp) if rope is not None else None
+            opt.paged = ctypes.cast(paged.ref(), vp) if paged is not None else None
+            opt.pooling = POOL_KV_HEAD if pooling is None else pooling
+            tk, tv = (_tensor(paged.k_pool, "k_pool"), _tensor(paged.v_pool, "v_pool")) if paged is not None \
+                else (_tensor(k, "k"), _tensor(v, "v"))
+            _check(lib().ihip_prefill_layer_ex(ctypes.byref(self.shape), _tensor(q, "q"), tk, tv, len(chunk_sizes),
+                                               _i32(chunk_sizes), _i32(keeps), sm_scale, ctypes.byref(opt),
+                                               _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws), ws.numel(),
+                                               _stream()))
+            return out
         if pooling is not None:
             _check(lib().ihip_prefill_layer_pooled(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
                                                    _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),

@@ -86,7 +86,7 @@ void cache_describe(const ihip_cache *, int32_t *, int32_t *, int64_t *, ihip_te
 size_t attn_decode_workspace(const ihip_shape &, int, int);
 int32_t launch_attn_prefill(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                             const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
-                            const ihip_rope *, hipStream_t);
+                            const ihip_rope *, hipStream_t, const KvFormat * = nullptr);
 
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
@@ -436,7 +436,7 @@ int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihi
                              sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
-static int32_t attn_prefill_entry(const char *who, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q,
+static int32_t attn_prefill_entry(const char *who, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q,
                                   ihip_tensor k, ihip_tensor v, const int32_t *block_starts, int32_t n_blocks,
                                   int32_t block, float sm_scale, void *out, float *out_lse, void *ws,
                                   size_t ws_bytes, void *stream)
@@ -453,14 +453,26 @@ static int32_t attn_prefill_entry(const char *who, const ihip_rope *rope, const 
     if (n_blocks > 0 && !block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: block_starts is NULL", who);
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
     return launch_attn_prefill(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, rope,
-                               (hipStream_t)stream);
+                               (hipStream_t)stream, fmt);
+}
+
+int32_t ihip_sparse_attn_prefill_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, ihip_tensor v_pool,
+                                       const ihip_paged_kv *paged, const int32_t *block_starts, int32_t n_blocks,
+                                       int32_t block, float sm_scale, const ihip_rope *rope, void *out,
+                                       float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    KvFormat fmt;
+    const int32_t rc = check_paged("ihip_sparse_attn_prefill_paged", shape, paged, &fmt);
+    if (rc != IHIP_OK) return rc;
+    return attn_prefill_entry("ihip_sparse_attn_prefill_paged", rope, &fmt, shape, q, k_pool, v_pool, block_starts,
+                              n_blocks, block, sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
 int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                  const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
                                  void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
 {
-    return attn_prefill_entry("ihip_sparse_attn_prefill", nullptr, shape, q, k, v, block_starts, n_blocks, block,
+    return attn_prefill_entry("ihip_sparse_attn_prefill", nullptr, nullptr, shape, q, k, v, block_starts, n_blocks, block,
                               sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
@@ -470,7 +482,7 @@ int32_t ihip_sparse_attn_prefill_rope(const ihip_shape *shape, ihip_tensor q, ih
                                       void *stream)
 {
     if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_sparse_attn_prefill_rope: rope is NULL");
-    return attn_prefill_entry("ihip_sparse_attn_prefill_rope", rope, shape, q, k, v, block_starts, n_blocks, block,
+    return attn_prefill_entry("ihip_sparse_attn_prefill_rope", rope, nullptr, shape, q, k, v, block_starts, n_blocks, block,
                               sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
@@ -675,7 +687,7 @@ int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor
                              out_block_starts, ws, ws_bytes, stream, opt->first_stage, opt->stage_starts);
 }
 
-static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_rope *rope, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
                            const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                            float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
@@ -698,17 +710,17 @@ static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_ro
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
     rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, rope, all_heads,
-                        (hipStream_t)stream);
+                        (hipStream_t)stream, fmt);
     if (rc != IHIP_OK) return rc;
     return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse, rope,
-                               (hipStream_t)stream);
+                               (hipStream_t)stream, fmt);
 }
 
 int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
                            const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                            float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
 {
-    return prefill_layer_impl("ihip_prefill_layer", false, nullptr, shape, q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out,
+    return prefill_layer_impl("ihip_prefill_layer", false, nullptr, nullptr, shape, q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out,
                               out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -719,7 +731,7 @@ int32_t ihip_prefill_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_t
 {
     const int32_t rc = check_pooling("ihip_prefill_layer_pooled", pooling);
     if (rc != IHIP_OK) return rc;
-    return prefill_layer_impl("ihip_prefill_layer_pooled", pooling == IHIP_POOL_ALL_HEADS, nullptr, shape, q, k, v, n_stages,
+    return prefill_layer_impl("ihip_prefill_layer_pooled", pooling == IHIP_POOL_ALL_HEADS, nullptr, nullptr, shape, q, k, v, n_stages,
                               chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
@@ -729,8 +741,24 @@ int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_ten
                                 void *ws, size_t ws_bytes, void *stream)
 {
     if (!rope) return fail(IHIP_ERR_INVALID_ARG, "ihip_prefill_layer_rope: rope is NULL");
-    return prefill_layer_impl("ihip_prefill_layer_rope", false, rope, shape, q, k, v, n_stages, chunk_sizes, keeps,
+    return prefill_layer_impl("ihip_prefill_layer_rope", false, rope, nullptr, shape, q, k, v, n_stages, chunk_sizes, keeps,
                               sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
+}
+
+int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
+                              const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale,
+                              const ihip_prefill_options *opt, void *out, float *out_lse, int32_t *out_block_starts,
+                              void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_prefill_layer_ex";
+    if (!opt) return fail(IHIP_ERR_INVALID_ARG, "%s: options are NULL", who);
+    int32_t rc;
+    KvFormat fmt{false, 1.0f, 1.0f, PagedView{nullptr, 0, 0}};
+    if (opt->paged && (rc = check_paged(who, shape, opt->paged, &fmt)) != IHIP_OK) return rc;
+    if ((rc = check_pooling(who, opt->pooling)) != IHIP_OK) return rc;
+    return prefill_layer_impl(who, opt->pooling == IHIP_POOL_ALL_HEADS, opt->rope, opt->paged ? &fmt : nullptr, shape,
+                              q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws,
+                              ws_bytes, stream);
 }
 
 int32_t ihip_profile_enable(int32_t on)

@@ -24,6 +24,8 @@ struct AttnPrefillArgs {
     uint16_t *out;       // bf16 [B, Hq, Tq, d]
     float *out_lse;      // [B, Hq, Tq] or null
     const float *rope_cos, *rope_sin;   // streaming-style RoPE instantiations only: fp32 [n_pos][d/2]
+    PagedView paged;                    // paged instantiations only: k / v are the page pools, k_sb / v_sb
+                                        // the page strides
 };
 
 // Streaming-style positions (Sec. 4 "Dynamic RoPE for OOL generalization"): the keys a query
@@ -80,6 +82,8 @@ __device__ inline int pf_slot_to_pos(const AttnPrefillArgs &a, const Problem &pr
 constexpr int kPf32MaxLds = 160 * 1024;  // LDS per workgroup the 32x32 kernel may ask for
 constexpr int kPf32MaxSlots = 24320;    // key slots whose positions (and per-tile flags) the 32x32 kernel keeps in LDS
 constexpr int kPf32MaxSlotsRope = 20224; // ... with streaming-style RoPE (one more K/V stage)
+constexpr int kPf32MaxSlotsPaged = 12160;     // ... with paged K/V (a page id per slot as well)
+constexpr int kPf32MaxSlotsRopePaged = 10176; // ... with both
 
 void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len, hipStream_t st);
 

@@ -189,11 +189,15 @@ __device__ inline bf16x8 rotate_operand(const bf16x8 x, const float *cos4, const
     return __builtin_bit_cast(bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, x), cos4, sin4));
 }
 
-template <int MT, int NT, int G, bool WIDE, bool ROPE>
+// PAGED: K is a page pool read through the sequence's row of the block table: the lane that owns a
+// candidate looks its page up and forms the row's element offset (64-bit) before the offsets are
+// handed to the loading lanes, so a level costs one more dependent (cache-resident) load.
+template <int MT, int NT, int G, bool WIDE, bool ROPE, bool PAGED>
 __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
                                                                             const RopeView rope)
 {
     static_assert(NT == 2, "the shared first phase assumes two 16-chunk tiles per wave");
+    static_assert(!PAGED || WIDE, "paged pools are addressed with 64-bit offsets");
     constexpr int kTile = NT * 16 * kD;              // one tile: 32 rows of 256 bytes, no padding
     constexpr bool kShare = G >= 2;                  // two tiles are needed for the shared phase
     __shared__ float sh_sigma[G][NT * 16];
@@ -227,6 +231,11 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     auto load4 = [&](const uint16_t *base, off_t stride, uint32_t dst, int row, int swz) {
         const off_t r = (off_t)max(row, 0);
         const off_t at = WIDE ? r * stride : (off_t)__umul24((uint32_t)r, (uint32_t)stride);
+        const uint16_t *src = base + at + ((n ^ swz) << 3);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+    };
+    // the same with the row's element offset already formed (paged K)
+    auto load4_at = [&](const uint16_t *base, int64_t at, uint32_t dst, int swz) {
         const uint16_t *src = base + at + ((n ^ swz) << 3);
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
     };
@@ -272,7 +281,14 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
         }
     }
     if (kShare) __syncthreads();                     // other waves' tiles are written below
-    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+    const uint16_t *kb = PAGED ? a.k + pr.g * a.k_sh : a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+    const int32_t *table = PAGED ? a.paged.block_table + (int64_t)pr.b * a.paged.table_stride : nullptr;
+    const int page_mask = PAGED ? (1 << a.paged.page_log2) - 1 : 0;
+    // paged K: element offset of row `pos` from kb (a row of -1 stands for row 0, as in load4)
+    auto paged_at = [&](int pos) {
+        const int r = max(pos, 0);
+        return (int64_t)table[r >> a.paged.page_log2] * a.k_sb + (int64_t)(r & page_mask) * a.k_st;
+    };
 
     // scores of the 32 rows of a tile (column n of 16-row tile t): max over the block's queries
     // (ROPE: sig against q_L, sigR against q_R)
@@ -313,13 +329,23 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     // score of candidate rows pos[t] of this wave's own searches.  The scores of columns whose
     // search has ended are ignored by the caller.
     auto score = [&](const int (&pos)[NT], const bool (&ok)[NT], float (&sig)[NT], float (&sigR)[NT]) {
-        int cand[NT * 4];
+        if constexpr (PAGED) {
+            int64_t at[NT], cand_at[NT * 4];
 #pragma unroll
-        for (int r = 0; r < NT * 4; ++r)     // lanes 0..15 hold column = lane
-            cand[r] = __shfl(ok[r >> 2] ? pos[r >> 2] : -1, (r & 3) * 4 + kq, 64);
+            for (int t = 0; t < NT; ++t) at[t] = paged_at(ok[t] ? pos[t] : -1);
 #pragma unroll
-        for (int r = 0; r < NT * 4; ++r)     // tile row r*4 + kq = candidate (t = r/4, column (r%4)*4 + kq)
-            load4(kb, k_st, dst_own[r], cand[r], (r & 3) * 4 + kq);
+            for (int r = 0; r < NT * 4; ++r) cand_at[r] = __shfl(at[r >> 2], (r & 3) * 4 + kq, 64);
+#pragma unroll
+            for (int r = 0; r < NT * 4; ++r) load4_at(kb, cand_at[r], dst_own[r], (r & 3) * 4 + kq);
+        } else {
+            int cand[NT * 4];
+#pragma unroll
+            for (int r = 0; r < NT * 4; ++r)     // lanes 0..15 hold column = lane
+                cand[r] = __shfl(ok[r >> 2] ? pos[r >> 2] : -1, (r & 3) * 4 + kq, 64);
+#pragma unroll
+            for (int r = 0; r < NT * 4; ++r)     // tile row r*4 + kq = candidate (t = r/4, column (r%4)*4 + kq)
+                load4(kb, k_st, dst_own[r], cand[r], (r & 3) * 4 + kq);
+        }
         // the loads count on vmcnt; the wave reads its own tile, so no barrier is needed
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         mfma_scores(tile, sig, sigR);
@@ -354,18 +380,21 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
             // wave scores both tiles against its own queries.
             constexpr int kPerWave = 16 / G;
             int cand[kPerWave];
+            int64_t cand_at[PAGED ? kPerWave : 1];
 #pragma unroll
             for (int i = 0; i < kPerWave; ++i) {
                 const int ld = hh * kPerWave + i;                    // wave-uniform
                 const int set = ld >> 3, r = ld & 7;
                 const int st_ = (r >> 2) ? start[1] : start[0], ln_ = (r >> 2) ? len[1] : len[0];
                 const int c = set == 0 ? st_ : (half >= 1 && half < ln_ ? st_ + half : -1);
-                cand[i] = __shfl(c, (r & 3) * 4 + kq, 64);
+                if constexpr (PAGED) cand_at[i] = __shfl(paged_at(c), (r & 3) * 4 + kq, 64);
+                else cand[i] = __shfl(c, (r & 3) * 4 + kq, 64);
             }
 #pragma unroll
             for (int i = 0; i < kPerWave; ++i) {
                 const int r = (hh * kPerWave + i) & 7;
-                load4(kb, k_st, dst_shared[i], cand[i], (r & 3) * 4 + kq);
+                if constexpr (PAGED) load4_at(kb, cand_at[i], dst_shared[i], (r & 3) * 4 + kq);
+                else load4(kb, k_st, dst_shared[i], cand[i], (r & 3) * 4 + kq);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
@@ -430,7 +459,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     }
 }
 
-template <int MT, bool WIDE, bool ROPE>
+template <int MT, bool WIDE, bool ROPE, bool PAGED>
 static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hipStream_t st)
 {
     constexpr int NT = 2;
@@ -442,10 +471,10 @@ static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hi
     dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
     KernelTimer timer(stage_name(kNamePrunePrefill, a.parent_starts == nullptr, a.chunk), st);
     switch (a.ge.G) {
-    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE, ROPE>), grid, dim3(64), 0, st, a, iters, rope); break;
-    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE, ROPE>), grid, dim3(128), 0, st, a, iters, rope); break;
-    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE>), grid, dim3(256), 0, st, a, iters, rope); break;
-    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE, ROPE>), grid, dim3(512), 0, st, a, iters, rope); break;
+    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE, ROPE, PAGED>), grid, dim3(64), 0, st, a, iters, rope); break;
+    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE, ROPE, PAGED>), grid, dim3(128), 0, st, a, iters, rope); break;
+    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED>), grid, dim3(256), 0, st, a, iters, rope); break;
+    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE, ROPE, PAGED>), grid, dim3(512), 0, st, a, iters, rope); break;
     }
 }
 
@@ -459,13 +488,16 @@ static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, const
     const int64_t lim24 = (int64_t)1 << 24;         // narrow offsets are formed by a 24-bit multiply
     const bool wide = max_seq_len * a.k_st + kD >= lim || (int64_t)a.ge.b_q * a.q_st + kD >= lim ||
                       a.k_st < 0 || a.q_st < 0 || max_seq_len >= lim24 || a.k_st >= lim24 || a.q_st >= lim24;
-    if (rope) {
-        if (wide) launch_prefill_w<MT, true, true>(a, P, *rope, st);
-        else launch_prefill_w<MT, false, true>(a, P, *rope, st);
+    const RopeView none{nullptr, nullptr, 0};
+    if (a.paged.block_table) {
+        if (rope) launch_prefill_w<MT, true, true, true>(a, P, *rope, st);
+        else launch_prefill_w<MT, true, false, true>(a, P, none, st);
+    } else if (rope) {
+        if (wide) launch_prefill_w<MT, true, true, false>(a, P, *rope, st);
+        else launch_prefill_w<MT, false, true, false>(a, P, *rope, st);
     } else {
-        const RopeView none{nullptr, nullptr, 0};
-        if (wide) launch_prefill_w<MT, true, false>(a, P, none, st);
-        else launch_prefill_w<MT, false, false>(a, P, none, st);
+        if (wide) launch_prefill_w<MT, true, false, false>(a, P, none, st);
+        else launch_prefill_w<MT, false, false, false>(a, P, none, st);
     }
 }
 
@@ -498,8 +530,8 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     const bool fp8 = fmt && fmt->fp8;
     a.k_scale = fp8 ? fmt->k_scale : 1.0f;
     a.paged = (fmt && fmt->paged.block_table) ? fmt->paged : PagedView{nullptr, 0, 0};
-    if (a.paged.block_table && (bank || s.b_q != 1))
-        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: paged K is built for decode from device memory only");
+    if (a.paged.block_table && bank)
+        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: paged K and the host tier exclude each other");
     a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;

@@ -22,7 +22,8 @@ namespace ihip {
 
 // ROPE: streaming-style dynamic RoPE; the queries are rotated once, a K piece on its way from the
 // staging registers into LDS (its table row is fetched along with it), both rounded to bf16.
-template <int QT, int G, bool ROPE>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
+// PAGED: K and V are page pools; a piece's page is looked up in the block table right before it is fetched.
+template <int QT, int G, bool ROPE, bool PAGED>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
 __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sK[kPfTile * kPfKStride];
@@ -67,8 +68,8 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
                 }
             }
     }
-    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
-    const uint16_t *vb = a.v + pr.b * a.v_sb + pr.g * a.v_sh;
+    const uint16_t *kb = PAGED ? a.k + pr.g * a.k_sh : a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+    const uint16_t *vb = PAGED ? a.v + pr.g * a.v_sh : a.v + pr.b * a.v_sb + pr.g * a.v_sh;
 
     f32x4 o[8][QT];
     float m_run[QT], l_run[QT];
@@ -100,8 +101,15 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
                 rk[r][e] = make_uint4(0, 0, 0, 0);
                 rv[r][e] = make_uint4(0, 0, 0, 0);
                 if (pos >= 0) {
-                    rk[r][e] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos * a.k_st + c * 8);
-                    rv[r][e] = *reinterpret_cast<const uint4 *>(vb + (int64_t)pos * a.v_st + c * 8);
+                    if constexpr (PAGED) {
+                        const int64_t page = a.paged.block_table[(int64_t)pr.b * a.paged.table_stride + (pos >> a.paged.page_log2)];
+                        const int64_t tok = pos & ((1 << a.paged.page_log2) - 1);
+                        rk[r][e] = *reinterpret_cast<const uint4 *>(kb + page * a.k_sb + tok * a.k_st + c * 8);
+                        rv[r][e] = *reinterpret_cast<const uint4 *>(vb + page * a.v_sb + tok * a.v_st + c * 8);
+                    } else {
+                        rk[r][e] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos * a.k_st + c * 8);
+                        rv[r][e] = *reinterpret_cast<const uint4 *>(vb + (int64_t)pos * a.v_st + c * 8);
+                    }
                 }
                 if constexpr (ROPE) {
                     const int64_t at = (int64_t)(pos >= 0 ? ids.key(slot) : 0) * (kD / 2) + c * 4;
@@ -244,9 +252,13 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
 
 int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k,
                             const ihip_tensor &v, const int32_t *block_starts, int n_blocks, int block,
-                            float sm_scale, void *out, float *out_lse, const ihip_rope *rope, hipStream_t st)
+                            float sm_scale, void *out, float *out_lse, const ihip_rope *rope, hipStream_t st,
+                            const KvFormat *fmt)
 {
     AttnPrefillArgs a;
+    if (fmt && fmt->fp8) return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_prefill: FP8 K/V is built for decode only");
+    a.paged = (fmt && fmt->paged.block_table) ? fmt->paged : PagedView{nullptr, 0, 0};
+    const bool paged = a.paged.block_table != nullptr;
     const bool use_rope = rope && rope->attn_style != IHIP_ROPE_NONE;
     a.rope_cos = a.rope_sin = nullptr;
     if (use_rope) {
@@ -276,19 +288,22 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     if (P == 0) return IHIP_OK;
     KernelTimer timer("attn_prefill", st);
     const dim3 block_dim(64 * a.ge.G), grid(P);
-#define IHIP_PF_BY_G2(KERNEL, QT, RP)                                                              \
+#define IHIP_PF_BY_G2(KERNEL, QT, RP, PG)                                                          \
     switch (a.ge.G) {                                                                              \
-    case 1: hipLaunchKernelGGL((KERNEL<QT, 1, RP>), grid, block_dim, 0, st, a); break;             \
-    case 2: hipLaunchKernelGGL((KERNEL<QT, 2, RP>), grid, block_dim, 0, st, a); break;             \
-    case 4: hipLaunchKernelGGL((KERNEL<QT, 4, RP>), grid, block_dim, 0, st, a); break;             \
-    default: hipLaunchKernelGGL((KERNEL<QT, 8, RP>), grid, block_dim, 0, st, a); break;            \
+    case 1: hipLaunchKernelGGL((KERNEL<QT, 1, RP, PG>), grid, block_dim, 0, st, a); break;         \
+    case 2: hipLaunchKernelGGL((KERNEL<QT, 2, RP, PG>), grid, block_dim, 0, st, a); break;         \
+    case 4: hipLaunchKernelGGL((KERNEL<QT, 4, RP, PG>), grid, block_dim, 0, st, a); break;         \
+    default: hipLaunchKernelGGL((KERNEL<QT, 8, RP, PG>), grid, block_dim, 0, st, a); break;        \
     }
 #define IHIP_PF_BY_G(KERNEL, QT)                                                                   \
-    if (use_rope) { IHIP_PF_BY_G2(KERNEL, QT, true) } else { IHIP_PF_BY_G2(KERNEL, QT, false) }
+    if (use_rope && paged) { IHIP_PF_BY_G2(KERNEL, QT, true, true) }                               \
+    else if (use_rope) { IHIP_PF_BY_G2(KERNEL, QT, true, false) }                                  \
+    else if (paged) { IHIP_PF_BY_G2(KERNEL, QT, false, true) }                                     \
+    else { IHIP_PF_BY_G2(KERNEL, QT, false, false) }
     // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
-    const bool fits32 = s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= kPf32MaxSlots;
-    const bool fits32_rope = s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= kPf32MaxSlotsRope;
-    if (use_rope ? fits32_rope : fits32) {
+    const int slot_limit = use_rope ? (paged ? kPf32MaxSlotsRopePaged : kPf32MaxSlotsRope)
+                                    : (paged ? kPf32MaxSlotsPaged : kPf32MaxSlots);
+    if (s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= slot_limit) {
         launch_attn_prefill32(a, P, s.max_seq_len, st);
         return check_launch("sparse_attn_prefill");
     }

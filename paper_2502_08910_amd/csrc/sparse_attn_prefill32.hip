@@ -67,15 +67,20 @@ constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above w
 // WIDE: 64-bit row offsets; otherwise every
 // row of a (sequence, KV head) slab of K and V lies within 2^31 elements of its base and positions
 // and strides are below 2^24, so an offset is one full-rate 24-bit multiply.
-template <int NQ, int G, bool WIDE, bool ROPE>
+// PAGED: K and V are page pools read through the sequence's row of the block table; the page id of
+// every slot is looked up once, next to its position, and kept in LDS as well.
+template <int NQ, int G, bool WIDE, bool ROPE, bool PAGED>
 __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || (ROPE && NQ * G == 8) ? 2 : NQ * G == 8 ? 3 : 4) void attn_prefill32_kernel(const AttnPrefillArgs a)
 {
+    static_assert(!PAGED || WIDE, "paged pools are addressed with 64-bit offsets");
     constexpr int kPfStages = ROPE ? kPfStagesRope : kPfStagesPlain;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     int *sPos = reinterpret_cast<int *>(smem + kPfStages * kPfStageEl);      // one int per key slot
-    // one flag per tile, behind the positions of the most slots this geometry can have
-    uint8_t *sMasked = reinterpret_cast<uint8_t *>(
-        sPos + (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile);
+    // the most slots this geometry can have
+    const int slots_cap = (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile;
+    int *sPage = sPos + slots_cap;                                           // PAGED: one page id per key slot
+    // one flag per tile, behind the per-slot arrays
+    uint8_t *sMasked = reinterpret_cast<uint8_t *>(sPos + (PAGED ? 2 : 1) * slots_cap);
 
     int p = blockIdx.x, head_part = 0;
     if (a.ge.G != G) {                               // blocks of 8 problems x (G_total/G) parts
@@ -107,6 +112,8 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || (ROPE && NQ * G == 8) ? 
     for (int slot = tid; slot < n_tiles * kPfTile; slot += nthreads) {
         const int pos = slot < total ? pf_slot_to_pos(a, pr, p, slot, n_sink_eff, w0) : -1;
         sPos[slot] = pos;
+        if constexpr (PAGED)        // an empty slot fetches row 0 of the sequence
+            sPage[slot] = a.paged.block_table[(int64_t)pr.b * a.paged.table_stride + (max(pos, 0) >> a.paged.page_log2)];
         const unsigned long long m = __ballot(pos < 0 || pos >= qpos0);      // a tile is half a wave
         if ((lane & 31) == 0) sMasked[slot >> 5] = (uint32_t)(m >> (lane & 32)) != 0u;
     }
@@ -130,8 +137,9 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || (ROPE && NQ * G == 8) ? 
             }
         }
     }
-    const uint16_t *kb = a.k + pr.b * a.k_sb + pr.g * a.k_sh;
-    const uint16_t *vb = a.v + pr.b * a.v_sb + pr.g * a.v_sh;
+    const uint16_t *kb = PAGED ? a.k + pr.g * a.k_sh : a.k + pr.b * a.k_sb + pr.g * a.k_sh;
+    const uint16_t *vb = PAGED ? a.v + pr.g * a.v_sh : a.v + pr.b * a.v_sb + pr.g * a.v_sh;
+    const int page_mask = PAGED ? (1 << a.paged.page_log2) - 1 : 0;
 
     f32x16 o[4];
 #pragma unroll
@@ -151,13 +159,14 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || (ROPE && NQ * G == 8) ? 
     // so LDS addresses are per-lane constants plus immediates
     auto stage_of = [&](int st) { return smem + (st % kPfStages) * kPfStageEl; };
     // key positions of this lane's rows in the loads of a tile (read a period ahead of the request)
-    struct Rows { int pos[kLoadsPerWave]; };
+    struct Rows { int pos[kLoadsPerWave]; int page[PAGED ? kLoadsPerWave : 1]; };
     auto rows_of = [&](int tile) {
         Rows r;
 #pragma unroll
         for (int i = 0; i < kLoadsPerWave; ++i) {
             const int j = wave_s + i * NW;
             r.pos[i] = tile < n_tiles ? sPos[tile * kPfTile + 4 * (j & 7) + (lane >> 4)] : 0;
+            if constexpr (PAGED) r.page[i] = tile < n_tiles ? sPage[tile * kPfTile + 4 * (j & 7) + (lane >> 4)] : 0;
         }
         return r;
     };
@@ -174,7 +183,10 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || (ROPE && NQ * G == 8) ? 
             const int slot = lane & 15;
             const int chunk = is_v ? slot ^ ((key & 3) << 2) : slot ^ (key & 15);
             const uint16_t *src;
-            if (WIDE) src = (is_v ? vb + (int64_t)pos * a.v_st : kb + (int64_t)pos * a.k_st) + chunk * 8;
+            if (PAGED)
+                src = (is_v ? vb + (int64_t)rows.page[PAGED ? i : 0] * a.v_sb + (int64_t)(pos & page_mask) * a.v_st
+                            : kb + (int64_t)rows.page[PAGED ? i : 0] * a.k_sb + (int64_t)(pos & page_mask) * a.k_st) + chunk * 8;
+            else if (WIDE) src = (is_v ? vb + (int64_t)pos * a.v_st : kb + (int64_t)pos * a.k_st) + chunk * 8;
             else src = (is_v ? vb : kb) + (__umul24((uint32_t)pos, (uint32_t)(is_v ? a.v_st : a.k_st)) + (uint32_t)(chunk * 8));
             const uint32_t dst = __builtin_amdgcn_readfirstlane(
                 (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)(stage + j * 4 * kD));
@@ -385,24 +397,26 @@ void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len,
     const int parts = a.ge.G / heads_per_wg;
     const dim3 block_dim(64 * NQ * heads_per_wg), grid(parts == 1 ? P : (P + 7) / 8 * 8 * parts);
     const int slots = (a.ge.n_sink + a.n_blocks * a.block + a.ge.n_stream + kPfTile - 1) / kPfTile * kPfTile;
-    const bool use_rope = a.rope_cos != nullptr;
+    const bool use_rope = a.rope_cos != nullptr, paged = a.paged.block_table != nullptr;
     const size_t lds = (size_t)(use_rope ? kPfStagesRope : kPfStagesPlain) * kPfStageEl * sizeof(uint16_t) +
-                       (size_t)slots * sizeof(int) + slots / kPfTile;     // stages, slot positions, per-tile flags
+                       (size_t)slots * sizeof(int) * (paged ? 2 : 1) + slots / kPfTile;   // stages, slot positions (and pages), per-tile flags
     const int64_t lim = (int64_t)1 << 31, lim24 = (int64_t)1 << 24;
-    const bool wide = max_seq_len >= lim24 || a.k_st < 0 || a.v_st < 0 || a.k_st >= lim24 || a.v_st >= lim24 ||
+    const bool wide = paged || max_seq_len >= lim24 || a.k_st < 0 || a.v_st < 0 || a.k_st >= lim24 || a.v_st >= lim24 ||
                       max_seq_len * a.k_st + kD >= lim || max_seq_len * a.v_st + kD >= lim;
-#define IHIP_PF32_R(NQV, GV, WV, RV)                                                                         \
+#define IHIP_PF32_R(NQV, GV, WV, RV, PV)                                                                     \
     {                                                                                                        \
         static bool attr_set = false;     /* allow more than 64 KiB of dynamic LDS, once per kernel */       \
         if (!attr_set) {                                                                                     \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_prefill32_kernel<NQV, GV, WV, RV>), \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_prefill32_kernel<NQV, GV, WV, RV, PV>), \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPf32MaxLds - (RV ? 64 : 0)); \
             attr_set = true;                                                                                 \
         }                                                                                                    \
-        hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV, WV, RV>), grid, block_dim, lds, st, a);          \
+        hipLaunchKernelGGL((attn_prefill32_kernel<NQV, GV, WV, RV, PV>), grid, block_dim, lds, st, a);      \
     }
 #define IHIP_PF32(NQV, GV, WV)                                                                               \
-    if (use_rope) IHIP_PF32_R(NQV, GV, WV, true) else IHIP_PF32_R(NQV, GV, WV, false)
+    if (WV && paged) {                                                                                       \
+        if (use_rope) IHIP_PF32_R(NQV, GV, true, true, true) else IHIP_PF32_R(NQV, GV, true, false, true)    \
+    } else if (use_rope) IHIP_PF32_R(NQV, GV, WV, true, false) else IHIP_PF32_R(NQV, GV, WV, false, false)
 #define IHIP_PF32_BY_G(NQV, WV)             \
     switch (heads_per_wg) {                 \
     case 1: IHIP_PF32(NQV, 1, WV); break;   \
