@@ -313,10 +313,11 @@ def bench_prefill(args, w, torch, ihip, configs):
 
     rope = None
     if args.rope:
-        assert args.rope == "relative", "chunked prefill: relative-style pruning + streaming-style attention only"
         from workloads import gen
-        cos, sin = gen.rope_table(w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8, w.d, device=dev)
-        rope = ihip.Rope(cos, sin, ihip.ROPE_RELATIVE, ihip.ROPE_STREAMING)
+        n_pos = max(L.stage1_slots(chunks[0]), max(keeps)) + w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8
+        cos, sin = gen.rope_table(n_pos, w.d, device=dev)
+        rope = ihip.Rope(cos, sin, ihip.ROPE_RELATIVE if args.rope == "relative" else ihip.ROPE_CHUNK_INDEXED,
+                         ihip.ROPE_STREAMING)
 
     paged = None
     if args.paged:
@@ -359,7 +360,7 @@ def bench_prefill(args, w, torch, ihip, configs):
         n_valid_prev = kept_valid
         first = ".first" if i == 0 else ""
         # relative-style RoPE: every candidate row against two rotated copies of the queries
-        flops[f"prune_prefill{first}.l{c}"] = w.B * w.Hq * pairs * w.d * 2 * (2 if rope else 1)
+        flops[f"prune_prefill{first}.l{c}"] = w.B * w.Hq * pairs * w.d * 2 * (2 if args.rope == "relative" else 1)
     keys = 0
     for m in range(w.Mq):
         E = (w.T - w.Tq) + (m + 1) * w.b_q
@@ -408,7 +409,7 @@ def bench_prefill(args, w, torch, ihip, configs):
     return {
         "metric": "sparse_attn_prefill_us_per_layer",
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
-        "config": {"workload": w.name + ("_dynamic_rope_relative" if rope else "")
+        "config": {"workload": w.name + (f"_dynamic_rope_{args.rope}" if rope else "")
                    + (f"_paged{args.paged}_{args.paged_order}" if paged else ""), "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
                    "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink, "n_stream": w.n_stream},

@@ -166,7 +166,9 @@ __device__ inline uint32_t f32_to_bf16_bits(float f)
 }
 
 // 8 bf16 = 4 (even, odd) dim pairs, each turned by the angle whose cos and sin are given (fp32
-// arithmetic, results rounded to bf16, nearest-even): ApplyRope of Sec. 4 on a 16-byte piece of a row
+// arithmetic, every product and sum rounded on its own -- no fused multiply-add, so that the value
+// does not depend on the compiler's contraction --, results rounded to bf16, nearest-even):
+// ApplyRope of Sec. 4 on a 16-byte piece of a row
 __device__ inline uint4 rotate_bf16x8(const uint4 x, const float4 c, const float4 sn)
 {
     const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
@@ -175,7 +177,8 @@ __device__ inline uint4 rotate_bf16x8(const uint4 x, const float4 c, const float
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const float e = __uint_as_float(in[i] << 16), o = __uint_as_float(in[i] & 0xffff0000u);
-        w[i] = f32_to_bf16_bits(e * cc[i] - o * ss[i]) | (f32_to_bf16_bits(e * ss[i] + o * cc[i]) << 16);
+        w[i] = f32_to_bf16_bits(__fsub_rn(__fmul_rn(e, cc[i]), __fmul_rn(o, ss[i]))) |
+               (f32_to_bf16_bits(__fadd_rn(__fmul_rn(e, ss[i]), __fmul_rn(o, cc[i]))) << 16);
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
 }

@@ -27,6 +27,28 @@ struct PruneArgs {
                               // count 2-byte units of the byte rows)
 };
 
+// Chunk-indexed RoPE needs the number of chunks this stage really has for problem p (valid slots are
+// a prefix of the slot list: parents are ascending with the empty ones last, and only the last chunk
+// before the end of the middle range can be cut short).  Every thread of the workgroup calls it
+// (uses *sh and barriers).
+__device__ inline int stage_n_chunk(const PruneArgs &a, const Problem &pr, int p, int nthreads, int *sh)
+{
+    if (a.parent_starts == nullptr) return max(0, (pr.hi - pr.lo + a.chunk - 1) / a.chunk);
+    if (threadIdx.x == 0) *sh = 0;
+    __syncthreads();
+    const int32_t *ps = a.parent_starts + (int64_t)p * a.n_parent;
+    const int parent_chunk = a.chunk << a.ratio_log2;
+    for (int i = threadIdx.x; i < a.n_parent; i += nthreads) {
+        const int s0 = ps[i];
+        const bool here = s0 >= 0 && s0 < pr.hi;
+        const int s1 = i + 1 < a.n_parent ? ps[i + 1] : -1;
+        if (here && !(s1 >= 0 && s1 < pr.hi))       // the last parent that holds keys
+            *sh = (i << a.ratio_log2) + (min(parent_chunk, pr.hi - s0) + a.chunk - 1) / a.chunk;
+    }
+    __syncthreads();
+    return *sh;
+}
+
 // SRC 0: K in HBM through strides; 1: host tier with the on-GPU bank; 2: paged pool
 template <int SRC> struct KeySource;
 template <> struct KeySource<0> {

@@ -184,6 +184,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // q_L = R(n_stream+1) q and q_R = R(n_stream) q (rounded to bf16 for the matrix cores), and every
 // candidate row is scored against both, because a key that wins as the right branch is the left
 // branch of the next iteration.  Twice the matrix work and twice the query registers.
+//
+// ROPE == 2: chunk-indexed style.  Every key of chunk j (index in the stage's chunk list) sits at
+// j, query t of the block at min(its own position, n_chunk - 1 + n_stream).  The queries differ in
+// position, so nothing folds: the query operands are rotated once (each row to its own position)
+// and every candidate row is rotated to its chunk's index after it has landed in LDS, each lane
+// turning in place the 16 bytes it fetched itself (tile row 4r + kq is candidate column 4(r%4) + kq
+// of tile r/4, whose chunk and therefore table row are the same at every level of a search: the 8
+// table pieces of a lane are fetched once per chunk group).  Same carried-score search and matrix
+// work as the plain kernel, plus 8 rotations and LDS round trips per level.
 __device__ inline bf16x8 rotate_operand(const bf16x8 x, const float *cos4, const float *sin4)
 {
     return __builtin_bit_cast(bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, x), cos4, sin4));
@@ -192,7 +201,7 @@ __device__ inline bf16x8 rotate_operand(const bf16x8 x, const float *cos4, const
 // PAGED: K is a page pool read through the sequence's row of the block table: the lane that owns a
 // candidate looks its page up and forms the row's element offset (64-bit) before the offsets are
 // handed to the loading lanes, so a level costs one more dependent (cache-resident) load.
-template <int MT, int NT, int G, bool WIDE, bool ROPE, bool PAGED>
+template <int MT, int NT, int G, bool WIDE, int ROPE, bool PAGED>
 __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
                                                                             const RopeView rope)
 {
@@ -253,8 +262,13 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     uint32_t dst_own[NT * 4];                        // this wave's tile, four rows at a time
 #pragma unroll
     for (int r = 0; r < NT * 4; ++r) dst_own[r] = lds_addr(tile + r * 4 * kD);
-    bf16x8 qa[MT][4];                                // ROPE: q_L
-    bf16x8 qaR[ROPE ? MT : 1][4];                    // ROPE: q_R
+    bf16x8 qa[MT][4];                                // relative RoPE: q_L
+    bf16x8 qaR[ROPE == 1 ? MT : 1][4];               // relative RoPE: q_R
+    int q_cap = 0;                                   // chunk-indexed RoPE: the largest query position
+    if constexpr (ROPE == 2) {
+        __shared__ int sh_n_chunk;
+        q_cap = stage_n_chunk(a, pr, p, 64 * G, &sh_n_chunk) - 1 + a.ge.n_stream;
+    }
     {
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(pr.m * a.ge.b_q) * a.q_st;
 #pragma unroll
@@ -269,7 +283,12 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
                     qa[mt][ks] = operand(tile, (mt - m0) * 16, ks);
-                    if constexpr (ROPE) {
+                    if constexpr (ROPE == 2) {
+                        const int qpos = min(pr.E - a.ge.b_q + mt * 16 + n, q_cap);
+                        const int64_t at = (int64_t)qpos * (kD / 2) + ((ks << 2) + kq) * 4;
+                        qa[mt][ks] = rotate_operand(qa[mt][ks], rope.cos + at, rope.sin + at);
+                    }
+                    if constexpr (ROPE == 1) {
                         const int pair = ((ks << 2) + kq) * 4;       // first of this operand's 4 dim pairs
                         const int64_t posR = (int64_t)a.ge.n_stream * (kD / 2) + pair, posL = posR + kD / 2;
                         qaR[mt][ks] = rotate_operand(qa[mt][ks], rope.cos + posR, rope.sin + posR);
@@ -308,7 +327,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
                 for (int ks = 0; ks < 4; ++ks)
                     c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[mt][ks], kr[t][ks], c, 0, 0, 0);
                 best = fmaxf(best, fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3])));
-                if constexpr (ROPE) {
+                if constexpr (ROPE == 1) {
                     f32x4 cr = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
@@ -319,12 +338,27 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
             best = fmaxf(best, __shfl_xor(best, 16, 64));
             best = fmaxf(best, __shfl_xor(best, 32, 64));
             sig[t] = best;
-            if constexpr (ROPE) {
+            if constexpr (ROPE == 1) {
                 bestR = fmaxf(bestR, __shfl_xor(bestR, 16, 64));
                 bestR = fmaxf(bestR, __shfl_xor(bestR, 32, 64));
                 sigR[t] = bestR;
             }
         }
+    };
+    // chunk-indexed RoPE: table pieces of this lane's 8 rows of a tile (set per chunk group below) and
+    // the in-place rotation of the 16 bytes this lane fetched with load instruction r of a tile
+    float4 tb_cos[ROPE == 2 ? NT * 4 : 1], tb_sin[ROPE == 2 ? NT * 4 : 1];
+    auto rotate_piece = [&](uint16_t *four_rows, const float4 c, const float4 sn) {
+        uint4 *piece = reinterpret_cast<uint4 *>(four_rows + kq * kD + n * 8);
+        *piece = rotate_bf16x8(*piece, c, sn);
+    };
+    auto rotate_own = [&](uint16_t *four_rows, int r) {      // r: compile-time after unrolling
+        rotate_piece(four_rows, tb_cos[ROPE == 2 ? r : 0], tb_sin[ROPE == 2 ? r : 0]);
+    };
+    // table piece of this lane for load instruction r of the chunk group at jt
+    auto table_at = [&](int jt, int r) {
+        const int j = min(jt + (r >> 2) * 16 + (r & 3) * 4 + kq, a.max_chunks - 1);
+        return (int64_t)j * (kD / 2) + ((n ^ ((r & 3) * 4 + kq)) << 2);
     };
     // score of candidate rows pos[t] of this wave's own searches.  The scores of columns whose
     // search has ended are ignored by the caller.
@@ -348,6 +382,10 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
         }
         // the loads count on vmcnt; the wave reads its own tile, so no barrier is needed
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if constexpr (ROPE == 2) {
+#pragma unroll
+            for (int r = 0; r < NT * 4; ++r) rotate_own(tile + r * 4 * kD, r);
+        }
         mfma_scores(tile, sig, sigR);
     };
 
@@ -371,6 +409,14 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
             len[t] = valid[t] ? min(a.chunk, pr.hi - start[t]) : 0;
             off[t] = 0;
             pos[t] = start[t];
+        }
+        if constexpr (ROPE == 2) {
+#pragma unroll
+            for (int r = 0; r < NT * 4; ++r) {
+                const int64_t at = table_at(jt, r);
+                tb_cos[r] = *reinterpret_cast<const float4 *>(rope.cos + at);
+                tb_sin[r] = *reinterpret_cast<const float4 *>(rope.sin + at);
+            }
         }
         int half = a.chunk >> 1;
         if (kShare) {
@@ -397,6 +443,17 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
                 else load4(kb, k_st, dst_shared[i], cand[i], (r & 3) * 4 + kq);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if constexpr (ROPE == 2) {
+#pragma unroll
+                for (int i = 0; i < kPerWave; ++i) {
+                    // which of the 16 loads this is depends on the wave: the piece is fetched again
+                    // rather than picked from the register array with a run-time index
+                    const int ld = hh * kPerWave + i;
+                    const int64_t at = table_at(jt, ld & 7);
+                    rotate_piece(&sh_rows[ld * 4 * kD], *reinterpret_cast<const float4 *>(rope.cos + at),
+                                 *reinterpret_cast<const float4 *>(rope.sin + at));
+                }
+            }
             __syncthreads();
             float l0r[NT];
             mfma_scores(&sh_rows[0], sigma, l0r);
@@ -404,7 +461,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const bool has_right = half >= 1 && half < len[t];
-                if constexpr (ROPE) {
+                if constexpr (ROPE == 1) {
                     const bool right = has_right && sR[t] > sigma[t];        // strict: tie keeps left
                     off[t] = right ? half : 0;
                     sL[t] = right ? s[t] : sigma[t];
@@ -415,7 +472,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
             __syncthreads();                         // tiles 0 and 1 go back to their waves
         } else {
             score(pos, valid, sigma, sR);
-            if constexpr (ROPE) {
+            if constexpr (ROPE == 1) {
 #pragma unroll
                 for (int t = 0; t < NT; ++t) { sL[t] = sigma[t]; sigma[t] = sR[t]; }
             }
@@ -429,7 +486,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
             score(pos, ok, s, sR);
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                if constexpr (ROPE) {
+                if constexpr (ROPE == 1) {
                     if (ok[t] && sR[t] > sL[t]) { off[t] += half; sL[t] = s[t]; sigma[t] = sR[t]; }
                 } else if (ok[t] && s[t] > sigma[t]) { off[t] += half; sigma[t] = s[t]; }   // strict: tie keeps left
             }
@@ -459,7 +516,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     }
 }
 
-template <int MT, bool WIDE, bool ROPE, bool PAGED>
+template <int MT, bool WIDE, int ROPE, bool PAGED>
 static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hipStream_t st)
 {
     constexpr int NT = 2;
@@ -482,7 +539,8 @@ static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hi
 // (batch, head) slab of Q and K lies within 2^31 elements of its base and positions and strides are
 // below 2^24; 64-bit offsets otherwise.
 template <int MT>
-static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, const RopeView *rope, hipStream_t st)
+static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, const RopeView *rope, int style,
+                           hipStream_t st)
 {
     const int64_t lim = (int64_t)1 << 31;
     const int64_t lim24 = (int64_t)1 << 24;         // narrow offsets are formed by a 24-bit multiply
@@ -490,14 +548,18 @@ static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, const
                       a.k_st < 0 || a.q_st < 0 || max_seq_len >= lim24 || a.k_st >= lim24 || a.q_st >= lim24;
     const RopeView none{nullptr, nullptr, 0};
     if (a.paged.block_table) {
-        if (rope) launch_prefill_w<MT, true, true, true>(a, P, *rope, st);
-        else launch_prefill_w<MT, true, false, true>(a, P, none, st);
+        if (rope && style == 2) launch_prefill_w<MT, true, 2, true>(a, P, *rope, st);
+        else if (rope) launch_prefill_w<MT, true, 1, true>(a, P, *rope, st);
+        else launch_prefill_w<MT, true, 0, true>(a, P, none, st);
+    } else if (rope && style == 2) {
+        if (wide) launch_prefill_w<MT, true, 2, false>(a, P, *rope, st);
+        else launch_prefill_w<MT, false, 2, false>(a, P, *rope, st);
     } else if (rope) {
-        if (wide) launch_prefill_w<MT, true, true, false>(a, P, *rope, st);
-        else launch_prefill_w<MT, false, true, false>(a, P, *rope, st);
+        if (wide) launch_prefill_w<MT, true, 1, false>(a, P, *rope, st);
+        else launch_prefill_w<MT, false, 1, false>(a, P, *rope, st);
     } else {
-        if (wide) launch_prefill_w<MT, true, false, false>(a, P, none, st);
-        else launch_prefill_w<MT, false, false, false>(a, P, none, st);
+        if (wide) launch_prefill_w<MT, true, 0, false>(a, P, none, st);
+        else launch_prefill_w<MT, false, 0, false>(a, P, none, st);
     }
 }
 
@@ -550,12 +612,11 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     if (fp8 && (s.b_q != 1 || bank))
         return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: FP8 keys are built for decode from device memory only");
     RopeView rope_view{nullptr, nullptr, 0};
+    int rope_style = 0;
     if (rope && rope->prune_style != IHIP_ROPE_NONE) {
         if (bank)
             return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: dynamic RoPE is built for K in device memory only");
         const int style = rope->prune_style;
-        if (s.b_q != 1 && style == IHIP_ROPE_CHUNK_INDEXED)
-            return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: chunk-indexed RoPE is built for decode only");
         if (style != IHIP_ROPE_RELATIVE && style != IHIP_ROPE_CHUNK_INDEXED)
             return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope prune_style = %d", style);
         if (!rope->cos || !rope->sin) return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope tables are NULL");
@@ -565,6 +626,7 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
             return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope table has %d positions, %lld needed", rope->n_pos,
                         (long long)need);
         rope_view = RopeView{rope->cos, rope->sin, rope->n_pos};
+        rope_style = style;
         if (s.b_q == 1) return launch_prune_stage_rope(a, rope_view, style, P, fp8, st);
     }
     const RopeView *rv = rope_view.cos ? &rope_view : nullptr;
@@ -579,9 +641,9 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
         return check_launch("prune_stage (decode)");
     }
     switch (s.b_q) {
-    case 16: launch_prefill<1>(a, P, s.max_seq_len, rv, st); break;
-    case 32: launch_prefill<2>(a, P, s.max_seq_len, rv, st); break;
-    case 64: launch_prefill<4>(a, P, s.max_seq_len, rv, st); break;
+    case 16: launch_prefill<1>(a, P, s.max_seq_len, rv, rope_style, st); break;
+    case 32: launch_prefill<2>(a, P, s.max_seq_len, rv, rope_style, st); break;
+    case 64: launch_prefill<4>(a, P, s.max_seq_len, rv, rope_style, st); break;
     default: return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: b_q = %d not in {1, 16, 32, 64}", s.b_q);
     }
     return check_launch("prune_stage (prefill)");

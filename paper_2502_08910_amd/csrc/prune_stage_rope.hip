@@ -50,28 +50,10 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
     const int grp = threadIdx.x >> 4;
     const int j0 = (blockIdx.x * 16 + grp) * U;
 
-    // chunk-indexed: the number of chunks this stage really has for this problem (valid slots are
-    // a prefix of the slot list: parents are ascending with the empty ones last, and only the
-    // last chunk before the end of the middle range can be cut short)
+    // chunk-indexed: the number of chunks this stage really has for this problem
     __shared__ int sh_n_chunk;
-    if (STYLE == 2) {
-        if (a.parent_starts == nullptr) {
-            if (threadIdx.x == 0) sh_n_chunk = max(0, (pr.hi - pr.lo + a.chunk - 1) / a.chunk);
-        } else {
-            if (threadIdx.x == 0) sh_n_chunk = 0;
-            __syncthreads();
-            const int32_t *ps = a.parent_starts + (int64_t)p * a.n_parent;
-            const int parent_chunk = a.chunk << a.ratio_log2;
-            for (int i = threadIdx.x; i < a.n_parent; i += 256) {
-                const int s0 = ps[i];
-                const bool here = s0 >= 0 && s0 < pr.hi;
-                const int s1 = i + 1 < a.n_parent ? ps[i + 1] : -1;
-                if (here && !(s1 >= 0 && s1 < pr.hi))       // the last parent that holds keys
-                    sh_n_chunk = (i << a.ratio_log2) + (min(parent_chunk, pr.hi - s0) + a.chunk - 1) / a.chunk;
-            }
-        }
-        __syncthreads();
-    }
+    int n_chunk = 0;
+    if (STYLE == 2) n_chunk = stage_n_chunk(a, pr, p, 256, &sh_n_chunk);
     if (j0 >= a.max_chunks) return;
 
     float qf[G][8];
@@ -193,7 +175,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
             }
         }
     } else {
-        const int qpos = min(pr.E - 1, sh_n_chunk - 1 + a.ge.n_stream);
+        const int qpos = min(pr.E - 1, n_chunk - 1 + a.ge.n_stream);
         float qr[U][G][8];
 #pragma unroll
         for (int u = 0; u < U; ++u) {

@@ -76,11 +76,12 @@ def test_argument_checks_of_the_variants_need_no_gpu(built_lib):
     r = RopeStruct(256, 256, 1025, 1, 1)                     # needs n_stream + 2 = 1026 rows
     assert L.ihip_prune_stage_rope(ctypes.byref(s), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None) == -1
     assert b"1026" in L.ihip_last_error()
-    # chunked prefill: the chunk-indexed style is a decode feature; the attention checks the table
+    # chunked prefill: the chunk-indexed style needs max_chunks + n_stream table rows; the attention
+    # checks the table too
     sp = Shape(1, 32, 8, 128, 64, 64, 1, 4096, 128, 1024)
-    r = RopeStruct(256, 256, 8192, 2, 1)
+    r = RopeStruct(256, 256, slots + 1024 - 1, 2, 1)
     rc = L.ihip_prune_stage_rope(ctypes.byref(sp), t, t, None, 0, 0, 64, slots, ctypes.byref(r), 256, None, None)
-    assert rc == -4
+    assert rc == -1
     f = ctypes.c_float
     assert L.ihip_sparse_attn_prefill_rope(ctypes.byref(sp), t, t, t, 256, 16, 16, f(0.1), None, 256, None, None, 0,
                                            None) == -1

@@ -40,10 +40,10 @@ def small(Tq=256, prefix=2048, b_q=64, B=1, Hq=32, Hkv=8, n_stream=256, stages=(
                           n_stream=n_stream, stages=stages, **kw)
 
 
-def gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune=True, attn=True, want_rep=True):
+def gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune="relative", attn=True, want_rep=True):
     qd, kd, vd, sld = [t.cuda() for t in (q, k, v, sl)]
-    rp = ihip.Rope(cos.cuda(), sin.cuda(), ihip.ROPE_RELATIVE if prune else ihip.ROPE_NONE,
-                   ihip.ROPE_STREAMING if attn else ihip.ROPE_NONE)
+    style = {None: ihip.ROPE_NONE, "relative": ihip.ROPE_RELATIVE, "chunk": ihip.ROPE_CHUNK_INDEXED}[prune]
+    rp = ihip.Rope(cos.cuda(), sin.cuda(), style, ihip.ROPE_STREAMING if attn else ihip.ROPE_NONE)
     L = ihip.Layer(qd, kd, sld, w.b_q, w.n_sink, w.n_stream)
     stages, parents, pchunk = [], None, 0
     for (l_c, keep) in w.stages:
@@ -123,14 +123,15 @@ def compare(w, o, stages, out, lse, exact, problems=None, score_tol=None):
     small(Hq=8, Hkv=8, Tq=128),                           # G = 1
     small(Hq=16, Hkv=2, Tq=64),                           # G = 8
 ], ids=["llama", "ragged-b2", "bq32", "bq16-3stage", "g1", "g8"])
-def test_quarter_turn_table_bit_exact(ihip, orc, w):
+@pytest.mark.parametrize("prune", ["relative", "chunk"])
+def test_quarter_turn_table_bit_exact(ihip, orc, w, prune):
     q, k, v, sl, _ = configs.make_inputs(w, 0, kind="int")
     if w.B == 2:
         sl = torch.tensor([w.T, w.T - 517], dtype=torch.int32)
     cos, sin = gen.quarter_turn_table(w.T, w.d)
     o = orc.Oracle(q, k, v, sl.tolist(), w.b_q, w.n_sink, w.n_stream,
-                   rope=orc.RopeSpec(cos.numpy(), sin.numpy(), prune="relative", attn="streaming"))
-    stages, out, lse, fused = gpu_prefill(ihip, w, q, k, v, sl, cos, sin)
+                   rope=orc.RopeSpec(cos.numpy(), sin.numpy(), prune=prune, attn="streaming"))
+    stages, out, lse, fused = gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune=prune)
     worst, _ = compare(w, o, stages, out, lse, exact=True)
     assert worst <= 2e-2
     assert torch.equal(fused, out)          # the one-enqueue layer call runs the same kernels
@@ -142,22 +143,30 @@ def test_rope_changes_selection_and_output(ihip, orc):
     q, k, v, sl, _ = configs.make_inputs(w, 0, kind="int")
     cos, sin = gen.quarter_turn_table(w.T, w.d)
     with_rope = gpu_prefill(ihip, w, q, k, v, sl, cos, sin)
-    without = gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune=False, attn=False)
+    without = gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune=None, attn=False)
     assert not torch.equal(with_rope[0][0][0], without[0][0][0])
     assert not torch.equal(with_rope[1], without[1])
 
 
+@pytest.mark.parametrize("prune", ["relative", "chunk"])
 @pytest.mark.parametrize("seed", [0, 1])
-def test_real_table_gaussian_recall_and_output(ihip, orc, seed):
+def test_real_table_gaussian_recall_and_output(ihip, orc, seed, prune):
     w = small(Tq=128, prefix=4096, stages=((64, 16), (16, 32)))
     q, k, v, sl, _ = configs.make_inputs(w, seed)
     cos, sin = gen.rope_table(w.T, w.d)
+    # Relative style: the kernel folds the key's rotation into the query, R(n_stream+1-j) q . k, and
+    # rounds the rotated query to bf16 (relative error 2^-9 per element); the oracle rotates both in
+    # fp32.  For |q| ~ |k| ~ sqrt(128) the dot products differ by about 2^-9 / sqrt(3) * sqrt(128)
+    # ~ 0.013 (one sigma); 0.1 leaves 7 sigma.
+    # Chunk-indexed style: the kernel does literally what the oracle does with operand rounding on
+    # (rotate q and k to their positions, round to bf16, multiply exactly, add in fp32), so the
+    # decisions are taken in the same precision and only the order of the fp32 additions differs.
+    literal = prune == "chunk"
     o = orc.Oracle(q, k, v, sl.tolist(), w.b_q, w.n_sink, w.n_stream,
-                   rope=orc.RopeSpec(cos.numpy(), sin.numpy(), prune="relative", attn="streaming"))
-    stages, out, lse, fused = gpu_prefill(ihip, w, q, k, v, sl, cos, sin, want_rep=False)
-    # rotated queries are rounded to bf16 (relative error 2^-9 per element): for |q| ~ |k| ~ sqrt(128) the
-    # error of a dot product is about 2^-9 / sqrt(3) * sqrt(128) ~ 0.013 (one sigma); 0.1 leaves 7 sigma
-    worst, (min_recall, recall) = compare(w, o, stages, out, lse, exact=False, score_tol=0.1)
+                   rope=orc.RopeSpec(cos.numpy(), sin.numpy(), prune=prune, attn="streaming",
+                                     round_operands=literal))
+    stages, out, lse, fused = gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune=prune, want_rep=False)
+    worst, (min_recall, recall) = compare(w, o, stages, out, lse, exact=False, score_tol=1e-3 if literal else 0.1)
     # block recall over the whole workload; a single problem keeps 16 or 32 chunks, so one chunk that
     # changes sides at the selection threshold already costs it 3 to 6 percent
     assert recall >= 0.99
