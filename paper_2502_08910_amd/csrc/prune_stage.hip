@@ -175,6 +175,7 @@ __global__ __launch_bounds__(256) void prune_decode_kernel(const PruneArgs a)
 // ---------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kPrefillMaxIters = 4;     // chunk groups (of 32 chunks) per workgroup, at most
 
 //
 // ROPE: relative-style dynamic RoPE (Sec. 4 "Dynamic RoPE for OOL generalization"; ApplyRopeQ /
@@ -201,7 +202,7 @@ __device__ inline bf16x8 rotate_operand(const bf16x8 x, const float *cos4, const
 // PAGED: K is a page pool read through the sequence's row of the block table: the lane that owns a
 // candidate looks its page up and forms the row's element offset (64-bit) before the offsets are
 // handed to the loading lanes, so a level costs one more dependent (cache-resident) load.
-template <int MT, int NT, int G, bool WIDE, int ROPE, bool PAGED>
+template <int MT, int NT, int G, bool WIDE, int ROPE, bool PAGED, int PARTS = 1>
 __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
                                                                             const RopeView rope)
 {
@@ -210,6 +211,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     constexpr int kTile = NT * 16 * kD;              // one tile: 32 rows of 256 bytes, no padding
     constexpr bool kShare = G >= 2;                  // two tiles are needed for the shared phase
     __shared__ float sh_sigma[G][NT * 16];
+    __shared__ float sh_best[kPrefillMaxIters][NT * 16];      // chunk scores over the head parts done so far
     __shared__ __attribute__((aligned(16))) uint16_t sh_rows[G * kTile];
     // Workgroups are dealt to the 8 XCDs round-robin by linear id; let the KV head be the fastest
     // index, so that (with 8 KV heads) one XCD's L2 only ever holds one head's K rows and all
@@ -219,7 +221,11 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     const Problem pr = problem_of(a.ge, p);
     const int lane = threadIdx.x & 63, hh = threadIdx.x >> 6;      // wave = query head of the group
     const int n = lane & 15, kq = lane >> 4;
-    const int h = pr.g * G + hh;
+    // G is the number of heads (waves) a pass works on; a group of G*PARTS heads (8, where 8 waves
+    // of this many registers would leave room for one workgroup per CU only) is done in PARTS
+    // passes, one after the other, by the same waves
+    constexpr int parts = PARTS;
+    int h = pr.g * (G * PARTS) + hh;
     using off_t = typename std::conditional<WIDE, int64_t, uint32_t>::type;   // element offset of a row
     const off_t k_st = (off_t)a.k_st;
 
@@ -269,7 +275,7 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
         __shared__ int sh_n_chunk;
         q_cap = stage_n_chunk(a, pr, p, 64 * G, &sh_n_chunk) - 1 + a.ge.n_stream;
     }
-    {
+    auto stage_queries = [&]() {
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(pr.m * a.ge.b_q) * a.q_st;
 #pragma unroll
         for (int m0 = 0; m0 < MT; m0 += 2) {
@@ -298,8 +304,11 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
             // the reads must have left LDS before the next loads land in the same tile
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
+    };
+    if constexpr (PARTS == 1) {
+        stage_queries();
+        if (kShare) __syncthreads();                 // other waves' tiles are written below
     }
-    if (kShare) __syncthreads();                     // other waves' tiles are written below
     const uint16_t *kb = PAGED ? a.k + pr.g * a.k_sh : a.k + pr.b * a.k_sb + pr.g * a.k_sh;
     const int32_t *table = PAGED ? a.paged.block_table + (int64_t)pr.b * a.paged.table_stride : nullptr;
     const int page_mask = PAGED ? (1 << a.paged.page_log2) - 1 : 0;
@@ -393,6 +402,12 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
     uint32_t dst_shared[kShare ? 16 / G : 1];
 #pragma unroll
     for (int i = 0; i < (kShare ? 16 / G : 1); ++i) dst_shared[i] = lds_addr(&sh_rows[(hh * (16 / G) + i) % (G * 8) * 4 * kD]);
+    for (int part = 0; part < parts; ++part) {
+    if constexpr (PARTS > 1) {
+        h = pr.g * (G * PARTS) + part * G + hh;
+        stage_queries();
+        if (kShare) __syncthreads();                 // other waves' tiles are written below
+    }
     for (int it = 0; it < iters; ++it) {
         const int jt = (blockIdx.y * iters + it) * NT * 16;
         int start[NT], len[NT], off[NT], pos[NT];
@@ -507,12 +522,18 @@ __global__ __launch_bounds__(64 * G, ROPE ? 2 : 3) void prune_prefill_kernel(con
             if (j < a.max_chunks) {
                 float best = sh_sigma[0][threadIdx.x];
                 for (int g2 = 1; g2 < G; ++g2) best = fmaxf(best, sh_sigma[g2][threadIdx.x]);
-                // validity is the same for every head; recompute it for this slot
-                const bool v = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, j) >= 0;
-                a.out_scores[(int64_t)p * a.max_chunks + j] = v ? best : -INFINITY;
+                if (part > 0) best = fmaxf(best, sh_best[it][threadIdx.x]);
+                if (part + 1 < parts) {
+                    sh_best[it][threadIdx.x] = best;
+                } else {
+                    // validity is the same for every head; recompute it for this slot
+                    const bool v = slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, j) >= 0;
+                    a.out_scores[(int64_t)p * a.max_chunks + j] = v ? best : -INFINITY;
+                }
             }
         }
         __syncthreads();
+    }
     }
 }
 
@@ -522,7 +543,7 @@ static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hi
     constexpr int NT = 2;
     // several chunk groups per workgroup amortise the staging of the queries, as long as the
     // launch still has a few thousand workgroups
-    int iters = 4;
+    int iters = kPrefillMaxIters;
     while (iters > 1 && (int64_t)P * ((a.max_chunks + NT * 16 * iters - 1) / (NT * 16 * iters)) < 2048) iters >>= 1;
     const int per_wg = NT * 16 * iters;
     dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
@@ -531,7 +552,14 @@ static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hi
     case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE, ROPE, PAGED>), grid, dim3(64), 0, st, a, iters, rope); break;
     case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE, ROPE, PAGED>), grid, dim3(128), 0, st, a, iters, rope); break;
     case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED>), grid, dim3(256), 0, st, a, iters, rope); break;
-    default: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE, ROPE, PAGED>), grid, dim3(512), 0, st, a, iters, rope); break;
+    default:
+        // 8 heads with 64-query blocks and no RoPE: 8 waves of ~160 registers fit a CU once only;
+        // two passes of 4 waves fit three times
+        if constexpr (MT == 4 && ROPE == 0)
+            hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED, 2>), grid, dim3(256), 0, st, a, iters, rope);
+        else
+            hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE, ROPE, PAGED>), grid, dim3(512), 0, st, a, iters, rope);
+        break;
     }
 }
 
