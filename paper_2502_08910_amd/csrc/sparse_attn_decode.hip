@@ -8,12 +8,14 @@
 // lane) and keeps an online-softmax state for all G heads; groups are merged
 // through LDS, splits by a second small kernel (log-sum-exp merge).
 #include "common.h"
+#include <algorithm>
 #include <type_traits>
 
 namespace ihip {
 
 constexpr int kAttnThreads = 256;
 constexpr int kAttnGroups = kAttnThreads / kRowLanes;   // 16 tokens in flight per step
+constexpr int kAttnMinSplit = 256, kAttnMaxSplit = 1024;   // slots of one split (a multiple of 16)
 constexpr float kNegBig = -1.0e30f;                      // finite stand-in for -inf in running maxima
 
 struct AttnDecodeArgs {
@@ -168,15 +170,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
     constexpr int UNR = 4;
     const int s0 = split * a.slots_per_split;
     const int s1 = s0 + a.slots_per_split;
-    // key position of every slot of this split, one per thread, so that the main loop has no
+    // key position of every slot of this split, computed up front, so that the main loop has no
     // dependent global loads (block start -> row address)
-    __shared__ int sh_pos[kAttnThreads];
-    __shared__ int sh_page[SRC == 2 ? kAttnThreads : 1];     // paged K/V: the slot's page id, looked up here once
-    {
-        const int pos = (int)threadIdx.x < a.slots_per_split
-                            ? slot_to_pos(a, pr, p, s0 + threadIdx.x, n_sink_eff, w0) : -1;
-        sh_pos[threadIdx.x] = pos;
-        if constexpr (SRC == 2) sh_page[threadIdx.x] = pos >= 0 ? ksrc.table_entry(pos) : 0;
+    __shared__ int sh_pos[kAttnMaxSplit];
+    __shared__ int sh_page[SRC == 2 ? kAttnMaxSplit : 1];    // paged K/V: the slot's page id, looked up here once
+    for (int i = threadIdx.x; i < a.slots_per_split; i += kAttnThreads) {
+        const int pos = slot_to_pos(a, pr, p, s0 + i, n_sink_eff, w0);
+        sh_pos[i] = pos;
+        if constexpr (SRC == 2) sh_page[i] = pos >= 0 ? ksrc.table_entry(pos) : 0;
     }
     __syncthreads();
     for (int base = s0 + grp; base < s1; base += kAttnGroups * UNR) {
@@ -353,11 +354,24 @@ __global__ __launch_bounds__(kD) void attn_decode_merge_kernel(const AttnDecodeA
         a.out_lse[(int64_t)pr.b * a.ge.Hq + hq] = (M + log2f(L)) * 0.69314718055994530942f;
 }
 
+// Splits of the slot list: as many workgroups as the chip holds at once (4 workgroups of 4 waves
+// per CU with the plain kernel's registers), so that no workgroup has to wait for a free slot and
+// run its whole latency chain after the others have drained -- with 256-slot splits the cfg3 shape
+// had 1344 workgroups for 1024 places.  Between 256 and 1024 slots per split, a multiple of 16.
 static int decode_splits(const ihip_shape &s, int n_blocks, int block, int *slots_per_split)
 {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+            n_cu = 256;
+    }
     const int total = s.n_sink + n_blocks * block + s.n_stream;
-    // 16 tokens per step and 4 steps per unrolled iteration: keep splits a multiple of 64 slots
-    const int per = kAttnThreads;          // one slot position per thread in the kernel's prologue
+    const int P = std::max(1, s.B * s.Hkv);
+    const int places = std::max(1, n_cu * 4 / P);              // splits per problem that run at once
+    int per = ((total + places - 1) / places + 15) / 16 * 16;
+    per = std::min(kAttnMaxSplit, std::max(kAttnMinSplit, per));
     *slots_per_split = per;
     return (total + per - 1) / per;
 }
