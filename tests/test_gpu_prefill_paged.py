@@ -118,3 +118,24 @@ def test_paged_prefill_with_rope_and_pooling_equals_contiguous(ihip, w):
     out, _ = L.sparse_attn_prefill(qd, None, None, b1, chunks[-1], rope=rp, paged=pg)
     ref, _ = L.sparse_attn_prefill(qd, kd, vd, b1, chunks[-1], rope=rp)
     assert torch.equal(out, ref)
+
+
+@pytest.mark.parametrize("prefix", [11000, 13000])
+def test_keep_everything_paged_is_dense_causal(ihip, prefix):
+    # every chunk kept -> dense causal attention (torch, fp64), read through 16-token pages.
+    # prefix 11000: just under the key slots the 32x32 kernel keeps in LDS with page ids (12,160);
+    # prefix 13000: above them -> the 16x16 kernel runs.
+    keep = (prefix + 512) // 64 + 1
+    w = small(Tq=512, prefix=prefix, n_stream=128, stages=((64, keep), (16, 4 * keep)))
+    q, k, v, sl, _ = configs.make_inputs(w, 5)
+    k_pool, v_pool, table = scatter_to_pages(k, v, 16, seed=9)
+    qd, kd, sld = q.cuda(), k.cuda(), sl.cuda()
+    pg = ihip.PagedKV(k_pool.cuda(), v_pool.cuda(), table.cuda())
+    L = ihip.Layer(qd, kd, sld, w.b_q, w.n_sink, w.n_stream)
+    out = L.prefill_layer(qd, None, None, [s[0] for s in w.stages], [s[1] for s in w.stages], paged=pg)
+    torch.cuda.synchronize()
+    G, T, Tq = w.G, w.T, w.Tq
+    mask = torch.arange(T).view(1, -1) <= torch.arange(T - Tq, T).view(-1, 1)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        q.double(), k.double().repeat_interleave(G, 1), v.double().repeat_interleave(G, 1), attn_mask=mask)
+    assert (out.cpu().double() - ref).abs().max().item() <= 2e-2

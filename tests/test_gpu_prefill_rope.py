@@ -199,3 +199,39 @@ def test_streaming_attention_alone_on_oracle_indices(ihip, orc):
     for (g, m), ref in refs.items():
         got = out[0, g * w.G:(g + 1) * w.G, m * w.b_q:(m + 1) * w.b_q].float().cpu().numpy()
         assert np.abs(got - ref).max() <= 2e-2
+
+
+def rotary(x, cos, sin, positions):
+    """Standard RoPE in fp64: pair (2j, 2j+1) of row t turned by the table row of positions[t]."""
+    c = cos[positions].double().view(1, 1, -1, cos.shape[1])
+    s = sin[positions].double().view(1, 1, -1, sin.shape[1])
+    xe, xo = x.double()[..., 0::2], x.double()[..., 1::2]
+    out = torch.empty_like(x, dtype=torch.float64)
+    out[..., 0::2] = xe * c - xo * s
+    out[..., 1::2] = xe * s + xo * c
+    return out
+
+
+@pytest.mark.parametrize("prefix", [1000, 19000, 21000])
+def test_keep_everything_with_streaming_ids_is_rotary_attention(ihip, prefix):
+    # When every chunk is kept a query attends to all keys before it, so the streaming ids are the
+    # positions themselves and the result is ordinary causal attention on rotary-embedded q and k,
+    # computed here by torch in fp64 without the oracle.
+    # prefix 19000: just under the key slots the 32x32 kernel keeps in LDS with RoPE (20,224);
+    # prefix 21000: above them -> the 16x16 kernel runs.
+    keep = (prefix + 512) // 64 + 1
+    w = small(Tq=512, prefix=prefix, n_stream=128, stages=((64, keep), (16, 4 * keep)))
+    q, k, v, sl, _ = configs.make_inputs(w, 5)
+    cos, sin = gen.rope_table(max(w.T, w.n_sink + 4 * keep * 16 + w.n_stream), w.d)     # a row per key slot
+    qd, kd, vd, sld = [t.cuda() for t in (q, k, v, sl)]
+    rp = ihip.Rope(cos.cuda(), sin.cuda(), ihip.ROPE_NONE, ihip.ROPE_STREAMING)     # plain selection
+    L = ihip.Layer(qd, kd, sld, w.b_q, w.n_sink, w.n_stream)
+    out = L.prefill_layer(qd, kd, vd, [s[0] for s in w.stages], [s[1] for s in w.stages], rope=rp)
+    torch.cuda.synchronize()
+    G, T, Tq = w.G, w.T, w.Tq
+    qr = rotary(q, cos, sin, torch.arange(T - Tq, T))
+    kr = rotary(k, cos, sin, torch.arange(T))
+    mask = torch.arange(T).view(1, -1) <= torch.arange(T - Tq, T).view(-1, 1)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        qr, kr.repeat_interleave(G, 1), v.double().repeat_interleave(G, 1), attn_mask=mask)
+    assert (out.cpu().double() - ref).abs().max().item() <= 2e-2
