@@ -60,7 +60,7 @@ def parse():
     ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
                     help="decode workloads: fp8 = K and V quantised to E4M3 bytes (scale 1/64 each), a separate metric")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
-                    help="decode workloads: K and V scattered into pages of this many tokens in a seeded random "
+                    help="decode and prefill workloads: K and V scattered into pages of this many tokens in a seeded random "
                          "order, read through a block table (a separate metric)")
     ap.add_argument("--paged-order", default="random", choices=["random", "sequential"],
                     help="with --paged: page ids in a seeded random order (default) or in token order")
@@ -68,7 +68,7 @@ def parse():
                     help="decode workloads: memory order of K and V (the same logical [B,Hkv,T,d] tensors; bthd = "
                          "token-major, the KV heads of a token adjacent)")
     ap.add_argument("--rope", default=None, choices=["relative", "chunk"],
-                    help="decode workloads: dynamic RoPE in the pruning stages (this style) and the attention "
+                    help="decode and prefill workloads: dynamic RoPE in the pruning stages (this style) and the attention "
                          "(streaming style); a separate metric, no roofline / cpu_baseline objects")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
