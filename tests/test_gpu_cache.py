@@ -114,3 +114,45 @@ def test_bank_contents_are_the_host_rows(ihip, orc):
         assert s["mask"]["last_touched"] > 0 and s["sa"]["last_touched"] > 0
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("pooling", [None, "all_heads"])
+def test_host_tier_with_mask_caching_equals_resident(ihip, pooling):
+    # Alg. 4's refresh schedule on top of the host tier (one options struct): bit-identical to the
+    # same schedule on resident K/V, and a step that reuses every cached list does not touch the
+    # key bank of the pruning stages at all.
+    w = configs.shrink(configs.CFG1, B=2, Hq=8, Hkv=2, T=3000, n_stream=256, n_needles=0,
+                       stages=((64, 8), (16, 8), (4, 16)))
+    chunks, keeps = [s[0] for s in w.stages], [s[1] for s in w.stages]
+    refresh = (4, 2, 2)
+    pool = None if pooling is None else ihip.POOL_ALL_HEADS
+    _, k, v, _, _ = configs.make_inputs(w, 0, kind="int")
+    hk = torch.empty(k.shape, dtype=torch.bfloat16, pin_memory=True).copy_(k)
+    hv = torch.empty(v.shape, dtype=torch.bfloat16, pin_memory=True).copy_(v)
+    kd, vd = k.cuda(), v.cuda()
+    cache = ihip.HostKVCache(hk, hv, 64, 24, 16)
+    try:
+        state_c = state_r = None
+        for step in range(9):
+            sl = torch.tensor([2900 + step, 2200 + 3 * step], dtype=torch.int32).cuda()
+            qd = configs.make_q(w, 200 + step, kind="int").cuda()
+            L = ihip.Layer(qd, kd, sl, 1, w.n_sink, w.n_stream)
+            if state_c is None:
+                state_c, state_r = L.mask_state(keeps), L.mask_state(keeps)
+            first = ihip.first_stage_due(step, refresh)
+            got = L.decode_layer(qd, None, None, chunks, keeps, cache=cache, stage_starts=state_c,
+                                 first_stage=first, pooling=pool)
+            cache.update()
+            ref = L.decode_layer(qd, kd, vd, chunks, keeps, stage_starts=state_r, first_stage=first,
+                                 pooling=pool if pool is not None else ihip.POOL_KV_HEAD)
+            torch.cuda.synchronize()
+            assert torch.equal(state_c, state_r), step
+            assert torch.equal(got, ref), step
+            s = cache.stats()
+            if first == len(chunks):
+                assert s["mask"]["last_touched"] == 0, step
+            else:
+                assert s["mask"]["last_touched"] > 0, step
+            assert s["sa"]["last_touched"] > 0, step
+    finally:
+        cache.close()
