@@ -212,19 +212,23 @@ def rotary(x, cos, sin, positions):
     return out
 
 
-@pytest.mark.parametrize("prefix", [1000, 19000, 21000])
-def test_keep_everything_with_streaming_ids_is_rotary_attention(ihip, prefix):
+@pytest.mark.parametrize("prefix,prune", [(0, None), (0, "chunk"), (100, "relative"), (100, "chunk"), (1000, None),
+                                          (1000, "chunk"), (19000, None), (21000, None)])
+def test_keep_everything_with_streaming_ids_is_rotary_attention(ihip, prefix, prune):
     # When every chunk is kept a query attends to all keys before it, so the streaming ids are the
     # positions themselves and the result is ordinary causal attention on rotary-embedded q and k,
     # computed here by torch in fp64 without the oracle.
     # prefix 19000: just under the key slots the 32x32 kernel keeps in LDS with RoPE (20,224);
-    # prefix 21000: above them -> the 16x16 kernel runs.
+    # prefix 21000: above them -> the 16x16 kernel runs.  prefix 0 / 100: prefill from scratch, early
+    # query blocks have an empty middle range and see only part of the sink.  With everything kept the
+    # pruning style cannot change the result; it is varied to run those kernels on the edge shapes.
     keep = (prefix + 512) // 64 + 1
     w = small(Tq=512, prefix=prefix, n_stream=128, stages=((64, keep), (16, 4 * keep)))
     q, k, v, sl, _ = configs.make_inputs(w, 5)
     cos, sin = gen.rope_table(max(w.T, w.n_sink + 4 * keep * 16 + w.n_stream), w.d)     # a row per key slot
     qd, kd, vd, sld = [t.cuda() for t in (q, k, v, sl)]
-    rp = ihip.Rope(cos.cuda(), sin.cuda(), ihip.ROPE_NONE, ihip.ROPE_STREAMING)     # plain selection
+    style = {None: ihip.ROPE_NONE, "relative": ihip.ROPE_RELATIVE, "chunk": ihip.ROPE_CHUNK_INDEXED}[prune]
+    rp = ihip.Rope(cos.cuda(), sin.cuda(), style, ihip.ROPE_STREAMING)
     L = ihip.Layer(qd, kd, sld, w.b_q, w.n_sink, w.n_stream)
     out = L.prefill_layer(qd, kd, vd, [s[0] for s in w.stages], [s[1] for s in w.stages], rope=rp)
     torch.cuda.synchronize()
