@@ -170,3 +170,42 @@ def test_mask_caching_with_variants_follows_oracle(ihip, orc, combo):
                 ref, _ = o.attend(b, g, 0, bs, bl)
                 err = np.abs(out[b, g * w.G:(g + 1) * w.G, 0].float().cpu().numpy() - ref[:, 0]).max()
                 assert err <= 2e-2, (step, b, g, err)
+
+
+@pytest.mark.parametrize("T", [2048, 4096 + 37])
+def test_keep_everything_with_all_variants_is_rotary_attention(ihip, T):
+    # Every chunk kept: the decode layer with streaming RoPE over FP8 pages must be ordinary rotary
+    # attention of the last token over the dequantised K and V (torch, fp64; no oracle involved).
+    w = configs.shrink(configs.CFG1, T=T, B=2, n_needles=0)
+    n1 = (T - w.n_sink - w.n_stream + 63) // 64
+    stages = ((64, n1), (16, 4 * n1), (4, 16 * n1))
+    q, k, v, _, _ = configs.make_inputs(w, 4)
+    sl = torch.tensor([T, T - 300], dtype=torch.int32)
+    scales = (1.0 / 32, 1.0 / 16)
+    k8, v8 = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
+    kf = k8.view(torch.float8_e4m3fn).double() * scales[0]
+    vf = v8.view(torch.float8_e4m3fn).double() * scales[1]
+    cos, sin = gen.rope_table(T + 64, w.d)
+    k_pool, v_pool, table = scatter_to_pages(k8, v8, 16, seed=11, fill=3)
+    pg = ihip.PagedKV(k_pool.cuda(), v_pool.cuda(), table.cuda())
+    rp = ihip.Rope(cos.cuda(), sin.cuda(), ihip.ROPE_RELATIVE, ihip.ROPE_STREAMING)
+    qd = q.cuda()
+    L = ihip.Layer(qd, k8.cuda(), sl.cuda(), 1, w.n_sink, w.n_stream)
+    out = L.decode_layer(qd, None, None, [s[0] for s in stages], [s[1] for s in stages], rope=rp, kv_scales=scales,
+                         paged=pg)
+    torch.cuda.synchronize()
+    G, d = w.G, w.d
+    for b in range(w.B):
+        n = int(sl[b])
+        pos = torch.arange(n)
+        c, s_ = cos[pos].double(), sin[pos].double()
+        ke, ko = kf[b, :, :n, 0::2], kf[b, :, :n, 1::2]
+        kr = torch.empty((w.Hkv, n, d), dtype=torch.float64)
+        kr[..., 0::2], kr[..., 1::2] = ke * c - ko * s_, ke * s_ + ko * c
+        qe, qo = q[b, :, 0, 0::2].double(), q[b, :, 0, 1::2].double()
+        qr = torch.empty((w.Hq, d), dtype=torch.float64)
+        qr[:, 0::2] = qe * c[n - 1] - qo * s_[n - 1]
+        qr[:, 1::2] = qe * s_[n - 1] + qo * c[n - 1]
+        logits = torch.einsum("hd,hnd->hn", qr, kr.repeat_interleave(G, 0)) / d ** 0.5
+        ref = torch.einsum("hn,hnd->hd", torch.softmax(logits, -1), vf[b, :, :n].repeat_interleave(G, 0))
+        assert (out[b, :, 0].cpu().double() - ref).abs().max().item() <= 2e-2, b
