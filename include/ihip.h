@@ -79,12 +79,12 @@ typedef struct {
  *   attn_style   IHIP_ROPE_STREAMING: the keys a query attends to, in position
  *                order, at 0..n-1, the query at n-1 (needs n_pos >= n_sink +
  *                n_blocks*block + n_stream).
- * Built for K and V in device memory: decode (Tq == b_q == 1) with every
- * style, chunked prefill with the relative style in the pruning stages and the
- * streaming style in the attention (all queries of a block share the relative
- * position; query t of a block gets its own streaming id from the number of
- * keys it attends to).  The prefill kernels round the rotated Q and K operands
- * to bf16 for the matrix cores.  Other uses return IHIP_ERR_UNSUPPORTED.
+ * Built for decode (Tq == b_q == 1), also behind the host tier, and for chunked
+ * prefill from device memory (all queries of a block share the relative
+ * position; query t of a block gets its own chunk-indexed position and its own
+ * streaming id, the latter from the number of keys it attends to).  The prefill
+ * kernels round the rotated Q and K operands to bf16 for the matrix cores.
+ * Other uses return IHIP_ERR_UNSUPPORTED.
  */
 #define IHIP_ROPE_NONE          0
 #define IHIP_ROPE_RELATIVE      1
@@ -426,8 +426,8 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
  *   stage_starts  mask-caching state as in ihip_decode_layer_masked, or NULL;
  *   first_stage   first stage to recompute (needs stage_starts unless 0)
  * Paged, FP8 and RoPE combine freely with each other, with either pooling rule
- * and with mask caching; the host tier combines with pooling and mask caching
- * only (IHIP_ERR_UNSUPPORTED otherwise).  With stage_starts the scratch is the
+ * and with mask caching; the host tier (contiguous bf16 K/V) combines with RoPE,
+ * pooling and mask caching (IHIP_ERR_UNSUPPORTED otherwise).  With stage_starts the scratch is the
  * scores buffer plus the attention partials (IHIP_OP_DECODE_LAYER covers it);
  * out_block_starts, if given, receives a copy of the final list.
  */

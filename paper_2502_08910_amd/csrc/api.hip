@@ -527,7 +527,6 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     const size_t attn_bytes = attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
     BankView mask_bank, sa_bank;
     if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
-    if (cache && rope) return fail(IHIP_ERR_UNSUPPORTED, "%s: dynamic RoPE is not built for the host tier", who);
     if (stage_starts) {
         if (first_stage < 0 || first_stage > n_stages)
             return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d not in 0..%d", who, first_stage, n_stages);

@@ -642,8 +642,6 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     RopeView rope_view{nullptr, nullptr, 0};
     int rope_style = 0;
     if (rope && rope->prune_style != IHIP_ROPE_NONE) {
-        if (bank)
-            return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: dynamic RoPE is built for K in device memory only");
         const int style = rope->prune_style;
         if (style != IHIP_ROPE_RELATIVE && style != IHIP_ROPE_CHUNK_INDEXED)
             return fail(IHIP_ERR_INVALID_ARG, "prune_stage: rope prune_style = %d", style);

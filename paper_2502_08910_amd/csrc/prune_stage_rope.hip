@@ -18,7 +18,8 @@
 //                        min(its own position, n_chunk - 1 + n_stream): one
 //                        rotated copy of q per chunk, R(qpos - j) q, and the
 //                        carried-score search of the plain kernel.
-// SRC 0: K through strides, 2: paged pool; KV8: rows are 128
+// SRC 0: K through strides, 1: host tier (a resident block is read from its bank, the touch and
+// miss bookkeeping is done by one lane per row read), 2: paged pool; KV8: rows are 128
 // bytes of E4M3, the scores are multiplied by the K scale at the end (a positive factor: the
 // searches do not depend on it).
 #include "prune_args.h"
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(256) void prune_decode_rope_kernel(const PruneArgs 
         if constexpr (SRC == 2)
             return *reinterpret_cast<const piece_t *>(src.row_in_page(page, pos) + l16 * kLaneOff);
         else
-            return *reinterpret_cast<const piece_t *>(src.row(pos, false) + l16 * kLaneOff);
+            return *reinterpret_cast<const piece_t *>(src.row(pos, l16 == 0) + l16 * kLaneOff);
     };
 
     int off[U][G];
@@ -272,7 +273,8 @@ template <int G>
 static void launch_rope_g(const PruneArgs &a, const RopeView &rope, int style, int P, bool fp8, hipStream_t st)
 {
     const bool paged = a.paged.block_table != nullptr;
-    if (paged && fp8) launch_rope<G, 2, true>(a, rope, style, P, st);
+    if (a.bank.page_table != nullptr) launch_rope<G, 1, false>(a, rope, style, P, st);     // host tier: bf16, contiguous
+    else if (paged && fp8) launch_rope<G, 2, true>(a, rope, style, P, st);
     else if (paged) launch_rope<G, 2, false>(a, rope, style, P, st);
     else if (fp8) launch_rope<G, 0, true>(a, rope, style, P, st);
     else launch_rope<G, 0, false>(a, rope, style, P, st);

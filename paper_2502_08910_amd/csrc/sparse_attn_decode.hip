@@ -402,7 +402,6 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     if (use_rope) {
         if (rope->attn_style != IHIP_ROPE_STREAMING)
             return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_decode: rope attn_style = %d", rope->attn_style);
-        if (bank) return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: dynamic RoPE is not built for the host tier");
         if (!rope->cos || !rope->sin) return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_decode: rope tables are NULL");
         const int64_t need = (int64_t)s.n_sink + (int64_t)n_blocks * block + s.n_stream;   // most keys a query can attend
         if (rope->n_pos < need)
@@ -447,7 +446,8 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     else if (fp8) IHIP_AD_KERNEL(GG, SRCV, false, true);                                                            \
     else IHIP_AD_KERNEL(GG, SRCV, false, false)
 #define IHIP_AD_LAUNCH(GG)                                                                                          \
-    if (bank) IHIP_AD_KERNEL(GG, 1, false, false);                                                                  \
+    if (bank && use_rope) IHIP_AD_KERNEL(GG, 1, true, false);                                                       \
+    else if (bank) IHIP_AD_KERNEL(GG, 1, false, false);                                                             \
     else if (paged) { IHIP_AD_BY_FMT(GG, 2); }                                                                      \
     else { IHIP_AD_BY_FMT(GG, 0); }
     case 1: IHIP_AD_LAUNCH(1); break;

@@ -156,3 +156,50 @@ def test_host_tier_with_mask_caching_equals_resident(ihip, pooling):
             assert s["sa"]["last_touched"] > 0, step
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("style", ["relative", "chunk"])
+def test_host_tier_with_dynamic_rope(ihip, orc, style):
+    # Dynamic RoPE over K/V behind the host tier: same bits as the resident RoPE path whatever the
+    # banks hold, and the banks follow the blocks the oracle (run with the same RoPE) touches.
+    from workloads import gen
+    w = configs.shrink(configs.CFG1, B=2, Hq=8, Hkv=2, T=4096 + 29, n_stream=256, n_needles=0,
+                       stages=((64, 8), (16, 8), (4, 16)))
+    bt, mask_slots, sa_slots = 64, 40, 24
+    chunks, keeps = [s[0] for s in w.stages], [s[1] for s in w.stages]
+    _, k, v, _, _ = configs.make_inputs(w, 0, kind="int")
+    sl = torch.tensor([w.T, w.T - 700], dtype=torch.int32)
+    cos, sin = gen.quarter_turn_table(w.T, w.d)
+    rp = ihip.Rope(cos.cuda(), sin.cuda(), {"relative": ihip.ROPE_RELATIVE, "chunk": ihip.ROPE_CHUNK_INDEXED}[style],
+                   ihip.ROPE_STREAMING)
+    spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune=style, attn="streaming")
+    hk = torch.empty(k.shape, dtype=torch.bfloat16, pin_memory=True).copy_(k)
+    hv = torch.empty(v.shape, dtype=torch.bfloat16, pin_memory=True).copy_(v)
+    kd, vd, sld = k.cuda(), v.cuda(), sl.cuda()
+    cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots)
+    blocks_per_head = (w.T + bt - 1) // bt
+    sim = [orc.LruBank(cache.n_blocks_total, mask_slots), orc.LruBank(cache.n_blocks_total, sa_slots)]
+    try:
+        for call, seed in enumerate([0, 1, 0, 2]):
+            q = configs.make_q(w, seed, kind="int")
+            qd = q.cuda()
+            L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
+            ref_blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+            ref = L.decode_layer(qd, kd, vd, chunks, keeps, out_blocks=ref_blocks, rope=rp)
+            got_blocks = torch.empty_like(ref_blocks)
+            got = L.decode_layer(qd, None, None, chunks, keeps, out_blocks=got_blocks, rope=rp, cache=cache)
+            cache.update()
+            torch.cuda.synchronize()
+            assert torch.equal(got_blocks, ref_blocks), call
+            assert torch.equal(got, ref), call
+            o = orc.Oracle(q, k, v, sl.tolist(), 1, w.n_sink, w.n_stream, rope=spec)
+            res = o.layer(w.stages)
+            stats = cache.stats()
+            for bank, name in ((0, "mask"), (1, "sa")):
+                sim[bank].call(touched_blocks(o, w, res, bt, blocks_per_head, bank))
+                pt, sb = cache.tables(bank)
+                assert stats[name]["last_touched"] == sim[bank].last_touched, (call, name)
+                assert stats[name]["last_misses"] == sim[bank].last_misses, (call, name)
+                assert pt.tolist() == sim[bank].page_table, (call, name)
+    finally:
+        cache.close()
