@@ -464,6 +464,25 @@ def bench_offload(args, w, torch, ihip, configs):
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t0
 
+    kv_scales = None
+    row_bytes = 256
+    if args.kv_dtype == "fp8":
+        # the same K/V (needles included) as E4M3 bytes in pinned memory; the same bank bytes hold twice the blocks
+        kv_scales = (1.0 / 64, 1.0 / 64)
+        hk8 = torch.empty(shape, dtype=torch.uint8, pin_memory=True)
+        hv8 = torch.empty(shape, dtype=torch.uint8, pin_memory=True)
+        for src, dst, sc in ((hk, hk8, kv_scales[0]), (hv, hv8, kv_scales[1])):
+            for t_lo in range(0, w.T, step_t):
+                t_hi = min(w.T, t_lo + step_t)
+                dst[:, :, t_lo:t_hi].copy_(gen.to_e4m3(src[:, :, t_lo:t_hi].to(dev), sc))
+        hk, hv = hk8, hv8
+        mask_slots, sa_slots, row_bytes = 2 * mask_slots, 2 * sa_slots, 128
+    rope = None
+    if args.rope:
+        n_pos = max(n_chunks + 1, max(keeps)) + w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8
+        cos, sin = gen.rope_table(n_pos, w.d, device=dev)
+        rope = ihip.Rope(cos, sin, ihip.ROPE_RELATIVE if args.rope == "relative" else ihip.ROPE_CHUNK_INDEXED,
+                         ihip.ROPE_STREAMING)
     cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots)
     kview = torch.empty((w.B, w.Hkv, w.T, 0), dtype=torch.bfloat16, device=dev)     # shape carrier only
     L = ihip.Layer(qs[0], kview, seq_lens, w.b_q, w.n_sink, w.n_stream)
@@ -471,7 +490,8 @@ def bench_offload(args, w, torch, ihip, configs):
     out = torch.empty((w.B, w.Hq, 1, w.d), dtype=torch.bfloat16, device=dev)
 
     def step(i):
-        ihip.decode_layer_cached(L, qs[i % n_calls], cache, chunks, keeps, ws=ws, out=out)
+        L.decode_layer(qs[i % n_calls], None, None, chunks, keeps, ws=ws, out=out, cache=cache, kv_scales=kv_scales,
+                       rope=rope)
         cache.update()
 
     for i in range(warmup):
@@ -499,19 +519,20 @@ def bench_offload(args, w, torch, ihip, configs):
         m = s1[bank]["misses"] - s0[bank]["misses"]
         hit[bank] = {"block_hits": h, "block_misses": m, "hit_ratio": h / max(1, h + m)}
     cpu = None
-    if args.cpu_seconds > 0:
+    if args.cpu_seconds > 0 and kv_scales is None and rope is None:
         sample = decode_oracle_sample(w, qs, [(hk, hv)], [w.T], args.cpu_seconds)
         cpu = {"value": sample["seconds"] / sample["layer_calls_one_sequence"] * 1e6, "unit": "us/layer", "cores": 1,
                "kind": "oracle", "sample": f"{sample['layer_calls_one_sequence']} whole layer calls (all {w.Hkv} KV heads), "
                                            f"{sample['seconds']:.1f} s"}
     cache.close()
     return {
-        "metric": "sparse_attn_decode_offload_us_per_layer", "value": us, "unit": "us/layer", "steps": steps,
+        "metric": "sparse_attn_decode_offload_us_per_layer" + (f"_dynamic_rope_{args.rope}" if rope else "")
+        + ("_fp8_kv" if kv_scales else ""), "value": us, "unit": "us/layer", "steps": steps,
         "warmup": warmup,
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
-                   "n_stream": w.n_stream, "block_tokens": bt, "mask_bank_MiB": mask_slots * bt * 256 >> 20,
-                   "sa_bank_MiB": sa_slots * bt * 512 >> 20, "needles": "Zipf(1.1) over scrambled chunk ranks"},
+                   "n_stream": w.n_stream, "block_tokens": bt, "mask_bank_MiB": mask_slots * bt * row_bytes >> 20,
+                   "sa_bank_MiB": sa_slots * bt * 2 * row_bytes >> 20, "needles": "Zipf(1.1) over scrambled chunk ranks"},
         "roofline": None, "cpu_baseline": cpu, "cache": hit, "kernels": kernels, "setup_s": t_setup,
     }
 

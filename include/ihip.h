@@ -406,6 +406,16 @@ size_t  ihip_cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t
 int32_t ihip_cache_create(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k,
                           ihip_tensor host_v, int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens,
                           int32_t mask_slots, int32_t sa_slots, void *stream);
+/*
+ * The same tier over E4M3 K/V (FP8 KV cache, see ihip_*_fp8kv): host_k / host_v hold bytes, their
+ * strides count bytes (multiples of 16), the banks hold 128-byte rows.  Such a cache is read through
+ * ihip_decode_layer_ex with kv_fp8 set and the scales given there.
+ */
+size_t  ihip_cache_device_bytes_fp8(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens,
+                                    int32_t mask_slots, int32_t sa_slots);
+int32_t ihip_cache_create_fp8(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k,
+                              ihip_tensor host_v, int32_t B, int32_t Hkv, int64_t T_alloc,
+                              int32_t block_tokens, int32_t mask_slots, int32_t sa_slots, void *stream);
 void    ihip_cache_destroy(ihip_cache *cache);
 int32_t ihip_cache_reset(ihip_cache *cache, void *stream);
 int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache,
@@ -426,8 +436,9 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
  *   stage_starts  mask-caching state as in ihip_decode_layer_masked, or NULL;
  *   first_stage   first stage to recompute (needs stage_starts unless 0)
  * Paged, FP8 and RoPE combine freely with each other, with either pooling rule
- * and with mask caching; the host tier (contiguous bf16 K/V) combines with RoPE,
- * pooling and mask caching (IHIP_ERR_UNSUPPORTED otherwise).  With stage_starts the scratch is the
+ * and with mask caching; the host tier (contiguous K/V) combines with FP8 (a
+ * cache made by ihip_cache_create_fp8), RoPE, pooling and mask caching
+ * (IHIP_ERR_UNSUPPORTED otherwise).  With stage_starts the scratch is the
  * scores buffer plus the attention partials (IHIP_OP_DECODE_LAYER covers it);
  * out_block_starts, if given, receives a copy of the final list.
  */

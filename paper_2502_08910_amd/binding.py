@@ -89,6 +89,9 @@ EXPORTS = {
     "ihip_prefill_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
                                    vp, vp, vp, vp, c_sz, vp]),
     "ihip_cache_device_bytes": (c_sz, [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32]),
+    "ihip_cache_device_bytes_fp8": (c_sz, [c_i32, c_i32, c_i64, c_i32, c_i32, c_i32]),
+    "ihip_cache_create_fp8": (c_i32, [ctypes.POINTER(vp), vp, c_sz, Tensor, Tensor, c_i32, c_i32, c_i64, c_i32,
+                                      c_i32, c_i32, vp]),
     "ihip_cache_create": (c_i32, [ctypes.POINTER(vp), vp, c_sz, Tensor, Tensor, c_i32, c_i32, c_i64, c_i32,
                                   c_i32, c_i32, vp]),
     "ihip_cache_destroy": (None, [vp]),
@@ -540,18 +543,23 @@ def first_stage_due(step: int, refresh: Sequence[int]) -> int:
 class HostKVCache:
     """Host-resident K/V (pinned memory) with the on-GPU hot-block cache.
 
-    host_k / host_v: pinned bf16 CPU tensors [B,Hkv,T,d] (torch's
-    pin_memory=True); the banks and tables are carved out of one device
-    buffer allocated here through PyTorch and kept alive with the handle."""
+    host_k / host_v: pinned CPU tensors [B,Hkv,T,d] (torch's pin_memory=True),
+    bf16 or -- for an FP8 KV cache -- uint8 holding E4M3 bytes; the banks and
+    tables are carved out of one device buffer allocated here through PyTorch
+    and kept alive with the handle."""
 
     def __init__(self, host_k: torch.Tensor, host_v: torch.Tensor, block_tokens: int, mask_slots: int,
                  sa_slots: int, device="cuda:0"):
+        self.fp8 = host_k.dtype in (torch.uint8, torch.float8_e4m3fn)
         for t, name in ((host_k, "host_k"), (host_v, "host_v")):
-            if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1 or t.is_cuda or not t.is_pinned():
-                raise IhipError(f"{name}: need a pinned 4-d bf16 CPU tensor with contiguous last dim")
+            if t.dtype != host_k.dtype or (not self.fp8 and t.dtype != torch.bfloat16) or t.dim() != 4 \
+                    or t.stride(3) != 1 or t.is_cuda or not t.is_pinned():
+                raise IhipError(f"{name}: need a pinned 4-d bf16 (or E4M3 byte) CPU tensor with contiguous last dim")
         self.host_k, self.host_v = host_k, host_v
         B, Hkv, T, _ = host_k.shape
-        need = lib().ihip_cache_device_bytes(B, Hkv, T, block_tokens, mask_slots, sa_slots)
+        size_fn = lib().ihip_cache_device_bytes_fp8 if self.fp8 else lib().ihip_cache_device_bytes
+        make_fn = lib().ihip_cache_create_fp8 if self.fp8 else lib().ihip_cache_create
+        need = size_fn(B, Hkv, T, block_tokens, mask_slots, sa_slots)
         if need == 0:
             raise IhipError("ihip_cache_device_bytes: bad sizes")
         self.dev_mem = torch.empty(need, dtype=torch.uint8, device=device)
@@ -559,8 +567,8 @@ class HostKVCache:
         hk = Tensor(host_k.data_ptr(), host_k.stride(0), host_k.stride(1), host_k.stride(2))
         hv = Tensor(host_v.data_ptr(), host_v.stride(0), host_v.stride(1), host_v.stride(2))
         with torch.cuda.device(self.dev_mem.device):
-            _check(lib().ihip_cache_create(ctypes.byref(self.handle), self.dev_mem.data_ptr(), need, hk, hv,
-                                           B, Hkv, T, block_tokens, mask_slots, sa_slots, _stream()))
+            _check(make_fn(ctypes.byref(self.handle), self.dev_mem.data_ptr(), need, hk, hv,
+                           B, Hkv, T, block_tokens, mask_slots, sa_slots, _stream()))
         self.block_tokens, self.mask_slots, self.sa_slots = block_tokens, mask_slots, sa_slots
         self.n_blocks_total = B * Hkv * ((T + block_tokens - 1) // block_tokens)
 

@@ -83,6 +83,7 @@ int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_t
                            void *, const BankView *, const ihip_rope *, hipStream_t, const KvFormat * = nullptr);
 BankView cache_bank_view(const ihip_cache *, int);
 void cache_describe(const ihip_cache *, int32_t *, int32_t *, int64_t *, ihip_tensor *, ihip_tensor *);
+bool cache_holds_fp8(const ihip_cache *);
 size_t attn_decode_workspace(const ihip_shape &, int, int);
 int32_t launch_attn_prefill(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                             const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
@@ -622,6 +623,8 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
 {
     const char *who = "ihip_decode_layer_cached";
     if (!cache) return fail(IHIP_ERR_INVALID_ARG, "%s: cache is NULL", who);
+    if (cache_holds_fp8(cache))
+        return fail(IHIP_ERR_INVALID_ARG, "%s: the host tier holds E4M3 rows: pass the scales through ihip_decode_layer_ex", who);
     int32_t B, Hkv;
     int64_t T_alloc;
     ihip_tensor hk, hv;
@@ -671,8 +674,10 @@ int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor
     if (opt->first_stage != 0 && !opt->stage_starts)
         return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d without stage_starts", who, opt->first_stage);
     if (opt->cache) {
-        if (opt->paged || opt->kv_fp8)
-            return fail(IHIP_ERR_UNSUPPORTED, "%s: the host tier holds contiguous bf16 K/V", who);
+        if (opt->paged) return fail(IHIP_ERR_UNSUPPORTED, "%s: the host tier holds contiguous K/V", who);
+        if (cache_holds_fp8(opt->cache) != (opt->kv_fp8 != 0))
+            return fail(IHIP_ERR_INVALID_ARG, "%s: the host tier holds %s rows", who,
+                        cache_holds_fp8(opt->cache) ? "E4M3" : "bf16");
         int32_t B, Hkv;
         int64_t T_alloc;
         cache_describe(opt->cache, &B, &Hkv, &T_alloc, &k, &v);

@@ -27,7 +27,7 @@ struct Bank {
     int32_t *miss_list;       // [n_gb]
     int32_t *victims;         // [n_slots]
     unsigned long long *counters;   // [8]: hit blocks, missed blocks (cumulative), last call's misses, touches, insertions
-    uint16_t *bank_k, *bank_v;      // [n_slots][block][d]; bank_v null for the keys-only bank
+    uint16_t *bank_k, *bank_v;      // [n_slots][block][row]; bank_v null for the keys-only bank
 };
 
 }  // namespace ihip
@@ -36,7 +36,8 @@ struct ihip_cache {
     int B, Hkv;
     int64_t T_alloc;
     int block_tokens, block_log2, blocks_per_head, n_gb;
-    ihip_tensor host_k, host_v;
+    ihip_tensor host_k, host_v;   // as given: strides in elements (bf16) or bytes (E4M3)
+    int row_units;                // 2-byte units per row: d (bf16) or d/2 (E4M3)
     ihip::Bank bank[2];
     uint32_t stamp;           // counter of the current layer call (starts at 1)
 };
@@ -48,7 +49,8 @@ constexpr int kCacheThreads = 1024;
 static size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // carve one bank out of dev memory starting at *off (or just measure when base == nullptr)
-static void carve_bank(Bank &b, char *base, size_t &off, int n_gb, int n_slots, int block_tokens, bool has_v)
+static void carve_bank(Bank &b, char *base, size_t &off, int n_gb, int n_slots, int block_tokens, bool has_v,
+                       int row_units)
 {
     auto take = [&](size_t bytes) { char *p = base ? base + off : nullptr; off += a256(bytes); return p; };
     b.n_slots = n_slots;
@@ -60,8 +62,8 @@ static void carve_bank(Bank &b, char *base, size_t &off, int n_gb, int n_slots, 
     b.miss_list = (int32_t *)take((size_t)n_gb * 4);
     b.victims = (int32_t *)take((size_t)n_slots * 4);
     b.counters = (unsigned long long *)take(8 * 8);
-    b.bank_k = (uint16_t *)take((size_t)n_slots * block_tokens * kD * 2);
-    b.bank_v = has_v ? (uint16_t *)take((size_t)n_slots * block_tokens * kD * 2) : nullptr;
+    b.bank_k = (uint16_t *)take((size_t)n_slots * block_tokens * row_units * 2);
+    b.bank_v = has_v ? (uint16_t *)take((size_t)n_slots * block_tokens * row_units * 2) : nullptr;
 }
 
 __global__ void cache_init_kernel(const Bank b, const int n_gb)
@@ -154,7 +156,8 @@ __global__ __launch_bounds__(kCacheThreads) void cache_victims_kernel(const Bank
 // workgroup i: evict victims[i], install miss_list[i] there and copy its rows from host memory
 __global__ __launch_bounds__(256) void cache_insert_kernel(const Bank b, const ihip_tensor hk, const ihip_tensor hv,
                                                            const int Hkv, const int64_t T_alloc, const int block_log2,
-                                                           const int blocks_per_head, const uint32_t stamp)
+                                                           const int blocks_per_head, const uint32_t stamp,
+                                                           const int row_units)
 {
     const int i = blockIdx.x;
     if (i >= (int)b.counters[4]) return;
@@ -170,18 +173,19 @@ __global__ __launch_bounds__(256) void cache_insert_kernel(const Bank b, const i
     const int bg = gb / blocks_per_head, blk = gb % blocks_per_head;
     const int bb = bg / Hkv, g = bg % Hkv;
     const int bt = 1 << block_log2;
-    const int l16 = threadIdx.x & 15;
+    const int lanes = row_units >> 3;                 // 16-byte pieces per row: 16 (bf16) or 8 (E4M3)
+    const int piece = threadIdx.x % lanes;
     const uint16_t *src_k = (const uint16_t *)hk.ptr + bb * hk.stride_b + g * hk.stride_h;
     const uint16_t *src_v = (const uint16_t *)hv.ptr + bb * hv.stride_b + g * hv.stride_h;
-    for (int r = threadIdx.x >> 4; r < bt; r += 16) {
+    for (int r = threadIdx.x / lanes; r < bt; r += 256 / lanes) {
         const int64_t pos = ((int64_t)blk << block_log2) + r;
         if (pos >= T_alloc) break;
-        const int64_t dst = (((int64_t)slot << block_log2) + r) * kD + l16 * 8;
+        const int64_t dst = (((int64_t)slot << block_log2) + r) * row_units + piece * 8;
         *reinterpret_cast<uint4 *>(b.bank_k + dst) =
-            *reinterpret_cast<const uint4 *>(src_k + pos * hk.stride_t + l16 * 8);
+            *reinterpret_cast<const uint4 *>(src_k + pos * hk.stride_t + piece * 8);
         if (b.bank_v != nullptr)
             *reinterpret_cast<uint4 *>(b.bank_v + dst) =
-                *reinterpret_cast<const uint4 *>(src_v + pos * hv.stride_t + l16 * 8);
+                *reinterpret_cast<const uint4 *>(src_v + pos * hv.stride_t + piece * 8);
     }
 }
 
@@ -198,8 +202,11 @@ BankView cache_bank_view(const ihip_cache *c, int which)
     v.block_log2 = c->block_log2;
     v.blocks_per_head = c->blocks_per_head;
     v.stamp = c->stamp;
+    v.row_units = c->row_units;
     return v;
 }
+
+bool cache_holds_fp8(const ihip_cache *c) { return c->row_units != kD; }
 
 void cache_describe(const ihip_cache *c, int32_t *B, int32_t *Hkv, int64_t *T_alloc, ihip_tensor *hk, ihip_tensor *hv)
 {
@@ -220,8 +227,8 @@ using namespace ihip;
 
 extern "C" {
 
-size_t ihip_cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
-                               int32_t sa_slots)
+static size_t cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
+                                 int32_t sa_slots, int row_units)
 {
     if (B <= 0 || Hkv <= 0 || T_alloc <= 0 || block_tokens <= 0 || (block_tokens & (block_tokens - 1)) ||
         mask_slots <= 0 || sa_slots <= 0)
@@ -230,28 +237,42 @@ size_t ihip_cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t 
     if (n_gb > 0x7fffffff) return 0;
     Bank b;
     size_t off = 0;
-    carve_bank(b, nullptr, off, (int)n_gb, mask_slots, block_tokens, false);
-    carve_bank(b, nullptr, off, (int)n_gb, sa_slots, block_tokens, true);
+    carve_bank(b, nullptr, off, (int)n_gb, mask_slots, block_tokens, false, row_units);
+    carve_bank(b, nullptr, off, (int)n_gb, sa_slots, block_tokens, true, row_units);
     return off;
 }
 
-int32_t ihip_cache_create(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k, ihip_tensor host_v,
-                          int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
-                          int32_t sa_slots, void *stream)
+size_t ihip_cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
+                               int32_t sa_slots)
 {
-    const char *who = "ihip_cache_create";
+    return cache_device_bytes(B, Hkv, T_alloc, block_tokens, mask_slots, sa_slots, kD);
+}
+
+size_t ihip_cache_device_bytes_fp8(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
+                                   int32_t sa_slots)
+{
+    return cache_device_bytes(B, Hkv, T_alloc, block_tokens, mask_slots, sa_slots, kD / 2);
+}
+
+static int32_t cache_create(const char *who, int row_units, ihip_cache **out, void *dev_mem, size_t dev_bytes,
+                            ihip_tensor host_k, ihip_tensor host_v, int32_t B, int32_t Hkv, int64_t T_alloc,
+                            int32_t block_tokens, int32_t mask_slots, int32_t sa_slots, void *stream)
+{
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
-    const size_t need = ihip_cache_device_bytes(B, Hkv, T_alloc, block_tokens, mask_slots, sa_slots);
+    const size_t need = cache_device_bytes(B, Hkv, T_alloc, block_tokens, mask_slots, sa_slots, row_units);
     if (need == 0) return fail(IHIP_ERR_INVALID_ARG, "%s: bad sizes (block_tokens must be a power of two)", who);
     if (mask_slots > 65536 * 16 || sa_slots > 65536 * 16)
         return fail(IHIP_ERR_UNSUPPORTED, "%s: at most 1,048,576 slots per bank", who);
     if (!dev_mem || dev_bytes < need || ((uintptr_t)dev_mem & 255))
         return fail(IHIP_ERR_WORKSPACE, "%s: %zu bytes of 256-byte aligned device memory needed, %zu given", who, need,
                     dev_bytes);
+    // strides: elements for bf16 rows (multiples of 8), bytes for E4M3 rows (multiples of 16)
+    const int64_t sm = row_units == kD ? 7 : 15;
     if (!host_k.ptr || !host_v.ptr || ((uintptr_t)host_k.ptr & 15) || ((uintptr_t)host_v.ptr & 15) ||
-        (host_k.stride_t & 7) || (host_v.stride_t & 7) || (host_k.stride_h & 7) || (host_v.stride_h & 7) ||
-        (host_k.stride_b & 7) || (host_v.stride_b & 7))
+        (host_k.stride_t & sm) || (host_v.stride_t & sm) || (host_k.stride_h & sm) || (host_v.stride_h & sm) ||
+        (host_k.stride_b & sm) || (host_v.stride_b & sm))
         return fail(IHIP_ERR_INVALID_ARG, "%s: host K/V must be non-NULL with 16-byte aligned rows", who);
+
     // the kernels dereference these pointers: insist on pinned, GPU-addressable host memory
     for (ihip_tensor *t : {&host_k, &host_v}) {
         hipPointerAttribute_t attr;
@@ -270,13 +291,30 @@ int32_t ihip_cache_create(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihi
     c->blocks_per_head = (int)((T_alloc + block_tokens - 1) / block_tokens);
     c->n_gb = B * Hkv * c->blocks_per_head;
     c->host_k = host_k; c->host_v = host_v;
+    c->row_units = row_units;
     size_t off = 0;
-    carve_bank(c->bank[0], (char *)dev_mem, off, c->n_gb, mask_slots, block_tokens, false);
-    carve_bank(c->bank[1], (char *)dev_mem, off, c->n_gb, sa_slots, block_tokens, true);
+    carve_bank(c->bank[0], (char *)dev_mem, off, c->n_gb, mask_slots, block_tokens, false, row_units);
+    carve_bank(c->bank[1], (char *)dev_mem, off, c->n_gb, sa_slots, block_tokens, true, row_units);
     const int32_t rc = init_banks(c, (hipStream_t)stream);
     if (rc != IHIP_OK) { delete c; return rc; }
     *out = c;
     return IHIP_OK;
+}
+
+int32_t ihip_cache_create(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k, ihip_tensor host_v,
+                          int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
+                          int32_t sa_slots, void *stream)
+{
+    return cache_create("ihip_cache_create", kD, out, dev_mem, dev_bytes, host_k, host_v, B, Hkv, T_alloc,
+                        block_tokens, mask_slots, sa_slots, stream);
+}
+
+int32_t ihip_cache_create_fp8(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k,
+                              ihip_tensor host_v, int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens,
+                              int32_t mask_slots, int32_t sa_slots, void *stream)
+{
+    return cache_create("ihip_cache_create_fp8", kD / 2, out, dev_mem, dev_bytes, host_k, host_v, B, Hkv, T_alloc,
+                        block_tokens, mask_slots, sa_slots, stream);
 }
 
 void ihip_cache_destroy(ihip_cache *c) { delete c; }
@@ -303,8 +341,11 @@ int32_t ihip_cache_update(ihip_cache *c, void *stream)
         }
         {
             KernelTimer t(w == 0 ? "cache_insert.mask" : "cache_insert.sa", st);
-            hipLaunchKernelGGL(cache_insert_kernel, dim3(b.n_slots), dim3(256), 0, st, b, c->host_k, c->host_v, c->Hkv,
-                               c->T_alloc, c->block_log2, c->blocks_per_head, c->stamp);
+            ihip_tensor hk = c->host_k, hv = c->host_v;      // the kernel counts in 2-byte units
+            if (c->row_units != kD)
+                for (ihip_tensor *x : {&hk, &hv}) { x->stride_b /= 2; x->stride_h /= 2; x->stride_t /= 2; }
+            hipLaunchKernelGGL(cache_insert_kernel, dim3(b.n_slots), dim3(256), 0, st, b, hk, hv, c->Hkv,
+                               c->T_alloc, c->block_log2, c->blocks_per_head, c->stamp, c->row_units);
         }
     }
     c->stamp += 1;

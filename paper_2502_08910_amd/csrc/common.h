@@ -129,6 +129,7 @@ struct BankView {
     int block_log2;
     int blocks_per_head;         // blocks of one (sequence, KV head)
     uint32_t stamp;              // this call's counter value
+    int row_units;               // 2-byte units of one row: d for bf16 rows, d/2 for E4M3 rows
 };
 
 struct CachedRows {
@@ -148,7 +149,7 @@ struct CachedRows {
             else c.miss_flag[gb] = 1;
         }
         if (slot >= 0)
-            return bank + ((((int64_t)slot << c.block_log2) | (pos & ((1 << c.block_log2) - 1))) * kD);
+            return bank + ((((int64_t)slot << c.block_log2) | (pos & ((1 << c.block_log2) - 1))) * c.row_units);
         return host_base + (int64_t)pos * host_st;
     }
 };

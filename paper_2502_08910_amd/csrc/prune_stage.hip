@@ -597,7 +597,9 @@ static void launch_decode(const PruneArgs &a, int P, bool fp8, hipStream_t st)
     constexpr int U = 2;
     dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
     KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
-    if (fp8 && a.paged.block_table != nullptr)
+    if (fp8 && a.bank.page_table != nullptr)
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, 1, true>), grid, dim3(256), 0, st, a);
+    else if (fp8 && a.paged.block_table != nullptr)
         hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, true>), grid, dim3(256), 0, st, a);
     else if (fp8)
         hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, true>), grid, dim3(256), 0, st, a);
@@ -637,8 +639,10 @@ int32_t launch_prune_stage(const ihip_shape &s, const ihip_tensor &q, const ihip
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (max_chunks == 0 || P == 0) return IHIP_OK;
     if (bank && s.b_q != 1) return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: the host tier serves decode only");
-    if (fp8 && (s.b_q != 1 || bank))
-        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: FP8 keys are built for decode from device memory only");
+    if (fp8 && s.b_q != 1)
+        return fail(IHIP_ERR_UNSUPPORTED, "prune_stage: FP8 keys are built for decode only");
+    if (bank && (bank->row_units == kD) == fp8)
+        return fail(IHIP_ERR_INVALID_ARG, "prune_stage: the host tier holds %s rows", fp8 ? "bf16" : "E4M3");
     RopeView rope_view{nullptr, nullptr, 0};
     int rope_style = 0;
     if (rope && rope->prune_style != IHIP_ROPE_NONE) {

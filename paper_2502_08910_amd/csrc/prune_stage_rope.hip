@@ -273,7 +273,8 @@ template <int G>
 static void launch_rope_g(const PruneArgs &a, const RopeView &rope, int style, int P, bool fp8, hipStream_t st)
 {
     const bool paged = a.paged.block_table != nullptr;
-    if (a.bank.page_table != nullptr) launch_rope<G, 1, false>(a, rope, style, P, st);     // host tier: bf16, contiguous
+    if (a.bank.page_table != nullptr && fp8) launch_rope<G, 1, true>(a, rope, style, P, st);   // host tier
+    else if (a.bank.page_table != nullptr) launch_rope<G, 1, false>(a, rope, style, P, st);
     else if (paged && fp8) launch_rope<G, 2, true>(a, rope, style, P, st);
     else if (paged) launch_rope<G, 2, false>(a, rope, style, P, st);
     else if (fp8) launch_rope<G, 0, true>(a, rope, style, P, st);

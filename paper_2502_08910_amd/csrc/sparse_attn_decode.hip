@@ -410,14 +410,14 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
         a.rope_cos = rope->cos;
         a.rope_sin = rope->sin;
     }
+    if (bank && (bank->row_units == kD) == fp8)
+        return fail(IHIP_ERR_INVALID_ARG, "sparse_attn_decode: the host tier holds %s rows", fp8 ? "bf16" : "E4M3");
     a.bank = bank ? *bank : BankView{};
     a.ge = make_geometry(s);
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
     a.v = (const uint16_t *)v.ptr; a.v_sb = v.stride_b; a.v_sh = v.stride_h; a.v_st = v.stride_t;
     if (fp8) {
-        if (bank)
-            return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_decode: FP8 K/V is built for decode from device memory only");
         a.k_sb /= 2; a.k_sh /= 2; a.k_st /= 2;      // byte strides (even) in 2-byte units
         a.v_sb /= 2; a.v_sh /= 2; a.v_st /= 2;
     }
@@ -446,8 +446,7 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     else if (fp8) IHIP_AD_KERNEL(GG, SRCV, false, true);                                                            \
     else IHIP_AD_KERNEL(GG, SRCV, false, false)
 #define IHIP_AD_LAUNCH(GG)                                                                                          \
-    if (bank && use_rope) IHIP_AD_KERNEL(GG, 1, true, false);                                                       \
-    else if (bank) IHIP_AD_KERNEL(GG, 1, false, false);                                                             \
+    if (bank) { IHIP_AD_BY_FMT(GG, 1); }                                                                            \
     else if (paged) { IHIP_AD_BY_FMT(GG, 2); }                                                                      \
     else { IHIP_AD_BY_FMT(GG, 0); }
     case 1: IHIP_AD_LAUNCH(1); break;

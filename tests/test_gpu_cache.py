@@ -203,3 +203,56 @@ def test_host_tier_with_dynamic_rope(ihip, orc, style):
                 assert pt.tolist() == sim[bank].page_table, (call, name)
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("rope", [False, True])
+def test_host_tier_with_fp8_rows(ihip, orc, rope):
+    # FP8 KV cache behind the host tier (128-byte rows in host memory and in the banks), with and
+    # without dynamic RoPE: same bits as the resident FP8 path, banks follow the oracle's touches.
+    from workloads import gen
+    w = configs.shrink(configs.CFG1, B=2, Hq=8, Hkv=2, T=4096 + 29, n_stream=256, n_needles=0,
+                       stages=((64, 8), (16, 8), (4, 16)))
+    bt, mask_slots, sa_slots = 64, 40, 24
+    chunks, keeps = [s[0] for s in w.stages], [s[1] for s in w.stages]
+    _, k, v, _, _ = configs.make_inputs(w, 0, kind="int")
+    scales = (0.5, 0.25)
+    k8, v8 = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
+    sl = torch.tensor([w.T, w.T - 700], dtype=torch.int32)
+    cos, sin = gen.quarter_turn_table(w.T, w.d)
+    rp = ihip.Rope(cos.cuda(), sin.cuda(), ihip.ROPE_RELATIVE, ihip.ROPE_STREAMING) if rope else None
+    spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune="relative", attn="streaming") if rope else None
+    hk = torch.empty(k8.shape, dtype=torch.uint8, pin_memory=True).copy_(k8)
+    hv = torch.empty(v8.shape, dtype=torch.uint8, pin_memory=True).copy_(v8)
+    kd, vd, sld = k8.cuda(), v8.cuda(), sl.cuda()
+    cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots)
+    blocks_per_head = (w.T + bt - 1) // bt
+    sim = [orc.LruBank(cache.n_blocks_total, mask_slots), orc.LruBank(cache.n_blocks_total, sa_slots)]
+    try:
+        for call, seed in enumerate([0, 1, 0, 2]):
+            q = configs.make_q(w, seed, kind="int")
+            qd = q.cuda()
+            L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
+            ref_blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+            ref = L.decode_layer(qd, kd, vd, chunks, keeps, out_blocks=ref_blocks, rope=rp, kv_scales=scales,
+                                 pooling=ihip.POOL_KV_HEAD)
+            got_blocks = torch.empty_like(ref_blocks)
+            got = L.decode_layer(qd, None, None, chunks, keeps, out_blocks=got_blocks, rope=rp, kv_scales=scales,
+                                 cache=cache)
+            cache.update()
+            torch.cuda.synchronize()
+            assert torch.equal(got_blocks, ref_blocks), call
+            assert torch.equal(got, ref), call
+            o = orc.Oracle(q, k8, v8, sl.tolist(), 1, w.n_sink, w.n_stream, rope=spec, kv_scales=scales)
+            res = o.layer(w.stages)
+            stats = cache.stats()
+            for bank, name in ((0, "mask"), (1, "sa")):
+                sim[bank].call(touched_blocks(o, w, res, bt, blocks_per_head, bank))
+                pt, sb = cache.tables(bank)
+                assert stats[name]["last_touched"] == sim[bank].last_touched, (call, name)
+                assert stats[name]["last_misses"] == sim[bank].last_misses, (call, name)
+                assert pt.tolist() == sim[bank].page_table, (call, name)
+        # a bf16 request against this cache is refused
+        with pytest.raises(ihip.IhipError):
+            L.decode_layer(qd, None, None, chunks, keeps, cache=cache)
+    finally:
+        cache.close()
