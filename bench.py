@@ -70,6 +70,9 @@ def parse():
     ap.add_argument("--rope", default=None, choices=["relative", "chunk"],
                     help="decode and prefill workloads: dynamic RoPE in the pruning stages (this style) and the attention "
                          "(streaming style); a separate metric, no roofline / cpu_baseline objects")
+    ap.add_argument("--graph", action="store_true",
+                    help="decode and prefill workloads: capture the timed steps into one HIP graph and time its replay "
+                         "(a separate metric)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 = skip)")
     ap.add_argument("--no-profile-pass", action="store_true")
@@ -88,17 +91,29 @@ def progress(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def timed_passes(step, steps, warmup, ihip, torch, profile):
+def timed_passes(step, steps, warmup, ihip, torch, profile, graph=False):
     """W warm-up steps, K timed steps between synchronisations, then (optionally)
-    the same K steps again with HIP events around every kernel launch."""
+    the same K steps again with HIP events around every kernel launch.
+    graph: the K steps are captured into one HIP graph (the library neither allocates nor
+    synchronises) and one replay of it is timed, after one untimed replay."""
     progress("inputs ready")
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     progress("warm-up done")
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(i)
+    if graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                step(i)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+    else:
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
     torch.cuda.synchronize()
     us = (time.perf_counter() - t0) / steps * 1e6
     progress(f"{steps} timed steps done")
@@ -246,7 +261,7 @@ def bench_decode(args, w, torch, ihip, configs):
                        paged=paged, stage_starts=state,
                        first_stage=ihip.first_stage_due(i, refresh) if refresh else None)
 
-    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
+    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass, args.graph)
 
     cpu = sample = None
     if args.cpu_seconds > 0 and not args.rope:
@@ -284,7 +299,8 @@ def bench_decode(args, w, torch, ihip, configs):
                         "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
     return {
         "metric": ("sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer")
-        + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else "") + ("_fp8_kv" if kv_scales else "") + (f"_paged{args.paged}_{args.paged_order}" if args.paged else ""),
+        + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else "") + ("_fp8_kv" if kv_scales else "") + (f"_paged{args.paged}_{args.paged_order}" if args.paged else "")
+        + ("_hip_graph" if args.graph else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name, "batch": w.B, "context": w.T, "q_heads": w.Hq, "kv_heads": w.Hkv,
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
@@ -340,7 +356,7 @@ def bench_prefill(args, w, torch, ihip, configs):
     def step(i):
         L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out, rope=rope, paged=paged)
 
-    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass)
+    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass, args.graph)
 
     # matrix-core flops actually multiplied, from the geometry alone
     flops = {}
@@ -407,7 +423,7 @@ def bench_prefill(args, w, torch, ihip, configs):
                "sample": f"{done} of {P} (KV head, query block) problems (KV head 0, blocks {blocks[:done]}), "
                          f"{secs:.1f} s; scaled x{P}/{done}"}
     return {
-        "metric": "sparse_attn_prefill_us_per_layer",
+        "metric": "sparse_attn_prefill_us_per_layer" + ("_hip_graph" if args.graph else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name + (f"_dynamic_rope_{args.rope}" if rope else "")
                    + (f"_paged{args.paged}_{args.paged_order}" if paged else ""), "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
