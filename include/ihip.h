@@ -140,8 +140,10 @@ int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
  * count bytes; rows are 128 bytes, 16-byte aligned.  Q and the output stay
  * bf16.  Chunk scores are k_scale * (q . decoded k) in fp32 (the selection does
  * not depend on the scale); the attention multiplies its scores by k_scale and
- * its output by v_scale.  Built for decode (Tq == b_q == 1) from device memory
- * without dynamic RoPE.
+ * its output by v_scale.  Built for decode (Tq == b_q == 1); these entry points
+ * read contiguous (strided) device memory without dynamic RoPE, and
+ * ihip_decode_layer_ex combines E4M3 rows with RoPE, page pools or the host tier.
+ * Chunked prefill over E4M3 rows returns IHIP_ERR_UNSUPPORTED.
  */
 int32_t ihip_prune_stage_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                                const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
