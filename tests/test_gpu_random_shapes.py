@@ -1,0 +1,153 @@
+"""Seeded random shapes and plans, every variant switched on at random: the layer
+calls against the oracle run with the same options.  Integer-valued inputs, the
+quarter-turn rotary table and power-of-two FP8 scales make every score exact, so
+the kept block lists must agree bit for bit; outputs within 2e-2.
+
+The draws stay inside what the entry points document (shape and plan checks);
+they aim at what the fixed cases do not hit together: odd sequence lengths,
+sequences shorter than sink + window, sinks and windows that are no multiple of
+anything, budgets larger than the number of chunks, chunk sizes down to 1, pages
+down to one token, three KV heads, every group size."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import configs, gen  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def ihip():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_08910_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def orc():
+    import oracle
+    oracle.build(force=False)
+    return oracle
+
+
+# IHIP_RANDOM_SEEDS=n widens the sweep to n draws per test (default: 14 decode, 10 prefill)
+N_DECODE = int(os.environ.get("IHIP_RANDOM_SEEDS", "14"))
+N_PREFILL = int(os.environ.get("IHIP_RANDOM_SEEDS", "10"))
+
+
+def scatter_to_pages(k, v, page, seed, fill):
+    B, Hkv, T, d = k.shape
+    per_seq = (T + page - 1) // page
+    n_pages = B * per_seq + 3
+    order = gen.distinct_ints(seed, 77, B * per_seq, n_pages).view(B, per_seq)
+    k_pool = torch.full((n_pages, Hkv, page, d), fill, dtype=k.dtype)
+    v_pool = torch.full((n_pages, Hkv, page, d), fill, dtype=v.dtype)
+    pad = per_seq * page - T
+    kp = torch.nn.functional.pad(k, (0, 0, 0, pad)).view(B, Hkv, per_seq, page, d)
+    vp = torch.nn.functional.pad(v, (0, 0, 0, pad)).view(B, Hkv, per_seq, page, d)
+    for b in range(B):
+        k_pool[order[b]] = kp[b].permute(1, 0, 2, 3)
+        v_pool[order[b]] = vp[b].permute(1, 0, 2, 3)
+    return k_pool, v_pool, order.to(torch.int32)
+
+
+def draw_plan(rng, first_choices):
+    chunks = [int(rng.choice(first_choices))]
+    while chunks[-1] > 1 and len(chunks) < 4 and rng.random() < 0.75:
+        chunks.append(chunks[-1] // int(rng.choice([2, 4] if chunks[-1] >= 4 else [2])))
+    keeps = [int(rng.integers(1, 40)) for _ in chunks]
+    return list(zip(chunks, keeps))
+
+
+def check_against_oracle(w, o, sl, blocks, out, b_q, pooled):
+    for b in range(w.B):
+        for m in range(w.Tq // b_q):
+            prs = o.prune_all_heads(b, m, w.stages) if pooled else [o.prune(b, g, m, w.stages) for g in range(w.Hkv)]
+            for g in range(w.Hkv):
+                pr = prs[g]
+                p = (b * w.Hkv + g) * (w.Tq // b_q) + m
+                kp = blocks[p].cpu().numpy()
+                assert np.array_equal(kp[kp >= 0], pr.block_starts), (b, g, m)
+                ref, _ = o.attend(b, g, m, pr.block_starts, pr.block_lens)
+                got = out[b, g * w.G:(g + 1) * w.G, m * b_q:(m + 1) * b_q].float().cpu().numpy()
+                assert np.abs(got - ref).max() <= 2e-2, (b, g, m)
+
+
+@pytest.mark.parametrize("seed", range(N_DECODE))
+def test_random_decode_layer(ihip, orc, seed):
+    rng = np.random.default_rng(1000 + seed)
+    B, Hkv, G = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 4, 8]))
+    T = int(rng.integers(300, 3000))
+    n_sink, n_stream = int(rng.choice([0, 4, 100, 128])), int(rng.choice([1, 17, 256]))
+    stages = tuple(draw_plan(rng, [256, 64, 32, 8]))
+    w = configs.shrink(configs.CFG1, B=B, Hq=Hkv * G, Hkv=Hkv, T=T, n_sink=n_sink, n_stream=n_stream,
+                       n_needles=0, stages=stages)
+    sl = torch.tensor([T if b == 0 else int(rng.integers(1, T + 1)) for b in range(B)], dtype=torch.int32)
+    rope = rng.choice([None, "relative", "chunk"])
+    fp8, page = bool(rng.integers(0, 2)), int(rng.choice([0, 0, 1, 4, 16, 64]))
+    pooled = bool(rng.integers(0, 4) == 0)
+    q, k, v, _, _ = configs.make_inputs(w, seed, kind="int")
+    scales = (0.5, 0.25) if fp8 else None
+    if fp8:
+        k, v = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
+    cos, sin = gen.quarter_turn_table(20000, w.d)        # a row for every position or id any draw can ask for
+    spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune=str(rope), attn="streaming") if rope is not None else None
+    rp = None
+    if rope is not None:
+        style = ihip.ROPE_RELATIVE if rope == "relative" else ihip.ROPE_CHUNK_INDEXED
+        rp = ihip.Rope(cos.cuda(), sin.cuda(), style, ihip.ROPE_STREAMING)
+    pg = None
+    if page:
+        k_pool, v_pool, table = scatter_to_pages(k, v, page, seed, 7)
+        pg = ihip.PagedKV(k_pool.cuda(), v_pool.cuda(), table.cuda())
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    L = ihip.Layer(qd, kd, sl.cuda(), 1, n_sink, n_stream)
+    chunks, keeps = [s[0] for s in stages], [s[1] for s in stages]
+    blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+    out = L.decode_layer(qd, kd, vd, chunks, keeps, out_blocks=blocks, rope=rp, kv_scales=scales, paged=pg,
+                         pooling=ihip.POOL_ALL_HEADS if pooled else None)
+    torch.cuda.synchronize()
+    o = orc.Oracle(q, k, v, sl.tolist(), 1, n_sink, n_stream, rope=spec, kv_scales=scales)
+    check_against_oracle(w, o, sl, blocks, out, 1, pooled)
+
+
+@pytest.mark.parametrize("seed", range(N_PREFILL))
+def test_random_prefill_layer(ihip, orc, seed):
+    rng = np.random.default_rng(2000 + seed)
+    B, Hkv, G = int(rng.integers(1, 3)), int(rng.integers(1, 3)), int(rng.choice([1, 2, 4, 8]))
+    b_q = int(rng.choice([16, 32, 64]))
+    Tq = b_q * int(rng.integers(1, 4))
+    T = Tq + int(rng.integers(0, 1500))
+    n_sink, n_stream = int(rng.choice([0, 4, 100, 128])), b_q + int(rng.choice([0, 1, 70, 192]))
+    stages = tuple(draw_plan(rng, [64, 32, 16]))
+    w = configs.shrink(configs.CFG4, B=B, Hq=Hkv * G, Hkv=Hkv, T=T, Tq=Tq, b_q=b_q, n_sink=n_sink,
+                       n_stream=n_stream, stages=stages)
+    sl = torch.tensor([T if b == 0 else int(rng.integers(Tq, T + 1)) for b in range(B)], dtype=torch.int32)
+    rope = rng.choice([None, "relative", "chunk"])
+    page = int(rng.choice([0, 0, 1, 4, 16, 64]))
+    pooled = bool(rng.integers(0, 4) == 0)
+    q, k, v, _, _ = configs.make_inputs(w, seed, kind="int")
+    cos, sin = gen.quarter_turn_table(20000, w.d)
+    spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune=str(rope), attn="streaming") if rope is not None else None
+    rp = None
+    if rope is not None:
+        style = ihip.ROPE_RELATIVE if rope == "relative" else ihip.ROPE_CHUNK_INDEXED
+        rp = ihip.Rope(cos.cuda(), sin.cuda(), style, ihip.ROPE_STREAMING)
+    pg = None
+    if page:
+        k_pool, v_pool, table = scatter_to_pages(k, v, page, seed, 7.0)
+        pg = ihip.PagedKV(k_pool.cuda(), v_pool.cuda(), table.cuda())
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    L = ihip.Layer(qd, kd, sl.cuda(), b_q, n_sink, n_stream)
+    chunks, keeps = [s[0] for s in stages], [s[1] for s in stages]
+    blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+    out = L.prefill_layer(qd, kd, vd, chunks, keeps, out_blocks=blocks, rope=rp, paged=pg,
+                          pooling=ihip.POOL_ALL_HEADS if pooled else None)
+    torch.cuda.synchronize()
+    o = orc.Oracle(q, k, v, sl.tolist(), b_q, n_sink, n_stream, rope=spec)
+    check_against_oracle(w, o, sl, blocks, out, b_q, pooled)
