@@ -78,13 +78,26 @@ def check_against_oracle(w, o, sl, blocks, out, b_q, pooled):
                 assert np.abs(got - ref).max() <= 2e-2, (b, g, m)
 
 
-@pytest.mark.parametrize("seed", range(N_DECODE))
+def draw_large_plan(rng):
+    """Thousands of slots per problem: the wide selection kernels, several attention splits."""
+    chunks = [int(rng.choice([16, 8, 4]))]
+    while chunks[-1] > 1 and len(chunks) < 3 and rng.random() < 0.7:
+        chunks.append(chunks[-1] // 2)
+    keeps = [int(rng.integers(200, 1500)) for _ in chunks]
+    return list(zip(chunks, keeps))
+
+
+@pytest.mark.parametrize("seed", [pytest.param(s, id=f"large{s}") for s in range(100, 100 + max(4, N_DECODE // 3))]
+                         + list(range(N_DECODE)))
 def test_random_decode_layer(ihip, orc, seed):
     rng = np.random.default_rng(1000 + seed)
+    large = seed >= 100
     B, Hkv, G = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 4, 8]))
-    T = int(rng.integers(300, 3000))
+    T = int(rng.integers(300, 3000)) if not large else int(rng.integers(20000, 70000))
     n_sink, n_stream = int(rng.choice([0, 4, 100, 128])), int(rng.choice([1, 17, 256]))
-    stages = tuple(draw_plan(rng, [256, 64, 32, 8]))
+    stages = tuple(draw_plan(rng, [256, 64, 32, 8]) if not large else draw_large_plan(rng))
+    if large:
+        B, Hkv = min(B, 2), min(Hkv, 2)
     w = configs.shrink(configs.CFG1, B=B, Hq=Hkv * G, Hkv=Hkv, T=T, n_sink=n_sink, n_stream=n_stream,
                        n_needles=0, stages=stages)
     sl = torch.tensor([T if b == 0 else int(rng.integers(1, T + 1)) for b in range(B)], dtype=torch.int32)
@@ -95,7 +108,7 @@ def test_random_decode_layer(ihip, orc, seed):
     scales = (0.5, 0.25) if fp8 else None
     if fp8:
         k, v = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
-    cos, sin = gen.quarter_turn_table(20000, w.d)        # a row for every position or id any draw can ask for
+    cos, sin = gen.quarter_turn_table(20000 if not large else 60000, w.d)   # a row for every position or id a draw can ask for
     spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune=str(rope), attn="streaming") if rope is not None else None
     rp = None
     if rope is not None:
@@ -116,15 +129,20 @@ def test_random_decode_layer(ihip, orc, seed):
     check_against_oracle(w, o, sl, blocks, out, 1, pooled)
 
 
-@pytest.mark.parametrize("seed", range(N_PREFILL))
+@pytest.mark.parametrize("seed", [pytest.param(s, id=f"large{s}") for s in range(100, 100 + max(3, N_PREFILL // 3))]
+                         + list(range(N_PREFILL)))
 def test_random_prefill_layer(ihip, orc, seed):
     rng = np.random.default_rng(2000 + seed)
+    large = seed >= 100         # hundreds of kept chunks: long key lists, either attention kernel
     B, Hkv, G = int(rng.integers(1, 3)), int(rng.integers(1, 3)), int(rng.choice([1, 2, 4, 8]))
     b_q = int(rng.choice([16, 32, 64]))
     Tq = b_q * int(rng.integers(1, 4))
-    T = Tq + int(rng.integers(0, 1500))
+    T = Tq + (int(rng.integers(0, 1500)) if not large else int(rng.integers(4000, 14000)))
     n_sink, n_stream = int(rng.choice([0, 4, 100, 128])), b_q + int(rng.choice([0, 1, 70, 192]))
     stages = tuple(draw_plan(rng, [64, 32, 16]))
+    if large:
+        B, Hkv = 1, min(Hkv, 2)
+        stages = tuple((c, int(rng.integers(100, 400))) for c, _ in stages)
     w = configs.shrink(configs.CFG4, B=B, Hq=Hkv * G, Hkv=Hkv, T=T, Tq=Tq, b_q=b_q, n_sink=n_sink,
                        n_stream=n_stream, stages=stages)
     sl = torch.tensor([T if b == 0 else int(rng.integers(Tq, T + 1)) for b in range(B)], dtype=torch.int32)
@@ -132,7 +150,7 @@ def test_random_prefill_layer(ihip, orc, seed):
     page = int(rng.choice([0, 0, 1, 4, 16, 64]))
     pooled = bool(rng.integers(0, 4) == 0)
     q, k, v, _, _ = configs.make_inputs(w, seed, kind="int")
-    cos, sin = gen.quarter_turn_table(20000, w.d)
+    cos, sin = gen.quarter_turn_table(20000 if not large else 60000, w.d)
     spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune=str(rope), attn="streaming") if rope is not None else None
     rp = None
     if rope is not None:
