@@ -358,7 +358,9 @@ __global__ __launch_bounds__(kD) void attn_decode_merge_kernel(const AttnDecodeA
 // per CU with the plain kernel's registers), so that no workgroup has to wait for a free slot and
 // run its whole latency chain after the others have drained -- with 256-slot splits the cfg3 shape
 // had 1344 workgroups for 1024 places.  Between 256 and 1024 slots per split, a multiple of 16.
-static int decode_splits(const ihip_shape &s, int n_blocks, int block, int *slots_per_split)
+// wg_per_cu: 4 for the plain kernels, 3 for the RoPE instantiations (more registers).  The workspace
+// is sized for 4, which gives the most splits.
+static int decode_splits(const ihip_shape &s, int n_blocks, int block, int *slots_per_split, int wg_per_cu = 4)
 {
     static int n_cu = 0;
     if (n_cu == 0) {
@@ -369,7 +371,7 @@ static int decode_splits(const ihip_shape &s, int n_blocks, int block, int *slot
     }
     const int total = s.n_sink + n_blocks * block + s.n_stream;
     const int P = std::max(1, s.B * s.Hkv);
-    const int places = std::max(1, n_cu * 4 / P);              // splits per problem that run at once
+    const int places = std::max(1, n_cu * wg_per_cu / P);      // splits per problem that run at once
     int per = ((total + places - 1) / places + 15) / 16 * 16;
     per = std::min(kAttnMaxSplit, std::max(kAttnMinSplit, per));
     *slots_per_split = per;
@@ -426,7 +428,7 @@ int32_t launch_attn_decode(const ihip_shape &s, const ihip_tensor &q, const ihip
     a.block = block;
     a.block_log2 = __builtin_ctz(block);
     a.scale_log2e = sm_scale * 1.44269504088896340736f * (fp8 ? fmt->k_scale : 1.0f);
-    a.n_splits = decode_splits(s, n_blocks, block, &a.slots_per_split);
+    a.n_splits = decode_splits(s, n_blocks, block, &a.slots_per_split, use_rope ? 3 : 4);
     const int P = s.B * s.Hkv;
     const int G = a.ge.G;
     a.part_ml = (float *)ws;
