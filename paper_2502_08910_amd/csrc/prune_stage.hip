@@ -591,24 +591,43 @@ static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, const
     }
 }
 
+// U chunks per 16-lane group.  What counts is the number of row loads in flight per SIMD, waves x
+// 4 groups x U x G, and how finely the work is cut: U = 1 (64 registers, 8 waves per SIMD) is best
+// for every later stage, for small problems, for E4M3 rows and for pages; U = 3 (127 registers, 4
+// waves, half as many loads again in flight) wins on the large first stage over contiguous bf16 rows
+// (cfg3: 278 us against 283 us with U = 1 and 294 us with U = 2, whose 97 registers miss the fifth
+// wave by one).
+template <int G, int U>
+static void launch_decode_u(const PruneArgs &a, int P, bool fp8, hipStream_t st)
+{
+    dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
+    KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
+    if constexpr (U == 1) {
+        if (fp8 && a.bank.page_table != nullptr)
+            hipLaunchKernelGGL((prune_decode_kernel<G, U, 1, true>), grid, dim3(256), 0, st, a);
+        else if (fp8 && a.paged.block_table != nullptr)
+            hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, true>), grid, dim3(256), 0, st, a);
+        else if (fp8)
+            hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, true>), grid, dim3(256), 0, st, a);
+        else if (a.paged.block_table != nullptr)
+            hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, false>), grid, dim3(256), 0, st, a);
+        else if (a.bank.page_table != nullptr)
+            hipLaunchKernelGGL((prune_decode_kernel<G, U, 1, false>), grid, dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, false>), grid, dim3(256), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, false>), grid, dim3(256), 0, st, a);
+    }
+}
+
 template <int G>
 static void launch_decode(const PruneArgs &a, int P, bool fp8, hipStream_t st)
 {
-    constexpr int U = 2;
-    dim3 grid((a.max_chunks + 16 * U - 1) / (16 * U), P);
-    KernelTimer timer(stage_name(kNamePruneDecode, a.parent_starts == nullptr, a.chunk), st);
-    if (fp8 && a.bank.page_table != nullptr)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, 1, true>), grid, dim3(256), 0, st, a);
-    else if (fp8 && a.paged.block_table != nullptr)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, true>), grid, dim3(256), 0, st, a);
-    else if (fp8)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, true>), grid, dim3(256), 0, st, a);
-    else if (a.paged.block_table != nullptr)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, 2, false>), grid, dim3(256), 0, st, a);
-    else if (a.bank.page_table != nullptr)
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, 1, false>), grid, dim3(256), 0, st, a);
+    const bool plain = !fp8 && a.paged.block_table == nullptr && a.bank.page_table == nullptr;
+    if (plain && a.parent_starts == nullptr && a.chunk >= 128 && (int64_t)P * a.max_chunks >= 65536)
+        launch_decode_u<G, 3>(a, P, fp8, st);
     else
-        hipLaunchKernelGGL((prune_decode_kernel<G, U, 0, false>), grid, dim3(256), 0, st, a);
+        launch_decode_u<G, 1>(a, P, fp8, st);
 }
 
 int32_t launch_prune_stage_rope(const PruneArgs &a, const RopeView &rope, int style, int P, bool fp8, hipStream_t st);
