@@ -42,8 +42,8 @@ N_QUERY_SETS = 32
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see
 # profiles/.  Absent = not measured for that workload / kernel.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 781,315 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 1,211 KiB x 1.0 per launch
-    ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781314.8 * 2.0 + 1211.4) * 1024.0,
+    # FETCH_SIZE 781,843 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 1,229 KiB x 1.0 per launch
+    ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781842.8 * 2.0 + 1229.2) * 1024.0,
     # prefill kernels: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per launch
     ("cfg4-prefill-4k-on-256k", "prune_prefill.first.l64"): (794001.9 * 2.0 + 10518.0) * 1024.0,
     ("cfg4-prefill-4k-on-256k", "prune_prefill.l16"): (486601.0 * 2.0 + 2048.0) * 1024.0,
