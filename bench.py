@@ -58,7 +58,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg3-decode-1m-b8")
     ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
-                    help="decode workloads: fp8 = K and V quantised to E4M3 bytes (scale 1/64 each), a separate metric")
+                    help="fp8 = K and V quantised to E4M3 bytes (scale 1/64 each), a separate metric")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
                     help="decode and prefill workloads: K and V scattered into pages of this many tokens in a seeded random "
                          "order, read through a block table (a separate metric)")
@@ -323,6 +323,11 @@ def bench_prefill(args, w, torch, ihip, configs):
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t0
 
+    kv_scales = None
+    if args.kv_dtype == "fp8":
+        from workloads import gen
+        kv_scales = (1.0 / 64, 1.0 / 64)
+        k, v = gen.to_e4m3(k, kv_scales[0]), gen.to_e4m3(v, kv_scales[1])
     L = ihip.Layer(q, k, seq_lens, w.b_q, w.n_sink, w.n_stream)
     ws = L.workspace(ihip.OP_PREFILL_LAYER, chunks, keeps)
     out = torch.empty((w.B, w.Hq, w.Tq, w.d), dtype=torch.bfloat16, device=dev)
@@ -354,7 +359,7 @@ def bench_prefill(args, w, torch, ihip, configs):
         paged = ihip.PagedKV(k_pool, v_pool, order.to(torch.int32).contiguous())
 
     def step(i):
-        L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out, rope=rope, paged=paged)
+        L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out, rope=rope, paged=paged, kv_scales=kv_scales)
 
     us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass, args.graph)
 
@@ -399,7 +404,7 @@ def bench_prefill(args, w, torch, ihip, configs):
         ach = kernels[dom]["TFLOPs"]
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": None if rope or paged else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "traffic": None if rope or paged or kv_scales else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                     "flops_per_launch": flops[dom], "us_per_launch": kernels[dom]["us"],
                     "measured_mfma_rate": measured[dom.split(".")[0]],
                     "frac_of_measured_mfma_rate": ach / measured[dom.split(".")[0]]}
@@ -409,7 +414,8 @@ def bench_prefill(args, w, torch, ihip, configs):
         import oracle
         oracle.build(force=False)
         blocks = [0, w.Mq // 3, (2 * w.Mq) // 3, w.Mq - 1]
-        o = oracle.Oracle(q[:, :w.G].cpu(), k[:, :1].cpu(), v[:, :1].cpu(), [w.T] * w.B, w.b_q, w.n_sink, w.n_stream)
+        o = oracle.Oracle(q[:, :w.G].cpu(), k[:, :1].cpu(), v[:, :1].cpu(), [w.T] * w.B, w.b_q, w.n_sink, w.n_stream,
+                          kv_scales=kv_scales)
         t0 = time.perf_counter()
         done = 0
         for m in blocks:
@@ -423,7 +429,7 @@ def bench_prefill(args, w, torch, ihip, configs):
                "sample": f"{done} of {P} (KV head, query block) problems (KV head 0, blocks {blocks[:done]}), "
                          f"{secs:.1f} s; scaled x{P}/{done}"}
     return {
-        "metric": "sparse_attn_prefill_us_per_layer" + ("_hip_graph" if args.graph else ""),
+        "metric": "sparse_attn_prefill_us_per_layer" + ("_fp8_kv" if kv_scales else "") + ("_hip_graph" if args.graph else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
         "config": {"workload": w.name + (f"_dynamic_rope_{args.rope}" if rope else "")
                    + (f"_paged{args.paged}_{args.paged_order}" if paged else ""), "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,

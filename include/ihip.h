@@ -140,10 +140,12 @@ int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
  * count bytes; rows are 128 bytes, 16-byte aligned.  Q and the output stay
  * bf16.  Chunk scores are k_scale * (q . decoded k) in fp32 (the selection does
  * not depend on the scale); the attention multiplies its scores by k_scale and
- * its output by v_scale.  Built for decode (Tq == b_q == 1); these entry points
- * read contiguous (strided) device memory without dynamic RoPE, and
- * ihip_decode_layer_ex combines E4M3 rows with RoPE, page pools or the host tier.
- * Chunked prefill over E4M3 rows returns IHIP_ERR_UNSUPPORTED.
+ * its output by v_scale.  ihip_prune_stage_fp8kv serves decode and chunked
+ * prefill (b_q in {1, 16, 32, 64}); the prefill kernels repack a row as bf16
+ * (exact) on its way into LDS and multiply in bf16 as before.  These entry
+ * points read contiguous (strided) device memory; ihip_decode_layer_ex and
+ * ihip_prefill_layer_ex combine E4M3 rows with RoPE, page pools, the pooling
+ * rule or (decode) the host tier.
  */
 int32_t ihip_prune_stage_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                                const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
@@ -168,8 +170,8 @@ int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_ten
  * entries beyond a sequence's length are never read.  page_tokens is a power
  * of two and table_stride * page_tokens >= max_seq_len.  Everything else as in
  * the entry points of the same names without the suffix.  Built for decode
- * and chunked prefill from bf16 pools; FP8 pools (decode only) and the other
- * variants combine through ihip_decode_layer_ex / ihip_prefill_layer_ex.
+ * and chunked prefill from bf16 pools; FP8 pools and the other variants
+ * combine through ihip_decode_layer_ex / ihip_prefill_layer_ex.
  */
 typedef struct ihip_paged_kv {
     const int32_t *block_table;
@@ -283,6 +285,12 @@ int32_t ihip_sparse_attn_prefill_rope(const ihip_shape *shape, ihip_tensor q, ih
                                       float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
                                       void *ws, size_t ws_bytes, void *stream);
 
+/* ihip_sparse_attn_prefill over E4M3 K and V (see "FP8 KV cache" above); rope may be NULL. */
+int32_t ihip_sparse_attn_prefill_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                       float sm_scale, float k_scale, float v_scale, const ihip_rope *rope,
+                                       void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream);
+
 /* ihip_sparse_attn_prefill reading K and V from page pools (see ihip_paged_kv); rope may be NULL. */
 int32_t ihip_sparse_attn_prefill_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
                                        ihip_tensor v_pool, const ihip_paged_kv *paged,
@@ -323,13 +331,17 @@ int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_ten
 /*
  * The prefill layer with the variants in any combination: dynamic RoPE
  * (relative style in the pruning stages, streaming style in the attention),
- * paged K/V (k and v are then the page pools) and the pooling rule.
+ * paged K/V (k and v are then the page pools), the pooling rule and E4M3
+ * K/V (kv_fp8 != 0: k and v, or the pools, hold bytes, strides count bytes,
+ * k_scale / v_scale as in the *_fp8kv entry points).
  * Zero-initialise the struct: every zero field means "off".
  */
 typedef struct ihip_prefill_options {
     const ihip_rope *rope;
     const ihip_paged_kv *paged;
     int32_t pooling;
+    int32_t kv_fp8;
+    float k_scale, v_scale;
 } ihip_prefill_options;
 int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                               int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,

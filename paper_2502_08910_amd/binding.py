@@ -49,6 +49,8 @@ EXPORTS = {
                                      vp, vp, vp, vp, c_sz, vp]),
     "ihip_sparse_attn_prefill_paged": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, vp, c_i32, c_i32,
                                                c_f, vp, vp, vp, vp, c_sz, vp]),
+    "ihip_sparse_attn_prefill_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
+                                               c_f, c_f, c_f, vp, vp, vp, vp, c_sz, vp]),
     "ihip_prefill_layer_ex": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
                                       vp, vp, vp, vp, c_sz, vp]),
     "ihip_sparse_attn_prefill_rope": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
@@ -233,7 +235,7 @@ class DecodeOptions(ctypes.Structure):
 
 class PrefillOptions(ctypes.Structure):
     """ihip_prefill_options (all zero = the plain prefill layer)."""
-    _fields_ = [("rope", vp), ("paged", vp), ("pooling", c_i32)]
+    _fields_ = [("rope", vp), ("paged", vp), ("pooling", c_i32), ("kv_fp8", c_i32), ("k_scale", c_f), ("v_scale", c_f)]
 
 
 class Layer:
@@ -367,7 +369,19 @@ class Layer:
                           sm_scale, want_lse, ws)
 
     def sparse_attn_prefill(self, q, k, v, block_starts, block, sm_scale=None, want_lse=False, ws=None,
-                            rope: Optional["Rope"] = None, paged: Optional["PagedKV"] = None):
+                            rope: Optional["Rope"] = None, paged: Optional["PagedKV"] = None,
+                            kv_scales: Optional[Sequence[float]] = None):
+        if kv_scales is not None:
+            if paged is not None:
+                raise ValueError("E4M3 page pools go through prefill_layer (ihip_prefill_layer_ex)")
+            sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
+            out = torch.empty((self.B, self.Hq, self.Tq, self.d), dtype=torch.bfloat16, device=self.device)
+            lse = torch.empty((self.B, self.Hq, self.Tq), dtype=torch.float32, device=self.device) if want_lse else None
+            _check(lib().ihip_sparse_attn_prefill_fp8kv(
+                ctypes.byref(self.shape), _tensor(q, "q"), _tensor8(k, "k"), _tensor8(v, "v"), _ptr(block_starts),
+                block_starts.shape[-1], block, sm_scale, kv_scales[0], kv_scales[1],
+                rope.ref() if rope is not None else None, _ptr(out), _ptr(lse), None, 0, _stream()))
+            return out, lse
         if paged is not None:
             def fn(shape, tq, tk, tv, bs, n_blocks, blk, scale, out, lse, w, w_bytes, stream):
                 return lib().ihip_sparse_attn_prefill_paged(shape, tq, tk, tv, paged.ref(), bs, n_blocks, blk, scale,
@@ -490,22 +504,25 @@ class Layer:
 
     def prefill_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
                       out_blocks=None, lse=None, pooling: Optional[int] = None, rope: Optional["Rope"] = None,
-                      paged: Optional["PagedKV"] = None):
+                      paged: Optional["PagedKV"] = None, kv_scales: Optional[Sequence[float]] = None):
         """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d].
-        paged: k and v are ignored.  One variant alone goes to its own entry point, paged K/V and
-        combinations to ihip_prefill_layer_ex."""
+        paged: k and v are ignored.  kv_scales: K and V (or the pools) hold E4M3 bytes.  One variant
+        alone goes to its own entry point; paged K/V, E4M3 K/V and combinations to ihip_prefill_layer_ex."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, self.Tq, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_PREFILL_LAYER, chunk_sizes, keeps)
-        if paged is not None or (pooling is not None and rope is not None):
+        if paged is not None or kv_scales is not None or (pooling is not None and rope is not None):
             opt = PrefillOptions()
+            if kv_scales is not None:
+                opt.kv_fp8, opt.k_scale, opt.v_scale = 1, kv_scales[0], kv_scales[1]
+            conv = _tensor8 if kv_scales is not None else _tensor
             opt.rope = ctypes.cast(rope.ref(), vp) if rope is not None else None
             opt.paged = ctypes.cast(paged.ref(), vp) if paged is not None else None
             opt.pooling = POOL_KV_HEAD if pooling is None else pooling
-            tk, tv = (_tensor(paged.k_pool, "k_pool"), _tensor(paged.v_pool, "v_pool")) if paged is not None \
-                else (_tensor(k, "k"), _tensor(v, "v"))
+            tk, tv = (conv(paged.k_pool, "k_pool"), conv(paged.v_pool, "v_pool")) if paged is not None \
+                else (conv(k, "k"), conv(v, "v"))
             _check(lib().ihip_prefill_layer_ex(ctypes.byref(self.shape), _tensor(q, "q"), tk, tv, len(chunk_sizes),
                                                _i32(chunk_sizes), _i32(keeps), sm_scale, ctypes.byref(opt),
                                                _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws), ws.numel(),

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libihip.so")
-SOURCES = ["api.hip", "prune_stage.hip", "prune_stage_rope.hip", "select_blocks.hip", "sparse_attn_decode.hip",
+SOURCES = ["api.hip", "prune_stage.hip", "prune_prefill_fp8.hip", "prune_stage_rope.hip", "select_blocks.hip", "sparse_attn_decode.hip",
            "sparse_attn_prefill.hip", "sparse_attn_prefill32.hip", "cache.hip", "mfma_rate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 # The pruning kernels take maxima of matrix-core results; told that NaNs need not be honoured the
 # compiler drops the canonicalising v_max x,x,x in front of each (a third of the vector
 # instructions of the prefill search loop).  Scores of NaN inputs are then unspecified values.
-EXTRA = {"prune_stage.hip": ["-fno-honor-nans"]}
+EXTRA = {"prune_stage.hip": ["-fno-honor-nans"], "prune_prefill_fp8.hip": ["-fno-honor-nans"]}
 
 
 def build(verbose: bool = True) -> str:

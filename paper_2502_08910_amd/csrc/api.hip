@@ -448,13 +448,25 @@ static int32_t attn_prefill_entry(const char *who, const ihip_rope *rope, const 
     if (shape->b_q != 16 && shape->b_q != 32 && shape->b_q != 64)
         return fail(IHIP_ERR_UNSUPPORTED, "%s: b_q = %d not in {16, 32, 64}", who, shape->b_q);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
     if (n_blocks < 0 || !pow2(block)) return fail(IHIP_ERR_INVALID_ARG, "%s: n_blocks = %d, block = %d", who, n_blocks, block);
     if (n_blocks > 0 && !block_starts) return fail(IHIP_ERR_INVALID_ARG, "%s: block_starts is NULL", who);
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
     return launch_attn_prefill(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, rope,
                                (hipStream_t)stream, fmt);
+}
+
+int32_t ihip_sparse_attn_prefill_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                       float sm_scale, float k_scale, float v_scale, const ihip_rope *rope,
+                                       void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    const int32_t rc = check_scales("ihip_sparse_attn_prefill_fp8kv", k_scale, v_scale);
+    if (rc != IHIP_OK) return rc;
+    const KvFormat fmt{true, k_scale, v_scale, PagedView{nullptr, 0, 0}};
+    return attn_prefill_entry("ihip_sparse_attn_prefill_fp8kv", rope, &fmt, shape, q, k, v, block_starts, n_blocks,
+                              block, sm_scale, out, out_lse, ws, ws_bytes, stream);
 }
 
 int32_t ihip_sparse_attn_prefill_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, ihip_tensor v_pool,
@@ -700,8 +712,8 @@ static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_ro
     if (shape->b_q != 16 && shape->b_q != 32 && shape->b_q != 64)
         return fail(IHIP_ERR_UNSUPPORTED, "%s: b_q = %d not in {16, 32, 64}", who, shape->b_q);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
-    if ((rc = check_tensor(v, who, "v")) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
+    if ((rc = (fmt && fmt->fp8 ? check_tensor8(v, who, "v") : check_tensor(v, who, "v"))) != IHIP_OK) return rc;
     if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
     const int last = n_stages - 1;
@@ -760,7 +772,12 @@ int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tenso
     KvFormat fmt{false, 1.0f, 1.0f, PagedView{nullptr, 0, 0}};
     if (opt->paged && (rc = check_paged(who, shape, opt->paged, &fmt)) != IHIP_OK) return rc;
     if ((rc = check_pooling(who, opt->pooling)) != IHIP_OK) return rc;
-    return prefill_layer_impl(who, opt->pooling == IHIP_POOL_ALL_HEADS, opt->rope, opt->paged ? &fmt : nullptr, shape,
+    if (opt->kv_fp8) {
+        if ((rc = check_scales(who, opt->k_scale, opt->v_scale)) != IHIP_OK) return rc;
+        fmt.fp8 = true; fmt.k_scale = opt->k_scale; fmt.v_scale = opt->v_scale;
+    }
+    return prefill_layer_impl(who, opt->pooling == IHIP_POOL_ALL_HEADS, opt->rope,
+                              opt->paged || opt->kv_fp8 ? &fmt : nullptr, shape,
                               q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws,
                               ws_bytes, stream);
 }

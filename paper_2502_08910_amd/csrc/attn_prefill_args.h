@@ -26,6 +26,7 @@ struct AttnPrefillArgs {
     const float *rope_cos, *rope_sin;   // streaming-style RoPE instantiations only: fp32 [n_pos][d/2]
     PagedView paged;                    // paged instantiations only: k / v are the page pools, k_sb / v_sb
                                         // the page strides
+    float v_scale;                      // E4M3 instantiations only (K, V strides then count 2-byte units)
 };
 
 // Streaming-style positions (Sec. 4 "Dynamic RoPE for OOL generalization"): the keys a query

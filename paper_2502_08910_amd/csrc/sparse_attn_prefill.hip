@@ -17,15 +17,21 @@
 // key kq*4+j-4 of the second for j >= 4 -- exactly what a lane's two S^T
 // accumulators hold.  V is transposed on its way into LDS.
 #include "attn_prefill_args.h"
+#include <type_traits>
 
 namespace ihip {
 
 // ROPE: streaming-style dynamic RoPE; the queries are rotated once, a K piece on its way from the
 // staging registers into LDS (its table row is fetched along with it), both rounded to bf16.
 // PAGED: K and V are page pools; a piece's page is looked up in the block table right before it is fetched.
-template <int QT, int G, bool ROPE, bool PAGED>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
+// KV8: K and V rows are 128 bytes of E4M3 (strides in 2-byte units); a piece stays 8 bytes in the
+// staging registers and is repacked as bf16 (exact) on its way into LDS.  The K scale is folded into
+// the softmax scale, the V scale into the final normalisation.
+template <int QT, int G, bool ROPE, bool PAGED, bool KV8 = false>   // query tiles of 16 (b_q = 16*QT); G query heads = G waves per workgroup
 __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillArgs a)
 {
+    using raw_t = typename std::conditional<KV8, uint2, uint4>::type;     // 8 elements of a row as fetched
+    constexpr int kPiece = KV8 ? 4 : 8;                                   // ... in 2-byte units
     __shared__ __attribute__((aligned(16))) uint16_t sK[kPfTile * kPfKStride];
     __shared__ __attribute__((aligned(16))) uint16_t sVt[kD * kPfVStride];
     __shared__ int sPos[kPfTile];
@@ -83,7 +89,7 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
     // loader role: item = (key pair a2, dim group c); 16 pairs x 16 groups per tile
     constexpr int kItems = (kPfTile / 2) * 16;
     constexpr int kMaxPerThread = (kItems + nthreads - 1) / nthreads;
-    uint4 rk[kMaxPerThread][2], rv[kMaxPerThread][2];
+    raw_t rk[kMaxPerThread][2], rv[kMaxPerThread][2];
     int rpos[kMaxPerThread][2];
     float4 rc[ROPE ? kMaxPerThread : 1][2], rs[ROPE ? kMaxPerThread : 1][2];     // table row piece of each K piece
 
@@ -98,17 +104,17 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
                 const int slot = tile * kPfTile + a2 * 2 + e;
                 const int pos = slot < total ? pf_slot_to_pos(a, pr, p, slot, n_sink_eff, w0) : -1;
                 rpos[r][e] = pos;
-                rk[r][e] = make_uint4(0, 0, 0, 0);
-                rv[r][e] = make_uint4(0, 0, 0, 0);
+                rk[r][e] = raw_t{};
+                rv[r][e] = raw_t{};
                 if (pos >= 0) {
                     if constexpr (PAGED) {
                         const int64_t page = a.paged.block_table[(int64_t)pr.b * a.paged.table_stride + (pos >> a.paged.page_log2)];
                         const int64_t tok = pos & ((1 << a.paged.page_log2) - 1);
-                        rk[r][e] = *reinterpret_cast<const uint4 *>(kb + page * a.k_sb + tok * a.k_st + c * 8);
-                        rv[r][e] = *reinterpret_cast<const uint4 *>(vb + page * a.v_sb + tok * a.v_st + c * 8);
+                        rk[r][e] = *reinterpret_cast<const raw_t *>(kb + page * a.k_sb + tok * a.k_st + c * kPiece);
+                        rv[r][e] = *reinterpret_cast<const raw_t *>(vb + page * a.v_sb + tok * a.v_st + c * kPiece);
                     } else {
-                        rk[r][e] = *reinterpret_cast<const uint4 *>(kb + (int64_t)pos * a.k_st + c * 8);
-                        rv[r][e] = *reinterpret_cast<const uint4 *>(vb + (int64_t)pos * a.v_st + c * 8);
+                        rk[r][e] = *reinterpret_cast<const raw_t *>(kb + (int64_t)pos * a.k_st + c * kPiece);
+                        rv[r][e] = *reinterpret_cast<const raw_t *>(vb + (int64_t)pos * a.v_st + c * kPiece);
                     }
                 }
                 if constexpr (ROPE) {
@@ -127,17 +133,20 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
             if (item >= kItems) break;
             const int a2 = item >> 4, c = item & 15;
             const int key0 = a2 * 2;                                   // keys key0, key0+1 of the 32
+            uint4 wv[2];
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                if constexpr (ROPE)
-                    rk[r][e] = rotate_bf16x8(rk[r][e], rc[r][e], rs[r][e]);
-                *reinterpret_cast<uint4 *>(&sK[(key0 + e) * kPfKStride + c * 8]) = rk[r][e];
+                uint4 wk;
+                if constexpr (KV8) { wk = fp8x8_to_bf16x8(rk[r][e]); wv[e] = fp8x8_to_bf16x8(rv[r][e]); }
+                else { wk = rk[r][e]; wv[e] = rv[r][e]; }
+                if constexpr (ROPE) wk = rotate_bf16x8(wk, rc[r][e], rs[r][e]);
+                *reinterpret_cast<uint4 *>(&sK[(key0 + e) * kPfKStride + c * 8]) = wk;
             }
             // k slot of key kk: tile t = kk/16, kq = (kk%16)/4, j = kk%4 + 4*t
             const int t = key0 >> 4, kk = key0 & 15;
             const int kslot = (kk >> 2) * 8 + (kk & 3) + 4 * t;        // even; key0+1 sits at kslot+1
-            const uint32_t v0[4] = {rv[r][0].x, rv[r][0].y, rv[r][0].z, rv[r][0].w};
-            const uint32_t v1[4] = {rv[r][1].x, rv[r][1].y, rv[r][1].z, rv[r][1].w};
+            const uint32_t v0[4] = {wv[0].x, wv[0].y, wv[0].z, wv[0].w};
+            const uint32_t v1[4] = {wv[1].x, wv[1].y, wv[1].z, wv[1].w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 // dims c*8+2i (low halves) and c*8+2i+1 (high halves)
@@ -235,7 +244,7 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
         float l = l_run[qt];
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
-        const float inv = 1.0f / l;
+        const float inv = KV8 ? a.v_scale / l : 1.0f / l;
         const int64_t row = ((int64_t)pr.b * a.ge.Hq + h) * a.ge.Tq + q0 + qt * 16 + n;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
@@ -256,7 +265,7 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
                             const KvFormat *fmt)
 {
     AttnPrefillArgs a;
-    if (fmt && fmt->fp8) return fail(IHIP_ERR_UNSUPPORTED, "sparse_attn_prefill: FP8 K/V is built for decode only");
+    const bool fp8 = fmt && fmt->fp8;
     a.paged = (fmt && fmt->paged.block_table) ? fmt->paged : PagedView{nullptr, 0, 0};
     const bool paged = a.paged.block_table != nullptr;
     const bool use_rope = rope && rope->attn_style != IHIP_ROPE_NONE;
@@ -277,24 +286,32 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     a.q = (const uint16_t *)q.ptr; a.q_sb = q.stride_b; a.q_sh = q.stride_h; a.q_st = q.stride_t;
     a.k = (const uint16_t *)k.ptr; a.k_sb = k.stride_b; a.k_sh = k.stride_h; a.k_st = k.stride_t;
     a.v = (const uint16_t *)v.ptr; a.v_sb = v.stride_b; a.v_sh = v.stride_h; a.v_st = v.stride_t;
+    a.v_scale = 1.0f;
+    if (fp8) {      // byte strides (even) in 2-byte units
+        a.k_sb /= 2; a.k_sh /= 2; a.k_st /= 2;
+        a.v_sb /= 2; a.v_sh /= 2; a.v_st /= 2;
+        a.v_scale = fmt->v_scale;
+    }
     a.block_starts = block_starts;
     a.n_blocks = n_blocks;
     a.block = block;
     a.block_log2 = __builtin_ctz(block);
-    a.scale_log2e = sm_scale * 1.44269504088896340736f;
+    a.scale_log2e = sm_scale * 1.44269504088896340736f * (fp8 ? fmt->k_scale : 1.0f);
     a.out = (uint16_t *)out;
     a.out_lse = out_lse;
     const int P = s.B * s.Hkv * (s.Tq / s.b_q);
     if (P == 0) return IHIP_OK;
     KernelTimer timer("attn_prefill", st);
     const dim3 block_dim(64 * a.ge.G), grid(P);
-#define IHIP_PF_BY_G2(KERNEL, QT, RP, PG)                                                          \
+#define IHIP_PF_BY_G3(KERNEL, QT, RP, PG, F8)                                                      \
     switch (a.ge.G) {                                                                              \
-    case 1: hipLaunchKernelGGL((KERNEL<QT, 1, RP, PG>), grid, block_dim, 0, st, a); break;         \
-    case 2: hipLaunchKernelGGL((KERNEL<QT, 2, RP, PG>), grid, block_dim, 0, st, a); break;         \
-    case 4: hipLaunchKernelGGL((KERNEL<QT, 4, RP, PG>), grid, block_dim, 0, st, a); break;         \
-    default: hipLaunchKernelGGL((KERNEL<QT, 8, RP, PG>), grid, block_dim, 0, st, a); break;        \
+    case 1: hipLaunchKernelGGL((KERNEL<QT, 1, RP, PG, F8>), grid, block_dim, 0, st, a); break;     \
+    case 2: hipLaunchKernelGGL((KERNEL<QT, 2, RP, PG, F8>), grid, block_dim, 0, st, a); break;     \
+    case 4: hipLaunchKernelGGL((KERNEL<QT, 4, RP, PG, F8>), grid, block_dim, 0, st, a); break;     \
+    default: hipLaunchKernelGGL((KERNEL<QT, 8, RP, PG, F8>), grid, block_dim, 0, st, a); break;    \
     }
+#define IHIP_PF_BY_G2(KERNEL, QT, RP, PG)                                                          \
+    if (fp8) { IHIP_PF_BY_G3(KERNEL, QT, RP, PG, true) } else { IHIP_PF_BY_G3(KERNEL, QT, RP, PG, false) }
 #define IHIP_PF_BY_G(KERNEL, QT)                                                                   \
     if (use_rope && paged) { IHIP_PF_BY_G2(KERNEL, QT, true, true) }                               \
     else if (use_rope) { IHIP_PF_BY_G2(KERNEL, QT, true, false) }                                  \
@@ -303,7 +320,8 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
     const int slot_limit = use_rope ? (paged ? kPf32MaxSlotsRopePaged : kPf32MaxSlotsRope)
                                     : (paged ? kPf32MaxSlotsPaged : kPf32MaxSlots);
-    if (s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= slot_limit) {
+    // (E4M3 rows are repacked in registers, which only the 16x16 kernel's staging path does)
+    if (!fp8 && s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= slot_limit) {
         launch_attn_prefill32(a, P, s.max_seq_len, st);
         return check_launch("sparse_attn_prefill");
     }
@@ -315,6 +333,7 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     }
 #undef IHIP_PF_BY_G
 #undef IHIP_PF_BY_G2
+#undef IHIP_PF_BY_G3
     return check_launch("sparse_attn_prefill");
 }
 

@@ -115,5 +115,17 @@ def test_argument_checks_of_the_variants_need_no_gpu(built_lib):
     assert b"first_stage" in L.ihip_last_error()
     o = DecodeOptions(); o.pooling = 9
     assert ex(ctypes.byref(o)) == -1
+    # the combined prefill entry point: NULL options, bad scales; E4M3 attention alone: bad scales
+    from paper_2502_08910_amd.binding import PrefillOptions
+    exp = lambda opt: L.ihip_prefill_layer_ex(ctypes.byref(sp), t, t, t, 1, i32(64), i32(8), f(0.1), opt, 256,  # noqa: E731
+                                              None, None, 256, 1 << 30, None)
+    assert exp(None) == -1
+    po = PrefillOptions(); po.kv_fp8, po.k_scale, po.v_scale = 1, 1.0, 0.0
+    assert exp(ctypes.byref(po)) == -1
+    assert b"scales" in L.ihip_last_error()
+    po = PrefillOptions(); po.pooling = 9
+    assert exp(ctypes.byref(po)) == -1
+    assert L.ihip_sparse_attn_prefill_fp8kv(ctypes.byref(sp), t, t, t, 256, 8, 16, f(0.1), f(-1.0), f(1.0), None,
+                                            256, None, None, 0, None) == -1
     # pooling rule
     assert L.ihip_select_blocks_pooled(ctypes.byref(s), 256, slots, None, 0, 0, 64, 8, 5, 256, None) == -1

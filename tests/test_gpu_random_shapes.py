@@ -149,7 +149,11 @@ def test_random_prefill_layer(ihip, orc, seed):
     rope = rng.choice([None, "relative", "chunk"])
     page = int(rng.choice([0, 0, 1, 4, 16, 64]))
     pooled = bool(rng.integers(0, 4) == 0)
+    fp8 = bool(rng.integers(0, 2))
     q, k, v, _, _ = configs.make_inputs(w, seed, kind="int")
+    scales = (0.25, 0.5) if fp8 else None
+    if fp8:
+        k, v = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
     cos, sin = gen.quarter_turn_table(20000 if not large else 60000, w.d)
     spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune=str(rope), attn="streaming") if rope is not None else None
     rp = None
@@ -158,14 +162,14 @@ def test_random_prefill_layer(ihip, orc, seed):
         rp = ihip.Rope(cos.cuda(), sin.cuda(), style, ihip.ROPE_STREAMING)
     pg = None
     if page:
-        k_pool, v_pool, table = scatter_to_pages(k, v, page, seed, 7.0)
+        k_pool, v_pool, table = scatter_to_pages(k, v, page, seed, 7)
         pg = ihip.PagedKV(k_pool.cuda(), v_pool.cuda(), table.cuda())
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     L = ihip.Layer(qd, kd, sl.cuda(), b_q, n_sink, n_stream)
     chunks, keeps = [s[0] for s in stages], [s[1] for s in stages]
     blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
-    out = L.prefill_layer(qd, kd, vd, chunks, keeps, out_blocks=blocks, rope=rp, paged=pg,
+    out = L.prefill_layer(qd, kd, vd, chunks, keeps, out_blocks=blocks, rope=rp, paged=pg, kv_scales=scales,
                           pooling=ihip.POOL_ALL_HEADS if pooled else None)
     torch.cuda.synchronize()
-    o = orc.Oracle(q, k, v, sl.tolist(), b_q, n_sink, n_stream, rope=spec)
+    o = orc.Oracle(q, k, v, sl.tolist(), b_q, n_sink, n_stream, rope=spec, kv_scales=scales)
     check_against_oracle(w, o, sl, blocks, out, b_q, pooled)
