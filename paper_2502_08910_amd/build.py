@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libihip.so")
 SOURCES = ["api.hip", "prune_stage.hip", "prune_prefill_fp8.hip", "prune_stage_rope.hip", "select_blocks.hip", "sparse_attn_decode.hip",
-           "sparse_attn_prefill.hip", "sparse_attn_prefill32.hip", "cache.hip", "mfma_rate.hip"]
+           "sparse_attn_prefill.hip", "sparse_attn_prefill32.hip", "sparse_attn_prefill32_fp8.hip", "cache.hip", "mfma_rate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
@@ -36,7 +36,7 @@ def build(verbose: bool = True) -> str:
         subprocess.check_call(cmd)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(os.cpu_count() or 8, len(SOURCES))) as pool:
         objs = list(pool.map(compile_one, SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     if verbose:

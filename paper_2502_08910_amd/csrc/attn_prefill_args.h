@@ -87,6 +87,7 @@ constexpr int kPf32MaxSlotsPaged = 12160;     // ... with paged K/V (a page id p
 constexpr int kPf32MaxSlotsRopePaged = 10176; // ... with both
 
 void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len, hipStream_t st);
+void launch_attn_prefill32_fp8(const AttnPrefillArgs &a, int P, hipStream_t st);   // E4M3 K and V
 
 
 }  // namespace ihip

@@ -320,7 +320,11 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
     const int slot_limit = use_rope ? (paged ? kPf32MaxSlotsRopePaged : kPf32MaxSlotsRope)
                                     : (paged ? kPf32MaxSlotsPaged : kPf32MaxSlots);
-    // (E4M3 rows are repacked in registers, which only the 16x16 kernel's staging path does)
+    if (fp8 && s.b_q >= 32 &&
+        s.n_sink + n_blocks * block + s.n_stream <= (paged ? kPf32MaxSlotsRopePaged : kPf32MaxSlotsRope)) {
+        launch_attn_prefill32_fp8(a, P, st);
+        return check_launch("sparse_attn_prefill");
+    }
     if (!fp8 && s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= slot_limit) {
         launch_attn_prefill32(a, P, s.max_seq_len, st);
         return check_launch("sparse_attn_prefill");

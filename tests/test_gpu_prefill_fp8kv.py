@@ -143,17 +143,24 @@ def test_fp8_with_rope_pages_and_pooling_bit_exact(ihip, orc, w, page, rope):
                     assert np.abs(got - ref).max() <= 2e-2, (pooling, b, g, m)
 
 
-def test_keep_everything_is_dense_causal_on_dequantised_values(ihip):
-    # nothing pruned -> dense causal attention over scale * decoded bytes (torch, fp64)
-    prefix = 3000
+@pytest.mark.parametrize("prefix,page", [(3000, 0), (21000, 0), (11000, 16)],
+                         ids=["32x32-kernel", "16x16-kernel", "16x16-kernel-paged"])
+def test_keep_everything_is_dense_causal_on_dequantised_values(ihip, prefix, page):
+    # nothing pruned -> dense causal attention over scale * decoded bytes (torch, fp64).  The longer
+    # key lists exceed the slots the 32x32 kernel keeps in LDS (20,224; 10,176 with page ids), so
+    # the 16x16 kernel runs.
     keep = (prefix + 256) // 64 + 1
-    w = small(Tq=256, prefix=prefix, n_stream=128, stages=((64, keep), (16, 4 * keep)))
+    w = small(Tq=256, prefix=prefix, n_stream=128, Hq=8, Hkv=2, stages=((64, keep), (16, 4 * keep)))
     q, k, v, sl, _ = configs.make_inputs(w, 5)
     scales = (0.017, 0.009)
     k8, v8 = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
+    pg = None
+    if page:
+        k_pool, v_pool, table = scatter_to_pages(k8, v8, page, 9, 7)
+        pg = ihip.PagedKV(k_pool.cuda(), v_pool.cuda(), table.cuda())
     L = ihip.Layer(q.cuda(), k8.cuda(), sl.cuda(), w.b_q, w.n_sink, w.n_stream)
     out = L.prefill_layer(q.cuda(), k8.cuda(), v8.cuda(), [s[0] for s in w.stages], [s[1] for s in w.stages],
-                          kv_scales=scales)
+                          kv_scales=scales, paged=pg)
     torch.cuda.synchronize()
     kd = k8.view(torch.float8_e4m3fn).double() * scales[0]
     vd = v8.view(torch.float8_e4m3fn).double() * scales[1]
