@@ -112,9 +112,16 @@ class Oracle:
 
     def __init__(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seq_lens,
                  b_q: int, n_sink: int, n_stream: int, rope: Optional[RopeSpec] = None,
-                 kv_scales: Optional[Tuple[float, float]] = None):
+                 kv_scales: Optional[Tuple[float, float]] = None, stage_b_q: Optional[Sequence[int]] = None):
         """kv_scales = (k_scale, v_scale): K and V are uint8 tensors of E4M3 bytes (FP8 KV cache),
-        an element being its scale times the decoded byte; otherwise they are bf16."""
+        an element being its scale times the decoded byte; otherwise they are bf16.
+
+        stage_b_q: query-block size of every pruning stage (Sec. 4, the m' rule after Eq. for
+        I^(i); Alg. 1: a stage's result for block m is handed to the finer blocks of the next stage
+        that lie inside it).  Non-increasing, each dividing the one before, the last equal to b_q
+        (the block size of the attention).  Alg. 1 step 1 defines the candidate range with the first
+        stage's block, so the middle range of every finer block ends at that coarse block's end
+        minus n_stream; a finer block's own window then runs from there to its own queries."""
         from . import lib, Tensors, Rope
         self.L = lib()
         self.rope = rope
@@ -136,6 +143,11 @@ class Oracle:
         self.G = self.Hq // self.Hkv
         self.seq_lens = [int(x) for x in seq_lens]
         self.b_q, self.n_sink, self.n_stream = b_q, n_sink, n_stream
+        self.stage_b_q = None if stage_b_q is None else [int(x) for x in stage_b_q]
+        if self.stage_b_q is not None:
+            sb = self.stage_b_q
+            assert sb[-1] == b_q and all(sb[i] % sb[i + 1] == 0 for i in range(len(sb) - 1))
+            assert self.Tq % sb[0] == 0 and n_stream >= sb[0]
         self.t = Tensors(self.q.ctypes.data, self.k.ctypes.data, self.v.ctypes.data,
                          self.B, self.Hq, self.Hkv, self.d, self.Tq, self.T_alloc,
                          0 if kv_scales is None else 1,
@@ -148,11 +160,23 @@ class Oracle:
         excluded, causality is kept because hi never exceeds the position of
         the block's first query)."""
         E = (self.seq_lens[b] - self.Tq) + (m + 1) * self.b_q
-        return self.n_sink, E - self.n_stream, E
+        if self.stage_b_q is None:
+            return self.n_sink, E - self.n_stream, E
+        first = self.stage_b_q[0]                       # the block that defines the candidate range
+        E_first = (self.seq_lens[b] - self.Tq) + (m * self.b_q // first + 1) * first
+        return self.n_sink, E_first - self.n_stream, E
+
+    def stage_queries(self, b: int, m: int, i: Optional[int]) -> Tuple[int, int, int]:
+        """(first query row, number of queries, position of the first query) of the block of
+        stage i that holds block m of the last stage (the block itself without stage_b_q)."""
+        nq = self.b_q if self.stage_b_q is None or i is None else self.stage_b_q[i]
+        q0 = (m * self.b_q // nq) * nq
+        return q0, nq, (self.seq_lens[b] - self.Tq) + q0
 
     # -- Alg. 2 -----------------------------------------------------------
-    def prune_stage(self, b, g, m, starts, lens, l_c, keep, exhaustive=False) -> StageResult:
+    def prune_stage(self, b, g, m, starts, lens, l_c, keep, exhaustive=False, stage=None) -> StageResult:
         n = len(starts)
+        q0, nq, qpos0 = self.stage_queries(b, m, stage)
         scores = np.empty(n, np.float32)
         reps = np.empty((self.G, n), np.int64)
         touched = np.zeros(self.T_alloc, np.uint8)
@@ -161,14 +185,13 @@ class Oracle:
         if self.rope is not None and self.rope.prune is not None:
             assert not exhaustive
             style = {"relative": 1, "chunk": 2}[self.rope.prune]
-            E = self.ranges(b, m)[2]
             need = self.n_stream + 2 if style == 1 else n + self.n_stream
             assert self._cos.shape[0] >= need, "RoPE table too short"
-            self.L.orc_prune_stage_rope(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q, E - self.b_q, n,
+            self.L.orc_prune_stage_rope(ctypes.byref(self.t), b, g, q0, nq, qpos0, n,
                                         _p(starts), _p(lens), l_c, ctypes.byref(self._rope), style,
                                         self.n_stream, _p(scores), _p(reps), _p(touched))
         else:
-            self.L.orc_prune_stage(ctypes.byref(self.t), b, g, m * self.b_q, self.b_q, n,
+            self.L.orc_prune_stage(ctypes.byref(self.t), b, g, q0, nq, n,
                                    _p(starts), _p(lens), l_c, int(exhaustive),
                                    _p(scores), _p(reps), _p(touched))
         ids = np.empty(max(min(keep, n), 1), np.int32)
@@ -188,7 +211,7 @@ class Oracle:
             if i > 0:
                 assert stages[i - 1][0] % l_c == 0
                 starts, lens = child_chunks(pr.stages[-1].kept_starts, pr.stages[-1].kept_lens, l_c)
-            pr.stages.append(self.prune_stage(b, g, m, starts, lens, l_c, keep, exhaustive))
+            pr.stages.append(self.prune_stage(b, g, m, starts, lens, l_c, keep, exhaustive, stage=i))
         return pr
 
     # -- Alg. 2 as printed: one mask per layer ---------------------------------
@@ -206,7 +229,7 @@ class Oracle:
         for i, (l_c, keep) in enumerate(stages):
             if i > 0:
                 starts, lens = child_chunks(prs[0].stages[-1].kept_starts, prs[0].stages[-1].kept_lens, l_c)
-            per_g = [self.prune_stage(b, g, m, starts, lens, l_c, keep) for g in range(self.Hkv)]
+            per_g = [self.prune_stage(b, g, m, starts, lens, l_c, keep, stage=i) for g in range(self.Hkv)]
             pooled = np.max(np.stack([r.scores for r in per_g]), axis=0) if len(starts) else np.zeros(0, np.float32)
             pooled = np.ascontiguousarray(pooled, np.float32)
             ids = np.empty(max(min(keep, len(starts)), 1), np.int32)
