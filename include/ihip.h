@@ -60,6 +60,12 @@ typedef struct {
     const int32_t *seq_lens;     /* device [B]: keys visible per sequence, the Tq new tokens included */
     int32_t max_seq_len;         /* host-side upper bound of seq_lens (sizes the launch) */
     int32_t n_sink, n_stream;
+    int32_t b_q_range;           /* 0 or b_q: every query block has its own candidate range.  Otherwise a
+                                  * multiple of b_q that divides Tq (and is <= n_stream): the block size
+                                  * of the first pruning stage when the stages use different block sizes
+                                  * (Sec. 4, the m' rule; Alg. 1 "subdivide query blocks"): the middle
+                                  * range of block m ends n_stream before the end of the b_q_range-sized
+                                  * block that holds it, and its window runs from there to its queries. */
 } ihip_shape;
 
 /*
@@ -202,6 +208,18 @@ int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tenso
 int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk);
 
 /*
+ * Alg. 1 "subdivide query blocks for the next stage" (Sec. 4: a stage's result
+ * for block m goes to the blocks m' of the next, smaller block size that lie
+ * inside it).  starts: device int32 [P, n], the kept chunk starts of a stage run
+ * with shape->b_q queries per block; out_starts: device int32 [P * b_q /
+ * b_q_fine, n], row (b, g, m') a copy of row (b, g, m' * b_q_fine / b_q).  The
+ * next stage is then called with b_q = b_q_fine and b_q_range = the first
+ * stage's block size.  b_q_fine divides shape->b_q; the buffers must differ.
+ */
+int32_t ihip_subdivide_blocks(const ihip_shape *shape, const int32_t *starts, int32_t n, int32_t b_q_fine,
+                              int32_t *out_starts, void *stream);
+
+/*
  * arg-top-K of the chunk scores (Alg. 2, "discard chunks with low estimated
  * scores"): per problem keeps the min(keep, #non-empty slots) best slots under
  * the order (score descending, slot ascending; -0.0 == +0.0) and writes their
@@ -342,6 +360,12 @@ typedef struct ihip_prefill_options {
     int32_t pooling;
     int32_t kv_fp8;
     float k_scale, v_scale;
+    const int32_t *stage_b_q;   /* host [n_stages] or NULL: query-block size of every stage (Sec. 4, the m'
+                                 * rule): 16, 32 or 64, non-increasing, each dividing the one before, the
+                                 * last equal to shape.b_q (the attention's block).  The candidate ranges
+                                 * are those of the first stage's blocks (see ihip_shape.b_q_range, which
+                                 * the call sets itself); where the block size drops, a block's kept
+                                 * chunks are handed to every finer block inside it. */
 } ihip_prefill_options;
 int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                               int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,

@@ -33,7 +33,7 @@ class Tensor(ctypes.Structure):
 class Shape(ctypes.Structure):
     _fields_ = [("B", c_i32), ("Hq", c_i32), ("Hkv", c_i32), ("d", c_i32), ("Tq", c_i32),
                 ("b_q", c_i32), ("seq_lens", vp), ("max_seq_len", c_i32), ("n_sink", c_i32),
-                ("n_stream", c_i32)]
+                ("n_stream", c_i32), ("b_q_range", c_i32)]
 
 
 EXPORTS = {
@@ -49,6 +49,7 @@ EXPORTS = {
                                      vp, vp, vp, vp, c_sz, vp]),
     "ihip_sparse_attn_prefill_paged": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, vp, c_i32, c_i32,
                                                c_f, vp, vp, vp, vp, c_sz, vp]),
+    "ihip_subdivide_blocks": (c_i32, [ctypes.POINTER(Shape), vp, c_i32, c_i32, vp, vp]),
     "ihip_sparse_attn_prefill_fp8kv": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, vp, c_i32, c_i32,
                                                c_f, c_f, c_f, vp, vp, vp, vp, c_sz, vp]),
     "ihip_prefill_layer_ex": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f, vp,
@@ -235,7 +236,8 @@ class DecodeOptions(ctypes.Structure):
 
 class PrefillOptions(ctypes.Structure):
     """ihip_prefill_options (all zero = the plain prefill layer)."""
-    _fields_ = [("rope", vp), ("paged", vp), ("pooling", c_i32), ("kv_fp8", c_i32), ("k_scale", c_f), ("v_scale", c_f)]
+    _fields_ = [("rope", vp), ("paged", vp), ("pooling", c_i32), ("kv_fp8", c_i32), ("k_scale", c_f), ("v_scale", c_f),
+                ("stage_b_q", vp)]
 
 
 class Layer:
@@ -243,7 +245,9 @@ class Layer:
     the C entry points of the same names."""
 
     def __init__(self, q: torch.Tensor, k: torch.Tensor, seq_lens: torch.Tensor, b_q: int, n_sink: int,
-                 n_stream: int, max_seq_len: Optional[int] = None):
+                 n_stream: int, max_seq_len: Optional[int] = None, b_q_range: int = 0):
+        """b_q_range: the first pruning stage's block size when the stages use different ones
+        (ihip_shape.b_q_range); 0 = b_q."""
         B, Hq, Tq, d = q.shape
         Hkv = k.shape[1]
         if seq_lens.dtype != torch.int32 or not seq_lens.is_cuda or seq_lens.numel() != B:
@@ -252,7 +256,7 @@ class Layer:
         self.max_seq_len = int(k.shape[2] if max_seq_len is None else max_seq_len)
         if self.max_seq_len > k.shape[2]:
             raise IhipError("max_seq_len exceeds the allocated tokens of K")
-        self.shape = Shape(B, Hq, Hkv, d, Tq, b_q, seq_lens.data_ptr(), self.max_seq_len, n_sink, n_stream)
+        self.shape = Shape(B, Hq, Hkv, d, Tq, b_q, seq_lens.data_ptr(), self.max_seq_len, n_sink, n_stream, b_q_range)
         self.B, self.Hq, self.Hkv, self.d, self.Tq, self.b_q = B, Hq, Hkv, d, Tq, b_q
         self.P = B * Hkv * (Tq // max(b_q, 1))
         self.device = q.device
@@ -308,6 +312,13 @@ class Layer:
                                       _ptr(parent_starts), n_parent, parent_chunk, chunk, slots,
                                       _ptr(scores), _ptr(rep), _stream()))
         return scores, rep
+
+    def subdivide_blocks(self, starts: torch.Tensor, b_q_fine: int) -> torch.Tensor:
+        """Kept lists [P, n] of this layer's blocks -> [P * b_q / b_q_fine, n] for blocks of b_q_fine queries."""
+        n = starts.shape[-1]
+        out = torch.empty((self.P * (self.b_q // b_q_fine), n), dtype=torch.int32, device=self.device)
+        _check(lib().ihip_subdivide_blocks(ctypes.byref(self.shape), _ptr(starts), n, b_q_fine, _ptr(out), _stream()))
+        return out
 
     def select_blocks(self, scores: torch.Tensor, chunk: int, keep: int,
                       parent_starts: Optional[torch.Tensor] = None, parent_chunk: int = 0,
@@ -504,7 +515,8 @@ class Layer:
 
     def prefill_layer(self, q, k, v, chunk_sizes, keeps, sm_scale=None, ws=None, out=None,
                       out_blocks=None, lse=None, pooling: Optional[int] = None, rope: Optional["Rope"] = None,
-                      paged: Optional["PagedKV"] = None, kv_scales: Optional[Sequence[float]] = None):
+                      paged: Optional["PagedKV"] = None, kv_scales: Optional[Sequence[float]] = None,
+                      stage_b_q: Optional[Sequence[int]] = None):
         """Pruning stages + block-sparse prefill attention in one enqueue -> bf16 [B,Hq,Tq,d].
         paged: k and v are ignored.  kv_scales: K and V (or the pools) hold E4M3 bytes.  One variant
         alone goes to its own entry point; paged K/V, E4M3 K/V and combinations to ihip_prefill_layer_ex."""
@@ -513,8 +525,11 @@ class Layer:
             out = torch.empty((self.B, self.Hq, self.Tq, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_PREFILL_LAYER, chunk_sizes, keeps)
-        if paged is not None or kv_scales is not None or (pooling is not None and rope is not None):
+        if paged is not None or kv_scales is not None or stage_b_q is not None or \
+                (pooling is not None and rope is not None):
             opt = PrefillOptions()
+            sbq = _i32(stage_b_q) if stage_b_q is not None else None      # kept alive until the call returns
+            opt.stage_b_q = ctypes.cast(sbq, vp) if sbq is not None else None
             if kv_scales is not None:
                 opt.kv_fp8, opt.k_scale, opt.v_scale = 1, kv_scales[0], kv_scales[1]
             conv = _tensor8 if kv_scales is not None else _tensor

@@ -76,6 +76,7 @@ void profile_end(hipStream_t st)
 int32_t launch_prune_stage(const ihip_shape &, const ihip_tensor &, const ihip_tensor &, const int32_t *,
                            int, int, int, int, float *, int32_t *, const BankView *, const ihip_rope *, hipStream_t,
                            const KvFormat * = nullptr);
+int32_t launch_subdivide_blocks(const ihip_shape &, const int32_t *, int, int, int32_t *, hipStream_t);
 int32_t launch_select_blocks(const ihip_shape &, const float *, int, const int32_t *, int, int, int, int,
                              int32_t *, bool, hipStream_t);
 int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
@@ -133,6 +134,11 @@ static int32_t check_shape(const ihip_shape *s, const char *who)
     if (s->n_sink < 0 || s->n_stream < s->b_q)
         return fail(IHIP_ERR_INVALID_ARG, "%s: need n_sink >= 0 and n_stream >= b_q (got %d, %d, b_q %d)", who,
                     s->n_sink, s->n_stream, s->b_q);
+    if (s->b_q_range != 0 && (s->b_q_range < s->b_q || s->b_q_range % s->b_q != 0 || s->Tq % s->b_q_range != 0 ||
+                              s->n_stream < s->b_q_range))
+        return fail(IHIP_ERR_INVALID_ARG,
+                    "%s: b_q_range = %d must be 0 or a multiple of b_q = %d that divides Tq = %d and is <= n_stream = %d",
+                    who, s->b_q_range, s->b_q, s->Tq, s->n_stream);
     if (s->max_seq_len < s->Tq)
         return fail(IHIP_ERR_INVALID_ARG, "%s: max_seq_len = %d < Tq = %d", who, s->max_seq_len, s->Tq);
     if (!s->seq_lens && s->B > 0) return fail(IHIP_ERR_INVALID_ARG, "%s: seq_lens is NULL", who);
@@ -236,6 +242,43 @@ static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, cons
         rc = launch_select_blocks(s, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i],
                                   stage_out[i], all_heads, st);
         if (rc != IHIP_OK) return rc;
+    }
+    return IHIP_OK;
+}
+
+// Alg. 1 with a query-block size per stage (Sec. 4, the m' rule): stage i runs on blocks of
+// stage_b_q[i] queries inside the candidate ranges of the first stage's blocks; where the next stage's
+// blocks are smaller its kept lists are copied to every block inside.  s.b_q is the last stage's
+// block size: the workspace of that shape has room for every stage.
+static int32_t prune_all_subdivided(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
+                                    const int32_t *chunks, const int32_t *keeps, const int32_t *stage_b_q,
+                                    int32_t *out_block_starts, char *ws, const ihip_rope *rope, bool all_heads,
+                                    hipStream_t st, const KvFormat *fmt)
+{
+    const PlanLayout L = plan_layout(s, n_stages, chunks, keeps);
+    int32_t *buf[2] = {(int32_t *)(ws + L.starts_off[0]), (int32_t *)(ws + L.starts_off[1])};
+    float *scores = (float *)(ws + L.scores_off);
+    const int32_t *parents = nullptr;
+    for (int i = 0; i < n_stages; ++i) {
+        ihip_shape si = s;
+        si.b_q = stage_b_q[i];
+        si.b_q_range = stage_b_q[0];
+        const int n_parent = i == 0 ? 0 : keeps[i - 1];
+        const int parent_chunk = i == 0 ? 0 : chunks[i - 1];
+        const int slots = i == 0 ? stage1_slots(si, chunks[0]) : n_parent * (parent_chunk / chunks[i]);
+        int32_t *out = i + 1 == n_stages ? out_block_starts : (parents == buf[0] ? buf[1] : buf[0]);
+        int32_t rc = launch_prune_stage(si, q, k, parents, n_parent, parent_chunk, chunks[i], slots, scores, nullptr,
+                                        nullptr, rope, st, fmt);
+        if (rc != IHIP_OK) return rc;
+        rc = launch_select_blocks(si, scores, slots, parents, n_parent, parent_chunk, chunks[i], keeps[i], out,
+                                  all_heads, st);
+        if (rc != IHIP_OK) return rc;
+        parents = out;
+        if (i + 1 < n_stages && stage_b_q[i + 1] != stage_b_q[i]) {
+            int32_t *finer = out == buf[0] ? buf[1] : buf[0];
+            if ((rc = launch_subdivide_blocks(si, out, keeps[i], stage_b_q[i + 1], finer, st)) != IHIP_OK) return rc;
+            parents = finer;
+        }
     }
     return IHIP_OK;
 }
@@ -348,6 +391,19 @@ int32_t ihip_prune_stage_paged(const ihip_shape *shape, ihip_tensor q, ihip_tens
     if (rc != IHIP_OK) return rc;
     return prune_stage_entry("ihip_prune_stage_paged", nullptr, &fmt, shape, q, k_pool, parent_starts, n_parent,
                              parent_chunk, chunk, max_chunks, out_scores, out_rep, stream);
+}
+
+int32_t ihip_subdivide_blocks(const ihip_shape *shape, const int32_t *starts, int32_t n, int32_t b_q_fine,
+                              int32_t *out_starts, void *stream)
+{
+    const char *who = "ihip_subdivide_blocks";
+    int32_t rc;
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (b_q_fine <= 0 || shape->b_q % b_q_fine != 0)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: b_q_fine = %d must divide b_q = %d", who, b_q_fine, shape->b_q);
+    if (n < 0 || (n > 0 && (!starts || !out_starts)) || starts == out_starts)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: n = %d, starts / out_starts NULL or the same buffer", who, n);
+    return launch_subdivide_blocks(*shape, starts, n, b_q_fine, out_starts, (hipStream_t)stream);
 }
 
 int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t max_chunks,
@@ -705,7 +761,8 @@ int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor
 
 static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
                            const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
-                           float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream)
+                           float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream,
+                           const int32_t *stage_b_q = nullptr)
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
@@ -725,11 +782,30 @@ static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_ro
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     char *w = (char *)ws;
     int32_t *blocks = out_block_starts ? out_block_starts : (int32_t *)(w + L.total);
-    rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, rope, all_heads,
-                        (hipStream_t)stream, fmt);
+    ihip_shape attn_shape = *shape;
+    if (stage_b_q) {
+        for (int i = 0; i < n_stages; ++i) {
+            const int bq = stage_b_q[i];
+            if ((bq != 16 && bq != 32 && bq != 64) || (i > 0 && (bq > stage_b_q[i - 1] || stage_b_q[i - 1] % bq != 0)))
+                return fail(IHIP_ERR_INVALID_ARG, "%s: stage_b_q[%d] = %d: need 16, 32 or 64, not above the stage before", who, i, bq);
+        }
+        if (stage_b_q[last] != shape->b_q)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: the last stage's block size %d must be shape.b_q = %d", who,
+                        stage_b_q[last], shape->b_q);
+        if (shape->b_q_range != 0 && shape->b_q_range != stage_b_q[0])
+            return fail(IHIP_ERR_INVALID_ARG, "%s: shape.b_q_range = %d, the first stage's block size is %d", who,
+                        shape->b_q_range, stage_b_q[0]);
+        attn_shape.b_q_range = stage_b_q[0];
+        if ((rc = check_shape(&attn_shape, who)) != IHIP_OK) return rc;
+        rc = prune_all_subdivided(attn_shape, q, k, n_stages, chunk_sizes, keeps, stage_b_q, blocks, w, rope, all_heads,
+                                  (hipStream_t)stream, fmt);
+    } else {
+        rc = prune_all_impl(*shape, q, k, n_stages, chunk_sizes, keeps, blocks, w, nullptr, rope, all_heads,
+                            (hipStream_t)stream, fmt);
+    }
     if (rc != IHIP_OK) return rc;
-    return launch_attn_prefill(*shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse, rope,
-                               (hipStream_t)stream, fmt);
+    return launch_attn_prefill(attn_shape, q, k, v, blocks, keeps[last], chunk_sizes[last], sm_scale, out, out_lse,
+                               rope, (hipStream_t)stream, fmt);
 }
 
 int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,
@@ -779,7 +855,7 @@ int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tenso
     return prefill_layer_impl(who, opt->pooling == IHIP_POOL_ALL_HEADS, opt->rope,
                               opt->paged || opt->kv_fp8 ? &fmt : nullptr, shape,
                               q, k, v, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse, out_block_starts, ws,
-                              ws_bytes, stream);
+                              ws_bytes, stream, opt->stage_b_q);
 }
 
 int32_t ihip_profile_enable(int32_t on)

@@ -39,6 +39,7 @@ double measure_mfma_rate(int kind, int iters, float *sink, hipStream_t st);
 struct Geometry {
     const int32_t *seq_lens;
     int32_t B, Hq, Hkv, G, Tq, b_q, Mq, n_sink, n_stream;
+    int32_t b_q_range;      // block size that defines the candidate range (>= b_q; b_q unless the stages differ)
 };
 
 __host__ __device__ inline Geometry make_geometry(const ihip_shape &s)
@@ -48,6 +49,7 @@ __host__ __device__ inline Geometry make_geometry(const ihip_shape &s)
     g.B = s.B; g.Hq = s.Hq; g.Hkv = s.Hkv; g.G = s.Hq / s.Hkv;
     g.Tq = s.Tq; g.b_q = s.b_q; g.Mq = s.Tq / s.b_q;
     g.n_sink = s.n_sink; g.n_stream = s.n_stream;
+    g.b_q_range = s.b_q_range > 0 ? s.b_q_range : s.b_q;
     return g;
 }
 
@@ -66,7 +68,11 @@ __device__ inline Problem problem_of(const Geometry &ge, int p)
     const int T = ge.seq_lens[r.b];
     r.E = (T - ge.Tq) + (r.m + 1) * ge.b_q;
     r.lo = ge.n_sink;
-    r.hi = r.E - ge.n_stream;
+    // Alg. 1 step 1 defines the candidate range with the first stage's query block: a finer block
+    // inherits the range of the coarse block that holds it (and a window that starts there)
+    const int E_range = ge.b_q_range == ge.b_q ? r.E
+                                               : (T - ge.Tq) + (r.m * ge.b_q / ge.b_q_range + 1) * ge.b_q_range;
+    r.hi = E_range - ge.n_stream;
     return r;
 }
 

@@ -241,6 +241,31 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
     for (int i = keep_eff + tid; i < a.keep; i += NT) view.put(i, -1);
 }
 
+// Alg. 1 "subdivide query blocks for the next stage": row p of dst (one per block of b_q / ratio
+// queries) is a copy of the row of the coarse block that holds it.
+__global__ __launch_bounds__(256) void subdivide_blocks_kernel(const int32_t *src, int32_t *dst, int n, int Mq_fine,
+                                                              int ratio)
+{
+    const int pf = blockIdx.x;                       // (sequence, KV head, fine block)
+    const int bg = pf / Mq_fine, m = pf % Mq_fine;
+    const int32_t *from = src + ((int64_t)bg * (Mq_fine / ratio) + m / ratio) * n;
+    int32_t *to = dst + (int64_t)pf * n;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) to[i] = from[i];
+}
+
+// s: the shape of the coarse stage (b_q = its block size)
+int32_t launch_subdivide_blocks(const ihip_shape &s, const int32_t *starts, int n, int b_q_fine, int32_t *out,
+                                hipStream_t st)
+{
+    const int ratio = s.b_q / b_q_fine;
+    const int Mq_fine = s.Tq / b_q_fine;
+    const int P = s.B * s.Hkv * Mq_fine;
+    if (P == 0 || n == 0) return IHIP_OK;
+    KernelTimer timer("subdivide_blocks", st);
+    hipLaunchKernelGGL(subdivide_blocks_kernel, dim3(P), dim3(256), 0, st, starts, out, n, Mq_fine, ratio);
+    return check_launch("subdivide_blocks");
+}
+
 int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_chunks,
                              const int32_t *parent_starts, int n_parent, int parent_chunk, int chunk,
                              int keep, int32_t *out_starts, bool all_heads, hipStream_t st)

@@ -7,7 +7,8 @@ The draws stay inside what the entry points document (shape and plan checks);
 they aim at what the fixed cases do not hit together: odd sequence lengths,
 sequences shorter than sink + window, sinks and windows that are no multiple of
 anything, budgets larger than the number of chunks, chunk sizes down to 1, pages
-down to one token, three KV heads, every group size."""
+down to one token, three KV heads, every group size; for prefill also E4M3 rows
+and a query-block size per stage."""
 import os
 
 import numpy as np
@@ -143,6 +144,20 @@ def test_random_prefill_layer(ihip, orc, seed):
     if large:
         B, Hkv = 1, min(Hkv, 2)
         stages = tuple((c, int(rng.integers(100, 400))) for c, _ in stages)
+    # a query-block size per stage (a stream of its own, so that the other draws stay as they were):
+    # built from the last stage (b_q) backwards, doubling at random; the new tokens are then a whole
+    # number of first-stage blocks and the window holds one
+    rng_b = np.random.default_rng(3000 + seed)
+    stage_b_q = [b_q]
+    for _ in stages[1:]:
+        stage_b_q.insert(0, min(64, stage_b_q[0] * int(rng_b.choice([1, 2]))))
+    if stage_b_q[0] == b_q:
+        stage_b_q = None
+    else:
+        first = stage_b_q[0]
+        T += -Tq % first
+        Tq += -Tq % first
+        n_stream = max(n_stream, first)
     w = configs.shrink(configs.CFG4, B=B, Hq=Hkv * G, Hkv=Hkv, T=T, Tq=Tq, b_q=b_q, n_sink=n_sink,
                        n_stream=n_stream, stages=stages)
     sl = torch.tensor([T if b == 0 else int(rng.integers(Tq, T + 1)) for b in range(B)], dtype=torch.int32)
@@ -169,7 +184,7 @@ def test_random_prefill_layer(ihip, orc, seed):
     chunks, keeps = [s[0] for s in stages], [s[1] for s in stages]
     blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
     out = L.prefill_layer(qd, kd, vd, chunks, keeps, out_blocks=blocks, rope=rp, paged=pg, kv_scales=scales,
-                          pooling=ihip.POOL_ALL_HEADS if pooled else None)
+                          pooling=ihip.POOL_ALL_HEADS if pooled else None, stage_b_q=stage_b_q)
     torch.cuda.synchronize()
-    o = orc.Oracle(q, k, v, sl.tolist(), b_q, n_sink, n_stream, rope=spec, kv_scales=scales)
+    o = orc.Oracle(q, k, v, sl.tolist(), b_q, n_sink, n_stream, rope=spec, kv_scales=scales, stage_b_q=stage_b_q)
     check_against_oracle(w, o, sl, blocks, out, b_q, pooled)
