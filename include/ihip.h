@@ -18,6 +18,8 @@
  *  - Every function returns 0 on success or a negative IHIP_ERR_* code; the
  *    text of the last error of the calling thread is in ihip_last_error().
  *    Nothing is enqueued when an argument check fails.
+ *  - An empty batch (shape->B == 0) is no error: the call returns IHIP_OK
+ *    after checking the shape, enqueues nothing and looks at no pointer.
  *  - Preconditions the library cannot check: inputs hold no NaN or Inf;
  *    seq_lens[b] <= max_seq_len <= the allocated token count of K and V.
  *
@@ -30,7 +32,9 @@
  *     lo = n_sink,  hi = E - n_stream  the middle range [lo, hi) that is pruned
  * (Alg. 1, first step).  Sink [0, n_sink) and window [max(hi,lo), E) are always
  * attended, the window causally.  n_stream >= b_q is required so that every
- * middle key precedes every query of the block.
+ * middle key precedes every query of the block.  (With shape->b_q_range set,
+ * hi is taken from the b_q_range-sized block that holds block m instead: see
+ * ihip_shape.)
  */
 #ifndef IHIP_H
 #define IHIP_H

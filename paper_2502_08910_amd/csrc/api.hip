@@ -326,6 +326,7 @@ static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const K
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
     if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
     if ((rc = check_slots(who, parent_starts, n_parent, parent_chunk, chunk, max_chunks)) != IHIP_OK) return rc;
@@ -362,6 +363,7 @@ static int32_t select_blocks_entry(const char *who, bool all_heads, const ihip_s
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if ((rc = check_slots(who, parent_starts, n_parent, parent_chunk, chunk, max_chunks)) != IHIP_OK) return rc;
     if (keep < 0) return fail(IHIP_ERR_INVALID_ARG, "%s: keep = %d", who, keep);
     if (max_chunks > 65535 * 16) return fail(IHIP_ERR_UNSUPPORTED, "%s: max_chunks = %d too large", who, max_chunks);
@@ -399,6 +401,7 @@ int32_t ihip_subdivide_blocks(const ihip_shape *shape, const int32_t *starts, in
     const char *who = "ihip_subdivide_blocks";
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if (b_q_fine <= 0 || shape->b_q % b_q_fine != 0)
         return fail(IHIP_ERR_INVALID_ARG, "%s: b_q_fine = %d must divide b_q = %d", who, b_q_fine, shape->b_q);
     if (n < 0 || (n > 0 && (!starts || !out_starts)) || starts == out_starts)
@@ -437,6 +440,7 @@ static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const K
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
     if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
@@ -501,6 +505,7 @@ static int32_t attn_prefill_entry(const char *who, const ihip_rope *rope, const 
     int32_t rc;
     (void)ws; (void)ws_bytes;       // this kernel needs no scratch
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if (shape->b_q != 16 && shape->b_q != 32 && shape->b_q != 64)
         return fail(IHIP_ERR_UNSUPPORTED, "%s: b_q = %d not in {16, 32, 64}", who, shape->b_q);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
@@ -562,6 +567,7 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, in
     const char *who = "ihip_prune_all";
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
     if ((rc = check_tensor(k, who, "k")) != IHIP_OK) return rc;
     if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
@@ -583,6 +589,7 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
     if ((rc = (fmt && fmt->fp8 ? check_tensor8(k, who, "k") : check_tensor(k, who, "k"))) != IHIP_OK) return rc;
@@ -766,6 +773,7 @@ static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_ro
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;          // an empty batch: nothing to do, no pointer is looked at
     if (shape->b_q != 16 && shape->b_q != 32 && shape->b_q != 64)
         return fail(IHIP_ERR_UNSUPPORTED, "%s: b_q = %d not in {16, 32, 64}", who, shape->b_q);
     if ((rc = check_tensor(q, who, "q")) != IHIP_OK) return rc;
@@ -900,15 +908,15 @@ size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stage
         return std::max<size_t>(256, attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]));
     case IHIP_OP_ATTN_PREFILL:
         return 256;
-    case IHIP_OP_PRUNE_ALL:
-        return plan_layout(*shape, n_stages, chunk_sizes, keeps).total;
+    case IHIP_OP_PRUNE_ALL:         // (never 0, which stands for an error: an empty batch needs nothing)
+        return std::max<size_t>(256, plan_layout(*shape, n_stages, chunk_sizes, keeps).total);
     case IHIP_OP_DECODE_LAYER:
-        return plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
-               align256(P * keeps[last] * sizeof(int32_t)) +
-               attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
+        return std::max<size_t>(256, plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
+                                         align256(P * keeps[last] * sizeof(int32_t)) +
+                                         attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]));
     case IHIP_OP_PREFILL_LAYER:
-        return plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
-               align256(P * keeps[last] * sizeof(int32_t));
+        return std::max<size_t>(256, plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
+                                         align256(P * keeps[last] * sizeof(int32_t)));
     default:
         fail(IHIP_ERR_INVALID_ARG, "ihip_workspace_bytes: unknown op %d", op);
         return 0;

@@ -266,3 +266,23 @@ def test_decode_layer_under_graph_capture(ihip, orc):
         torch.cuda.synchronize()
         assert torch.equal(blocks, ref_blocks), seed
         assert torch.equal(out, ref), seed
+
+
+def test_empty_batch_is_a_no_op(ihip):
+    # B = 0: every entry point returns without enqueuing anything or touching a pointer
+    w = configs.shrink(configs.CFG1, T=2048, n_needles=0)
+    q = torch.empty((0, w.Hq, 1, w.d), dtype=torch.bfloat16, device="cuda")
+    k = torch.empty((0, w.Hkv, w.T, w.d), dtype=torch.bfloat16, device="cuda")
+    sl = torch.empty((0,), dtype=torch.int32, device="cuda")
+    L = ihip.Layer(q, k, sl, 1, w.n_sink, w.n_stream)
+    chunks, keeps = [s[0] for s in w.stages], [s[1] for s in w.stages]
+    scores, _ = L.prune_stage(q, k, chunks[0])
+    assert scores.shape[0] == 0
+    kept = L.select_blocks(scores, chunks[0], keeps[0])
+    assert kept.shape == (0, keeps[0])
+    out = L.decode_layer(q, k, k, chunks, keeps)
+    assert out.shape == (0, w.Hq, 1, w.d)
+    Lp = ihip.Layer(torch.empty((0, w.Hq, 64, w.d), dtype=torch.bfloat16, device="cuda"), k, sl, 64, w.n_sink, 1024)
+    outp = Lp.prefill_layer(torch.empty((0, w.Hq, 64, w.d), dtype=torch.bfloat16, device="cuda"), k, k, chunks, keeps)
+    torch.cuda.synchronize()
+    assert outp.shape == (0, w.Hq, 64, w.d)
