@@ -460,6 +460,24 @@ int32_t ihip_cache_create_fp8(ihip_cache **out, void *dev_mem, size_t dev_bytes,
                               int32_t block_tokens, int32_t mask_slots, int32_t sa_slots, void *stream);
 void    ihip_cache_destroy(ihip_cache *cache);
 int32_t ihip_cache_reset(ihip_cache *cache, void *stream);
+/*
+ * The stage-by-stage calls through the host tier: ihip_prune_stage (decode,
+ * Tq == b_q == 1) reading K through the cache's mask bank, and
+ * ihip_sparse_attn_decode reading K and V through its sparse-attention bank;
+ * everything else as in the calls without the suffix, results bit-identical to
+ * them on the same data.  They record touched and missed blocks like the layer
+ * call, for a later ihip_cache_update.  rope may be NULL (the pruning call uses
+ * rope->prune_style, the attention rope->attn_style); k_scale / v_scale are
+ * used by an E4M3 tier only.
+ */
+int32_t ihip_prune_stage_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache,
+                                const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                                int32_t chunk, int32_t max_chunks, const ihip_rope *rope, float k_scale,
+                                float *out_scores, int32_t *out_rep, void *stream);
+int32_t ihip_sparse_attn_decode_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache,
+                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                       float sm_scale, const ihip_rope *rope, float k_scale, float v_scale,
+                                       void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream);
 int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache,
                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                                  float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,

@@ -101,6 +101,10 @@ EXPORTS = {
     "ihip_cache_reset": (c_i32, [vp, vp]),
     "ihip_decode_layer_cached": (c_i32, [ctypes.POINTER(Shape), Tensor, vp, c_i32, vp, vp, c_f, vp, vp, vp,
                                          vp, c_sz, vp]),
+    "ihip_prune_stage_cached": (c_i32, [ctypes.POINTER(Shape), Tensor, vp, vp, c_i32, c_i32, c_i32, c_i32, vp, c_f,
+                                        vp, vp, vp]),
+    "ihip_sparse_attn_decode_cached": (c_i32, [ctypes.POINTER(Shape), Tensor, vp, vp, c_i32, c_i32, c_f, vp, c_f, c_f,
+                                               vp, vp, vp, c_sz, vp]),
     "ihip_cache_update": (c_i32, [vp, vp]),
     "ihip_cache_stats": (c_i32, [vp, vp]),
     "ihip_cache_read_tables": (c_i32, [vp, c_i32, vp, vp]),
@@ -635,6 +639,39 @@ class HostKVCache:
         sb = np.empty(self.mask_slots if bank == 0 else self.sa_slots, np.int32)
         _check(lib().ihip_cache_read_tables(self.handle, bank, pt.ctypes.data_as(vp), sb.ctypes.data_as(vp)))
         return pt, sb
+
+
+def prune_stage_cached(layer: "Layer", q, cache: HostKVCache, chunk: int, parent_starts=None, parent_chunk: int = 0,
+                       want_rep: bool = False, rope: Optional["Rope"] = None, k_scale: float = 1.0):
+    """ihip_prune_stage_cached -> scores fp32 [P, slots], rep int32 [B,Hq,1,slots] or None."""
+    if parent_starts is None:
+        n_parent, slots = 0, layer.stage1_slots(chunk)
+    else:
+        n_parent = parent_starts.shape[-1]
+        slots = n_parent * (parent_chunk // chunk)
+    scores = torch.empty((layer.P, slots), dtype=torch.float32, device=layer.device)
+    rep = torch.empty((layer.B, layer.Hq, 1, slots), dtype=torch.int32, device=layer.device) if want_rep else None
+    _check(lib().ihip_prune_stage_cached(ctypes.byref(layer.shape), _tensor(q, "q"), cache.handle, _ptr(parent_starts),
+                                         n_parent, parent_chunk, chunk, slots,
+                                         rope.ref() if rope is not None else None, k_scale, _ptr(scores), _ptr(rep),
+                                         _stream()))
+    return scores, rep
+
+
+def sparse_attn_decode_cached(layer: "Layer", q, cache: HostKVCache, block_starts, block: int, sm_scale=None,
+                              want_lse: bool = False, rope: Optional["Rope"] = None,
+                              kv_scales: Sequence[float] = (1.0, 1.0)):
+    """ihip_sparse_attn_decode_cached -> (out bf16 [B,Hq,1,d], lse or None)."""
+    n_blocks = block_starts.shape[-1]
+    sm_scale = 1.0 / math.sqrt(layer.d) if sm_scale is None else sm_scale
+    out = torch.empty((layer.B, layer.Hq, 1, layer.d), dtype=torch.bfloat16, device=layer.device)
+    lse = torch.empty((layer.B, layer.Hq, 1), dtype=torch.float32, device=layer.device) if want_lse else None
+    ws = layer.workspace(OP_ATTN_DECODE, [block], [max(n_blocks, 1)])
+    _check(lib().ihip_sparse_attn_decode_cached(ctypes.byref(layer.shape), _tensor(q, "q"), cache.handle,
+                                                _ptr(block_starts), n_blocks, block, sm_scale,
+                                                rope.ref() if rope is not None else None, kv_scales[0], kv_scales[1],
+                                                _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream()))
+    return out, lse
 
 
 def decode_layer_cached(layer: "Layer", q, cache: HostKVCache, chunk_sizes, keeps, sm_scale=None, ws=None,

@@ -322,7 +322,7 @@ int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk)
 
 static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
                          int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
-                         float *out_scores, int32_t *out_rep, void *stream)
+                         float *out_scores, int32_t *out_rep, void *stream, const BankView *bank = nullptr)
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
@@ -337,7 +337,7 @@ static int32_t prune_stage_entry(const char *who, const ihip_rope *rope, const K
     if (shape->b_q == 1 && shape->Tq != 1)
         return fail(IHIP_ERR_INVALID_ARG, "%s: b_q == 1 is the decode path and needs Tq == 1", who);
     return launch_prune_stage(*shape, q, k, parent_starts, n_parent, parent_chunk, chunk, max_chunks, out_scores,
-                              out_rep, nullptr, rope, (hipStream_t)stream, fmt);
+                              out_rep, bank, rope, (hipStream_t)stream, fmt);
 }
 
 int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, const int32_t *parent_starts,
@@ -436,7 +436,8 @@ int32_t ihip_select_blocks_pooled(const ihip_shape *shape, const float *scores, 
 
 static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                 const int32_t *block_starts, int32_t n_blocks, int32_t block, float sm_scale,
-                                void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+                                void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream,
+                                const BankView *bank = nullptr)
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
@@ -452,7 +453,7 @@ static int32_t attn_decode_entry(const char *who, const ihip_rope *rope, const K
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
     return launch_attn_decode(*shape, q, k, v, block_starts, n_blocks, block, sm_scale, out, out_lse, ws,
-                              nullptr, rope, (hipStream_t)stream, fmt);
+                              bank, rope, (hipStream_t)stream, fmt);
 }
 
 int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
@@ -709,6 +710,61 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
                     who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
     return decode_layer_impl(who, shape, q, hk, hv, cache, nullptr, false, nullptr, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
                              out_block_starts, ws, ws_bytes, stream);
+}
+
+// what the stage-by-stage calls through the host tier share: the cache fits the shape; E4M3 tiers
+// bring their scales
+static int32_t cached_stage_setup(const char *who, const ihip_shape *shape, const ihip_cache *cache, float k_scale,
+                                  float v_scale, ihip_tensor *hk, ihip_tensor *hv, KvFormat *fmt, bool *fp8)
+{
+    if (!cache) return fail(IHIP_ERR_INVALID_ARG, "%s: cache is NULL", who);
+    int32_t B, Hkv;
+    int64_t T_alloc;
+    cache_describe(cache, &B, &Hkv, &T_alloc, hk, hv);
+    if (shape && (shape->B != B || shape->Hkv != Hkv || shape->max_seq_len > T_alloc))
+        return fail(IHIP_ERR_INVALID_ARG, "%s: shape (B %d, Hkv %d, max_seq_len %d) does not fit the cache (%d, %d, %lld)",
+                    who, shape->B, shape->Hkv, shape->max_seq_len, B, Hkv, (long long)T_alloc);
+    *fp8 = cache_holds_fp8(cache);
+    *fmt = KvFormat{*fp8, 1.0f, 1.0f, PagedView{nullptr, 0, 0}};
+    if (*fp8) {
+        const int32_t rc = check_scales(who, k_scale, v_scale);
+        if (rc != IHIP_OK) return rc;
+        fmt->k_scale = k_scale;
+        fmt->v_scale = v_scale;
+    }
+    return IHIP_OK;
+}
+
+int32_t ihip_prune_stage_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache, const int32_t *parent_starts,
+                                int32_t n_parent, int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
+                                const ihip_rope *rope, float k_scale, float *out_scores, int32_t *out_rep,
+                                void *stream)
+{
+    const char *who = "ihip_prune_stage_cached";
+    ihip_tensor hk, hv;
+    KvFormat fmt;
+    bool fp8;
+    const int32_t rc = cached_stage_setup(who, shape, cache, k_scale, 1.0f, &hk, &hv, &fmt, &fp8);
+    if (rc != IHIP_OK) return rc;
+    const BankView bank = cache_bank_view(cache, 0);
+    return prune_stage_entry(who, rope, fp8 ? &fmt : nullptr, shape, q, hk, parent_starts, n_parent, parent_chunk,
+                             chunk, max_chunks, out_scores, out_rep, stream, &bank);
+}
+
+int32_t ihip_sparse_attn_decode_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache,
+                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                       float sm_scale, const ihip_rope *rope, float k_scale, float v_scale,
+                                       void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ihip_sparse_attn_decode_cached";
+    ihip_tensor hk, hv;
+    KvFormat fmt;
+    bool fp8;
+    const int32_t rc = cached_stage_setup(who, shape, cache, k_scale, v_scale, &hk, &hv, &fmt, &fp8);
+    if (rc != IHIP_OK) return rc;
+    const BankView bank = cache_bank_view(cache, 1);
+    return attn_decode_entry(who, rope, fp8 ? &fmt : nullptr, shape, q, hk, hv, block_starts, n_blocks, block,
+                             sm_scale, out, out_lse, ws, ws_bytes, stream, &bank);
 }
 
 size_t ihip_mask_state_elems(const ihip_shape *shape, int32_t n_stages, const int32_t *keeps)

@@ -256,3 +256,55 @@ def test_host_tier_with_fp8_rows(ihip, orc, rope):
             L.decode_layer(qd, None, None, chunks, keeps, cache=cache)
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_stage_by_stage_calls_through_the_host_tier(ihip, orc, fp8):
+    """ihip_prune_stage_cached / ihip_sparse_attn_decode_cached: every stage bit-identical to the resident
+    stage calls, the recorded touches and misses those of the layer call (same LRU simulation)."""
+    from workloads import gen
+    w = configs.shrink(configs.CFG1, B=2, Hq=8, Hkv=2, T=4096 + 29, n_stream=256, n_needles=0,
+                       stages=((64, 8), (16, 8), (4, 16)))
+    bt, mask_slots, sa_slots = 64, 40, 24
+    _, k, v, _, _ = configs.make_inputs(w, 0, kind="int")
+    sl = torch.tensor([w.T, w.T - 700], dtype=torch.int32)
+    scales = (0.5, 0.25) if fp8 else None
+    if fp8:
+        k, v = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
+    hk = torch.empty(k.shape, dtype=k.dtype, pin_memory=True).copy_(k)
+    hv = torch.empty(v.shape, dtype=v.dtype, pin_memory=True).copy_(v)
+    kd, vd, sld = k.cuda(), v.cuda(), sl.cuda()
+    cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots)
+    blocks_per_head = (w.T + bt - 1) // bt
+    sim = [orc.LruBank(cache.n_blocks_total, mask_slots), orc.LruBank(cache.n_blocks_total, sa_slots)]
+    try:
+        for call, seed in enumerate([0, 1, 0, 2]):
+            q = configs.make_q(w, seed, kind="int")
+            qd = q.cuda()
+            L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
+            parents, pchunk = None, 0
+            for (l_c, keep) in w.stages:
+                ref_s, ref_r = L.prune_stage(qd, kd, l_c, parents, pchunk, want_rep=True,
+                                             k_scale=scales[0] if fp8 else None)
+                got_s, got_r = ihip.prune_stage_cached(L, qd, cache, l_c, parents, pchunk, want_rep=True,
+                                                       k_scale=scales[0] if fp8 else 1.0)
+                assert torch.equal(ref_s, got_s) and torch.equal(ref_r, got_r), (call, l_c)
+                parents, pchunk = L.select_blocks(got_s, l_c, keep, parents, pchunk), l_c
+            ref_o, ref_l = L.sparse_attn_decode(qd, kd, vd, parents, pchunk, want_lse=True, kv_scales=scales)
+            got_o, got_l = ihip.sparse_attn_decode_cached(L, qd, cache, parents, pchunk, want_lse=True,
+                                                          kv_scales=scales if fp8 else (1.0, 1.0))
+            cache.update()
+            torch.cuda.synchronize()
+            assert torch.equal(ref_o, got_o) and torch.equal(ref_l, got_l), call
+            o = orc.Oracle(q, k, v, sl.tolist(), 1, w.n_sink, w.n_stream, kv_scales=scales)
+            res = o.layer(w.stages)
+            stats = cache.stats()
+            for bank, name in ((0, "mask"), (1, "sa")):
+                sim[bank].call(touched_blocks(o, w, res, bt, blocks_per_head, bank))
+                pt, sb = cache.tables(bank)
+                assert stats[name]["last_touched"] == sim[bank].last_touched, (call, name)
+                assert stats[name]["last_misses"] == sim[bank].last_misses, (call, name)
+                assert pt.tolist() == sim[bank].page_table, (call, name)
+                assert sb.tolist() == sim[bank].slot_block, (call, name)
+    finally:
+        cache.close()
