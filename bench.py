@@ -80,6 +80,8 @@ def parse():
                     help="decode only: comma-separated mask refresh intervals per stage (e.g. 16,8,4,2); "
                          "stage i is recomputed only at steps that are multiples of its interval and the "
                          "cached masks are reused otherwise (the reported value is then the amortised time)")
+    ap.add_argument("--bank-mib", type=int, default=512,
+                    help="cfg5 only: on-GPU bytes of the hot-block banks (default 512 MiB: a 16 GB budget over 32 layers)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 device copies of 1 GiB (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -126,7 +128,22 @@ def timed_passes(step, steps, warmup, ihip, torch, profile, graph=False):
         ihip.profile_enable(False)
         for name, (ms, n) in ihip.profile_read().items():
             kernels[name] = {"us": ms / n * 1e3, "launches_per_step": n / steps}
-    return us, kernels
+    return us, kernels, step_spread(step, steps, torch) if not graph else None
+
+
+def step_spread(step, steps, torch, first=0):
+    """The same steps once more with an event pair around each (the library enqueues on torch's current
+    stream): p10 / median / p90 of the per-step times, which the mean over the timed region hides."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i in range(steps):
+        ev[i][0].record()
+        step(first + i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+    pick = lambda f: t[min(len(t) - 1, int(f * len(t)))]      # noqa: E731
+    progress("per-step spread done")
+    return {"p10": pick(0.1), "median": pick(0.5), "p90": pick(0.9), "n": len(t), "unit": "us"}
 
 
 def dominant(kernels):
@@ -261,7 +278,7 @@ def bench_decode(args, w, torch, ihip, configs):
                        paged=paged, stage_starts=state,
                        first_stage=ihip.first_stage_due(i, refresh) if refresh else None)
 
-    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass, args.graph)
+    us_per_layer, kernels, spread = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass, args.graph)
 
     cpu = sample = None
     if args.cpu_seconds > 0 and not args.rope:
@@ -306,7 +323,8 @@ def bench_decode(args, w, torch, ihip, configs):
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
                    "n_stream": w.n_stream, "query_sets": N_QUERY_SETS, "distinct_kv_layers": n_layers,
                    "mask_refresh": refresh, "kv_layout": args.kv_layout},
-        "roofline": roofline, "cpu_baseline": cpu, "whole_path": whole, "kernels": kernels, "setup_s": t_setup,
+        "roofline": roofline, "cpu_baseline": cpu, "whole_path": whole, "kernels": kernels, "step_us": spread,
+        "setup_s": t_setup,
     }
 
 
@@ -361,7 +379,7 @@ def bench_prefill(args, w, torch, ihip, configs):
     def step(i):
         L.prefill_layer(q, k, v, chunks, keeps, ws=ws, out=out, rope=rope, paged=paged, kv_scales=kv_scales)
 
-    us_per_layer, kernels = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass, args.graph)
+    us_per_layer, kernels, spread = timed_passes(step, steps, warmup, ihip, torch, not args.no_profile_pass, args.graph)
 
     # matrix-core flops actually multiplied, from the geometry alone
     flops = {}
@@ -440,7 +458,7 @@ def bench_prefill(args, w, torch, ihip, configs):
                        "achieved_TFLOPs": sum(flops.values()) / (us_per_layer * 1e-6) / 1e12,
                        "measured_mfma_rate_TFLOPs": {"32x32x16_bf16": measured["attn_prefill"],
                                                      "16x16x32_bf16": measured["prune_prefill"]}},
-        "kernels": kernels, "setup_s": t_setup,
+        "kernels": kernels, "step_us": spread, "setup_s": t_setup,
     }
 
 
@@ -456,7 +474,12 @@ def bench_offload(args, w, torch, ihip, configs):
     warmup = 4 if args.warmup is None else args.warmup
     chunks = [s[0] for s in w.stages]
     keeps = [s[1] for s in w.stages]
-    bt, mask_slots, sa_slots = 64, 16384, 8192
+    # --bank-mib: the on-GPU budget, half for the pruning stages' key bank, half for the attention's
+    # key+value bank (64-token blocks of 256-byte rows); never more slots than the layer has blocks
+    bt = 64
+    n_blocks_total = w.B * w.Hkv * ((w.T + bt - 1) // bt)
+    mask_slots = min(n_blocks_total, (args.bank_mib << 20) // 2 // (bt * 256))
+    sa_slots = min(n_blocks_total, (args.bank_mib << 20) // 2 // (bt * 512))
     shape = (w.B, w.Hkv, w.T, w.d)
 
     t0 = time.perf_counter()
@@ -498,7 +521,7 @@ def bench_offload(args, w, torch, ihip, configs):
                 t_hi = min(w.T, t_lo + step_t)
                 dst[:, :, t_lo:t_hi].copy_(gen.to_e4m3(src[:, :, t_lo:t_hi].to(dev), sc))
         hk, hv = hk8, hv8
-        mask_slots, sa_slots, row_bytes = 2 * mask_slots, 2 * sa_slots, 128
+        mask_slots, sa_slots, row_bytes = min(n_blocks_total, 2 * mask_slots), min(n_blocks_total, 2 * sa_slots), 128
     rope = None
     if args.rope:
         n_pos = max(n_chunks + 1, max(keeps)) + w.n_sink + w.n_stream + keeps[-1] * chunks[-1] + 8
