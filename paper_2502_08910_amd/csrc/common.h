@@ -284,6 +284,19 @@ __device__ inline float row16_sum(float v)
     return v;
 }
 
+// Maximum over the four 16-lane rows of a wave (lanes l, l^16, l^32, l^48), in every lane.  Two
+// in-register row swaps (v_permlane16_swap: odd rows of one copy against even rows of the other;
+// v_permlane32_swap: upper half against lower half) instead of two round trips through LDS.
+__device__ inline float max_over_rows(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    const unsigned w = __float_as_uint(x);
+    const auto s = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return fmaxf(__uint_as_float(s[0]), __uint_as_float(s[1]));
+}
+
 __device__ inline int ilog2(int x) { return 31 - __builtin_clz(x); }
 
 // 16-byte row fragment load for lane l16 of a row group

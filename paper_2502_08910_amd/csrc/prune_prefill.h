@@ -210,13 +210,9 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
                     bestR = fmaxf(bestR, fmaxf(fmaxf(cr[0], cr[1]), fmaxf(cr[2], cr[3])));
                 }
             }
-            best = fmaxf(best, __shfl_xor(best, 16, 64));
-            best = fmaxf(best, __shfl_xor(best, 32, 64));
-            sig[t] = best;
+            sig[t] = max_over_rows(best);
             if constexpr (ROPE == 1) {
-                bestR = fmaxf(bestR, __shfl_xor(bestR, 16, 64));
-                bestR = fmaxf(bestR, __shfl_xor(bestR, 32, 64));
-                sigR[t] = bestR;
+                sigR[t] = max_over_rows(bestR);
             }
         }
     };
