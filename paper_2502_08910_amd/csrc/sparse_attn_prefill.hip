@@ -212,8 +212,7 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
             }
             float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                              fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = max_over_rows(mx);        // over the four key groups of the lane's query
             const float mn = fmaxf(m_run[qt], mx);
             const float corr = exp2f(m_run[qt] - mn);
             m_run[qt] = mn;
