@@ -458,6 +458,21 @@ size_t  ihip_cache_device_bytes_fp8(int32_t B, int32_t Hkv, int64_t T_alloc, int
 int32_t ihip_cache_create_fp8(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k,
                               ihip_tensor host_v, int32_t B, int32_t Hkv, int64_t T_alloc,
                               int32_t block_tokens, int32_t mask_slots, int32_t sa_slots, void *stream);
+/*
+ * The same tier with the host memory organised in pages (the serving systems
+ * the paper runs in keep K and V in fixed-size pages, also when they are
+ * offloaded): host_k_pool / host_v_pool are pinned host page pools laid out as
+ * in ihip_paged_kv (stride_b = between pages), host_pages->block_table is a
+ * DEVICE int32 [B][table_stride] array of page ids that must stay valid and
+ * unchanged while the cache is in use, table_stride * page_tokens >= T_alloc.
+ * kv_fp8 != 0: E4M3 pools (strides in bytes).  The banks, their block ids
+ * (logical positions) and the LRU policy are those of the contiguous tier;
+ * only the address of a row in host memory goes through the table.
+ */
+int32_t ihip_cache_create_paged(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k_pool,
+                                ihip_tensor host_v_pool, const ihip_paged_kv *host_pages, int32_t kv_fp8,
+                                int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens,
+                                int32_t mask_slots, int32_t sa_slots, void *stream);
 void    ihip_cache_destroy(ihip_cache *cache);
 int32_t ihip_cache_reset(ihip_cache *cache, void *stream);
 /*

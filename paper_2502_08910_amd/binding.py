@@ -98,6 +98,8 @@ EXPORTS = {
     "ihip_cache_create": (c_i32, [ctypes.POINTER(vp), vp, c_sz, Tensor, Tensor, c_i32, c_i32, c_i64, c_i32,
                                   c_i32, c_i32, vp]),
     "ihip_cache_destroy": (None, [vp]),
+    "ihip_cache_create_paged": (c_i32, [ctypes.POINTER(vp), vp, c_sz, Tensor, Tensor, vp, c_i32, c_i32, c_i32, c_i64,
+                                        c_i32, c_i32, c_i32, vp]),
     "ihip_cache_reset": (c_i32, [vp, vp]),
     "ihip_decode_layer_cached": (c_i32, [ctypes.POINTER(Shape), Tensor, vp, c_i32, vp, vp, c_f, vp, vp, vp,
                                          vp, c_sz, vp]),
@@ -582,10 +584,14 @@ class HostKVCache:
     host_k / host_v: pinned CPU tensors [B,Hkv,T,d] (torch's pin_memory=True),
     bf16 or -- for an FP8 KV cache -- uint8 holding E4M3 bytes; the banks and
     tables are carved out of one device buffer allocated here through PyTorch
-    and kept alive with the handle."""
+    and kept alive with the handle.
+
+    block_table (device int32 [B, pages per sequence]) + seq_tokens: host_k / host_v are page pools
+    [n_pages,Hkv,page_tokens,d] read through the table (ihip_cache_create_paged); seq_tokens is the
+    token capacity per sequence."""
 
     def __init__(self, host_k: torch.Tensor, host_v: torch.Tensor, block_tokens: int, mask_slots: int,
-                 sa_slots: int, device="cuda:0"):
+                 sa_slots: int, device="cuda:0", block_table: Optional[torch.Tensor] = None, seq_tokens: int = 0):
         self.fp8 = host_k.dtype in (torch.uint8, torch.float8_e4m3fn)
         for t, name in ((host_k, "host_k"), (host_v, "host_v")):
             if t.dtype != host_k.dtype or (not self.fp8 and t.dtype != torch.bfloat16) or t.dim() != 4 \
@@ -593,6 +599,12 @@ class HostKVCache:
                 raise IhipError(f"{name}: need a pinned 4-d bf16 (or E4M3 byte) CPU tensor with contiguous last dim")
         self.host_k, self.host_v = host_k, host_v
         B, Hkv, T, _ = host_k.shape
+        self.block_table = block_table
+        if block_table is not None:
+            if block_table.dtype != torch.int32 or not block_table.is_cuda or block_table.dim() != 2 \
+                    or block_table.stride(1) != 1:
+                raise IhipError("block_table: need a device int32 [B, pages per sequence] tensor")
+            B, T = block_table.shape[0], seq_tokens
         size_fn = lib().ihip_cache_device_bytes_fp8 if self.fp8 else lib().ihip_cache_device_bytes
         make_fn = lib().ihip_cache_create_fp8 if self.fp8 else lib().ihip_cache_create
         need = size_fn(B, Hkv, T, block_tokens, mask_slots, sa_slots)
@@ -603,8 +615,14 @@ class HostKVCache:
         hk = Tensor(host_k.data_ptr(), host_k.stride(0), host_k.stride(1), host_k.stride(2))
         hv = Tensor(host_v.data_ptr(), host_v.stride(0), host_v.stride(1), host_v.stride(2))
         with torch.cuda.device(self.dev_mem.device):
-            _check(make_fn(ctypes.byref(self.handle), self.dev_mem.data_ptr(), need, hk, hv,
-                           B, Hkv, T, block_tokens, mask_slots, sa_slots, _stream()))
+            if block_table is not None:
+                self._pages = PagedStruct(block_table.data_ptr(), block_table.stride(0), host_k.shape[2])
+                _check(lib().ihip_cache_create_paged(ctypes.byref(self.handle), self.dev_mem.data_ptr(), need, hk, hv,
+                                                     ctypes.byref(self._pages), 1 if self.fp8 else 0, B, Hkv, T,
+                                                     block_tokens, mask_slots, sa_slots, _stream()))
+            else:
+                _check(make_fn(ctypes.byref(self.handle), self.dev_mem.data_ptr(), need, hk, hv,
+                               B, Hkv, T, block_tokens, mask_slots, sa_slots, _stream()))
         self.block_tokens, self.mask_slots, self.sa_slots = block_tokens, mask_slots, sa_slots
         self.n_blocks_total = B * Hkv * ((T + block_tokens - 1) // block_tokens)
 

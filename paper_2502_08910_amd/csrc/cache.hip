@@ -38,6 +38,8 @@ struct ihip_cache {
     int block_tokens, block_log2, blocks_per_head, n_gb;
     ihip_tensor host_k, host_v;   // as given: strides in elements (bf16) or bytes (E4M3)
     int row_units;                // 2-byte units per row: d (bf16) or d/2 (E4M3)
+    const int32_t *host_table;    // paged host tier: device int32 [B][host_table_stride] page ids, else nullptr
+    int host_table_stride, host_page_log2;
     ihip::Bank bank[2];
     uint32_t stamp;           // counter of the current layer call (starts at 1)
 };
@@ -157,7 +159,8 @@ __global__ __launch_bounds__(kCacheThreads) void cache_victims_kernel(const Bank
 __global__ __launch_bounds__(256) void cache_insert_kernel(const Bank b, const ihip_tensor hk, const ihip_tensor hv,
                                                            const int Hkv, const int64_t T_alloc, const int block_log2,
                                                            const int blocks_per_head, const uint32_t stamp,
-                                                           const int row_units)
+                                                           const int row_units, const int32_t *host_table,
+                                                           const int host_table_stride, const int host_page_log2)
 {
     const int i = blockIdx.x;
     if (i >= (int)b.counters[4]) return;
@@ -175,17 +178,23 @@ __global__ __launch_bounds__(256) void cache_insert_kernel(const Bank b, const i
     const int bt = 1 << block_log2;
     const int lanes = row_units >> 3;                 // 16-byte pieces per row: 16 (bf16) or 8 (E4M3)
     const int piece = threadIdx.x % lanes;
-    const uint16_t *src_k = (const uint16_t *)hk.ptr + bb * hk.stride_b + g * hk.stride_h;
-    const uint16_t *src_v = (const uint16_t *)hv.ptr + bb * hv.stride_b + g * hv.stride_h;
+    const bool paged = host_table != nullptr;      // the host tensors are page pools: stride_b between pages
+    const uint16_t *src_k = (const uint16_t *)hk.ptr + (paged ? 0 : bb * hk.stride_b) + g * hk.stride_h;
+    const uint16_t *src_v = (const uint16_t *)hv.ptr + (paged ? 0 : bb * hv.stride_b) + g * hv.stride_h;
     for (int r = threadIdx.x / lanes; r < bt; r += 256 / lanes) {
         const int64_t pos = ((int64_t)blk << block_log2) + r;
         if (pos >= T_alloc) break;
         const int64_t dst = (((int64_t)slot << block_log2) + r) * row_units + piece * 8;
-        *reinterpret_cast<uint4 *>(b.bank_k + dst) =
-            *reinterpret_cast<const uint4 *>(src_k + pos * hk.stride_t + piece * 8);
+        int64_t at_k = pos * hk.stride_t, at_v = pos * hv.stride_t;
+        if (paged) {
+            const int64_t page = host_table[(int64_t)bb * host_table_stride + (pos >> host_page_log2)];
+            const int64_t tok = pos & ((1 << host_page_log2) - 1);
+            at_k = page * hk.stride_b + tok * hk.stride_t;
+            at_v = page * hv.stride_b + tok * hv.stride_t;
+        }
+        *reinterpret_cast<uint4 *>(b.bank_k + dst) = *reinterpret_cast<const uint4 *>(src_k + at_k + piece * 8);
         if (b.bank_v != nullptr)
-            *reinterpret_cast<uint4 *>(b.bank_v + dst) =
-                *reinterpret_cast<const uint4 *>(src_v + pos * hv.stride_t + piece * 8);
+            *reinterpret_cast<uint4 *>(b.bank_v + dst) = *reinterpret_cast<const uint4 *>(src_v + at_v + piece * 8);
     }
 }
 
@@ -203,6 +212,9 @@ BankView cache_bank_view(const ihip_cache *c, int which)
     v.blocks_per_head = c->blocks_per_head;
     v.stamp = c->stamp;
     v.row_units = c->row_units;
+    v.host_table = c->host_table;
+    v.host_table_stride = c->host_table_stride;
+    v.host_page_log2 = c->host_page_log2;
     return v;
 }
 
@@ -256,9 +268,19 @@ size_t ihip_cache_device_bytes_fp8(int32_t B, int32_t Hkv, int64_t T_alloc, int3
 
 static int32_t cache_create(const char *who, int row_units, ihip_cache **out, void *dev_mem, size_t dev_bytes,
                             ihip_tensor host_k, ihip_tensor host_v, int32_t B, int32_t Hkv, int64_t T_alloc,
-                            int32_t block_tokens, int32_t mask_slots, int32_t sa_slots, void *stream)
+                            int32_t block_tokens, int32_t mask_slots, int32_t sa_slots, void *stream,
+                            const ihip_paged_kv *host_pages = nullptr)
 {
     if (!out) return fail(IHIP_ERR_INVALID_ARG, "%s: out is NULL", who);
+    if (host_pages) {
+        if (!host_pages->block_table || host_pages->page_tokens <= 0 ||
+            (host_pages->page_tokens & (host_pages->page_tokens - 1)))
+            return fail(IHIP_ERR_INVALID_ARG, "%s: block_table is NULL or page_tokens = %d is no power of two", who,
+                        host_pages->page_tokens);
+        if ((int64_t)host_pages->table_stride * host_pages->page_tokens < T_alloc)
+            return fail(IHIP_ERR_INVALID_ARG, "%s: the block table covers %lld tokens, T_alloc is %lld", who,
+                        (long long)host_pages->table_stride * host_pages->page_tokens, (long long)T_alloc);
+    }
     const size_t need = cache_device_bytes(B, Hkv, T_alloc, block_tokens, mask_slots, sa_slots, row_units);
     if (need == 0) return fail(IHIP_ERR_INVALID_ARG, "%s: bad sizes (block_tokens must be a power of two)", who);
     if (mask_slots > 65536 * 16 || sa_slots > 65536 * 16)
@@ -292,6 +314,9 @@ static int32_t cache_create(const char *who, int row_units, ihip_cache **out, vo
     c->n_gb = B * Hkv * c->blocks_per_head;
     c->host_k = host_k; c->host_v = host_v;
     c->row_units = row_units;
+    c->host_table = host_pages ? host_pages->block_table : nullptr;
+    c->host_table_stride = host_pages ? host_pages->table_stride : 0;
+    c->host_page_log2 = host_pages ? __builtin_ctz(host_pages->page_tokens) : 0;
     size_t off = 0;
     carve_bank(c->bank[0], (char *)dev_mem, off, c->n_gb, mask_slots, block_tokens, false, row_units);
     carve_bank(c->bank[1], (char *)dev_mem, off, c->n_gb, sa_slots, block_tokens, true, row_units);
@@ -315,6 +340,16 @@ int32_t ihip_cache_create_fp8(ihip_cache **out, void *dev_mem, size_t dev_bytes,
 {
     return cache_create("ihip_cache_create_fp8", kD / 2, out, dev_mem, dev_bytes, host_k, host_v, B, Hkv, T_alloc,
                         block_tokens, mask_slots, sa_slots, stream);
+}
+
+int32_t ihip_cache_create_paged(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k_pool,
+                                ihip_tensor host_v_pool, const ihip_paged_kv *host_pages, int32_t kv_fp8, int32_t B,
+                                int32_t Hkv, int64_t T_alloc, int32_t block_tokens, int32_t mask_slots,
+                                int32_t sa_slots, void *stream)
+{
+    if (!host_pages) return fail(IHIP_ERR_INVALID_ARG, "ihip_cache_create_paged: host_pages is NULL");
+    return cache_create("ihip_cache_create_paged", kv_fp8 ? kD / 2 : kD, out, dev_mem, dev_bytes, host_k_pool,
+                        host_v_pool, B, Hkv, T_alloc, block_tokens, mask_slots, sa_slots, stream, host_pages);
 }
 
 void ihip_cache_destroy(ihip_cache *c) { delete c; }
@@ -345,7 +380,8 @@ int32_t ihip_cache_update(ihip_cache *c, void *stream)
             if (c->row_units != kD)
                 for (ihip_tensor *x : {&hk, &hv}) { x->stride_b /= 2; x->stride_h /= 2; x->stride_t /= 2; }
             hipLaunchKernelGGL(cache_insert_kernel, dim3(b.n_slots), dim3(256), 0, st, b, hk, hv, c->Hkv,
-                               c->T_alloc, c->block_log2, c->blocks_per_head, c->stamp, c->row_units);
+                               c->T_alloc, c->block_log2, c->blocks_per_head, c->stamp, c->row_units,
+                               c->host_table, c->host_table_stride, c->host_page_log2);
         }
     }
     c->stamp += 1;

@@ -136,14 +136,20 @@ struct BankView {
     int blocks_per_head;         // blocks of one (sequence, KV head)
     uint32_t stamp;              // this call's counter value
     int row_units;               // 2-byte units of one row: d for bf16 rows, d/2 for E4M3 rows
+    // the host tier is a page pool read through a block table (device int32 [B][host_table_stride]),
+    // or contiguous per sequence (host_table == nullptr)
+    const int32_t *host_table;
+    int host_table_stride, host_page_log2;
 };
 
 struct CachedRows {
     BankView c;
-    const uint16_t *host_base;   // row 0 of this (sequence, KV head) in host memory
+    const uint16_t *host_base;   // row 0 of this (sequence, KV head) in host memory (paged: of this head in page 0)
     int64_t host_st;
     const uint16_t *bank;        // bank_k or bank_v
     int gb0;                     // global id of this (sequence, KV head)'s block 0
+    const int32_t *host_pages;   // paged host tier: this sequence's row of the block table, else nullptr
+    int64_t host_page_stride;
     // leader: one lane per row does the bookkeeping stores
     __device__ const uint16_t *row(int pos, bool leader) const
     {
@@ -156,9 +162,22 @@ struct CachedRows {
         }
         if (slot >= 0)
             return bank + ((((int64_t)slot << c.block_log2) | (pos & ((1 << c.block_log2) - 1))) * c.row_units);
+        if (host_pages != nullptr)
+            return host_base + (int64_t)host_pages[pos >> c.host_page_log2] * host_page_stride +
+                   (int64_t)(pos & ((1 << c.host_page_log2) - 1)) * host_st;
         return host_base + (int64_t)pos * host_st;
     }
 };
+
+// Rows of (sequence b, KV head g) behind the host tier.  base / sb / sh / st: the host tensor (paged:
+// the pool, sb = elements between pages); bank: the bank's K or V rows.
+__device__ inline CachedRows cached_rows(const BankView &c, const uint16_t *base, int64_t sb, int64_t sh, int64_t st,
+                                         const uint16_t *bank, int b, int g, int Hkv)
+{
+    const bool paged = c.host_table != nullptr;
+    return CachedRows{c, paged ? base + g * sh : base + b * sb + g * sh, st, bank, (b * Hkv + g) * c.blocks_per_head,
+                      paged ? c.host_table + (int64_t)b * c.host_table_stride : nullptr, sb};
+}
 
 // ---- bf16 ------------------------------------------------------------------
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

@@ -62,8 +62,7 @@ template <> struct KeySource<1> {
     typedef CachedRows type;
     static __device__ type make(const PruneArgs &a, const Problem &pr)
     {
-        return CachedRows{a.bank, a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st, a.bank.bank_k,
-                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+        return cached_rows(a.bank, a.k, a.k_sb, a.k_sh, a.k_st, a.bank.bank_k, pr.b, pr.g, a.ge.Hkv);
     }
 };
 

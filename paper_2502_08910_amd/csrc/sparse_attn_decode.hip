@@ -58,13 +58,11 @@ template <> struct KvSource<1> {
     typedef CachedRows type;
     static __device__ type k(const AttnDecodeArgs &a, const Problem &pr)
     {
-        return CachedRows{a.bank, a.k + pr.b * a.k_sb + pr.g * a.k_sh, a.k_st, a.bank.bank_k,
-                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+        return cached_rows(a.bank, a.k, a.k_sb, a.k_sh, a.k_st, a.bank.bank_k, pr.b, pr.g, a.ge.Hkv);
     }
     static __device__ type v(const AttnDecodeArgs &a, const Problem &pr)
     {
-        return CachedRows{a.bank, a.v + pr.b * a.v_sb + pr.g * a.v_sh, a.v_st, a.bank.bank_v,
-                          (pr.b * a.ge.Hkv + pr.g) * a.bank.blocks_per_head};
+        return cached_rows(a.bank, a.v, a.v_sb, a.v_sh, a.v_st, a.bank.bank_v, pr.b, pr.g, a.ge.Hkv);
     }
 };
 

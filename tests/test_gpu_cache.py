@@ -308,3 +308,50 @@ def test_stage_by_stage_calls_through_the_host_tier(ihip, orc, fp8):
                 assert sb.tolist() == sim[bank].slot_block, (call, name)
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("page", [16, 256])
+def test_paged_host_tier_equals_resident_and_follows_lru(ihip, orc, page, fp8):
+    """ihip_cache_create_paged: the host memory is a page pool in a seeded random page order (pages smaller
+    and larger than a cache block); outputs bit-identical to the resident path, tables as the simulation."""
+    from workloads import gen
+    from test_gpu_random_shapes import scatter_to_pages
+    w = configs.shrink(configs.CFG1, B=2, Hq=8, Hkv=2, T=4096, n_stream=256, n_needles=0,
+                       stages=((64, 8), (16, 8), (4, 16)))
+    bt, mask_slots, sa_slots = 64, 40, 24
+    chunks, keeps = [s[0] for s in w.stages], [s[1] for s in w.stages]
+    _, k, v, _, _ = configs.make_inputs(w, 0, kind="int")
+    sl = torch.tensor([w.T, w.T - 700], dtype=torch.int32)
+    scales = (0.5, 0.25) if fp8 else None
+    if fp8:
+        k, v = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
+    k_pool, v_pool, table = scatter_to_pages(k, v, page, 21, 7)
+    hk = torch.empty(k_pool.shape, dtype=k.dtype, pin_memory=True).copy_(k_pool)
+    hv = torch.empty(v_pool.shape, dtype=v.dtype, pin_memory=True).copy_(v_pool)
+    kd, vd, sld = k.cuda(), v.cuda(), sl.cuda()
+    cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots, block_table=table.cuda(), seq_tokens=w.T)
+    blocks_per_head = (w.T + bt - 1) // bt
+    sim = [orc.LruBank(cache.n_blocks_total, mask_slots), orc.LruBank(cache.n_blocks_total, sa_slots)]
+    try:
+        for call, seed in enumerate([0, 1, 0, 2, 1]):
+            q = configs.make_q(w, seed, kind="int")
+            qd = q.cuda()
+            L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
+            ref_blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+            ref = L.decode_layer(qd, kd, vd, chunks, keeps, out_blocks=ref_blocks, kv_scales=scales)
+            got_blocks = torch.empty_like(ref_blocks)
+            got = L.decode_layer(qd, None, None, chunks, keeps, out_blocks=got_blocks, cache=cache, kv_scales=scales)
+            cache.update()
+            torch.cuda.synchronize()
+            assert torch.equal(got_blocks, ref_blocks) and torch.equal(got, ref), call
+            o = orc.Oracle(q, k, v, sl.tolist(), 1, w.n_sink, w.n_stream, kv_scales=scales)
+            res = o.layer(w.stages)
+            stats = cache.stats()
+            for bank, name in ((0, "mask"), (1, "sa")):
+                sim[bank].call(touched_blocks(o, w, res, bt, blocks_per_head, bank))
+                pt, sb = cache.tables(bank)
+                assert stats[name]["last_misses"] == sim[bank].last_misses, (call, name)
+                assert pt.tolist() == sim[bank].page_table and sb.tolist() == sim[bank].slot_block, (call, name)
+    finally:
+        cache.close()
