@@ -130,6 +130,63 @@ def test_random_decode_layer(ihip, orc, seed):
     check_against_oracle(w, o, sl, blocks, out, 1, pooled)
 
 
+@pytest.mark.parametrize("seed", list(range(max(8, N_DECODE // 2))))
+def test_random_decode_layer_behind_the_host_tier(ihip, orc, seed):
+    """The same draws with K/V in pinned host memory (contiguous or a page pool) behind hot-block banks of
+    random size: two calls with an update in between (the second is served partly from the banks), both
+    against the oracle; RoPE, E4M3 rows and all-heads pooling at random."""
+    rng = np.random.default_rng(4000 + seed)
+    B, Hkv, G = int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 4, 8]))
+    T = int(rng.integers(300, 3000))
+    n_sink, n_stream = int(rng.choice([0, 4, 100, 128])), int(rng.choice([1, 17, 256]))
+    stages = tuple(draw_plan(rng, [256, 64, 32, 8]))
+    w = configs.shrink(configs.CFG1, B=B, Hq=Hkv * G, Hkv=Hkv, T=T, n_sink=n_sink, n_stream=n_stream,
+                       n_needles=0, stages=stages)
+    sl = torch.tensor([T if b == 0 else int(rng.integers(1, T + 1)) for b in range(B)], dtype=torch.int32)
+    rope = rng.choice([None, "relative", "chunk"])
+    fp8, page = bool(rng.integers(0, 2)), int(rng.choice([0, 0, 4, 16, 128]))
+    pooled = bool(rng.integers(0, 4) == 0)
+    bt = int(rng.choice([16, 64]))
+    mask_slots, sa_slots = int(rng.integers(1, 60)), int(rng.integers(1, 60))
+    q, k, v, _, _ = configs.make_inputs(w, seed, kind="int")
+    scales = (0.5, 0.25) if fp8 else None
+    if fp8:
+        k, v = gen.to_e4m3(k, scales[0]), gen.to_e4m3(v, scales[1])
+    cos, sin = gen.quarter_turn_table(20000, w.d)
+    spec = orc.RopeSpec(cos.numpy(), sin.numpy(), prune=str(rope), attn="streaming") if rope is not None else None
+    rp = None
+    if rope is not None:
+        style = ihip.ROPE_RELATIVE if rope == "relative" else ihip.ROPE_CHUNK_INDEXED
+        rp = ihip.Rope(cos.cuda(), sin.cuda(), style, ihip.ROPE_STREAMING)
+    if page:
+        k_pool, v_pool, table = scatter_to_pages(k, v, page, seed, 7)
+        hk = torch.empty(k_pool.shape, dtype=k.dtype, pin_memory=True).copy_(k_pool)
+        hv = torch.empty(v_pool.shape, dtype=v.dtype, pin_memory=True).copy_(v_pool)
+        cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots, block_table=table.cuda(), seq_tokens=T)
+    else:
+        hk = torch.empty(k.shape, dtype=k.dtype, pin_memory=True).copy_(k)
+        hv = torch.empty(v.shape, dtype=v.dtype, pin_memory=True).copy_(v)
+        cache = ihip.HostKVCache(hk, hv, bt, mask_slots, sa_slots)
+    try:
+        chunks, keeps = [s[0] for s in stages], [s[1] for s in stages]
+        for call in range(2):
+            q = configs.make_q(w, seed + call, kind="int")
+            qd = q.cuda()
+            L = ihip.Layer(qd, torch.empty((B, Hkv, T, 0), dtype=torch.bfloat16, device="cuda"), sl.cuda(), 1,
+                           n_sink, n_stream)
+            blocks = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+            out = L.decode_layer(qd, None, None, chunks, keeps, out_blocks=blocks, rope=rp, kv_scales=scales,
+                                 cache=cache, pooling=ihip.POOL_ALL_HEADS if pooled else None)
+            cache.update()
+            torch.cuda.synchronize()
+            o = orc.Oracle(q, k, v, sl.tolist(), 1, n_sink, n_stream, rope=spec, kv_scales=scales)
+            check_against_oracle(w, o, sl, blocks, out, 1, pooled)
+        st = cache.stats()
+        assert st["mask"]["last_touched"] >= 0 and st["sa"]["last_touched"] > 0
+    finally:
+        cache.close()
+
+
 @pytest.mark.parametrize("seed", [pytest.param(s, id=f"large{s}") for s in range(100, 100 + max(3, N_PREFILL // 3))]
                          + list(range(N_PREFILL)))
 def test_random_prefill_layer(ihip, orc, seed):
