@@ -91,16 +91,29 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
     // on the source side: 16-byte slot c of tile row R holds dims 8*(c ^ (R%16)).., which makes the
     // 16 rows of an operand read hit 16 different bank groups.
     // load4(base, stride, dst, row, swz): lanes 16*kq..+15 fetch row `row` (their own copy of it)
-    // to the tile row dst + kq; dst is the LDS byte address of a four-row group, wave-uniform.  A
-    // row of -1 stands for "no candidate": row 0 is fetched instead (always readable) and the
-    // caller ignores the score, which keeps the loads free of branches: with exec-masked loads
+    // to the tile row dst + kq; dst is the LDS byte address of a four-row group, wave-uniform.
+    // "No candidate" is row 0 (always readable; the lane that owns the candidate substitutes it) and
+    // the caller ignores the score, which keeps the loads free of branches: with exec-masked loads
     // every shuffle result has to be waited for on its own.  The instruction is written as
     // assembly so that the destinations can be computed once, outside the search loops.
+    // Narrow offsets: the base is wave-uniform (scalar registers) and the lane's byte offset one
+    // 24-bit multiply and an add, the load's scalar-base form.
+    // `row` is never negative here: the lane that owns a candidate passes row 0 for "no candidate".
     auto load4 = [&](const uint16_t *base, off_t stride, uint32_t dst, int row, int swz) {
-        const off_t r = (off_t)max(row, 0);
-        const off_t at = WIDE ? r * stride : (off_t)__umul24((uint32_t)r, (uint32_t)stride);
-        const uint16_t *src = base + at + ((n ^ swz) << 3);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+        const off_t r = (off_t)row;
+        if constexpr (WIDE) {
+            const uint16_t *src = base + r * stride + ((n ^ swz) << 3);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+        } else {
+            const uint32_t byte_off = __umul24((uint32_t)r, (uint32_t)stride * 2u) + (uint32_t)((n ^ swz) << 4);
+            const uint64_t b64 = (uint64_t)(uintptr_t)base;
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b64);
+            const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
+            const uint64_t sbase = ((uint64_t)hi << 32) | lo;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(byte_off),
+                         "s"(sbase)
+                         : "memory");
+        }
     };
     // the same with the row's element offset already formed (paged K)
     auto load4_at = [&](const uint16_t *base, int64_t at, uint32_t dst, int swz) {
@@ -272,7 +285,7 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
             int cand[NT * 4];
 #pragma unroll
             for (int r = 0; r < NT * 4; ++r)     // lanes 0..15 hold column = lane
-                cand[r] = __shfl(ok[r >> 2] ? pos[r >> 2] : -1, (r & 3) * 4 + kq, 64);
+                cand[r] = __shfl(ok[r >> 2] ? pos[r >> 2] : 0, (r & 3) * 4 + kq, 64);
 #pragma unroll
             for (int r = 0; r < NT * 4; ++r)     // tile row r*4 + kq = candidate (t = r/4, column (r%4)*4 + kq)
                 load4(kb, k_st, dst_own[r], cand[r], (r & 3) * 4 + kq);
@@ -337,7 +350,7 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
                 const int st_ = (r >> 2) ? start[1] : start[0], ln_ = (r >> 2) ? len[1] : len[0];
                 const int c = set == 0 ? st_ : (half >= 1 && half < ln_ ? st_ + half : -1);
                 if constexpr (PAGED) cand_at[i] = __shfl(paged_at(c), (r & 3) * 4 + kq, 64);
-                else cand[i] = __shfl(c, (r & 3) * 4 + kq, 64);
+                else cand[i] = __shfl(max(c, 0), (r & 3) * 4 + kq, 64);
             }
             if constexpr (KV8) {
                 uint2 raw[kPerWave];

@@ -170,8 +170,9 @@ static void launch_prefill(const PruneArgs &a, int P, int64_t max_seq_len, const
 {
     const int64_t lim = (int64_t)1 << 31;
     const int64_t lim24 = (int64_t)1 << 24;         // narrow offsets are formed by a 24-bit multiply
+    // (row x byte stride, as an unsigned 32-bit byte offset from a scalar base)
     const bool wide = max_seq_len * a.k_st + kD >= lim || (int64_t)a.ge.b_q * a.q_st + kD >= lim ||
-                      a.k_st < 0 || a.q_st < 0 || max_seq_len >= lim24 || a.k_st >= lim24 || a.q_st >= lim24;
+                      a.k_st < 0 || a.q_st < 0 || max_seq_len >= lim24 || a.k_st * 2 >= lim24 || a.q_st * 2 >= lim24;
     const RopeView none{nullptr, nullptr, 0};
     if (a.paged.block_table) {
         if (rope && style == 2) launch_prefill_w<MT, true, 2, true>(a, P, *rope, st);
