@@ -180,3 +180,40 @@ def test_attention_alone_on_oracle_indices(ihip, orc):
         assert np.abs(got - ref).max() <= 1e-2
         np.testing.assert_allclose(lse[0, g * w.G:(g + 1) * w.G, m * 64:(m + 1) * 64].cpu().numpy(), ref_lse,
                                    rtol=2e-5, atol=2e-5)
+
+
+def test_rows_two_megabytes_apart_take_the_64_bit_offsets(ihip, orc):
+    # K and V rows 2^20 elements apart: row offsets pass 2^31 elements, so the pruning and attention kernels
+    # built for 64-bit offsets run (prefill and decode); same values, so the same results as the dense layout
+    w = small(Tq=256, prefix=2048, Hq=4, Hkv=1)
+    q, k, v, sl, _ = configs.make_inputs(w, 0, kind="int")
+    stride = 1 << 20
+    qd, sld = q.cuda(), sl.cuda()
+    kbuf = torch.empty(w.T * stride, dtype=torch.bfloat16, device="cuda")
+    vbuf = torch.empty(w.T * stride, dtype=torch.bfloat16, device="cuda")
+    kw = kbuf.as_strided((1, 1, w.T, w.d), (0, 0, stride, 1))
+    vw = vbuf.as_strided((1, 1, w.T, w.d), (0, 0, stride, 1))
+    kw.copy_(k.cuda())
+    vw.copy_(v.cuda())
+    chunks, keeps = [s[0] for s in w.stages], [s[1] for s in w.stages]
+    L = ihip.Layer(qd, kw, sld, w.b_q, w.n_sink, w.n_stream)
+    b1 = torch.empty((L.P, keeps[-1]), dtype=torch.int32, device="cuda")
+    b2 = torch.empty_like(b1)
+    got = L.prefill_layer(qd, kw, vw, chunks, keeps, out_blocks=b1)
+    ref = L.prefill_layer(qd, k.cuda(), v.cuda(), chunks, keeps, out_blocks=b2)
+    torch.cuda.synchronize()
+    assert torch.equal(b1, b2) and torch.equal(got, ref)
+    o = orc.Oracle(q, k, v, sl.tolist(), w.b_q, w.n_sink, w.n_stream)
+    for m in (0, w.Mq - 1):
+        pr = o.prune(0, 0, m, w.stages)
+        kp = b1[m].cpu().numpy()
+        assert np.array_equal(kp[kp >= 0], pr.block_starts)
+    # the decode kernels on the same buffers
+    qdec = q[:, :, -1:].contiguous().cuda()
+    Ld = ihip.Layer(qdec, kw, sld, 1, w.n_sink, w.n_stream)
+    d1 = Ld.decode_layer(qdec, kw, vw, chunks, keeps)
+    d2 = Ld.decode_layer(qdec, k.cuda(), v.cuda(), chunks, keeps)
+    torch.cuda.synchronize()
+    assert torch.equal(d1, d2)
+    del kbuf, vbuf
+    torch.cuda.empty_cache()
