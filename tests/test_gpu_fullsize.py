@@ -162,7 +162,15 @@ def test_cfg3_decode_full_size_rope_fp8_pages(ihip, orc):
         assert np.array_equal(got[got >= 0], pr.block_starts), (b, g)
         ref, _ = o.attend(0, 0, 0, pr.block_starts, pr.block_lens)
         assert np.abs(out[b, g * G:(g + 1) * G, 0].float().cpu().numpy() - ref[:, 0]).max() <= 2e-2, (b, g)
-    del pg, k8, v8
+    # the same rows contiguous (no pages): the large first stage takes the RoPE kernel's three-chunks-per-
+    # lane-group variant; same arithmetic, so the same bits
+    del pg
+    torch.cuda.empty_cache()
+    blocks2 = torch.empty_like(blocks)
+    out2 = L.decode_layer(q, k8, v8, chunks, keeps, out_blocks=blocks2, rope=rp, kv_scales=scales)
+    torch.cuda.synchronize()
+    assert torch.equal(blocks2, blocks) and torch.equal(out2, out)
+    del k8, v8
     torch.cuda.empty_cache()
 
 
