@@ -129,3 +129,22 @@ def test_argument_checks_of_the_variants_need_no_gpu(built_lib):
                                             256, None, None, 0, None) == -1
     # pooling rule
     assert L.ihip_select_blocks_pooled(ctypes.byref(s), 256, slots, None, 0, 0, 64, 8, 5, 256, None) == -1
+
+
+def test_a_plain_c_client_links_and_runs(built_lib, tmp_path):
+    """gcc -std=c99 compiles tests/c_client/client.c against include/ihip.h, links it with the built
+    library and runs it: version, slot and workspace arithmetic and an argument check from C."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(built_lib.LIB_PATH)
+    exe = str(tmp_path / "client")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                           os.path.join(root, "tests", "c_client", "client.c"), "-o", exe,
+                           "-L", libdir, "-l:libihip.so", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([exe], check=True, capture_output=True, text=True, timeout=120).stdout.splitlines()
+    assert out[0] == "version 100"
+    assert out[1] == "stage1_slots 4092"               # ceil((1048576 - 1024 - 128) / 256)
+    assert int(out[2].split()[1]) >= 64 * 4092 * 4     # at least the first stage's scores
+    assert out[3].startswith("null tensor rc -1: ihip_prune_stage: q.ptr is NULL")
+    assert out[4] == "d=64 rc -1"
