@@ -286,6 +286,8 @@ int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_c
     KernelTimer timer(stage_name(kNameSelect, parent_starts == nullptr, chunk), st);
     if (max_chunks <= 256 * kFastItems)
         hipLaunchKernelGGL(select_blocks_fast_kernel<256>, dim3(P), dim3(256), 0, st, a);
+    else if (max_chunks <= 512 * kFastItems)
+        hipLaunchKernelGGL(select_blocks_fast_kernel<512>, dim3(P), dim3(512), 0, st, a);
     else if (max_chunks <= 1024 * kFastItems)
         hipLaunchKernelGGL(select_blocks_fast_kernel<1024>, dim3(P), dim3(1024), 0, st, a);
     else

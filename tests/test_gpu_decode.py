@@ -205,6 +205,7 @@ def test_strided_kv_layout(ihip, orc):
 
 @pytest.mark.parametrize("n,keep,ties", [(1, 1, False), (110, 64, False), (257, 64, True), (1000, 1000, True),
                                          (50, 80, True), (4092, 256, False), (4092, 256, True),
+                                         (4143, 256, False), (6000, 2500, True), (8192, 300, True),
                                          (12288, 300, True), (20000, 777, True), (300, 1, True)])
 def test_select_blocks_alone(ihip, orc, n, keep, ties):
     rng = np.random.default_rng(n + keep)
