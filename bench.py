@@ -564,11 +564,29 @@ def bench_offload(args, w, torch, ihip, configs):
         m = s1[bank]["misses"] - s0[bank]["misses"]
         hit[bank] = {"block_hits": h, "block_misses": m, "hit_ratio": h / max(1, h + m)}
     cpu = None
+    host_link = None
     if args.cpu_seconds > 0 and kv_scales is None and rope is None:
         sample = decode_oracle_sample(w, qs, [(hk, hv)], [w.T], args.cpu_seconds)
         cpu = {"value": sample["seconds"] / sample["layer_calls_one_sequence"] * 1e6, "unit": "us/layer", "cores": 1,
                "kind": "oracle", "sample": f"{sample['layer_calls_one_sequence']} whole layer calls (all {w.Hkv} KV heads), "
                                            f"{sample['seconds']:.1f} s"}
+        # bytes that cross the host link per layer call: the rows the kernels read from blocks that are not
+        # resident (distinct rows scored, counted by the oracle, x the banks' miss ratios) and the blocks
+        # the update copies in afterwards
+        P = w.B * w.Hkv
+        miss = {b: 1.0 - hit[b]["hit_ratio"] for b in hit}
+        first = f"prune_decode.first.l{chunks[0]}"
+        first_bytes = P * sample["rows_per_problem"][0] * row_bytes * miss["mask"]
+        prune_bytes = P * sum(sample["rows_per_problem"]) * row_bytes * miss["mask"]
+        attn_bytes = P * sample["tokens_per_problem"] * 2 * row_bytes * miss["sa"]
+        insert_bytes = (min(mask_slots, hit["mask"]["block_misses"] / steps) * bt * row_bytes
+                        + min(sa_slots, hit["sa"]["block_misses"] / steps) * bt * 2 * row_bytes)
+        host_link = {"est_bytes_per_layer_read_on_misses": prune_bytes + attn_bytes,
+                     "bytes_per_layer_inserted": insert_bytes,
+                     "est_GBps_over_the_layer": (prune_bytes + attn_bytes + insert_bytes) / (us * 1e-6) / 1e9,
+                     "note": "rows read on misses are estimated: oracle-counted distinct rows x block miss ratio"}
+        if first in kernels:
+            host_link["est_first_stage_GBps"] = first_bytes / (kernels[first]["us"] * 1e-6) / 1e9
     cache.close()
     return {
         "metric": "sparse_attn_decode_offload_us_per_layer" + (f"_dynamic_rope_{args.rope}" if rope else "")
@@ -578,7 +596,8 @@ def bench_offload(args, w, torch, ihip, configs):
                    "head_dim": w.d, "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink,
                    "n_stream": w.n_stream, "block_tokens": bt, "mask_bank_MiB": mask_slots * bt * row_bytes >> 20,
                    "sa_bank_MiB": sa_slots * bt * 2 * row_bytes >> 20, "needles": "Zipf(1.1) over scrambled chunk ranks"},
-        "roofline": None, "cpu_baseline": cpu, "cache": hit, "kernels": kernels, "setup_s": t_setup,
+        "roofline": None, "cpu_baseline": cpu, "cache": hit, "host_link": host_link, "kernels": kernels,
+        "setup_s": t_setup,
     }
 
 
