@@ -330,6 +330,27 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                           float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
                           void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * ihip_decode_layer for callers that cannot allocate device memory or hand a
+ * workspace over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results, but the scratch (scores, the kept lists between the
+ * stages, the final block list, the attention's split partials) is a device
+ * array inside the library of IHIP_STATIC_SCRATCH_BYTES bytes, which every GPU
+ * the library runs on holds until the process ends.  The call allocates and
+ * frees nothing.  A shape and plan whose scratch
+ * (ihip_workspace_bytes(IHIP_OP_DECODE_LAYER, ...)) exceeds the array returns
+ * IHIP_ERR_WORKSPACE and enqueues nothing; the batch-8, 1M-token plan with
+ * four stages needs about 4 MiB.  Every call on a GPU shares that GPU's array
+ * (nothing in it has to survive or be cleared between calls): calls that
+ * overlap on one GPU, on different streams or threads, race.
+ */
+#define IHIP_STATIC_SCRATCH_BYTES (8u << 20)
+int32_t ihip_decode_layer_static(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
+                                 void *stream);
+
 /* ihip_decode_layer / ihip_prefill_layer with the given pooling rule in every stage's selection. */
 int32_t ihip_decode_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,

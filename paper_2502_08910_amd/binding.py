@@ -86,6 +86,8 @@ EXPORTS = {
     "ihip_prune_all": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, c_i32, vp, vp, vp, vp, c_sz, vp]),
     "ihip_decode_layer": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
                                   vp, vp, vp, vp, c_sz, vp]),
+    "ihip_decode_layer_static": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_f,
+                                         vp, vp, vp, vp]),
     "ihip_mask_state_elems": (c_sz, [ctypes.POINTER(Shape), c_i32, vp]),
     "ihip_decode_layer_masked": (c_i32, [ctypes.POINTER(Shape), Tensor, Tensor, Tensor, c_i32, vp, vp, c_i32, vp,
                                          c_f, vp, vp, vp, c_sz, vp]),
@@ -498,6 +500,15 @@ class Layer:
                                        _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
                                        sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _ptr(ws),
                                        ws.numel(), _stream()))
+        return out
+
+    def decode_layer_static(self, q, k, v, chunk_sizes, keeps, out, out_blocks=None, lse=None, sm_scale=None):
+        """ihip_decode_layer_static: the decode layer on the library's own static scratch.  `out`
+        (bf16 [B,Hq,1,d]) and the optional outputs are the caller's: nothing is allocated here."""
+        sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
+        _check(lib().ihip_decode_layer_static(ctypes.byref(self.shape), _tensor(q, "q"), _tensor(k, "k"),
+                                              _tensor(v, "v"), len(chunk_sizes), _i32(chunk_sizes), _i32(keeps),
+                                              sm_scale, _ptr(out), _ptr(lse), _ptr(out_blocks), _stream()))
         return out
 
     def mask_state(self, keeps) -> torch.Tensor:

@@ -645,6 +645,62 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                              keeps, sm_scale, out, out_lse, out_block_starts, ws, ws_bytes, stream);
 }
 
+// ---- the decode layer for callers that cannot allocate -----------------------
+// Its scratch (scores, the kept lists between the stages, the final block list and the attention's
+// split partials) is a device array of the library itself; every GPU holds its own copy at its own
+// address, looked up once per device.  The array's name is only a host-side handle of the symbol:
+// host code uses the looked-up address.
+static __device__ __align__(256) unsigned char scratch[IHIP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch(const char *who, void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(IHIP_ERR_HIP, "%s: hipGetDevice: %s", who, hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(IHIP_ERR_UNSUPPORTED, "%s: device %d beyond %d", who, dev, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(IHIP_ERR_HIP, "%s: hipGetSymbolAddress(scratch): %s", who, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return IHIP_OK;
+}
+}  // namespace
+
+int32_t ihip_decode_layer_static(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 float sm_scale, void *out, float *out_lse, int32_t *out_block_starts, void *stream)
+{
+    const char *who = "ihip_decode_layer_static";
+    int32_t rc;
+    // sizes first: a plan that does not fit the array is refused before anything is looked up or enqueued
+    if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
+    if (shape->B == 0) return IHIP_OK;
+    if (shape->Tq != 1 || shape->b_q != 1) return fail(IHIP_ERR_INVALID_ARG, "%s: needs Tq == b_q == 1", who);
+    if ((rc = check_plan(who, shape, n_stages, chunk_sizes, keeps)) != IHIP_OK) return rc;
+    const size_t need = plan_layout(*shape, n_stages, chunk_sizes, keeps).total +
+                        align256((size_t)shape->B * shape->Hkv * keeps[n_stages - 1] * sizeof(int32_t)) +
+                        attn_decode_workspace(*shape, keeps[n_stages - 1], chunk_sizes[n_stages - 1]);
+    if (need > (size_t)IHIP_STATIC_SCRATCH_BYTES)
+        return fail(IHIP_ERR_WORKSPACE, "%s: this shape and plan need %zu bytes of scratch, the static array holds %zu",
+                    who, need, (size_t)IHIP_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if ((rc = static_scratch(who, &ws)) != IHIP_OK) return rc;
+    // nothing in the scratch has to start at zero: every score, list entry and partial that a kernel
+    // reads was written earlier in the same call
+    return decode_layer_impl(who, shape, q, k, v, nullptr, nullptr, false, nullptr, n_stages, chunk_sizes, keeps,
+                             sm_scale, out, out_lse, out_block_starts, ws, IHIP_STATIC_SCRATCH_BYTES, stream);
+}
+
 int32_t ihip_decode_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps, int32_t pooling,
                                  float sm_scale, void *out, float *out_lse, int32_t *out_block_starts, void *ws,

@@ -60,6 +60,20 @@ def test_argument_checks_need_no_gpu(built_lib):
     assert L.ihip_workspace_bytes(99, ctypes.byref(s), 1, one, one) == 0
 
 
+def test_static_scratch_limit_needs_no_gpu(built_lib):
+    """ihip_decode_layer_static refuses a plan beyond its array before it touches the device."""
+    from paper_2502_08910_amd.binding import Shape, Tensor
+    L = built_lib.lib()
+    s = Shape(64, 32, 8, 128, 1, 1, 1, 1 << 20, 128, 1024, 0)       # batch 64 x 1M keys: ~ 33 MiB of scores
+    t = Tensor(256, 0, 0, 128)
+    chunks = (ctypes.c_int32 * 2)(256, 16)
+    keeps = (ctypes.c_int32 * 2)(256, 256)
+    rc = L.ihip_decode_layer_static(ctypes.byref(s), t, t, t, 2, chunks, keeps, 1.0, 256, None, None, None)
+    assert rc == -2 and b"static" in L.ihip_last_error()
+    need = L.ihip_workspace_bytes(4, ctypes.byref(s), 2, chunks, keeps)
+    assert need > (8 << 20)
+
+
 def test_argument_checks_of_the_variants_need_no_gpu(built_lib):
     """Dynamic RoPE, FP8 K/V, paged K/V and pooled selection: what they refuse, before any launch."""
     from paper_2502_08910_amd.binding import Shape, Tensor, RopeStruct, PagedStruct
