@@ -38,17 +38,25 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 N_QUERY_SETS = 32
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see
-# profiles/.  Absent = not measured for that workload / kernel.
+# HBM traffic per launch from rocprofv3 --pmc runs of this same command (FETCH_SIZE, then WRITE_SIZE, KiB
+# per dispatch, each scaled by what the counter reads for a device copy of known size: FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0).  Counters cannot be read inside this process, so the figure is carried from the
+# summary named in `traffic_source`, which also gives the date and commit it was taken at; a kernel that
+# has no current summary reports traffic null.
+TRAFFIC_SOURCE = "profiles/decode_cfg3_and_prefill_cfg4_kernel_trace_and_hbm_counters.txt"
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 781,843 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 1,229 KiB x 1.0 per launch
     ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781842.8 * 2.0 + 1229.2) * 1024.0,
-    # prefill kernels: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per launch
     ("cfg4-prefill-4k-on-256k", "prune_prefill.first.l64"): (794001.9 * 2.0 + 10518.0) * 1024.0,
     ("cfg4-prefill-4k-on-256k", "prune_prefill.l16"): (486601.0 * 2.0 + 2048.0) * 1024.0,
     ("cfg4-prefill-4k-on-256k", "attn_prefill"): (636677.4 * 2.0 + 32768.8) * 1024.0,
 }
+
+
+def measured_traffic(workload, kernel):
+    t = MEASURED_TRAFFIC_BYTES.get((workload, kernel))
+    if t is None:
+        return {"traffic": None}
+    return {"traffic": t, "traffic_source": TRAFFIC_SOURCE}
 
 
 def parse():
@@ -82,6 +90,10 @@ def parse():
                          "cached masks are reused otherwise (the reported value is then the amortised time)")
     ap.add_argument("--bank-mib", type=int, default=512,
                     help="cfg5 only: on-GPU bytes of the hot-block banks (default 512 MiB: a 16 GB budget over 32 layers)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="default workload only: do not append the `prefill` (cfg4) and `offload` (cfg5) objects")
+    ap.add_argument("--extras-budget-s", type=float, default=150.0,
+                    help="an extra workload is started only while the run is younger than this")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 10 device copies of 1 GiB (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -151,35 +163,63 @@ def dominant(kernels):
 
 
 # ---------------------------------------------------------------------------
+def host_threads():
+    """Worker threads of the CPU baseline: the host cores this process may use (the box's share,
+    OMP_NUM_THREADS where it is set), at most 16.  The oracle's C routines run outside the
+    interpreter lock, so threads scale like processes and nothing is forked after the GPU is up."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit() and int(env) > 0:
+        n = min(n, int(env))
+    return max(1, min(16, n))
+
+
 def decode_oracle_sample(w, qs, kvs, seq_lens, budget_s, kv_scales=None):
-    """Times the CPU oracle on sequence 0 (all its KV heads), one query set
-    (with its layer's K/V) after another until the budget is used; also returns
-    the mean number of distinct K rows each stage scores per problem and the
-    attended tokens."""
+    """Times the CPU oracle, as it stands, on sequence 0: its (query set, KV head) problems are dealt
+    to host_threads() threads -- the arithmetic of a problem is untouched --, a wave of whole layer
+    calls at a time until the budget is used.  Also returns the mean number of distinct K rows each
+    stage scores per problem and the attended tokens."""
+    from concurrent.futures import ThreadPoolExecutor
     import oracle
     oracle.build(force=False)
+    threads = host_threads()
     host = {}
     rows = [0.0] * len(w.stages)
     tokens, problems, calls, t_used = 0.0, 0, 0, 0.0
-    for i, q in enumerate(qs):
-        layer = i % len(kvs)
-        if layer not in host:
-            host = {layer: (kvs[layer][0][0:1].cpu(), kvs[layer][1][0:1].cpu())}
-        k0, v0 = host[layer]
-        o = oracle.Oracle(q[0:1].cpu(), k0, v0, [int(seq_lens[0])], w.b_q, w.n_sink, w.n_stream,
-                          kv_scales=kv_scales)
-        t0 = time.perf_counter()
-        res = o.layer(w.stages)
-        t_used += time.perf_counter() - t0
-        calls += 1
-        for (b, g, m), (pr, out, lse) in res.items():
-            for s, st in enumerate(pr.stages):
-                rows[s] += st.rows_touched
-            tokens += o.attended_tokens(b, m, pr.block_lens)
-            problems += 1
-        if t_used >= budget_s:
-            break
-    return {"seconds": t_used, "layer_calls_one_sequence": calls, "problems": problems,
+    sets_per_wave = max(1, threads // w.Hkv)
+
+    def one(task):
+        o, g = task
+        pr = o.prune(0, g, 0, w.stages)
+        o.attend(0, g, 0, pr.block_starts, pr.block_lens)
+        return [st.rows_touched for st in pr.stages], o.attended_tokens(0, 0, pr.block_lens)
+
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        for i0 in range(0, len(qs), sets_per_wave):
+            tasks = []
+            for i in range(i0, min(len(qs), i0 + sets_per_wave)):
+                layer = i % len(kvs)
+                if layer not in host:
+                    host = {layer: (kvs[layer][0][0:1].cpu(), kvs[layer][1][0:1].cpu())}
+                k0, v0 = host[layer]
+                o = oracle.Oracle(qs[i][0:1].cpu(), k0, v0, [int(seq_lens[0])], w.b_q, w.n_sink, w.n_stream,
+                                  kv_scales=kv_scales)
+                tasks += [(o, g) for g in range(w.Hkv)]
+                calls += 1
+            t0 = time.perf_counter()
+            done = list(pool.map(one, tasks))
+            t_used += time.perf_counter() - t0
+            for stage_rows, toks in done:
+                for s_, r in enumerate(stage_rows):
+                    rows[s_] += r
+                tokens += toks
+                problems += 1
+            if t_used >= budget_s:
+                break
+    return {"seconds": t_used, "layer_calls_one_sequence": calls, "problems": problems, "threads": threads,
             "rows_per_problem": [r / problems for r in rows], "tokens_per_problem": tokens / problems}
 
 
@@ -284,9 +324,10 @@ def bench_decode(args, w, torch, ihip, configs):
     if args.cpu_seconds > 0 and not args.rope:
         sample = decode_oracle_sample(w, qs, kvs, seq_lens.cpu().tolist(), args.cpu_seconds, kv_scales)
         per_seq_call = sample["seconds"] / sample["layer_calls_one_sequence"]
-        cpu = {"value": per_seq_call * w.B * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
+        cpu = {"value": per_seq_call * w.B * 1e6, "unit": "us/layer", "cores": sample["threads"], "kind": "oracle",
                "sample": f"sequence 0 of {w.B} (its {w.Hkv} KV heads), {sample['layer_calls_one_sequence']} "
-                         f"layer calls with different queries, {sample['seconds']:.1f} s; scaled x{w.B} to the batch"}
+                         f"layer calls with different queries, their (query set, KV head) problems dealt to "
+                         f"{sample['threads']} threads, {sample['seconds']:.1f} s of wall time; scaled x{w.B} to the batch"}
 
     P = w.B * w.Hkv
     row_bytes = w.d * (1 if kv_scales else 2)
@@ -312,8 +353,9 @@ def bench_decode(args, w, torch, ihip, configs):
             ach = kernels[dom]["alg_GBps"]
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": ach / HBM_PEAK_GBS,
-                        "traffic": None if kv_scales else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                         "algorithmic_bytes_per_launch": alg[dom], "us_per_launch": kernels[dom]["us"]}
+            plain = not (kv_scales or paged or rope or args.kv_layout != "bhtd")
+            roofline.update(measured_traffic(w.name if plain else None, dom))
     return {
         "metric": ("sparse_attn_decode_us_per_layer_1m_ctx" if w.T == 1048576 else "sparse_attn_decode_us_per_layer")
         + ("_amortised_mask_cache" if refresh else "") + (f"_dynamic_rope_{args.rope}" if args.rope else "") + ("_fp8_kv" if kv_scales else "") + (f"_paged{args.paged}_{args.paged_order}" if args.paged else "")
@@ -416,36 +458,44 @@ def bench_prefill(args, w, torch, ihip, configs):
         if "TFLOPs" in kernels[n]:
             kernels[n]["frac_of_peak"] = kernels[n]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
             kernels[n]["frac_of_measured_mfma_rate"] = kernels[n]["TFLOPs"] / measured[n.split(".")[0]]
+    def mfma_roofline(name):
+        ach = kernels[name]["TFLOPs"]
+        r = {"kernel": name, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+             "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+             "flops_per_launch": flops[name], "us_per_launch": kernels[name]["us"],
+             "measured_mfma_rate": measured[name.split(".")[0]],
+             "frac_of_measured_mfma_rate": ach / measured[name.split(".")[0]]}
+        r.update(measured_traffic(None if rope or paged or kv_scales else w.name, name))
+        return r
+
     roofline = None
     if kernels and dominant(kernels) in flops:
-        dom = dominant(kernels)
-        ach = kernels[dom]["TFLOPs"]
-        roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": None if rope or paged or kv_scales else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
-                    "flops_per_launch": flops[dom], "us_per_launch": kernels[dom]["us"],
-                    "measured_mfma_rate": measured[dom.split(".")[0]],
-                    "frac_of_measured_mfma_rate": ach / measured[dom.split(".")[0]]}
+        roofline = mfma_roofline(dominant(kernels))
+    rooflines = {n: mfma_roofline(n) for n in kernels if n in flops}
 
     cpu = None
     if args.cpu_seconds > 0 and not rope:
+        from concurrent.futures import ThreadPoolExecutor
         import oracle
         oracle.build(force=False)
+        threads = host_threads()
         blocks = [0, w.Mq // 3, (2 * w.Mq) // 3, w.Mq - 1]
-        o = oracle.Oracle(q[:, :w.G].cpu(), k[:, :1].cpu(), v[:, :1].cpu(), [w.T] * w.B, w.b_q, w.n_sink, w.n_stream,
-                          kv_scales=kv_scales)
+        o = oracle.Oracle(q.cpu(), k.cpu(), v.cpu(), [w.T] * w.B, w.b_q, w.n_sink, w.n_stream, kv_scales=kv_scales)
         t0 = time.perf_counter()
         done = 0
-        for m in blocks:
-            o.layer(w.stages, problems=[(0, 0, m)])
-            done += 1
-            if time.perf_counter() - t0 > args.cpu_seconds:
-                break
+        # the oracle as it stands, its (KV head, query block) problems dealt to the threads, one query
+        # block (all KV heads) at a time
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            for m in blocks:
+                list(pool.map(lambda g: o.layer(w.stages, problems=[(0, g, m)]), range(w.Hkv)))
+                done += w.Hkv
+                if time.perf_counter() - t0 > args.cpu_seconds:
+                    break
         secs = time.perf_counter() - t0
         P = w.B * w.Hkv * w.Mq
-        cpu = {"value": secs / done * P * 1e6, "unit": "us/layer", "cores": 1, "kind": "oracle",
-               "sample": f"{done} of {P} (KV head, query block) problems (KV head 0, blocks {blocks[:done]}), "
-                         f"{secs:.1f} s; scaled x{P}/{done}"}
+        cpu = {"value": secs / done * P * 1e6, "unit": "us/layer", "cores": threads, "kind": "oracle",
+               "sample": f"{done} of {P} (KV head, query block) problems (all KV heads of blocks "
+                         f"{blocks[:done // w.Hkv]}) on {threads} threads, {secs:.1f} s of wall time; scaled x{P}/{done}"}
     return {
         "metric": "sparse_attn_prefill_us_per_layer" + ("_fp8_kv" if kv_scales else "") + ("_hip_graph" if args.graph else ""),
         "value": us_per_layer, "unit": "us/layer", "steps": steps, "warmup": warmup,
@@ -453,7 +503,7 @@ def bench_prefill(args, w, torch, ihip, configs):
                    + (f"_paged{args.paged}_{args.paged_order}" if paged else ""), "batch": w.B, "context": w.T, "new_tokens": w.Tq, "query_block": w.b_q,
                    "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
                    "stages_chunk_keep": list(map(list, w.stages)), "n_sink": w.n_sink, "n_stream": w.n_stream},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "rooflines": rooflines, "cpu_baseline": cpu,
         "whole_path": {"mfma_flops_per_layer": sum(flops.values()),
                        "achieved_TFLOPs": sum(flops.values()) / (us_per_layer * 1e-6) / 1e12,
                        "measured_mfma_rate_TFLOPs": {"32x32x16_bf16": measured["attn_prefill"],
@@ -567,9 +617,10 @@ def bench_offload(args, w, torch, ihip, configs):
     host_link = None
     if args.cpu_seconds > 0 and kv_scales is None and rope is None:
         sample = decode_oracle_sample(w, qs, [(hk, hv)], [w.T], args.cpu_seconds)
-        cpu = {"value": sample["seconds"] / sample["layer_calls_one_sequence"] * 1e6, "unit": "us/layer", "cores": 1,
-               "kind": "oracle", "sample": f"{sample['layer_calls_one_sequence']} whole layer calls (all {w.Hkv} KV heads), "
-                                           f"{sample['seconds']:.1f} s"}
+        cpu = {"value": sample["seconds"] / sample["layer_calls_one_sequence"] * 1e6, "unit": "us/layer",
+               "cores": sample["threads"], "kind": "oracle",
+               "sample": f"{sample['layer_calls_one_sequence']} whole layer calls (all {w.Hkv} KV heads) on "
+                         f"{sample['threads']} threads, {sample['seconds']:.1f} s of wall time"}
         # bytes that cross the host link per layer call: the rows the kernels read from blocks that are not
         # resident (distinct rows scored, counted by the oracle, x the banks' miss ratios) and the blocks
         # the update copies in afterwards
@@ -601,6 +652,48 @@ def bench_offload(args, w, torch, ihip, configs):
     }
 
 
+def extra_workloads(args, torch, ihip, configs, t_run):
+    """The other two measured workloads, appended to the default line so that one recorded run carries
+    them: `prefill` = one chunked-prefill layer of cfg4 (the second target: matrix-core rate of the
+    block-sparse attention and of the first pruning stage), `offload` = the cfg5 decode layer with K/V
+    in host memory.  Short runs of the same code `--workload` times; each starts only while the run is
+    younger than --extras-budget-s."""
+    import copy
+    import gc
+    out = {}
+
+    def young():
+        return time.perf_counter() - t_run < args.extras_budget_s
+
+    gc.collect()
+    torch.cuda.empty_cache()
+    if young():
+        a = copy.copy(args)
+        a.steps, a.warmup, a.cpu_seconds, a.no_profile_pass = 10, 3, 0.0, False
+        pf = bench_prefill(a, configs.CFG4, torch, ihip, configs)
+        first = f"prune_prefill.first.l{configs.CFG4.stages[0][0]}"
+        out["prefill"] = {"workload": configs.CFG4.name, "us_per_layer": pf["value"], "steps": pf["steps"],
+                          "warmup": pf["warmup"],
+                          "kernels_us": {n: kk["us"] for n, kk in pf["kernels"].items()},
+                          "roofline": {"attn_prefill": pf["rooflines"].get("attn_prefill"),
+                                       "prune_prefill_first_stage": pf["rooflines"].get(first)},
+                          "whole_path": pf["whole_path"], "step_us": pf["step_us"]}
+        progress("prefill workload done")
+        del pf
+        gc.collect()
+        torch.cuda.empty_cache()
+    if young():
+        a = copy.copy(args)
+        a.steps, a.warmup, a.cpu_seconds, a.no_profile_pass = 16, 4, min(args.cpu_seconds, 3.0), False
+        off = bench_offload(a, configs.CFG5, torch, ihip, configs)
+        out["offload"] = {"workload": configs.CFG5.name, "us_per_layer": off["value"], "steps": off["steps"],
+                          "warmup": off["warmup"], "banks": {kk: off["config"][kk] for kk in ("block_tokens", "mask_bank_MiB", "sa_bank_MiB")},
+                          "cache": off["cache"], "host_link": off["host_link"],
+                          "kernels_us": {n: kk["us"] for n, kk in off["kernels"].items()}}
+        progress("offload workload done")
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -622,12 +715,17 @@ def main():
     ihip.lib()
     w = configs.BY_NAME[args.workload]
     torch.cuda.set_device(0)
+    t_run = time.perf_counter()
     if w.name.startswith("cfg5"):
         body = bench_offload(args, w, torch, ihip, configs)
     elif w.Tq == 1:
         body = bench_decode(args, w, torch, ihip, configs)
     else:
         body = bench_prefill(args, w, torch, ihip, configs)
+    headline = (w.name == "cfg3-decode-1m-b8" and args.kv_dtype == "bf16" and not args.paged and not args.rope
+                and not args.graph and not args.refresh and args.kv_layout == "bhtd")
+    if headline and not args.no_extras:
+        body.update(extra_workloads(args, torch, ihip, configs, t_run))
     line = {"metric": body.pop("metric"), "value": body.pop("value"), "unit": body.pop("unit"), "n_gpus": 1,
             "steps": body.pop("steps"), "warmup": body.pop("warmup")}
     line["ms_per_step"] = line["value"] / 1e3
