@@ -408,8 +408,10 @@ int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tenso
  * taken as cached (first_stage = 0 recomputes everything, = n_stages only
  * runs the attention over the cached final blocks).  The window and the
  * cut of blocks at the end of the middle range always follow the current
- * seq_lens.  Which stage is due at which step (c mod n_refresh == 0) is the
- * caller's policy.  Scratch as for IHIP_OP_DECODE_LAYER.
+ * seq_lens.  Which stage is due at which step (c mod n_refresh == 0):
+ * ihip_refresh_due; schedules in which a later stage is not due while an
+ * earlier one is go through ihip_decode_layer_ex (stage_due).  Scratch as
+ * for IHIP_OP_DECODE_LAYER.
  */
 size_t  ihip_mask_state_elems(const ihip_shape *shape, int32_t n_stages, const int32_t *keeps);
 
@@ -453,7 +455,10 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
  * tie; never-used slots first; never a slot touched in this same call) and
  * copies the missed blocks in, in ascending block order; if more blocks were
  * missed than there are such slots, only the lowest-numbered ones are inserted.  Layer calls and updates on one cache
- * must not overlap.
+ * must not overlap.  The counter that stamps the calls lives on the host, so
+ * the calls that read or update a cache (the *_cached calls, ihip_decode_layer_ex
+ * with a cache, ihip_cache_update) cannot be captured into a HIP graph: on a
+ * stream under capture they return IHIP_ERR_UNSUPPORTED.
  *
  * ihip_cache_stats (synchronises the device) fills stats8 (host):
  * [0..3] mask bank, [4..7] sparse-attention bank: blocks hit (cumulative over
@@ -531,6 +536,11 @@ int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_ca
  *   pooling       IHIP_POOL_KV_HEAD / IHIP_POOL_ALL_HEADS
  *   stage_starts  mask-caching state as in ihip_decode_layer_masked, or NULL;
  *   first_stage   first stage to recompute (needs stage_starts unless 0)
+ *   stage_due     host int32 [n_stages] or NULL (needs stage_starts; first_stage must be 0): Alg. 4's
+ *                 per-stage test as it is printed -- stage i is re-run iff stage_due[i] != 0, reading
+ *                 the list of stage i-1 as it stands (re-run in this call or cached), and a stage that
+ *                 is not due keeps its cached list even when an earlier stage was re-run.
+ *                 ihip_refresh_due fills it from the refresh intervals and the step number.
  * Paged, FP8 and RoPE combine freely with each other, with either pooling rule
  * and with mask caching; the host tier (contiguous K/V) combines with FP8 (a
  * cache made by ihip_cache_create_fp8), RoPE, pooling and mask caching
@@ -547,11 +557,21 @@ typedef struct ihip_decode_options {
     int32_t pooling;
     int32_t first_stage;
     int32_t *stage_starts;
+    const int32_t *stage_due;
 } ihip_decode_options;
 int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                              int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                              float sm_scale, const ihip_decode_options *opt, void *out, float *out_lse,
                              int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+/*
+ * Alg. 4's counters (c^(i) starts at 0 and advances by one per generated token modulo n_refresh^(i);
+ * stage i is re-run when c^(i) = 0): for decode step `step` (0 = the first) writes
+ * stage_due[i] = (step mod n_refresh[i] == 0) to the host array stage_due (may be NULL) and returns
+ * the first due stage, n_stages if none is, or a negative error.  Host arithmetic only.  With nested
+ * intervals (each a multiple of the next) every stage after the first due one is due as well and the
+ * return value is all ihip_decode_layer_masked needs.
+ */
+int32_t ihip_refresh_due(int32_t n_stages, const int32_t *n_refresh, int64_t step, int32_t *stage_due);
 int32_t ihip_cache_update(ihip_cache *cache, void *stream);
 int32_t ihip_cache_stats(ihip_cache *cache, uint64_t *stats8);
 int32_t ihip_cache_read_tables(ihip_cache *cache, int32_t bank, int32_t *host_page_table,

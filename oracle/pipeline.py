@@ -247,12 +247,20 @@ class Oracle:
         kept chunk starts (int64 arrays) of that earlier step.  Returns the per
         stage kept starts after this step and the final blocks (starts, lens).
         Lengths always follow the current end of the middle range."""
+        return self.prune_due(b, g, m, stages, [i >= first_stage for i in range(len(stages))], cached_kept)
+
+    def prune_due(self, b, g, m, stages, due, cached_kept):
+        """One decode step of Alg. 4's stage loop for one problem: stage i is re-run
+        (with the current queries, on the list stage i-1 holds at this moment, be it
+        re-run in this step or cached) iff due[i]; a stage that is not due keeps
+        its cached list, also when an earlier stage was re-run.  Returns as
+        prune_from."""
         lo, hi, E = self.ranges(b, m)
         kept = [np.asarray(x, np.int64) for x in cached_kept]
         if hi <= lo:
             return [np.zeros(0, np.int64) for _ in stages], np.zeros(0, np.int64), np.zeros(0, np.int32)
         for i, (l_c, keep) in enumerate(stages):
-            if i < first_stage:
+            if not due[i]:
                 continue
             if i == 0:
                 starts, lens = stage1_chunks(lo, hi, l_c)

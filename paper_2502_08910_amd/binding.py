@@ -109,6 +109,7 @@ EXPORTS = {
                                         vp, vp, vp]),
     "ihip_sparse_attn_decode_cached": (c_i32, [ctypes.POINTER(Shape), Tensor, vp, vp, c_i32, c_i32, c_f, vp, c_f, c_f,
                                                vp, vp, vp, c_sz, vp]),
+    "ihip_refresh_due": (c_i32, [c_i32, vp, c_i64, vp]),
     "ihip_cache_update": (c_i32, [vp, vp]),
     "ihip_cache_stats": (c_i32, [vp, vp]),
     "ihip_cache_read_tables": (c_i32, [vp, c_i32, vp, vp]),
@@ -239,7 +240,7 @@ class PagedKV:
 class DecodeOptions(ctypes.Structure):
     """ihip_decode_options (all zero = the plain decode layer)."""
     _fields_ = [("rope", vp), ("cache", vp), ("paged", vp), ("kv_fp8", c_i32), ("k_scale", c_f), ("v_scale", c_f),
-                ("pooling", c_i32), ("first_stage", c_i32), ("stage_starts", vp)]
+                ("pooling", c_i32), ("first_stage", c_i32), ("stage_starts", vp), ("stage_due", vp)]
 
 
 class PrefillOptions(ctypes.Structure):
@@ -431,21 +432,22 @@ class Layer:
                      out_blocks=None, lse=None, rope: Optional["Rope"] = None, pooling: Optional[int] = None,
                      kv_scales: Optional[Sequence[float]] = None, paged: Optional["PagedKV"] = None,
                      cache: Optional["HostKVCache"] = None, stage_starts: Optional[torch.Tensor] = None,
-                     first_stage: Optional[int] = None):
+                     first_stage: Optional[int] = None, stage_due: Optional[Sequence[int]] = None):
         """Pruning stages + block-sparse decode attention in one enqueue -> bf16 [B,Hq,1,d].
         paged: k and v are ignored, the pools of `paged` are read through its block table.
         cache: k and v are ignored, the host tier is read.  stage_starts / first_stage: mask caching
-        (see decode_layer_masked).  One variant alone goes to its own entry point, combinations (and
-        the host tier) to ihip_decode_layer_ex."""
+        (see decode_layer_masked); stage_due: one flag per stage instead of first_stage (Alg. 4's per-stage
+        test).  One variant alone goes to its own entry point, combinations (and the host tier, and
+        stage_due) to ihip_decode_layer_ex."""
         sm_scale = 1.0 / math.sqrt(self.d) if sm_scale is None else sm_scale
         if out is None:
             out = torch.empty((self.B, self.Hq, 1, self.d), dtype=torch.bfloat16, device=self.device)
         if ws is None:
             ws = self.workspace(OP_DECODE_LAYER, chunk_sizes, keeps)
         n_variants = sum(x is not None for x in (rope, pooling, kv_scales, paged, cache, stage_starts))
-        if stage_starts is not None and first_stage is None:
-            raise IhipError("decode_layer: stage_starts needs first_stage")
-        if n_variants > 1 or cache is not None:
+        if stage_starts is not None and first_stage is None and stage_due is None:
+            raise IhipError("decode_layer: stage_starts needs first_stage or stage_due")
+        if n_variants > 1 or cache is not None or stage_due is not None:
             # combinations go through the one entry point that takes them all
             opt = DecodeOptions()
             opt.rope = ctypes.cast(rope.ref(), vp) if rope is not None else None
@@ -454,8 +456,10 @@ class Layer:
             if kv_scales is not None:
                 opt.kv_fp8, opt.k_scale, opt.v_scale = 1, kv_scales[0], kv_scales[1]
             opt.pooling = POOL_KV_HEAD if pooling is None else pooling
-            opt.first_stage = 0 if first_stage is None else first_stage
+            opt.first_stage = 0 if first_stage is None or stage_due is not None else first_stage
             opt.stage_starts = stage_starts.data_ptr() if stage_starts is not None else None
+            due = _i32([int(bool(x)) for x in stage_due]) if stage_due is not None else None   # alive until the call returns
+            opt.stage_due = ctypes.cast(due, vp) if due is not None else None
             conv = _tensor8 if kv_scales is not None else _tensor
             if paged is not None:
                 tk, tv = conv(paged.k_pool, "k_pool"), conv(paged.v_pool, "v_pool")
@@ -579,14 +583,18 @@ class Layer:
         return out
 
 
+def refresh_due(step: int, refresh: Sequence[int]):
+    """ihip_refresh_due: (first due stage or len(refresh), [stage i due at this step])."""
+    due = (c_i32 * len(refresh))()
+    first = lib().ihip_refresh_due(len(refresh), _i32(refresh), step, due)
+    if first < 0:
+        _check(first)
+    return first, [bool(x) for x in due]
+
+
 def first_stage_due(step: int, refresh: Sequence[int]) -> int:
-    """Alg. 4's refresh rule: the first stage i whose counter is due (step mod refresh[i] == 0);
-    len(refresh) if none is.  With nested intervals (each a multiple of the next) every later
-    stage is due as well."""
-    for i, r in enumerate(refresh):
-        if step % r == 0:
-            return i
-    return len(refresh)
+    """The first stage Alg. 4's counters make due at this step (ihip_refresh_due); len(refresh) if none."""
+    return refresh_due(step, refresh)[0]
 
 
 class HostKVCache:

@@ -85,6 +85,7 @@ int32_t launch_attn_decode(const ihip_shape &, const ihip_tensor &, const ihip_t
 BankView cache_bank_view(const ihip_cache *, int);
 void cache_describe(const ihip_cache *, int32_t *, int32_t *, int64_t *, ihip_tensor *, ihip_tensor *);
 bool cache_holds_fp8(const ihip_cache *);
+int32_t refuse_capture(const char *, hipStream_t);
 size_t attn_decode_workspace(const ihip_shape &, int, int);
 int32_t launch_attn_prefill(const ihip_shape &, const ihip_tensor &, const ihip_tensor &,
                             const ihip_tensor &, const int32_t *, int, int, float, void *, float *,
@@ -222,16 +223,18 @@ static PlanLayout plan_layout(const ihip_shape &s, int n_stages, const int32_t *
     return L;
 }
 
-// Stages first_stage..n_stages-1 of Alg. 1.  stage_out[i] receives stage i's kept starts; for
-// first_stage > 0 stage_out[first_stage-1] must already hold the previous stage's kept starts
-// (a cached mask, Alg. 4).
+// The stages of Alg. 1 whose bit is set in `due`.  stage_out[i] receives stage i's kept starts; a
+// stage that is re-run reads the list of the stage before it as it stands, re-run in this call or
+// cached from an earlier one (Alg. 4: a stage is re-run when its counter says so, with the current
+// lists of the earlier stages; a stage that is not due keeps its list).
 static int32_t prune_stages_impl(const ihip_shape &s, const ihip_tensor &q, const ihip_tensor &k, int n_stages,
-                                 const int32_t *chunks, const int32_t *keeps, int first_stage,
+                                 const int32_t *chunks, const int32_t *keeps, uint32_t due,
                                  int32_t *const *stage_out, float *scores, const BankView *bank,
                                  const ihip_rope *rope, bool all_heads, hipStream_t st,
                                  const KvFormat *fmt = nullptr)
 {
-    for (int i = first_stage; i < n_stages; ++i) {
+    for (int i = 0; i < n_stages; ++i) {
+        if (!((due >> i) & 1u)) continue;
         const int32_t *parents = i == 0 ? nullptr : stage_out[i - 1];
         const int n_parent = i == 0 ? 0 : keeps[i - 1];
         const int parent_chunk = i == 0 ? 0 : chunks[i - 1];
@@ -292,7 +295,7 @@ static int32_t prune_all_impl(const ihip_shape &s, const ihip_tensor &q, const i
     int32_t *stage_out[8];
     for (int i = 0; i < n_stages; ++i)
         stage_out[i] = (i + 1 == n_stages) ? out_block_starts : (int32_t *)(ws + L.starts_off[i & 1]);
-    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, 0, stage_out, (float *)(ws + L.scores_off), bank, rope, all_heads, st, fmt);
+    return prune_stages_impl(s, q, k, n_stages, chunks, keeps, ~0u, stage_out, (float *)(ws + L.scores_off), bank, rope, all_heads, st, fmt);
 }
 
 }  // namespace ihip
@@ -580,13 +583,15 @@ int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, in
                           false, (hipStream_t)stream);
 }
 
-// stage_starts != NULL: mask caching (the caller's per-stage lists; stages first_stage.. are recomputed)
+// stage_starts != NULL: mask caching (the caller's per-stage lists; stages first_stage.. are recomputed,
+// or, with stage_due, exactly the stages whose entry is non-zero)
 static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                                  ihip_tensor v, const ihip_cache *cache, const ihip_rope *rope, bool all_heads,
                                  const KvFormat *fmt, int32_t n_stages,
                                  const int32_t *chunk_sizes, const int32_t *keeps, float sm_scale, void *out,
                                  float *out_lse, int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream,
-                                 int32_t first_stage = 0, int32_t *stage_starts = nullptr)
+                                 int32_t first_stage = 0, int32_t *stage_starts = nullptr,
+                                 const int32_t *stage_due = nullptr)
 {
     int32_t rc;
     if ((rc = check_shape(shape, who)) != IHIP_OK) return rc;
@@ -603,7 +608,11 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
     const size_t blocks_bytes = align256(P * keeps[last] * sizeof(int32_t));
     const size_t attn_bytes = attn_decode_workspace(*shape, keeps[last], chunk_sizes[last]);
     BankView mask_bank, sa_bank;
-    if (cache) { mask_bank = cache_bank_view(cache, 0); sa_bank = cache_bank_view(cache, 1); }
+    if (cache) {
+        if ((rc = refuse_capture(who, (hipStream_t)stream)) != IHIP_OK) return rc;
+        mask_bank = cache_bank_view(cache, 0);
+        sa_bank = cache_bank_view(cache, 1);
+    }
     if (stage_starts) {
         if (first_stage < 0 || first_stage > n_stages)
             return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d not in 0..%d", who, first_stage, n_stages);
@@ -613,7 +622,10 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
         int32_t *stage_out[8];
         size_t off = 0;
         for (int i = 0; i < n_stages; ++i) { stage_out[i] = stage_starts + off; off += P * (size_t)keeps[i]; }
-        rc = prune_stages_impl(*shape, q, k, n_stages, chunk_sizes, keeps, first_stage, stage_out, (float *)ws,
+        uint32_t due = 0;
+        for (int i = 0; i < n_stages; ++i)
+            if (stage_due ? stage_due[i] != 0 : i >= first_stage) due |= 1u << i;
+        rc = prune_stages_impl(*shape, q, k, n_stages, chunk_sizes, keeps, due, stage_out, (float *)ws,
                                cache ? &mask_bank : nullptr, rope, all_heads, (hipStream_t)stream, fmt);
         if (rc != IHIP_OK) return rc;
         if (out_block_starts &&
@@ -624,7 +636,8 @@ static int32_t decode_layer_impl(const char *who, const ihip_shape *shape, ihip_
                                   out_lse, (char *)ws + L.scores_bytes, cache ? &sa_bank : nullptr, rope,
                                   (hipStream_t)stream, fmt);
     }
-    if (first_stage != 0) return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d without stage_starts", who, first_stage);
+    if (first_stage != 0 || stage_due)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d / stage_due without stage_starts", who, first_stage);
     const size_t need = L.total + blocks_bytes + attn_bytes;
     if (!ws || ws_bytes < need)
         return fail(IHIP_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
@@ -800,8 +813,9 @@ int32_t ihip_prune_stage_cached(const ihip_shape *shape, ihip_tensor q, ihip_cac
     ihip_tensor hk, hv;
     KvFormat fmt;
     bool fp8;
-    const int32_t rc = cached_stage_setup(who, shape, cache, k_scale, 1.0f, &hk, &hv, &fmt, &fp8);
+    int32_t rc = cached_stage_setup(who, shape, cache, k_scale, 1.0f, &hk, &hv, &fmt, &fp8);
     if (rc != IHIP_OK) return rc;
+    if ((rc = refuse_capture(who, (hipStream_t)stream)) != IHIP_OK) return rc;
     const BankView bank = cache_bank_view(cache, 0);
     return prune_stage_entry(who, rope, fp8 ? &fmt : nullptr, shape, q, hk, parent_starts, n_parent, parent_chunk,
                              chunk, max_chunks, out_scores, out_rep, stream, &bank);
@@ -816,8 +830,9 @@ int32_t ihip_sparse_attn_decode_cached(const ihip_shape *shape, ihip_tensor q, i
     ihip_tensor hk, hv;
     KvFormat fmt;
     bool fp8;
-    const int32_t rc = cached_stage_setup(who, shape, cache, k_scale, v_scale, &hk, &hv, &fmt, &fp8);
+    int32_t rc = cached_stage_setup(who, shape, cache, k_scale, v_scale, &hk, &hv, &fmt, &fp8);
     if (rc != IHIP_OK) return rc;
+    if ((rc = refuse_capture(who, (hipStream_t)stream)) != IHIP_OK) return rc;
     const BankView bank = cache_bank_view(cache, 1);
     return attn_decode_entry(who, rope, fp8 ? &fmt : nullptr, shape, q, hk, hv, block_starts, n_blocks, block,
                              sm_scale, out, out_lse, ws, ws_bytes, stream, &bank);
@@ -858,8 +873,10 @@ int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor
         fmt.fp8 = true; fmt.k_scale = opt->k_scale; fmt.v_scale = opt->v_scale;
     }
     if ((rc = check_pooling(who, opt->pooling)) != IHIP_OK) return rc;
-    if (opt->first_stage != 0 && !opt->stage_starts)
-        return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d without stage_starts", who, opt->first_stage);
+    if ((opt->first_stage != 0 || opt->stage_due) && !opt->stage_starts)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: first_stage = %d / stage_due without stage_starts", who, opt->first_stage);
+    if (opt->stage_due && opt->first_stage != 0)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: stage_due and first_stage = %d exclude each other", who, opt->first_stage);
     if (opt->cache) {
         if (opt->paged) return fail(IHIP_ERR_UNSUPPORTED, "%s: the host tier holds contiguous K/V", who);
         if (cache_holds_fp8(opt->cache) != (opt->kv_fp8 != 0))
@@ -875,7 +892,23 @@ int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor
     const bool plain = !opt->paged && !opt->kv_fp8;
     return decode_layer_impl(who, shape, q, k, v, opt->cache, opt->rope, opt->pooling == IHIP_POOL_ALL_HEADS,
                              plain ? nullptr : &fmt, n_stages, chunk_sizes, keeps, sm_scale, out, out_lse,
-                             out_block_starts, ws, ws_bytes, stream, opt->first_stage, opt->stage_starts);
+                             out_block_starts, ws, ws_bytes, stream, opt->first_stage, opt->stage_starts, opt->stage_due);
+}
+
+int32_t ihip_refresh_due(int32_t n_stages, const int32_t *n_refresh, int64_t step, int32_t *stage_due)
+{
+    const char *who = "ihip_refresh_due";
+    if (n_stages < 1 || n_stages > 8 || !n_refresh || step < 0)
+        return fail(IHIP_ERR_INVALID_ARG, "%s: need 1..8 stages, their intervals and step >= 0", who);
+    int32_t first = n_stages;
+    for (int i = 0; i < n_stages; ++i) {
+        if (n_refresh[i] < 1) return fail(IHIP_ERR_INVALID_ARG, "%s: n_refresh[%d] = %d", who, i, n_refresh[i]);
+        // the counter of stage i starts at 0 and advances by one per step modulo its interval
+        const bool due = step % n_refresh[i] == 0;
+        if (stage_due) stage_due[i] = due ? 1 : 0;
+        if (due && first == n_stages) first = i;
+    }
+    return first;
 }
 
 static int32_t prefill_layer_impl(const char *who, bool all_heads, const ihip_rope *rope, const KvFormat *fmt, const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v, int32_t n_stages,

@@ -209,7 +209,11 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || ((ROPE || KV8) && NQ * G
                 src += (lane & 7) * 8;
                 const uint32_t dst = __builtin_amdgcn_readfirstlane(
                     (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)(stage + j * 512));
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+                uint32_t m0_saved;       // M0 is put back: the compiler is not told that it changes
+                asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                             "s_mov_b32 m0, %0"
+                             : "=&s"(m0_saved)
+                             : "s"(dst), "v"(src)
                              : "memory");
             }
             return;
@@ -232,7 +236,11 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || ((ROPE || KV8) && NQ * G
             else src = (is_v ? vb : kb) + (__umul24((uint32_t)pos, (uint32_t)(is_v ? a.v_st : a.k_st)) + (uint32_t)(chunk * 8));
             const uint32_t dst = __builtin_amdgcn_readfirstlane(
                 (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)(stage + j * 4 * kD));
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src)
+            uint32_t m0_saved;           // M0 is put back: the compiler is not told that it changes
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                         "s_mov_b32 m0, %0"
+                         : "=&s"(m0_saved)
+                         : "s"(dst), "v"(src)
                          : "memory");
         }
     };

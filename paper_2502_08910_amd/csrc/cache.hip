@@ -1,6 +1,6 @@
 // Host-memory KV tier with two on-GPU hot-block banks (Sec. 4 "KV Cache
-// Offloading"; Alg. 4: "obtain a list of GPU cache misses ... evict cold
-// tokens ... replace them with the cache misses, depending on LRU policy").
+// Offloading"; Alg. 4: per-layer miss lists, then LRU replacement after the
+// layer's attention).
 //
 // K/V of the layer live in pinned host memory that kernels can read directly
 // over the host link.  Two banks in HBM hold copies of 2^k-token blocks: the
@@ -13,6 +13,11 @@
 // never a slot touched in this same call) and copies the missed blocks from
 // host memory into them.  Everything is
 // deterministic, so a CPU simulation of the same policy reproduces the tables.
+//
+// The call counter that stamps touches is a host variable copied into the
+// kernel arguments at enqueue time: a captured graph would replay a frozen
+// stamp (every slot would look "touched in this call" and replacement would
+// stop), so calls on a stream under capture are refused (refuse_capture).
 #include "block_select.h"
 
 namespace ihip {
@@ -220,6 +225,21 @@ BankView cache_bank_view(const ihip_cache *c, int which)
 
 bool cache_holds_fp8(const ihip_cache *c) { return c->row_units != kD; }
 
+// IHIP_ERR_UNSUPPORTED if `stream` is being captured into a graph (see the header of this file)
+int32_t refuse_capture(const char *who, hipStream_t st)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &status) != hipSuccess) {
+        (void)hipGetLastError();            // the query itself failed: nothing is known, go on
+        return IHIP_OK;
+    }
+    if (status != hipStreamCaptureStatusNone)
+        return fail(IHIP_ERR_UNSUPPORTED,
+                    "%s: the host tier stamps its calls with a host-side counter and cannot be captured into a graph",
+                    who);
+    return IHIP_OK;
+}
+
 void cache_describe(const ihip_cache *c, int32_t *B, int32_t *Hkv, int64_t *T_alloc, ihip_tensor *hk, ihip_tensor *hv)
 {
     *B = c->B; *Hkv = c->Hkv; *T_alloc = c->T_alloc; *hk = c->host_k; *hv = c->host_v;
@@ -364,6 +384,8 @@ int32_t ihip_cache_update(ihip_cache *c, void *stream)
 {
     if (!c) return fail(IHIP_ERR_INVALID_ARG, "ihip_cache_update: cache is NULL");
     hipStream_t st = (hipStream_t)stream;
+    const int32_t rc = refuse_capture("ihip_cache_update", st);
+    if (rc != IHIP_OK) return rc;
     for (int w = 0; w < 2; ++w) {
         const Bank &b = c->bank[w];
         {

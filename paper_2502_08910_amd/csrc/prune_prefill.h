@@ -103,22 +103,35 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
         const off_t r = (off_t)row;
         if constexpr (WIDE) {
             const uint16_t *src = base + r * stride + ((n ^ swz) << 3);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+            uint32_t m0_saved;           // M0 is put back: the compiler is not told that it changes
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                         "s_mov_b32 m0, %0"
+                         : "=&s"(m0_saved)
+                         : "s"(dst), "v"(src)
+                         : "memory");
         } else {
             const uint32_t byte_off = __umul24((uint32_t)r, (uint32_t)stride * 2u) + (uint32_t)((n ^ swz) << 4);
             const uint64_t b64 = (uint64_t)(uintptr_t)base;
             const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b64);
             const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b64 >> 32));
             const uint64_t sbase = ((uint64_t)hi << 32) | lo;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(byte_off),
-                         "s"(sbase)
+            uint32_t m0_saved;
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\t"
+                         "s_mov_b32 m0, %0"
+                         : "=&s"(m0_saved)
+                         : "s"(dst), "v"(byte_off), "s"(sbase)
                          : "memory");
         }
     };
     // the same with the row's element offset already formed (paged K)
     auto load4_at = [&](const uint16_t *base, int64_t at, uint32_t dst, int swz) {
         const uint16_t *src = base + at + ((n ^ swz) << 3);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+        uint32_t m0_saved;
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+                     "s_mov_b32 m0, %0"
+                     : "=&s"(m0_saved)
+                     : "s"(dst), "v"(src)
+                     : "memory");
     };
     // E4M3 keys: this lane's 8 bytes of row `row` (or of the row at element offset `at`), and their
     // place in a four-row group of a tile

@@ -25,8 +25,12 @@ def orc():
     return oracle
 
 
-@pytest.mark.parametrize("refresh", [(4, 2, 1), (1, 1, 1), (6, 3, 3)])
+@pytest.mark.parametrize("refresh", [(4, 2, 1), (1, 1, 1), (6, 3, 3), (3, 4, 2), (2, 5, 3)])
 def test_masked_decode_follows_oracle(ihip, orc, refresh):
+    """Nested intervals go through ihip_decode_layer_masked ("recompute from stage i on"); intervals
+    that are not nested -- a stage due while the next one is not -- through the per-stage flags of
+    ihip_decode_layer_ex, which ihip_refresh_due fills from Alg. 4's counters."""
+    nested = all(refresh[i] % refresh[i + 1] == 0 for i in range(len(refresh) - 1))
     w = configs.shrink(configs.CFG1, B=2, Hq=8, Hkv=2, T=3000, n_stream=256, n_needles=0,
                        stages=((64, 8), (16, 8), (4, 16)))
     chunks = [s[0] for s in w.stages]
@@ -43,8 +47,12 @@ def test_masked_decode_follows_oracle(ihip, orc, refresh):
         L = ihip.Layer(qd, kd, sld, 1, w.n_sink, w.n_stream)
         if state is None:
             state = L.mask_state(keeps)
-        first = ihip.first_stage_due(step, refresh)
-        out = L.decode_layer_masked(qd, kd, vd, chunks, keeps, first, state)
+        first, due = ihip.refresh_due(step, refresh)
+        if nested:
+            assert due == [i >= first for i in range(3)]
+            out = L.decode_layer_masked(qd, kd, vd, chunks, keeps, first, state)
+        else:
+            out = L.decode_layer(qd, kd, vd, chunks, keeps, stage_starts=state, stage_due=due)
         torch.cuda.synchronize()
         o = orc.Oracle(q, k, v, sl.tolist(), 1, w.n_sink, w.n_stream)
         P = w.B * w.Hkv
@@ -55,7 +63,7 @@ def test_masked_decode_follows_oracle(ihip, orc, refresh):
             off += P * keep
         for b in range(w.B):
             for g in range(w.Hkv):
-                kept, bs, bl = o.prune_from(b, g, 0, w.stages, first, cached[(b, g)])
+                kept, bs, bl = o.prune_due(b, g, 0, w.stages, due, cached[(b, g)])
                 cached[(b, g)] = kept
                 p = b * w.Hkv + g
                 for i in range(3):

@@ -60,9 +60,9 @@ def test_default_preset_runs_through_alg1_with_the_printed_budgets(k3_key):
 @pytest.mark.parametrize("name", ["n_refresh_default", "n_refresh_fast", "n_refresh_flash"])
 def test_refresh_rule_reruns_stage_i_once_per_interval(name):
     """Alg. 4 with the printed intervals: counters start at 0, stage i runs when c^(i) mod n^(i) = 0 and the
-    counters advance by one per generated token.  The library exposes the rule as 'first stage to
-    recompute' (host logic in the binding); simulate the counters literally and compare."""
-    from paper_2502_08910_amd.binding import first_stage_due
+    counters advance by one per generated token.  The library has the rule in ihip_refresh_due (host
+    arithmetic in the C library); simulate the counters literally and compare."""
+    from paper_2502_08910_amd.binding import first_stage_due, refresh_due
     n = presets()[name]
     steps = 2 * math.lcm(*n)
     c = [0] * len(n)
@@ -72,7 +72,48 @@ def test_refresh_rule_reruns_stage_i_once_per_interval(name):
         first = first_stage_due(step, n)
         # the intervals are nested (each a multiple of the next), so a due stage makes every later one due
         assert due == [i >= first for i in range(len(n))], (step, due, first)
+        assert refresh_due(step, n) == (first, due)
         for i, d_ in enumerate(due):
             runs[i] += d_
         c = [(ci + 1) % ni for ci, ni in zip(c, n)]
     assert runs == [steps // ni for ni in n]
+
+
+def test_alg4_stage_loop_with_intervals_that_are_not_nested():
+    """Alg. 4's stage loop, simulated literally over decode steps with counters c^(i) and intervals
+    (3, 4, 2) -- at step 3 the first stage is due and the second is not, at step 4 the second and third
+    are due and the first is not --, against Oracle.prune_due driven by the library's ihip_refresh_due.
+    The literal loop below keeps its own lists and calls only the single-stage routine."""
+    from oracle.pipeline import stage1_chunks, child_chunks
+    from paper_2502_08910_amd.binding import refresh_due
+    from workloads import configs
+    w = configs.shrink(configs.CFG1, T=2048 + 64, n_stream=256, n_needles=0, stages=((64, 8), (16, 8), (4, 16)))
+    n_refresh = (3, 4, 2)
+    _, k, v, _, _ = configs.make_inputs(w, 0, kind="int")
+    N = len(w.stages)
+    c = [0] * N                                                   # Alg. 4: c^(i) <- 0
+    lists = [np.zeros(0, np.int64)] * N                           # I^(l,i) of the literal loop
+    cached = [np.zeros(0, np.int64)] * N                          # the same, handed to prune_due
+    patterns = set()
+    for step in range(13):
+        T = 2048 + 5 * step                                       # the sequence grows
+        q = configs.make_q(w, 50 + step, kind="int")
+        o = Oracle(q, k, v, [T], 1, w.n_sink, w.n_stream)
+        lo, hi, _ = o.ranges(0, 0)
+        for i, (l_c, keep) in enumerate(w.stages):                # for each stage i = 1..N
+            if c[i] % n_refresh[i] == 0:                          #   if c^(i) mod n_refresh^(i) = 0: run stage i on I^(<i)
+                if i == 0:
+                    starts, lens = stage1_chunks(lo, hi, l_c)
+                else:
+                    plens = np.minimum(w.stages[i - 1][0], hi - lists[i - 1]).astype(np.int32)
+                    starts, lens = child_chunks(lists[i - 1], plens, l_c)
+                lists[i] = o.prune_stage(0, 1, 0, starts, lens, l_c, keep).kept_starts
+        first, due = refresh_due(step, n_refresh)
+        assert due == [ci % ni == 0 for ci, ni in zip(c, n_refresh)]
+        patterns.add(tuple(due))
+        cached, bs, bl = o.prune_due(0, 1, 0, w.stages, due, cached)
+        assert [x.tolist() for x in cached] == [x.tolist() for x in lists], step
+        assert bs.tolist() == lists[-1].tolist()
+        assert (bs + bl <= hi).all() and (bl >= 1).all()
+        c = [(ci + 1) % ni for ci, ni in zip(c, n_refresh)]       # c^(i) <- (c^(i) + 1) mod n_refresh^(i)
+    assert (True, False, False) in patterns and (False, True, True) in patterns and (True, False, True) in patterns
