@@ -26,8 +26,7 @@ def build(force: bool = True) -> str:
 
 
 class Rope(ctypes.Structure):
-    _fields_ = [("cos", ctypes.c_void_p), ("sin", ctypes.c_void_p), ("n_pos", ctypes.c_int32),
-                ("round_bf16", ctypes.c_int32)]
+    _fields_ = [("cos", ctypes.c_void_p), ("sin", ctypes.c_void_p), ("n_pos", ctypes.c_int32)]
 
 
 class Tensors(ctypes.Structure):

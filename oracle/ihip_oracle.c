@@ -290,28 +290,13 @@ void orc_sparse_attention(const orc_tensors *t, int b, int g, int64_t q0, int bq
  *    order, are at positions 0, 1, ..., n-1 and the query at n-1 (the position
  *    of the most recent key, which is the query's own token).
  * Rotations for the selection scores are fp32 (products and sums rounded one
- * by one), the attention is fp64 throughout.
- *  - Precision of the rotated vectors in the selection scores: the paper does
- *    not fix it.  round_bf16 = 0 keeps them in fp32; round_bf16 = 1 rounds every
- *    rotated element of q and k to bf16 (nearest-even) before the dot product,
- *    which is what a 16-bit tensor-core / matrix-core product of rotated
- *    operands computes (the products of two bf16 values are exact in fp32).
+ * by one; the paper does not fix the precision of the rotated vectors, fp32 is
+ * that of every other selection score here), the attention is fp64 throughout.
  * =========================================================================== */
 typedef struct {
     const float *cos, *sin;     /* [n_pos][d/2] */
     int32_t n_pos;
-    int32_t round_bf16;         /* selection scores only */
 } orc_rope;
-
-static float round_to_bf16(float f)
-{
-    uint32_t u;
-    memcpy(&u, &f, 4);
-    u += 0x7fffu + ((u >> 16) & 1u);      /* nearest, ties to even (finite values) */
-    u &= 0xffff0000u;
-    memcpy(&f, &u, 4);
-    return f;
-}
 
 static void rope_f32(const float *x, const orc_rope *r, int64_t pos, int d, float *out)
 {
@@ -321,8 +306,6 @@ static void rope_f32(const float *x, const orc_rope *r, int64_t pos, int d, floa
         out[2 * j] = a * c[j] - b * s[j];
         out[2 * j + 1] = a * s[j] + b * c[j];
     }
-    if (r->round_bf16)
-        for (int j = 0; j < d; ++j) out[j] = round_to_bf16(out[j]);
 }
 
 /* max over the block's queries t of ApplyRope(q_t, qpos[t]) . ApplyRope(k_p, kpos)   (fp32) */

@@ -74,15 +74,11 @@ class ProblemResult:
 class RopeSpec:
     """Dynamic RoPE (Sec. 4 "Dynamic RoPE for OOL generalization").  cos / sin:
     float32 [n_pos, d/2], cos and sin of (position x frequency j's angle);
-    prune: None, "relative" or "chunk"; attn: None or "streaming".
-    round_operands: the rotated q and k of the selection scores are rounded to
-    bf16 before their dot product (the precision of a 16-bit matrix product of
-    rotated operands; the paper does not fix it) instead of staying fp32."""
+    prune: None, "relative" or "chunk"; attn: None or "streaming"."""
     cos: np.ndarray
     sin: np.ndarray
     prune: Optional[str] = None
     attn: Optional[str] = None
-    round_operands: bool = False
 
 
 def stage1_chunks(lo: int, hi: int, l_c: int):
@@ -129,8 +125,7 @@ class Oracle:
             self._cos = np.ascontiguousarray(rope.cos, np.float32)
             self._sin = np.ascontiguousarray(rope.sin, np.float32)
             assert self._cos.shape == self._sin.shape and self._cos.shape[1] * 2 == q.shape[-1]
-            self._rope = Rope(self._cos.ctypes.data, self._sin.ctypes.data, self._cos.shape[0],
-                              1 if rope.round_operands else 0)
+            self._rope = Rope(self._cos.ctypes.data, self._sin.ctypes.data, self._cos.shape[0])
         if kv_scales is None:
             self.q, self.k, self.v = _u16(q), _u16(k), _u16(v)
         else:

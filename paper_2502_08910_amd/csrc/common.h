@@ -208,6 +208,27 @@ __device__ inline uint4 rotate_bf16x8(const uint4 x, const float4 c, const float
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
+// The same rotation kept to twice the mantissa: hi = the rotated values rounded to bf16 (what
+// rotate_bf16x8 returns), lo = what the rounding dropped, itself rounded to bf16 (the difference is
+// exact in fp32).  A product with hi + lo on one side is the fp32 rotation's to about 2^-17 relative.
+__device__ inline void rotate_bf16x8_split(const uint4 x, const float4 c, const float4 sn, uint4 &hi, uint4 &lo)
+{
+    const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+    const uint32_t in[4] = {x.x, x.y, x.z, x.w};
+    uint32_t wh[4], wl[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float e = __uint_as_float(in[i] << 16), o = __uint_as_float(in[i] & 0xffff0000u);
+        const float re = __fsub_rn(__fmul_rn(e, cc[i]), __fmul_rn(o, ss[i]));
+        const float ro = __fadd_rn(__fmul_rn(e, ss[i]), __fmul_rn(o, cc[i]));
+        const uint32_t he = f32_to_bf16_bits(re), ho = f32_to_bf16_bits(ro);
+        wh[i] = he | (ho << 16);
+        wl[i] = f32_to_bf16_bits(__fsub_rn(re, __uint_as_float(he << 16))) |
+                (f32_to_bf16_bits(__fsub_rn(ro, __uint_as_float(ho << 16))) << 16);
+    }
+    hi = make_uint4(wh[0], wh[1], wh[2], wh[3]);
+    lo = make_uint4(wl[0], wl[1], wl[2], wl[3]);
+}
 __device__ inline uint4 rotate_bf16x8(const uint4 x, const float *cos4, const float *sin4)
 {
     return rotate_bf16x8(x, *reinterpret_cast<const float4 *>(cos4), *reinterpret_cast<const float4 *>(sin4));

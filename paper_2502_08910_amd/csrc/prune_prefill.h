@@ -33,6 +33,15 @@ constexpr int kPrefillMaxIters = 4;     // chunk groups (of 32 chunks) per workg
 // candidate row is scored against both, because a key that wins as the right branch is the left
 // branch of the next iteration.  Twice the matrix work and twice the query registers.
 //
+// Precision of the rotated operands: a rotated vector is kept as two bf16 operands, its rounded
+// value and the rounded rest (rotate_bf16x8_split), and the products of the rests with the other
+// side's rounded values are added on the matrix cores as well, so that a score agrees with the
+// product of the fp32 rotations to about 2^-16 relative and a selection is decided as an fp32
+// evaluation decides it.  Relative style: both rotated query sets have a rest (the keys are not
+// rotated: exact), twice the matrix work again.  Chunk-indexed style: queries and keys have one
+// (q_hi.k_hi + q_lo.k_hi + q_hi.k_lo; the rests' own product is below fp32 rounding), three times the
+// plain kernel's matrix work; the rests of a key tile live in a second LDS tile.
+//
 // ROPE == 2: chunk-indexed style.  Every key of chunk j (index in the stage's chunk list) sits at
 // j, query t of the block at min(its own position, n_chunk - 1 + n_stream).  The queries differ in
 // position, so nothing folds: the query operands are rotated once (each row to its own position)
@@ -41,9 +50,14 @@ constexpr int kPrefillMaxIters = 4;     // chunk groups (of 32 chunks) per workg
 // of tile r/4, whose chunk and therefore table row are the same at every level of a search: the 8
 // table pieces of a lane are fetched once per chunk group).  Same carried-score search and matrix
 // work as the plain kernel, plus 8 rotations and LDS round trips per level.
-__device__ inline bf16x8 rotate_operand(const bf16x8 x, const float *cos4, const float *sin4)
+__device__ inline void rotate_operand_split(const bf16x8 x, const float *cos4, const float *sin4, bf16x8 &hi,
+                                            bf16x8 &lo)
 {
-    return __builtin_bit_cast(bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, x), cos4, sin4));
+    uint4 h, l;
+    rotate_bf16x8_split(__builtin_bit_cast(uint4, x), *reinterpret_cast<const float4 *>(cos4),
+                        *reinterpret_cast<const float4 *>(sin4), h, l);
+    hi = __builtin_bit_cast(bf16x8, h);
+    lo = __builtin_bit_cast(bf16x8, l);
 }
 
 // PAGED: K is a page pool read through the sequence's row of the block table: the lane that owns a
@@ -56,7 +70,7 @@ __device__ inline bf16x8 rotate_operand(const bf16x8 x, const float *cos4, const
 // trip through LDS); everything after that is the bf16 kernel.  The chunk score is multiplied by the
 // tensor's scale at the end.  K strides count 2-byte units.
 template <int MT, int NT, int G, bool WIDE, int ROPE, bool PAGED, int PARTS = 1, bool KV8 = false>
-__global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
+__global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
                                                                             const RopeView rope)
 {
     static_assert(NT == 2, "the shared first phase assumes two 16-chunk tiles per wave");
@@ -65,7 +79,8 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
     constexpr bool kShare = G >= 2;                  // two tiles are needed for the shared phase
     __shared__ float sh_sigma[G][NT * 16];
     __shared__ float sh_best[kPrefillMaxIters][NT * 16];      // chunk scores over the head parts done so far
-    __shared__ __attribute__((aligned(16))) uint16_t sh_rows[G * kTile];
+    constexpr int kLo = ROPE == 2 ? G * kTile : 0;   // ROPE == 2: from a tile to the tile of its rests
+    __shared__ __attribute__((aligned(16))) uint16_t sh_rows[(ROPE == 2 ? 2 * G : G) * kTile];
     // Workgroups are dealt to the 8 XCDs round-robin by linear id; let the KV head be the fastest
     // index, so that (with 8 KV heads) one XCD's L2 only ever holds one head's K rows and all
     // query blocks that share those rows run on that XCD at about the same time.
@@ -162,6 +177,8 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
     for (int r = 0; r < NT * 4; ++r) dst_own[r] = lds_addr(tile + r * 4 * kD);
     bf16x8 qa[MT][4];                                // relative RoPE: q_L
     bf16x8 qaR[ROPE == 1 ? MT : 1][4];               // relative RoPE: q_R
+    bf16x8 qaLo[ROPE ? MT : 1][4];                   // RoPE: what rounding the rotated queries to bf16 dropped
+    bf16x8 qaRLo[ROPE == 1 ? MT : 1][4];
     int q_cap = 0;                                   // chunk-indexed RoPE: the largest query position
     if constexpr (ROPE == 2) {
         __shared__ int sh_n_chunk;
@@ -184,13 +201,13 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
                     if constexpr (ROPE == 2) {
                         const int qpos = min(pr.E - a.ge.b_q + mt * 16 + n, q_cap);
                         const int64_t at = (int64_t)qpos * (kD / 2) + ((ks << 2) + kq) * 4;
-                        qa[mt][ks] = rotate_operand(qa[mt][ks], rope.cos + at, rope.sin + at);
+                        rotate_operand_split(qa[mt][ks], rope.cos + at, rope.sin + at, qa[mt][ks], qaLo[mt][ks]);
                     }
                     if constexpr (ROPE == 1) {
                         const int pair = ((ks << 2) + kq) * 4;       // first of this operand's 4 dim pairs
                         const int64_t posR = (int64_t)a.ge.n_stream * (kD / 2) + pair, posL = posR + kD / 2;
-                        qaR[mt][ks] = rotate_operand(qa[mt][ks], rope.cos + posR, rope.sin + posR);
-                        qa[mt][ks] = rotate_operand(qa[mt][ks], rope.cos + posL, rope.sin + posL);
+                        rotate_operand_split(qa[mt][ks], rope.cos + posR, rope.sin + posR, qaR[mt][ks], qaRLo[mt][ks]);
+                        rotate_operand_split(qa[mt][ks], rope.cos + posL, rope.sin + posL, qa[mt][ks], qaLo[mt][ks]);
                     }
                 }
             // the reads must have left LDS before the next loads land in the same tile
@@ -213,26 +230,40 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
     // scores of the 32 rows of a tile (column n of 16-row tile t): max over the block's queries
     // (ROPE: sig against q_L, sigR against q_R)
     auto mfma_scores = [&](const uint16_t *src, float (&sig)[NT], float (&sigR)[NT]) {
-        bf16x8 kr[NT][4];
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) kr[t][ks] = operand(src, t * 16, ks);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
+            bf16x8 kr[4], krLo[ROPE == 2 ? 4 : 1];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                kr[ks] = operand(src, t * 16, ks);
+                if constexpr (ROPE == 2) krLo[ks] = operand(src + kLo, t * 16, ks);
+            }
             float best = -INFINITY, bestR = -INFINITY;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 f32x4 c = {0.f, 0.f, 0.f, 0.f};
+                if constexpr (ROPE != 0) {           // the small terms first
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qaLo[mt][ks], kr[ks], c, 0, 0, 0);
+                }
+                if constexpr (ROPE == 2) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[mt][ks], krLo[ks], c, 0, 0, 0);
+                }
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-                    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[mt][ks], kr[t][ks], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[mt][ks], kr[ks], c, 0, 0, 0);
                 best = fmaxf(best, fmaxf(fmaxf(c[0], c[1]), fmaxf(c[2], c[3])));
                 if constexpr (ROPE == 1) {
                     f32x4 cr = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
-                        cr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qaR[mt][ks], kr[t][ks], cr, 0, 0, 0);
+                        cr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qaRLo[mt][ks], kr[ks], cr, 0, 0, 0);
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        cr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qaR[mt][ks], kr[ks], cr, 0, 0, 0);
                     bestR = fmaxf(bestR, fmaxf(fmaxf(cr[0], cr[1]), fmaxf(cr[2], cr[3])));
                 }
             }
@@ -247,7 +278,10 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
     float4 tb_cos[ROPE == 2 ? NT * 4 : 1], tb_sin[ROPE == 2 ? NT * 4 : 1];
     auto rotate_piece = [&](uint16_t *four_rows, const float4 c, const float4 sn) {
         uint4 *piece = reinterpret_cast<uint4 *>(four_rows + kq * kD + n * 8);
-        *piece = rotate_bf16x8(*piece, c, sn);
+        uint4 hi, lo;
+        rotate_bf16x8_split(*piece, c, sn, hi, lo);
+        *piece = hi;
+        *reinterpret_cast<uint4 *>(four_rows + kLo + kq * kD + n * 8) = lo;
     };
     auto rotate_own = [&](uint16_t *four_rows, int r) {      // r: compile-time after unrolling
         rotate_piece(four_rows, tb_cos[ROPE == 2 ? r : 0], tb_sin[ROPE == 2 ? r : 0]);
@@ -278,7 +312,11 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
 #pragma unroll
             for (int r = 0; r < NT * 4; ++r) {
                 uint4 piece = fp8x8_to_bf16x8(raw[r]);
-                if constexpr (ROPE == 2) piece = rotate_bf16x8(piece, tb_cos[r], tb_sin[r]);
+                if constexpr (ROPE == 2) {
+                    uint4 rest;
+                    rotate_bf16x8_split(piece, tb_cos[r], tb_sin[r], piece, rest);
+                    put16(tile + kLo + r * 4 * kD, rest);
+                }
                 put16(tile + r * 4 * kD, piece);
             }
             // the wave reads back what its other lanes stored: LDS serves a wave's requests in order
@@ -379,8 +417,10 @@ __global__ __launch_bounds__(64 * G, (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void 
                     uint4 piece = fp8x8_to_bf16x8(raw[i]);
                     if constexpr (ROPE == 2) {
                         const int64_t at = table_at(jt, ld & 7);
-                        piece = rotate_bf16x8(piece, *reinterpret_cast<const float4 *>(rope.cos + at),
-                                              *reinterpret_cast<const float4 *>(rope.sin + at));
+                        uint4 rest;
+                        rotate_bf16x8_split(piece, *reinterpret_cast<const float4 *>(rope.cos + at),
+                                            *reinterpret_cast<const float4 *>(rope.sin + at), piece, rest);
+                        put16(&sh_rows[kLo + ld * 4 * kD], rest);
                     }
                     put16(&sh_rows[ld * 4 * kD], piece);
                 }
@@ -488,9 +528,10 @@ static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hi
     case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE, ROPE, PAGED, 1, KV8>), grid, dim3(128), 0, st, a, iters, rope); break;
     case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED, 1, KV8>), grid, dim3(256), 0, st, a, iters, rope); break;
     default:
-        // 8 heads with 64-query blocks and no RoPE: 8 waves of ~160 registers fit a CU once only;
-        // two passes of 4 waves fit three times
-        if constexpr (MT == 4 && ROPE == 0)
+        // 8 heads with 64-query blocks: 8 waves of ~160 registers fit a CU once only, two passes of 4
+        // waves fit three times; with RoPE the query operands alone take more registers than 8 waves
+        // leave each other
+        if constexpr (MT == 4)
             hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED, 2, KV8>), grid, dim3(256), 0, st, a, iters, rope);
         else
             hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE, ROPE, PAGED, 1, KV8>), grid, dim3(512), 0, st, a, iters, rope);

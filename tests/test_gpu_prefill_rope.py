@@ -5,10 +5,13 @@ oracle, through the C ABI.
 
 Bit-exact bar: integer-valued Q/K/V with a quarter-turn rotary table (cos and
 sin are 0 or +-1: rotated vectors stay small integers, exact in bf16 and in
-the fp32 accumulators of the matrix cores).  Real tables on Gaussian inputs:
-the kernels round the rotated operands to bf16 where the oracle keeps fp32
-(pruning) or fp64 (attention), so scores agree to bf16 rounding of the
-operands, block recall >= 0.99 and outputs within 2e-2.
+the fp32 accumulators of the matrix cores).  Real tables on Gaussian inputs,
+against the oracle as it stands (rotations and dot products in fp32): the
+pruning kernels keep every rotated operand as a bf16 value plus a bf16 rest,
+so their scores agree with the oracle's to a few 2^-18 of sum |q_i||k_i| and
+every problem's kept list has recall >= 0.99 at every stage; the attention
+rounds its rotated operands to bf16 (no decision hangs on them) and its
+outputs agree within 2e-2.
 """
 import numpy as np
 import pytest
@@ -57,20 +60,25 @@ def gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune="relative", attn=True, wan
     return stages, out, lse, fused
 
 
-def compare(w, o, stages, out, lse, exact, problems=None, score_tol=None):
+def compare(w, o, stages, out, lse, exact, problems=None, score_tol=None, max_off=0.05, stagewise=False):
+    """stagewise (inexact mode): a stage after the first is compared with the oracle's stage run on the
+    list the kernel kept in the stage before, and end to end only where those lists are the oracle's."""
     G, Mq = w.G, w.Mq
     worst, min_recall = 0.0, 1.0
     n_off = n_all = n_hit = n_want = 0
+    N = len(w.stages)
     if problems is None:
         problems = [(b, g, m) for b in range(w.B) for g in range(w.Hkv) for m in range(Mq)]
     for (b, g, m) in problems:
         p = (b * w.Hkv + g) * Mq + m
         pr = o.prune(b, g, m, w.stages)
+        gpu_kept = []
         for i, st in enumerate(pr.stages):
             scores, rep, kept = stages[i]
             n = len(st.starts)
             sc = scores[p].cpu().numpy()
             kp = kept[p].cpu().numpy()
+            gpu_kept.append(kp[kp >= 0].astype(np.int64))
             if exact:
                 assert np.array_equal(sc[:n], st.scores), (b, g, m, i)
                 assert np.isneginf(sc[n:]).all(), (b, g, m, i)
@@ -82,15 +90,20 @@ def compare(w, o, stages, out, lse, exact, problems=None, score_tol=None):
                 assert np.array_equal(kp[:len(ks)], ks), (b, g, m, i)
                 assert (kp[len(ks):] == -1).all()
             else:
-                if i == 0:      # later stages start from the GPU's own kept set
+                if i == 0:
                     # a search that turns the other way at a near-tie ends at another representative
                     # and another score: such chunks must be rare, all others agree to rounding
                     off = np.abs(sc[:n] - st.scores) > score_tol
-                    assert off.mean() <= 0.10, (b, g, m, off.mean())
+                    assert off.mean() <= 2 * max_off, (b, g, m, off.mean())
                     n_off += int(off.sum())
                     n_all += n
-                want = set(st.kept_starts.tolist())
-                got = set(kp[kp >= 0].tolist())
+                want = st.kept_starts
+                same_input = all(np.array_equal(gpu_kept[j], pr.stages[j].kept_starts) for j in range(i))
+                if stagewise and i > 0 and not same_input:
+                    cached = gpu_kept[:i] + [np.zeros(0, np.int64)] * (N - i)
+                    want = o.prune_due(b, g, m, w.stages, [j == i for j in range(N)], cached)[0][i]
+                want = set(want.tolist())
+                got = set(gpu_kept[i].tolist())
                 assert len(got) == len(want)
                 min_recall = min(min_recall, len(got & want) / max(1, len(want)))
                 n_hit += len(got & want)
@@ -102,8 +115,7 @@ def compare(w, o, stages, out, lse, exact, problems=None, score_tol=None):
         else:
             # where a near-tie made the kernel keep another block than the oracle, the attention is
             # checked on the blocks the kernel kept
-            kp = stages[-1][2][p].cpu().numpy()
-            kp = kp[kp >= 0].astype(np.int64)
+            kp = gpu_kept[-1]
             hi = o.ranges(b, m)[1]
             ref, ref_lse = o.attend(b, g, m, kp, np.minimum(w.stages[-1][0], hi - kp).astype(np.int32))
         got = out[b, g * G:(g + 1) * G, m * w.b_q:(m + 1) * w.b_q].float().cpu().numpy()
@@ -111,7 +123,7 @@ def compare(w, o, stages, out, lse, exact, problems=None, score_tol=None):
         if exact:
             np.testing.assert_allclose(lse[b, g * G:(g + 1) * G, m * w.b_q:(m + 1) * w.b_q].cpu().numpy(),
                                        ref_lse, rtol=2e-5, atol=2e-5)
-    assert n_off <= 0.05 * max(n_all, 1), (n_off, n_all)
+    assert n_off <= max_off * max(n_all, 1), (n_off, n_all)
     return worst, (min_recall, n_hit / max(n_want, 1))
 
 
@@ -151,26 +163,28 @@ def test_rope_changes_selection_and_output(ihip, orc):
 @pytest.mark.parametrize("prune", ["relative", "chunk"])
 @pytest.mark.parametrize("seed", [0, 1])
 def test_real_table_gaussian_recall_and_output(ihip, orc, seed, prune):
-    w = small(Tq=128, prefix=4096, stages=((64, 16), (16, 32)))
+    # 256 / 257 first-stage chunks per problem of which 128 are kept, then 256 of 512: one chunk that
+    # changes sides costs a problem less than 1 % of its recall.
+    w = small(Tq=128, prefix=16384 + 320, Hq=16, Hkv=4, stages=((64, 128), (16, 256)))
     q, k, v, sl, _ = configs.make_inputs(w, seed)
     cos, sin = gen.rope_table(w.T, w.d)
-    # Relative style: the kernel folds the key's rotation into the query, R(n_stream+1-j) q . k, and
-    # rounds the rotated query to bf16 (relative error 2^-9 per element); the oracle rotates both in
-    # fp32.  For |q| ~ |k| ~ sqrt(128) the dot products differ by about 2^-9 / sqrt(3) * sqrt(128)
-    # ~ 0.013 (one sigma); 0.1 leaves 7 sigma.
-    # Chunk-indexed style: the kernel does literally what the oracle does with operand rounding on
-    # (rotate q and k to their positions, round to bf16, multiply exactly, add in fp32), so the
-    # decisions are taken in the same precision and only the order of the fp32 additions differs.
-    literal = prune == "chunk"
+    # The oracle as it stands: rotations and dot products in fp32.  A rotated operand of the kernels is
+    # a bf16 value plus the bf16-rounded rest, i.e. within 2^-18 of its fp32 value, relatively; with
+    # both sides and the dropped product of the two rests that bounds the difference of a score by
+    # 3 * 2^-18 * sum |q_i||k_i| <= 3 * 2^-18 * |q||k| ~ 2e-3 for these vectors (|q|, |k| <= 13),
+    # typically a tenth of that.  Chunks beyond it are those whose search turned the other way at
+    # a near-tie and ended at another representative: at most 1 in 100.
     o = orc.Oracle(q, k, v, sl.tolist(), w.b_q, w.n_sink, w.n_stream,
-                   rope=orc.RopeSpec(cos.numpy(), sin.numpy(), prune=prune, attn="streaming",
-                                     round_operands=literal))
+                   rope=orc.RopeSpec(cos.numpy(), sin.numpy(), prune=prune, attn="streaming"))
     stages, out, lse, fused = gpu_prefill(ihip, w, q, k, v, sl, cos, sin, prune=prune, want_rep=False)
-    worst, (min_recall, recall) = compare(w, o, stages, out, lse, exact=False, score_tol=1e-3 if literal else 0.1)
-    # block recall over the whole workload; a single problem keeps 16 or 32 chunks, so one chunk that
-    # changes sides at the selection threshold already costs it 3 to 6 percent
-    assert recall >= 0.99
-    assert min_recall >= 0.9
+    # Chunk-indexed style: a key's position is the index of its chunk in the stage's list, so a single
+    # chunk that changes sides at a near-tie of the stage before renumbers every chunk behind it and
+    # the two runs score different problems from there on.  A later stage is therefore held against
+    # the oracle's stage on the list the kernel kept before it (and end to end wherever the lists
+    # agree); the relative style has no such coupling and is compared end to end throughout.
+    worst, (min_recall, recall) = compare(w, o, stages, out, lse, exact=False, score_tol=2e-3, max_off=0.01,
+                                          stagewise=prune == "chunk")
+    assert min_recall >= 0.99           # every (sequence, KV head, query block) problem, every stage
     assert worst <= 2e-2
 
 

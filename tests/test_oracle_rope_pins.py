@@ -175,28 +175,3 @@ def test_streaming_ids_count_only_attended_keys():
         return o.attend(0, 0, 0, np.array([2, 6 + skip]), np.array([4, 4], np.int32))
     (oa, la), (ob, lb) = run(4), run(8)
     assert np.array_equal(oa, ob) and np.array_equal(la, lb)
-
-
-def test_operand_rounding_mode_rounds_rotated_vectors_to_bf16():
-    # An eighth-turn table: cos = sin = sqrt(1/2) at position 1 (fp32: 0.70710677), identity at 0.
-    # q = k = e0, both at position 1, rotate to (c, c) with c = 0.70710677; their product is
-    # 2 c^2 = 1 within an ulp in fp32.  Rounded to bf16, c becomes 0.70703125 = 181/256 exactly and
-    # the score 2 * (181/256)^2 = 65522/65536 exactly, which is what a product of bf16 operands gives.
-    d = 128
-    cos = np.ones((2, d // 2), np.float32)
-    sin = np.zeros((2, d // 2), np.float32)
-    cos[1, :] = sin[1, :] = np.float32(math.sqrt(0.5))
-    e0 = vec([(0, 1.0)])
-    plain = make([e0], [e0], rope=RopeSpec(cos, sin))
-    rounded = make([e0], [e0], rope=RopeSpec(cos, sin, round_operands=True))
-    assert abs(score(plain, 0, [1], 1) - 1.0) <= 2e-7
-    assert score(rounded, 0, [1], 1) == 2 * (181 / 256) ** 2
-    # positions with an identity rotation are untouched by the rounding (the inputs are bf16 already)
-    assert score(rounded, 0, [0], 0) == 1.0
-    # and the mode is invisible on a quarter-turn table, whose rotated values are the inputs, permuted
-    cq, sq = gen.quarter_turn_table(8, d)
-    torch.manual_seed(3)
-    q, k = torch.randn(d).to(torch.bfloat16), torch.randn(d).to(torch.bfloat16)
-    a = make([q], [k], rope=RopeSpec(cq.numpy(), sq.numpy()))
-    b = make([q], [k], rope=RopeSpec(cq.numpy(), sq.numpy(), round_operands=True))
-    assert all(score(a, 0, [i], j) == score(b, 0, [i], j) for i in range(4) for j in range(4))
