@@ -108,12 +108,71 @@ typedef struct ihip_rope {
     int32_t attn_style;          /* IHIP_ROPE_NONE / _STREAMING */
 } ihip_rope;
 
+/* Handle of a host-memory KV tier (see "Host-memory KV tier" below); owned by the library. */
+typedef struct ihip_cache ihip_cache;
+
 /* Operation ids for ihip_workspace_bytes. */
 #define IHIP_OP_ATTN_DECODE   1
 #define IHIP_OP_ATTN_PREFILL  2
 #define IHIP_OP_PRUNE_ALL     3
 #define IHIP_OP_DECODE_LAYER  4
 #define IHIP_OP_PREFILL_LAYER 5
+
+/* ==========================================================================
+ * Variants of the storage and of the scores, used by the calls below
+ * ========================================================================== */
+
+/*
+ * FP8 KV cache (the paper's end-to-end runs keep K and V in 8 bits): the
+ * *_fp8kv entry points take K and V as bytes in the OCP FP8 format E4M3 (1 sign,
+ * 4 exponent bits with bias 7, 3 mantissa bits, no infinities), one positive
+ * scale per tensor: element = scale * decoded byte.  Their ihip_tensor strides
+ * count bytes; rows are 128 bytes, 16-byte aligned.  Q and the output stay
+ * bf16.  Chunk scores are k_scale * (q . decoded k) in fp32 (the selection does
+ * not depend on the scale); the attention multiplies its scores by k_scale and
+ * its output by v_scale.  ihip_prune_stage_fp8kv serves decode and chunked
+ * prefill (b_q in {1, 16, 32, 64}); the prefill kernels repack a row as bf16
+ * (exact) on its way into LDS and multiply in bf16 as before.  These entry
+ * points read contiguous (strided) device memory; ihip_decode_layer_ex and
+ * ihip_prefill_layer_ex combine E4M3 rows with RoPE, page pools, the pooling
+ * rule or (decode) the host tier.
+ */
+
+/*
+ * Paged KV cache (the serving systems the paper runs in keep K and V in
+ * fixed-size pages): the *_paged entry points take K and V as page pools plus a
+ * block table.  k_pool / v_pool: ptr = page 0, stride_b = elements between
+ * pages, stride_h = between the KV heads of a page, stride_t = between the
+ * tokens of a page.  block_table: device int32 [B][table_stride], the page id
+ * of logical page i (tokens [i*page_tokens, (i+1)*page_tokens)) of sequence b;
+ * entries beyond a sequence's length are never read.  page_tokens is a power
+ * of two and table_stride * page_tokens >= max_seq_len.  Everything else as in
+ * the entry points of the same names without the suffix.  Built for decode
+ * and chunked prefill from bf16 pools; FP8 pools and the other variants
+ * combine through ihip_decode_layer_ex / ihip_prefill_layer_ex.
+ */
+typedef struct ihip_paged_kv {
+    const int32_t *block_table;
+    int32_t table_stride;
+    int32_t page_tokens;
+} ihip_paged_kv;
+
+/*
+ * Pooling of the chunk scores before the arg-top-K.  IHIP_POOL_KV_HEAD: one
+ * selection per (sequence, KV head, query block), the scores as ihip_prune_stage
+ * writes them (pooled over the query heads of the KV head) -- what every other
+ * entry point does.  IHIP_POOL_ALL_HEADS: the paper's own rule (Sec. 4 and
+ * Alg. 2: max over all attention heads h = 1..H): the Hkv score rows of a
+ * (sequence, query block) are max-pooled and one selection is written to all
+ * Hkv rows of out_starts, i.e. one mask per layer.  Requires the Hkv problems
+ * to have identical slots (true when every earlier stage was pooled the same way).
+ */
+#define IHIP_POOL_KV_HEAD   0
+#define IHIP_POOL_ALL_HEADS 1
+
+/* ==========================================================================
+ * The path, stage by stage: prune_stage -> select_blocks -> ... -> sparse_attn_{decode,prefill}
+ * ========================================================================== */
 
 /*
  * One pruning stage up to the arg-top-K (Alg. 2 with SelectRep of Alg. 3 inside):
@@ -142,86 +201,8 @@ int32_t ihip_prune_stage(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                          int32_t chunk, int32_t max_chunks,
                          float *out_scores, int32_t *out_rep, void *stream);
 
-/*
- * FP8 KV cache (the paper's end-to-end runs keep K and V in 8 bits): the
- * *_fp8kv entry points take K and V as bytes in the OCP FP8 format E4M3 (1 sign,
- * 4 exponent bits with bias 7, 3 mantissa bits, no infinities), one positive
- * scale per tensor: element = scale * decoded byte.  Their ihip_tensor strides
- * count bytes; rows are 128 bytes, 16-byte aligned.  Q and the output stay
- * bf16.  Chunk scores are k_scale * (q . decoded k) in fp32 (the selection does
- * not depend on the scale); the attention multiplies its scores by k_scale and
- * its output by v_scale.  ihip_prune_stage_fp8kv serves decode and chunked
- * prefill (b_q in {1, 16, 32, 64}); the prefill kernels repack a row as bf16
- * (exact) on its way into LDS and multiply in bf16 as before.  These entry
- * points read contiguous (strided) device memory; ihip_decode_layer_ex and
- * ihip_prefill_layer_ex combine E4M3 rows with RoPE, page pools, the pooling
- * rule or (decode) the host tier.
- */
-int32_t ihip_prune_stage_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
-                               const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
-                               int32_t chunk, int32_t max_chunks, float k_scale,
-                               float *out_scores, int32_t *out_rep, void *stream);
-int32_t ihip_sparse_attn_decode_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
-                                      float sm_scale, float k_scale, float v_scale, void *out,
-                                      float *out_lse, void *ws, size_t ws_bytes, void *stream);
-int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                                float sm_scale, float k_scale, float v_scale, void *out, float *out_lse,
-                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
-
-/*
- * Paged KV cache (the serving systems the paper runs in keep K and V in
- * fixed-size pages): the *_paged entry points take K and V as page pools plus a
- * block table.  k_pool / v_pool: ptr = page 0, stride_b = elements between
- * pages, stride_h = between the KV heads of a page, stride_t = between the
- * tokens of a page.  block_table: device int32 [B][table_stride], the page id
- * of logical page i (tokens [i*page_tokens, (i+1)*page_tokens)) of sequence b;
- * entries beyond a sequence's length are never read.  page_tokens is a power
- * of two and table_stride * page_tokens >= max_seq_len.  Everything else as in
- * the entry points of the same names without the suffix.  Built for decode
- * and chunked prefill from bf16 pools; FP8 pools and the other variants
- * combine through ihip_decode_layer_ex / ihip_prefill_layer_ex.
- */
-typedef struct ihip_paged_kv {
-    const int32_t *block_table;
-    int32_t table_stride;
-    int32_t page_tokens;
-} ihip_paged_kv;
-int32_t ihip_prune_stage_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
-                               const ihip_paged_kv *paged, const int32_t *parent_starts, int32_t n_parent,
-                               int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
-                               float *out_scores, int32_t *out_rep, void *stream);
-int32_t ihip_sparse_attn_decode_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
-                                      ihip_tensor v_pool, const ihip_paged_kv *paged,
-                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
-                                      float sm_scale, void *out, float *out_lse, void *ws, size_t ws_bytes,
-                                      void *stream);
-int32_t ihip_decode_layer_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, ihip_tensor v_pool,
-                                const ihip_paged_kv *paged, int32_t n_stages, const int32_t *chunk_sizes,
-                                const int32_t *keeps, float sm_scale, void *out, float *out_lse,
-                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
-
-/* ihip_prune_stage with rope->prune_style applied; rope must not be NULL. */
-int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
-                              const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
-                              int32_t chunk, int32_t max_chunks, const ihip_rope *rope,
-                              float *out_scores, int32_t *out_rep, void *stream);
-
 /* Slots the first stage needs per problem: ceil((max_seq_len - n_stream - n_sink) / chunk), >= 0. */
 int32_t ihip_stage1_slots(const ihip_shape *shape, int32_t chunk);
-
-/*
- * Alg. 1 "subdivide query blocks for the next stage" (Sec. 4: a stage's result
- * for block m goes to the blocks m' of the next, smaller block size that lie
- * inside it).  starts: device int32 [P, n], the kept chunk starts of a stage run
- * with shape->b_q queries per block; out_starts: device int32 [P * b_q /
- * b_q_fine, n], row (b, g, m') a copy of row (b, g, m' * b_q_fine / b_q).  The
- * next stage is then called with b_q = b_q_fine and b_q_range = the first
- * stage's block size.  b_q_fine divides shape->b_q; the buffers must differ.
- */
-int32_t ihip_subdivide_blocks(const ihip_shape *shape, const int32_t *starts, int32_t n, int32_t b_q_fine,
-                              int32_t *out_starts, void *stream);
 
 /*
  * arg-top-K of the chunk scores (Alg. 2, "discard chunks with low estimated
@@ -237,21 +218,16 @@ int32_t ihip_select_blocks(const ihip_shape *shape, const float *scores, int32_t
                            int32_t chunk, int32_t keep, int32_t *out_starts, void *stream);
 
 /*
- * Pooling of the chunk scores before the arg-top-K.  IHIP_POOL_KV_HEAD: one
- * selection per (sequence, KV head, query block), the scores as ihip_prune_stage
- * writes them (pooled over the query heads of the KV head) -- what every other
- * entry point does.  IHIP_POOL_ALL_HEADS: the paper's own rule (Sec. 4 and
- * Alg. 2: max over all attention heads h = 1..H): the Hkv score rows of a
- * (sequence, query block) are max-pooled and one selection is written to all
- * Hkv rows of out_starts, i.e. one mask per layer.  Requires the Hkv problems
- * to have identical slots (true when every earlier stage was pooled the same way).
+ * Alg. 1 "subdivide query blocks for the next stage" (Sec. 4: a stage's result
+ * for block m goes to the blocks m' of the next, smaller block size that lie
+ * inside it).  starts: device int32 [P, n], the kept chunk starts of a stage run
+ * with shape->b_q queries per block; out_starts: device int32 [P * b_q /
+ * b_q_fine, n], row (b, g, m') a copy of row (b, g, m' * b_q_fine / b_q).  The
+ * next stage is then called with b_q = b_q_fine and b_q_range = the first
+ * stage's block size.  b_q_fine divides shape->b_q; the buffers must differ.
  */
-#define IHIP_POOL_KV_HEAD   0
-#define IHIP_POOL_ALL_HEADS 1
-int32_t ihip_select_blocks_pooled(const ihip_shape *shape, const float *scores, int32_t max_chunks,
-                                  const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
-                                  int32_t chunk, int32_t keep, int32_t pooling, int32_t *out_starts,
-                                  void *stream);
+int32_t ihip_subdivide_blocks(const ihip_shape *shape, const int32_t *starts, int32_t n, int32_t b_q_fine,
+                              int32_t *out_starts, void *stream);
 
 /*
  * Block-sparse decode attention (Tq == b_q == 1): for every query head,
@@ -271,12 +247,6 @@ int32_t ihip_sparse_attn_decode(const ihip_shape *shape, ihip_tensor q, ihip_ten
                                 float sm_scale, void *out, float *out_lse,
                                 void *ws, size_t ws_bytes, void *stream);
 
-/* ihip_sparse_attn_decode with rope->attn_style applied to q and K (V is not rotated). */
-int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                     const int32_t *block_starts, int32_t n_blocks, int32_t block,
-                                     float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
-                                     void *ws, size_t ws_bytes, void *stream);
-
 /*
  * Block-sparse chunked-prefill attention: the same key set per query block m,
  * every query of the block attending causally inside the window (keys after
@@ -291,6 +261,18 @@ int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_te
                                  void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Scratch bytes an operation needs.  n_stages / chunk_sizes / keeps describe
+ * the stage plan (for the attention-only ops pass n_stages = 1 with
+ * chunk_sizes[0] = block and keeps[0] = n_blocks).  Returns 0 on bad arguments.
+ */
+size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stages,
+                            const int32_t *chunk_sizes, const int32_t *keeps);
+
+/* ==========================================================================
+ * The path in one enqueue: every stage, every selection and the attention (what bench.py times)
+ * ========================================================================== */
+
+/*
  * Alg. 1: every pruning stage and its arg-top-K, coarse to fine, in one
  * enqueue.  chunk_sizes / keeps are host int32 [n_stages] (l_c and K = k/l_c per
  * stage; each chunk size divides the previous one).  out_block_starts is
@@ -300,25 +282,6 @@ int32_t ihip_sparse_attn_prefill(const ihip_shape *shape, ihip_tensor q, ihip_te
 int32_t ihip_prune_all(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                        int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                        int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
-
-/* ihip_sparse_attn_prefill with rope->attn_style applied to Q and K (V is not rotated). */
-int32_t ihip_sparse_attn_prefill_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
-                                      float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
-                                      void *ws, size_t ws_bytes, void *stream);
-
-/* ihip_sparse_attn_prefill over E4M3 K and V (see "FP8 KV cache" above); rope may be NULL. */
-int32_t ihip_sparse_attn_prefill_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
-                                       float sm_scale, float k_scale, float v_scale, const ihip_rope *rope,
-                                       void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream);
-
-/* ihip_sparse_attn_prefill reading K and V from page pools (see ihip_paged_kv); rope may be NULL. */
-int32_t ihip_sparse_attn_prefill_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
-                                       ihip_tensor v_pool, const ihip_paged_kv *paged,
-                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
-                                       float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
-                                       void *ws, size_t ws_bytes, void *stream);
 
 /*
  * One decode layer call: ihip_prune_all followed by ihip_sparse_attn_decode
@@ -331,45 +294,55 @@ int32_t ihip_decode_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
- * ihip_decode_layer for callers that cannot allocate device memory or hand a
- * workspace over: code under HIP graph capture, tight serving loops,
- * harnesses that forbid hipMalloc.  Same arguments, same kernels and
- * bit-identical results, but the scratch (scores, the kept lists between the
- * stages, the final block list, the attention's split partials) is a device
- * array inside the library of IHIP_STATIC_SCRATCH_BYTES bytes, which every GPU
- * the library runs on holds until the process ends.  The call allocates and
- * frees nothing.  A shape and plan whose scratch
- * (ihip_workspace_bytes(IHIP_OP_DECODE_LAYER, ...)) exceeds the array returns
- * IHIP_ERR_WORKSPACE and enqueues nothing; the batch-8, 1M-token plan with
- * four stages needs about 4 MiB.  Every call on a GPU shares that GPU's array
- * (nothing in it has to survive or be cleared between calls): calls that
- * overlap on one GPU, on different streams or threads, race.
+ * One chunked-prefill layer call: ihip_prune_all followed by
+ * ihip_sparse_attn_prefill (Alg. 1 per query block, then block-sparse
+ * attention).  out / out_lse as in ihip_sparse_attn_prefill; out_block_starts
+ * device int32 [P, keeps[last]] or NULL.
  */
-#define IHIP_STATIC_SCRATCH_BYTES (8u << 20)
-int32_t ihip_decode_layer_static(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                                 float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
-                                 void *stream);
+int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                           int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                           float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
+                           void *ws, size_t ws_bytes, void *stream);
 
-/* ihip_decode_layer / ihip_prefill_layer with the given pooling rule in every stage's selection. */
-int32_t ihip_decode_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                                 int32_t pooling, float sm_scale, void *out, float *out_lse,
-                                 int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
-int32_t ihip_prefill_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                                  int32_t pooling, float sm_scale, void *out, float *out_lse,
-                                  int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
-
-/* ihip_decode_layer / ihip_prefill_layer with dynamic RoPE in every pruning stage and in the attention. */
-int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                               int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                               float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
-                               int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
-int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                                float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
-                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+/*
+ * The decode layer with any combination of the variants above that the kernels
+ * are built for, chosen by one options struct (zero-initialise it: every zero
+ * field means "off"):
+ *   rope          dynamic RoPE (pruning and attention styles inside), or NULL
+ *   cache         host tier: k and v are ignored, the handle's host tensors and
+ *                 banks are used, or NULL
+ *   paged         k and v are page pools read through this block table, or NULL
+ *   kv_fp8        non-zero: k and v hold E4M3 bytes with the scales k_scale, v_scale
+ *   pooling       IHIP_POOL_KV_HEAD / IHIP_POOL_ALL_HEADS
+ *   stage_starts  mask-caching state as in ihip_decode_layer_masked, or NULL;
+ *   first_stage   first stage to recompute (needs stage_starts unless 0)
+ *   stage_due     host int32 [n_stages] or NULL (needs stage_starts; first_stage must be 0): Alg. 4's
+ *                 per-stage test as it is printed -- stage i is re-run iff stage_due[i] != 0, reading
+ *                 the list of stage i-1 as it stands (re-run in this call or cached), and a stage that
+ *                 is not due keeps its cached list even when an earlier stage was re-run.
+ *                 ihip_refresh_due fills it from the refresh intervals and the step number.
+ * Paged, FP8 and RoPE combine freely with each other, with either pooling rule
+ * and with mask caching; the host tier (contiguous K/V) combines with FP8 (a
+ * cache made by ihip_cache_create_fp8), RoPE, pooling and mask caching
+ * (IHIP_ERR_UNSUPPORTED otherwise).  With stage_starts the scratch is the
+ * scores buffer plus the attention partials (IHIP_OP_DECODE_LAYER covers it);
+ * out_block_starts, if given, receives a copy of the final list.
+ */
+typedef struct ihip_decode_options {
+    const ihip_rope *rope;
+    const ihip_cache *cache;
+    const ihip_paged_kv *paged;
+    int32_t kv_fp8;
+    float k_scale, v_scale;
+    int32_t pooling;
+    int32_t first_stage;
+    int32_t *stage_starts;
+    const int32_t *stage_due;
+} ihip_decode_options;
+int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                             int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                             float sm_scale, const ihip_decode_options *opt, void *out, float *out_lse,
+                             int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * The prefill layer with the variants in any combination: dynamic RoPE
@@ -414,22 +387,45 @@ int32_t ihip_prefill_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tenso
  * for IHIP_OP_DECODE_LAYER.
  */
 size_t  ihip_mask_state_elems(const ihip_shape *shape, int32_t n_stages, const int32_t *keeps);
-
 int32_t ihip_decode_layer_masked(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                                  int32_t first_stage, int32_t *stage_starts, float sm_scale, void *out,
                                  float *out_lse, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * One chunked-prefill layer call: ihip_prune_all followed by
- * ihip_sparse_attn_prefill (Alg. 1 per query block, then block-sparse
- * attention).  out / out_lse as in ihip_sparse_attn_prefill; out_block_starts
- * device int32 [P, keeps[last]] or NULL.
+ * Alg. 4's counters (c^(i) starts at 0 and advances by one per generated token modulo n_refresh^(i);
+ * stage i is re-run when c^(i) = 0): for decode step `step` (0 = the first) writes
+ * stage_due[i] = (step mod n_refresh[i] == 0) to the host array stage_due (may be NULL) and returns
+ * the first due stage, n_stages if none is, or a negative error.  Host arithmetic only.  With nested
+ * intervals (each a multiple of the next) every stage after the first due one is due as well and the
+ * return value is all ihip_decode_layer_masked needs.
  */
-int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                           int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                           float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
-                           void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_refresh_due(int32_t n_stages, const int32_t *n_refresh, int64_t step, int32_t *stage_due);
+
+/*
+ * ihip_decode_layer for callers that cannot allocate device memory or hand a
+ * workspace over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results, but the scratch (scores, the kept lists between the
+ * stages, the final block list, the attention's split partials) is a device
+ * array inside the library of IHIP_STATIC_SCRATCH_BYTES bytes, which every GPU
+ * the library runs on holds until the process ends.  The call allocates and
+ * frees nothing.  A shape and plan whose scratch
+ * (ihip_workspace_bytes(IHIP_OP_DECODE_LAYER, ...)) exceeds the array returns
+ * IHIP_ERR_WORKSPACE and enqueues nothing; the batch-8, 1M-token plan with
+ * four stages needs about 4 MiB.  Every call on a GPU shares that GPU's array
+ * (nothing in it has to survive or be cleared between calls): calls that
+ * overlap on one GPU, on different streams or threads, race.
+ */
+#define IHIP_STATIC_SCRATCH_BYTES (8u << 20)
+int32_t ihip_decode_layer_static(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
+                                 void *stream);
+
+/* ==========================================================================
+ * Host-memory KV tier with the on-GPU hot-block cache
+ * ========================================================================== */
 
 /*
  * Host-memory KV tier with an on-GPU hot-block cache (Sec. 4 "KV Cache
@@ -468,7 +464,6 @@ int32_t ihip_prefill_layer(const ihip_shape *shape, ihip_tensor q, ihip_tensor k
  * global block id (b*Hkv+g)*blocks_per_head + block: slot or -1) and slot
  * table (block id per slot or -1) to host arrays; either may be NULL.
  */
-typedef struct ihip_cache ihip_cache;
 size_t  ihip_cache_device_bytes(int32_t B, int32_t Hkv, int64_t T_alloc, int32_t block_tokens,
                                 int32_t mask_slots, int32_t sa_slots);
 int32_t ihip_cache_create(ihip_cache **out, void *dev_mem, size_t dev_bytes, ihip_tensor host_k,
@@ -501,6 +496,13 @@ int32_t ihip_cache_create_paged(ihip_cache **out, void *dev_mem, size_t dev_byte
                                 int32_t mask_slots, int32_t sa_slots, void *stream);
 void    ihip_cache_destroy(ihip_cache *cache);
 int32_t ihip_cache_reset(ihip_cache *cache, void *stream);
+int32_t ihip_cache_update(ihip_cache *cache, void *stream);
+int32_t ihip_cache_stats(ihip_cache *cache, uint64_t *stats8);
+int32_t ihip_cache_read_tables(ihip_cache *cache, int32_t bank, int32_t *host_page_table,
+                               int32_t *host_slot_block);
+int32_t ihip_cache_geometry(const ihip_cache *cache, int32_t *n_blocks_total, int32_t *mask_slots,
+                            int32_t *sa_slots);
+
 /*
  * The stage-by-stage calls through the host tier: ihip_prune_stage (decode,
  * Tq == b_q == 1) reading K through the cache's mask bank, and
@@ -519,97 +521,97 @@ int32_t ihip_sparse_attn_decode_cached(const ihip_shape *shape, ihip_tensor q, i
                                        const int32_t *block_starts, int32_t n_blocks, int32_t block,
                                        float sm_scale, const ihip_rope *rope, float k_scale, float v_scale,
                                        void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream);
+
+/* ==========================================================================
+ * The stage-by-stage calls with one variant of the storage or of the scores
+ * ========================================================================== */
+
+/* ihip_prune_stage / ihip_sparse_attn_decode / ihip_sparse_attn_prefill over E4M3 K and V ("FP8 KV cache" above);
+ * the prefill attention takes rope as well (may be NULL). */
+int32_t ihip_prune_stage_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
+                               const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                               int32_t chunk, int32_t max_chunks, float k_scale,
+                               float *out_scores, int32_t *out_rep, void *stream);
+int32_t ihip_sparse_attn_decode_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                      float sm_scale, float k_scale, float v_scale, void *out,
+                                      float *out_lse, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_sparse_attn_prefill_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                       float sm_scale, float k_scale, float v_scale, const ihip_rope *rope,
+                                       void *out, float *out_lse, void *ws, size_t ws_bytes, void *stream);
+
+/* ... reading K and V from page pools (ihip_paged_kv above); the prefill attention takes rope as well (may be NULL). */
+int32_t ihip_prune_stage_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
+                               const ihip_paged_kv *paged, const int32_t *parent_starts, int32_t n_parent,
+                               int32_t parent_chunk, int32_t chunk, int32_t max_chunks,
+                               float *out_scores, int32_t *out_rep, void *stream);
+int32_t ihip_sparse_attn_decode_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
+                                      ihip_tensor v_pool, const ihip_paged_kv *paged,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                      float sm_scale, void *out, float *out_lse, void *ws, size_t ws_bytes,
+                                      void *stream);
+int32_t ihip_sparse_attn_prefill_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool,
+                                       ihip_tensor v_pool, const ihip_paged_kv *paged,
+                                       const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                       float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                       void *ws, size_t ws_bytes, void *stream);
+
+/* ... with dynamic RoPE: the pruning call applies rope->prune_style, the attention calls rope->attn_style to q and K
+ * (V is not rotated); rope must not be NULL. */
+int32_t ihip_prune_stage_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k,
+                              const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                              int32_t chunk, int32_t max_chunks, const ihip_rope *rope,
+                              float *out_scores, int32_t *out_rep, void *stream);
+int32_t ihip_sparse_attn_decode_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                     const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                     float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                     void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_sparse_attn_prefill_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                      const int32_t *block_starts, int32_t n_blocks, int32_t block,
+                                      float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                      void *ws, size_t ws_bytes, void *stream);
+
+/* ihip_select_blocks with a pooling rule (IHIP_POOL_* above). */
+int32_t ihip_select_blocks_pooled(const ihip_shape *shape, const float *scores, int32_t max_chunks,
+                                  const int32_t *parent_starts, int32_t n_parent, int32_t parent_chunk,
+                                  int32_t chunk, int32_t keep, int32_t pooling, int32_t *out_starts,
+                                  void *stream);
+
+/* ==========================================================================
+ * Conveniences: a layer call with exactly one variant.  Each is ihip_decode_layer_ex /
+ * ihip_prefill_layer_ex with that one option set (same checks, same kernels, same results); new code
+ * can use the _ex calls alone.
+ * ========================================================================== */
+
+int32_t ihip_decode_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                 int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                 int32_t pooling, float sm_scale, void *out, float *out_lse,
+                                 int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_prefill_layer_pooled(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                  int32_t pooling, float sm_scale, void *out, float *out_lse,
+                                  int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_decode_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                               int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                               float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                               int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_prefill_layer_rope(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                float sm_scale, const ihip_rope *rope, void *out, float *out_lse,
+                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_decode_layer_fp8kv(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
+                                int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
+                                float sm_scale, float k_scale, float v_scale, void *out, float *out_lse,
+                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
+int32_t ihip_decode_layer_paged(const ihip_shape *shape, ihip_tensor q, ihip_tensor k_pool, ihip_tensor v_pool,
+                                const ihip_paged_kv *paged, int32_t n_stages, const int32_t *chunk_sizes,
+                                const int32_t *keeps, float sm_scale, void *out, float *out_lse,
+                                int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
 int32_t ihip_decode_layer_cached(const ihip_shape *shape, ihip_tensor q, ihip_cache *cache,
                                  int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
                                  float sm_scale, void *out, float *out_lse, int32_t *out_block_starts,
                                  void *ws, size_t ws_bytes, void *stream);
-
-/*
- * The decode layer with any combination of the variants above that the kernels
- * are built for, chosen by one options struct (zero-initialise it: every zero
- * field means "off"):
- *   rope          dynamic RoPE (pruning and attention styles inside), or NULL
- *   cache         host tier: k and v are ignored, the handle's host tensors and
- *                 banks are used, or NULL
- *   paged         k and v are page pools read through this block table, or NULL
- *   kv_fp8        non-zero: k and v hold E4M3 bytes with the scales k_scale, v_scale
- *   pooling       IHIP_POOL_KV_HEAD / IHIP_POOL_ALL_HEADS
- *   stage_starts  mask-caching state as in ihip_decode_layer_masked, or NULL;
- *   first_stage   first stage to recompute (needs stage_starts unless 0)
- *   stage_due     host int32 [n_stages] or NULL (needs stage_starts; first_stage must be 0): Alg. 4's
- *                 per-stage test as it is printed -- stage i is re-run iff stage_due[i] != 0, reading
- *                 the list of stage i-1 as it stands (re-run in this call or cached), and a stage that
- *                 is not due keeps its cached list even when an earlier stage was re-run.
- *                 ihip_refresh_due fills it from the refresh intervals and the step number.
- * Paged, FP8 and RoPE combine freely with each other, with either pooling rule
- * and with mask caching; the host tier (contiguous K/V) combines with FP8 (a
- * cache made by ihip_cache_create_fp8), RoPE, pooling and mask caching
- * (IHIP_ERR_UNSUPPORTED otherwise).  With stage_starts the scratch is the
- * scores buffer plus the attention partials (IHIP_OP_DECODE_LAYER covers it);
- * out_block_starts, if given, receives a copy of the final list.
- */
-typedef struct ihip_decode_options {
-    const ihip_rope *rope;
-    const ihip_cache *cache;
-    const ihip_paged_kv *paged;
-    int32_t kv_fp8;
-    float k_scale, v_scale;
-    int32_t pooling;
-    int32_t first_stage;
-    int32_t *stage_starts;
-    const int32_t *stage_due;
-} ihip_decode_options;
-int32_t ihip_decode_layer_ex(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
-                             int32_t n_stages, const int32_t *chunk_sizes, const int32_t *keeps,
-                             float sm_scale, const ihip_decode_options *opt, void *out, float *out_lse,
-                             int32_t *out_block_starts, void *ws, size_t ws_bytes, void *stream);
-/*
- * Alg. 4's counters (c^(i) starts at 0 and advances by one per generated token modulo n_refresh^(i);
- * stage i is re-run when c^(i) = 0): for decode step `step` (0 = the first) writes
- * stage_due[i] = (step mod n_refresh[i] == 0) to the host array stage_due (may be NULL) and returns
- * the first due stage, n_stages if none is, or a negative error.  Host arithmetic only.  With nested
- * intervals (each a multiple of the next) every stage after the first due one is due as well and the
- * return value is all ihip_decode_layer_masked needs.
- */
-int32_t ihip_refresh_due(int32_t n_stages, const int32_t *n_refresh, int64_t step, int32_t *stage_due);
-int32_t ihip_cache_update(ihip_cache *cache, void *stream);
-int32_t ihip_cache_stats(ihip_cache *cache, uint64_t *stats8);
-int32_t ihip_cache_read_tables(ihip_cache *cache, int32_t bank, int32_t *host_page_table,
-                               int32_t *host_slot_block);
-int32_t ihip_cache_geometry(const ihip_cache *cache, int32_t *n_blocks_total, int32_t *mask_slots,
-                            int32_t *sa_slots);
-
-/*
- * Scratch bytes an operation needs.  n_stages / chunk_sizes / keeps describe
- * the stage plan (for the attention-only ops pass n_stages = 1 with
- * chunk_sizes[0] = block and keeps[0] = n_blocks).  Returns 0 on bad arguments.
- */
-size_t ihip_workspace_bytes(int32_t op, const ihip_shape *shape, int32_t n_stages,
-                            const int32_t *chunk_sizes, const int32_t *keeps);
-
-/*
- * Optional per-kernel timing (the measurement protocol, not the method): while
- * enabled, every kernel the library launches is bracketed by two HIP events on
- * its stream (events are created on first use and recycled).  ihip_profile_read
- * waits for the recorded events, adds them up per kernel name and forgets
- * them: it fills up to max_entries of names (static strings owned by the
- * library), total_ms and launches (host arrays) and returns the number of
- * distinct kernels, or a negative error.  Not for use under graph capture.
- */
-int32_t ihip_profile_enable(int32_t on);
-int32_t ihip_profile_read(int32_t max_entries, const char **names, double *total_ms, int64_t *launches);
-
-/*
- * Dense matrix-core rate of the current device (the measurement protocol, not
- * the method): runs independent accumulation chains of one bf16 MFMA shape
- * (kind 0: 32x32x16, the prefill attention's; kind 1: 16x16x32, the prefill
- * pruning's) with no memory traffic, `iters` instructions per chain, on every
- * compute unit, twice (the second run is timed with HIP events on `stream`),
- * and writes the rate in TFLOP/s (2 flops per multiply-add) to the host double
- * *tflops.  scratch: device, >= 512 floats, never written in practice.  Blocks
- * until the timed run has finished.  Not for use under graph capture.
- */
-int32_t ihip_mfma_rate(int32_t kind, int32_t iters, float *scratch, double *tflops, void *stream);
 
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char *ihip_last_error(void);
@@ -621,3 +623,4 @@ int32_t ihip_version(void);
 }
 #endif
 #endif /* IHIP_H */
+

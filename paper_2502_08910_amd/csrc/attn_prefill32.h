@@ -81,14 +81,9 @@ constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above w
 // and strides are below 2^24, so an offset is one full-rate 24-bit multiply.
 // PAGED: K and V are page pools read through the sequence's row of the block table; the page id of
 // every slot is looked up once, next to its position, and kept in LDS as well.
-// QW: query tiles of 32 per wave.  With QW = 2 (b_q = 64) a wave owns all 64 queries of its head:
-// every K and V operand it reads from LDS feeds two matrix products, which halves the LDS traffic
-// per flop -- the resource the kernel otherwise waits for --; the 128 accumulator, 64 query and 32
-// score registers then leave room for one wave per SIMD only.
-template <int NQ, int G, bool WIDE, bool ROPE, bool PAGED, bool KV8 = false, int QW = 1>
-__global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROPE || KV8) && NQ * G == 8) ? 2 : NQ * G == 8 ? 3 : 4) void attn_prefill32_kernel(const AttnPrefillArgs a)
+template <int NQ, int G, bool WIDE, bool ROPE, bool PAGED, bool KV8 = false>
+__global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || ((ROPE || KV8) && NQ * G == 8) ? 2 : NQ * G == 8 ? 3 : 4) void attn_prefill32_kernel(const AttnPrefillArgs a)
 {
-    static_assert(QW == 1 || (QW == 2 && NQ == 2), "a wave owns one query tile, or both tiles of a 64-query block");
     static_assert(!PAGED || WIDE, "paged pools are addressed with 64-bit offsets");
     static_assert(!KV8 || WIDE, "E4M3 rows are addressed with 64-bit offsets");
     constexpr int kPfStages = KV8 ? kPfStagesFp8 : ROPE ? kPfStagesRope : kPfStagesPlain;
@@ -111,19 +106,17 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
         if (p >= a.ge.B * a.ge.Hkv * a.ge.Mq) return;
     }
     const Problem pr = problem_of(a.ge, p);
-    constexpr int NW = NQ * G / QW;
+    constexpr int NW = NQ * G;
     constexpr int nthreads = 64 * NW;
     constexpr int b_q = 32 * NQ;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int hh = wave % G, qt = wave / G;          // this wave's head and first query tile (of QW)
+    const int hh = wave % G, qt = wave / G;          // this wave's head and query tile
     const int n = lane & 31, half = lane >> 5;
     const int h = pr.g * a.ge.G + head_part * G + hh;
-    const int q0 = pr.m * b_q + qt * QW * 32;        // first query row of this wave
+    const int q0 = pr.m * b_q + qt * 32;             // first query row of this wave
     const int qpos0 = pr.E - b_q;                    // absolute position of the block's first query
-    int qpos[QW];                                    // ... of this lane's queries
-#pragma unroll
-    for (int j = 0; j < QW; ++j) qpos[j] = qpos0 + (qt * QW + j) * 32 + n;
+    const int qpos = qpos0 + qt * 32 + n;            // ... of this lane's query
 
     const int n_sink_eff = min(a.ge.n_sink, pr.E);
     const int w0 = max(pr.hi, a.ge.n_sink);
@@ -146,17 +139,16 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
         ids.block_tokens = pf_block_tokens(a, pr, p, nthreads, &sh_tokens);
     }
 
-    bf16x8 qb[QW][8];
-#pragma unroll
-    for (int j = 0; j < QW; ++j) {
-        const uint16_t *qp = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(q0 + j * 32 + n) * a.q_st + half * 8;
+    bf16x8 qb[8];
+    {
+        const uint16_t *qp = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(q0 + n) * a.q_st + half * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            qb[j][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+            qb[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
             if constexpr (ROPE) {       // dims 16*ks + 8*half .. +7 = pairs 8*ks + 4*half .. +3
-                const int64_t at = (int64_t)ids.query(a.ge.n_sink, qpos[j]) * (kD / 2) + ks * 8 + half * 4;
-                qb[j][ks] = __builtin_bit_cast(
-                    bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, qb[j][ks]), a.rope_cos + at, a.rope_sin + at));
+                const int64_t at = (int64_t)ids.query(a.ge.n_sink, qpos) * (kD / 2) + ks * 8 + half * 4;
+                qb[ks] = __builtin_bit_cast(
+                    bf16x8, rotate_bf16x8(__builtin_bit_cast(uint4, qb[ks]), a.rope_cos + at, a.rope_sin + at));
             }
         }
     }
@@ -164,17 +156,12 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
     const uint16_t *vb = PAGED ? a.v + pr.g * a.v_sh : a.v + pr.b * a.v_sb + pr.g * a.v_sh;
     const int page_mask = PAGED ? (1 << a.paged.page_log2) - 1 : 0;
 
-    f32x16 o[QW][4];
-    float m_run[QW], l_run[QW];
+    f32x16 o[4];
 #pragma unroll
-    for (int j = 0; j < QW; ++j) {
-        m_run[j] = kNegBigPf;
-        l_run[j] = 0.f;
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[j][dt][r] = 0.f;
-    }
+        for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    float m_run = kNegBigPf, l_run = 0.f;
 
     // Loads of a tile: 8 four-row instructions for K and 8 for V (KV8: 4 eight-row instructions
     // each), dealt to the NW waves.
@@ -306,23 +293,21 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
         }
     };
 
-    // first product of a tile: S^T = K Q^T for this wave's queries (a K operand serves all QW tiles)
-    auto scores = [&](int st, f32x16 (&s)[QW]) {
+    // first product of a tile: S^T = K Q^T for this wave's 32 queries
+    auto scores = [&](int st) -> f32x16 {
         const uint16_t *cK = stage_of(st) + n * kD;
+        f32x16 s;
 #pragma unroll
-        for (int j = 0; j < QW; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[j][r] = 0.f;
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(&cK[((ks * 2 + half) ^ (n & 15)) * 8]);
-#pragma unroll
-            for (int j = 0; j < QW; ++j) s[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[j][ks], s[j], 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[ks], s, 0, 0, 0);
         }
+        return s;
     };
     // softmax update of a tile's scores: P (bf16) for the second product, running sum, rescale
-    auto softmax = [&](int tile, bool masked, f32x16 &s, bf16x8 (&pb)[2], float &m_run, float &l_run,
-                       f32x16 (&o)[4], const int qpos) {
+    auto softmax = [&](int tile, bool masked, f32x16 &s, bf16x8 (&pb)[2]) {
         if (masked) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -384,17 +369,13 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
             (__attribute__((address_space(3))) s16x4 *)(cV + voff[dt] + (16 * kk + 8) * kD));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    auto accumulate = [&](int st, const bf16x8 (&pb)[QW][2]) {
+    auto accumulate = [&](int st, const bf16x8 (&pb)[2]) {
         const uint16_t *cV = stage_of(st);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 va = v_operand(cV, dt, kk);
-#pragma unroll
-                for (int j = 0; j < QW; ++j)
-                    o[j][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j][kk], o[j][dt], 0, 0, 0);
-            }
+            for (int kk = 0; kk < 2; ++kk)
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(cV, dt, kk), pb[kk], o[dt], 0, 0, 0);
     };
     // Tile t+D is requested at the start of period t (D = kPfStages-1); tile t+2 (ROPE: t+3) must
     // have landed at the barrier that ends it, so one newer request may still be on its way then
@@ -421,14 +402,9 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
         __syncthreads();
         if constexpr (KV8) request(3, 3, rows_of(3));       // into the raw stage tile 0 has left
     }
-    f32x16 s_nxt[QW];
-    bf16x8 pb[QW][2];
-    auto softmax_all = [&](int tile, bool masked) {
-#pragma unroll
-        for (int j = 0; j < QW; ++j) softmax(tile, masked, s_nxt[j], pb[j], m_run[j], l_run[j], o[j], qpos[j]);
-    };
-    scores(0, s_nxt);
-    softmax_all(0, sMasked[0] != 0);
+    f32x16 s_nxt = scores(0);
+    bf16x8 pb[2];
+    softmax(0, sMasked[0] != 0, s_nxt, pb);
     int masked_nxt = n_tiles > 1 ? sMasked[1] : 0;      // read a period ahead, like the row positions
     // one tile period; ST = tile % kPfStages
     auto period = [&](auto st_c, int tile) {
@@ -438,9 +414,9 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
         Table table_nxt{};
         if constexpr (ROPE) table_nxt = table_of(tile + 3);
         request(tile + D, ST + D, rows);
-        if (tile + 1 < n_tiles) scores(ST + 1, s_nxt);
+        if (tile + 1 < n_tiles) s_nxt = scores(ST + 1);
         accumulate(ST, pb);
-        if (tile + 1 < n_tiles) softmax_all(tile + 1, masked_nxt != 0);
+        if (tile + 1 < n_tiles) softmax(tile + 1, masked_nxt != 0, s_nxt, pb);
         masked_nxt = tile + 2 < n_tiles ? sMasked[tile + 2] : 0;
         rows = rows_of(tile + D + 1);
         if constexpr (kTouch) {
@@ -470,24 +446,21 @@ __global__ __launch_bounds__(64 * NQ * G / QW, QW == 2 ? 1 : NQ * G < 8 || ((ROP
                     std::integral_constant<int, 5>{});
     }
 
+    float l = l_run;
+    l += __shfl_xor(l, 32, 64);
+    const float inv = KV8 ? a.v_scale / l : 1.0f / l;
+    const int64_t row = ((int64_t)pr.b * a.ge.Hq + h) * a.ge.Tq + q0 + n;
 #pragma unroll
-    for (int j = 0; j < QW; ++j) {
-        float l = l_run[j];
-        l += __shfl_xor(l, 32, 64);
-        const float inv = KV8 ? a.v_scale / l : 1.0f / l;
-        const int64_t row = ((int64_t)pr.b * a.ge.Hq + h) * a.ge.Tq + q0 + j * 32 + n;
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                uint2 w;
-                w.x = f32_to_bf16_bits(o[j][dt][r4 * 4 + 0] * inv) | (f32_to_bf16_bits(o[j][dt][r4 * 4 + 1] * inv) << 16);
-                w.y = f32_to_bf16_bits(o[j][dt][r4 * 4 + 2] * inv) | (f32_to_bf16_bits(o[j][dt][r4 * 4 + 3] * inv) << 16);
-                *reinterpret_cast<uint2 *>(a.out + row * kD + dt * 32 + r4 * 8 + half * 4) = w;
-            }
-        if (a.out_lse != nullptr && half == 0)
-            a.out_lse[row] = (m_run[j] + log2f(l)) * 0.69314718055994530942f;
-    }
+        for (int r4 = 0; r4 < 4; ++r4) {
+            uint2 w;
+            w.x = f32_to_bf16_bits(o[dt][r4 * 4 + 0] * inv) | (f32_to_bf16_bits(o[dt][r4 * 4 + 1] * inv) << 16);
+            w.y = f32_to_bf16_bits(o[dt][r4 * 4 + 2] * inv) | (f32_to_bf16_bits(o[dt][r4 * 4 + 3] * inv) << 16);
+            *reinterpret_cast<uint2 *>(a.out + row * kD + dt * 32 + r4 * 8 + half * 4) = w;
+        }
+    if (a.out_lse != nullptr && half == 0)
+        a.out_lse[row] = (m_run + log2f(l)) * 0.69314718055994530942f;
 }
 
 }  // namespace ihip

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/ihip.h"
+#include "../../include/ihip_measure.h"
 
 struct ihip_cache;
 

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ihip.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("ihip.h", "ihip_measure.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ihip_[a-z0-9_]+)\s*\(", text)))
 
