@@ -48,7 +48,9 @@ struct SelView {
     }
     __device__ void put(int rank, int value) const
     {
-        for (int g = 0; g < pool; ++g) out[g * out_stride + rank] = value;
+        out[rank] = value;
+        if (pool > 1)
+            for (int g = 1; g < pool; ++g) out[g * out_stride + rank] = value;
     }
 };
 
@@ -135,14 +137,45 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
     const int per = (n + NT - 1) / NT;                  // <= kFastItems, slots [tid*per, tid*per + per)
     const int i0 = tid * per;
 
+    // The start positions of this thread's slots depend on nothing the selection computes: the
+    // sequence length and the parents' starts are requested now, next to the scores, and are there
+    // when the kept slots are written at the end (asked for then, they would be two more dependent
+    // trips to memory on a path that consists of little else).
+    if (n == 0) {                                       // no slots at all: only the padding is written
+        for (int i = tid; i < a.keep; i += NT) view.put(i, -1);
+        return;
+    }
+    // All of these loads are written without a branch or a loop between them, so that they are in
+    // flight together: with a per-item loop over the pooled rows, or an early return per slot, the
+    // compiler waits for every load before it issues the next, and 16 trips to L2 one after the
+    // other were half of this kernel's time.
+    const Problem pr = problem_of(a.ge, p);
+    const bool has_parents = a.parent_starts != nullptr;
+    const int32_t *parents = has_parents ? a.parent_starts + (int64_t)p * a.n_parent : nullptr;
+    int start_of[kFastItems];
     float v[kFastItems];
+#pragma unroll
+    for (int i = 0; i < kFastItems; ++i) {
+        const int idx = min(i0 + i, n - 1);              // clamped: the value is ignored when out of range
+        start_of[i] = has_parents ? parents[idx >> a.ratio_log2] : 0;
+        v[i] = view.sc[idx];
+    }
+    if (view.pool > 1) {
+#pragma unroll
+        for (int i = 0; i < kFastItems; ++i)
+            for (int g = 1; g < view.pool; ++g) v[i] = fmaxf(v[i], view.sc[g * view.in_stride + min(i0 + i, n - 1)]);
+    }
     float mn = INFINITY, mx = -INFINITY;
     uint32_t valid = 0;
 #pragma unroll
     for (int i = 0; i < kFastItems; ++i) {
         const int idx = i0 + i;
-        v[i] = (i < per && idx < n) ? view.score(idx) + 0.0f : -INFINITY;      // -0.0 -> +0.0
-        if (i < per && idx < n) keys[idx] = order_key(v[i]);
+        const bool in = i < per && idx < n;
+        // the slot's start position (as slot_start computes it), -1 for a slot without keys
+        const int st = has_parents ? start_of[i] + (idx & ((1 << a.ratio_log2) - 1)) * a.chunk : pr.lo + idx * a.chunk;
+        start_of[i] = in && (!has_parents || start_of[i] >= 0) && st < pr.hi ? st : -1;
+        v[i] = in ? v[i] + 0.0f : -INFINITY;                                    // -0.0 -> +0.0
+        if (in) keys[idx] = order_key(v[i]);
         if (v[i] > -INFINITY) { mn = fminf(mn, v[i]); mx = fmaxf(mx, v[i]); ++valid; }
     }
 #pragma unroll
@@ -176,10 +209,12 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
         // suffix sums over the bins: thread t owns bins [t*bp, t*bp + bp), highest bins = lowest threads
         constexpr int bp = kFastBins / NT > 0 ? kFastBins / NT : 1;
         const bool owns = tid * bp < kFastBins;
-        uint32_t mine = 0;
-        if (owns)
+        uint32_t mine = 0, hv[bp];
 #pragma unroll
-            for (int j = 0; j < bp; ++j) mine += hist[kFastBins - 1 - (tid * bp + j)];
+        for (int j = 0; j < bp; ++j) {
+            hv[j] = owns ? hist[kFastBins - 1 - (tid * bp + j)] : 0u;
+            mine += hv[j];
+        }
         uint32_t incl = wave_incl_scan_u32(mine, lane);
         if (lane == 63) wave_tot[wv] = incl;
         __syncthreads();
@@ -187,10 +222,15 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
         // the K-th best lies in the first bin (from the top) where the running count reaches keep_eff
         if (owns && incl >= (uint32_t)keep_eff && incl - mine < (uint32_t)keep_eff) {
             uint32_t run = incl - mine;
+            bool found = false;
+#pragma unroll
             for (int j = 0; j < bp; ++j) {
-                const int b = kFastBins - 1 - (tid * bp + j);
-                if (run + hist[b] >= (uint32_t)keep_eff) { sh_bin = b; sh_above = run; break; }
-                run += hist[b];
+                if (!found && run + hv[j] >= (uint32_t)keep_eff) {
+                    sh_bin = kFastBins - 1 - (tid * bp + j);
+                    sh_above = run;
+                    found = true;
+                }
+                run += hv[j];
             }
         }
         __syncthreads();
@@ -213,23 +253,26 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
                 if (rank < need) sel[me] = 1;
             }
             __syncthreads();
-            // ordered compaction
+            // ordered compaction (the flags are read without conditions, all at once)
+            bool take[kFastItems];
+#pragma unroll
+            for (int i = 0; i < kFastItems; ++i) take[i] = sel[min(i0 + i, NT * kFastItems - 1)] != 0;
             uint32_t cnt = 0;
 #pragma unroll
-            for (int i = 0; i < kFastItems; ++i) cnt += bin[i] > tb || (bin[i] == tb && sel[i0 + i]);
+            for (int i = 0; i < kFastItems; ++i) {
+                take[i] = bin[i] > tb || (bin[i] == tb && take[i]);
+                cnt += take[i];
+            }
             uint32_t cincl = wave_incl_scan_u32(cnt, lane);
             if (lane == 63) red_cnt[wv] = cincl;
             __syncthreads();
             uint32_t pos = cincl - cnt;
             for (int w = 0; w < wv; ++w) pos += red_cnt[w];
-            const Problem pr = problem_of(a.ge, p);
 #pragma unroll
             for (int i = 0; i < kFastItems; ++i)
-                if (bin[i] > tb || (bin[i] == tb && sel[i0 + i]))
-                    view.put(pos++, slot_start(pr, a.parent_starts, a.n_parent, a.ratio_log2, a.chunk, p, i0 + i));
+                if (take[i]) view.put(pos++, start_of[i]);
         } else {
             // heavy ties: exact radix select over the keys in LDS
-            const Problem pr = problem_of(a.ge, p);
             block_select_largest<NT>(
                 n, keep_eff, [&](int i) -> uint32_t { return keys[i]; },
                 [&](uint32_t rank, int i) {
