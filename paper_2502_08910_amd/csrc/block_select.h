@@ -19,15 +19,7 @@ struct SelectScratch {
     uint32_t prefix, remaining;
 };
 
-__device__ inline uint32_t wave_incl_scan_u32(uint32_t v, int lane)
-{
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(v, d, 64);
-        if (lane >= d) v += o;
-    }
-    return v;
-}
+__device__ inline uint32_t wave_incl_scan_u32(uint32_t v, int lane) { return wave_scan_u32(v, lane); }
 
 // All NT threads of the workgroup must call this with the same n, keep
 // (1 <= keep <= n).  key_at(i) returns the key of index i; emit(rank, i) is

@@ -338,6 +338,56 @@ __device__ inline float max_over_rows(float x)
     return fmaxf(__uint_as_float(s[0]), __uint_as_float(s[1]));
 }
 
+// Reductions and an inclusive scan over the 64 lanes of a wave that stay in the vector registers:
+// four DPP steps inside each 16-lane row, then the two row swaps above (reductions) or the three
+// row totals read as scalars (scan).  The shuffle-based forms go through the LDS crossbar once per
+// step, six dependent steps of ~100 cycles each.
+template <int CTRL>
+__device__ inline uint32_t dpp_u32(uint32_t v)      // lanes without a source lane read 0
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+template <class Op>
+__device__ inline uint32_t wave_reduce_bits(uint32_t v, Op op)      // op: commutative and associative on the bit patterns
+{
+    v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true));     // quad_perm [1,0,3,2]
+    v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true));     // quad_perm [2,3,0,1]
+    v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true));    // row_half_mirror
+    v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, true));    // row_mirror
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = op(r[0], r[1]);
+    const auto q = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return op(q[0], q[1]);
+}
+__device__ inline float wave_max_f32(float x)
+{
+    return __uint_as_float(wave_reduce_bits(__float_as_uint(x), [](uint32_t a, uint32_t b) {
+        return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b)));
+    }));
+}
+__device__ inline float wave_min_f32(float x)
+{
+    return __uint_as_float(wave_reduce_bits(__float_as_uint(x), [](uint32_t a, uint32_t b) {
+        return __float_as_uint(fminf(__uint_as_float(a), __uint_as_float(b)));
+    }));
+}
+__device__ inline uint32_t wave_sum_u32(uint32_t x)
+{
+    return wave_reduce_bits(x, [](uint32_t a, uint32_t b) { return a + b; });
+}
+// inclusive prefix sum over the wave's lanes
+__device__ inline uint32_t wave_scan_u32(uint32_t v, int lane)
+{
+    v += dpp_u32<0x111>(v);      // row_shr:1
+    v += dpp_u32<0x112>(v);      // row_shr:2
+    v += dpp_u32<0x114>(v);      // row_shr:4
+    v += dpp_u32<0x118>(v);      // row_shr:8
+    const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
+    const uint32_t t1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+    const uint32_t t2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47);
+    return v + (lane >= 16 ? t0 : 0u) + (lane >= 32 ? t1 : 0u) + (lane >= 48 ? t2 : 0u);
+}
+
 __device__ inline int ilog2(int x) { return 31 - __builtin_clz(x); }
 
 // 16-byte row fragment load for lane l16 of a row group

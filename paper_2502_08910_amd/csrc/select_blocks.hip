@@ -178,12 +178,9 @@ __global__ __launch_bounds__(NT) void select_blocks_fast_kernel(const SelectArgs
         if (in) keys[idx] = order_key(v[i]);
         if (v[i] > -INFINITY) { mn = fminf(mn, v[i]); mx = fmaxf(mx, v[i]); ++valid; }
     }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        mn = fminf(mn, __shfl_xor(mn, d, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, d, 64));
-        valid += __shfl_xor(valid, d, 64);
-    }
+    mn = wave_min_f32(mn);
+    mx = wave_max_f32(mx);
+    valid = wave_sum_u32(valid);
     if (lane == 0) { red_min[wv] = mn; red_max[wv] = mx; red_cnt[wv] = valid; }
     for (int i = tid; i < kFastBins; i += NT) hist[i] = 0;
     for (int i = tid; i < NT * kFastItems / 4; i += NT) reinterpret_cast<uint32_t *>(sel)[i] = 0;

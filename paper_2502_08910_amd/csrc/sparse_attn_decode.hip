@@ -261,21 +261,35 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
         }
     }
 
-    // merge the 4 groups of each wave in registers (lanes l, l^16, l^32, l^48 hold the same dims)
+    // merge the 4 groups of each wave in registers (lanes l, l^16, l^32, l^48 hold the same dims): a
+    // row swap hands every lane its own and its partner's value (which of the two is which differs
+    // between the partners; the merge is symmetric in them, so both compute the same bits)
+    auto both = [](float x, int d, float &a, float &b) {
+        const unsigned u = __float_as_uint(x);
+        if (d == 16) {
+            const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+            a = __uint_as_float(r[0]); b = __uint_as_float(r[1]);
+        } else {
+            const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+            a = __uint_as_float(r[0]); b = __uint_as_float(r[1]);
+        }
+    };
 #pragma unroll
     for (int d = 16; d <= 32; d <<= 1) {
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-            const float mo = __shfl_xor(m[h], d, 64);
-            const float lo = __shfl_xor(l[h], d, 64);
-            const float mn = fmaxf(m[h], mo);
-            const float wa = __builtin_amdgcn_exp2f(m[h] - mn), wb = __builtin_amdgcn_exp2f(mo - mn);
-            l[h] = l[h] * wa + lo * wb;
+            float ma, mb, la, lb;
+            both(m[h], d, ma, mb);
+            both(l[h], d, la, lb);
+            const float mn = fmaxf(ma, mb);
+            const float wa = __builtin_amdgcn_exp2f(ma - mn), wb = __builtin_amdgcn_exp2f(mb - mn);
+            l[h] = la * wa + lb * wb;
             m[h] = mn;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const float ao = __shfl_xor(acc[h][i], d, 64);
-                acc[h][i] = acc[h][i] * wa + ao * wb;
+                float xa, xb;
+                both(acc[h][i], d, xa, xb);
+                acc[h][i] = xa * wa + xb * wb;
             }
         }
     }
