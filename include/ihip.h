@@ -415,7 +415,9 @@ int32_t ihip_refresh_due(int32_t n_stages, const int32_t *n_refresh, int64_t ste
  * IHIP_ERR_WORKSPACE and enqueues nothing; the batch-8, 1M-token plan with
  * four stages needs about 4 MiB.  Every call on a GPU shares that GPU's array
  * (nothing in it has to survive or be cleared between calls): calls that
- * overlap on one GPU, on different streams or threads, race.
+ * overlap on one GPU, on different streams or threads, race.  The GPU the
+ * stream belongs to must be the calling thread's current device (the array
+ * of that device is the one used).
  */
 #define IHIP_STATIC_SCRATCH_BYTES (8u << 20)
 int32_t ihip_decode_layer_static(const ihip_shape *shape, ihip_tensor q, ihip_tensor k, ihip_tensor v,
