@@ -70,7 +70,7 @@ __device__ inline void rotate_operand_split(const bf16x8 x, const float *cos4, c
 // trip through LDS); everything after that is the bf16 kernel.  The chunk score is multiplied by the
 // tensor's scale at the end.  K strides count 2-byte units.
 template <int MT, int NT, int G, bool WIDE, int ROPE, bool PAGED, int PARTS = 1, bool KV8 = false>
-__global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PARTS > 1)) ? 2 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
+__global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PARTS > 1)) ? 2 : (PARTS == 1) ? 4 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
                                                                             const RopeView rope)
 {
     static_assert(NT == 2, "the shared first phase assumes two 16-chunk tiles per wave");
