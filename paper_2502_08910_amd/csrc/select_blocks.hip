@@ -105,16 +105,23 @@ int32_t launch_select_blocks(const ihip_shape &s, const float *scores, int max_c
     const int P = s.B * (all_heads ? 1 : s.Hkv) * (s.Tq / s.b_q);      // workgroups
     if (P == 0 || keep == 0) return IHIP_OK;
     KernelTimer timer(stage_name(kNameSelect, parent_starts == nullptr, chunk), st);
-    if (max_chunks <= 256 * 4)
-        hipLaunchKernelGGL((select_blocks_fast_kernel<256, 4>), dim3(P), dim3(256), 0, st, a);
-    else if (max_chunks <= 256 * 8)
-        hipLaunchKernelGGL((select_blocks_fast_kernel<256, 8>), dim3(P), dim3(256), 0, st, a);
-    else if (max_chunks <= 256 * kFastItems)
-        hipLaunchKernelGGL((select_blocks_fast_kernel<256, kFastItems>), dim3(P), dim3(256), 0, st, a);
-    else if (max_chunks <= 512 * kFastItems)
-        hipLaunchKernelGGL((select_blocks_fast_kernel<512, kFastItems>), dim3(P), dim3(512), 0, st, a);
-    else if (max_chunks <= 1024 * kFastItems)
-        hipLaunchKernelGGL((select_blocks_fast_kernel<1024, kFastItems>), dim3(P), dim3(1024), 0, st, a);
+    // Workgroup shape.  A few problems (at most one workgroup per CU, all running at once): the
+    // kernel is a chain of latencies, and 4 slots per thread in as many threads as that takes is
+    // the shortest (cfg3's 4,092 first-stage slots: 1024 x 4 9.0 us, 512 x 8 10.2, 256 x 16 11.3).
+    // Many problems (chunked prefill: one per query block): the workgroups queue for the CUs, and
+    // the fewest threads that hold the slots win (cfg4's 4,143 slots: 512 threads 13.6 us, 1024
+    // threads 16.4).
+#define IHIP_SEL(NTV, ITV) hipLaunchKernelGGL((select_blocks_fast_kernel<NTV, ITV>), dim3(P), dim3(NTV), 0, st, a)
+    const bool few = P <= 256;
+    if (max_chunks <= 256 * 4) IHIP_SEL(256, 4);
+    else if (few && max_chunks <= 512 * 4) IHIP_SEL(512, 4);
+    else if (few && max_chunks <= 1024 * 4) IHIP_SEL(1024, 4);
+    else if (few && max_chunks <= 1024 * 8) IHIP_SEL(1024, 8);
+    else if (max_chunks <= 256 * 8) IHIP_SEL(256, 8);
+    else if (max_chunks <= 256 * kFastItems) IHIP_SEL(256, kFastItems);
+    else if (max_chunks <= 512 * kFastItems) IHIP_SEL(512, kFastItems);
+    else if (max_chunks <= 1024 * kFastItems) IHIP_SEL(1024, kFastItems);
+#undef IHIP_SEL
     else
         hipLaunchKernelGGL(select_blocks_kernel, dim3(P), dim3(kSelThreads), 0, st, a);
     return check_launch("select_blocks");
