@@ -45,10 +45,10 @@ N_QUERY_SETS = 32
 # has no current summary reports traffic null.
 TRAFFIC_SOURCE = "profiles/decode_cfg3_and_prefill_cfg4_kernel_trace_and_hbm_counters.txt"
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781765.1 * 2.0 + 1225.9) * 1024.0,
-    ("cfg4-prefill-4k-on-256k", "prune_prefill.first.l64"): (793459.7 * 2.0 + 10537.9) * 1024.0,
-    ("cfg4-prefill-4k-on-256k", "prune_prefill.l16"): (486169.0 * 2.0 + 2048.0) * 1024.0,
-    ("cfg4-prefill-4k-on-256k", "attn_prefill"): (636745.3 * 2.0 + 32769.2) * 1024.0,
+    ("cfg3-decode-1m-b8", "prune_decode.first.l256"): (781758.3 * 2.0 + 1225.5) * 1024.0,
+    ("cfg4-prefill-4k-on-256k", "prune_prefill.first.l64"): (765662.2 * 2.0 + 10655.5) * 1024.0,
+    ("cfg4-prefill-4k-on-256k", "prune_prefill.l16"): (469639.2 * 2.0 + 2048.0) * 1024.0,
+    ("cfg4-prefill-4k-on-256k", "attn_prefill"): (636708.9 * 2.0 + 32769.9) * 1024.0,
 }
 
 

@@ -203,26 +203,22 @@ def test_strided_kv_layout(ihip, orc):
     assert worst <= 2e-2
 
 
-@pytest.mark.parametrize("n,keep,ties", [(1, 1, False), (110, 64, False), (257, 64, True), (1000, 1000, True),
-                                         (50, 80, True), (4092, 256, False), (4092, 256, True),
-                                         (4143, 256, False), (6000, 2500, True), (8192, 300, True),
-                                         (12288, 300, True), (20000, 777, True), (300, 1, True)])
-def test_select_blocks_alone(ihip, orc, n, keep, ties):
-    rng = np.random.default_rng(n + keep)
-    P, chunk, n_sink, n_stream = 3, 4, 8, 16
+def select_case(ihip, orc, P, n, keep, ties):
+    rng = np.random.default_rng(n + keep + P)
+    chunk, n_sink, n_stream = 4, 8, 16
     s = rng.standard_normal((P, n)).astype(np.float32)
     if ties:
         s = np.round(s * 2) / 2
         s[:, ::7] = -0.0
         s[:, 3::7] = 0.0
-    n_valid = [n, max(1, n - 5), max(1, n // 2)]
+    n_valid = [(n, max(1, n - 5), max(1, n // 2))[p % 3] for p in range(P)]
     T = n_sink + n * chunk + n_stream
     seq = []
     for p in range(P):
         s[p, n_valid[p]:] = -np.inf
         seq.append(n_sink + n_valid[p] * chunk - (1 if n_valid[p] > 1 else 0) + n_stream)   # last chunk ragged
     q = torch.zeros((P, 1, 1, 128), dtype=torch.bfloat16).cuda()
-    k = torch.zeros((P, 1, T, 128), dtype=torch.bfloat16).cuda()
+    k = torch.zeros((1, 1, T, 128), dtype=torch.bfloat16).cuda().expand(P, 1, T, 128)      # never read
     L = ihip.Layer(q, k, torch.tensor(seq, dtype=torch.int32).cuda(), 1, n_sink, n_stream)
     got = L.select_blocks(torch.from_numpy(s).cuda(), chunk, keep).cpu().numpy()
     lib = orc.lib()
@@ -233,6 +229,25 @@ def test_select_blocks_alone(ihip, orc, n, keep, ties):
         want = n_sink + ids[:cnt].astype(np.int64) * chunk
         assert np.array_equal(got[p, :cnt], want), p
         assert (got[p, cnt:] == -1).all()
+
+
+@pytest.mark.parametrize("n,keep,ties", [(1, 1, False), (110, 64, False), (257, 64, True), (1000, 1000, True),
+                                         (50, 80, True), (1500, 300, False), (2048, 512, True),
+                                         (4092, 256, False), (4092, 256, True),
+                                         (4143, 256, False), (6000, 2500, True), (8192, 300, True),
+                                         (12288, 300, True), (20000, 777, True), (300, 1, True)])
+def test_select_blocks_alone(ihip, orc, n, keep, ties):
+    """Three problems: every workgroup shape of the selection that few problems get (4 slots per thread in
+    256, 512 or 1024 threads, then 8 and 16 in 1024), the radix fallback beyond, heavy ties."""
+    select_case(ihip, orc, 3, n, keep, ties)
+
+
+@pytest.mark.parametrize("n,keep,ties", [(900, 100, False), (1500, 300, True), (3000, 256, False), (6000, 700, True),
+                                         (12000, 300, False), (20000, 500, True)])
+def test_select_blocks_many_problems(ihip, orc, n, keep, ties):
+    """More problems than CUs: the smallest workgroup that holds the slots (256 threads with 4, 8 or 16
+    slots each, 512 and 1024 threads with 16), and the radix select beyond."""
+    select_case(ihip, orc, 260, n, keep, ties)
 
 
 def test_decode_layer_under_graph_capture(ihip, orc):
