@@ -331,39 +331,54 @@ __global__ __launch_bounds__(kAttnThreads) void attn_decode_split_kernel(const A
     }
 }
 
-// merge the splits: one workgroup of 128 threads per (problem, head)
+// merge the splits: one workgroup of 128 threads per (problem, head), a thread per dim.  The partial
+// results of the first 16 splits (all of them in the usual shapes) are requested at once, before
+// anything is computed, and every thread takes the maximum over the splits itself: one trip to
+// memory and no barrier, where a reduction of the maxima first and the sums after it made two
+// dependent trips.  The sums run over the splits in order, so the result does not depend on this.
+constexpr int kMergeAhead = 16;
 __global__ __launch_bounds__(kD) void attn_decode_merge_kernel(const AttnDecodeArgs a)
 {
     const int G = a.ge.G;
     const int p = blockIdx.x / G, h = blockIdx.x % G;
     const int c = threadIdx.x;
-    const Problem pr = problem_of(a.ge, p);
+    const int b = p / a.ge.Hkv, g = p % a.ge.Hkv;            // decode: one problem per (sequence, KV head)
     const int64_t pbase = (int64_t)p * a.n_splits * G;
     const float2 *ml = reinterpret_cast<const float2 *>(a.part_ml);
-    // running maximum over the splits: strided over the threads, then reduced
-    __shared__ float sh_max[kD / 64];
-    float M = kNegBig;
-    for (int s = c; s < a.n_splits; s += kD) M = fmaxf(M, ml[pbase + (int64_t)s * G + h].x);
+    float2 mlv[kMergeAhead];
+    float av[kMergeAhead];
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d, 64));
-    if ((c & 63) == 0) sh_max[c >> 6] = M;
-    __syncthreads();
-    M = fmaxf(sh_max[0], sh_max[1]);
-    // every thread walks all splits for its own dim; the loads of a step do not depend on the
-    // previous one, so unrolling keeps several in flight
+    for (int s = 0; s < kMergeAhead; ++s) {
+        const int64_t r = pbase + (int64_t)min(s, a.n_splits - 1) * G + h;      // clamped: ignored beyond the last split
+        mlv[s] = ml[r];
+        av[s] = a.part_acc[r * kD + c];
+    }
+    float M = kNegBig;
+#pragma unroll
+    for (int s = 0; s < kMergeAhead; ++s)
+        if (s < a.n_splits) M = fmaxf(M, mlv[s].x);
+    for (int s = kMergeAhead; s < a.n_splits; ++s) M = fmaxf(M, ml[pbase + (int64_t)s * G + h].x);
     float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMergeAhead; ++s) {
+        if (s < a.n_splits) {
+            const float w = __builtin_amdgcn_exp2f(mlv[s].x - M);
+            L = fmaf(w, mlv[s].y, L);
+            A = fmaf(w, av[s], A);
+        }
+    }
 #pragma unroll 8
-    for (int s = 0; s < a.n_splits; ++s) {
+    for (int s = kMergeAhead; s < a.n_splits; ++s) {
         const int64_t r = pbase + (int64_t)s * G + h;
         const float2 x = ml[r];
         const float w = __builtin_amdgcn_exp2f(x.x - M);
         L = fmaf(w, x.y, L);
         A = fmaf(w, a.part_acc[r * kD + c], A);
     }
-    const int hq = pr.g * G + h;
-    a.out[((int64_t)pr.b * a.ge.Hq + hq) * kD + c] = (uint16_t)f32_to_bf16_bits(A / L * a.v_scale);
+    const int hq = g * G + h;
+    a.out[((int64_t)b * a.ge.Hq + hq) * kD + c] = (uint16_t)f32_to_bf16_bits(A / L * a.v_scale);
     if (a.out_lse != nullptr && c == 0)
-        a.out_lse[(int64_t)pr.b * a.ge.Hq + hq] = (M + log2f(L)) * 0.69314718055994530942f;
+        a.out_lse[(int64_t)b * a.ge.Hq + hq] = (M + log2f(L)) * 0.69314718055994530942f;
 }
 
 // Splits of the slot list: as many workgroups as the chip holds at once (4 workgroups of 4 waves
