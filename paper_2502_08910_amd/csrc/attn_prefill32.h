@@ -33,27 +33,30 @@
 //  * The position of every key slot is computed once into LDS, so the steady
 //    state has no dependent global loads.  Empty slots fetch row 0 (finite
 //    data) and are masked in the scores.
-// Four LDS stages: the rows of tile t+3 are requested at the start of period
-// t, tile t+2 must have landed at the barrier that ends it.  K(u) is read in
-// period u-1 (and before the loop for u = 0), V(u) in period u, so the stage of
-// tile t-1 is free when period t begins and takes tile t+3.  The loop is
-// unrolled by the four stages.
+// Three LDS stages: the rows of tile t+2 are requested at the start of period
+// t and must have landed at the barrier that ends it.  K(u) is read in period
+// u-1 (and before the loop for u = 0), V(u) in period u, so the stage of tile
+// t-1 is free when period t begins and takes tile t+2.  The loop is unrolled
+// by the three stages.  (A fourth stage, with requests a period earlier, made
+// no difference in time -- the other waves of the CU cover a period -- and its
+// 16 KB decide how many workgroups of four waves share a CU: with 5,280 key
+// slots two instead of one, 484 against 604 us on the shape measured.)
 //
 // ROPE (streaming-style dynamic RoPE, Sec. 4 "Dynamic RoPE for OOL
 // generalization"): the queries are rotated once, to the id of their last key.
 // A K tile is rotated in place in LDS, each thread one 16-byte piece, in the
-// period between its landing and its first read, which takes a fifth stage:
-// tile t+4 is requested at the start of period t, tile t+3 must have landed at
-// its end, K(t+2) is rotated during it (with table pieces fetched a period
+// period between its landing and its first read, which takes a fourth stage:
+// tile t+3 is requested at the start of period t and must have landed at its
+// end, K(t+2) is rotated during it (with table pieces fetched a period
 // earlier) and read in period t+1.  Rotated operands are rounded to bf16.
 //
 // KV8 (K and V rows are 128 bytes of E4M3): the direct loads bring the raw rows (16 bytes per
 // lane: 8 lanes a row, 8 rows an instruction, 8 instructions a tile) into a ring of three raw
 // stages; the tile is widened to bf16 (exact) into one of three bf16 stages, every thread 8 bytes
 // of K and 8 of V, in the period the RoPE variant uses for its rotation (and rotated on the way
-// with ROPE), in the swizzled layout the reads below expect.  Same schedule as ROPE: tile t+4 is
-// requested at the start of period t, tile t+3 must have landed at its end, tile t+2 is widened
-// during it, K(t+1) and V(t) are read.  The K scale is folded into the softmax scale on the host,
+// with ROPE), in the swizzled layout the reads below expect.  The raw ring puts requests a period
+// further ahead than ROPE does: tile t+4 is requested at the start of period t, tile t+3 must have
+// landed at its end, tile t+2 is widened during it, K(t+1) and V(t) are read.  The K scale is folded into the softmax scale on the host,
 // the V scale into the final normalisation.
 #pragma once
 
@@ -66,7 +69,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kPfStagesPlain = 4, kPfStagesRope = 5, kPfStagesFp8 = 3;
+constexpr int kPfStagesPlain = 3, kPfStagesRope = 4, kPfStagesFp8 = 3;
 constexpr int kPfRawStages = 3;                     // E4M3: raw stages of kPfTileEl 2-byte units (K rows, then V rows)
 constexpr int kPfTileEl = kPfTile * kD;            // elements of one K (or V) tile: 32 rows of 256 bytes
 constexpr int kPfStageEl = 2 * kPfTileEl;          // K tile, then V tile
