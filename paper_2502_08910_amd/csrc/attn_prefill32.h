@@ -69,10 +69,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kPfStagesPlain = 3, kPfStagesRope = 4, kPfStagesFp8 = 3;
-constexpr int kPfRawStages = 3;                     // E4M3: raw stages of kPfTileEl 2-byte units (K rows, then V rows)
-constexpr int kPfTileEl = kPfTile * kD;            // elements of one K (or V) tile: 32 rows of 256 bytes
-constexpr int kPfStageEl = 2 * kPfTileEl;          // K tile, then V tile
 constexpr float kPfMaxSum = 1024.0f;                // row sum of a tile above which the softmax reference moves
 
 // NQ = b_q / 32 query tiles, G query heads per workgroup: NQ*G waves.  A group of more heads than

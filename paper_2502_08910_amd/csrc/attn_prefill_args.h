@@ -80,11 +80,29 @@ __device__ inline int pf_slot_to_pos(const AttnPrefillArgs &a, const Problem &pr
     return pos < pr.E ? pos : -1;
 }
 
-constexpr int kPf32MaxLds = 160 * 1024;  // LDS per workgroup the 32x32 kernel may ask for
-constexpr int kPf32MaxSlots = 24320;    // key slots whose positions (and per-tile flags) the 32x32 kernel keeps in LDS
-constexpr int kPf32MaxSlotsRope = 20224; // ... with streaming-style RoPE (one more K/V stage)
-constexpr int kPf32MaxSlotsPaged = 12160;     // ... with paged K/V (a page id per slot as well)
-constexpr int kPf32MaxSlotsRopePaged = 10176; // ... with both
+// LDS of the 32x32 kernel: K/V stages of 16 KB (32 rows of 256 bytes each), for E4M3 also raw stages of
+// 8 KB; then an int per key slot (two with paged K/V: the page id) and a flag per tile.  The most key
+// slots a kernel can take follow from the 160 KB of a CU (64 bytes are left for static variables).
+constexpr int kPfStagesPlain = 3, kPfStagesRope = 4, kPfStagesFp8 = 3;
+constexpr int kPfRawStages = 3;                     // E4M3: raw stages of one K or V tile's size
+constexpr int kPfTileEl = kPfTile * kD;             // elements of one K (or V) tile: 32 rows of 256 bytes
+constexpr int kPfStageEl = 2 * kPfTileEl;           // K tile, then V tile
+constexpr int kPf32MaxLds = 160 * 1024;             // LDS per workgroup the 32x32 kernel may ask for
+constexpr int pf32_max_slots(int stage_bytes, int ints_per_slot)
+{
+    // slots * 4 * ints_per_slot + slots / 32 <= room, slots a multiple of the tile
+    return (int)((int64_t)(kPf32MaxLds - 64 - stage_bytes) * kPfTile / (4 * ints_per_slot * kPfTile + 1)) / kPfTile * kPfTile;
+}
+constexpr int kPfStageBytes = kPfStageEl * 2, kPfRawBytes = kPfTileEl * 2;
+constexpr int kPfFp8StageBytes = kPfStagesFp8 * kPfStageBytes + kPfRawStages * kPfRawBytes;
+constexpr int kPf32MaxSlots = pf32_max_slots(kPfStagesPlain * kPfStageBytes, 1);            // 28,416
+constexpr int kPf32MaxSlotsRope = pf32_max_slots(kPfStagesRope * kPfStageBytes, 1);         // 24,352
+constexpr int kPf32MaxSlotsPaged = pf32_max_slots(kPfStagesPlain * kPfStageBytes, 2);       // 14,272: a page id per slot as well
+constexpr int kPf32MaxSlotsRopePaged = pf32_max_slots(kPfStagesRope * kPfStageBytes, 2);
+constexpr int kPf32MaxSlotsFp8 = pf32_max_slots(kPfFp8StageBytes, 1);                      // E4M3, with or without RoPE
+constexpr int kPf32MaxSlotsFp8Paged = pf32_max_slots(kPfFp8StageBytes, 2);
+static_assert(kPf32MaxSlots * 4 + kPf32MaxSlots / kPfTile + kPfStagesPlain * kPfStageBytes + 64 <= kPf32MaxLds, "LDS");
+static_assert(kPf32MaxSlotsFp8Paged * 8 + kPf32MaxSlotsFp8Paged / kPfTile + kPfFp8StageBytes + 64 <= kPf32MaxLds, "LDS");
 
 void launch_attn_prefill32(const AttnPrefillArgs &a, int P, int64_t max_seq_len, hipStream_t st);
 void launch_attn_prefill32_fp8(const AttnPrefillArgs &a, int P, hipStream_t st);   // E4M3 K and V

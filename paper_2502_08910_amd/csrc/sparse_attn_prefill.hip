@@ -319,8 +319,7 @@ int32_t launch_attn_prefill(const ihip_shape &s, const ihip_tensor &q, const ihi
     // the 32x32 kernel keeps every slot's position in LDS; longer key lists take the 16x16 one
     const int slot_limit = use_rope ? (paged ? kPf32MaxSlotsRopePaged : kPf32MaxSlotsRope)
                                     : (paged ? kPf32MaxSlotsPaged : kPf32MaxSlots);
-    if (fp8 && s.b_q >= 32 &&
-        s.n_sink + n_blocks * block + s.n_stream <= (paged ? kPf32MaxSlotsRopePaged : kPf32MaxSlotsRope)) {
+    if (fp8 && s.b_q >= 32 && s.n_sink + n_blocks * block + s.n_stream <= (paged ? kPf32MaxSlotsFp8Paged : kPf32MaxSlotsFp8)) {
         launch_attn_prefill32_fp8(a, P, st);
         return check_launch("sparse_attn_prefill");
     }

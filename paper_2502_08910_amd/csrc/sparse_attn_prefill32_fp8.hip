@@ -6,8 +6,7 @@
 namespace ihip {
 
 // K / V strides of `a` count 2-byte units; a.v_scale and the K scale (inside a.scale_log2e) are set.
-// The caller keeps n_sink + n_blocks * block + n_stream within the RoPE variants' slot limits (the
-// three bf16 and three raw stages, 72 KB, fit into the 80 KB that those limits leave for stages).
+// The caller keeps n_sink + n_blocks * block + n_stream within kPf32MaxSlotsFp8 (paged: ...Fp8Paged).
 void launch_attn_prefill32_fp8(const AttnPrefillArgs &a, int P, hipStream_t st)
 {
     const int NQ = a.ge.b_q / 32;

@@ -122,10 +122,11 @@ def test_gaussian_recall_and_output(ihip, orc, seed):
     assert worst <= 2e-2
 
 
-@pytest.mark.parametrize("prefix", [0, 100, 1000, 26000])
+@pytest.mark.parametrize("prefix", [0, 100, 1000, 26000, 27584, 30000])
 def test_keep_everything_is_dense_causal(ihip, orc, prefix):
     # prefix 0: prefill from scratch -- early blocks see only (part of) the sink, causally;
-    # prefix 26000: more key slots than the 32x32 kernel keeps in LDS -> the 16x16 kernel runs
+    # prefix 27584: 28,416 key slots, exactly what the 32x32 kernel can keep in LDS (26000: a little less);
+    # prefix 30000: more than that -> the 16x16 kernel runs
     keep = max(100, (prefix + 512) // 64 + 1)
     w = small(Tq=512, prefix=prefix, n_stream=128, stages=((64, keep), (16, 4 * keep)))
     q, k, v, sl, _ = configs.make_inputs(w, 5)

@@ -143,12 +143,13 @@ def test_fp8_with_rope_pages_and_pooling_bit_exact(ihip, orc, w, page, rope):
                     assert np.abs(got - ref).max() <= 2e-2, (pooling, b, g, m)
 
 
-@pytest.mark.parametrize("prefix,page", [(3000, 0), (21000, 0), (11000, 16)],
-                         ids=["32x32-kernel", "16x16-kernel", "16x16-kernel-paged"])
+@pytest.mark.parametrize("prefix,page", [(3000, 0), (21760, 0), (23000, 0), (10624, 16), (11000, 16)],
+                         ids=["32x32-kernel", "32x32-kernel-at-its-limit", "16x16-kernel", "32x32-kernel-paged-at-its-limit",
+                              "16x16-kernel-paged"])
 def test_keep_everything_is_dense_causal_on_dequantised_values(ihip, prefix, page):
-    # nothing pruned -> dense causal attention over scale * decoded bytes (torch, fp64).  The longer
-    # key lists exceed the slots the 32x32 kernel keeps in LDS (20,224; 10,176 with page ids), so
-    # the 16x16 kernel runs.
+    # nothing pruned -> dense causal attention over scale * decoded bytes (torch, fp64).  The 32x32
+    # kernel keeps up to 22,336 key slots in LDS (11,200 with page ids): prefixes 21760 / 10624 give
+    # exactly that many, the longer key lists go to the 16x16 kernel.
     keep = (prefix + 256) // 64 + 1
     w = small(Tq=256, prefix=prefix, n_stream=128, Hq=8, Hkv=2, stages=((64, keep), (16, 4 * keep)))
     q, k, v, sl, _ = configs.make_inputs(w, 5)

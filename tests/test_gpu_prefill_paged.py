@@ -120,11 +120,11 @@ def test_paged_prefill_with_rope_and_pooling_equals_contiguous(ihip, w):
     assert torch.equal(out, ref)
 
 
-@pytest.mark.parametrize("prefix", [11000, 13000])
+@pytest.mark.parametrize("prefix", [11000, 13440, 15000])
 def test_keep_everything_paged_is_dense_causal(ihip, prefix):
     # every chunk kept -> dense causal attention (torch, fp64), read through 16-token pages.
-    # prefix 11000: just under the key slots the 32x32 kernel keeps in LDS with page ids (12,160);
-    # prefix 13000: above them -> the 16x16 kernel runs.
+    # prefix 13440: exactly the key slots the 32x32 kernel keeps in LDS with page ids (14,272);
+    # prefix 15000: above them -> the 16x16 kernel runs.
     keep = (prefix + 512) // 64 + 1
     w = small(Tq=512, prefix=prefix, n_stream=128, stages=((64, keep), (16, 4 * keep)))
     q, k, v, sl, _ = configs.make_inputs(w, 5)

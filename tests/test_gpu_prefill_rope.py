@@ -227,13 +227,13 @@ def rotary(x, cos, sin, positions):
 
 
 @pytest.mark.parametrize("prefix,prune", [(0, None), (0, "chunk"), (100, "relative"), (100, "chunk"), (1000, None),
-                                          (1000, "chunk"), (19000, None), (21000, None)])
+                                          (1000, "chunk"), (19000, None), (23488, None), (23552, None)])
 def test_keep_everything_with_streaming_ids_is_rotary_attention(ihip, prefix, prune):
     # When every chunk is kept a query attends to all keys before it, so the streaming ids are the
     # positions themselves and the result is ordinary causal attention on rotary-embedded q and k,
     # computed here by torch in fp64 without the oracle.
-    # prefix 19000: just under the key slots the 32x32 kernel keeps in LDS with RoPE (20,224);
-    # prefix 21000: above them -> the 16x16 kernel runs.  prefix 0 / 100: prefill from scratch, early
+    # prefix 23488: 24,320 key slots, the most below what the 32x32 kernel keeps in LDS with RoPE (24,352);
+    # prefix 23552: one chunk more -> the 16x16 kernel runs.  prefix 0 / 100: prefill from scratch, early
     # query blocks have an empty middle range and see only part of the sink.  With everything kept the
     # pruning style cannot change the result; it is varied to run those kernels on the edge shapes.
     keep = (prefix + 512) // 64 + 1
