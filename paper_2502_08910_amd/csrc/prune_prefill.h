@@ -69,25 +69,47 @@ __device__ inline void rotate_operand_split(const bf16x8 x, const float *cos4, c
 // direct load would have put them (chunk-indexed RoPE: rotated on the way, which saves the round
 // trip through LDS); everything after that is the bf16 kernel.  The chunk score is multiplied by the
 // tensor's scale at the end.  K strides count 2-byte units.
-template <int MT, int NT, int G, bool WIDE, int ROPE, bool PAGED, int PARTS = 1, bool KV8 = false>
-__global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PARTS > 1)) ? 2 : (PARTS == 1) ? 4 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
+//
+// QS = 2: two waves per query head, each with half of the block's queries (relative-style RoPE with
+// 64-query blocks, whose four rotated operand sets of 64 queries leave room for one wave per SIMD
+// only; two waves of 32 queries fit a SIMD together).  The two walk the same searches on their own
+// copies of the candidate rows and exchange their maxima over the queries through LDS after every
+// scoring step, so that both take the same decisions.  The exchange is a handshake of the two
+// waves, not a workgroup barrier: a barrier per search level puts all waves of the workgroup in
+// step -- all wait for rows at once, then all multiply at once -- and the second wave per SIMD buys
+// nothing (3.86 ms on the first stage of cfg4 against 3.81 ms with one wave per SIMD).  Each wave
+// writes its maxima, then a turn counter (LDS keeps a wave's requests in order), and reads the
+// other's maxima once the other's counter has reached the same turn.  Both write before they wait
+// and both are resident (one workgroup), so the wait ends; it is bounded all the same.
+template <int MT, int NT, int G, bool WIDE, int ROPE, bool PAGED, int PARTS = 1, bool KV8 = false, int QS = 1>
+__global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PARTS > 1)) ? 2 : (PARTS == 1) ? 4 : 3) void prune_prefill_kernel(const PruneArgs a, const int iters,
                                                                             const RopeView rope)
 {
     static_assert(NT == 2, "the shared first phase assumes two 16-chunk tiles per wave");
     static_assert(!PAGED || WIDE, "paged pools are addressed with 64-bit offsets");
+    static_assert(QS == 1 || (QS == 2 && MT % 2 == 0), "one or two waves per head");
+    constexpr int NWV = G * QS;                      // waves of the workgroup
+    constexpr int MTW = MT / QS;                     // 16-query tiles of a wave
     constexpr int kTile = NT * 16 * kD;              // one tile: 32 rows of 256 bytes, no padding
-    constexpr bool kShare = G >= 2;                  // two tiles are needed for the shared phase
+    constexpr bool kShare = NWV >= 2;                // two tiles are needed for the shared phase
     __shared__ float sh_sigma[G][NT * 16];
     __shared__ float sh_best[kPrefillMaxIters][NT * 16];      // chunk scores over the head parts done so far
-    constexpr int kLo = ROPE == 2 ? G * kTile : 0;   // ROPE == 2: from a tile to the tile of its rests
-    __shared__ __attribute__((aligned(16))) uint16_t sh_rows[(ROPE == 2 ? 2 * G : G) * kTile];
+    // QS == 2: a wave's maxima over its queries, for the other wave of its head (two buffers: a wave
+    // may write its next values while the other still reads the last ones)
+    __shared__ float sh_pair[QS == 2 ? 2 : 1][QS == 2 ? NWV : 1][2 * NT][16];
+    __shared__ uint32_t sh_pair_turn[QS == 2 ? NWV : 1];      // exchanges a wave has written so far
+    constexpr int kLo = ROPE == 2 ? NWV * kTile : 0;  // ROPE == 2: from a tile to the tile of its rests
+    __shared__ __attribute__((aligned(16))) uint16_t sh_rows[(ROPE == 2 ? 2 * NWV : NWV) * kTile];
     // Workgroups are dealt to the 8 XCDs round-robin by linear id; let the KV head be the fastest
     // index, so that (with 8 KV heads) one XCD's L2 only ever holds one head's K rows and all
     // query blocks that share those rows run on that XCD at about the same time.
     const int p = ((blockIdx.x / a.ge.Hkv / a.ge.Mq) * a.ge.Hkv + blockIdx.x % a.ge.Hkv) * a.ge.Mq +
                   (blockIdx.x / a.ge.Hkv) % a.ge.Mq;
     const Problem pr = problem_of(a.ge, p);
-    const int lane = threadIdx.x & 63, hh = threadIdx.x >> 6;      // wave = query head of the group
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int hh = wv / QS, qs = wv % QS;             // the wave's query head of the group, and its share of the queries
+    const int qrow0 = qs * MTW * 16;                  // first query row of the block that is this wave's
+    if (QS == 2 && lane == 0) sh_pair_turn[wv] = 0;   // a workgroup barrier follows before the first exchange
     const int n = lane & 15, kq = lane >> 4;
     // G is the number of heads (waves) a pass works on; a group of G*PARTS heads (8, where 8 waves
     // of this many registers would leave room for one workgroup per CU only) is done in PARTS
@@ -171,35 +193,35 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
 
     // A operands: the block's queries, [MT tiles of 16 rows] x [4 steps of 32 dims], staged
     // through this wave's own tile, 32 rows at a time
-    uint16_t *tile = &sh_rows[hh * kTile];
+    uint16_t *tile = &sh_rows[wv * kTile];
     uint32_t dst_own[NT * 4];                        // this wave's tile, four rows at a time
 #pragma unroll
     for (int r = 0; r < NT * 4; ++r) dst_own[r] = lds_addr(tile + r * 4 * kD);
-    bf16x8 qa[MT][4];                                // relative RoPE: q_L
-    bf16x8 qaR[ROPE == 1 ? MT : 1][4];               // relative RoPE: q_R
-    bf16x8 qaLo[ROPE ? MT : 1][4];                   // RoPE: what rounding the rotated queries to bf16 dropped
-    bf16x8 qaRLo[ROPE == 1 ? MT : 1][4];
+    bf16x8 qa[MTW][4];                               // relative RoPE: q_L
+    bf16x8 qaR[ROPE == 1 ? MTW : 1][4];              // relative RoPE: q_R
+    bf16x8 qaLo[ROPE ? MTW : 1][4];                  // RoPE: what rounding the rotated queries to bf16 dropped
+    bf16x8 qaRLo[ROPE == 1 ? MTW : 1][4];
     int q_cap = 0;                                   // chunk-indexed RoPE: the largest query position
     if constexpr (ROPE == 2) {
         __shared__ int sh_n_chunk;
-        q_cap = stage_n_chunk(a, pr, p, 64 * G, &sh_n_chunk) - 1 + a.ge.n_stream;
+        q_cap = stage_n_chunk(a, pr, p, 64 * NWV, &sh_n_chunk) - 1 + a.ge.n_stream;
     }
     auto stage_queries = [&]() {
         const uint16_t *qb = a.q + pr.b * a.q_sb + (int64_t)h * a.q_sh + (int64_t)(pr.m * a.ge.b_q) * a.q_st;
 #pragma unroll
-        for (int m0 = 0; m0 < MT; m0 += 2) {
-            constexpr int kRows = MT >= 2 ? 32 : 16;
+        for (int m0 = 0; m0 < MTW; m0 += 2) {
+            constexpr int kRows = MTW >= 2 ? 32 : 16;
 #pragma unroll
             for (int r = 0; r < kRows / 4; ++r)
-                load4(qb, (off_t)a.q_st, dst_own[r], m0 * 16 + r * 4 + kq, (r & 3) * 4 + kq);
+                load4(qb, (off_t)a.q_st, dst_own[r], qrow0 + m0 * 16 + r * 4 + kq, (r & 3) * 4 + kq);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int mt = m0; mt < m0 + 2 && mt < MT; ++mt)
+            for (int mt = m0; mt < m0 + 2 && mt < MTW; ++mt)
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
                     qa[mt][ks] = operand(tile, (mt - m0) * 16, ks);
                     if constexpr (ROPE == 2) {
-                        const int qpos = min(pr.E - a.ge.b_q + mt * 16 + n, q_cap);
+                        const int qpos = min(pr.E - a.ge.b_q + qrow0 + mt * 16 + n, q_cap);
                         const int64_t at = (int64_t)qpos * (kD / 2) + ((ks << 2) + kq) * 4;
                         rotate_operand_split(qa[mt][ks], rope.cos + at, rope.sin + at, qa[mt][ks], qaLo[mt][ks]);
                     }
@@ -240,7 +262,7 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
             }
             float best = -INFINITY, bestR = -INFINITY;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
+            for (int mt = 0; mt < MTW; ++mt) {
                 f32x4 c = {0.f, 0.f, 0.f, 0.f};
                 if constexpr (ROPE != 0) {           // the small terms first
 #pragma unroll
@@ -270,6 +292,32 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
             sig[t] = max_over_rows(best);
             if constexpr (ROPE == 1) {
                 sigR[t] = max_over_rows(bestR);
+            }
+        }
+    };
+    // QS == 2: the maxima of mfma_scores over all the block's queries, from the two waves of a head
+    uint32_t pair_turn = 0;
+    auto pair_max = [&](float (&sig)[NT], float (&sigR)[NT]) {
+        if constexpr (QS == 2) {
+            float (*mine)[16] = sh_pair[pair_turn & 1][wv];
+            const float (*theirs)[16] = sh_pair[pair_turn & 1][wv ^ 1];
+            if (kq == 0) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    mine[t][n] = sig[t];
+                    if constexpr (ROPE == 1) mine[NT + t][n] = sigR[t];
+                }
+            }
+            ++pair_turn;
+            if (lane == 0) __hip_atomic_store(&sh_pair_turn[wv], pair_turn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            int budget = 1 << 16;             // a wait is a few dozen turns of this loop
+            while ((int32_t)(__hip_atomic_load(&sh_pair_turn[wv ^ 1], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) -
+                             pair_turn) < 0 && --budget > 0)
+                __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                sig[t] = fmaxf(sig[t], theirs[t][n]);
+                if constexpr (ROPE == 1) sigR[t] = fmaxf(sigR[t], theirs[NT + t][n]);
             }
         }
     };
@@ -322,6 +370,7 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
             // the wave reads back what its other lanes stored: LDS serves a wave's requests in order
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             mfma_scores(tile, sig, sigR);
+            pair_max(sig, sigR);
             return;
         }
         if constexpr (PAGED) {
@@ -348,12 +397,13 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
             for (int r = 0; r < NT * 4; ++r) rotate_own(tile + r * 4 * kD, r);
         }
         mfma_scores(tile, sig, sigR);
+        pair_max(sig, sigR);
     };
 
     // destinations of this wave's share of the loads of the shared first phase
-    uint32_t dst_shared[kShare ? 16 / G : 1];
+    uint32_t dst_shared[kShare ? 16 / NWV : 1];
 #pragma unroll
-    for (int i = 0; i < (kShare ? 16 / G : 1); ++i) dst_shared[i] = lds_addr(&sh_rows[(hh * (16 / G) + i) % (G * 8) * 4 * kD]);
+    for (int i = 0; i < (kShare ? 16 / NWV : 1); ++i) dst_shared[i] = lds_addr(&sh_rows[(wv * (16 / NWV) + i) % (NWV * 8) * 4 * kD]);
     for (int part = 0; part < parts; ++part) {
     if constexpr (PARTS > 1) {
         h = pr.g * (G * PARTS) + part * G + hh;
@@ -391,12 +441,12 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
             // the group: the waves fetch them together, once (tile 0: first keys, tile 1: first
             // keys of the right halves; 16 four-row loads dealt evenly to the G waves), and each
             // wave scores both tiles against its own queries.
-            constexpr int kPerWave = 16 / G;
+            constexpr int kPerWave = 16 / NWV;
             int cand[kPerWave];
             int64_t cand_at[PAGED ? kPerWave : 1];
 #pragma unroll
             for (int i = 0; i < kPerWave; ++i) {
-                const int ld = hh * kPerWave + i;                    // wave-uniform
+                const int ld = wv * kPerWave + i;                    // wave-uniform
                 const int set = ld >> 3, r = ld & 7;
                 const int st_ = (r >> 2) ? start[1] : start[0], ln_ = (r >> 2) ? len[1] : len[0];
                 const int c = set == 0 ? st_ : (half >= 1 && half < ln_ ? st_ + half : -1);
@@ -407,13 +457,13 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
                 uint2 raw[kPerWave];
 #pragma unroll
                 for (int i = 0; i < kPerWave; ++i) {
-                    const int r = (hh * kPerWave + i) & 7;
+                    const int r = (wv * kPerWave + i) & 7;
                     if constexpr (PAGED) raw[i] = fetch8_at(kb, cand_at[i], (r & 3) * 4 + kq);
                     else raw[i] = fetch8(kb, k_st, cand[i], (r & 3) * 4 + kq);
                 }
 #pragma unroll
                 for (int i = 0; i < kPerWave; ++i) {
-                    const int ld = hh * kPerWave + i;
+                    const int ld = wv * kPerWave + i;
                     uint4 piece = fp8x8_to_bf16x8(raw[i]);
                     if constexpr (ROPE == 2) {
                         const int64_t at = table_at(jt, ld & 7);
@@ -427,7 +477,7 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
             } else {
 #pragma unroll
             for (int i = 0; i < kPerWave; ++i) {
-                const int r = (hh * kPerWave + i) & 7;
+                const int r = (wv * kPerWave + i) & 7;
                 if constexpr (PAGED) load4_at(kb, cand_at[i], dst_shared[i], (r & 3) * 4 + kq);
                 else load4(kb, k_st, dst_shared[i], cand[i], (r & 3) * 4 + kq);
             }
@@ -438,7 +488,7 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
                 for (int i = 0; i < kPerWave; ++i) {
                     // which of the 16 loads this is depends on the wave: the piece is fetched again
                     // rather than picked from the register array with a run-time index
-                    const int ld = hh * kPerWave + i;
+                    const int ld = wv * kPerWave + i;
                     const int64_t at = table_at(jt, ld & 7);
                     rotate_piece(&sh_rows[ld * 4 * kD], *reinterpret_cast<const float4 *>(rope.cos + at),
                                  *reinterpret_cast<const float4 *>(rope.sin + at));
@@ -447,7 +497,9 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
             __syncthreads();
             float l0r[NT];
             mfma_scores(&sh_rows[0], sigma, l0r);
+            pair_max(sigma, l0r);
             mfma_scores(&sh_rows[kTile], s, sR);
+            pair_max(s, sR);
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const bool has_right = half >= 1 && half < len[t];
@@ -486,7 +538,7 @@ __global__ __launch_bounds__(64 * G, (ROPE && MT == 4) ? 1 : (ROPE || (KV8 && PA
         for (int t = 0; t < NT; ++t) {
             const int j = jt + t * 16 + n;
             if (kq == 0) sh_sigma[hh][t * 16 + n] = sigma[t];
-            if (a.out_rep != nullptr && kq == 0 && j < a.max_chunks) {
+            if (a.out_rep != nullptr && kq == 0 && qs == 0 && j < a.max_chunks) {
                 const int64_t row = ((int64_t)(pr.b * a.ge.Hq + h) * a.ge.Mq + pr.m);
                 a.out_rep[row * a.max_chunks + j] = valid[t] ? start[t] + off[t] : -1;
             }
@@ -523,16 +575,18 @@ static void launch_prefill_w(const PruneArgs &a, int P, const RopeView &rope, hi
     const int per_wg = NT * 16 * iters;
     dim3 grid(P, (a.max_chunks + per_wg - 1) / per_wg);
     KernelTimer timer(stage_name(kNamePrunePrefill, a.parent_starts == nullptr, a.chunk), st);
+    // relative-style RoPE on 64-query blocks: two waves per head, 32 queries each
+    constexpr int QS = (ROPE == 1 && MT == 4) ? 2 : 1;
     switch (a.ge.G) {
-    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE, ROPE, PAGED, 1, KV8>), grid, dim3(64), 0, st, a, iters, rope); break;
-    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE, ROPE, PAGED, 1, KV8>), grid, dim3(128), 0, st, a, iters, rope); break;
-    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED, 1, KV8>), grid, dim3(256), 0, st, a, iters, rope); break;
+    case 1: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 1, WIDE, ROPE, PAGED, 1, KV8, QS>), grid, dim3(64 * QS), 0, st, a, iters, rope); break;
+    case 2: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 2, WIDE, ROPE, PAGED, 1, KV8, QS>), grid, dim3(128 * QS), 0, st, a, iters, rope); break;
+    case 4: hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED, 1, KV8, QS>), grid, dim3(256 * QS), 0, st, a, iters, rope); break;
     default:
         // 8 heads with 64-query blocks: 8 waves of ~160 registers fit a CU once only, two passes of 4
         // waves fit three times; with RoPE the query operands alone take more registers than 8 waves
         // leave each other
         if constexpr (MT == 4)
-            hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED, 2, KV8>), grid, dim3(256), 0, st, a, iters, rope);
+            hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 4, WIDE, ROPE, PAGED, 2, KV8, QS>), grid, dim3(256 * QS), 0, st, a, iters, rope);
         else
             hipLaunchKernelGGL((prune_prefill_kernel<MT, NT, 8, WIDE, ROPE, PAGED, 1, KV8>), grid, dim3(512), 0, st, a, iters, rope);
         break;
