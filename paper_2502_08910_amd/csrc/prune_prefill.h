@@ -310,7 +310,7 @@ __global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : 
             }
             ++pair_turn;
             if (lane == 0) __hip_atomic_store(&sh_pair_turn[wv], pair_turn, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-            int budget = 1 << 16;             // a wait is a few dozen turns of this loop
+            int budget = 1 << 18;             // a wait is a few dozen turns of this loop; the bound is ~10 ms
             while ((int32_t)(__hip_atomic_load(&sh_pair_turn[wv ^ 1], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) -
                              pair_turn) < 0 && --budget > 0)
                 __builtin_amdgcn_s_sleep(1);
