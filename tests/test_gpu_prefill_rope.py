@@ -134,9 +134,12 @@ def compare(w, o, stages, out, lse, exact, problems=None, score_tol=None, max_of
     small(b_q=16, Tq=64, Hq=4, Hkv=2, stages=((32, 8), (8, 16), (2, 40))),
     small(Hq=8, Hkv=8, Tq=128),                           # G = 1
     small(Hq=16, Hkv=2, Tq=64),                           # G = 8
-], ids=["llama", "ragged-b2", "bq32", "bq16-3stage", "g1", "g8"])
+    small(Hq=4, Hkv=2, Tq=128),                           # G = 2
+], ids=["llama", "ragged-b2", "bq32", "bq16-3stage", "g1", "g8", "g2"])
 @pytest.mark.parametrize("prune", ["relative", "chunk"])
 def test_quarter_turn_table_bit_exact(ihip, orc, w, prune):
+    # 64-query blocks with the relative style run two waves per head (every G here: 1, 2, 4 and 8 heads in
+    # two passes), which exchange their maxima; 32- and 16-query blocks and the chunk-indexed style one
     q, k, v, sl, _ = configs.make_inputs(w, 0, kind="int")
     if w.B == 2:
         sl = torch.tensor([w.T, w.T - 517], dtype=torch.int32)
