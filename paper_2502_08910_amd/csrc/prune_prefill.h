@@ -92,7 +92,7 @@ __global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : 
     constexpr int MTW = MT / QS;                     // 16-query tiles of a wave
     constexpr int kTile = NT * 16 * kD;              // one tile: 32 rows of 256 bytes, no padding
     constexpr bool kShare = NWV >= 2;                // two tiles are needed for the shared phase
-    __shared__ float sh_sigma[G][NT * 16];
+    __shared__ float sh_sigma[2][G][NT * 16];       // two buffers: a chunk group writes while the last one is still read
     __shared__ float sh_best[kPrefillMaxIters][NT * 16];      // chunk scores over the head parts done so far
     // QS == 2: a wave's maxima over its queries, for the other wave of its head (two buffers: a wave
     // may write its next values while the other still reads the last ones)
@@ -537,7 +537,7 @@ __global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : 
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int j = jt + t * 16 + n;
-            if (kq == 0) sh_sigma[hh][t * 16 + n] = sigma[t];
+            if (kq == 0) sh_sigma[it & 1][hh][t * 16 + n] = sigma[t];
             if (a.out_rep != nullptr && kq == 0 && qs == 0 && j < a.max_chunks) {
                 const int64_t row = ((int64_t)(pr.b * a.ge.Hq + h) * a.ge.Mq + pr.m);
                 a.out_rep[row * a.max_chunks + j] = valid[t] ? start[t] + off[t] : -1;
@@ -547,8 +547,8 @@ __global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : 
         if (threadIdx.x < NT * 16) {
             const int j = jt + threadIdx.x;
             if (j < a.max_chunks) {
-                float best = sh_sigma[0][threadIdx.x];
-                for (int g2 = 1; g2 < G; ++g2) best = fmaxf(best, sh_sigma[g2][threadIdx.x]);
+                float best = sh_sigma[it & 1][0][threadIdx.x];
+                for (int g2 = 1; g2 < G; ++g2) best = fmaxf(best, sh_sigma[it & 1][g2][threadIdx.x]);
                 if (part > 0) best = fmaxf(best, sh_best[it][threadIdx.x]);
                 if (part + 1 < parts) {
                     sh_best[it][threadIdx.x] = best;
@@ -559,7 +559,8 @@ __global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : 
                 }
             }
         }
-        __syncthreads();
+        // no barrier here: every wave has left its searches (the barrier above), the next chunk group
+        // writes the other sh_sigma buffer, and sh_best is per chunk group
     }
     }
 }
