@@ -152,6 +152,38 @@ def test_quarter_turn_table_bit_exact(ihip, orc, w, prune):
     assert torch.equal(fused, out)          # the one-enqueue layer call runs the same kernels
 
 
+@pytest.mark.parametrize("fp8", [False, True])
+def test_two_waves_per_head_give_the_same_result_every_time(ihip, fp8):
+    """Relative style on 64-query blocks: the two waves of a head exchange their maxima by a handshake
+    whose timing differs from run to run; scores and representatives must not.  A shape with many
+    workgroups per CU, Gaussian values (no ties to hide a missed exchange), 12 runs of both stages."""
+    w = small(Tq=1024, prefix=16384, stages=((64, 64), (16, 128)))
+    q, k, v, sl, _ = configs.make_inputs(w, 4)
+    cos, sin = gen.rope_table(4096, w.d)
+    qd, sld = q.cuda(), sl.cuda()
+    kd = gen.to_e4m3(k, 1.0 / 64).cuda() if fp8 else k.cuda()
+    rp = ihip.Rope(cos.cuda(), sin.cuda(), ihip.ROPE_RELATIVE, ihip.ROPE_NONE)
+    L = ihip.Layer(qd, kd, sld, w.b_q, w.n_sink, w.n_stream)
+    first = None
+    for run in range(12):
+        if fp8:
+            blocks = torch.empty((L.P, w.stages[-1][1]), dtype=torch.int32, device="cuda")
+            out = L.prefill_layer(qd, kd, kd, [s[0] for s in w.stages], [s[1] for s in w.stages], rope=rp,
+                                  kv_scales=(1.0 / 64, 1.0 / 64), out_blocks=blocks)       # V = the same bytes
+            cur = (out, blocks)
+        else:
+            scores, rep = L.prune_stage(qd, kd, 64, want_rep=True, rope=rp)
+            kept = L.select_blocks(scores, 64, w.stages[0][1])
+            scores2, rep2 = L.prune_stage(qd, kd, 16, kept, 64, want_rep=True, rope=rp)
+            cur = (scores, rep, scores2, rep2)
+        torch.cuda.synchronize()
+        if first is None:
+            first = [t.clone() for t in cur]
+        else:
+            for a, b in zip(first, cur):
+                assert torch.equal(a, b), run
+
+
 def test_rope_changes_selection_and_output(ihip, orc):
     # guards against a path that silently ignores the table
     w = small(Tq=128, prefix=2048)
