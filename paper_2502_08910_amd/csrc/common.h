@@ -192,6 +192,15 @@ __device__ inline uint32_t f32_to_bf16_bits(float f)
     return u >> 16;
 }
 
+// Two fp32 -> a packed pair of bf16 (a in the low half), round to nearest even: one
+// v_cvt_pk_bf16_f32, where the integer form above takes a dozen instructions for the pair.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack_bf16x2(float a, float b)
+{
+    const bf16x2_t v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 // 8 bf16 = 4 (even, odd) dim pairs, each turned by the angle whose cos and sin are given (fp32
 // arithmetic, every product and sum rounded on its own -- no fused multiply-add, so that the value
 // does not depend on the compiler's contraction --, results rounded to bf16, nearest-even):
@@ -204,8 +213,8 @@ __device__ inline uint4 rotate_bf16x8(const uint4 x, const float4 c, const float
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const float e = __uint_as_float(in[i] << 16), o = __uint_as_float(in[i] & 0xffff0000u);
-        w[i] = f32_to_bf16_bits(__fsub_rn(__fmul_rn(e, cc[i]), __fmul_rn(o, ss[i]))) |
-               (f32_to_bf16_bits(__fadd_rn(__fmul_rn(e, ss[i]), __fmul_rn(o, cc[i]))) << 16);
+        w[i] = pack_bf16x2(__fsub_rn(__fmul_rn(e, cc[i]), __fmul_rn(o, ss[i])),
+                           __fadd_rn(__fmul_rn(e, ss[i]), __fmul_rn(o, cc[i])));
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
@@ -222,10 +231,9 @@ __device__ inline void rotate_bf16x8_split(const uint4 x, const float4 c, const 
         const float e = __uint_as_float(in[i] << 16), o = __uint_as_float(in[i] & 0xffff0000u);
         const float re = __fsub_rn(__fmul_rn(e, cc[i]), __fmul_rn(o, ss[i]));
         const float ro = __fadd_rn(__fmul_rn(e, ss[i]), __fmul_rn(o, cc[i]));
-        const uint32_t he = f32_to_bf16_bits(re), ho = f32_to_bf16_bits(ro);
-        wh[i] = he | (ho << 16);
-        wl[i] = f32_to_bf16_bits(__fsub_rn(re, __uint_as_float(he << 16))) |
-                (f32_to_bf16_bits(__fsub_rn(ro, __uint_as_float(ho << 16))) << 16);
+        wh[i] = pack_bf16x2(re, ro);
+        wl[i] = pack_bf16x2(__fsub_rn(re, __uint_as_float(wh[i] << 16)),
+                            __fsub_rn(ro, __uint_as_float(wh[i] & 0xffff0000u)));
     }
     hi = make_uint4(wh[0], wh[1], wh[2], wh[3]);
     lo = make_uint4(wl[0], wl[1], wl[2], wl[3]);
