@@ -90,6 +90,25 @@ def test_fp8_result_equals_bf16_kernels_on_dequantised_values(ihip):
     assert (ref.float() - got.float()).abs().max().item() <= 1.6e-2      # other kernel, other summation order
 
 
+def test_every_e4m3_byte_is_widened_exactly(ihip):
+    # K rows that hold all 254 finite E4M3 bytes (subnormals, both zeros, the largest values): the
+    # pruning scores over the bytes must equal, bit for bit, the bf16 kernel's scores over the decoded
+    # values -- the widening in the kernels is exact for every byte
+    w = small(Tq=128, prefix=4096, stages=((64, 16), (16, 32)))
+    q, k, v, sl, _ = configs.make_inputs(w, 2)
+    codes = torch.arange(256, dtype=torch.int64)
+    codes = codes[(codes & 0x7f) != 0x7f]                               # no NaN
+    idx = (torch.arange(k.numel()) * 37 + 11) % codes.numel()            # every byte, in every lane position
+    k8 = codes[idx].to(torch.uint8).view(k.shape)
+    scale = 2.0 ** -6                                                    # a power of two: products stay exact
+    kd = (k8.view(torch.float8_e4m3fn).float() * scale).to(torch.bfloat16)
+    assert torch.equal(kd.float(), k8.view(torch.float8_e4m3fn).float() * scale)
+    L = ihip.Layer(q.cuda(), kd.cuda(), sl.cuda(), w.b_q, w.n_sink, w.n_stream)
+    s_ref, r_ref = L.prune_stage(q.cuda(), kd.cuda(), 64, want_rep=True)
+    s_got, r_got = L.prune_stage(q.cuda(), k8.cuda(), 64, want_rep=True, k_scale=scale)
+    assert torch.equal(s_ref, s_got) and torch.equal(r_ref, r_got)
+
+
 @pytest.mark.parametrize("scales", [(1.0 / 64, 1.0 / 64), (0.013, 0.021)])
 def test_gaussian_recall_and_output(ihip, orc, scales):
     w = small(Tq=256, prefix=4096, stages=((64, 16), (16, 32)))
