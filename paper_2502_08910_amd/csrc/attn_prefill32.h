@@ -275,9 +275,11 @@ __global__ __launch_bounds__(64 * NQ * G, NQ * G < 8 || ((ROPE || KV8) && NQ * G
                 const int item = tid + i * nthreads;
                 if (kPfTile * 16 % nthreads != 0 && item >= kPfTile * 16) break;
                 const int r = item >> 4, c = item & 15;
-                uint4 wk = fp8x8_to_bf16x8(*reinterpret_cast<const uint2 *>(raw + item * 4));
+                const uint2 rk = *reinterpret_cast<const uint2 *>(raw + item * 4);
+                uint4 wk;
+                if constexpr (ROPE) wk = rotate_fp8x8(rk, tb.c[ROPE ? i : 0], tb.s[ROPE ? i : 0]);
+                else wk = fp8x8_to_bf16x8(rk);
                 const uint4 wv = fp8x8_to_bf16x8(*reinterpret_cast<const uint2 *>(raw + kPfTileEl / 2 + item * 4));
-                if constexpr (ROPE) wk = rotate_bf16x8(wk, tb.c[ROPE ? i : 0], tb.s[ROPE ? i : 0]);
                 *reinterpret_cast<uint4 *>(stage + r * kD + ((c ^ (r & 15)) << 3)) = wk;
                 *reinterpret_cast<uint4 *>(stage + kPfTileEl + r * kD + ((c ^ ((r & 3) << 2)) << 3)) = wv;
             }

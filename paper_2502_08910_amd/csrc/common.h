@@ -205,30 +205,43 @@ __device__ inline uint32_t pack_bf16x2(float a, float b)
 // arithmetic, every product and sum rounded on its own -- no fused multiply-add, so that the value
 // does not depend on the compiler's contraction --, results rounded to bf16, nearest-even):
 // ApplyRope of Sec. 4 on a 16-byte piece of a row
-__device__ inline uint4 rotate_bf16x8(const uint4 x, const float4 c, const float4 sn)
+__device__ inline uint4 rotate_f32x8(const float (&f)[8], const float4 c, const float4 sn)
 {
     const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
-    const uint32_t in[4] = {x.x, x.y, x.z, x.w};
     uint32_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const float e = __uint_as_float(in[i] << 16), o = __uint_as_float(in[i] & 0xffff0000u);
+        const float e = f[2 * i], o = f[2 * i + 1];
         w[i] = pack_bf16x2(__fsub_rn(__fmul_rn(e, cc[i]), __fmul_rn(o, ss[i])),
                            __fadd_rn(__fmul_rn(e, ss[i]), __fmul_rn(o, cc[i])));
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
+__device__ inline void unpack_bf16x8(const uint4 x, float (&f)[8])
+{
+    const uint32_t in[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(in[i] << 16);
+        f[2 * i + 1] = __uint_as_float(in[i] & 0xffff0000u);
+    }
+}
+__device__ inline uint4 rotate_bf16x8(const uint4 x, const float4 c, const float4 sn)
+{
+    float f[8];
+    unpack_bf16x8(x, f);
+    return rotate_f32x8(f, c, sn);
+}
 // The same rotation kept to twice the mantissa: hi = the rotated values rounded to bf16 (what
 // rotate_bf16x8 returns), lo = what the rounding dropped, itself rounded to bf16 (the difference is
 // exact in fp32).  A product with hi + lo on one side is the fp32 rotation's to about 2^-17 relative.
-__device__ inline void rotate_bf16x8_split(const uint4 x, const float4 c, const float4 sn, uint4 &hi, uint4 &lo)
+__device__ inline void rotate_f32x8_split(const float (&f)[8], const float4 c, const float4 sn, uint4 &hi, uint4 &lo)
 {
     const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
-    const uint32_t in[4] = {x.x, x.y, x.z, x.w};
     uint32_t wh[4], wl[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const float e = __uint_as_float(in[i] << 16), o = __uint_as_float(in[i] & 0xffff0000u);
+        const float e = f[2 * i], o = f[2 * i + 1];
         const float re = __fsub_rn(__fmul_rn(e, cc[i]), __fmul_rn(o, ss[i]));
         const float ro = __fadd_rn(__fmul_rn(e, ss[i]), __fmul_rn(o, cc[i]));
         wh[i] = pack_bf16x2(re, ro);
@@ -237,6 +250,12 @@ __device__ inline void rotate_bf16x8_split(const uint4 x, const float4 c, const 
     }
     hi = make_uint4(wh[0], wh[1], wh[2], wh[3]);
     lo = make_uint4(wl[0], wl[1], wl[2], wl[3]);
+}
+__device__ inline void rotate_bf16x8_split(const uint4 x, const float4 c, const float4 sn, uint4 &hi, uint4 &lo)
+{
+    float f[8];
+    unpack_bf16x8(x, f);
+    rotate_f32x8_split(f, c, sn, hi, lo);
 }
 __device__ inline uint4 rotate_bf16x8(const uint4 x, const float *cos4, const float *sin4)
 {
@@ -314,6 +333,21 @@ __device__ inline uint4 fp8x8_to_bf16x8(const uint2 &k)
     return r;
 }
 __device__ inline void unpack8(const uint2 &k, float (&f)[8]) { unpack8_fp8(k, f); }
+// 8 E4M3 bytes decoded and turned: the rotation takes the decoded fp32 values as they are (widening
+// to bf16 first and unpacking again costs a dozen instructions more and, in the chunk-indexed
+// pruning kernel, a third of its time)
+__device__ inline uint4 rotate_fp8x8(const uint2 &k, const float4 c, const float4 sn)
+{
+    float f[8];
+    unpack8_fp8(k, f);
+    return rotate_f32x8(f, c, sn);
+}
+__device__ inline void rotate_fp8x8_split(const uint2 &k, const float4 c, const float4 sn, uint4 &hi, uint4 &lo)
+{
+    float f[8];
+    unpack8_fp8(k, f);
+    rotate_f32x8_split(f, c, sn, hi, lo);
+}
 
 // ---- cross-lane -----------------------------------------------------------
 template <int CTRL>

@@ -359,11 +359,13 @@ __global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : 
             }
 #pragma unroll
             for (int r = 0; r < NT * 4; ++r) {
-                uint4 piece = fp8x8_to_bf16x8(raw[r]);
+                uint4 piece;
                 if constexpr (ROPE == 2) {
                     uint4 rest;
-                    rotate_bf16x8_split(piece, tb_cos[r], tb_sin[r], piece, rest);
+                    rotate_fp8x8_split(raw[r], tb_cos[r], tb_sin[r], piece, rest);
                     put16(tile + kLo + r * 4 * kD, rest);
+                } else {
+                    piece = fp8x8_to_bf16x8(raw[r]);
                 }
                 put16(tile + r * 4 * kD, piece);
             }
@@ -464,13 +466,15 @@ __global__ __launch_bounds__(64 * G * QS, QS == 2 ? 2 : (ROPE && MT == 4) ? 1 : 
 #pragma unroll
                 for (int i = 0; i < kPerWave; ++i) {
                     const int ld = wv * kPerWave + i;
-                    uint4 piece = fp8x8_to_bf16x8(raw[i]);
+                    uint4 piece;
                     if constexpr (ROPE == 2) {
                         const int64_t at = table_at(jt, ld & 7);
                         uint4 rest;
-                        rotate_bf16x8_split(piece, *reinterpret_cast<const float4 *>(rope.cos + at),
-                                            *reinterpret_cast<const float4 *>(rope.sin + at), piece, rest);
+                        rotate_fp8x8_split(raw[i], *reinterpret_cast<const float4 *>(rope.cos + at),
+                                           *reinterpret_cast<const float4 *>(rope.sin + at), piece, rest);
                         put16(&sh_rows[kLo + ld * 4 * kD], rest);
+                    } else {
+                        piece = fp8x8_to_bf16x8(raw[i]);
                     }
                     put16(&sh_rows[ld * 4 * kD], piece);
                 }

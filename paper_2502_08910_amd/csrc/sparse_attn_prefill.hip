@@ -137,9 +137,15 @@ __global__ __launch_bounds__(64 * G) void attn_prefill_kernel(const AttnPrefillA
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 uint4 wk;
-                if constexpr (KV8) { wk = fp8x8_to_bf16x8(rk[r][e]); wv[e] = fp8x8_to_bf16x8(rv[r][e]); }
-                else { wk = rk[r][e]; wv[e] = rv[r][e]; }
-                if constexpr (ROPE) wk = rotate_bf16x8(wk, rc[r][e], rs[r][e]);
+                if constexpr (KV8) {
+                    if constexpr (ROPE) wk = rotate_fp8x8(rk[r][e], rc[r][e], rs[r][e]);
+                    else wk = fp8x8_to_bf16x8(rk[r][e]);
+                    wv[e] = fp8x8_to_bf16x8(rv[r][e]);
+                } else {
+                    wk = rk[r][e];
+                    wv[e] = rv[r][e];
+                    if constexpr (ROPE) wk = rotate_bf16x8(wk, rc[r][e], rs[r][e]);
+                }
                 *reinterpret_cast<uint4 *>(&sK[(key0 + e) * kPfKStride + c * 8]) = wk;
             }
             // k slot of key kk: tile t = kk/16, kq = (kk%16)/4, j = kk%4 + 4*t
